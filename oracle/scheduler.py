@@ -1,0 +1,223 @@
+"""FCFS continuous-batching scheduler with paged-KV accounting: an integer state machine.
+Oracle code: test infrastructure only.
+
+Follows the scheduler loop of section 4.2 of the paper (persistent scheduler; continuous
+batching with inline prefill; ring buffer): scan the ring for submitted prompts, claim
+them, run a prefill pass for the newly admitted while running decodes are paused, otherwise
+a decode pass over everything running, then publish tokens and retire finished requests.
+The paper gives no KV-block algorithm; the reading taken here:
+
+  * Requests carry tickets 0,1,2,.. in submission order; ring slot = ticket mod ring_slots.
+  * One iteration = one forward pass. At its start: (1) retire what finished in the previous
+    iteration, batch slot ascending, pushing blocks back in block-table order; (2) poll:
+    tickets below `tail` are visible; (3) admit strictly in ticket order, no skipping, while
+    a batch slot is free, the worst-case reservation ceil((P + max_new - 1)/bs) (at least 1)
+    fits in n_blocks - committed, and the prompt tokens admitted this iteration stay within
+    max_prefill_tokens (the first admitted request is exempt); (4) any admission makes this
+    a prefill iteration over exactly the admitted requests, else a decode iteration over all
+    running requests, else idle; (5) allocate physical blocks, batch slot ascending:
+    ceil(P/bs) for a prefill, one more for a decode whose context fills its blocks exactly;
+    the free list is a stack whose first pops return 0,1,2,..; (6) build the batch metadata.
+  * After the forward pass and sampling: append the token, finish a request when it has
+    max_new tokens or emitted the end-of-sequence id (which is emitted and counted).
+"""
+import numpy as np
+
+EMPTY, PREFILL_PENDING, PREFILL_PROCESSING, DECODE_PROCESSING, DECODE_COMPLETED, DECODE_PAUSED = range(6)
+
+LEGAL_EDGES = {
+    (EMPTY, PREFILL_PENDING), (PREFILL_PENDING, PREFILL_PROCESSING),
+    (PREFILL_PROCESSING, DECODE_PROCESSING), (PREFILL_PROCESSING, DECODE_COMPLETED),
+    (DECODE_PROCESSING, DECODE_PAUSED), (DECODE_PAUSED, DECODE_PROCESSING),
+    (DECODE_PROCESSING, DECODE_COMPLETED), (DECODE_PAUSED, DECODE_COMPLETED),
+    (DECODE_COMPLETED, EMPTY),
+}
+
+IDLE, PREFILL, DECODE = 0, 1, 2
+
+
+class Running:
+    __slots__ = ("ticket", "P", "max_new", "gen", "ctx_len", "reserved", "blocks", "finished", "last_token")
+
+
+class Plan:
+    """Batch metadata of one iteration (section 4.2: what the scheduler populates before a launch)."""
+
+    def __init__(self):
+        self.kind = IDLE
+        self.iteration = 0
+        self.tail = 0
+        self.admitted = []      # tickets admitted this iteration, in order
+        self.batch_slots = []   # batch slot of each sequence in this iteration, ascending
+        self.tickets = []
+        self.seq_lens = []      # context length of each sequence after this iteration's tokens
+        self.cu_seqlens = [0]   # token offsets per sequence
+        self.input_ids = []
+        self.positions = []
+        self.slot_mapping = []
+        self.tok_seq = []
+        self.last_idx = []
+        self.block_tables = []  # per sequence, list of block ids
+        self.gen_index = []     # index of the output token each sequence samples in this iteration
+        self.free_blocks_after = 0
+
+
+def blocks_needed(P, max_new, bs):
+    return max(1, -(-(P + max_new - 1) // bs))
+
+
+class Scheduler:
+    def __init__(self, n_blocks, block_size, max_batch, max_prefill_tokens, ring_slots, eos_token_id=-1,
+                 free_list=None):
+        self.n_blocks, self.bs, self.max_batch = n_blocks, block_size, max_batch
+        self.max_prefill_tokens, self.ring_slots, self.eos = max_prefill_tokens, ring_slots, eos_token_id
+        # stack: pop from the end. Default order makes the first pops return 0, 1, 2, ...
+        self.free = list(range(n_blocks - 1, -1, -1)) if free_list is None else list(free_list)
+        self.running = [None] * max_batch
+        self.committed = 0
+        self.next_ticket = 0
+        self.iteration = 0
+        self.requests = {}          # ticket -> (prompt, max_new)
+        self.state = {}             # ticket -> slot state
+        self.transitions = []       # (ticket, from, to)
+        self.outputs = {}           # ticket -> list of tokens
+
+    # ---- ring side -------------------------------------------------------------------
+    def submit(self, prompt, max_new):
+        t = len(self.requests)
+        self.requests[t] = (np.asarray(prompt, dtype=np.int64), int(max_new))
+        self.outputs[t] = []
+        self.state[t] = EMPTY
+        self._set(t, PREFILL_PENDING)
+        return t
+
+    def _set(self, ticket, new):
+        old = self.state[ticket]
+        self.transitions.append((ticket, old, new))
+        self.state[ticket] = new
+
+    # ---- one iteration: steps (1)-(6) -------------------------------------------------
+    def step(self, tail):
+        bs = self.bs
+        plan = Plan()
+        plan.tail = tail
+        # (1) retire
+        for b in range(self.max_batch):
+            r = self.running[b]
+            if r is not None and r.finished:
+                self.free.extend(r.blocks)
+                self.committed -= r.reserved
+                self.running[b] = None
+        # (2)+(3) admit in ticket order
+        admitted_tokens = 0
+        new_slots = []
+        while self.next_ticket < tail:
+            t = self.next_ticket
+            prompt, max_new = self.requests[t]
+            P = prompt.size
+            need = blocks_needed(P, max_new, bs)
+            free_slots = [b for b in range(self.max_batch) if self.running[b] is None]
+            if not free_slots:
+                break
+            if self.committed + need > self.n_blocks:
+                break
+            if new_slots and admitted_tokens + P > self.max_prefill_tokens:
+                break
+            r = Running()
+            r.ticket, r.P, r.max_new, r.gen, r.ctx_len = t, P, max_new, 0, 0
+            r.reserved, r.blocks, r.finished, r.last_token = need, [], False, -1
+            b = free_slots[0]
+            self.running[b] = r
+            self.committed += need
+            admitted_tokens += P
+            new_slots.append(b)
+            plan.admitted.append(t)
+            self._set(t, PREFILL_PROCESSING)
+            self.next_ticket = t + 1
+        # (4) kind
+        if new_slots:
+            plan.kind = PREFILL
+            slots = sorted(new_slots)
+            for b in range(self.max_batch):   # running decodes are paused for this iteration
+                r = self.running[b]
+                if r is not None and b not in new_slots and self.state[r.ticket] == DECODE_PROCESSING:
+                    self._set(r.ticket, DECODE_PAUSED)
+        else:
+            slots = [b for b in range(self.max_batch) if self.running[b] is not None]
+            if not slots:
+                plan.kind = IDLE
+                return plan
+            plan.kind = DECODE
+            for b in slots:
+                r = self.running[b]
+                if self.state[r.ticket] == DECODE_PAUSED:
+                    self._set(r.ticket, DECODE_PROCESSING)
+        plan.iteration = self.iteration
+        self.iteration += 1
+        # (5) allocate, (6) metadata
+        for si, b in enumerate(slots):
+            r = self.running[b]
+            if plan.kind == PREFILL:
+                for _ in range(-(-r.P // bs)):
+                    r.blocks.append(self.free.pop())
+                toks = list(self.requests[r.ticket][0])
+                pos = list(range(r.P))
+                r.ctx_len = r.P
+            else:
+                if r.ctx_len == len(r.blocks) * bs:
+                    r.blocks.append(self.free.pop())
+                toks = [r.last_token]
+                pos = [r.ctx_len]
+                r.ctx_len += 1
+            plan.batch_slots.append(b)
+            plan.tickets.append(r.ticket)
+            plan.seq_lens.append(r.ctx_len)
+            plan.input_ids += [int(x) for x in toks]
+            plan.positions += pos
+            plan.slot_mapping += [r.blocks[p // bs] * bs + p % bs for p in pos]
+            plan.tok_seq += [si] * len(pos)
+            plan.cu_seqlens.append(len(plan.input_ids))
+            plan.last_idx.append(len(plan.input_ids) - 1)
+            plan.block_tables.append(list(r.blocks))
+            plan.gen_index.append(r.gen)
+        plan.free_blocks_after = len(self.free)
+        return plan
+
+    # ---- steps (7)-(8): tokens of the iteration ----------------------------------------
+    def commit(self, plan, tokens):
+        """tokens[i]: sampled token of sequence i of the plan. Returns events
+        (ticket, index, token, is_first, is_last) in batch-slot order."""
+        events = []
+        for b, tok in zip(plan.batch_slots, tokens):
+            r = self.running[b]
+            tok = int(tok)
+            self.outputs[r.ticket].append(tok)
+            idx = r.gen
+            r.gen += 1
+            r.last_token = tok
+            done = r.gen == r.max_new or tok == self.eos
+            if self.state[r.ticket] == PREFILL_PROCESSING and not done:
+                self._set(r.ticket, DECODE_PROCESSING)
+            if done:
+                r.finished = True
+                self._set(r.ticket, DECODE_COMPLETED)
+            events.append((r.ticket, idx, tok, idx == 0, done))
+        return events
+
+    # ---- invariants ---------------------------------------------------------------------
+    def check_invariants(self):
+        held = [blk for r in self.running if r is not None for blk in r.blocks]
+        allb = held + self.free
+        assert len(allb) == self.n_blocks, "block leaked or duplicated"
+        assert len(set(allb)) == self.n_blocks, "block id appears twice"
+        assert sum(r.reserved for r in self.running if r is not None) == self.committed
+        assert len(held) <= self.committed <= self.n_blocks
+        for r in self.running:
+            if r is not None:
+                assert len(r.blocks) <= r.reserved
+                assert len(r.blocks) * self.bs >= r.ctx_len
+        for (_, a, b) in self.transitions:
+            assert (a, b) in LEGAL_EDGES, (a, b)
+
+    def n_running(self):
+        return sum(r is not None for r in self.running)

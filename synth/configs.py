@@ -1,0 +1,45 @@
+"""Model and engine configurations of the five synthetic workloads.
+
+Names: tiny, churn, llama3_8b, sched_stress (the interference run reuses llama3_8b).
+dtype: 0 = fp32 weights and KV, 1 = bf16 weights and KV.
+"""
+
+MODEL_CONFIGS = {
+    "tiny": dict(n_layers=2, d_model=256, n_q_heads=4, n_kv_heads=4, head_dim=64, d_ffn=1024,
+                 vocab=4096, dtype=0, rms_eps=1e-5, rope_theta=10000.0),
+    "churn": dict(n_layers=8, d_model=1024, n_q_heads=16, n_kv_heads=16, head_dim=64, d_ffn=4096,
+                  vocab=32000, dtype=1, rms_eps=1e-5, rope_theta=10000.0),
+    "llama3_8b": dict(n_layers=32, d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128,
+                      d_ffn=14336, vocab=128256, dtype=1, rms_eps=1e-5, rope_theta=500000.0),
+    "sched_stress": dict(n_layers=1, d_model=128, n_q_heads=2, n_kv_heads=2, head_dim=64, d_ffn=512,
+                         vocab=8192, dtype=0, rms_eps=1e-5, rope_theta=10000.0),
+    # small GQA bf16 model used by parity tests only (several tiles, ragged tails, fast oracle)
+    "mini_gqa": dict(n_layers=3, d_model=384, n_q_heads=6, n_kv_heads=2, head_dim=64, d_ffn=832,
+                     vocab=2500, dtype=1, rms_eps=1e-5, rope_theta=500000.0),
+    "mini_gqa128": dict(n_layers=2, d_model=512, n_q_heads=4, n_kv_heads=1, head_dim=128, d_ffn=1152,
+                        vocab=3001, dtype=1, rms_eps=1e-5, rope_theta=500000.0),
+}
+
+# kv_num_blocks == 0 means "derived from the workload" (churn: 60 % of peak demand)
+ENGINE_CONFIGS = {
+    "tiny": dict(kv_block_size=16, kv_num_blocks=256, max_batch=8, max_seq_len=128,
+                 max_prefill_tokens=8192, ring_slots=64, eos_token_id=-1),
+    "churn": dict(kv_block_size=16, kv_num_blocks=0, max_batch=64, max_seq_len=2048 + 256,
+                  max_prefill_tokens=8192, ring_slots=512, eos_token_id=-1),
+    "llama3_8b": dict(kv_block_size=16, kv_num_blocks=32768, max_batch=256, max_seq_len=4096 + 1024,
+                      max_prefill_tokens=8192, ring_slots=2048, eos_token_id=-1),
+    "sched_stress": dict(kv_block_size=16, kv_num_blocks=65536, max_batch=512, max_seq_len=64,
+                         max_prefill_tokens=8192, ring_slots=4096, eos_token_id=-1),
+    "mini_gqa": dict(kv_block_size=16, kv_num_blocks=96, max_batch=6, max_seq_len=160,
+                     max_prefill_tokens=256, ring_slots=32, eos_token_id=-1),
+    "mini_gqa128": dict(kv_block_size=16, kv_num_blocks=64, max_batch=5, max_seq_len=200,
+                        max_prefill_tokens=300, ring_slots=16, eos_token_id=-1),
+}
+
+
+def model_config(name):
+    return dict(MODEL_CONFIGS[name])
+
+
+def engine_config(name):
+    return dict(ENGINE_CONFIGS[name])

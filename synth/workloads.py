@@ -1,0 +1,94 @@
+"""Seeded request workloads shaped like the five configurations.
+
+A request is a dict: arrival_s (float), prompt (int32 array), max_new_tokens (int),
+temperature (float, 0 = greedy), top_k (int, 0 = all), top_p (float), seed (uint64 as int).
+"""
+import numpy as np
+
+_M64 = (1 << 64) - 1
+
+
+def splitmix64(seed, index):
+    """Per-request sampling seed: the splitmix64 output function applied to seed + (index+1)*golden."""
+    z = (seed + (index + 1) * 0x9E3779B97F4A7C15) & _M64
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & _M64
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & _M64
+    return z ^ (z >> 31)
+
+
+def _lognormal_len(rng, n, median, sigma, cap):
+    x = rng.lognormal(np.log(median), sigma, n)
+    return np.clip(np.rint(x), 1, cap).astype(np.int64)
+
+
+def make_workload(name, vocab, seed, n_requests=None, rate=None):
+    """Returns a list of request dicts sorted by arrival time (ticket order = list order)."""
+    rng = np.random.default_rng(seed)
+    greedy = dict(temperature=0.0, top_k=0, top_p=1.0)
+    if name == "tiny":
+        n = n_requests or 8
+        plen = rng.integers(16, 65, n)
+        olen = np.full(n, 32)
+        arr = np.zeros(n)
+        samp = greedy
+    elif name == "churn":
+        n = n_requests or 256
+        arr = np.cumsum(rng.exponential(1.0 / (rate or 20.0), n))
+        plen = _lognormal_len(rng, n, 256, 0.8, 2048)
+        olen = rng.integers(64, 257, n)
+        samp = greedy
+    elif name == "llama3_8b":
+        n = n_requests or 1024
+        arr = np.cumsum(rng.exponential(1.0 / (rate or 8.0), n))
+        plen = _lognormal_len(rng, n, 512, 1.0, 4096)
+        olen = _lognormal_len(rng, n, 128, 0.7, 1024)
+        samp = dict(temperature=0.8, top_k=50, top_p=0.9)
+    elif name == "sched_stress":
+        n = n_requests or 4096
+        arr = (np.arange(n) // 512) * 0.050
+        plen = rng.integers(4, 33, n)
+        olen = rng.integers(1, 17, n)
+        samp = greedy
+    elif name == "mini":  # parity-test mix: ragged prompts around block and tile boundaries
+        n = n_requests or 10
+        arr = np.zeros(n)
+        plen = rng.integers(1, 100, n)
+        plen[: min(n, 5)] = np.array([1, 15, 16, 17, 64])[: min(n, 5)]
+        olen = rng.integers(1, 40, n)
+        samp = greedy
+    else:
+        raise ValueError(name)
+    reqs = []
+    for i in range(n):
+        reqs.append(dict(arrival_s=float(arr[i]),
+                         prompt=rng.integers(0, vocab, int(plen[i])).astype(np.int32),
+                         max_new_tokens=int(olen[i]), seed=splitmix64(seed, i), **samp))
+    return reqs
+
+
+def blocks_needed(req, bs):
+    """Worst-case KV reservation of one request: every token but the last sampled one is cached."""
+    return max(1, -(-(len(req["prompt"]) + req["max_new_tokens"] - 1) // bs))
+
+
+def peak_block_demand(reqs, bs, step_s=2.0e-3, prefill_s_per_token=2.0e-5):
+    """Peak of the summed reservations if every request held its reservation from arrival for
+    prompt*prefill_s_per_token + output*step_s seconds (a fluid model with unlimited pool)."""
+    ev = []
+    for r in reqs:
+        need = blocks_needed(r, bs)
+        t0 = r["arrival_s"]
+        t1 = t0 + len(r["prompt"]) * prefill_s_per_token + r["max_new_tokens"] * step_s
+        ev.append((t0, need))
+        ev.append((t1, -need))
+    ev.sort(key=lambda e: (e[0], e[1]))
+    cur = peak = 0
+    for _, dlt in ev:
+        cur += dlt
+        peak = max(peak, cur)
+    return peak
+
+
+def churn_pool_blocks(reqs, bs=16):
+    """Churn pool: 60 % of the fluid-model peak demand, at least the largest single reservation."""
+    return int(max(-(-6 * peak_block_demand(reqs, bs) // 10), max(blocks_needed(r, bs) for r in reqs)))

@@ -1,0 +1,155 @@
+"""Pins for the oracle's scheduler: a schedule worked out by hand, invariants under random load,
+emission counts, FCFS head-of-line blocking, window restarts, and service == per-request generation."""
+import numpy as np
+import pytest
+
+import synth
+from oracle import model as M, serve as SV
+from oracle.scheduler import Scheduler, PREFILL, DECODE, IDLE, blocks_needed, LEGAL_EDGES
+
+
+def req(P, n, first=0):
+    return dict(prompt=np.arange(first, first + P) % 50, max_new_tokens=n, temperature=0.0, top_k=0, top_p=1.0, seed=0)
+
+
+def test_reservation_formula():
+    assert blocks_needed(20, 3, 16) == 2 and blocks_needed(10, 8, 16) == 2 and blocks_needed(5, 2, 16) == 1
+    assert blocks_needed(16, 1, 16) == 1 and blocks_needed(16, 2, 16) == 2 and blocks_needed(1, 1, 16) == 1
+
+
+def test_hand_worked_three_requests_pool_of_four():
+    """bs 16, 4 blocks, 2 batch slots; requests (P, max_new) = (20,3), (10,8), (5,2).
+    Worked by hand from the iteration rules: see the expected table below."""
+    s = Scheduler(4, 16, 2, 8192, 8)
+    plans = []
+    SV.run_schedule(s, [req(20, 3), req(10, 8), req(5, 2)], lambda pl: [7] * len(pl.tickets), on_plan=plans.append)
+    # iteration: (kind, tickets, batch slots, positions of each sequence's last token, block tables, free after)
+    exp = [
+        (PREFILL, [0, 1], [0, 1], [19, 9], [[0, 1], [2]], 1),
+        (DECODE, [0, 1], [0, 1], [20, 10], [[0, 1], [2]], 1),
+        (DECODE, [0, 1], [0, 1], [21, 11], [[0, 1], [2]], 1),      # request 0 emits its 3rd token
+        (PREFILL, [2], [0], [4], [[1]], 2),                        # blocks 0,1 pushed back; pop returns 1
+        (DECODE, [2, 1], [0, 1], [5, 12], [[1], [2]], 2),          # request 2 done
+        (DECODE, [1], [1], [13], [[2]], 3),
+        (DECODE, [1], [1], [14], [[2]], 3),
+        (DECODE, [1], [1], [15], [[2]], 3),
+        (DECODE, [1], [1], [16], [[2, 1]], 2),                     # crosses a block boundary: pop returns 1
+    ]
+    assert len(plans) == len(exp)
+    for pl, e in zip(plans, exp):
+        got = (pl.kind, pl.tickets, pl.batch_slots, [pl.positions[i] for i in pl.last_idx], pl.block_tables, pl.free_blocks_after)
+        assert got == e, (pl.iteration, got, e)
+    assert plans[0].slot_mapping[:20] == list(range(0, 20)) and plans[0].slot_mapping[20:] == list(range(32, 42))
+    assert plans[0].cu_seqlens == [0, 20, 30] and plans[0].tok_seq == [0] * 20 + [1] * 10
+    assert plans[8].slot_mapping == [16] and plans[8].input_ids == [7]
+    assert plans[3].admitted == [2] and plans[0].admitted == [0, 1]
+    assert [len(s.outputs[t]) for t in range(3)] == [3, 8, 2]
+    s.step(3)
+    assert s.free == [3, 0, 2, 1] and s.committed == 0
+
+
+def test_head_of_line_blocks_and_prefill_budget():
+    # ticket 1 needs more blocks than are uncommitted: ticket 2, which would fit, must wait behind it
+    s = Scheduler(6, 16, 4, 8192, 8)
+    plans = []
+    SV.run_schedule(s, [req(40, 9), req(60, 10), req(3, 2)], lambda pl: [1] * len(pl.tickets), on_plan=plans.append)
+    assert plans[0].admitted == [0]
+    first_adm_1 = next(p.iteration for p in plans if 1 in p.admitted)
+    first_adm_2 = next(p.iteration for p in plans if 2 in p.admitted)
+    assert first_adm_1 == 9 and first_adm_2 == 9      # after request 0 retires, both fit
+    # prefill token budget: the first request is exempt, the next must fit in the remainder
+    s = Scheduler(64, 16, 4, 50, 8)
+    plans = []
+    SV.run_schedule(s, [req(70, 2), req(10, 2), req(30, 2), req(30, 2)], lambda pl: [1] * len(pl.tickets), on_plan=plans.append)
+    assert plans[0].admitted == [0] and plans[1].admitted == [1, 2] and plans[2].admitted == [3]
+
+
+def test_eos_is_emitted_and_counted():
+    s = Scheduler(8, 16, 2, 8192, 8, eos_token_id=9)
+    seq = iter([1, 2, 9, 4, 5])
+    ev = SV.run_schedule(s, [req(4, 10)], lambda pl: [next(seq)])
+    assert s.outputs[0] == [1, 2, 9] and ev[-1][-1] is True
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_invariants_random_load_and_exact_counts(seed):
+    rng = np.random.default_rng(seed)
+    n = 60
+    reqs = [req(int(rng.integers(1, 70)), int(rng.integers(1, 20))) for _ in range(n)]
+    need_max = max(blocks_needed(len(r["prompt"]), r["max_new_tokens"], 16) for r in reqs)
+    s = Scheduler(max(need_max, 12), 16, 5, 100, 16, eos_token_id=3)
+    tok_rng = np.random.default_rng(seed + 100)
+    peak = [0]
+
+    def on_plan(pl):
+        assert s.n_running() <= 5
+        peak[0] = max(peak[0], s.committed)
+        assert pl.admitted == sorted(pl.admitted)
+        assert pl.kind in (PREFILL, DECODE)
+        if pl.kind == PREFILL:
+            assert sorted(pl.tickets) == sorted(pl.admitted)
+        # slot mapping addresses each sequence's own blocks only
+        for t, sl in enumerate(pl.slot_mapping):
+            assert sl // 16 in pl.block_tables[pl.tok_seq[t]]
+        assert len(set(pl.slot_mapping)) == len(pl.slot_mapping)
+
+    ev = SV.run_schedule(s, reqs, lambda pl: list(tok_rng.integers(0, 12, len(pl.tickets))), on_plan=on_plan)
+    admitted_order = [t for (t, a, b) in s.transitions if b == 2]
+    assert admitted_order == list(range(n))
+    for t in range(n):
+        out = s.outputs[t]
+        exp = reqs[t]["max_new_tokens"]
+        if 3 in out:
+            exp = min(exp, out.index(3) + 1)
+        assert len(out) == exp
+    assert all((a, b) in LEGAL_EDGES for _, a, b in s.transitions)
+    assert peak[0] <= s.n_blocks
+    # events: per request consecutive indices, exactly one first and one last
+    for t in range(n):
+        mine = [e for e in ev if e[1] == t]
+        assert [e[2] for e in mine] == list(range(len(mine)))
+        assert [e[4] for e in mine].count(True) == 1 and mine[-1][5] is True
+
+
+def test_windowed_run_equals_single_run():
+    """State survives stopping the loop every few iterations (section 4.2, window recovery)."""
+    rng = np.random.default_rng(5)
+    reqs = [req(int(rng.integers(1, 40)), int(rng.integers(1, 12))) for _ in range(20)]
+    f = lambda pl: [(pl.iteration * 7 + b) % 11 for b in pl.batch_slots]
+    s1 = Scheduler(16, 16, 4, 64, 8)
+    e1 = SV.run_schedule(s1, reqs, f)
+    s2 = Scheduler(16, 16, 4, 64, 8)
+    for r in reqs:
+        s2.submit(r["prompt"], r["max_new_tokens"])
+    e2 = []
+    while True:
+        for _ in range(3):                       # a window of 3 iterations
+            pl = s2.step(len(reqs))
+            if pl.kind == IDLE:
+                break
+            e2 += [(pl.iteration,) + e for e in s2.commit(pl, f(pl))]
+        if pl.kind == IDLE:
+            break
+    assert e1 == e2
+
+
+def test_service_equals_per_request_generation_and_replay_tails():
+    cfg = dict(n_layers=2, d_model=64, n_q_heads=4, n_kv_heads=2, head_dim=16, d_ffn=96, vocab=50, dtype=0,
+               rms_eps=1e-5, rope_theta=10000.0)
+    W = M.Weights(cfg, synth.make_weights(cfg, 11, std=0.3))
+    rng = np.random.default_rng(6)
+    reqs = []
+    for i in range(7):
+        r = req(int(rng.integers(1, 30)), int(rng.integers(1, 9)), first=i * 3)
+        if i % 2:
+            r.update(temperature=0.8, top_k=5, top_p=0.9, seed=synth.splitmix64(3, i))
+        reqs.append(r)
+    eng = dict(kv_block_size=4, kv_num_blocks=24, max_batch=3, max_prefill_tokens=40, ring_slots=8, eos_token_id=-1)
+    ev, s = SV.serve(cfg, W, eng, reqs)
+    for t, r in enumerate(reqs):
+        assert s.outputs[t] == SV.generate_reference(cfg, W, r)
+    # arrivals trickling in (tails per iteration) change the schedule but not the streams
+    tails = [1, 1, 2, 2, 4, 4, 4, 7]
+    ev2, s2 = SV.serve(cfg, W, eng, reqs, tails=tails)
+    assert [s2.outputs[t] for t in range(7)] == [s.outputs[t] for t in range(7)]
+    assert [e[0] for e in ev2] != [e[0] for e in ev]
