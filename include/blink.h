@@ -1,0 +1,182 @@
+/*
+ * blink.h - C ABI of the on-GPU serving step of Blink (CPU-free LLM serving).
+ *
+ * The library implements the backend of section 4.2 of the paper ("Backend: GPU-resident
+ * inference engine") for one AMD MI355X: a request ring in HBM, a persistent on-GPU
+ * scheduler (ring poll, FCFS continuous batching with inline prefill, paged-KV block
+ * accounting, batch metadata), the prefill/decode forward pass of a Llama-style decoder
+ * over paged KV, on-device sampling and token publication. After blink_init no host
+ * decision is taken per iteration. The host side of this ABI stands in for the paper's
+ * SmartNIC frontend (section 4.4): blink_submit plays the RDMA datapath (payload first,
+ * then the slot state), blink_poll_outputs plays the token reader (one bulk read of the
+ * slot metadata, compare generation counts, fetch new tokens).
+ *
+ * All functions return 0 on success or a negative BLINK_ERR_* code. Nothing throws.
+ * All pointers are HOST pointers. The engine owns every byte of device memory; the caller
+ * owns `weights`, `prompt` and event buffers, which are copied before the call returns.
+ * Threads: one thread may call blink_submit while another calls blink_poll_outputs and the
+ * device loop runs; all other calls are made from one control thread.
+ */
+#ifndef BLINK_H
+#define BLINK_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BLINK_OK 0
+#define BLINK_ERR_INVAL (-1)     /* null pointer, empty prompt, token id outside [0, vocab), bad sampling parameter */
+#define BLINK_ERR_TOO_LARGE (-2) /* prompt + max_new_tokens exceeds max_seq_len, or its KV reservation exceeds the pool */
+#define BLINK_ERR_FULL (-3)      /* the ring slot of the next ticket is not empty yet: back-pressure, retry later */
+#define BLINK_ERR_DEVICE (-4)    /* a HIP call failed, or the device loop reported an internal error */
+#define BLINK_ERR_STATE (-5)     /* call not allowed now: run while running, submit after shutdown, ... */
+
+/* blink_config.flags */
+#define BLINK_FLAG_TRACE 1u          /* record one trace record per iteration (blink_get_trace) */
+#define BLINK_FLAG_EXIT_WHEN_IDLE 2u /* the loop stops by itself once nothing is running and nothing is pending */
+#define BLINK_FLAG_PERSISTENT 4u     /* one resident kernel runs the whole loop; without it the host enqueues a
+                                        fixed, decision-free kernel sequence per iteration (bring-up mode) */
+#define BLINK_FLAG_KEEP_LOGITS 8u    /* keep the logits of the last iteration readable via blink_debug_read */
+
+/* slot life cycle of the ring (section 4.2, "Ring buffer") */
+enum {
+  BLINK_SLOT_EMPTY = 0,
+  BLINK_SLOT_PREFILL_PENDING = 1,
+  BLINK_SLOT_PREFILL_PROCESSING = 2,
+  BLINK_SLOT_DECODE_PROCESSING = 3,
+  BLINK_SLOT_DECODE_COMPLETED = 4,
+  BLINK_SLOT_DECODE_PAUSED = 5
+};
+
+typedef struct blink_engine blink_engine;
+
+typedef struct {
+  /* model: Llama-style decoder, no biases, untied LM head */
+  uint32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  uint32_t dtype;              /* 0: fp32 weights and KV; 1: bf16 weights and KV (fp32 accumulation) */
+  float rms_eps;
+  float rope_theta;
+  const void* weights;         /* blob: embed[V][d]; per layer g1[d] wq[nq*hd][d] wk[nkv*hd][d] wv[nkv*hd][d]
+                                  wo[d][nq*hd] g2[d] wg[F][d] wu[F][d] wd[d][F]; gf[d]; lm[V][d]. Matrices
+                                  row-major [out][in] in `dtype`; the gains g1,g2,gf always fp32 */
+  uint64_t weights_bytes;      /* must equal the size implied by the fields above */
+  /* KV pool and scheduler */
+  uint32_t kv_block_size;      /* tokens per KV block; 16 */
+  uint32_t kv_num_blocks;      /* blocks in the pool */
+  uint32_t max_batch;          /* batch slots (running sequences), <= 1024 */
+  uint32_t max_seq_len;        /* prompt + generated tokens of one request */
+  uint32_t max_prefill_tokens; /* prompt tokens per prefill iteration (the first admitted request is exempt) */
+  uint32_t ring_slots;         /* power of two */
+  int32_t eos_token_id;        /* -1: none */
+  int32_t device;              /* HIP device ordinal */
+  uint32_t flags;              /* BLINK_FLAG_* */
+  uint32_t trace_capacity;     /* trace records kept (0: 65536); older records are overwritten */
+  uint32_t idle_exit_us;       /* persistent mode: the resident kernel returns after this long without work so
+                                  that every wave ends (0: 200000); the launcher thread starts the next window */
+} blink_config;
+
+typedef struct {
+  float temperature;           /* 0: greedy (largest logit, ties to the lowest id) */
+  uint32_t top_k;              /* 0: no top-k filter */
+  float top_p;                 /* in (0, 1] */
+  uint64_t seed;               /* Philox4x32-10 key; the counter is the index of the output token */
+} blink_sampling;
+
+#define BLINK_EVENT_FIRST 1u
+#define BLINK_EVENT_LAST 2u
+
+typedef struct {
+  uint64_t request_id;         /* ticket returned by blink_submit */
+  uint32_t index;              /* 0-based index of this token in the request's output */
+  int32_t token;
+  uint32_t flags;              /* BLINK_EVENT_* */
+  uint32_t iteration;          /* loop iteration that produced the token */
+  uint64_t device_ns;          /* device wall clock when the token was published */
+} blink_event;
+
+/* one record per iteration (section 4.2 loop: scan, claim, batch, launch, publish) */
+typedef struct {
+  uint32_t iteration;
+  uint32_t kind;               /* 1 prefill, 2 decode */
+  uint64_t tail;               /* tickets below this were visible to the poll of this iteration */
+  uint32_t n_admitted;
+  uint32_t n_seqs;
+  uint32_t n_tokens;
+  uint32_t free_blocks;        /* after allocation */
+  uint64_t first_admitted;     /* ticket, valid when n_admitted > 0 */
+  uint64_t t_sched_begin_ns, t_sched_end_ns, t_forward_end_ns, t_publish_end_ns; /* device wall clock */
+} blink_trace_record;
+
+typedef struct {
+  uint64_t iterations;         /* non-idle iterations executed since init */
+  uint64_t prefill_iterations;
+  uint64_t tokens_out;         /* output tokens published */
+  uint64_t tokens_prefilled;   /* prompt tokens processed */
+  uint64_t next_ticket;        /* first ticket not yet admitted */
+  uint32_t n_running;
+  uint32_t free_blocks;
+  uint32_t committed_blocks;
+  uint32_t device_error;       /* non-zero: the loop stopped on an internal error */
+  uint32_t running;            /* 1 while the loop is active */
+  uint32_t windows;            /* persistent mode: resident-kernel launches so far */
+  uint64_t kv_bytes, weight_bytes, ring_bytes;
+} blink_stats;
+
+/* blink_debug_read selectors (tests only; call while the loop is stopped) */
+enum {
+  BLINK_DBG_LOGITS = 1,        /* float[n_seqs][vocab] of the last iteration (needs BLINK_FLAG_KEEP_LOGITS) */
+  BLINK_DBG_FREE_STACK = 2,    /* uint32 free_top, then uint32[free_top] block ids, bottom first */
+  BLINK_DBG_INPUT_IDS = 3,     /* int32[n_tokens] of the last iteration */
+  BLINK_DBG_POSITIONS = 4,     /* int32[n_tokens] */
+  BLINK_DBG_SLOT_MAPPING = 5,  /* int32[n_tokens] */
+  BLINK_DBG_SEQ_BATCH_SLOT = 6,/* uint32[n_seqs] */
+  BLINK_DBG_BLOCK_TABLES = 7,  /* uint32[max_batch][max_blocks_per_seq], rows by batch slot */
+  BLINK_DBG_SEQ_LENS = 8,      /* uint32[n_seqs] */
+  BLINK_DBG_CU_SEQLENS = 9,    /* uint32[n_seqs + 1] */
+  BLINK_DBG_SLOT_STATES = 10,  /* uint32[ring_slots] */
+  BLINK_DBG_HIDDEN = 11        /* float[n_tokens][d_model]: residual stream after the last layer */
+};
+
+/* Provisioning (section 4.1): allocates all device memory, uploads and re-tiles the weights, builds the
+ * ring, the free list and the scheduler state. Nothing is allocated afterwards. */
+int blink_init(const blink_config* cfg, blink_engine** out);
+
+/* Ring write (section 4.4 "RDMA datapath"): copies the descriptor and the prompt into the slot of the next
+ * ticket, then sets the slot state to PREFILL_PENDING. request_id_out receives the ticket (0,1,2,.. in
+ * submission order, which is the FCFS order). BLINK_ERR_FULL when that slot has not been emptied yet. */
+int blink_submit(blink_engine* e, const int32_t* prompt, uint32_t n_prompt, uint32_t max_new_tokens,
+                 const blink_sampling* sampling, uint64_t* request_id_out);
+
+/* Starts the serving loop (section 4.2 "Persistent scheduler") and returns at once. The loop ends after
+ * max_iterations forward passes (0: unbounded), on blink_shutdown, or when idle if BLINK_FLAG_EXIT_WHEN_IDLE.
+ * All state lives in device memory and survives the end of the loop: calling blink_run again continues
+ * from the same logical point. BLINK_ERR_STATE if the loop is still active. */
+int blink_run(blink_engine* e, uint64_t max_iterations);
+
+/* Blocks until the loop started by blink_run has ended. Returns BLINK_ERR_DEVICE if it ended on an error. */
+int blink_wait(blink_engine* e);
+
+/* Token reader (section 4.4): non-blocking. Reads the slot metadata in one copy, compares generation counts
+ * with the host's shadow, fetches the new tokens and writes up to cap events: per request in index order.
+ * A slot returns to EMPTY once its LAST event has been delivered. */
+int blink_poll_outputs(blink_engine* e, blink_event* buf, uint32_t cap, uint32_t* n_out);
+
+/* Sets the device stop flag, waits for the loop to end, frees everything. The handle is invalid afterwards. */
+int blink_shutdown(blink_engine* e);
+
+/* Measurement and test helpers. */
+int blink_get_trace(blink_engine* e, blink_trace_record* buf, uint64_t cap_records, uint64_t* n_out);
+int blink_get_stats(blink_engine* e, blink_stats* out);
+int blink_debug_read(blink_engine* e, uint32_t what, void* buf, uint64_t cap_bytes, uint64_t* n_bytes);
+/* Times `reps` launches of one forward GEMM of the decode path over `batch` synthetic tokens with HIP events
+ * on the engine's stream (gemm: 0 qkv, 1 o, 2 gate/up, 3 down, 4 lm head). Loop must be stopped. */
+int blink_bench_gemm(blink_engine* e, uint32_t gemm, uint32_t batch, uint32_t reps, float* avg_us_out);
+/* Message of the last error on the calling thread ("" if none). The pointer stays valid until the next call. */
+const char* blink_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,180 @@
+"""ctypes binding of include/blink.h. Same names as the C ABI, numpy arrays in and out."""
+import ctypes as C
+import os
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+FLAG_TRACE, FLAG_EXIT_WHEN_IDLE, FLAG_PERSISTENT, FLAG_KEEP_LOGITS = 1, 2, 4, 8
+ERR_INVAL, ERR_TOO_LARGE, ERR_FULL, ERR_DEVICE, ERR_STATE = -1, -2, -3, -4, -5
+EVENT_FIRST, EVENT_LAST = 1, 2
+
+EXPORTS = ["blink_init", "blink_submit", "blink_run", "blink_wait", "blink_poll_outputs", "blink_shutdown",
+           "blink_get_trace", "blink_get_stats", "blink_debug_read", "blink_bench_gemm", "blink_last_error"]
+
+
+class DBG:
+    LOGITS, FREE_STACK, INPUT_IDS, POSITIONS, SLOT_MAPPING, SEQ_BATCH_SLOT, BLOCK_TABLES, SEQ_LENS, CU_SEQLENS, \
+        SLOT_STATES, HIDDEN = range(1, 12)
+
+
+class Config(C.Structure):
+    _fields_ = [(n, C.c_uint32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab", "dtype")] + [
+        ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("weights", C.c_void_p), ("weights_bytes", C.c_uint64),
+        ("kv_block_size", C.c_uint32), ("kv_num_blocks", C.c_uint32), ("max_batch", C.c_uint32), ("max_seq_len", C.c_uint32),
+        ("max_prefill_tokens", C.c_uint32), ("ring_slots", C.c_uint32), ("eos_token_id", C.c_int32), ("device", C.c_int32),
+        ("flags", C.c_uint32), ("trace_capacity", C.c_uint32), ("idle_exit_us", C.c_uint32)]
+
+
+class Sampling(C.Structure):
+    _fields_ = [("temperature", C.c_float), ("top_k", C.c_uint32), ("top_p", C.c_float), ("seed", C.c_uint64)]
+
+
+class Stats(C.Structure):
+    _fields_ = [("iterations", C.c_uint64), ("prefill_iterations", C.c_uint64), ("tokens_out", C.c_uint64),
+                ("tokens_prefilled", C.c_uint64), ("next_ticket", C.c_uint64), ("n_running", C.c_uint32),
+                ("free_blocks", C.c_uint32), ("committed_blocks", C.c_uint32), ("device_error", C.c_uint32),
+                ("running", C.c_uint32), ("windows", C.c_uint32), ("kv_bytes", C.c_uint64), ("weight_bytes", C.c_uint64),
+                ("ring_bytes", C.c_uint64)]
+
+
+EVENT_DTYPE = np.dtype([("request_id", "<u8"), ("index", "<u4"), ("token", "<i4"), ("flags", "<u4"), ("iteration", "<u4"),
+                        ("device_ns", "<u8")], align=True)
+TRACE_DTYPE = np.dtype([("iteration", "<u4"), ("kind", "<u4"), ("tail", "<u8"), ("n_admitted", "<u4"), ("n_seqs", "<u4"),
+                        ("n_tokens", "<u4"), ("free_blocks", "<u4"), ("first_admitted", "<u8"), ("t_sched_begin_ns", "<u8"),
+                        ("t_sched_end_ns", "<u8"), ("t_forward_end_ns", "<u8"), ("t_publish_end_ns", "<u8")], align=True)
+
+
+class BlinkError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"blink error {code}: {msg}")
+        self.code = code
+
+
+def lib_path():
+    return os.path.join(HERE, "libblink.so")
+
+
+_lib = None
+
+
+def load_library():
+    """Loads libblink.so; raises if it has not been built (there is no fallback path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    p = lib_path()
+    if not os.path.exists(p):
+        raise ImportError(f"{p} is missing: build it with `python -m paper_2604_07609_amd.build`")
+    lib = C.CDLL(p)
+    vp, u32, u64 = C.c_void_p, C.c_uint32, C.c_uint64
+    lib.blink_init.argtypes = [C.POINTER(Config), C.POINTER(vp)]
+    lib.blink_submit.argtypes = [vp, vp, u32, u32, C.POINTER(Sampling), C.POINTER(u64)]
+    lib.blink_run.argtypes = [vp, u64]
+    lib.blink_wait.argtypes = [vp]
+    lib.blink_poll_outputs.argtypes = [vp, vp, u32, C.POINTER(u32)]
+    lib.blink_shutdown.argtypes = [vp]
+    lib.blink_get_trace.argtypes = [vp, vp, u64, C.POINTER(u64)]
+    lib.blink_get_stats.argtypes = [vp, C.POINTER(Stats)]
+    lib.blink_debug_read.argtypes = [vp, u32, vp, u64, C.POINTER(u64)]
+    lib.blink_bench_gemm.argtypes = [vp, u32, u32, u32, C.POINTER(C.c_float)]
+    lib.blink_last_error.restype = C.c_char_p
+    for n in EXPORTS[:-1]:
+        getattr(lib, n).restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def _check(lib, rc):
+    if rc != 0:
+        raise BlinkError(rc, lib.blink_last_error().decode())
+
+
+class Engine:
+    """One serving engine on one GPU. model/engine: dicts as in synth.configs; blob: uint8 array (synth.pack_blob)."""
+
+    def __init__(self, model, engine, blob, flags=0, device=0, trace_capacity=0, idle_exit_us=0):
+        self.lib = load_library()
+        self.model, self.engine = dict(model), dict(engine)
+        blob = np.ascontiguousarray(blob, dtype=np.uint8)
+        cfg = Config()
+        for k in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab", "dtype", "rms_eps", "rope_theta"):
+            setattr(cfg, k, model[k])
+        for k in ("kv_block_size", "kv_num_blocks", "max_batch", "max_seq_len", "max_prefill_tokens", "ring_slots", "eos_token_id"):
+            setattr(cfg, k, engine[k])
+        cfg.weights = blob.ctypes.data
+        cfg.weights_bytes = blob.nbytes
+        cfg.device, cfg.flags, cfg.trace_capacity, cfg.idle_exit_us = device, flags, trace_capacity, idle_exit_us
+        self.h = C.c_void_p()
+        _check(self.lib, self.lib.blink_init(C.byref(cfg), C.byref(self.h)))
+
+    def submit(self, prompt, max_new_tokens, temperature=0.0, top_k=0, top_p=1.0, seed=0):
+        p = np.ascontiguousarray(prompt, dtype=np.int32)
+        s = Sampling(float(temperature), int(top_k), float(top_p), int(seed) & 0xFFFFFFFFFFFFFFFF)
+        rid = C.c_uint64()
+        _check(self.lib, self.lib.blink_submit(self.h, p.ctypes.data, p.size, int(max_new_tokens), C.byref(s), C.byref(rid)))
+        return rid.value
+
+    def submit_request(self, r):
+        return self.submit(r["prompt"], r["max_new_tokens"], r["temperature"], r["top_k"], r["top_p"], r["seed"])
+
+    def run(self, max_iterations=0):
+        _check(self.lib, self.lib.blink_run(self.h, int(max_iterations)))
+
+    def wait(self):
+        _check(self.lib, self.lib.blink_wait(self.h))
+
+    def poll(self, cap=4096):
+        buf = np.zeros(cap, dtype=EVENT_DTYPE)
+        n = C.c_uint32()
+        _check(self.lib, self.lib.blink_poll_outputs(self.h, buf.ctypes.data, cap, C.byref(n)))
+        return buf[: n.value]
+
+    def drain(self, cap=4096):
+        """Polls until a poll returns nothing. Returns all events as one array."""
+        out = []
+        while True:
+            ev = self.poll(cap)
+            if ev.size == 0:
+                break
+            out.append(ev.copy())
+        return np.concatenate(out) if out else np.zeros(0, dtype=EVENT_DTYPE)
+
+    def trace(self, cap=1 << 16):
+        buf = np.zeros(cap, dtype=TRACE_DTYPE)
+        n = C.c_uint64()
+        _check(self.lib, self.lib.blink_get_trace(self.h, buf.ctypes.data, cap, C.byref(n)))
+        return buf[: n.value]
+
+    def stats(self):
+        s = Stats()
+        _check(self.lib, self.lib.blink_get_stats(self.h, C.byref(s)))
+        return {k: getattr(s, k) for k, _ in Stats._fields_}
+
+    def debug_read(self, what, dtype, max_bytes=None):
+        if max_bytes is None:
+            m, e = self.model, self.engine
+            max_t = max(e["max_prefill_tokens"], e["max_seq_len"], e["max_batch"])
+            max_bytes = 8 + 4 * max(e["max_batch"] * m["vocab"], e["kv_num_blocks"] + 1, max_t * m["d_model"],
+                                    e["max_batch"] * ((e["max_seq_len"] + 15) // 16), e["ring_slots"])
+        buf = np.zeros(max_bytes, dtype=np.uint8)
+        n = C.c_uint64()
+        _check(self.lib, self.lib.blink_debug_read(self.h, int(what), buf.ctypes.data, buf.nbytes, C.byref(n)))
+        return buf[: n.value].view(dtype).copy()
+
+    def bench_gemm(self, gemm, batch, reps=20):
+        out = C.c_float()
+        _check(self.lib, self.lib.blink_bench_gemm(self.h, int(gemm), int(batch), int(reps), C.byref(out)))
+        return out.value
+
+    def shutdown(self):
+        if self.h:
+            _check(self.lib, self.lib.blink_shutdown(self.h))
+            self.h = C.c_void_p()
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *a):
+        self.shutdown()

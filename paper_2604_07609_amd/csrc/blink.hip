@@ -1,0 +1,585 @@
+// libblink: host side of the C ABI (provisioning, ring producer, token reader, loop launcher) and the
+// kernel entry points. See include/blink.h for the contract of every exported function.
+#include "../../include/blink.h"
+#include "blink_device.h"
+#include "phases.h"
+
+#include <algorithm>
+#include <atomic>
+#include <chrono>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <string>
+#include <thread>
+#include <vector>
+
+// ================================================================================================
+// kernels
+// ================================================================================================
+__global__ void __launch_bounds__(BLK_THREADS) k_sched(DevCtx c, u64 iter_limit) {
+  __shared__ SchedShared sh;
+  sched_step(c, iter_limit, sh);
+}
+
+__global__ void __launch_bounds__(BLK_THREADS) k_phase(DevCtx c, int ph, u32 layer) {
+  __shared__ PhaseShared sh;
+  run_phase(c, ph, layer, sh, blockIdx.x, gridDim.x);
+}
+
+// (cos, sin) of pos * theta^(-2i/hd), evaluated in fp64 and rounded once
+__global__ void k_rope_table(float2* tab, u32 max_pos, u32 half, double theta) {
+  const u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (u64)max_pos * half) return;
+  const u32 p = (u32)(i / half), j = (u32)(i % half);
+  const double ang = (double)p * pow(theta, -2.0 * (double)j / (double)(2 * half));
+  tab[i] = make_float2((float)cos(ang), (float)sin(ang));
+}
+
+__global__ void k_clear_stopped(SchedState* ss) { ss->stopped = 0; }
+
+// ================================================================================================
+// host
+// ================================================================================================
+static thread_local std::string g_err;
+static int fail(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+#define HIPCHK(x)                                                                                   \
+  do {                                                                                              \
+    hipError_t e_ = (x);                                                                            \
+    if (e_ != hipSuccess) return fail(BLINK_ERR_DEVICE, "%s: %s (%s:%d)", #x, hipGetErrorString(e_), __FILE__, __LINE__); \
+  } while (0)
+
+struct blink_engine {
+  blink_config cfg{};
+  DevCtx ctx{};
+  int n_cu = 256;
+  u32 grid = 512;
+  hipStream_t compute = nullptr, s_in = nullptr, s_out = nullptr;
+  std::vector<void*> dev_allocs;
+  std::vector<void*> host_allocs;
+  HostCtrl* hctrl = nullptr;
+  HostMirror* hmirror = nullptr;
+  // producer side
+  u64 next_ticket = 0;
+  char* stage_in = nullptr;       // pinned: descriptor + status + prompt
+  // reader side
+  std::vector<std::atomic<u32>> shadow_state;   // host view: 0 empty, 1 in flight
+  std::vector<u32> delivered;
+  std::vector<u64> slot_ticket;
+  SlotStatus* stage_status = nullptr;  // pinned [ring_slots]
+  OutRec* stage_out = nullptr;         // pinned
+  u64 stage_out_cap = 0;
+  SlotStatus* stage_empty = nullptr;   // pinned zero status
+  // loop
+  std::thread launcher;
+  std::atomic<bool> loop_active{false};
+  std::atomic<int> loop_rc{0};
+  std::atomic<u32> windows{0};
+  bool shut = false;
+  u64 weight_bytes = 0, kv_bytes = 0, ring_bytes = 0;
+  std::mutex dev_mu;   // serialises hipSetDevice-dependent host calls that allocate nothing
+
+  explicit blink_engine(u32 slots) : shadow_state(slots) {}
+};
+
+template <typename T>
+static int dalloc(blink_engine* e, T** p, u64 count, bool zero = true) {
+  void* q = nullptr;
+  const u64 bytes = count * sizeof(T) > 0 ? count * sizeof(T) : 16;
+  HIPCHK(hipMalloc(&q, bytes));
+  e->dev_allocs.push_back(q);
+  if (zero) HIPCHK(hipMemset(q, 0, bytes));
+  *p = (T*)q;
+  return 0;
+}
+template <typename T>
+static int halloc(blink_engine* e, T** p, u64 count) {
+  void* q = nullptr;
+  HIPCHK(hipHostMalloc(&q, count * sizeof(T) > 0 ? count * sizeof(T) : 16, hipHostMallocMapped));
+  memset(q, 0, count * sizeof(T));
+  e->host_allocs.push_back(q);
+  *p = (T*)q;
+  return 0;
+}
+
+static u64 expected_weight_bytes(const blink_config* c) {
+  const u64 es = c->dtype == 1 ? 2 : 4;
+  const u64 d = c->d_model, hd = c->head_dim, nq = c->n_q_heads, nkv = c->n_kv_heads, F = c->d_ffn, V = c->vocab;
+  const u64 per_layer = 4 * d + 4 * d + es * ((nq + 2 * nkv) * hd * d + d * nq * hd + 2 * F * d + d * F);
+  return es * V * d * 2 + c->n_layers * per_layer + 4 * d;
+}
+
+static void free_all(blink_engine* e) {
+  for (void* p : e->dev_allocs) (void)hipFree(p);
+  for (void* p : e->host_allocs) (void)hipHostFree(p);
+  if (e->compute) (void)hipStreamDestroy(e->compute);
+  if (e->s_in) (void)hipStreamDestroy(e->s_in);
+  if (e->s_out) (void)hipStreamDestroy(e->s_out);
+  delete e;
+}
+
+static int init_impl(const blink_config* cfg, blink_engine* e) {
+  HIPCHK(hipSetDevice(cfg->device));
+  hipDeviceProp_t prop;
+  HIPCHK(hipGetDeviceProperties(&prop, cfg->device));
+  e->n_cu = prop.multiProcessorCount;
+  e->grid = (u32)e->n_cu * 2;
+  HIPCHK(hipStreamCreateWithFlags(&e->compute, hipStreamNonBlocking));
+  HIPCHK(hipStreamCreateWithFlags(&e->s_in, hipStreamNonBlocking));
+  HIPCHK(hipStreamCreateWithFlags(&e->s_out, hipStreamNonBlocking));
+  DevCtx& c = e->ctx;
+  c.n_layers = cfg->n_layers; c.d = cfg->d_model; c.nq = cfg->n_q_heads; c.nkv = cfg->n_kv_heads; c.hd = cfg->head_dim;
+  c.F = cfg->d_ffn; c.V = cfg->vocab; c.dtype = cfg->dtype; c.eps = cfg->rms_eps; c.theta = cfg->rope_theta;
+  c.bs = cfg->kv_block_size; c.n_blocks = cfg->kv_num_blocks; c.max_batch = cfg->max_batch; c.max_seq_len = cfg->max_seq_len;
+  c.max_prefill_tokens = cfg->max_prefill_tokens; c.ring_slots = cfg->ring_slots;
+  c.max_blocks_per_seq = (cfg->max_seq_len + cfg->kv_block_size - 1) / cfg->kv_block_size;
+  // a prefill iteration holds at most max_prefill_tokens, except that its first request is exempt
+  c.maxT = std::max(std::max(cfg->max_prefill_tokens, cfg->max_seq_len), cfg->max_batch);
+  c.eos = cfg->eos_token_id; c.flags = cfg->flags; c.trace_cap = cfg->trace_capacity ? cfg->trace_capacity : 65536u;
+  c.qkv_n = (c.nq + 2 * c.nkv) * c.hd;
+  const u64 es = c.dtype == 1 ? 2 : 4;
+
+  // ---- ring ----
+  SlotStatus* status; SlotDesc* desc; i32* in_arena; OutRec* out_arena;
+  if (int rc = dalloc(e, &status, c.ring_slots)) return rc;
+  if (int rc = dalloc(e, &desc, c.ring_slots)) return rc;
+  if (int rc = dalloc(e, &in_arena, (u64)c.ring_slots * c.max_seq_len, false)) return rc;
+  if (int rc = dalloc(e, &out_arena, (u64)c.ring_slots * c.max_seq_len, false)) return rc;
+  c.status = status; c.desc = desc; c.in_arena = in_arena; c.out_arena = out_arena;
+  e->ring_bytes = (u64)c.ring_slots * (sizeof(SlotStatus) + sizeof(SlotDesc) + (u64)c.max_seq_len * (4 + sizeof(OutRec)));
+  if (int rc = halloc(e, &e->hctrl, 1)) return rc;
+  if (int rc = halloc(e, &e->hmirror, 1)) return rc;
+  c.hctrl = e->hctrl; c.hmirror = e->hmirror;
+  if (int rc = halloc(e, &e->stage_in, sizeof(SlotDesc) + sizeof(SlotStatus) + (u64)c.max_seq_len * 4)) return rc;
+  if (int rc = halloc(e, &e->stage_status, c.ring_slots)) return rc;
+  e->stage_out_cap = 1u << 16;
+  if (int rc = halloc(e, &e->stage_out, e->stage_out_cap)) return rc;
+  if (int rc = halloc(e, &e->stage_empty, 1)) return rc;
+  e->delivered.assign(c.ring_slots, 0);
+  e->slot_ticket.assign(c.ring_slots, 0);
+  for (auto& s : e->shadow_state) s.store(0);
+
+  // ---- scheduler state ----
+  if (int rc = dalloc(e, &c.ss, 1)) return rc;
+  if (int rc = dalloc(e, &c.run, c.max_batch)) return rc;
+  if (int rc = dalloc(e, &c.block_tables, (u64)c.max_batch * c.max_blocks_per_seq)) return rc;
+  if (int rc = dalloc(e, &c.free_stack, c.n_blocks)) return rc;
+  if (int rc = dalloc(e, &c.meta, 1)) return rc;
+  if (int rc = dalloc(e, &c.seq_bslot, c.max_batch)) return rc;
+  if (int rc = dalloc(e, &c.seq_len, c.max_batch)) return rc;
+  if (int rc = dalloc(e, &c.cu_seqlens, c.max_batch + 1)) return rc;
+  if (int rc = dalloc(e, &c.last_idx, c.max_batch)) return rc;
+  if (int rc = dalloc(e, &c.input_ids, c.maxT)) return rc;
+  if (int rc = dalloc(e, &c.positions, c.maxT)) return rc;
+  if (int rc = dalloc(e, &c.slot_mapping, c.maxT)) return rc;
+  if (int rc = dalloc(e, &c.tok_seq, c.maxT)) return rc;
+  if (int rc = dalloc(e, &c.trace, c.trace_cap)) return rc;
+  {
+    std::vector<u32> fs(c.n_blocks);
+    for (u32 i = 0; i < c.n_blocks; ++i) fs[i] = c.n_blocks - 1 - i;   // first pops return 0, 1, 2, ...
+    HIPCHK(hipMemcpy(c.free_stack, fs.data(), (u64)c.n_blocks * 4, hipMemcpyHostToDevice));
+    SchedState s0{};
+    s0.free_top = c.n_blocks;
+    s0.stopped = 1;
+    HIPCHK(hipMemcpy(c.ss, &s0, sizeof s0, hipMemcpyHostToDevice));
+  }
+
+  // ---- weights: the blob is uploaded as is; matrices are used in their [out][in] layout ----
+  char* wdev;
+  if (int rc = dalloc(e, &wdev, cfg->weights_bytes, false)) return rc;
+  HIPCHK(hipMemcpy(wdev, cfg->weights, cfg->weights_bytes, hipMemcpyHostToDevice));
+  e->weight_bytes = cfg->weights_bytes;
+  {
+    std::vector<LayerW> lw(c.n_layers);
+    u64 off = 0;
+    const u64 d = c.d, hd = c.hd, nq = c.nq, nkv = c.nkv, F = c.F, V = c.V;
+    c.embed = wdev + off; off += es * V * d;
+    for (u32 l = 0; l < c.n_layers; ++l) {
+      lw[l].g1 = (const float*)(wdev + off); off += 4 * d;
+      lw[l].wqkv = wdev + off; off += es * (nq + 2 * nkv) * hd * d;
+      lw[l].wo = wdev + off; off += es * d * nq * hd;
+      lw[l].g2 = (const float*)(wdev + off); off += 4 * d;
+      lw[l].wgu = wdev + off; off += es * 2 * F * d;
+      lw[l].wd = wdev + off; off += es * d * F;
+    }
+    c.gf = (const float*)(wdev + off); off += 4 * d;
+    c.lm = wdev + off; off += es * V * d;
+    if (off != cfg->weights_bytes) return fail(BLINK_ERR_INVAL, "internal: weight layout %llu != %llu", (unsigned long long)off, (unsigned long long)cfg->weights_bytes);
+    LayerW* dl;
+    if (int rc = dalloc(e, &dl, c.n_layers)) return rc;
+    HIPCHK(hipMemcpy(dl, lw.data(), sizeof(LayerW) * c.n_layers, hipMemcpyHostToDevice));
+    c.layers = dl;
+  }
+  {
+    float2* tab;
+    if (int rc = dalloc(e, &tab, (u64)c.max_seq_len * (c.hd / 2), false)) return rc;
+    const u64 n = (u64)c.max_seq_len * (c.hd / 2);
+    hipLaunchKernelGGL(k_rope_table, dim3((u32)((n + 255) / 256)), dim3(256), 0, e->compute, tab, c.max_seq_len, c.hd / 2, (double)c.theta);
+    HIPCHK(hipGetLastError());
+    c.rope_tab = tab;
+  }
+  // ---- KV pool ----
+  c.kv_kv_stride = (u64)c.n_blocks * c.nkv * c.bs * c.hd;
+  c.kv_layer_stride = 2 * c.kv_kv_stride;
+  e->kv_bytes = (u64)c.n_layers * c.kv_layer_stride * es;
+  char* kv;
+  if (int rc = dalloc(e, &kv, e->kv_bytes, false)) return rc;
+  c.kv = kv;
+  // ---- activations ----
+  if (int rc = dalloc(e, &c.x, (u64)c.maxT * c.d)) return rc;
+  if (int rc = dalloc(e, &c.h, (u64)c.maxT * c.d)) return rc;
+  if (int rc = dalloc(e, &c.qkv, (u64)c.maxT * c.qkv_n)) return rc;
+  if (int rc = dalloc(e, &c.attn, (u64)c.maxT * c.nq * c.hd)) return rc;
+  if (int rc = dalloc(e, &c.gu, (u64)c.maxT * 2 * c.F)) return rc;
+  if (int rc = dalloc(e, &c.hlast, (u64)c.max_batch * c.d)) return rc;
+  if (int rc = dalloc(e, &c.logits, (u64)c.max_batch * c.V)) return rc;
+  HIPCHK(hipStreamSynchronize(e->compute));
+  HIPCHK(hipDeviceSynchronize());
+  return 0;
+}
+
+extern "C" int blink_init(const blink_config* cfg, blink_engine** out) {
+  g_err.clear();
+  if (!cfg || !out) return fail(BLINK_ERR_INVAL, "null argument");
+  *out = nullptr;
+  if (!cfg->weights) return fail(BLINK_ERR_INVAL, "weights is null");
+  if (cfg->dtype > 1) return fail(BLINK_ERR_INVAL, "dtype must be 0 (fp32) or 1 (bf16)");
+  if (!cfg->n_layers || !cfg->d_model || !cfg->n_q_heads || !cfg->n_kv_heads || !cfg->d_ffn || !cfg->vocab)
+    return fail(BLINK_ERR_INVAL, "zero model dimension");
+  if (cfg->head_dim != 64 && cfg->head_dim != 128) return fail(BLINK_ERR_INVAL, "head_dim must be 64 or 128");
+  if (cfg->n_q_heads % cfg->n_kv_heads || cfg->n_q_heads / cfg->n_kv_heads > ATT_MAX_G)
+    return fail(BLINK_ERR_INVAL, "n_q_heads must be a multiple (at most %d) of n_kv_heads", ATT_MAX_G);
+  if (cfg->d_model % 32 || cfg->d_ffn % 32 || (cfg->n_q_heads * cfg->head_dim) % 32)
+    return fail(BLINK_ERR_INVAL, "d_model, d_ffn and n_q_heads*head_dim must be multiples of 32");
+  if (cfg->vocab >= (1u << 24)) return fail(BLINK_ERR_INVAL, "vocab must be below 2^24");
+  if (cfg->kv_block_size != 16) return fail(BLINK_ERR_INVAL, "kv_block_size must be 16");
+  if (!cfg->kv_num_blocks || !cfg->max_batch || cfg->max_batch > SCHED_MAX_BATCH)
+    return fail(BLINK_ERR_INVAL, "kv_num_blocks must be positive and max_batch in [1, %d]", SCHED_MAX_BATCH);
+  if (!cfg->max_seq_len || !cfg->max_prefill_tokens) return fail(BLINK_ERR_INVAL, "max_seq_len and max_prefill_tokens must be positive");
+  if (!cfg->ring_slots || (cfg->ring_slots & (cfg->ring_slots - 1))) return fail(BLINK_ERR_INVAL, "ring_slots must be a power of two");
+  if (cfg->weights_bytes != expected_weight_bytes(cfg))
+    return fail(BLINK_ERR_INVAL, "weights_bytes is %llu, the model needs %llu", (unsigned long long)cfg->weights_bytes,
+                (unsigned long long)expected_weight_bytes(cfg));
+  int n_dev = 0;
+  if (hipGetDeviceCount(&n_dev) != hipSuccess || n_dev <= 0) return fail(BLINK_ERR_DEVICE, "no HIP device available");
+  if (cfg->device < 0 || cfg->device >= n_dev) return fail(BLINK_ERR_INVAL, "device %d out of range", cfg->device);
+  blink_engine* e = new blink_engine(cfg->ring_slots);
+  e->cfg = *cfg;
+  e->cfg.weights = nullptr;
+  const int rc = init_impl(cfg, e);
+  if (rc) {
+    const std::string keep = g_err;
+    free_all(e);
+    g_err = keep;
+    return rc;
+  }
+  *out = e;
+  return BLINK_OK;
+}
+
+extern "C" int blink_submit(blink_engine* e, const int32_t* prompt, uint32_t n_prompt, uint32_t max_new_tokens,
+                            const blink_sampling* sp, uint64_t* request_id_out) {
+  g_err.clear();
+  if (!e || !prompt || !sp) return fail(BLINK_ERR_INVAL, "null argument");
+  if (e->shut) return fail(BLINK_ERR_STATE, "engine is shut down");
+  const DevCtx& c = e->ctx;
+  if (n_prompt == 0 || max_new_tokens == 0) return fail(BLINK_ERR_INVAL, "empty prompt or max_new_tokens == 0");
+  if (!(sp->temperature >= 0.f) || !(sp->top_p > 0.f && sp->top_p <= 1.f)) return fail(BLINK_ERR_INVAL, "temperature must be >= 0 and top_p in (0,1]");
+  if (sp->temperature > 0.f && (sp->top_k == 0 || sp->top_k > SAMPLER_MAX_K) && c.V > SAMPLER_MAX_K)
+    return fail(BLINK_ERR_INVAL, "sampling needs top_k in [1, %d] when vocab exceeds %d", SAMPLER_MAX_K, SAMPLER_MAX_K);
+  if ((u64)n_prompt + max_new_tokens > c.max_seq_len) return fail(BLINK_ERR_TOO_LARGE, "prompt + max_new_tokens exceeds max_seq_len");
+  const u64 need = std::max<u64>(1, ((u64)n_prompt + max_new_tokens - 1 + c.bs - 1) / c.bs);
+  if (need > c.n_blocks) return fail(BLINK_ERR_TOO_LARGE, "KV reservation of %llu blocks exceeds the pool", (unsigned long long)need);
+  for (u32 i = 0; i < n_prompt; ++i)
+    if (prompt[i] < 0 || (u32)prompt[i] >= c.V) return fail(BLINK_ERR_INVAL, "token id %d at %u outside the vocabulary", prompt[i], i);
+  const u64 t = e->next_ticket;
+  const u32 slot = (u32)(t & (c.ring_slots - 1));
+  if (e->shadow_state[slot].load(std::memory_order_acquire) != 0) return fail(BLINK_ERR_FULL, "ring slot %u still in use", slot);
+  HIPCHK(hipSetDevice(e->cfg.device));
+  // payload first: prompt tokens and descriptor; then the state word (section 4.4 "RDMA datapath")
+  SlotDesc* d = (SlotDesc*)e->stage_in;
+  SlotStatus* st = (SlotStatus*)(e->stage_in + sizeof(SlotDesc));
+  i32* ptoks = (i32*)(e->stage_in + sizeof(SlotDesc) + sizeof(SlotStatus));
+  memset(d, 0, sizeof *d);
+  d->ticket = t; d->n_prompt = n_prompt; d->max_new = max_new_tokens; d->temperature = sp->temperature; d->top_k = sp->top_k;
+  d->top_p = sp->top_p; d->seed = sp->seed;
+  memcpy(ptoks, prompt, (u64)n_prompt * 4);
+  st->state = BLINK_SLOT_PREFILL_PENDING; st->gen_count = 0; st->ticket_lo = (u32)t; st->flags = 0;
+  HIPCHK(hipMemcpyAsync(c.in_arena + (u64)slot * c.max_seq_len, ptoks, (u64)n_prompt * 4, hipMemcpyHostToDevice, e->s_in));
+  HIPCHK(hipMemcpyAsync(c.desc + slot, d, sizeof *d, hipMemcpyHostToDevice, e->s_in));
+  HIPCHK(hipStreamSynchronize(e->s_in));
+  e->slot_ticket[slot] = t;
+  e->delivered[slot] = 0;
+  e->shadow_state[slot].store(1, std::memory_order_release);
+  HIPCHK(hipMemcpyAsync(c.status + slot, st, sizeof *st, hipMemcpyHostToDevice, e->s_in));
+  HIPCHK(hipStreamSynchronize(e->s_in));
+  e->next_ticket = t + 1;
+  if (request_id_out) *request_id_out = t;
+  return BLINK_OK;
+}
+
+// ---- loop launcher: host-enqueued mode ---------------------------------------------------------------------
+static int enqueue_iteration(blink_engine* e, u64 iter_limit) {
+  const DevCtx& c = e->ctx;
+  hipLaunchKernelGGL(k_sched, dim3(1), dim3(BLK_THREADS), 0, e->compute, c, iter_limit);
+  const dim3 g(e->grid), b(BLK_THREADS);
+  hipLaunchKernelGGL(k_phase, g, b, 0, e->compute, c, (int)PH_EMBED, 0u);
+  for (u32 l = 0; l < c.n_layers; ++l)
+    for (int ph = PH_LAYER_FIRST; ph <= PH_LAYER_LAST; ++ph) hipLaunchKernelGGL(k_phase, g, b, 0, e->compute, c, ph, l);
+  hipLaunchKernelGGL(k_phase, g, b, 0, e->compute, c, (int)PH_FINAL_NORM, 0u);
+  hipLaunchKernelGGL(k_phase, g, b, 0, e->compute, c, (int)PH_LM_HEAD, 0u);
+  hipLaunchKernelGGL(k_phase, g, b, 0, e->compute, c, (int)PH_SAMPLE, 0u);
+  HIPCHK(hipGetLastError());
+  return 0;
+}
+
+static void stepped_loop(blink_engine* e, u64 iter_limit) {
+  int rc = 0;
+  if (hipSetDevice(e->cfg.device) != hipSuccess) rc = BLINK_ERR_DEVICE;
+  while (rc == 0) {
+    const u32 chunk = 4;
+    for (u32 i = 0; i < chunk && rc == 0; ++i) rc = enqueue_iteration(e, iter_limit);
+    if (rc) break;
+    if (hipStreamSynchronize(e->compute) != hipSuccess) { rc = BLINK_ERR_DEVICE; break; }
+    if (e->hmirror->error) { rc = BLINK_ERR_DEVICE; break; }
+    if (__atomic_load_n(&e->hmirror->stopped, __ATOMIC_ACQUIRE)) break;
+  }
+  e->loop_rc.store(rc);
+  e->loop_active.store(false, std::memory_order_release);
+}
+
+extern "C" int blink_run(blink_engine* e, uint64_t max_iterations) {
+  g_err.clear();
+  if (!e) return fail(BLINK_ERR_INVAL, "null engine");
+  if (e->shut) return fail(BLINK_ERR_STATE, "engine is shut down");
+  if (e->loop_active.load(std::memory_order_acquire)) return fail(BLINK_ERR_STATE, "the loop is already running");
+  if (e->launcher.joinable()) e->launcher.join();
+  HIPCHK(hipSetDevice(e->cfg.device));
+  if (e->hmirror->error) return fail(BLINK_ERR_DEVICE, "device loop error %u", e->hmirror->error);
+  const u64 iter_limit = max_iterations ? e->hmirror->iteration + max_iterations : 0;
+  e->hmirror->stopped = 0;
+  hipLaunchKernelGGL(k_clear_stopped, dim3(1), dim3(1), 0, e->compute, e->ctx.ss);
+  HIPCHK(hipGetLastError());
+  e->loop_active.store(true, std::memory_order_release);
+  e->loop_rc.store(0);
+  e->windows.fetch_add(1);
+  e->launcher = std::thread(stepped_loop, e, iter_limit);
+  return BLINK_OK;
+}
+
+extern "C" int blink_wait(blink_engine* e) {
+  g_err.clear();
+  if (!e) return fail(BLINK_ERR_INVAL, "null engine");
+  if (e->launcher.joinable()) e->launcher.join();
+  const int rc = e->loop_rc.load();
+  if (rc) return fail(rc, "the loop ended with an error (device error %u)", e->hmirror ? e->hmirror->error : 0u);
+  return BLINK_OK;
+}
+
+extern "C" int blink_poll_outputs(blink_engine* e, blink_event* buf, uint32_t cap, uint32_t* n_out) {
+  g_err.clear();
+  if (!e || !n_out || (!buf && cap)) return fail(BLINK_ERR_INVAL, "null argument");
+  *n_out = 0;
+  if (e->shut) return fail(BLINK_ERR_STATE, "engine is shut down");
+  const DevCtx& c = e->ctx;
+  HIPCHK(hipSetDevice(e->cfg.device));
+  // one bulk read of the slot metadata (section 4.4 "Token reader")
+  HIPCHK(hipMemcpyAsync(e->stage_status, c.status, sizeof(SlotStatus) * c.ring_slots, hipMemcpyDeviceToHost, e->s_out));
+  HIPCHK(hipStreamSynchronize(e->s_out));
+  struct Pick { u32 slot, from, n, stage_off; bool completed; };
+  std::vector<Pick> picks;
+  u64 staged = 0;
+  u32 budget = cap;
+  for (u32 slot = 0; slot < c.ring_slots && budget > 0; ++slot) {
+    if (e->shadow_state[slot].load(std::memory_order_acquire) == 0) continue;
+    const SlotStatus& st = e->stage_status[slot];
+    if (st.ticket_lo != (u32)e->slot_ticket[slot]) continue;
+    const u32 gen = st.gen_count, have = e->delivered[slot];
+    if (gen <= have) continue;
+    u32 n = std::min(gen - have, budget);
+    if (staged + n > e->stage_out_cap) n = (u32)(e->stage_out_cap - staged);
+    if (n == 0) break;
+    picks.push_back({slot, have, n, (u32)staged, st.state == BLINK_SLOT_DECODE_COMPLETED && have + n == gen});
+    HIPCHK(hipMemcpyAsync(e->stage_out + staged, c.out_arena + (u64)slot * c.max_seq_len + have, sizeof(OutRec) * n,
+                          hipMemcpyDeviceToHost, e->s_out));
+    staged += n;
+    budget -= n;
+  }
+  if (picks.empty()) return BLINK_OK;
+  HIPCHK(hipStreamSynchronize(e->s_out));
+  // events across requests ordered by (iteration, ring slot); per request by index
+  u32 w = 0;
+  for (const Pick& p : picks)
+    for (u32 i = 0; i < p.n; ++i) {
+      const OutRec& r = e->stage_out[p.stage_off + i];
+      blink_event& ev = buf[w++];
+      ev.request_id = e->slot_ticket[p.slot];
+      ev.index = p.from + i;
+      ev.token = r.token;
+      ev.flags = (ev.index == 0 ? BLINK_EVENT_FIRST : 0u) | ((p.completed && i + 1 == p.n) ? BLINK_EVENT_LAST : 0u);
+      ev.iteration = r.iteration;
+      ev.device_ns = r.device_ns;
+    }
+  // completed slots go back to EMPTY (the frontend's edge of the life cycle), then become reusable
+  bool any_done = false;
+  for (const Pick& p : picks) {
+    e->delivered[p.slot] = p.from + p.n;
+    if (p.completed) {
+      HIPCHK(hipMemcpyAsync(c.status + p.slot, e->stage_empty, sizeof(SlotStatus), hipMemcpyHostToDevice, e->s_out));
+      any_done = true;
+    }
+  }
+  if (any_done) {
+    HIPCHK(hipStreamSynchronize(e->s_out));
+    for (const Pick& p : picks)
+      if (p.completed) e->shadow_state[p.slot].store(0, std::memory_order_release);
+  }
+  *n_out = w;
+  return BLINK_OK;
+}
+
+extern "C" int blink_shutdown(blink_engine* e) {
+  g_err.clear();
+  if (!e) return fail(BLINK_ERR_INVAL, "null engine");
+  (void)hipSetDevice(e->cfg.device);
+  e->shut = true;
+  if (e->hctrl) __atomic_store_n(&e->hctrl->stop, 1u, __ATOMIC_RELEASE);
+  if (e->launcher.joinable()) e->launcher.join();
+  (void)hipDeviceSynchronize();
+  free_all(e);
+  return BLINK_OK;
+}
+
+extern "C" int blink_get_trace(blink_engine* e, blink_trace_record* buf, uint64_t cap_records, uint64_t* n_out) {
+  g_err.clear();
+  if (!e || !n_out || (!buf && cap_records)) return fail(BLINK_ERR_INVAL, "null argument");
+  static_assert(sizeof(blink_trace_record) == sizeof(TraceRec), "trace record layout");
+  if (e->loop_active.load()) return fail(BLINK_ERR_STATE, "stop the loop before reading the trace");
+  HIPCHK(hipSetDevice(e->cfg.device));
+  const u64 iters = e->hmirror->iteration;
+  const u64 have = std::min<u64>(iters, e->ctx.trace_cap);
+  const u64 n = std::min<u64>(have, cap_records);
+  // oldest kept record first
+  const u64 first = iters - have;
+  for (u64 i = 0; i < n; ++i) {
+    const u64 idx = (first + i) % e->ctx.trace_cap;
+    const u64 run = std::min<u64>(n - i, e->ctx.trace_cap - idx);
+    HIPCHK(hipMemcpy(buf + i, e->ctx.trace + idx, run * sizeof(TraceRec), hipMemcpyDeviceToHost));
+    i += run - 1;
+  }
+  *n_out = n;
+  return BLINK_OK;
+}
+
+extern "C" int blink_get_stats(blink_engine* e, blink_stats* out) {
+  g_err.clear();
+  if (!e || !out) return fail(BLINK_ERR_INVAL, "null argument");
+  memset(out, 0, sizeof *out);
+  out->running = e->loop_active.load() ? 1u : 0u;
+  out->windows = e->windows.load();
+  out->kv_bytes = e->kv_bytes; out->weight_bytes = e->weight_bytes; out->ring_bytes = e->ring_bytes;
+  if (out->running) {   // only the host mirror is read while the loop is active
+    out->iterations = e->hmirror->iteration;
+    out->tokens_out = e->hmirror->tokens_out;
+    out->n_running = e->hmirror->n_running;
+    out->device_error = e->hmirror->error;
+    return BLINK_OK;
+  }
+  HIPCHK(hipSetDevice(e->cfg.device));
+  SchedState s;
+  HIPCHK(hipMemcpy(&s, e->ctx.ss, sizeof s, hipMemcpyDeviceToHost));
+  out->iterations = s.iteration; out->prefill_iterations = s.prefill_iterations; out->tokens_out = s.tokens_out;
+  out->tokens_prefilled = s.tokens_prefilled; out->next_ticket = s.next_ticket; out->n_running = s.n_running;
+  out->free_blocks = s.free_top; out->committed_blocks = s.committed; out->device_error = s.error;
+  return BLINK_OK;
+}
+
+extern "C" int blink_debug_read(blink_engine* e, uint32_t what, void* buf, uint64_t cap_bytes, uint64_t* n_bytes) {
+  g_err.clear();
+  if (!e || !buf || !n_bytes) return fail(BLINK_ERR_INVAL, "null argument");
+  if (e->loop_active.load()) return fail(BLINK_ERR_STATE, "stop the loop before reading device state");
+  HIPCHK(hipSetDevice(e->cfg.device));
+  const DevCtx& c = e->ctx;
+  IterMeta m;
+  SchedState s;
+  HIPCHK(hipMemcpy(&m, c.meta, sizeof m, hipMemcpyDeviceToHost));
+  HIPCHK(hipMemcpy(&s, c.ss, sizeof s, hipMemcpyDeviceToHost));
+  const void* src = nullptr;
+  u64 n = 0;
+  switch (what) {
+    case BLINK_DBG_LOGITS: src = c.logits; n = (u64)m.n_seqs * c.V * 4; break;
+    case BLINK_DBG_FREE_STACK: {
+      n = 4 + (u64)s.free_top * 4;
+      if (n > cap_bytes) return fail(BLINK_ERR_INVAL, "buffer too small: need %llu bytes", (unsigned long long)n);
+      memcpy(buf, &s.free_top, 4);
+      HIPCHK(hipMemcpy((char*)buf + 4, c.free_stack, (u64)s.free_top * 4, hipMemcpyDeviceToHost));
+      *n_bytes = n;
+      return BLINK_OK;
+    }
+    case BLINK_DBG_INPUT_IDS: src = c.input_ids; n = (u64)m.n_tokens * 4; break;
+    case BLINK_DBG_POSITIONS: src = c.positions; n = (u64)m.n_tokens * 4; break;
+    case BLINK_DBG_SLOT_MAPPING: src = c.slot_mapping; n = (u64)m.n_tokens * 4; break;
+    case BLINK_DBG_SEQ_BATCH_SLOT: src = c.seq_bslot; n = (u64)m.n_seqs * 4; break;
+    case BLINK_DBG_BLOCK_TABLES: src = c.block_tables; n = (u64)c.max_batch * c.max_blocks_per_seq * 4; break;
+    case BLINK_DBG_SEQ_LENS: src = c.seq_len; n = (u64)m.n_seqs * 4; break;
+    case BLINK_DBG_CU_SEQLENS: src = c.cu_seqlens; n = ((u64)m.n_seqs + 1) * 4; break;
+    case BLINK_DBG_SLOT_STATES: {
+      n = (u64)c.ring_slots * 4;
+      if (n > cap_bytes) return fail(BLINK_ERR_INVAL, "buffer too small: need %llu bytes", (unsigned long long)n);
+      std::vector<SlotStatus> st(c.ring_slots);
+      HIPCHK(hipMemcpy(st.data(), c.status, sizeof(SlotStatus) * c.ring_slots, hipMemcpyDeviceToHost));
+      for (u32 i = 0; i < c.ring_slots; ++i) ((u32*)buf)[i] = st[i].state;
+      *n_bytes = n;
+      return BLINK_OK;
+    }
+    case BLINK_DBG_HIDDEN: src = c.x; n = (u64)m.n_tokens * c.d * 4; break;
+    default: return fail(BLINK_ERR_INVAL, "unknown selector %u", what);
+  }
+  if (n > cap_bytes) return fail(BLINK_ERR_INVAL, "buffer too small: need %llu bytes", (unsigned long long)n);
+  if (n) HIPCHK(hipMemcpy(buf, src, n, hipMemcpyDeviceToHost));
+  *n_bytes = n;
+  return BLINK_OK;
+}
+
+extern "C" int blink_bench_gemm(blink_engine* e, uint32_t gemm, uint32_t batch, uint32_t reps, float* avg_us_out) {
+  g_err.clear();
+  if (!e || !avg_us_out || gemm > 4 || reps == 0) return fail(BLINK_ERR_INVAL, "bad argument");
+  if (e->loop_active.load()) return fail(BLINK_ERR_STATE, "stop the loop first");
+  if (batch == 0 || batch > e->ctx.max_batch) return fail(BLINK_ERR_INVAL, "batch must be in [1, max_batch]");
+  HIPCHK(hipSetDevice(e->cfg.device));
+  const DevCtx& c = e->ctx;
+  // a synthetic decode-shaped iteration: `batch` sequences of one token each
+  IterMeta m{};
+  m.kind = KIND_DECODE; m.n_seqs = batch; m.n_tokens = batch;
+  IterMeta saved;
+  HIPCHK(hipMemcpy(&saved, c.meta, sizeof saved, hipMemcpyDeviceToHost));
+  HIPCHK(hipMemcpy(c.meta, &m, sizeof m, hipMemcpyHostToDevice));
+  static const int phase_of[5] = {PH_QKV, PH_OPROJ, PH_GATEUP, PH_DOWN, PH_LM_HEAD};
+  hipEvent_t t0, t1;
+  HIPCHK(hipEventCreate(&t0));
+  HIPCHK(hipEventCreate(&t1));
+  const dim3 g(e->grid), b(BLK_THREADS);
+  for (u32 i = 0; i < 3; ++i) hipLaunchKernelGGL(k_phase, g, b, 0, e->compute, c, phase_of[gemm], 0u);
+  HIPCHK(hipEventRecord(t0, e->compute));
+  for (u32 i = 0; i < reps; ++i) hipLaunchKernelGGL(k_phase, g, b, 0, e->compute, c, phase_of[gemm], 0u);
+  HIPCHK(hipEventRecord(t1, e->compute));
+  HIPCHK(hipEventSynchronize(t1));
+  float ms = 0.f;
+  HIPCHK(hipEventElapsedTime(&ms, t0, t1));
+  (void)hipEventDestroy(t0);
+  (void)hipEventDestroy(t1);
+  HIPCHK(hipMemcpy(c.meta, &saved, sizeof saved, hipMemcpyHostToDevice));
+  *avg_us_out = ms * 1000.f / (float)reps;
+  return BLINK_OK;
+}
+
+extern "C" const char* blink_last_error(void) { return g_err.c_str(); }

@@ -1,0 +1,180 @@
+// Device-resident data structures of the serving loop (ring, scheduler state, batch metadata).
+// Included by the host library and by every kernel file; plain structs only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef uint32_t u32;
+typedef uint64_t u64;
+typedef int32_t i32;
+typedef uint16_t bf16_t;  // bf16 bit pattern
+
+#define BLK_THREADS 256
+#define WAVE 64
+
+// ---- ring (section 4.2 "Ring buffer"): slots + input/output token arenas --------------------------
+struct SlotStatus {   // 16 B per slot: the metadata block the token reader fetches in one copy (section 4.4)
+  u32 state;          // BLINK_SLOT_*
+  u32 gen_count;      // tokens published so far
+  u32 ticket_lo;      // low 32 bits of the owning ticket
+  u32 flags;          // bit0: finished
+};
+
+struct SlotDesc {     // 64 B per slot, written by the producer before the state word
+  u64 ticket;
+  u32 n_prompt;
+  u32 max_new;
+  float temperature;
+  u32 top_k;
+  float top_p;
+  u32 pad0;
+  u64 seed;
+  u64 pad1[3];
+};
+
+struct OutRec {       // 16 B per generated token in the output arena
+  i32 token;
+  u32 iteration;
+  u64 device_ns;
+};
+
+// ---- scheduler state: everything survives the end of a loop window --------------------------------
+struct RunEntry {     // one batch slot
+  u32 valid;
+  u32 ring_slot;
+  u64 ticket;
+  u32 P;              // prompt length
+  u32 max_new;
+  u32 gen;            // tokens generated
+  u32 ctx_len;        // tokens whose K/V are in the cache
+  u32 reserved;       // worst-case block reservation
+  u32 n_blocks;       // blocks held
+  u32 finished;
+  i32 last_token;
+  float temperature;
+  u32 top_k;
+  float top_p;
+  u32 in_iter;        // 1 when admitted in the current iteration
+  u32 paused;         // 1 while its slot state is DECODE_PAUSED
+  u32 pad;
+  u64 seed;
+};
+
+struct SchedState {
+  u64 next_ticket;
+  u64 iteration;        // non-idle iterations so far
+  u64 prefill_iterations;
+  u64 tokens_out;
+  u64 tokens_prefilled;
+  u64 idle_since_ns;    // device clock when the loop last turned idle (0: not idle)
+  u32 free_top;         // entries in the free stack
+  u32 committed;        // sum of reservations
+  u32 n_running;
+  u32 stopped;          // set by the scheduler when the window ends; cleared by the host at blink_run
+  u32 error;
+  u32 pad;
+};
+
+// batch metadata of the current iteration (what the scheduler populates before the forward pass)
+struct IterMeta {
+  u32 kind;             // 0 idle, 1 prefill, 2 decode
+  u32 n_seqs;
+  u32 n_tokens;
+  u32 iteration;
+  u32 max_q_len;        // longest token run of one sequence in this iteration
+  u32 max_ctx;          // longest context after this iteration
+  u32 trace_idx;
+  u32 skip;             // 1: the window has ended, phases do nothing (the rest describes the last real iteration)
+};
+
+struct TraceRec {       // mirrors blink_trace_record
+  u32 iteration, kind;
+  u64 tail;
+  u32 n_admitted, n_seqs, n_tokens, free_blocks;
+  u64 first_admitted;
+  u64 t_sched_begin, t_sched_end, t_forward_end, t_publish_end;
+};
+
+// host-visible mirror in pinned host memory, written by the scheduler with system-scope stores
+struct HostMirror {
+  u64 iteration;
+  u64 tokens_out;
+  u32 stopped;
+  u32 error;
+  u32 n_running;
+  u32 idle;
+};
+
+// host -> device control words (pinned host memory, read by the scheduler with system-scope loads)
+struct HostCtrl {
+  u32 stop;             // blink_shutdown
+  u32 pad;
+};
+
+struct LayerW {
+  const float* g1;
+  const void* wqkv;     // [ (nq+2nkv)*hd ][d]
+  const void* wo;       // [d][nq*hd]
+  const float* g2;
+  const void* wgu;      // [2F][d]: gate rows then up rows
+  const void* wd;       // [d][F]
+};
+
+struct DevCtx {
+  // model
+  u32 n_layers, d, nq, nkv, hd, F, V, dtype;
+  float eps, theta;
+  // engine
+  u32 bs, n_blocks, max_batch, max_seq_len, max_prefill_tokens, ring_slots, max_blocks_per_seq, maxT;
+  i32 eos;
+  u32 flags, trace_cap, qkv_n;
+  // ring
+  SlotStatus* status;
+  SlotDesc* desc;
+  i32* in_arena;        // [ring_slots][max_seq_len]
+  OutRec* out_arena;    // [ring_slots][max_seq_len]
+  HostCtrl* hctrl;
+  HostMirror* hmirror;
+  // scheduler
+  SchedState* ss;
+  RunEntry* run;
+  u32* block_tables;    // [max_batch][max_blocks_per_seq]
+  u32* free_stack;      // [n_blocks]
+  IterMeta* meta;
+  u32* seq_bslot;       // [max_batch]
+  u32* seq_len;         // [max_batch]
+  u32* cu_seqlens;      // [max_batch+1]
+  u32* last_idx;        // [max_batch]
+  i32* input_ids;       // [maxT]
+  i32* positions;       // [maxT]
+  i32* slot_mapping;    // [maxT]
+  u32* tok_seq;         // [maxT]
+  TraceRec* trace;
+  // weights
+  const void* embed;
+  const LayerW* layers;
+  const float* gf;
+  const void* lm;
+  const float2* rope_tab;  // [max_seq_len][hd/2] (cos, sin)
+  // KV pool: [layer][2][n_blocks][nkv][bs][hd]
+  void* kv;
+  u64 kv_layer_stride;  // elements
+  u64 kv_kv_stride;     // elements between the K and the V half of a layer
+  // activations
+  float* x;             // [maxT][d] residual stream
+  float* h;             // [maxT][d] normalised input of a GEMM
+  float* qkv;           // [maxT][qkv_n]
+  float* attn;          // [maxT][nq*hd]
+  float* gu;            // [maxT][2F]
+  float* hlast;         // [max_batch][d]
+  float* logits;        // [max_batch][V]
+};
+
+__device__ __forceinline__ u64 dev_now_ns() { return wall_clock64() * 10ull; }  // 100 MHz constant clock
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((u32)b) << 16); }
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {  // round to nearest even; inputs are finite
+  u32 u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}

@@ -1,0 +1,61 @@
+// The ordered list of phases of one loop iteration and their dispatch. A phase is a grid-wide step that
+// must be complete before the next begins (a kernel boundary in host-enqueued mode, a grid barrier in
+// the resident loop). Shapes are read from the device metadata written by the scheduler step.
+#pragma once
+#include "blink_device.h"
+#include "sched.h"
+#include "forward.h"
+#include "sampler.h"
+
+enum {
+  PH_EMBED = 0,
+  PH_NORM1, PH_QKV, PH_ROPE, PH_ATTN, PH_OPROJ, PH_NORM2, PH_GATEUP, PH_DOWN,   // per layer
+  PH_FINAL_NORM, PH_LM_HEAD, PH_SAMPLE
+};
+#define PH_LAYER_FIRST PH_NORM1
+#define PH_LAYER_LAST PH_DOWN
+
+union PhaseShared {
+  SchedShared sched;
+  GemmShared gemm;
+  AttnShared attn;
+  SamplerShared sampler;
+  float red[8];
+};
+
+template <typename WT>
+__device__ __forceinline__ void run_phase_t(const DevCtx& c, int ph, u32 layer, PhaseShared& sh, u32 wg, u32 nwg) {
+  const IterMeta* m = c.meta;
+  const u32 T = m->n_tokens, B = m->n_seqs;
+  const LayerW* L = c.layers + layer;
+  switch (ph) {
+    case PH_EMBED: phase_embed<WT>(c, wg, nwg); break;
+    case PH_NORM1: phase_rmsnorm(c, c.x, L->g1, c.h, nullptr, sh.red, wg, nwg); break;
+    case PH_QKV:
+      phase_gemm<WT, GA_PLAIN, GE_STORE>(c.h, c.d, (const WT*)L->wqkv, c.qkv, c.qkv_n, T, c.qkv_n, c.d, sh.gemm, wg, nwg);
+      break;
+    case PH_ROPE: phase_rope_kvwrite<WT>(c, layer, wg, nwg); break;
+    case PH_ATTN: phase_attention<WT>(c, layer, sh.attn, wg, nwg); break;
+    case PH_OPROJ:
+      phase_gemm<WT, GA_PLAIN, GE_ADD>(c.attn, c.nq * c.hd, (const WT*)L->wo, c.x, c.d, T, c.d, c.nq * c.hd, sh.gemm, wg, nwg);
+      break;
+    case PH_NORM2: phase_rmsnorm(c, c.x, L->g2, c.h, nullptr, sh.red, wg, nwg); break;
+    case PH_GATEUP:
+      phase_gemm<WT, GA_PLAIN, GE_STORE>(c.h, c.d, (const WT*)L->wgu, c.gu, 2 * c.F, T, 2 * c.F, c.d, sh.gemm, wg, nwg);
+      break;
+    case PH_DOWN:
+      phase_gemm<WT, GA_SILU_MUL, GE_ADD>(c.gu, 2 * c.F, (const WT*)L->wd, c.x, c.d, T, c.d, c.F, sh.gemm, wg, nwg);
+      break;
+    case PH_FINAL_NORM: phase_rmsnorm(c, c.x, c.gf, c.hlast, c.last_idx, sh.red, wg, nwg); break;
+    case PH_LM_HEAD:
+      phase_gemm<WT, GA_PLAIN, GE_STORE>(c.hlast, c.d, (const WT*)c.lm, c.logits, c.V, B, c.V, c.d, sh.gemm, wg, nwg);
+      break;
+    case PH_SAMPLE: phase_sample_publish(c, sh.sampler, wg, nwg); break;
+  }
+}
+
+__device__ __forceinline__ void run_phase(const DevCtx& c, int ph, u32 layer, PhaseShared& sh, u32 wg, u32 nwg) {
+  if (c.meta->skip || c.meta->kind == KIND_IDLE) return;
+  if (c.dtype == 1) run_phase_t<bf16_t>(c, ph, layer, sh, wg, nwg);
+  else run_phase_t<float>(c, ph, layer, sh, wg, nwg);
+}

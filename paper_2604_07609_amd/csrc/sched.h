@@ -1,0 +1,371 @@
+// The scheduler step of the serving loop: one workgroup of 256 threads (section 4.2 of the paper:
+// "Persistent scheduler", "Parallel slot scanning", "Continuous batching with inline prefill").
+// Per iteration: retire finished requests, poll the ring for the contiguous run of pending tickets,
+// admit FCFS under the batch-slot / block-reservation / prefill-token limits, allocate KV blocks from
+// the free stack by prefix-sum offsets (deterministic block ids), and build the batch metadata.
+// Integer work only; all decisions are functions of device state, never of the host.
+#pragma once
+#include "blink_device.h"
+
+#define SLOT_EMPTY 0u
+#define SLOT_PREFILL_PENDING 1u
+#define SLOT_PREFILL_PROCESSING 2u
+#define SLOT_DECODE_PROCESSING 3u
+#define SLOT_DECODE_COMPLETED 4u
+#define SLOT_DECODE_PAUSED 5u
+
+#define KIND_IDLE 0u
+#define KIND_PREFILL 1u
+#define KIND_DECODE 2u
+
+#define SCHED_MAX_BATCH 1024
+
+struct SchedShared {
+  u32 wave_part[8];
+  u32 wave_part2[8];
+  u32 free_list[SCHED_MAX_BATCH];
+  u32 flag;
+};
+
+// Exclusive prefix sum over the 256 threads of the workgroup; total returned in `total`.
+__device__ __forceinline__ u32 block_excl_scan(u32 v, u32& total, u32* part) {
+  const u32 lane = threadIdx.x & 63u, w = threadIdx.x >> 6;
+  u32 inc = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    u32 t = __shfl_up(inc, o);
+    if (lane >= (u32)o) inc += t;
+  }
+  __syncthreads();
+  if (lane == 63u) part[w] = inc;
+  __syncthreads();
+  u32 base = 0, tot = 0;
+#pragma unroll
+  for (u32 i = 0; i < BLK_THREADS / WAVE; ++i) {
+    u32 s = part[i];
+    if (i < w) base += s;
+    tot += s;
+  }
+  total = tot;
+  return base + inc - v;
+}
+
+__device__ __forceinline__ u32 block_max(u32 v, u32* part) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = max(v, (u32)__shfl_xor((int)v, o));
+  __syncthreads();
+  if ((threadIdx.x & 63u) == 0) part[threadIdx.x >> 6] = v;
+  __syncthreads();
+  u32 m = 0;
+#pragma unroll
+  for (u32 i = 0; i < BLK_THREADS / WAVE; ++i) m = max(m, part[i]);
+  return m;
+}
+
+// Number of leading threads (thread 0 upwards) whose predicate holds.
+__device__ __forceinline__ u32 block_prefix_count(bool pred, u32* part) {
+  const u32 w = threadIdx.x >> 6;
+  unsigned long long b = __ballot(pred);
+  u32 cnt = (~b == 0ull) ? 64u : (u32)(__ffsll((long long)~b) - 1);
+  __syncthreads();
+  if ((threadIdx.x & 63u) == 0) part[w] = cnt;
+  __syncthreads();
+  u32 tot = 0;
+#pragma unroll
+  for (u32 i = 0; i < BLK_THREADS / WAVE; ++i) {
+    u32 s = part[i];
+    tot += s;
+    if (s < 64u) break;
+  }
+  return tot;
+}
+
+__device__ __forceinline__ void set_slot_state(SlotStatus* st, u32 state) {
+  __hip_atomic_store(&st->state, state, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+// One scheduler step. Must be called by all 256 threads of exactly one workgroup.
+// iter_limit: stop the window once this many iterations have run in total (0: no limit).
+__device__ void sched_step(const DevCtx& c, u64 iter_limit, SchedShared& sh) {
+  const u32 tid = threadIdx.x;
+  SchedState* ss = c.ss;
+  const u64 t_begin = dev_now_ns();
+
+  // ---- window gate -----------------------------------------------------------------------------------
+  if (tid == 0) {
+    u32 stop = ss->stopped | ss->error;
+    if (iter_limit != 0 && ss->iteration >= iter_limit) stop = 1;
+    if (__hip_atomic_load(&c.hctrl->stop, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_SYSTEM)) stop = 1;
+    sh.flag = stop;
+  }
+  __syncthreads();
+  if (sh.flag) {
+    if (tid == 0) {
+      ss->stopped = 1;
+      c.meta->skip = 1;
+      c.hmirror->iteration = ss->iteration;
+      c.hmirror->tokens_out = ss->tokens_out;
+      c.hmirror->n_running = ss->n_running;
+      c.hmirror->error = ss->error;
+      __hip_atomic_store(&c.hmirror->stopped, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+    return;
+  }
+
+  u32 top = ss->free_top, committed = ss->committed, nrun = ss->n_running;
+  const u64 next0 = ss->next_ticket;
+  const u32 mbs = c.max_blocks_per_seq;
+  __syncthreads();
+
+  // ---- (1) retire, batch slot ascending; blocks go back in block-table order ------------------------------
+  for (u32 base = 0; base < c.max_batch; base += BLK_THREADS) {
+    const u32 b = base + tid;
+    const bool fin = b < c.max_batch && c.run[b].valid && c.run[b].finished;
+    const u32 nb = fin ? c.run[b].n_blocks : 0u;
+    u32 tot, tot_resv, tot_fin;
+    const u32 off = block_excl_scan(nb, tot, sh.wave_part);
+    block_excl_scan(fin ? c.run[b].reserved : 0u, tot_resv, sh.wave_part2);
+    block_excl_scan(fin ? 1u : 0u, tot_fin, sh.wave_part);
+    for (u32 j = 0; j < nb; ++j) c.free_stack[top + off + j] = c.block_tables[(u64)b * mbs + j];
+    if (fin) c.run[b].valid = 0;
+    top += tot;
+    committed -= tot_resv;
+    nrun -= tot_fin;
+  }
+  __syncthreads();
+
+  // ---- free batch slots, ascending -----------------------------------------------------------------------
+  u32 n_free = 0;
+  for (u32 base = 0; base < c.max_batch; base += BLK_THREADS) {
+    const u32 b = base + tid;
+    const bool fr = b < c.max_batch && !c.run[b].valid;
+    u32 tot;
+    const u32 off = block_excl_scan(fr ? 1u : 0u, tot, sh.wave_part);
+    if (fr) sh.free_list[n_free + off] = b;
+    n_free += tot;
+  }
+  __syncthreads();
+
+  // ---- (2) poll the ring + (3) admit FCFS, 256 candidate tickets at a time ----------------------------------
+  u32 admitted = 0, tokens_admitted = 0;
+  u64 tail = next0;
+  u64 first_admitted = 0;
+  for (;;) {
+    const u64 t = next0 + admitted + tid;
+    const u32 slot = (u32)(t & (u64)(c.ring_slots - 1));
+    bool pend = false;
+    u32 P = 0, max_new = 0;
+    if (tid < c.ring_slots) {
+      const u32 st = __hip_atomic_load(&c.status[slot].state, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_SYSTEM);
+      if (st == SLOT_PREFILL_PENDING) {
+        const u64 tk = __hip_atomic_load(&c.desc[slot].ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        pend = tk == t;
+      }
+    }
+    const u32 vis = block_prefix_count(pend, sh.wave_part);
+    tail = next0 + admitted + vis;
+    const bool cand = tid < vis;
+    if (cand) {
+      P = __hip_atomic_load(&c.desc[slot].n_prompt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      max_new = __hip_atomic_load(&c.desc[slot].max_new, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+    u32 need = 0;
+    if (cand) {
+      need = (P + max_new - 1 + c.bs - 1) / c.bs;
+      if (need == 0) need = 1;
+    }
+    u32 totn, totp;
+    const u32 sn = block_excl_scan(need, totn, sh.wave_part) + need;     // inclusive
+    const u32 sp = block_excl_scan(cand ? P : 0u, totp, sh.wave_part2) + (cand ? P : 0u);
+    const u32 ord = admitted + tid;                                        // admission order within the iteration
+    const bool ok = cand && ord < n_free && (u64)committed + sn <= (u64)c.n_blocks &&
+                    (ord == 0 || (u64)tokens_admitted + sp <= (u64)c.max_prefill_tokens);
+    const u32 adm = block_prefix_count(ok, sh.wave_part);
+    if (tid < adm) {
+      const u32 b = sh.free_list[ord];
+      RunEntry& r = c.run[b];
+      r.valid = 1;
+      r.ring_slot = slot;
+      r.ticket = t;
+      r.P = P;
+      r.max_new = max_new;
+      r.gen = 0;
+      r.ctx_len = 0;
+      r.reserved = need;
+      r.n_blocks = 0;
+      r.finished = 0;
+      r.last_token = -1;
+      r.temperature = c.desc[slot].temperature;
+      r.top_k = c.desc[slot].top_k;
+      r.top_p = c.desc[slot].top_p;
+      r.seed = c.desc[slot].seed;
+      r.in_iter = 1;
+      r.paused = 0;
+      // claim by compare-and-swap (section 4.2 "Ring buffer")
+      u32 expect = SLOT_PREFILL_PENDING;
+      if (!__hip_atomic_compare_exchange_strong(&c.status[slot].state, &expect, SLOT_PREFILL_PROCESSING, __ATOMIC_ACQ_REL,
+                                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM))
+        ss->error = 2;
+    }
+    // totals of the admitted prefix: broadcast sn/sp of thread adm-1
+    __syncthreads();
+    if (adm > 0 && tid == adm - 1) {
+      sh.wave_part2[0] = sn;
+      sh.wave_part2[1] = sp;
+    }
+    __syncthreads();
+    if (adm > 0) {
+      committed += sh.wave_part2[0];
+      tokens_admitted += sh.wave_part2[1];
+      if (admitted == 0) first_admitted = next0;
+    }
+    admitted += adm;
+    __syncthreads();
+    if (adm < BLK_THREADS) break;   // stopped inside this chunk (nothing pending, or a limit was hit)
+  }
+  nrun += admitted;
+
+  // ---- (4) kind --------------------------------------------------------------------------------------------
+  const u32 kind = admitted > 0 ? KIND_PREFILL : (nrun > 0 ? KIND_DECODE : KIND_IDLE);
+  __syncthreads();
+
+  // ---- (5) allocate + (6) metadata, batch slot ascending ----------------------------------------------------
+  u32 n_seqs = 0, n_tok = 0, n_alloc = 0, max_q = 0, max_ctx = 0;
+  if (kind != KIND_IDLE) {
+    for (u32 base = 0; base < c.max_batch; base += BLK_THREADS) {
+      const u32 b = base + tid;
+      bool in = false;
+      u32 nalloc = 0, ntok = 0, ctx = 0, nb = 0;
+      if (b < c.max_batch && c.run[b].valid) {
+        RunEntry& r = c.run[b];
+        if (kind == KIND_PREFILL) {
+          in = r.in_iter != 0;
+          if (in) {
+            nalloc = (r.P + c.bs - 1) / c.bs;
+            ntok = r.P;
+          } else if (!r.paused) {
+            set_slot_state(&c.status[r.ring_slot], SLOT_DECODE_PAUSED);   // running decodes wait for the prefill
+            r.paused = 1;
+          }
+        } else {
+          in = true;
+          nalloc = (r.ctx_len == r.n_blocks * c.bs) ? 1u : 0u;
+          ntok = 1;
+        }
+        ctx = r.ctx_len;
+        nb = r.n_blocks;
+      }
+      u32 tots, tota, tott;
+      const u32 si = n_seqs + block_excl_scan(in ? 1u : 0u, tots, sh.wave_part);
+      const u32 aoff = n_alloc + block_excl_scan(nalloc, tota, sh.wave_part2);
+      const u32 toff = n_tok + block_excl_scan(ntok, tott, sh.wave_part);
+      if (in) {
+        RunEntry& r = c.run[b];
+        u32* bt = c.block_tables + (u64)b * mbs;
+        for (u32 j = 0; j < nalloc; ++j) bt[nb + j] = c.free_stack[top - 1 - (aoff + j)];
+        r.n_blocks = nb + nalloc;
+        c.seq_bslot[si] = b;
+        c.cu_seqlens[si] = toff;
+        c.last_idx[si] = toff + ntok - 1;
+        if (kind == KIND_DECODE) {
+          c.input_ids[toff] = r.last_token;
+          c.positions[toff] = (i32)ctx;
+          c.slot_mapping[toff] = (i32)(bt[ctx / c.bs] * c.bs + ctx % c.bs);
+          c.tok_seq[toff] = si;
+          r.ctx_len = ctx + 1;
+          c.seq_len[si] = ctx + 1;
+          if (r.paused) {
+            set_slot_state(&c.status[r.ring_slot], SLOT_DECODE_PROCESSING);
+            r.paused = 0;
+          }
+        } else {
+          r.ctx_len = r.P;
+          c.seq_len[si] = r.P;
+          r.in_iter = 0;
+        }
+      }
+      max_q = max(max_q, block_max(ntok, sh.wave_part2));
+      max_ctx = max(max_ctx, block_max(in ? (kind == KIND_DECODE ? ctx + 1 : ntok) : 0u, sh.wave_part));
+      n_seqs += tots;
+      n_alloc += tota;
+      n_tok += tott;
+    }
+    top -= n_alloc;
+    __syncthreads();
+    if (tid == 0) c.cu_seqlens[n_seqs] = n_tok;
+    if (kind == KIND_PREFILL) {
+      // token-level metadata of the prompts: one sequence after the other, threads over its tokens
+      for (u32 s = 0; s < n_seqs; ++s) {
+        const u32 b = c.seq_bslot[s];
+        const RunEntry& r = c.run[b];
+        const u32 toff = c.cu_seqlens[s];
+        const u32* bt = c.block_tables + (u64)b * mbs;
+        const i32* prompt = c.in_arena + (u64)r.ring_slot * c.max_seq_len;
+        for (u32 p = tid; p < r.P; p += BLK_THREADS) {
+          c.input_ids[toff + p] = __hip_atomic_load(&prompt[p], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+          c.positions[toff + p] = (i32)p;
+          c.slot_mapping[toff + p] = (i32)(bt[p / c.bs] * c.bs + p % c.bs);
+          c.tok_seq[toff + p] = s;
+        }
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- write back ------------------------------------------------------------------------------------------
+  if (tid == 0) {
+    const u64 now = dev_now_ns();
+    ss->free_top = top;
+    ss->committed = committed;
+    ss->n_running = nrun;
+    ss->next_ticket = next0 + admitted;
+    IterMeta* m = c.meta;
+    m->kind = kind;
+    m->skip = 0;
+    m->n_seqs = n_seqs;
+    m->n_tokens = n_tok;
+    m->max_q_len = max_q;
+    m->max_ctx = max_ctx;
+    u32 stopped = 0;
+    if (kind != KIND_IDLE) {
+      const u64 it = ss->iteration;
+      m->iteration = (u32)it;
+      ss->iteration = it + 1;
+      ss->tokens_out += n_seqs;
+      ss->idle_since_ns = 0;
+      if (kind == KIND_PREFILL) {
+        ss->prefill_iterations += 1;
+        ss->tokens_prefilled += n_tok;
+      }
+      const u32 ti = (u32)(it % c.trace_cap);
+      m->trace_idx = ti;
+      if (c.flags & 1u) {
+        TraceRec& tr = c.trace[ti];
+        tr.iteration = (u32)it;
+        tr.kind = kind;
+        tr.tail = tail;
+        tr.n_admitted = admitted;
+        tr.n_seqs = n_seqs;
+        tr.n_tokens = n_tok;
+        tr.free_blocks = top;
+        tr.first_admitted = first_admitted;
+        tr.t_sched_begin = t_begin;
+        tr.t_sched_end = now;
+        tr.t_forward_end = 0;
+        tr.t_publish_end = 0;
+      }
+    } else {
+      if (ss->idle_since_ns == 0) ss->idle_since_ns = now;
+      if (c.flags & 2u) {            // exit when idle: nothing running, nothing pending
+        ss->stopped = 1;
+        stopped = 1;
+      }
+    }
+    c.hmirror->iteration = ss->iteration;
+    c.hmirror->tokens_out = ss->tokens_out;
+    c.hmirror->n_running = nrun;
+    c.hmirror->error = ss->error;
+    c.hmirror->idle = kind == KIND_IDLE;
+    __hip_atomic_store(&c.hmirror->stopped, stopped, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+  }
+}
