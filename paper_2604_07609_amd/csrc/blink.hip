@@ -18,9 +18,9 @@
 // ================================================================================================
 // kernels
 // ================================================================================================
-__global__ void __launch_bounds__(BLK_THREADS) k_sched(DevCtx c, u64 iter_limit) {
+__global__ void __launch_bounds__(BLK_THREADS) k_sched(DevCtx c) {
   __shared__ SchedShared sh;
-  sched_step(c, iter_limit, sh);
+  sched_step(c, sh);
 }
 
 __global__ void __launch_bounds__(BLK_THREADS) k_phase(DevCtx c, int ph, u32 layer) {
@@ -37,7 +37,10 @@ __global__ void k_rope_table(float2* tab, u32 max_pos, u32 half, double theta) {
   tab[i] = make_float2((float)cos(ang), (float)sin(ang));
 }
 
-__global__ void k_clear_stopped(SchedState* ss) { ss->stopped = 0; }
+__global__ void k_open_window(SchedState* ss, u64 iter_limit) {
+  ss->stopped = 0;
+  ss->iter_limit = iter_limit;
+}
 
 // ================================================================================================
 // host
@@ -81,6 +84,8 @@ struct blink_engine {
   SlotStatus* stage_empty = nullptr;   // pinned zero status
   // loop
   std::thread launcher;
+  hipGraphExec_t iter_graph = nullptr;
+  std::vector<hipEvent_t> events;
   std::atomic<bool> loop_active{false};
   std::atomic<int> loop_rc{0};
   std::atomic<u32> windows{0};
@@ -119,6 +124,8 @@ static u64 expected_weight_bytes(const blink_config* c) {
 }
 
 static void free_all(blink_engine* e) {
+  if (e->iter_graph) (void)hipGraphExecDestroy(e->iter_graph);
+  for (hipEvent_t ev : e->events) (void)hipEventDestroy(ev);
   for (void* p : e->dev_allocs) (void)hipFree(p);
   for (void* p : e->host_allocs) (void)hipHostFree(p);
   if (e->compute) (void)hipStreamDestroy(e->compute);
@@ -126,6 +133,8 @@ static void free_all(blink_engine* e) {
   if (e->s_out) (void)hipStreamDestroy(e->s_out);
   delete e;
 }
+
+static int build_graph(blink_engine* e);
 
 static int init_impl(const blink_config* cfg, blink_engine* e) {
   HIPCHK(hipSetDevice(cfg->device));
@@ -244,6 +253,15 @@ static int init_impl(const blink_config* cfg, blink_engine* e) {
   if (int rc = dalloc(e, &c.logits, (u64)c.max_batch * c.V)) return rc;
   HIPCHK(hipStreamSynchronize(e->compute));
   HIPCHK(hipDeviceSynchronize());
+  {
+    const char* dv = getenv("BLINK_PUMP_DEPTH");
+    u32 depth = dv ? (u32)atoi(dv) : 8u;
+    if (depth < 1) depth = 1;
+    if (depth > 1024) depth = 1024;
+    e->events.resize(depth);
+    for (u32 i = 0; i < depth; ++i) HIPCHK(hipEventCreateWithFlags(&e->events[i], hipEventDisableTiming));
+  }
+  if (int rc = build_graph(e)) return rc;
   return 0;
 }
 
@@ -327,32 +345,62 @@ extern "C" int blink_submit(blink_engine* e, const int32_t* prompt, uint32_t n_p
   return BLINK_OK;
 }
 
-// ---- loop launcher: host-enqueued mode ---------------------------------------------------------------------
-static int enqueue_iteration(blink_engine* e, u64 iter_limit) {
+// ---- loop launcher -----------------------------------------------------------------------------------------
+// The host thread is a pump: it enqueues the fixed kernel chain of one iteration, several iterations ahead,
+// and never reads a result the device waits for. Every decision (what runs, on which shapes, when the window
+// ends) is taken on the device; an iteration enqueued after the window has ended costs a few empty kernels.
+static int enqueue_iteration_kernels(blink_engine* e, hipStream_t st) {
   const DevCtx& c = e->ctx;
-  hipLaunchKernelGGL(k_sched, dim3(1), dim3(BLK_THREADS), 0, e->compute, c, iter_limit);
+  hipLaunchKernelGGL(k_sched, dim3(1), dim3(BLK_THREADS), 0, st, c);
   const dim3 g(e->grid), b(BLK_THREADS);
-  hipLaunchKernelGGL(k_phase, g, b, 0, e->compute, c, (int)PH_EMBED, 0u);
+  hipLaunchKernelGGL(k_phase, g, b, 0, st, c, (int)PH_EMBED, 0u);
   for (u32 l = 0; l < c.n_layers; ++l)
-    for (int ph = PH_LAYER_FIRST; ph <= PH_LAYER_LAST; ++ph) hipLaunchKernelGGL(k_phase, g, b, 0, e->compute, c, ph, l);
-  hipLaunchKernelGGL(k_phase, g, b, 0, e->compute, c, (int)PH_FINAL_NORM, 0u);
-  hipLaunchKernelGGL(k_phase, g, b, 0, e->compute, c, (int)PH_LM_HEAD, 0u);
-  hipLaunchKernelGGL(k_phase, g, b, 0, e->compute, c, (int)PH_SAMPLE, 0u);
+    for (int ph = PH_LAYER_FIRST; ph <= PH_LAYER_LAST; ++ph) hipLaunchKernelGGL(k_phase, g, b, 0, st, c, ph, l);
+  hipLaunchKernelGGL(k_phase, g, b, 0, st, c, (int)PH_FINAL_NORM, 0u);
+  hipLaunchKernelGGL(k_phase, g, b, 0, st, c, (int)PH_LM_HEAD, 0u);
+  hipLaunchKernelGGL(k_phase, g, b, 0, st, c, (int)PH_SAMPLE, 0u);
   HIPCHK(hipGetLastError());
   return 0;
 }
 
-static void stepped_loop(blink_engine* e, u64 iter_limit) {
+static int build_graph(blink_engine* e) {
+  if (getenv("BLINK_NO_GRAPH")) return 0;
+  hipGraph_t g = nullptr;
+  HIPCHK(hipStreamBeginCapture(e->compute, hipStreamCaptureModeThreadLocal));
+  const int rc = enqueue_iteration_kernels(e, e->compute);
+  hipError_t er = hipStreamEndCapture(e->compute, &g);
+  if (rc) return rc;
+  HIPCHK(er);
+  HIPCHK(hipGraphInstantiate(&e->iter_graph, g, nullptr, nullptr, 0));
+  HIPCHK(hipGraphDestroy(g));
+  return 0;
+}
+
+static int enqueue_iteration(blink_engine* e) {
+  if (e->iter_graph) {
+    HIPCHK(hipGraphLaunch(e->iter_graph, e->compute));
+    return 0;
+  }
+  return enqueue_iteration_kernels(e, e->compute);
+}
+
+static void pump_loop(blink_engine* e) {
   int rc = 0;
   if (hipSetDevice(e->cfg.device) != hipSuccess) rc = BLINK_ERR_DEVICE;
+  const u32 depth = (u32)e->events.size();
+  u64 enq = 0;
   while (rc == 0) {
-    const u32 chunk = 4;
-    for (u32 i = 0; i < chunk && rc == 0; ++i) rc = enqueue_iteration(e, iter_limit);
-    if (rc) break;
-    if (hipStreamSynchronize(e->compute) != hipSuccess) { rc = BLINK_ERR_DEVICE; break; }
-    if (e->hmirror->error) { rc = BLINK_ERR_DEVICE; break; }
-    if (__atomic_load_n(&e->hmirror->stopped, __ATOMIC_ACQUIRE)) break;
+    if (enq >= depth) {   // wait for the iteration enqueued `depth` ago: bounds the work in flight
+      if (hipEventSynchronize(e->events[enq % depth]) != hipSuccess) { rc = BLINK_ERR_DEVICE; break; }
+      if (e->hmirror->error) { rc = BLINK_ERR_DEVICE; break; }
+      if (__atomic_load_n(&e->hmirror->stopped, __ATOMIC_ACQUIRE)) break;
+    }
+    rc = enqueue_iteration(e);
+    if (rc == 0 && hipEventRecord(e->events[enq % depth], e->compute) != hipSuccess) rc = BLINK_ERR_DEVICE;
+    ++enq;
   }
+  if (hipStreamSynchronize(e->compute) != hipSuccess && rc == 0) rc = BLINK_ERR_DEVICE;
+  if (rc == 0 && e->hmirror->error) rc = BLINK_ERR_DEVICE;
   e->loop_rc.store(rc);
   e->loop_active.store(false, std::memory_order_release);
 }
@@ -367,12 +415,12 @@ extern "C" int blink_run(blink_engine* e, uint64_t max_iterations) {
   if (e->hmirror->error) return fail(BLINK_ERR_DEVICE, "device loop error %u", e->hmirror->error);
   const u64 iter_limit = max_iterations ? e->hmirror->iteration + max_iterations : 0;
   e->hmirror->stopped = 0;
-  hipLaunchKernelGGL(k_clear_stopped, dim3(1), dim3(1), 0, e->compute, e->ctx.ss);
+  hipLaunchKernelGGL(k_open_window, dim3(1), dim3(1), 0, e->compute, e->ctx.ss, iter_limit);
   HIPCHK(hipGetLastError());
   e->loop_active.store(true, std::memory_order_release);
   e->loop_rc.store(0);
   e->windows.fetch_add(1);
-  e->launcher = std::thread(stepped_loop, e, iter_limit);
+  e->launcher = std::thread(pump_loop, e);
   return BLINK_OK;
 }
 

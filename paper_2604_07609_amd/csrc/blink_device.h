@@ -73,6 +73,7 @@ struct SchedState {
   u32 stopped;          // set by the scheduler when the window ends; cleared by the host at blink_run
   u32 error;
   u32 pad;
+  u64 iter_limit;       // the window ends once `iteration` reaches this (0: no limit); set at blink_run
 };
 
 // batch metadata of the current iteration (what the scheduler populates before the forward pass)

@@ -85,8 +85,7 @@ __device__ __forceinline__ void set_slot_state(SlotStatus* st, u32 state) {
 }
 
 // One scheduler step. Must be called by all 256 threads of exactly one workgroup.
-// iter_limit: stop the window once this many iterations have run in total (0: no limit).
-__device__ void sched_step(const DevCtx& c, u64 iter_limit, SchedShared& sh) {
+__device__ void sched_step(const DevCtx& c, SchedShared& sh) {
   const u32 tid = threadIdx.x;
   SchedState* ss = c.ss;
   const u64 t_begin = dev_now_ns();
@@ -94,6 +93,7 @@ __device__ void sched_step(const DevCtx& c, u64 iter_limit, SchedShared& sh) {
   // ---- window gate -----------------------------------------------------------------------------------
   if (tid == 0) {
     u32 stop = ss->stopped | ss->error;
+    const u64 iter_limit = ss->iter_limit;
     if (iter_limit != 0 && ss->iteration >= iter_limit) stop = 1;
     if (__hip_atomic_load(&c.hctrl->stop, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_SYSTEM)) stop = 1;
     sh.flag = stop;
