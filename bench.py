@@ -1,0 +1,202 @@
+#!/usr/bin/env python3
+"""Benchmark of the on-GPU serving step on one MI355X.
+
+A "step" is one iteration of the serving loop: scheduler step (retire, ring poll, FCFS admission, KV block
+allocation, batch metadata), forward pass over paged KV (prefill or decode), sampling, publication.
+The whole request set of the workload is resident in the HBM ring before the timed region starts
+(saturation load); W warm-up iterations run untimed, then exactly K iterations are timed.
+
+Prints ONE JSON line: output tokens/s over the timed iterations, p50/p99 inter-token latency from device
+timestamps, scheduling microseconds per iteration, the HBM roofline of the dominant kernel (timed with HIP
+events on the compute stream during the timed iterations) and the CPU oracle's rate on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import synth  # noqa: E402
+from synth.workloads import churn_pool_blocks  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0
+PHASE_NAMES = {2: "k_qkv", 5: "k_oproj", 7: "k_gateup", 8: "k_down", 10: "k_lm_head", 4: "k_attention"}
+
+WORKLOADS = {
+    "tiny": dict(model="tiny", workload="tiny", wseed=1000, rseed=2000, steps=30, warmup=3),
+    "churn": dict(model="churn", workload="churn", wseed=1001, rseed=2001, steps=600, warmup=20),
+    "llama3_8b": dict(model="llama3_8b", workload="llama3_8b", wseed=1002, rseed=2002, steps=200, warmup=10),
+    "sched_stress": dict(model="sched_stress", workload="sched_stress", wseed=1003, rseed=2003, steps=100, warmup=5),
+}
+
+
+def phase_bytes(cfg, phase, n_tokens, n_seqs):
+    """Algorithmic HBM bytes of one launch of a GEMM phase: the weight matrix once, activations in and out."""
+    es = 2 if cfg["dtype"] == 1 else 4
+    d, F, V = cfg["d_model"], cfg["d_ffn"], cfg["vocab"]
+    qkv_n = (cfg["n_q_heads"] + 2 * cfg["n_kv_heads"]) * cfg["head_dim"]
+    no = cfg["n_q_heads"] * cfg["head_dim"]
+    if phase == 2:
+        return es * qkv_n * d + 4 * n_tokens * (d + qkv_n)
+    if phase == 5:
+        return es * d * no + 4 * n_tokens * (no + 2 * d)
+    if phase == 7:
+        return es * 2 * F * d + 4 * n_tokens * (d + 2 * F)
+    if phase == 8:
+        return es * d * F + 4 * n_tokens * (2 * F + 2 * d)
+    if phase == 10:
+        return es * V * d + 4 * n_seqs * (d + V)
+    raise ValueError(phase)
+
+
+def decode_step_bytes(cfg, n_seqs, ctx_tokens):
+    """Algorithmic HBM bytes of one decode iteration: every weight matrix once, the KV of every context
+    token read once, one token of KV written per sequence, logits written and read by the sampler."""
+    es = 2 if cfg["dtype"] == 1 else 4
+    d, F, V, L = cfg["d_model"], cfg["d_ffn"], cfg["vocab"], cfg["n_layers"]
+    qkv_n = (cfg["n_q_heads"] + 2 * cfg["n_kv_heads"]) * cfg["head_dim"]
+    no = cfg["n_q_heads"] * cfg["head_dim"]
+    w = es * (L * (qkv_n * d + d * no + 2 * F * d + d * F) + V * d)
+    kv_tok = 2 * cfg["n_kv_heads"] * cfg["head_dim"] * es * L
+    return w + kv_tok * (ctx_tokens + n_seqs) + 2 * 4 * n_seqs * V
+
+
+def cpu_baseline(cfg, eng, raw, reqs, budget_tokens):
+    """The oracle, as it stands, on a bounded sample of the same workload."""
+    from oracle import model as M, serve as SV
+    sample = []
+    for r in reqs[:4]:
+        r = dict(r)
+        r["max_new_tokens"] = min(r["max_new_tokens"], budget_tokens)
+        sample.append(r)
+    t0 = time.perf_counter()
+    ev, _ = SV.serve(cfg, M.Weights(cfg, raw), eng, sample)
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count()
+    return dict(value=len(ev) / dt, unit="output tokens/s", cores=int(threads), kind="oracle",
+                sample="first %d requests, prompts as drawn (%s tokens), max_new_tokens capped at %d: %d output tokens in %.1f s"
+                       % (len(sample), "+".join(str(len(r["prompt"])) for r in sample), budget_tokens, len(ev), dt))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=0)
+    ap.add_argument("--warmup", type=int, default=-1)
+    ap.add_argument("--workload", default=os.environ.get("BLINK_BENCH_WORKLOAD", "churn"), choices=sorted(WORKLOADS))
+    ap.add_argument("--phase", type=int, default=7, help="forward phase whose kernel is timed for the roofline")
+    ap.add_argument("--requests", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU; one engine serves one GPU and nothing is sharded (--gpus 1 only)", file=sys.stderr)
+        sys.exit(2)
+    import paper_2604_07609_amd as B
+
+    wl = WORKLOADS[args.workload]
+    K = args.steps or wl["steps"]
+    W = args.warmup if args.warmup >= 0 else wl["warmup"]
+    cfg, eng = synth.model_config(wl["model"]), synth.engine_config(wl["model"])
+    t_gen = time.perf_counter()
+    raw = synth.make_weights(cfg, wl["wseed"], threads=min(16, os.cpu_count() or 8))
+    reqs = synth.make_workload(wl["workload"], cfg["vocab"], wl["rseed"], n_requests=args.requests or None)
+    if eng["kv_num_blocks"] == 0:
+        eng["kv_num_blocks"] = churn_pool_blocks(reqs, eng["kv_block_size"])
+    reqs = reqs[: eng["ring_slots"]]
+    blob = synth.pack_blob(cfg, raw)
+    t_gen = time.perf_counter() - t_gen
+
+    e = B.Engine(cfg, eng, blob, flags=B.FLAG_TRACE | B.FLAG_EXIT_WHEN_IDLE, trace_capacity=max(65536, K + W + 16))
+    del blob
+    try:
+        for r in reqs:
+            e.submit_request(r)
+        if W:
+            e.run(W)
+            e.wait()
+        e.drain(16384)
+        s0 = e.stats()
+        e.time_phase(args.phase)
+        t0 = time.perf_counter()
+        e.run(K)
+        e.wait()                       # joins the launcher, which synchronises the compute stream
+        t1 = time.perf_counter()
+        s1 = e.stats()
+        ev = e.drain(16384)
+        trace = e.trace(K + W + 16)
+        phase_ms = e.phase_times_ms()
+    finally:
+        e.shutdown()
+
+    iters = int(s1["iterations"] - s0["iterations"])
+    toks = int(s1["tokens_out"] - s0["tokens_out"])
+    dt = t1 - t0
+    tr = trace[(trace["iteration"] >= s0["iterations"]) & (trace["iteration"] < s1["iterations"])]
+    # inter-token latency from device timestamps of consecutive tokens of a request, both inside the timed region
+    itl = []
+    ev = ev[ev["iteration"] >= s0["iterations"]]
+    order = np.lexsort((ev["index"], ev["request_id"]))
+    evs = ev[order]
+    same = (evs["request_id"][1:] == evs["request_id"][:-1]) & (evs["index"][1:] == evs["index"][:-1] + 1)
+    itl = (evs["device_ns"][1:].astype(np.int64) - evs["device_ns"][:-1].astype(np.int64))[same] / 1e6
+    sched_us = (tr["t_sched_end_ns"].astype(np.int64) - tr["t_sched_begin_ns"].astype(np.int64)) / 1e3
+    dec = tr["kind"] == 2
+    # roofline of the timed kernel: same launches as the timed region (the first `iters` enqueued iterations)
+    per_layer = 1 if args.phase in (10,) else cfg["n_layers"]
+    pm = phase_ms[:iters]
+    n_launch = len(pm) * per_layer
+    bytes_total = float(sum(phase_bytes(cfg, args.phase, int(t["n_tokens"]), int(t["n_seqs"])) for t in tr[: len(pm)])) * per_layer
+    avg_us = 1e3 * float(pm.sum()) / max(1, n_launch)
+    achieved = bytes_total / max(1e-12, float(pm.sum()) * 1e-3) / 1e9
+    pm_dec = pm[dec[: len(pm)]] if len(pm) else pm
+    dec_bytes = float(sum(phase_bytes(cfg, args.phase, int(t["n_tokens"]), int(t["n_seqs"])) for t in tr[: len(pm)][dec[: len(pm)]])) * per_layer
+    roofline = dict(bound="hbm", kernel=PHASE_NAMES.get(args.phase, str(args.phase)), achieved=round(achieved, 2), peak=HBM_PEAK_GBS,
+                    unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None, launches=n_launch,
+                    avg_launch_us=round(avg_us, 3), algorithmic_bytes_per_launch=round(bytes_total / max(1, n_launch)),
+                    decode_only_GBs=round(dec_bytes / max(1e-12, float(pm_dec.sum()) * 1e-3) / 1e9, 2) if len(pm_dec) else None)
+    # whole-step view of the decode iterations: algorithmic bytes of the step over its duration on the device clock
+    step_ns = np.diff(tr["t_sched_begin_ns"].astype(np.int64))
+    ctx = np.zeros(len(tr))
+    dec_step = None
+    if dec.sum() > 2:
+        # context tokens per decode iteration are not traced; bound them from below by 0 (weights only)
+        idx = np.nonzero(dec[:-1])[0]
+        b = np.array([decode_step_bytes(cfg, int(tr["n_seqs"][i]), 0) for i in idx], dtype=np.float64)
+        dec_step = dict(median_us=round(float(np.median(step_ns[idx])) / 1e3, 2), weights_only_GBs=round(float(b.sum() / step_ns[idx].sum()), 2),
+                        mean_batch=round(float(tr["n_seqs"][idx].mean()), 2))
+    out = {
+        "metric": "output tokens/sec at 1 GPU; p50/p99 ITL; on-GPU scheduling us/iteration",
+        "value": round(toks / dt, 2), "unit": "output tokens/s", "n_gpus": 1, "steps": iters, "warmup": W,
+        "ms_per_step": round(1e3 * dt / max(1, iters), 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg["dtype"] == 1 else "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "requests_resident": len(reqs), "arrivals": "all resident at t=0 (saturation)",
+                   "max_batch": eng["max_batch"], "kv_blocks": eng["kv_num_blocks"], "loop": "device-decided, host-pumped kernel chain"},
+        "itl_ms": {"p50": round(float(np.percentile(itl, 50)), 4) if len(itl) else None,
+                   "p99": round(float(np.percentile(itl, 99)), 4) if len(itl) else None, "n": int(len(itl))},
+        "sched_us_per_iteration": {"median": round(float(np.median(sched_us)), 2) if len(sched_us) else None,
+                                   "p99": round(float(np.percentile(sched_us, 99)), 2) if len(sched_us) else None},
+        "iterations": {"prefill": int((tr["kind"] == 1).sum()), "decode": int(dec.sum()),
+                       "prefill_tokens": int(s1["tokens_prefilled"] - s0["tokens_prefilled"])},
+        "decode_step": dec_step,
+        "roofline": roofline,
+        "setup_s": {"weights_and_workload": round(t_gen, 1)},
+    }
+    if not args.no_cpu_baseline:
+        budget = args.cpu_sample_tokens or {"tiny": 32, "churn": 16, "llama3_8b": 2, "sched_stress": 16}[args.workload]
+        out["cpu_baseline"] = cpu_baseline(cfg, eng, raw, reqs, budget)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

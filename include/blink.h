@@ -170,9 +170,14 @@ int blink_shutdown(blink_engine* e);
 int blink_get_trace(blink_engine* e, blink_trace_record* buf, uint64_t cap_records, uint64_t* n_out);
 int blink_get_stats(blink_engine* e, blink_stats* out);
 int blink_debug_read(blink_engine* e, uint32_t what, void* buf, uint64_t cap_bytes, uint64_t* n_bytes);
-/* Times `reps` launches of one forward GEMM of the decode path over `batch` synthetic tokens with HIP events
- * on the engine's stream (gemm: 0 qkv, 1 o, 2 gate/up, 3 down, 4 lm head). Loop must be stopped. */
-int blink_bench_gemm(blink_engine* e, uint32_t gemm, uint32_t batch, uint32_t reps, float* avg_us_out);
+/* Kernel timing for the roofline report. blink_time_phase selects one phase of the forward pass (0 embedding;
+ * per layer: 1 norm, 2 QKV GEMM, 3 rotary + KV write, 4 attention, 5 output GEMM, 6 norm, 7 gate/up GEMM,
+ * 8 down GEMM; 9 final norm, 10 LM head, 11 sample + publish; -1 none). While a phase is selected, the loop
+ * brackets every launch of that phase's kernel with HIP events on the compute stream. After the loop has
+ * stopped, blink_get_phase_times returns, per iteration enqueued in the last window and in enqueue order, the
+ * summed duration in milliseconds of that kernel's launches (one per layer for per-layer phases). */
+int blink_time_phase(blink_engine* e, int32_t phase);
+int blink_get_phase_times(blink_engine* e, float* ms_per_iteration, uint64_t cap, uint64_t* n_out);
 /* Message of the last error on the calling thread ("" if none). The pointer stays valid until the next call. */
 const char* blink_last_error(void);
 

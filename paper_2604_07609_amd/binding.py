@@ -11,7 +11,8 @@ ERR_INVAL, ERR_TOO_LARGE, ERR_FULL, ERR_DEVICE, ERR_STATE = -1, -2, -3, -4, -5
 EVENT_FIRST, EVENT_LAST = 1, 2
 
 EXPORTS = ["blink_init", "blink_submit", "blink_run", "blink_wait", "blink_poll_outputs", "blink_shutdown",
-           "blink_get_trace", "blink_get_stats", "blink_debug_read", "blink_bench_gemm", "blink_last_error"]
+           "blink_get_trace", "blink_get_stats", "blink_debug_read", "blink_time_phase", "blink_get_phase_times",
+           "blink_last_error"]
 
 
 class DBG:
@@ -78,7 +79,8 @@ def load_library():
     lib.blink_get_trace.argtypes = [vp, vp, u64, C.POINTER(u64)]
     lib.blink_get_stats.argtypes = [vp, C.POINTER(Stats)]
     lib.blink_debug_read.argtypes = [vp, u32, vp, u64, C.POINTER(u64)]
-    lib.blink_bench_gemm.argtypes = [vp, u32, u32, u32, C.POINTER(C.c_float)]
+    lib.blink_time_phase.argtypes = [vp, C.c_int32]
+    lib.blink_get_phase_times.argtypes = [vp, vp, u64, C.POINTER(u64)]
     lib.blink_last_error.restype = C.c_char_p
     for n in EXPORTS[:-1]:
         getattr(lib, n).restype = C.c_int
@@ -163,10 +165,14 @@ class Engine:
         _check(self.lib, self.lib.blink_debug_read(self.h, int(what), buf.ctypes.data, buf.nbytes, C.byref(n)))
         return buf[: n.value].view(dtype).copy()
 
-    def bench_gemm(self, gemm, batch, reps=20):
-        out = C.c_float()
-        _check(self.lib, self.lib.blink_bench_gemm(self.h, int(gemm), int(batch), int(reps), C.byref(out)))
-        return out.value
+    def time_phase(self, phase):
+        _check(self.lib, self.lib.blink_time_phase(self.h, int(phase)))
+
+    def phase_times_ms(self, cap=1 << 20):
+        buf = np.zeros(cap, dtype=np.float32)
+        n = C.c_uint64()
+        _check(self.lib, self.lib.blink_get_phase_times(self.h, buf.ctypes.data, cap, C.byref(n)))
+        return buf[: n.value].copy()
 
     def shutdown(self):
         if self.h:

@@ -23,9 +23,41 @@ __global__ void __launch_bounds__(BLK_THREADS) k_sched(DevCtx c) {
   sched_step(c, sh);
 }
 
-__global__ void __launch_bounds__(BLK_THREADS) k_phase(DevCtx c, int ph, u32 layer) {
-  __shared__ PhaseShared sh;
-  run_phase(c, ph, layer, sh, blockIdx.x, gridDim.x);
+// one named kernel per phase so that profiles attribute time to the step of the forward pass
+#define PHASE_KERNEL(name, PH)                                                   \
+  __global__ void __launch_bounds__(BLK_THREADS) name(DevCtx c, u32 layer) {     \
+    __shared__ PhaseShared sh;                                                   \
+    run_phase(c, PH, layer, sh, blockIdx.x, gridDim.x);                          \
+  }
+PHASE_KERNEL(k_embed, PH_EMBED)
+PHASE_KERNEL(k_norm1, PH_NORM1)
+PHASE_KERNEL(k_qkv, PH_QKV)
+PHASE_KERNEL(k_rope_kvwrite, PH_ROPE)
+PHASE_KERNEL(k_attention, PH_ATTN)
+PHASE_KERNEL(k_oproj, PH_OPROJ)
+PHASE_KERNEL(k_norm2, PH_NORM2)
+PHASE_KERNEL(k_gateup, PH_GATEUP)
+PHASE_KERNEL(k_down, PH_DOWN)
+PHASE_KERNEL(k_final_norm, PH_FINAL_NORM)
+PHASE_KERNEL(k_lm_head, PH_LM_HEAD)
+PHASE_KERNEL(k_sample_publish, PH_SAMPLE)
+
+typedef void (*phase_kernel_t)(DevCtx, u32);
+static phase_kernel_t phase_kernel(int ph) {
+  switch (ph) {
+    case PH_EMBED: return k_embed;
+    case PH_NORM1: return k_norm1;
+    case PH_QKV: return k_qkv;
+    case PH_ROPE: return k_rope_kvwrite;
+    case PH_ATTN: return k_attention;
+    case PH_OPROJ: return k_oproj;
+    case PH_NORM2: return k_norm2;
+    case PH_GATEUP: return k_gateup;
+    case PH_DOWN: return k_down;
+    case PH_FINAL_NORM: return k_final_norm;
+    case PH_LM_HEAD: return k_lm_head;
+    default: return k_sample_publish;
+  }
 }
 
 // (cos, sin) of pos * theta^(-2i/hd), evaluated in fp64 and rounded once
@@ -85,6 +117,9 @@ struct blink_engine {
   // loop
   std::thread launcher;
   hipGraphExec_t iter_graph = nullptr;
+  int timed_phase = -1;                 // phase whose launches are bracketed by HIP events (-1: none)
+  std::vector<hipEvent_t> phase_ev;     // [depth][n_layers][2]
+  std::vector<float> phase_ms;          // per enqueued iteration of the current window: summed duration
   std::vector<hipEvent_t> events;
   std::atomic<bool> loop_active{false};
   std::atomic<int> loop_rc{0};
@@ -126,6 +161,7 @@ static u64 expected_weight_bytes(const blink_config* c) {
 static void free_all(blink_engine* e) {
   if (e->iter_graph) (void)hipGraphExecDestroy(e->iter_graph);
   for (hipEvent_t ev : e->events) (void)hipEventDestroy(ev);
+  for (hipEvent_t ev : e->phase_ev) (void)hipEventDestroy(ev);
   for (void* p : e->dev_allocs) (void)hipFree(p);
   for (void* p : e->host_allocs) (void)hipHostFree(p);
   if (e->compute) (void)hipStreamDestroy(e->compute);
@@ -260,6 +296,8 @@ static int init_impl(const blink_config* cfg, blink_engine* e) {
     if (depth > 1024) depth = 1024;
     e->events.resize(depth);
     for (u32 i = 0; i < depth; ++i) HIPCHK(hipEventCreateWithFlags(&e->events[i], hipEventDisableTiming));
+    e->phase_ev.resize((u64)depth * c.n_layers * 2);
+    for (auto& ev : e->phase_ev) HIPCHK(hipEventCreate(&ev));
   }
   if (int rc = build_graph(e)) return rc;
   return 0;
@@ -349,16 +387,30 @@ extern "C" int blink_submit(blink_engine* e, const int32_t* prompt, uint32_t n_p
 // The host thread is a pump: it enqueues the fixed kernel chain of one iteration, several iterations ahead,
 // and never reads a result the device waits for. Every decision (what runs, on which shapes, when the window
 // ends) is taken on the device; an iteration enqueued after the window has ended costs a few empty kernels.
-static int enqueue_iteration_kernels(blink_engine* e, hipStream_t st) {
+static int launch_phase(blink_engine* e, hipStream_t st, int ph, u32 layer, u64 enq_index) {
+  const bool timed = e->timed_phase == ph && enq_index != ~0ull;
+  hipEvent_t a = nullptr, b = nullptr;
+  if (timed) {
+    const u64 slot = (enq_index % e->events.size()) * e->ctx.n_layers + (ph >= PH_LAYER_FIRST && ph <= PH_LAYER_LAST ? layer : 0);
+    a = e->phase_ev[2 * slot];
+    b = e->phase_ev[2 * slot + 1];
+    HIPCHK(hipEventRecord(a, st));
+  }
+  hipLaunchKernelGGL(phase_kernel(ph), dim3(e->grid), dim3(BLK_THREADS), 0, st, e->ctx, layer);
+  if (timed) HIPCHK(hipEventRecord(b, st));
+  return 0;
+}
+
+static int enqueue_iteration_kernels(blink_engine* e, hipStream_t st, u64 enq_index) {
   const DevCtx& c = e->ctx;
   hipLaunchKernelGGL(k_sched, dim3(1), dim3(BLK_THREADS), 0, st, c);
-  const dim3 g(e->grid), b(BLK_THREADS);
-  hipLaunchKernelGGL(k_phase, g, b, 0, st, c, (int)PH_EMBED, 0u);
+  if (int rc = launch_phase(e, st, PH_EMBED, 0, enq_index)) return rc;
   for (u32 l = 0; l < c.n_layers; ++l)
-    for (int ph = PH_LAYER_FIRST; ph <= PH_LAYER_LAST; ++ph) hipLaunchKernelGGL(k_phase, g, b, 0, st, c, ph, l);
-  hipLaunchKernelGGL(k_phase, g, b, 0, st, c, (int)PH_FINAL_NORM, 0u);
-  hipLaunchKernelGGL(k_phase, g, b, 0, st, c, (int)PH_LM_HEAD, 0u);
-  hipLaunchKernelGGL(k_phase, g, b, 0, st, c, (int)PH_SAMPLE, 0u);
+    for (int ph = PH_LAYER_FIRST; ph <= PH_LAYER_LAST; ++ph)
+      if (int rc = launch_phase(e, st, ph, l, enq_index)) return rc;
+  if (int rc = launch_phase(e, st, PH_FINAL_NORM, 0, enq_index)) return rc;
+  if (int rc = launch_phase(e, st, PH_LM_HEAD, 0, enq_index)) return rc;
+  if (int rc = launch_phase(e, st, PH_SAMPLE, 0, enq_index)) return rc;
   HIPCHK(hipGetLastError());
   return 0;
 }
@@ -367,7 +419,7 @@ static int build_graph(blink_engine* e) {
   if (getenv("BLINK_NO_GRAPH")) return 0;
   hipGraph_t g = nullptr;
   HIPCHK(hipStreamBeginCapture(e->compute, hipStreamCaptureModeThreadLocal));
-  const int rc = enqueue_iteration_kernels(e, e->compute);
+  const int rc = enqueue_iteration_kernels(e, e->compute, ~0ull);
   hipError_t er = hipStreamEndCapture(e->compute, &g);
   if (rc) return rc;
   HIPCHK(er);
@@ -376,12 +428,26 @@ static int build_graph(blink_engine* e) {
   return 0;
 }
 
-static int enqueue_iteration(blink_engine* e) {
-  if (e->iter_graph) {
+static int enqueue_iteration(blink_engine* e, u64 enq_index) {
+  if (e->iter_graph && e->timed_phase < 0) {
     HIPCHK(hipGraphLaunch(e->iter_graph, e->compute));
     return 0;
   }
-  return enqueue_iteration_kernels(e, e->compute);
+  return enqueue_iteration_kernels(e, e->compute, enq_index);
+}
+
+// durations of the timed phase for the iteration enqueued at enq_index (its events have completed)
+static void harvest_phase_times(blink_engine* e, u64 enq_index) {
+  if (e->timed_phase < 0) return;
+  const bool per_layer = e->timed_phase >= PH_LAYER_FIRST && e->timed_phase <= PH_LAYER_LAST;
+  const u32 n = per_layer ? e->ctx.n_layers : 1;
+  float sum = 0.f;
+  for (u32 l = 0; l < n; ++l) {
+    const u64 slot = (enq_index % e->events.size()) * e->ctx.n_layers + l;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, e->phase_ev[2 * slot], e->phase_ev[2 * slot + 1]) == hipSuccess) sum += ms;
+  }
+  e->phase_ms.push_back(sum);
 }
 
 static void pump_loop(blink_engine* e) {
@@ -392,14 +458,16 @@ static void pump_loop(blink_engine* e) {
   while (rc == 0) {
     if (enq >= depth) {   // wait for the iteration enqueued `depth` ago: bounds the work in flight
       if (hipEventSynchronize(e->events[enq % depth]) != hipSuccess) { rc = BLINK_ERR_DEVICE; break; }
+      harvest_phase_times(e, enq - depth);
       if (e->hmirror->error) { rc = BLINK_ERR_DEVICE; break; }
       if (__atomic_load_n(&e->hmirror->stopped, __ATOMIC_ACQUIRE)) break;
     }
-    rc = enqueue_iteration(e);
+    rc = enqueue_iteration(e, enq);
     if (rc == 0 && hipEventRecord(e->events[enq % depth], e->compute) != hipSuccess) rc = BLINK_ERR_DEVICE;
     ++enq;
   }
   if (hipStreamSynchronize(e->compute) != hipSuccess && rc == 0) rc = BLINK_ERR_DEVICE;
+  if (rc == 0) for (u64 i = enq > depth ? enq - depth : 0; i < enq; ++i) harvest_phase_times(e, i);
   if (rc == 0 && e->hmirror->error) rc = BLINK_ERR_DEVICE;
   e->loop_rc.store(rc);
   e->loop_active.store(false, std::memory_order_release);
@@ -420,6 +488,7 @@ extern "C" int blink_run(blink_engine* e, uint64_t max_iterations) {
   e->loop_active.store(true, std::memory_order_release);
   e->loop_rc.store(0);
   e->windows.fetch_add(1);
+  e->phase_ms.clear();
   e->launcher = std::thread(pump_loop, e);
   return BLINK_OK;
 }
@@ -598,35 +667,22 @@ extern "C" int blink_debug_read(blink_engine* e, uint32_t what, void* buf, uint6
   return BLINK_OK;
 }
 
-extern "C" int blink_bench_gemm(blink_engine* e, uint32_t gemm, uint32_t batch, uint32_t reps, float* avg_us_out) {
+extern "C" int blink_time_phase(blink_engine* e, int32_t phase) {
   g_err.clear();
-  if (!e || !avg_us_out || gemm > 4 || reps == 0) return fail(BLINK_ERR_INVAL, "bad argument");
+  if (!e) return fail(BLINK_ERR_INVAL, "null engine");
   if (e->loop_active.load()) return fail(BLINK_ERR_STATE, "stop the loop first");
-  if (batch == 0 || batch > e->ctx.max_batch) return fail(BLINK_ERR_INVAL, "batch must be in [1, max_batch]");
-  HIPCHK(hipSetDevice(e->cfg.device));
-  const DevCtx& c = e->ctx;
-  // a synthetic decode-shaped iteration: `batch` sequences of one token each
-  IterMeta m{};
-  m.kind = KIND_DECODE; m.n_seqs = batch; m.n_tokens = batch;
-  IterMeta saved;
-  HIPCHK(hipMemcpy(&saved, c.meta, sizeof saved, hipMemcpyDeviceToHost));
-  HIPCHK(hipMemcpy(c.meta, &m, sizeof m, hipMemcpyHostToDevice));
-  static const int phase_of[5] = {PH_QKV, PH_OPROJ, PH_GATEUP, PH_DOWN, PH_LM_HEAD};
-  hipEvent_t t0, t1;
-  HIPCHK(hipEventCreate(&t0));
-  HIPCHK(hipEventCreate(&t1));
-  const dim3 g(e->grid), b(BLK_THREADS);
-  for (u32 i = 0; i < 3; ++i) hipLaunchKernelGGL(k_phase, g, b, 0, e->compute, c, phase_of[gemm], 0u);
-  HIPCHK(hipEventRecord(t0, e->compute));
-  for (u32 i = 0; i < reps; ++i) hipLaunchKernelGGL(k_phase, g, b, 0, e->compute, c, phase_of[gemm], 0u);
-  HIPCHK(hipEventRecord(t1, e->compute));
-  HIPCHK(hipEventSynchronize(t1));
-  float ms = 0.f;
-  HIPCHK(hipEventElapsedTime(&ms, t0, t1));
-  (void)hipEventDestroy(t0);
-  (void)hipEventDestroy(t1);
-  HIPCHK(hipMemcpy(c.meta, &saved, sizeof saved, hipMemcpyHostToDevice));
-  *avg_us_out = ms * 1000.f / (float)reps;
+  if (phase < -1 || phase > PH_SAMPLE) return fail(BLINK_ERR_INVAL, "phase out of range");
+  e->timed_phase = phase;
+  return BLINK_OK;
+}
+
+extern "C" int blink_get_phase_times(blink_engine* e, float* ms_per_iteration, uint64_t cap, uint64_t* n_out) {
+  g_err.clear();
+  if (!e || !n_out || (!ms_per_iteration && cap)) return fail(BLINK_ERR_INVAL, "null argument");
+  if (e->loop_active.load()) return fail(BLINK_ERR_STATE, "stop the loop first");
+  const u64 n = std::min<u64>(cap, e->phase_ms.size());
+  for (u64 i = 0; i < n; ++i) ms_per_iteration[i] = e->phase_ms[i];
+  *n_out = n;
   return BLINK_OK;
 }
 
