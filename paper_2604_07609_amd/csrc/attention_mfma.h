@@ -1,0 +1,223 @@
+// Paged attention of the bf16 path on the matrix cores.
+//
+// Data layout (per layer):  K cache [block][kv head][16 tokens][hd]   (token-major: a tile is the A operand of QK^T)
+//                           V cache [block][kv head][hd][16 tokens]   (dimension-major: a tile is the B operand of PV)
+//                           q       [token][q head][hd] bf16, already rotated and scaled by 1/sqrt(hd)
+// One KV block (16 tokens of one kv head) is one contiguous 2-4 KB tile that a wave loads with 16-byte (K) and
+// 8-byte (V) lane loads. Scores are computed as S[token][column] = K_tile . q_column (v_mfma_f32_16x16x32_bf16),
+// where a column is a q head of the GQA group (decode) or a query position of one head (prefill). The
+// accumulator layout of S (column = lane%16, tokens = 4*(lane/16)+i) is exactly the A-operand layout of
+// v_mfma_f32_16x16x16_bf16, so the probabilities feed O[column][dim] += P . V without leaving registers.
+// Softmax is the online form (running maximum and sum per column), all in fp32.
+#pragma once
+#include "blink_device.h"
+#include "mfma_gemm.h"
+
+typedef short short4_t __attribute__((ext_vector_type(4)));
+
+template <int HD, int CT>
+struct AttnAcc {
+  floatx4_t o[CT][HD / 16];   // rows = columns of S (4*(lane/16)+i), column = dim d*16 + lane%16
+  float m[CT], l[CT];         // running max / sum of this lane's column (lane%16)
+};
+
+template <int HD, int CT>
+__device__ __forceinline__ void attn_init(AttnAcc<HD, CT>& a) {
+#pragma unroll
+  for (int c = 0; c < CT; ++c) {
+    a.m[c] = -INFINITY;
+    a.l[c] = 0.f;
+#pragma unroll
+    for (int d = 0; d < HD / 16; ++d) a.o[c][d] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+  }
+}
+
+// One KV block. Kt/Vt: the block's tiles for this kv head. j0: position of the block's first token.
+// lim[c]: number of visible keys (position + 1) for this lane's column of column-tile c.
+template <int HD, int CT>
+__device__ __forceinline__ void attn_block(const bf16_t* Kt, const bf16_t* Vt, const bf16x8_t (&q)[CT][HD / 32], u32 j0,
+                                           const u32 (&lim)[CT], AttnAcc<HD, CT>& a) {
+  const u32 lane = threadIdx.x & 63, lg = lane >> 4, lc = lane & 15;
+  bf16x8_t ka[HD / 32];
+  short4_t vb[HD / 16];
+#pragma unroll
+  for (int s = 0; s < HD / 32; ++s) ka[s] = ld_tile(Kt + lc * HD + s * 32 + lg * 8);
+#pragma unroll
+  for (int d = 0; d < HD / 16; ++d) {
+    const uint2 v = *(const uint2*)(Vt + (d * 16 + lc) * 16 + lg * 4);
+    vb[d] = *(const short4_t*)&v;
+  }
+#pragma unroll
+  for (int c = 0; c < CT; ++c) {
+    floatx4_t s4 = floatx4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < HD / 32; ++s) s4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[s], q[c][s], s4, 0, 0, 0);
+    float bm = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (j0 + lg * 4 + i >= lim[c]) s4[i] = -INFINITY;
+      bm = fmaxf(bm, s4[i]);
+    }
+    bm = fmaxf(bm, __shfl_xor(bm, 16));
+    bm = fmaxf(bm, __shfl_xor(bm, 32));
+    const float mn = fmaxf(a.m[c], bm);
+    float p[4], ps = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      p[i] = __expf(s4[i] - mn);      // exp(-inf) = 0 for masked keys
+      ps += p[i];
+    }
+    ps += __shfl_xor(ps, 16);
+    ps += __shfl_xor(ps, 32);
+    const float corr = __expf(a.m[c] - mn);
+    a.l[c] = a.l[c] * corr + ps;
+    a.m[c] = mn;
+    float c4[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) c4[i] = __shfl(corr, lg * 4 + i);
+    short4_t pa;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) pa[i] = (short)f32_to_bf16(p[i]);
+#pragma unroll
+    for (int d = 0; d < HD / 16; ++d) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a.o[c][d][i] *= c4[i];
+      a.o[c][d] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, vb[d], a.o[c][d], 0, 0, 0);
+    }
+  }
+}
+
+struct AttnMfmaShared {
+  float m[4][16], l[4][16];
+  float o[4][16][128];
+};
+
+// ---- decode: one workgroup per (sequence, kv head); the four waves take the KV blocks round-robin ----------------
+template <int HD>
+__device__ void attn_decode(const DevCtx& c, u32 layer, AttnMfmaShared& sh, u32 wg, u32 nwg) {
+  const u32 B = c.meta->n_seqs, G = c.nq / c.nkv;
+  const u32 lane = threadIdx.x & 63, w = threadIdx.x >> 6, lg = lane >> 4, lc = lane & 15;
+  const bf16_t* Kc = (const bf16_t*)c.kv + (u64)layer * c.kv_layer_stride;
+  const bf16_t* Vc = Kc + c.kv_kv_stride;
+  const u64 tile = (u64)16 * HD;
+  for (u32 item = wg; item < B * c.nkv; item += nwg) {
+    const u32 s = item / c.nkv, g = item % c.nkv;
+    const u32 t = c.cu_seqlens[s];              // the sequence's single token of this iteration
+    const u32 ctx = c.seq_len[s];
+    const u32* bt = c.block_tables + (u64)c.seq_bslot[s] * c.max_blocks_per_seq;
+    bf16x8_t q[1][HD / 32];
+#pragma unroll
+    for (int st = 0; st < HD / 32; ++st) {
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (lc < G) v = *(const uint4*)(c.qbuf + ((u64)t * c.nq + g * G + lc) * HD + st * 32 + lg * 8);
+      q[0][st] = *(const bf16x8_t*)&v;
+    }
+    AttnAcc<HD, 1> acc;
+    attn_init(acc);
+    const u32 lim[1] = {ctx};
+    const u32 nb = (ctx + 15) / 16;
+    for (u32 jb = w; jb < nb; jb += 4) {
+      const u64 base = ((u64)bt[jb] * c.nkv + g) * tile;
+      attn_block<HD, 1>(Kc + base, Vc + base, q, jb * 16, lim, acc);
+    }
+    __syncthreads();   // the previous item's combine has finished reading LDS
+    if (lg == 0) { sh.m[w][lc] = acc.m[0]; sh.l[w][lc] = acc.l[0]; }
+#pragma unroll
+    for (int d = 0; d < HD / 16; ++d)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) sh.o[w][lg * 4 + i][d * 16 + lc] = acc.o[0][d][i];
+    __syncthreads();
+    for (u32 idx = threadIdx.x; idx < G * HD; idx += BLK_THREADS) {
+      const u32 h = idx / HD, dim = idx % HD;
+      const float M = fmaxf(fmaxf(sh.m[0][h], sh.m[1][h]), fmaxf(sh.m[2][h], sh.m[3][h]));
+      float L = 0.f, O = 0.f;
+#pragma unroll
+      for (int ww = 0; ww < 4; ++ww) {
+        const float f = __expf(sh.m[ww][h] - M);
+        L += sh.l[ww][h] * f;
+        O += sh.o[ww][h][dim] * f;
+      }
+      c.aq[packed_off(t, (g * G + h) * HD + dim, c.TBS)] = f32_to_bf16(O / L);
+    }
+  }
+}
+
+// ---- prefill: one wave per (sequence, kv head, head group, tile of 16 query positions) -----------------------------
+template <int HD, int CT>
+__device__ void attn_prefill(const DevCtx& c, u32 layer, u32 wg, u32 nwg) {
+  const u32 B = c.meta->n_seqs, G = c.nq / c.nkv, groups = G / CT;
+  const u32 lane = threadIdx.x & 63, w = threadIdx.x >> 6, lg = lane >> 4, lc = lane & 15;
+  const bf16_t* Kc = (const bf16_t*)c.kv + (u64)layer * c.kv_layer_stride;
+  const bf16_t* Vc = Kc + c.kv_kv_stride;
+  const u64 tile = (u64)16 * HD;
+  const u32 total_qt = c.cu_qtiles[B];
+  const u32 per_tile = c.nkv * groups;
+  for (u64 item = (u64)wg * 4 + w; item < (u64)total_qt * per_tile; item += (u64)nwg * 4) {
+    const u32 qi = (u32)(item / per_tile), rem = (u32)(item % per_tile), g = rem / groups, hg = rem % groups;
+    u32 lo = 0, hi = B;                       // sequence of query tile qi: last s with cu_qtiles[s] <= qi
+    while (hi - lo > 1) {
+      const u32 mid = (lo + hi) / 2;
+      if (c.cu_qtiles[mid] <= qi) lo = mid; else hi = mid;
+    }
+    const u32 s = lo, p0 = (qi - c.cu_qtiles[s]) * 16;
+    const u32 t0 = c.cu_seqlens[s], P = c.cu_seqlens[s + 1] - t0;
+    const u32* bt = c.block_tables + (u64)c.seq_bslot[s] * c.max_blocks_per_seq;
+    const bool colv = p0 + lc < P;
+    bf16x8_t q[CT][HD / 32];
+    u32 lim[CT];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+      lim[ct] = colv ? p0 + lc + 1 : 1;
+#pragma unroll
+      for (int st = 0; st < HD / 32; ++st) {
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (colv) v = *(const uint4*)(c.qbuf + ((u64)(t0 + p0 + lc) * c.nq + g * G + hg * CT + ct) * HD + st * 32 + lg * 8);
+        q[ct][st] = *(const bf16x8_t*)&v;
+      }
+    }
+    AttnAcc<HD, CT> acc;
+    attn_init(acc);
+    const u32 last = min(p0 + 15, P - 1) / 16;
+    for (u32 jb = 0; jb <= last; ++jb) {
+      const u64 base = ((u64)bt[jb] * c.nkv + g) * tile;
+      attn_block<HD, CT>(Kc + base, Vc + base, q, jb * 16, lim, acc);
+    }
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+      float inv[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) inv[i] = 1.0f / __shfl(acc.l[ct], lg * 4 + i);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const u32 r = lg * 4 + i;
+        if (p0 + r < P) {
+#pragma unroll
+          for (int d = 0; d < HD / 16; ++d)
+            c.aq[packed_off(t0 + p0 + r, (g * G + hg * CT + ct) * HD + d * 16 + lc, c.TBS)] = f32_to_bf16(acc.o[ct][d][i] * inv[i]);
+        }
+      }
+    }
+  }
+}
+
+template <int HD>
+__device__ __forceinline__ void attn_prefill_hd(const DevCtx& c, u32 layer, u32 wg, u32 nwg) {
+  const u32 G = c.nq / c.nkv;
+  switch (G) {
+    case 1: attn_prefill<HD, 1>(c, layer, wg, nwg); break;
+    case 2: attn_prefill<HD, 2>(c, layer, wg, nwg); break;
+    case 3: attn_prefill<HD, 3>(c, layer, wg, nwg); break;
+    case 4: attn_prefill<HD, 4>(c, layer, wg, nwg); break;
+    case 6: attn_prefill<HD, 3>(c, layer, wg, nwg); break;
+    case 8: attn_prefill<HD, 4>(c, layer, wg, nwg); break;
+    default: break;   // rejected at init
+  }
+}
+
+__device__ void phase_attention_mfma(const DevCtx& c, u32 layer, AttnMfmaShared& sh, u32 wg, u32 nwg) {
+  if (c.meta->kind == 2u) {
+    if (c.hd == 64) attn_decode<64>(c, layer, sh, wg, nwg); else attn_decode<128>(c, layer, sh, wg, nwg);
+  } else {
+    if (c.hd == 64) attn_prefill_hd<64>(c, layer, wg, nwg); else attn_prefill_hd<128>(c, layer, wg, nwg);
+  }
+}

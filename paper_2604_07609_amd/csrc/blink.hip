@@ -69,6 +69,10 @@ __global__ void k_rope_table(float2* tab, u32 max_pos, u32 half, double theta) {
   tab[i] = make_float2((float)cos(ang), (float)sin(ang));
 }
 
+__global__ void __launch_bounds__(BLK_THREADS) k_pack_weights(const bf16_t* src, bf16_t* dst, u32 N, u32 K, u32 pair_rows, u32 perm_hd) {
+  pack_weights(src, dst, N, K, pair_rows, perm_hd, (u64)blockIdx.x * blockDim.x + threadIdx.x, (u64)gridDim.x * blockDim.x);
+}
+
 __global__ void k_open_window(SchedState* ss, u64 iter_limit) {
   ss->stopped = 0;
   ss->iter_limit = iter_limit;
@@ -223,6 +227,7 @@ static int init_impl(const blink_config* cfg, blink_engine* e) {
   if (int rc = dalloc(e, &c.seq_len, c.max_batch)) return rc;
   if (int rc = dalloc(e, &c.cu_seqlens, c.max_batch + 1)) return rc;
   if (int rc = dalloc(e, &c.last_idx, c.max_batch)) return rc;
+  if (int rc = dalloc(e, &c.cu_qtiles, c.max_batch + 1)) return rc;
   if (int rc = dalloc(e, &c.input_ids, c.maxT)) return rc;
   if (int rc = dalloc(e, &c.positions, c.maxT)) return rc;
   if (int rc = dalloc(e, &c.slot_mapping, c.maxT)) return rc;
@@ -272,20 +277,56 @@ static int init_impl(const blink_config* cfg, blink_engine* e) {
     HIPCHK(hipGetLastError());
     c.rope_tab = tab;
   }
+  // ---- bf16 path: weights re-tiled into MFMA operand order, packed activation buffers ----
+  c.TBS = ((c.maxT + 127) / 128) * 8;
+  if (c.dtype == 1) {
+    std::vector<LayerWP> lp(c.n_layers);
+    std::vector<LayerW> lw(c.n_layers);
+    HIPCHK(hipMemcpy(lw.data(), c.layers, sizeof(LayerW) * c.n_layers, hipMemcpyDeviceToHost));
+    auto pack = [&](const void* src, u32 N, u32 K, u32 pair_rows, u32 perm_hd, const bf16_t** dst) -> int {
+      bf16_t* p;
+      const u64 elems = (u64)((N + 15) / 16) * 16 * K;
+      if (int rc = dalloc(e, &p, elems, false)) return rc;
+      hipLaunchKernelGGL(k_pack_weights, dim3(2048), dim3(BLK_THREADS), 0, e->compute, (const bf16_t*)src, p, N, K, pair_rows, perm_hd);
+      HIPCHK(hipGetLastError());
+      *dst = p;
+      e->weight_bytes += elems * 2;
+      return 0;
+    };
+    for (u32 l = 0; l < c.n_layers; ++l) {
+      if (int rc = pack(lw[l].wqkv, c.qkv_n, c.d, 0, c.hd, &lp[l].wqkv)) return rc;
+      if (int rc = pack(lw[l].wo, c.d, c.nq * c.hd, 0, 0, &lp[l].wo)) return rc;
+      if (int rc = pack(lw[l].wgu, 2 * c.F, c.d, c.F, 0, &lp[l].wgu)) return rc;
+      if (int rc = pack(lw[l].wd, c.d, c.F, 0, 0, &lp[l].wd)) return rc;
+    }
+    if (int rc = pack(c.lm, c.V, c.d, 0, 0, &c.lm_p)) return rc;
+    LayerWP* dp;
+    if (int rc = dalloc(e, &dp, c.n_layers)) return rc;
+    HIPCHK(hipMemcpy(dp, lp.data(), sizeof(LayerWP) * c.n_layers, hipMemcpyHostToDevice));
+    c.players = dp;
+    const u64 tile_tokens = (u64)c.TBS * 16;
+    if (int rc = dalloc(e, &c.xq, tile_tokens * c.d)) return rc;
+    if (int rc = dalloc(e, &c.aq, tile_tokens * c.nq * c.hd)) return rc;
+    if (int rc = dalloc(e, &c.hq, tile_tokens * c.F)) return rc;
+    if (int rc = dalloc(e, &c.ssq, tile_tokens * (c.d / 16))) return rc;
+    if (int rc = dalloc(e, &c.qbuf, (u64)c.maxT * c.nq * c.hd)) return rc;
+  }
   // ---- KV pool ----
   c.kv_kv_stride = (u64)c.n_blocks * c.nkv * c.bs * c.hd;
   c.kv_layer_stride = 2 * c.kv_kv_stride;
   e->kv_bytes = (u64)c.n_layers * c.kv_layer_stride * es;
   char* kv;
-  if (int rc = dalloc(e, &kv, e->kv_bytes, false)) return rc;
+  if (int rc = dalloc(e, &kv, e->kv_bytes, true)) return rc;   // zeroed: masked keys multiply cached values by 0
   c.kv = kv;
   // ---- activations ----
   if (int rc = dalloc(e, &c.x, (u64)c.maxT * c.d)) return rc;
-  if (int rc = dalloc(e, &c.h, (u64)c.maxT * c.d)) return rc;
-  if (int rc = dalloc(e, &c.qkv, (u64)c.maxT * c.qkv_n)) return rc;
-  if (int rc = dalloc(e, &c.attn, (u64)c.maxT * c.nq * c.hd)) return rc;
-  if (int rc = dalloc(e, &c.gu, (u64)c.maxT * 2 * c.F)) return rc;
-  if (int rc = dalloc(e, &c.hlast, (u64)c.max_batch * c.d)) return rc;
+  if (c.dtype == 0) {
+    if (int rc = dalloc(e, &c.h, (u64)c.maxT * c.d)) return rc;
+    if (int rc = dalloc(e, &c.qkv, (u64)c.maxT * c.qkv_n)) return rc;
+    if (int rc = dalloc(e, &c.attn, (u64)c.maxT * c.nq * c.hd)) return rc;
+    if (int rc = dalloc(e, &c.gu, (u64)c.maxT * 2 * c.F)) return rc;
+    if (int rc = dalloc(e, &c.hlast, (u64)c.max_batch * c.d)) return rc;
+  }
   if (int rc = dalloc(e, &c.logits, (u64)c.max_batch * c.V)) return rc;
   HIPCHK(hipStreamSynchronize(e->compute));
   HIPCHK(hipDeviceSynchronize());
@@ -316,6 +357,11 @@ extern "C" int blink_init(const blink_config* cfg, blink_engine** out) {
     return fail(BLINK_ERR_INVAL, "n_q_heads must be a multiple (at most %d) of n_kv_heads", ATT_MAX_G);
   if (cfg->d_model % 32 || cfg->d_ffn % 32 || (cfg->n_q_heads * cfg->head_dim) % 32)
     return fail(BLINK_ERR_INVAL, "d_model, d_ffn and n_q_heads*head_dim must be multiples of 32");
+  if (cfg->dtype == 1) {
+    const u32 G = cfg->n_q_heads / cfg->n_kv_heads;
+    if (!(G == 1 || G == 2 || G == 3 || G == 4 || G == 6 || G == 8))
+      return fail(BLINK_ERR_INVAL, "bf16 path: n_q_heads / n_kv_heads must be 1, 2, 3, 4, 6 or 8");
+  }
   if (cfg->vocab >= (1u << 24)) return fail(BLINK_ERR_INVAL, "vocab must be below 2^24");
   if (cfg->kv_block_size != 16) return fail(BLINK_ERR_INVAL, "kv_block_size must be 16");
   if (!cfg->kv_num_blocks || !cfg->max_batch || cfg->max_batch > SCHED_MAX_BATCH)
@@ -388,6 +434,7 @@ extern "C" int blink_submit(blink_engine* e, const int32_t* prompt, uint32_t n_p
 // and never reads a result the device waits for. Every decision (what runs, on which shapes, when the window
 // ends) is taken on the device; an iteration enqueued after the window has ended costs a few empty kernels.
 static int launch_phase(blink_engine* e, hipStream_t st, int ph, u32 layer, u64 enq_index) {
+  if (e->ctx.dtype == 1 && (ph == PH_NORM1 || ph == PH_NORM2 || ph == PH_FINAL_NORM || ph == PH_ROPE)) return 0;   // fused into the GEMMs
   const bool timed = e->timed_phase == ph && enq_index != ~0ull;
   hipEvent_t a = nullptr, b = nullptr;
   if (timed) {

@@ -121,6 +121,13 @@ struct LayerW {
   const void* wd;       // [d][F]
 };
 
+struct LayerWP {        // bf16 weights re-tiled into MFMA operand order (see mfma_gemm.h)
+  const bf16_t* wqkv;   // N = (nq+2nkv)*hd, K = d
+  const bf16_t* wo;     // N = d, K = nq*hd
+  const bf16_t* wgu;    // N = 2F (gate_j, up_j interleaved), K = d
+  const bf16_t* wd;     // N = d, K = F
+};
+
 struct DevCtx {
   // model
   u32 n_layers, d, nq, nkv, hd, F, V, dtype;
@@ -146,6 +153,7 @@ struct DevCtx {
   u32* seq_len;         // [max_batch]
   u32* cu_seqlens;      // [max_batch+1]
   u32* last_idx;        // [max_batch]
+  u32* cu_qtiles;       // [max_batch+1] prefix sum of ceil(tokens/16) per sequence of the iteration
   i32* input_ids;       // [maxT]
   i32* positions;       // [maxT]
   i32* slot_mapping;    // [maxT]
@@ -169,6 +177,16 @@ struct DevCtx {
   float* gu;            // [maxT][2F]
   float* hlast;         // [max_batch][d]
   float* logits;        // [max_batch][V]
+  // bf16 path: packed weights and packed activation operands
+  const LayerWP* players;
+  const bf16_t* lm_p;
+  bf16_t* xq;           // packed bf16(x * gain of the next RMSNorm), inner dimension d
+  bf16_t* aq;           // packed attention output, inner dimension nq*hd
+  bf16_t* qbuf;         // [maxT][nq][hd] rotated queries scaled by 1/sqrt(hd)
+  bf16_t* hq;           // packed silu(gate)*up, inner dimension F
+  float* ssq;           // [d/16][TBS*16] partial sums of squares of the residual stream
+  u32 TBS;              // token-block stride of the packed activation buffers
+  u32 pad1;
 };
 
 __device__ __forceinline__ u64 dev_now_ns() { return wall_clock64() * 10ull; }  // 100 MHz constant clock

@@ -55,6 +55,10 @@ __device__ __forceinline__ float block_max_f(float v, float* red) {
   return fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
 }
 
+__device__ __forceinline__ u64 packed_act_off(u32 t, u32 k, u32 TBS) {   // same layout as mfma_gemm.h
+  return ((u64)((k >> 5) * TBS + (t >> 4)) * 64 + (t & 15) + 16 * ((k & 31) >> 3)) * 8 + (k & 7);
+}
+
 // ---- embedding gather: x[t] = E[input_ids[t]] ---------------------------------------------------------------
 template <typename WT>
 __device__ void phase_embed(const DevCtx& c, u32 wg, u32 nwg) {
@@ -68,6 +72,36 @@ __device__ void phase_embed(const DevCtx& c, u32 wg, u32 nwg) {
     float* o = c.x + (u64)t * d + j;
     *(float4*)o = make_float4(v[0], v[1], v[2], v[3]);
     *(float4*)(o + 4) = make_float4(v[4], v[5], v[6], v[7]);
+  }
+}
+
+// ---- embedding gather of the bf16 path: residual stream, packed operand of the first GEMM (x * g1 of layer 0)
+// and the partial sums of squares its RMSNorm needs; one thread per (token, 16 columns) --------------------------
+__device__ void phase_embed_packed(const DevCtx& c, u32 wg, u32 nwg) {
+  const u32 T = c.meta->n_tokens, d = c.d, per_row = d / 16;
+  const bf16_t* E = (const bf16_t*)c.embed;
+  const float* g = c.layers[0].g1;
+  for (u64 i = (u64)wg * BLK_THREADS + threadIdx.x; i < (u64)T * per_row; i += (u64)nwg * BLK_THREADS) {
+    const u32 t = (u32)(i / per_row), nt = (u32)(i % per_row), k0 = nt * 16;
+    float v[16];
+    WLoad<bf16_t>::load8(E + (u64)c.input_ids[t] * d + k0, v);
+    WLoad<bf16_t>::load8(E + (u64)c.input_ids[t] * d + k0 + 8, v + 8);
+    float* o = c.x + (u64)t * d + k0;
+    float ss = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) *(float4*)(o + 4 * j) = make_float4(v[4 * j], v[4 * j + 1], v[4 * j + 2], v[4 * j + 3]);
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      u32 w[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float a = v[8 * h + 2 * j], b = v[8 * h + 2 * j + 1];
+        ss += a * a + b * b;
+        w[j] = (u32)f32_to_bf16(a * g[k0 + 8 * h + 2 * j]) | ((u32)f32_to_bf16(b * g[k0 + 8 * h + 2 * j + 1]) << 16);
+      }
+      *(uint4*)(c.xq + packed_act_off(t, k0 + 8 * h, c.TBS)) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+    c.ssq[(u64)nt * (c.TBS * 16) + t] = ss;
   }
 }
 
@@ -199,7 +233,7 @@ struct AttnShared {
   float accred[4][ATT_MAX_G][64];
 };
 
-template <typename WT>
+template <typename WT, bool PACKED_OUT>
 __device__ void phase_attention(const DevCtx& c, u32 layer, AttnShared& sh, u32 wg, u32 nwg) {
   const u32 T = c.meta->n_tokens, hd = c.hd, G = c.nq / c.nkv, tid = threadIdx.x;
   const WT* Kc = (const WT*)c.kv + (u64)layer * c.kv_layer_stride;
@@ -276,7 +310,8 @@ __device__ void phase_attention(const DevCtx& c, u32 layer, AttnShared& sh, u32 
           if ((u32)h < G) {
             float a = 0.f;
             for (u32 pp = 0; pp < nparts; ++pp) a += sh.accred[pp][h][slot64];
-            c.attn[(u64)t * (c.nq * hd) + (u64)(g * G + h) * hd + dd] = a / l[h];
+            if (PACKED_OUT) c.aq[packed_act_off(t, (g * G + h) * hd + dd, c.TBS)] = f32_to_bf16(a / l[h]);
+            else c.attn[(u64)t * (c.nq * hd) + (u64)(g * G + h) * hd + dd] = a / l[h];
           }
       }
     }

@@ -1,0 +1,307 @@
+// bf16 GEMMs of the forward pass on the CDNA4 matrix cores (v_mfma_f32_16x16x32_bf16), the only dense
+// contractions of the serving step. Both operands live in HBM already in MFMA operand order, so that
+// every wave-wide load is one contiguous kilobyte and no LDS staging or transposition is needed:
+//
+//   weights      Wp[n/16][k/32][lane][8]      lane = n%16 + 16*((k%32)/8), element = k%8   (packed once at init)
+//   activations  Xp[k/32][t/16][lane][8]      lane = t%16 + 16*((k%32)/8), element = k%8   (written packed by the
+//                                                                                  producing kernel's epilogue)
+//
+// out[t][n] = sum_k X[t][k] * W[n][k]. Two schedules, chosen from the token count of the iteration:
+//   stream (T <= 64, decode): one 16-row weight tile per workgroup, the four waves split K and keep many
+//     1 KB weight loads in flight (pure weight streaming, HBM bound); partial sums are reduced through LDS
+//     in a fixed order.
+//   tile (T > 64, prefill): 128 x 128 output tile per workgroup, 64 x 64 per wave (16 accumulator tiles).
+// Epilogues fuse what follows the GEMM in the model: RMSNorm scale of the *input* (a per-token scalar,
+// applied to the accumulator), residual add, SiLU-gating, and re-packing of the result as the next
+// GEMM's activation operand together with the partial sums of squares the next RMSNorm needs.
+#pragma once
+#include "blink_device.h"
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float floatx4_t __attribute__((ext_vector_type(4)));
+
+#define EPI_SCALED_STORE 0   // out[t][n] = rstd[t] * acc                      (QKV projection, LM head)
+#define EPI_RESIDUAL 1       // x[t][n] += acc; emit packed bf16(x * g_next) and sum-of-squares partials
+#define EPI_SILU_GATE 2      // rows interleaved (gate_j, up_j): emit packed bf16(silu(r*g) * (r*u))
+#define EPI_QKV_ROPE 3       // rows of every head interleaved (dim p, dim p+hd/2): rotary embedding, then q to the query
+                             // buffer, k and v straight into the paged cache through the slot mapping
+
+struct MfmaGemmArgs {
+  const bf16_t* Wp;        // packed weights
+  const bf16_t* Xp;        // packed activations (K = inner dimension)
+  u32 N, K;                // logical output rows and inner dimension (K % 32 == 0)
+  u32 T;                   // tokens (columns)
+  u32 TBS;                 // token-block stride of every packed activation buffer
+  const u32* tok_index;    // optional indirection: column t reads token tok_index[t] of Xp / ssq_in (LM head)
+  const float* ssq_in;     // [K/16][TBS*16] partial sums of squares of the un-normalised input (null: no scaling)
+  float eps;
+  // EPI_SCALED_STORE
+  float* out; u32 ldo;
+  // EPI_RESIDUAL
+  float* x; u32 ldx;       // residual stream, updated in place
+  const float* g_next;     // gain of the RMSNorm that consumes x next
+  bf16_t* Xp_next;         // packed bf16(x * g_next), inner dimension N
+  float* ssq_out;          // [N/16][TBS*16]
+  // EPI_SILU_GATE
+  bf16_t* Hp;              // packed activations with inner dimension N/2
+  // EPI_QKV_ROPE
+  const DevCtx* ctx;
+  u32 layer;
+};
+
+struct MfmaShared {
+  float red[4][4][64][4];  // [wave][token block][lane][4]  (stream schedule)
+  float rstd[128];
+};
+
+__device__ __forceinline__ u64 packed_off(u32 t, u32 k, u32 TBS) {
+  return ((u64)((k >> 5) * TBS + (t >> 4)) * 64 + (t & 15) + 16 * ((k & 31) >> 3)) * 8 + (k & 7);
+}
+
+__device__ __forceinline__ bf16x8_t ld_tile(const bf16_t* p) {   // one lane's 16 bytes of a packed tile
+  const uint4 v = *(const uint4*)p;
+  return *(const bf16x8_t*)&v;
+}
+
+// rstd of `count` tokens starting at column t0 into sh.rstd[0..count)
+__device__ __forceinline__ void compute_rstd(const MfmaGemmArgs& a, u32 t0, u32 count, MfmaShared& sh) {
+  const u32 tid = threadIdx.x;
+  __syncthreads();
+  if (a.ssq_in == nullptr) {
+    if (tid < 128) sh.rstd[tid] = 1.0f;
+  } else {
+    // 256 threads: two threads per token for 128 tokens (or up to four for 64): fixed-order split of the partials
+    const u32 parts = count <= 64 ? 4u : 2u, span = BLK_THREADS / parts;
+    const u32 tl = tid % span, part = tid / span;
+    float s = 0.f;
+    const u32 np = a.K / 16;
+    if (tl < count && t0 + tl < a.T) {
+      const u32 tok = a.tok_index ? a.tok_index[t0 + tl] : t0 + tl;
+      for (u32 p = part; p < np; p += parts) s += a.ssq_in[(u64)p * (a.TBS * 16) + tok];
+    }
+    float* scratch = &sh.red[0][0][0][0];
+    scratch[part * span + tl] = s;
+    __syncthreads();
+    if (tid < count) {
+      float tot = 0.f;
+      for (u32 p = 0; p < parts; ++p) tot += scratch[p * span + tid];
+      sh.rstd[tid] = 1.0f / sqrtf(tot / (float)a.K + a.eps);
+    }
+  }
+  __syncthreads();
+}
+
+// Epilogue of one 16(n) x 16(t) accumulator tile held by one wave. rl: index of the tile's first token in sh.rstd.
+template <int EPI>
+__device__ __forceinline__ void epilogue_tile(const MfmaGemmArgs& a, floatx4_t acc, u32 nt, u32 t_base, const float* rstd16) {
+  const u32 lane = threadIdx.x & 63;
+  const u32 t = t_base + (lane & 15);
+  const u32 n0 = nt * 16 + (lane >> 4) * 4;
+  const bool tv = t < a.T;
+  if (EPI == EPI_SCALED_STORE) {
+    if (!tv) return;
+    const float r = rstd16[lane & 15];
+    float* o = a.out + (u64)t * a.ldo + n0;
+    if (n0 + 3 < a.N && (a.ldo & 3) == 0) {
+      *(float4*)o = make_float4(acc[0] * r, acc[1] * r, acc[2] * r, acc[3] * r);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (n0 + i < a.N) o[i] = acc[i] * r;
+    }
+  } else if (EPI == EPI_RESIDUAL) {
+    float v[4] = {0.f, 0.f, 0.f, 0.f};
+    if (tv) {
+      float* xp = a.x + (u64)t * a.ldx + n0;
+      const float4 old = *(const float4*)xp;
+      v[0] = old.x + acc[0]; v[1] = old.y + acc[1]; v[2] = old.z + acc[2]; v[3] = old.w + acc[3];
+      *(float4*)xp = make_float4(v[0], v[1], v[2], v[3]);
+      const float4 g = *(const float4*)(a.g_next + n0);
+      const u32 lo = (u32)f32_to_bf16(v[0] * g.x) | ((u32)f32_to_bf16(v[1] * g.y) << 16);
+      const u32 hi = (u32)f32_to_bf16(v[2] * g.z) | ((u32)f32_to_bf16(v[3] * g.w) << 16);
+      *(uint2*)(a.Xp_next + packed_off(t, n0, a.TBS)) = make_uint2(lo, hi);
+    }
+    float s = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+    s += __shfl_xor(s, 16);
+    s += __shfl_xor(s, 32);
+    if (lane < 16 && tv) a.ssq_out[(u64)nt * (a.TBS * 16) + t] = s;
+  } else if (EPI == EPI_QKV_ROPE) {
+    if (!tv) return;
+    const DevCtx& c = *a.ctx;
+    const float r = rstd16[lane & 15];
+    const u32 hd = c.hd, half = hd / 2, head = n0 / hd, p = (n0 % hd) >> 1;   // rows: (p, p+half, p+1, p+1+half)
+    float lo0 = acc[0] * r, hi0 = acc[1] * r, lo1 = acc[2] * r, hi1 = acc[3] * r;
+    if (head < c.nq + c.nkv) {
+      const float2* rt = c.rope_tab + (u64)c.positions[t] * half + p;
+      const float2 cs0 = rt[0], cs1 = rt[1];
+      const float a0 = lo0 * cs0.x - hi0 * cs0.y, b0 = hi0 * cs0.x + lo0 * cs0.y;
+      const float a1 = lo1 * cs1.x - hi1 * cs1.y, b1 = hi1 * cs1.x + lo1 * cs1.y;
+      lo0 = a0; hi0 = b0; lo1 = a1; hi1 = b1;
+    }
+    if (head < c.nq) {
+      const float sc = 1.0f / sqrtf((float)hd);
+      bf16_t* q = c.qbuf + ((u64)t * c.nq + head) * hd;
+      *(u32*)(q + p) = (u32)f32_to_bf16(lo0 * sc) | ((u32)f32_to_bf16(lo1 * sc) << 16);
+      *(u32*)(q + half + p) = (u32)f32_to_bf16(hi0 * sc) | ((u32)f32_to_bf16(hi1 * sc) << 16);
+    } else {
+      const u32 slot = (u32)c.slot_mapping[t];
+      bf16_t* Kc = (bf16_t*)c.kv + (u64)a.layer * c.kv_layer_stride;
+      if (head < c.nq + c.nkv) {
+        bf16_t* k = Kc + (((u64)(slot / c.bs) * c.nkv + (head - c.nq)) * c.bs + slot % c.bs) * hd;
+        *(u32*)(k + p) = (u32)f32_to_bf16(lo0) | ((u32)f32_to_bf16(lo1) << 16);
+        *(u32*)(k + half + p) = (u32)f32_to_bf16(hi0) | ((u32)f32_to_bf16(hi1) << 16);
+      } else {   // V is kept dimension-major inside a block: [hd][16 tokens]
+        bf16_t* v = Kc + c.kv_kv_stride + ((u64)(slot / c.bs) * c.nkv + (head - c.nq - c.nkv)) * c.bs * hd + slot % c.bs;
+        v[(u64)p * c.bs] = f32_to_bf16(lo0);
+        v[(u64)(p + 1) * c.bs] = f32_to_bf16(lo1);
+        v[(u64)(half + p) * c.bs] = f32_to_bf16(hi0);
+        v[(u64)(half + p + 1) * c.bs] = f32_to_bf16(hi1);
+      }
+    }
+  } else {  // EPI_SILU_GATE
+    if (!tv) return;
+    const float r = rstd16[lane & 15];
+    const float g0 = acc[0] * r, u0 = acc[1] * r, g1 = acc[2] * r, u1 = acc[3] * r;
+    const float h0 = g0 / (1.f + __expf(-g0)) * u0, h1 = g1 / (1.f + __expf(-g1)) * u1;
+    const u32 j = n0 >> 1;   // pair index = inner index of the next GEMM
+    *(u32*)(a.Hp + packed_off(t, j, a.TBS)) = (u32)f32_to_bf16(h0) | ((u32)f32_to_bf16(h1) << 16);
+  }
+}
+
+// ---- stream schedule: T <= 64 ------------------------------------------------------------------------------------
+template <int EPI, int TW>
+__device__ __forceinline__ void gemm_stream(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg) {
+  const u32 lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const u32 NT = (a.N + 15) / 16, KT = a.K / 32;
+  const u32 kb = (u32)((u64)KT * w / 4), ke = (u32)((u64)KT * (w + 1) / 4);
+  compute_rstd(a, 0, 64, sh);
+  // per-lane offsets (in elements) of this lane's 16 bytes inside the token blocks of one k-tile
+  u32 xoff[TW];
+#pragma unroll
+  for (int tw = 0; tw < TW; ++tw) {
+    u32 tok = tw * 16 + (lane & 15);
+    if (a.tok_index) tok = tok < a.T ? a.tok_index[tok] : 0;
+    xoff[tw] = ((tok >> 4) * 64 + (tok & 15) + 16 * (lane >> 4)) * 8;
+  }
+  const u64 xk_stride = (u64)a.TBS * 512;
+  for (u32 nt = wg; nt < NT; nt += nwg) {
+    floatx4_t acc[TW];
+#pragma unroll
+    for (int tw = 0; tw < TW; ++tw) acc[tw] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+    const bf16_t* wp = a.Wp + ((u64)nt * KT) * 512 + lane * 8;
+    u32 kt = kb;
+    for (; kt + 8 <= ke; kt += 8) {
+      bf16x8_t wv[8], xv[8][TW];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) wv[u] = ld_tile(wp + (u64)(kt + u) * 512);
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int tw = 0; tw < TW; ++tw) xv[u][tw] = ld_tile(a.Xp + (u64)(kt + u) * xk_stride + xoff[tw]);
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int tw = 0; tw < TW; ++tw) acc[tw] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv[u], xv[u][tw], acc[tw], 0, 0, 0);
+    }
+    for (; kt < ke; ++kt) {
+      const bf16x8_t wv = ld_tile(wp + (u64)kt * 512);
+#pragma unroll
+      for (int tw = 0; tw < TW; ++tw)
+        acc[tw] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv, ld_tile(a.Xp + (u64)kt * xk_stride + xoff[tw]), acc[tw], 0, 0, 0);
+    }
+    __syncthreads();   // previous tile's reduction has been read
+#pragma unroll
+    for (int tw = 0; tw < TW; ++tw) *(floatx4_t*)&sh.red[w][tw][lane][0] = acc[tw];
+    __syncthreads();
+    if (w < TW) {      // wave w finishes token block w: sum the four K-quarters in a fixed order
+      const floatx4_t s = (*(floatx4_t*)&sh.red[0][w][lane][0] + *(floatx4_t*)&sh.red[1][w][lane][0]) +
+                          (*(floatx4_t*)&sh.red[2][w][lane][0] + *(floatx4_t*)&sh.red[3][w][lane][0]);
+      epilogue_tile<EPI>(a, s, nt, w * 16, &sh.rstd[w * 16]);
+    }
+  }
+}
+
+// ---- tile schedule: T > 64 -----------------------------------------------------------------------------------------
+template <int EPI>
+__device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg) {
+  const u32 lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const u32 NT = (a.N + 15) / 16, KT = a.K / 32;
+  const u32 nblocks = (NT + 7) / 8, tblocks = (a.T + 127) / 128;
+  const u32 wn = w & 1, wt = w >> 1;
+  const u64 xk_stride = (u64)a.TBS * 512;
+  for (u32 item = wg; item < nblocks * tblocks; item += nwg) {
+    const u32 nb = item % nblocks, tb = item / nblocks;
+    compute_rstd(a, tb * 128, 128, sh);
+    const u32 nt0 = nb * 8 + wn * 4;
+    u32 xoff[4];
+#pragma unroll
+    for (int tw = 0; tw < 4; ++tw) {
+      u32 tok = tb * 128 + wt * 64 + tw * 16 + (lane & 15);
+      if (a.tok_index) tok = tok < a.T ? a.tok_index[tok] : 0;
+      xoff[tw] = ((tok >> 4) * 64 + (tok & 15) + 16 * (lane >> 4)) * 8;
+    }
+    const bf16_t* wp[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) wp[i] = a.Wp + ((u64)min(nt0 + i, NT - 1) * KT) * 512 + lane * 8;
+    floatx4_t acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[i][j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 2
+    for (u32 kt = 0; kt < KT; ++kt) {
+      bf16x8_t wv[4], xv[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) wv[i] = ld_tile(wp[i] + (u64)kt * 512);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) xv[j] = ld_tile(a.Xp + (u64)kt * xk_stride + xoff[j]);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv[i], xv[j], acc[i][j], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (nt0 + i < NT) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          epilogue_tile<EPI>(a, acc[i][j], nt0 + i, tb * 128 + wt * 64 + j * 16, &sh.rstd[wt * 64 + j * 16]);
+      }
+  }
+}
+
+template <int EPI>
+__device__ void gemm_mfma(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg) {
+  if (a.T == 0) return;
+  if (a.T <= 16) gemm_stream<EPI, 1>(a, sh, wg, nwg);
+  else if (a.T <= 32) gemm_stream<EPI, 2>(a, sh, wg, nwg);
+  else if (a.T <= 48) gemm_stream<EPI, 3>(a, sh, wg, nwg);
+  else if (a.T <= 64) gemm_stream<EPI, 4>(a, sh, wg, nwg);
+  else gemm_tile<EPI>(a, sh, wg, nwg);
+}
+
+// ---- packing -----------------------------------------------------------------------------------------------------
+// Weights [N][K] row-major -> packed tiles. pair_rows > 0: the source holds `pair_rows` gate rows followed by
+// `pair_rows` up rows, and packed row 2j is gate_j, row 2j+1 is up_j. perm_hd > 0: rows are heads of perm_hd
+// dimensions each, re-ordered so that the two dimensions a rotary embedding pairs up are adjacent rows.
+__device__ __forceinline__ void pack_weights(const bf16_t* src, bf16_t* dst, u32 N, u32 K, u32 pair_rows, u32 perm_hd, u64 gtid,
+                                             u64 gthreads) {
+  const u32 NT = (N + 15) / 16, KT = K / 32;
+  const u64 chunks = (u64)NT * KT * 64;
+  for (u64 i = gtid; i < chunks; i += gthreads) {
+    const u32 lane = (u32)(i & 63);
+    const u64 tile = i >> 6;
+    const u32 kt = (u32)(tile % KT), nt = (u32)(tile / KT);
+    const u32 n = nt * 16 + (lane & 15), k = kt * 32 + (lane >> 4) * 8;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (n < N) {
+      u32 row = pair_rows ? ((n & 1) ? pair_rows + (n >> 1) : (n >> 1)) : n;
+      if (perm_hd) {   // packed row 2p of a head is its dimension p, row 2p+1 its dimension p + hd/2
+        const u32 pi = n % perm_hd;
+        row = n - pi + ((pi & 1) ? perm_hd / 2 + (pi >> 1) : (pi >> 1));
+      }
+      v = *(const uint4*)(src + (u64)row * K + k);
+    }
+    *(uint4*)(dst + i * 8) = v;
+  }
+}

@@ -5,6 +5,8 @@
 #include "blink_device.h"
 #include "sched.h"
 #include "forward.h"
+#include "mfma_gemm.h"
+#include "attention_mfma.h"
 #include "sampler.h"
 
 enum {
@@ -19,6 +21,8 @@ union PhaseShared {
   SchedShared sched;
   GemmShared gemm;
   AttnShared attn;
+  MfmaShared mfma;
+  AttnMfmaShared attn_mfma;
   SamplerShared sampler;
   float red[8];
 };
@@ -35,7 +39,7 @@ __device__ __forceinline__ void run_phase_t(const DevCtx& c, int ph, u32 layer, 
       phase_gemm<WT, GA_PLAIN, GE_STORE>(c.h, c.d, (const WT*)L->wqkv, c.qkv, c.qkv_n, T, c.qkv_n, c.d, sh.gemm, wg, nwg);
       break;
     case PH_ROPE: phase_rope_kvwrite<WT>(c, layer, wg, nwg); break;
-    case PH_ATTN: phase_attention<WT>(c, layer, sh.attn, wg, nwg); break;
+    case PH_ATTN: phase_attention<WT, false>(c, layer, sh.attn, wg, nwg); break;
     case PH_OPROJ:
       phase_gemm<WT, GA_PLAIN, GE_ADD>(c.attn, c.nq * c.hd, (const WT*)L->wo, c.x, c.d, T, c.d, c.nq * c.hd, sh.gemm, wg, nwg);
       break;
@@ -54,8 +58,49 @@ __device__ __forceinline__ void run_phase_t(const DevCtx& c, int ph, u32 layer, 
   }
 }
 
+// bf16 path: MFMA GEMMs on packed operands with the norms, the residual adds and the SiLU gate fused into their
+// epilogues; the separate norm phases do not exist here.
+__device__ __forceinline__ void run_phase_bf16(const DevCtx& c, int ph, u32 layer, PhaseShared& sh, u32 wg, u32 nwg) {
+  const IterMeta* m = c.meta;
+  const LayerWP* P = c.players + layer;
+  MfmaGemmArgs a{};
+  a.T = m->n_tokens;
+  a.TBS = c.TBS;
+  a.eps = c.eps;
+  switch (ph) {
+    case PH_EMBED: phase_embed_packed(c, wg, nwg); break;
+    case PH_QKV:
+      a.Wp = P->wqkv; a.Xp = c.xq; a.N = c.qkv_n; a.K = c.d; a.ssq_in = c.ssq; a.ctx = &c; a.layer = layer;
+      gemm_mfma<EPI_QKV_ROPE>(a, sh.mfma, wg, nwg);
+      break;
+    case PH_ATTN: phase_attention_mfma(c, layer, sh.attn_mfma, wg, nwg); break;
+    case PH_OPROJ:
+      a.Wp = P->wo; a.Xp = c.aq; a.N = c.d; a.K = c.nq * c.hd; a.x = c.x; a.ldx = c.d; a.g_next = c.layers[layer].g2;
+      a.Xp_next = c.xq; a.ssq_out = c.ssq;
+      gemm_mfma<EPI_RESIDUAL>(a, sh.mfma, wg, nwg);
+      break;
+    case PH_GATEUP:
+      a.Wp = P->wgu; a.Xp = c.xq; a.N = 2 * c.F; a.K = c.d; a.ssq_in = c.ssq; a.Hp = c.hq;
+      gemm_mfma<EPI_SILU_GATE>(a, sh.mfma, wg, nwg);
+      break;
+    case PH_DOWN:
+      a.Wp = P->wd; a.Xp = c.hq; a.N = c.d; a.K = c.F; a.x = c.x; a.ldx = c.d;
+      a.g_next = layer + 1 < c.n_layers ? c.layers[layer + 1].g1 : c.gf;
+      a.Xp_next = c.xq; a.ssq_out = c.ssq;
+      gemm_mfma<EPI_RESIDUAL>(a, sh.mfma, wg, nwg);
+      break;
+    case PH_LM_HEAD:
+      a.Wp = c.lm_p; a.Xp = c.xq; a.N = c.V; a.K = c.d; a.T = m->n_seqs; a.tok_index = c.last_idx; a.ssq_in = c.ssq;
+      a.out = c.logits; a.ldo = c.V;
+      gemm_mfma<EPI_SCALED_STORE>(a, sh.mfma, wg, nwg);
+      break;
+    case PH_SAMPLE: phase_sample_publish(c, sh.sampler, wg, nwg); break;
+    default: break;   // the norms and the rotary / KV-write step are fused into the GEMMs
+  }
+}
+
 __device__ __forceinline__ void run_phase(const DevCtx& c, int ph, u32 layer, PhaseShared& sh, u32 wg, u32 nwg) {
   if (c.meta->skip || c.meta->kind == KIND_IDLE) return;
-  if (c.dtype == 1) run_phase_t<bf16_t>(c, ph, layer, sh, wg, nwg);
+  if (c.dtype == 1) run_phase_bf16(c, ph, layer, sh, wg, nwg);
   else run_phase_t<float>(c, ph, layer, sh, wg, nwg);
 }

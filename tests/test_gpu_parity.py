@@ -33,7 +33,7 @@ def test_bf16_gqa_end_to_end(lib, name, seed):
     ev, trace, st = parity.run_engine(lib, cfg, eng, blob, reqs)
     assert st["free_blocks"] == eng["kv_num_blocks"] and st["committed_blocks"] == 0 and st["n_running"] == 0
     assert len(ev) == sum(r["max_new_tokens"] for r in reqs)
-    res = parity.check_against_oracle(cfg, M.Weights(cfg, raw), eng, reqs, ev, trace, rtol=2e-2, tok_rtol=6e-3)
+    res = parity.check_against_oracle(cfg, M.Weights(cfg, raw), eng, reqs, ev, trace, rtol=2e-2, tok_rtol=1e-2)
     print(name, "tokens", res["tokens"], "near ties", res["near_ties"], "prefill iterations", st["prefill_iterations"])
     assert st["prefill_iterations"] >= 2          # the pool / batch limit forced queueing
     assert res["near_ties"] < res["tokens"] // 2
@@ -45,6 +45,19 @@ def test_bf16_gqa_stepwise_logits(lib, name, seed):
     reqs = synth.make_workload("mini", cfg["vocab"], seed + 100, n_requests=9)
     worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2)
     print(name, "worst relative logit error", worst)
+
+
+@pytest.mark.parametrize("max_batch,n_req", [(24, 30), (40, 44), (60, 64), (80, 90)])
+def test_bf16_wide_decode_batches(lib, max_batch, n_req):
+    """Decode batches of 17..80 sequences: every token-block count of the streaming GEMM schedule and, above 64,
+    the tiled schedule; prefill iterations of several hundred tokens."""
+    cfg, eng, raw, blob = setup("mini_gqa128", 33)
+    eng = dict(eng, max_batch=max_batch, kv_num_blocks=max_batch * 8, max_prefill_tokens=700, ring_slots=128)
+    reqs = synth.make_workload("mini", cfg["vocab"], 133 + max_batch, n_requests=n_req)
+    for r in reqs:
+        r["max_new_tokens"] = min(r["max_new_tokens"], 6)
+    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2)
+    print("max_batch", max_batch, "worst relative logit error", worst)
 
 
 def test_fp32_gqa_stepwise_logits(lib):
@@ -64,7 +77,7 @@ def test_sampled_requests(lib, name, seed):
     reqs = sampled(base, seed)
     ev, trace, st = parity.run_engine(lib, cfg, eng, blob, reqs)
     res = parity.check_against_oracle(cfg, M.Weights(cfg, raw), eng, reqs, ev, trace, rtol=2e-2 if cfg["dtype"] else 1e-4,
-                                      tok_rtol=6e-3 if cfg["dtype"] else 1e-5)
+                                      tok_rtol=1e-2 if cfg["dtype"] else 1e-5)
     print(name, "sampled: tokens", res["tokens"], "undecided", res["near_ties"])
     if cfg["dtype"] == 0:
         assert res["near_ties"] < res["tokens"] // 5
