@@ -96,6 +96,7 @@ def main():
     ap.add_argument("--workload", default=os.environ.get("BLINK_BENCH_WORKLOAD", "churn"), choices=sorted(WORKLOADS))
     ap.add_argument("--phase", type=int, default=7, help="forward phase whose kernel is timed for the roofline")
     ap.add_argument("--requests", type=int, default=0)
+    ap.add_argument("--max-batch", type=int, default=0, help="override the engine's batch slots")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0)
     args = ap.parse_args()
@@ -111,6 +112,8 @@ def main():
     t_gen = time.perf_counter()
     raw = synth.make_weights(cfg, wl["wseed"], threads=min(16, os.cpu_count() or 8))
     reqs = synth.make_workload(wl["workload"], cfg["vocab"], wl["rseed"], n_requests=args.requests or None)
+    if args.max_batch:
+        eng["max_batch"] = args.max_batch
     if eng["kv_num_blocks"] == 0:
         eng["kv_num_blocks"] = churn_pool_blocks(reqs, eng["kv_block_size"])
     reqs = reqs[: eng["ring_slots"]]

@@ -34,19 +34,30 @@ __device__ __forceinline__ void attn_init(AttnAcc<HD, CT>& a) {
 
 // One KV block. Kt/Vt: the block's tiles for this kv head. j0: position of the block's first token.
 // lim[c]: number of visible keys (position + 1) for this lane's column of column-tile c.
-template <int HD, int CT>
-__device__ __forceinline__ void attn_block(const bf16_t* Kt, const bf16_t* Vt, const bf16x8_t (&q)[CT][HD / 32], u32 j0,
-                                           const u32 (&lim)[CT], AttnAcc<HD, CT>& a) {
-  const u32 lane = threadIdx.x & 63, lg = lane >> 4, lc = lane & 15;
+template <int HD>
+struct KVTile {
   bf16x8_t ka[HD / 32];
   short4_t vb[HD / 16];
+};
+
+template <int HD>
+__device__ __forceinline__ void kv_load(const bf16_t* Kt, const bf16_t* Vt, KVTile<HD>& r) {
+  const u32 lane = threadIdx.x & 63, lg = lane >> 4, lc = lane & 15;
 #pragma unroll
-  for (int s = 0; s < HD / 32; ++s) ka[s] = ld_tile(Kt + lc * HD + s * 32 + lg * 8);
+  for (int s = 0; s < HD / 32; ++s) r.ka[s] = ld_tile(Kt + lc * HD + s * 32 + lg * 8);
 #pragma unroll
   for (int d = 0; d < HD / 16; ++d) {
     const uint2 v = *(const uint2*)(Vt + (d * 16 + lc) * 16 + lg * 4);
-    vb[d] = *(const short4_t*)&v;
+    r.vb[d] = *(const short4_t*)&v;
   }
+}
+
+template <int HD, int CT>
+__device__ __forceinline__ void attn_block(const KVTile<HD>& kv, const bf16x8_t (&q)[CT][HD / 32], u32 j0,
+                                           const u32 (&lim)[CT], AttnAcc<HD, CT>& a) {
+  const u32 lane = threadIdx.x & 63, lg = lane >> 4;
+  const bf16x8_t (&ka)[HD / 32] = kv.ka;
+  const short4_t (&vb)[HD / 16] = kv.vb;
 #pragma unroll
   for (int c = 0; c < CT; ++c) {
     floatx4_t s4 = floatx4_t{0.f, 0.f, 0.f, 0.f};
@@ -94,7 +105,7 @@ struct AttnMfmaShared {
 
 // ---- decode: one workgroup per (sequence, kv head); the four waves take the KV blocks round-robin ----------------
 template <int HD>
-__device__ void attn_decode(const DevCtx& c, u32 layer, AttnMfmaShared& sh, u32 wg, u32 nwg) {
+__device__ __forceinline__ void attn_decode(const DevCtx& c, u32 layer, AttnMfmaShared& sh, u32 wg, u32 nwg) {
   const u32 B = c.meta->n_seqs, G = c.nq / c.nkv;
   const u32 lane = threadIdx.x & 63, w = threadIdx.x >> 6, lg = lane >> 4, lc = lane & 15;
   const bf16_t* Kc = (const bf16_t*)c.kv + (u64)layer * c.kv_layer_stride;
@@ -116,9 +127,23 @@ __device__ void attn_decode(const DevCtx& c, u32 layer, AttnMfmaShared& sh, u32 
     attn_init(acc);
     const u32 lim[1] = {ctx};
     const u32 nb = (ctx + 15) / 16;
-    for (u32 jb = w; jb < nb; jb += 4) {
-      const u64 base = ((u64)bt[jb] * c.nkv + g) * tile;
-      attn_block<HD, 1>(Kc + base, Vc + base, q, jb * 16, lim, acc);
+    // software pipeline: three KV blocks of this wave (blocks w, w+4, ...) are in flight at any time; the tiles
+    // rotate by code position (no register copies). Block ids are fetched 64 at a time, one per lane.
+    const u32 nmine = nb > w ? (nb - w + 3) / 4 : 0;       // blocks of this wave
+    KVTile<HD> t0, t1, t2;
+    u32 ids = 0;
+    for (u32 base_it = 0; base_it < nmine; base_it += 63) {   // 63 = multiple of the pipeline depth within one id batch
+      const u32 mine = w + 4 * (base_it + lane);
+      ids = mine < nb ? bt[mine] : 0u;
+      const u32 lim_it = min(nmine - base_it, 63u);
+      auto ld = [&](KVTile<HD>& tl, u32 j) { if (j < lim_it) { const u64 bs = ((u64)__shfl(ids, j) * c.nkv + g) * tile; kv_load<HD>(Kc + bs, Vc + bs, tl); } };
+      auto us = [&](const KVTile<HD>& tl, u32 j) { if (j < lim_it) attn_block<HD, 1>(tl, q, (w + 4 * (base_it + j)) * 16, lim, acc); };
+      ld(t0, 0); ld(t1, 1); ld(t2, 2);
+      for (u32 j = 0; j < lim_it; j += 3) {
+        us(t0, j); ld(t0, j + 3);
+        us(t1, j + 1); ld(t1, j + 4);
+        us(t2, j + 2); ld(t2, j + 5);
+      }
     }
     __syncthreads();   // the previous item's combine has finished reading LDS
     if (lg == 0) { sh.m[w][lc] = acc.m[0]; sh.l[w][lc] = acc.l[0]; }
@@ -144,7 +169,7 @@ __device__ void attn_decode(const DevCtx& c, u32 layer, AttnMfmaShared& sh, u32 
 
 // ---- prefill: one wave per (sequence, kv head, head group, tile of 16 query positions) -----------------------------
 template <int HD, int CT>
-__device__ void attn_prefill(const DevCtx& c, u32 layer, u32 wg, u32 nwg) {
+__device__ __forceinline__ void attn_prefill(const DevCtx& c, u32 layer, u32 wg, u32 nwg) {
   const u32 B = c.meta->n_seqs, G = c.nq / c.nkv, groups = G / CT;
   const u32 lane = threadIdx.x & 63, w = threadIdx.x >> 6, lg = lane >> 4, lc = lane & 15;
   const bf16_t* Kc = (const bf16_t*)c.kv + (u64)layer * c.kv_layer_stride;
@@ -178,9 +203,18 @@ __device__ void attn_prefill(const DevCtx& c, u32 layer, u32 wg, u32 nwg) {
     AttnAcc<HD, CT> acc;
     attn_init(acc);
     const u32 last = min(p0 + 15, P - 1) / 16;
+    KVTile<HD> cur, nxt;
+    {
+      const u64 base = ((u64)bt[0] * c.nkv + g) * tile;
+      kv_load<HD>(Kc + base, Vc + base, cur);
+    }
     for (u32 jb = 0; jb <= last; ++jb) {
-      const u64 base = ((u64)bt[jb] * c.nkv + g) * tile;
-      attn_block<HD, CT>(Kc + base, Vc + base, q, jb * 16, lim, acc);
+      if (jb < last) {
+        const u64 base = ((u64)bt[jb + 1] * c.nkv + g) * tile;
+        kv_load<HD>(Kc + base, Vc + base, nxt);
+      }
+      attn_block<HD, CT>(cur, q, jb * 16, lim, acc);
+      cur = nxt;
     }
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) {
@@ -214,7 +248,7 @@ __device__ __forceinline__ void attn_prefill_hd(const DevCtx& c, u32 layer, u32 
   }
 }
 
-__device__ void phase_attention_mfma(const DevCtx& c, u32 layer, AttnMfmaShared& sh, u32 wg, u32 nwg) {
+__device__ __forceinline__ void phase_attention_mfma(const DevCtx& c, u32 layer, AttnMfmaShared& sh, u32 wg, u32 nwg) {
   if (c.meta->kind == 2u) {
     if (c.hd == 64) attn_decode<64>(c, layer, sh, wg, nwg); else attn_decode<128>(c, layer, sh, wg, nwg);
   } else {

@@ -26,8 +26,8 @@ __global__ void __launch_bounds__(BLK_THREADS) k_sched(DevCtx c) {
 // one named kernel per phase so that profiles attribute time to the step of the forward pass
 #define PHASE_KERNEL(name, PH)                                                   \
   __global__ void __launch_bounds__(BLK_THREADS) name(DevCtx c, u32 layer) {     \
-    __shared__ PhaseShared sh;                                                   \
-    run_phase(c, PH, layer, sh, blockIdx.x, gridDim.x);                          \
+    __shared__ PhaseSharedOf<PH>::type sh;                                       \
+    run_phase(c, PH, layer, &sh, blockIdx.x, gridDim.x);                         \
   }
 PHASE_KERNEL(k_embed, PH_EMBED)
 PHASE_KERNEL(k_norm1, PH_NORM1)

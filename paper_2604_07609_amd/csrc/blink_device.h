@@ -184,7 +184,7 @@ struct DevCtx {
   bf16_t* aq;           // packed attention output, inner dimension nq*hd
   bf16_t* qbuf;         // [maxT][nq][hd] rotated queries scaled by 1/sqrt(hd)
   bf16_t* hq;           // packed silu(gate)*up, inner dimension F
-  float* ssq;           // [d/16][TBS*16] partial sums of squares of the residual stream
+  float* ssq;           // [token][d/16] partial sums of squares of the residual stream
   u32 TBS;              // token-block stride of the packed activation buffers
   u32 pad1;
 };

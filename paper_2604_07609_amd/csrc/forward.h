@@ -61,7 +61,7 @@ __device__ __forceinline__ u64 packed_act_off(u32 t, u32 k, u32 TBS) {   // same
 
 // ---- embedding gather: x[t] = E[input_ids[t]] ---------------------------------------------------------------
 template <typename WT>
-__device__ void phase_embed(const DevCtx& c, u32 wg, u32 nwg) {
+__device__ __forceinline__ void phase_embed(const DevCtx& c, u32 wg, u32 nwg) {
   const u32 T = c.meta->n_tokens, d = c.d;
   const WT* E = (const WT*)c.embed;
   const u32 per_row = d / 8;
@@ -77,7 +77,7 @@ __device__ void phase_embed(const DevCtx& c, u32 wg, u32 nwg) {
 
 // ---- embedding gather of the bf16 path: residual stream, packed operand of the first GEMM (x * g1 of layer 0)
 // and the partial sums of squares its RMSNorm needs; one thread per (token, 16 columns) --------------------------
-__device__ void phase_embed_packed(const DevCtx& c, u32 wg, u32 nwg) {
+__device__ __forceinline__ void phase_embed_packed(const DevCtx& c, u32 wg, u32 nwg) {
   const u32 T = c.meta->n_tokens, d = c.d, per_row = d / 16;
   const bf16_t* E = (const bf16_t*)c.embed;
   const float* g = c.layers[0].g1;
@@ -101,13 +101,13 @@ __device__ void phase_embed_packed(const DevCtx& c, u32 wg, u32 nwg) {
       }
       *(uint4*)(c.xq + packed_act_off(t, k0 + 8 * h, c.TBS)) = make_uint4(w[0], w[1], w[2], w[3]);
     }
-    c.ssq[(u64)nt * (c.TBS * 16) + t] = ss;
+    c.ssq[(u64)t * per_row + nt] = ss;
   }
 }
 
 // ---- RMSNorm: out[r] = in[row(r)] * g / sqrt(mean(in^2) + eps); one workgroup per row -------------------------
 // rows == nullptr: row(r) = r, n_rows = n_tokens; else row(r) = rows[r], n_rows = n_seqs (last positions).
-__device__ void phase_rmsnorm(const DevCtx& c, const float* in, const float* g, float* out, const u32* rows, float* red,
+__device__ __forceinline__ void phase_rmsnorm(const DevCtx& c, const float* in, const float* g, float* out, const u32* rows, float* red,
                               u32 wg, u32 nwg) {
   const u32 n = rows ? c.meta->n_seqs : c.meta->n_tokens, d = c.d;
   for (u32 r = wg; r < n; r += nwg) {
@@ -135,7 +135,7 @@ struct GemmShared {
 };
 
 template <typename WT, int AMODE, int EMODE>
-__device__ void phase_gemm(const float* A, u32 lda, const WT* W, float* out, u32 ldo, u32 T, u32 N, u32 K, GemmShared& sh,
+__device__ __forceinline__ void phase_gemm(const float* A, u32 lda, const WT* W, float* out, u32 ldo, u32 T, u32 N, u32 K, GemmShared& sh,
                            u32 wg, u32 nwg) {
   const u32 tid = threadIdx.x;
   const u32 mt = (T + G_BM - 1) / G_BM, nt = (N + G_BN - 1) / G_BN;
@@ -194,7 +194,7 @@ __device__ void phase_gemm(const float* A, u32 lda, const WT* W, float* out, u32
 
 // ---- rotary embedding on q and k (rotate-half pairing), K/V write through the slot mapping --------------------
 template <typename WT>
-__device__ void phase_rope_kvwrite(const DevCtx& c, u32 layer, u32 wg, u32 nwg) {
+__device__ __forceinline__ void phase_rope_kvwrite(const DevCtx& c, u32 layer, u32 wg, u32 nwg) {
   const u32 T = c.meta->n_tokens, hd = c.hd, half = hd / 2, nh = c.nq + 2 * c.nkv;
   WT* Kc = (WT*)c.kv + (u64)layer * c.kv_layer_stride;
   WT* Vc = Kc + c.kv_kv_stride;
@@ -234,7 +234,7 @@ struct AttnShared {
 };
 
 template <typename WT, bool PACKED_OUT>
-__device__ void phase_attention(const DevCtx& c, u32 layer, AttnShared& sh, u32 wg, u32 nwg) {
+__device__ __forceinline__ void phase_attention(const DevCtx& c, u32 layer, AttnShared& sh, u32 wg, u32 nwg) {
   const u32 T = c.meta->n_tokens, hd = c.hd, G = c.nq / c.nkv, tid = threadIdx.x;
   const WT* Kc = (const WT*)c.kv + (u64)layer * c.kv_layer_stride;
   const WT* Vc = Kc + c.kv_kv_stride;

@@ -33,7 +33,7 @@ struct MfmaGemmArgs {
   u32 T;                   // tokens (columns)
   u32 TBS;                 // token-block stride of every packed activation buffer
   const u32* tok_index;    // optional indirection: column t reads token tok_index[t] of Xp / ssq_in (LM head)
-  const float* ssq_in;     // [K/16][TBS*16] partial sums of squares of the un-normalised input (null: no scaling)
+  const float* ssq_in;     // [token][K/16] partial sums of squares of the un-normalised input (null: no scaling)
   float eps;
   // EPI_SCALED_STORE
   float* out; u32 ldo;
@@ -41,12 +41,17 @@ struct MfmaGemmArgs {
   float* x; u32 ldx;       // residual stream, updated in place
   const float* g_next;     // gain of the RMSNorm that consumes x next
   bf16_t* Xp_next;         // packed bf16(x * g_next), inner dimension N
-  float* ssq_out;          // [N/16][TBS*16]
+  float* ssq_out;          // [token][N/16]
   // EPI_SILU_GATE
   bf16_t* Hp;              // packed activations with inner dimension N/2
   // EPI_QKV_ROPE
-  const DevCtx* ctx;
-  u32 layer;
+  const i32* positions;
+  const i32* slot_mapping;
+  const float2* rope_tab;
+  bf16_t* qbuf;
+  bf16_t* Kc;              // this layer's K cache and V cache
+  bf16_t* Vc;
+  u32 nq, nkv, hd, bs;
 };
 
 struct MfmaShared {
@@ -70,14 +75,26 @@ __device__ __forceinline__ void compute_rstd(const MfmaGemmArgs& a, u32 t0, u32 
   if (a.ssq_in == nullptr) {
     if (tid < 128) sh.rstd[tid] = 1.0f;
   } else {
-    // 256 threads: two threads per token for 128 tokens (or up to four for 64): fixed-order split of the partials
+    // 256 threads: two threads per token for 128 tokens (or four for 64): each sums a contiguous run of the
+    // token's partials with 16-byte loads (K/16 is a multiple of 2; runs are multiples of 4 when K % 256 == 0)
     const u32 parts = count <= 64 ? 4u : 2u, span = BLK_THREADS / parts;
     const u32 tl = tid % span, part = tid / span;
     float s = 0.f;
     const u32 np = a.K / 16;
     if (tl < count && t0 + tl < a.T) {
       const u32 tok = a.tok_index ? a.tok_index[t0 + tl] : t0 + tl;
-      for (u32 p = part; p < np; p += parts) s += a.ssq_in[(u64)p * (a.TBS * 16) + tok];
+      const float* pp = a.ssq_in + (u64)tok * np;
+      const u32 lo = np * part / parts, hi = np * (part + 1) / parts;
+      if (((lo | hi) & 3u) == 0) {
+        float4 acc4 = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (u32 p = lo; p < hi; p += 4) {
+          const float4 v = *(const float4*)(pp + p);
+          acc4.x += v.x; acc4.y += v.y; acc4.z += v.z; acc4.w += v.w;
+        }
+        s = (acc4.x + acc4.y) + (acc4.z + acc4.w);
+      } else {
+        for (u32 p = lo; p < hi; ++p) s += pp[p];
+      }
     }
     float* scratch = &sh.red[0][0][0][0];
     scratch[part * span + tl] = s;
@@ -124,38 +141,35 @@ __device__ __forceinline__ void epilogue_tile(const MfmaGemmArgs& a, floatx4_t a
     float s = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
     s += __shfl_xor(s, 16);
     s += __shfl_xor(s, 32);
-    if (lane < 16 && tv) a.ssq_out[(u64)nt * (a.TBS * 16) + t] = s;
+    if (lane < 16 && tv) a.ssq_out[(u64)t * (a.N / 16) + nt] = s;
   } else if (EPI == EPI_QKV_ROPE) {
     if (!tv) return;
-    const DevCtx& c = *a.ctx;
     const float r = rstd16[lane & 15];
-    const u32 hd = c.hd, half = hd / 2, head = n0 / hd, p = (n0 % hd) >> 1;   // rows: (p, p+half, p+1, p+1+half)
+    const u32 hd = a.hd, half = hd / 2, head = n0 / hd, p = (n0 % hd) >> 1;   // rows: (p, p+half, p+1, p+1+half)
     float lo0 = acc[0] * r, hi0 = acc[1] * r, lo1 = acc[2] * r, hi1 = acc[3] * r;
-    if (head < c.nq + c.nkv) {
-      const float2* rt = c.rope_tab + (u64)c.positions[t] * half + p;
-      const float2 cs0 = rt[0], cs1 = rt[1];
-      const float a0 = lo0 * cs0.x - hi0 * cs0.y, b0 = hi0 * cs0.x + lo0 * cs0.y;
-      const float a1 = lo1 * cs1.x - hi1 * cs1.y, b1 = hi1 * cs1.x + lo1 * cs1.y;
+    if (head < a.nq + a.nkv) {
+      const float4 cs = *(const float4*)(a.rope_tab + (u64)a.positions[t] * half + p);   // (cos,sin) of pairs p, p+1
+      const float a0 = lo0 * cs.x - hi0 * cs.y, b0 = hi0 * cs.x + lo0 * cs.y;
+      const float a1 = lo1 * cs.z - hi1 * cs.w, b1 = hi1 * cs.z + lo1 * cs.w;
       lo0 = a0; hi0 = b0; lo1 = a1; hi1 = b1;
     }
-    if (head < c.nq) {
+    if (head < a.nq) {
       const float sc = 1.0f / sqrtf((float)hd);
-      bf16_t* q = c.qbuf + ((u64)t * c.nq + head) * hd;
+      bf16_t* q = a.qbuf + ((u64)t * a.nq + head) * hd;
       *(u32*)(q + p) = (u32)f32_to_bf16(lo0 * sc) | ((u32)f32_to_bf16(lo1 * sc) << 16);
       *(u32*)(q + half + p) = (u32)f32_to_bf16(hi0 * sc) | ((u32)f32_to_bf16(hi1 * sc) << 16);
     } else {
-      const u32 slot = (u32)c.slot_mapping[t];
-      bf16_t* Kc = (bf16_t*)c.kv + (u64)a.layer * c.kv_layer_stride;
-      if (head < c.nq + c.nkv) {
-        bf16_t* k = Kc + (((u64)(slot / c.bs) * c.nkv + (head - c.nq)) * c.bs + slot % c.bs) * hd;
+      const u32 slot = (u32)a.slot_mapping[t];
+      if (head < a.nq + a.nkv) {
+        bf16_t* k = a.Kc + (((u64)(slot / a.bs) * a.nkv + (head - a.nq)) * a.bs + slot % a.bs) * hd;
         *(u32*)(k + p) = (u32)f32_to_bf16(lo0) | ((u32)f32_to_bf16(lo1) << 16);
         *(u32*)(k + half + p) = (u32)f32_to_bf16(hi0) | ((u32)f32_to_bf16(hi1) << 16);
       } else {   // V is kept dimension-major inside a block: [hd][16 tokens]
-        bf16_t* v = Kc + c.kv_kv_stride + ((u64)(slot / c.bs) * c.nkv + (head - c.nq - c.nkv)) * c.bs * hd + slot % c.bs;
-        v[(u64)p * c.bs] = f32_to_bf16(lo0);
-        v[(u64)(p + 1) * c.bs] = f32_to_bf16(lo1);
-        v[(u64)(half + p) * c.bs] = f32_to_bf16(hi0);
-        v[(u64)(half + p + 1) * c.bs] = f32_to_bf16(hi1);
+        bf16_t* v = a.Vc + ((u64)(slot / a.bs) * a.nkv + (head - a.nq - a.nkv)) * a.bs * hd + slot % a.bs;
+        v[(u64)p * a.bs] = f32_to_bf16(lo0);
+        v[(u64)(p + 1) * a.bs] = f32_to_bf16(lo1);
+        v[(u64)(half + p) * a.bs] = f32_to_bf16(hi0);
+        v[(u64)(half + p + 1) * a.bs] = f32_to_bf16(hi1);
       }
     }
   } else {  // EPI_SILU_GATE
@@ -169,12 +183,28 @@ __device__ __forceinline__ void epilogue_tile(const MfmaGemmArgs& a, floatx4_t a
 }
 
 // ---- stream schedule: T <= 64 ------------------------------------------------------------------------------------
+// Weight loads bypass temporal caching: every weight byte is used once per launch, while the activation operand
+// is re-read by every workgroup and should stay in L2.
+__device__ __forceinline__ bf16x8_t ld_tile_stream(const bf16_t* p) {
+  typedef u32 u32x4_t __attribute__((ext_vector_type(4)));
+  const u32x4_t v = __builtin_nontemporal_load((const u32x4_t*)p);
+  return *(const bf16x8_t*)&v;
+}
+
+template <int U, int TW>
+struct StreamBuf {
+  bf16x8_t w[U];
+  bf16x8_t x[U][TW];
+};
+
 template <int EPI, int TW>
 __device__ __forceinline__ void gemm_stream(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg) {
+  constexpr int U = TW == 1 ? 8 : (TW == 2 ? 6 : 4);   // k-tiles per batch of loads
   const u32 lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const u32 NT = (a.N + 15) / 16, KT = a.K / 32;
   const u32 kb = (u32)((u64)KT * w / 4), ke = (u32)((u64)KT * (w + 1) / 4);
-  compute_rstd(a, 0, 64, sh);
+  const u32 nbatch = (ke - kb + U - 1) / U;
+  if (wg >= NT) return;
   // per-lane offsets (in elements) of this lane's 16 bytes inside the token blocks of one k-tile
   u32 xoff[TW];
 #pragma unroll
@@ -184,32 +214,40 @@ __device__ __forceinline__ void gemm_stream(const MfmaGemmArgs& a, MfmaShared& s
     xoff[tw] = ((tok >> 4) * 64 + (tok & 15) + 16 * (lane >> 4)) * 8;
   }
   const u64 xk_stride = (u64)a.TBS * 512;
-  for (u32 nt = wg; nt < NT; nt += nwg) {
-    floatx4_t acc[TW];
-#pragma unroll
-    for (int tw = 0; tw < TW; ++tw) acc[tw] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+  const bf16x8_t zero = {0, 0, 0, 0, 0, 0, 0, 0};
+  auto issue = [&](StreamBuf<U, TW>& b, u32 nt, u32 kt0) {
     const bf16_t* wp = a.Wp + ((u64)nt * KT) * 512 + lane * 8;
-    u32 kt = kb;
-    for (; kt + 8 <= ke; kt += 8) {
-      bf16x8_t wv[8], xv[8][TW];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) wv[u] = ld_tile(wp + (u64)(kt + u) * 512);
+    for (int u = 0; u < U; ++u) {
+      const u32 kt = kt0 + u;
+      const bool ok = kt < ke;
+      b.w[u] = ok ? ld_tile_stream(wp + (u64)kt * 512) : zero;
 #pragma unroll
-      for (int u = 0; u < 8; ++u)
-#pragma unroll
-        for (int tw = 0; tw < TW; ++tw) xv[u][tw] = ld_tile(a.Xp + (u64)(kt + u) * xk_stride + xoff[tw]);
-#pragma unroll
-      for (int u = 0; u < 8; ++u)
-#pragma unroll
-        for (int tw = 0; tw < TW; ++tw) acc[tw] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv[u], xv[u][tw], acc[tw], 0, 0, 0);
+      for (int tw = 0; tw < TW; ++tw) b.x[u][tw] = ok ? ld_tile(a.Xp + (u64)kt * xk_stride + xoff[tw]) : zero;
     }
-    for (; kt < ke; ++kt) {
-      const bf16x8_t wv = ld_tile(wp + (u64)kt * 512);
+  };
+  // Software pipeline over the flat sequence of (tile, batch) steps of this workgroup: while one buffer is consumed
+  // by the MFMAs, the loads of the following step (possibly the first batch of the next tile) fill the other.
+  // The two buffers swap roles by code position (no register copies, which would wait for the loads in flight).
+  StreamBuf<U, TW> bufA, bufB;
+  u32 nt = wg, b = 0;
+  floatx4_t acc[TW];
 #pragma unroll
-      for (int tw = 0; tw < TW; ++tw)
-        acc[tw] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv, ld_tile(a.Xp + (u64)kt * xk_stride + xoff[tw]), acc[tw], 0, 0, 0);
+  for (int tw = 0; tw < TW; ++tw) acc[tw] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+  issue(bufA, nt, kb);               // the first loads are in flight while the norm scales are computed
+  compute_rstd(a, 0, 64, sh);
+  auto step = [&](StreamBuf<U, TW>& use, StreamBuf<U, TW>& fill) -> bool {
+    const bool last = b + 1 >= nbatch;
+    const u32 nnt = last ? nt + nwg : nt;
+    if (nnt < NT) issue(fill, nnt, last ? kb : kb + (b + 1) * U);
+    if (b < nbatch) {
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int tw = 0; tw < TW; ++tw) acc[tw] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(use.w[u], use.x[u][tw], acc[tw], 0, 0, 0);
     }
-    __syncthreads();   // previous tile's reduction has been read
+    if (!last) { ++b; return true; }
+    __syncthreads();   // the previous tile's reduction has been read
 #pragma unroll
     for (int tw = 0; tw < TW; ++tw) *(floatx4_t*)&sh.red[w][tw][lane][0] = acc[tw];
     __syncthreads();
@@ -218,6 +256,15 @@ __device__ __forceinline__ void gemm_stream(const MfmaGemmArgs& a, MfmaShared& s
                           (*(floatx4_t*)&sh.red[2][w][lane][0] + *(floatx4_t*)&sh.red[3][w][lane][0]);
       epilogue_tile<EPI>(a, s, nt, w * 16, &sh.rstd[w * 16]);
     }
+#pragma unroll
+    for (int tw = 0; tw < TW; ++tw) acc[tw] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+    nt = nnt;
+    b = 0;
+    return nt < NT;
+  };
+  for (;;) {
+    if (!step(bufA, bufB)) break;
+    if (!step(bufB, bufA)) break;
   }
 }
 
@@ -271,7 +318,7 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& a, MfmaShared& sh,
 }
 
 template <int EPI>
-__device__ void gemm_mfma(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg) {
+__device__ __forceinline__ void gemm_mfma(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg) {
   if (a.T == 0) return;
   if (a.T <= 16) gemm_stream<EPI, 1>(a, sh, wg, nwg);
   else if (a.T <= 32) gemm_stream<EPI, 2>(a, sh, wg, nwg);

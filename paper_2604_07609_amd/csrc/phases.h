@@ -17,8 +17,9 @@ enum {
 #define PH_LAYER_FIRST PH_NORM1
 #define PH_LAYER_LAST PH_DOWN
 
+// LDS of a phase kernel: the union of what the fp32 and the bf16 variant of that phase need (kept per phase so
+// that the GEMM kernels are not charged the attention kernels' LDS and keep their occupancy)
 union PhaseShared {
-  SchedShared sched;
   GemmShared gemm;
   AttnShared attn;
   MfmaShared mfma;
@@ -26,9 +27,21 @@ union PhaseShared {
   SamplerShared sampler;
   float red[8];
 };
+union GemmPhaseShared { GemmShared gemm; MfmaShared mfma; };
+union AttnPhaseShared { AttnShared attn; AttnMfmaShared attn_mfma; };
+union SmallPhaseShared { float red[8]; };
+template <int PH> struct PhaseSharedOf { typedef GemmPhaseShared type; };
+template <> struct PhaseSharedOf<PH_ATTN> { typedef AttnPhaseShared type; };
+template <> struct PhaseSharedOf<PH_SAMPLE> { typedef SamplerShared type; };
+template <> struct PhaseSharedOf<PH_EMBED> { typedef SmallPhaseShared type; };
+template <> struct PhaseSharedOf<PH_NORM1> { typedef SmallPhaseShared type; };
+template <> struct PhaseSharedOf<PH_NORM2> { typedef SmallPhaseShared type; };
+template <> struct PhaseSharedOf<PH_FINAL_NORM> { typedef SmallPhaseShared type; };
+template <> struct PhaseSharedOf<PH_ROPE> { typedef SmallPhaseShared type; };
 
 template <typename WT>
-__device__ __forceinline__ void run_phase_t(const DevCtx& c, int ph, u32 layer, PhaseShared& sh, u32 wg, u32 nwg) {
+__device__ __forceinline__ void run_phase_t(const DevCtx& c, int ph, u32 layer, void* shp, u32 wg, u32 nwg) {
+  PhaseShared& sh = *(PhaseShared*)shp;   // only the member that belongs to phase `ph` is touched
   const IterMeta* m = c.meta;
   const u32 T = m->n_tokens, B = m->n_seqs;
   const LayerW* L = c.layers + layer;
@@ -54,13 +67,14 @@ __device__ __forceinline__ void run_phase_t(const DevCtx& c, int ph, u32 layer, 
     case PH_LM_HEAD:
       phase_gemm<WT, GA_PLAIN, GE_STORE>(c.hlast, c.d, (const WT*)c.lm, c.logits, c.V, B, c.V, c.d, sh.gemm, wg, nwg);
       break;
-    case PH_SAMPLE: phase_sample_publish(c, sh.sampler, wg, nwg); break;
+    case PH_SAMPLE: phase_sample_publish(c, *(SamplerShared*)shp, wg, nwg); break;
   }
 }
 
 // bf16 path: MFMA GEMMs on packed operands with the norms, the residual adds and the SiLU gate fused into their
 // epilogues; the separate norm phases do not exist here.
-__device__ __forceinline__ void run_phase_bf16(const DevCtx& c, int ph, u32 layer, PhaseShared& sh, u32 wg, u32 nwg) {
+__device__ __forceinline__ void run_phase_bf16(const DevCtx& c, int ph, u32 layer, void* shp, u32 wg, u32 nwg) {
+  PhaseShared& sh = *(PhaseShared*)shp;
   const IterMeta* m = c.meta;
   const LayerWP* P = c.players + layer;
   MfmaGemmArgs a{};
@@ -70,7 +84,10 @@ __device__ __forceinline__ void run_phase_bf16(const DevCtx& c, int ph, u32 laye
   switch (ph) {
     case PH_EMBED: phase_embed_packed(c, wg, nwg); break;
     case PH_QKV:
-      a.Wp = P->wqkv; a.Xp = c.xq; a.N = c.qkv_n; a.K = c.d; a.ssq_in = c.ssq; a.ctx = &c; a.layer = layer;
+      a.Wp = P->wqkv; a.Xp = c.xq; a.N = c.qkv_n; a.K = c.d; a.ssq_in = c.ssq;
+      a.positions = c.positions; a.slot_mapping = c.slot_mapping; a.rope_tab = c.rope_tab; a.qbuf = c.qbuf;
+      a.Kc = (bf16_t*)c.kv + (u64)layer * c.kv_layer_stride; a.Vc = a.Kc + c.kv_kv_stride;
+      a.nq = c.nq; a.nkv = c.nkv; a.hd = c.hd; a.bs = c.bs;
       gemm_mfma<EPI_QKV_ROPE>(a, sh.mfma, wg, nwg);
       break;
     case PH_ATTN: phase_attention_mfma(c, layer, sh.attn_mfma, wg, nwg); break;
@@ -94,12 +111,12 @@ __device__ __forceinline__ void run_phase_bf16(const DevCtx& c, int ph, u32 laye
       a.out = c.logits; a.ldo = c.V;
       gemm_mfma<EPI_SCALED_STORE>(a, sh.mfma, wg, nwg);
       break;
-    case PH_SAMPLE: phase_sample_publish(c, sh.sampler, wg, nwg); break;
+    case PH_SAMPLE: phase_sample_publish(c, *(SamplerShared*)shp, wg, nwg); break;
     default: break;   // the norms and the rotary / KV-write step are fused into the GEMMs
   }
 }
 
-__device__ __forceinline__ void run_phase(const DevCtx& c, int ph, u32 layer, PhaseShared& sh, u32 wg, u32 nwg) {
+__device__ __forceinline__ void run_phase(const DevCtx& c, int ph, u32 layer, void* sh, u32 wg, u32 nwg) {
   if (c.meta->skip || c.meta->kind == KIND_IDLE) return;
   if (c.dtype == 1) run_phase_bf16(c, ph, layer, sh, wg, nwg);
   else run_phase_t<float>(c, ph, layer, sh, wg, nwg);

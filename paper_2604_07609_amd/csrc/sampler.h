@@ -27,6 +27,29 @@ __device__ __forceinline__ float key_to_float(u32 k) {
   return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
 }
 
+// Visits every element of a logits row once: f(value, index). 16-byte loads, eight in flight per thread.
+template <typename F>
+__device__ __forceinline__ void scan_row(const float* row, u32 V, F f) {
+  const u32 tid = threadIdx.x;
+  if ((V & 3u) == 0 && ((size_t)row & 15u) == 0) {
+    for (u32 c0 = 0; c0 < V; c0 += BLK_THREADS * 32) {
+      float4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const u32 idx = c0 + u * (BLK_THREADS * 4) + tid * 4;
+        v[u] = idx < V ? *(const float4*)(row + idx) : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const u32 idx = c0 + u * (BLK_THREADS * 4) + tid * 4;
+        if (idx < V) { f(v[u].x, idx); f(v[u].y, idx + 1); f(v[u].z, idx + 2); f(v[u].w, idx + 3); }
+      }
+    }
+  } else {
+    for (u32 i = tid; i < V; i += BLK_THREADS) f(row[i], i);
+  }
+}
+
 // Philox4x32-10 (Salmon et al., SC'11): returns the first output word.
 __device__ __forceinline__ u32 philox4x32_10_first(u32 c0, u32 c1, u32 c2, u32 c3, u32 k0, u32 k1) {
 #pragma unroll
@@ -64,10 +87,10 @@ __device__ __forceinline__ void radix_digit(const float* row, u32 V, int shift, 
   sh.hist[tid] = 0;
   __syncthreads();
   const unsigned long long himask = shift + 8 >= 64 ? 0ull : (~0ull << (shift + 8));
-  for (u32 i = tid; i < V; i += BLK_THREADS) {
-    const unsigned long long key = ((unsigned long long)order_key(row[i]) << 32) | (u32)~i;
+  scan_row(row, V, [&](float val, u32 i) {
+    const unsigned long long key = ((unsigned long long)order_key(val) << 32) | (u32)~i;
     if ((key & himask) == (prefix & himask)) atomicAdd(&sh.hist[(u32)(key >> shift) & 255u], 1u);
-  }
+  });
   __syncthreads();
   if (tid == 0) {
     u32 rem = k_rem, digit = 0;
@@ -84,7 +107,106 @@ __device__ __forceinline__ void radix_digit(const float* row, u32 V, int shift, 
   k_rem = sh.misc[1];
 }
 
-__device__ void phase_sample_publish(const DevCtx& c, SamplerShared& sh, u32 wg, u32 nwg) {
+// Bitonic sort of n (a power of two) 64-bit keys in LDS, descending; all 256 threads.
+__device__ __forceinline__ void bitonic_sort_desc(unsigned long long* v, u32 n) {
+  const u32 tid = threadIdx.x;
+  for (u32 size = 2; size <= n; size <<= 1) {
+    for (u32 stride = size >> 1; stride > 0; stride >>= 1) {
+      for (u32 i = tid; i < n / 2; i += BLK_THREADS) {
+        const u32 lo = (i / stride) * stride * 2 + (i % stride), hi = lo + stride;
+        const bool desc = ((lo & size) == 0);
+        const unsigned long long a = v[lo], b = v[hi];
+        if ((a < b) == desc) { v[lo] = b; v[hi] = a; }
+      }
+      __syncthreads();
+    }
+  }
+}
+
+// Leaves the k largest composite keys (order_key(logit) << 32 | ~id) of the row in sh.cand[0..k), descending, the
+// rest of sh.cand[0..npow) holding smaller keys or zero padding. Returns npow (a power of two >= k).
+__device__ __forceinline__ u32 select_top_k(const float* row, u32 V, u32 k, SamplerShared& sh) {
+  const u32 tid = threadIdx.x;
+  // (1) One pass: every thread keeps the four largest keys among the elements it visits and the largest key it
+  // dropped. The 1024 kept keys are sorted; their k-th largest is the exact threshold unless some thread dropped
+  // a key at or above it.
+  if (k <= 256) {
+    unsigned long long k0 = 0, k1 = 0, k2 = 0, k3 = 0, dropped = 0;
+    scan_row(row, V, [&](float val, u32 i) {
+      const unsigned long long key = ((unsigned long long)order_key(val) << 32) | (u32)~i;
+      if (key > k3) {
+        dropped = k3 > dropped ? k3 : dropped;
+        if (key > k0) { k3 = k2; k2 = k1; k1 = k0; k0 = key; }
+        else if (key > k1) { k3 = k2; k2 = k1; k1 = key; }
+        else if (key > k2) { k3 = k2; k2 = key; }
+        else k3 = key;
+      } else {
+        dropped = key > dropped ? key : dropped;
+      }
+    });
+    __syncthreads();
+    sh.cand[tid * 4] = k0; sh.cand[tid * 4 + 1] = k1; sh.cand[tid * 4 + 2] = k2; sh.cand[tid * 4 + 3] = k3;
+    __syncthreads();
+    bitonic_sort_desc(sh.cand, SAMPLER_MAX_K);
+    const unsigned long long thr = sh.cand[k - 1];
+    const unsigned long long worst = block_max_u64(dropped, sh.red64);
+    if (worst < thr) return SAMPLER_MAX_K;
+  }
+  // (2) Counting search for a key `lo` with k <= f(lo) <= SAMPLER_MAX_K, f(p) = #{key >= p} (non-increasing in p):
+  // start at the row maximum, double the distance below it until k keys are covered, bisect if too many are.
+  u32 kmax = 0;
+  scan_row(row, V, [&](float val, u32) { kmax = max(kmax, order_key(val)); });
+  kmax = block_max(kmax, sh.misc);
+  u32 lo = 0, cnt = 0;
+  bool found = false;
+  {
+    u32 few = kmax, many = 0, step = 1u << 18;   // `few`: a probe with f < k; `many`: one with f > SAMPLER_MAX_K
+    bool have_many = false, few_is_open = true;
+    for (int pass = 0; pass < 64 && !found; ++pass) {
+      u32 probe;
+      if (pass == 0) probe = kmax;
+      else if (!have_many) { probe = few > step ? few - step : 0u; step = step < (1u << 30) ? step << 1 : step; }
+      else { if (few - many <= 1) break; probe = many + (few - many) / 2; }
+      u32 local = 0;
+      scan_row(row, V, [&](float val, u32) { local += order_key(val) >= probe ? 1u : 0u; });
+      u32 total;
+      block_excl_scan(local, total, sh.misc);
+      if (total < k) { few = probe; few_is_open = false; if (probe == 0) break; }
+      else if (total <= SAMPLER_MAX_K) { lo = probe; cnt = total; found = true; }
+      else { many = probe; have_many = true; if (few_is_open) break; }
+    }
+  }
+  unsigned long long prefix;
+  if (found) {
+    prefix = (unsigned long long)lo << 32;      // every (key, id) with key >= lo is a candidate
+  } else {                                      // (3) massive ties: exact radix select on the composite key
+    prefix = 0;
+    u32 k_rem = k;
+    for (int shift = 56; shift >= 32; shift -= 8) radix_digit(row, V, shift, prefix, k_rem, sh);
+    prefix |= 0xFF000000ull;                    // ids are below 2^24: the top byte of ~id is 0xFF for every item
+    for (int shift = 16; shift >= 0; shift -= 8) radix_digit(row, V, shift, prefix, k_rem, sh);
+    cnt = k;
+  }
+  __syncthreads();
+  if (tid == 0) sh.misc[2] = 0;
+  __syncthreads();
+  scan_row(row, V, [&](float val, u32 i) {
+    const unsigned long long key = ((unsigned long long)order_key(val) << 32) | (u32)~i;
+    if (key >= prefix) {
+      const u32 p = atomicAdd(&sh.misc[2], 1u);
+      if (p < SAMPLER_MAX_K) sh.cand[p] = key;
+    }
+  });
+  __syncthreads();
+  u32 npow = 1;
+  while (npow < cnt) npow <<= 1;
+  for (u32 i = cnt + tid; i < npow; i += BLK_THREADS) sh.cand[i] = 0ull;   // padding sorts to the end
+  __syncthreads();
+  bitonic_sort_desc(sh.cand, npow);
+  return npow;
+}
+
+__device__ __forceinline__ void phase_sample_publish(const DevCtx& c, SamplerShared& sh, u32 wg, u32 nwg) {
   const IterMeta* meta = c.meta;
   const u32 n_seqs = meta->n_seqs, V = c.V, tid = threadIdx.x;
   if (wg == 0 && tid == 0 && (c.flags & 1u)) c.trace[meta->trace_idx].t_forward_end = dev_now_ns();
@@ -95,60 +217,27 @@ __device__ void phase_sample_publish(const DevCtx& c, SamplerShared& sh, u32 wg,
     i32 token;
     if (r.temperature == 0.f) {
       unsigned long long best = 0;
-      for (u32 i = tid; i < V; i += BLK_THREADS) {
-        const unsigned long long key = ((unsigned long long)order_key(row[i]) << 32) | (u32)~i;
+      scan_row(row, V, [&](float val, u32 i) {
+        const unsigned long long key = ((unsigned long long)order_key(val) << 32) | (u32)~i;
         best = key > best ? key : best;
-      }
+      });
       best = block_max_u64(best, sh.red64);
       token = (i32)(~(u32)best);
     } else {
       u32 k = r.top_k == 0 || r.top_k > V ? V : r.top_k;
       if (k > SAMPLER_MAX_K) k = SAMPLER_MAX_K;   // submit rejects what does not fit; defensive clamp
-      // threshold composite key of the k-th largest candidate
-      unsigned long long prefix = 0;
-      u32 k_rem = k;
-      for (int shift = 56; shift >= 32; shift -= 8) radix_digit(row, V, shift, prefix, k_rem, sh);
-      // ids below 2^24: the low word is ~id, its top byte is 0xFF for every item
-      prefix |= 0xFF000000ull;
-      for (int shift = 16; shift >= 0; shift -= 8) radix_digit(row, V, shift, prefix, k_rem, sh);
-      // gather the k items with composite key >= threshold
-      __syncthreads();
-      if (tid == 0) sh.misc[2] = 0;
-      __syncthreads();
-      for (u32 i = tid; i < V; i += BLK_THREADS) {
-        const unsigned long long key = ((unsigned long long)order_key(row[i]) << 32) | (u32)~i;
-        if (key >= prefix) {
-          const u32 p = atomicAdd(&sh.misc[2], 1u);
-          if (p < SAMPLER_MAX_K) sh.cand[p] = key;
-        }
-      }
-      __syncthreads();
-      u32 npow = 1;
-      while (npow < k) npow <<= 1;
-      for (u32 i = k + tid; i < npow; i += BLK_THREADS) sh.cand[i] = 0ull;   // pads sort to the end
-      __syncthreads();
-      // bitonic sort, descending
-      for (u32 size = 2; size <= npow; size <<= 1) {
-        for (u32 stride = size >> 1; stride > 0; stride >>= 1) {
-          for (u32 i = tid; i < npow / 2; i += BLK_THREADS) {
-            const u32 lo = (i / stride) * stride * 2 + (i % stride), hi = lo + stride;
-            const bool desc = ((lo & size) == 0);
-            const unsigned long long a = sh.cand[lo], bb = sh.cand[hi];
-            if ((a < bb) == desc) { sh.cand[lo] = bb; sh.cand[hi] = a; }
-          }
-          __syncthreads();
-        }
-      }
+      const u32 npow = select_top_k(row, V, k, sh);   // sh.cand[0..k) = the k largest (logit, then lower id) in order
       // softmax numerators of the kept candidates at temperature T, cumulative sums in candidate order
       const float invT = 1.0f / r.temperature;
       const float zmax = key_to_float((u32)(sh.cand[0] >> 32)) * invT;
       const u32 per = (npow + BLK_THREADS - 1) / BLK_THREADS;   // consecutive candidates per thread
       float local[SAMPLER_MAX_K / BLK_THREADS];
       float run_sum = 0.f;
-      for (u32 j = 0; j < per; ++j) {
+#pragma unroll
+      for (u32 j = 0; j < SAMPLER_MAX_K / BLK_THREADS; ++j) {
         const u32 i = tid * per + j;
         float p = 0.f;
-        if (i < k) p = __expf(key_to_float((u32)(sh.cand[i] >> 32)) * invT - zmax);
+        if (j < per && i < k) p = __expf(key_to_float((u32)(sh.cand[i] >> 32)) * invT - zmax);
         run_sum += p;
         local[j] = run_sum;
       }
@@ -164,9 +253,10 @@ __device__ void phase_sample_publish(const DevCtx& c, SamplerShared& sh, u32 wg,
       __syncthreads();
       float base = inc - run_sum;
       for (u32 w = 0; w < (tid >> 6); ++w) base += sh.redf[w];
-      for (u32 j = 0; j < per; ++j) {
+#pragma unroll
+      for (u32 j = 0; j < SAMPLER_MAX_K / BLK_THREADS; ++j) {
         const u32 i = tid * per + j;
-        if (i < npow) sh.cum[i] = base + local[j];
+        if (j < per && i < npow) sh.cum[i] = base + local[j];
       }
       __syncthreads();
       if (tid == 0) {
