@@ -98,12 +98,13 @@ __device__ __forceinline__ void attn_block(const KVTile<HD>& kv, const bf16x8_t 
   }
 }
 
+#define ATTN_WAVES 8          // the attention kernel of the bf16 path runs 512 threads per workgroup
 struct AttnMfmaShared {
-  float m[4][16], l[4][16];
-  float o[4][16][128];
+  float m[ATTN_WAVES][16], l[ATTN_WAVES][16];
+  float o[ATTN_WAVES][8][128];   // [wave][q head of the group][dim]
 };
 
-// ---- decode: one workgroup per (sequence, kv head); the four waves take the KV blocks round-robin ----------------
+// ---- decode: one workgroup per (sequence, kv head); its waves take the KV blocks round-robin ----------------------
 template <int HD>
 __device__ __forceinline__ void attn_decode(const DevCtx& c, u32 layer, AttnMfmaShared& sh, u32 wg, u32 nwg) {
   const u32 B = c.meta->n_seqs, G = c.nq / c.nkv;
@@ -127,17 +128,18 @@ __device__ __forceinline__ void attn_decode(const DevCtx& c, u32 layer, AttnMfma
     attn_init(acc);
     const u32 lim[1] = {ctx};
     const u32 nb = (ctx + 15) / 16;
-    // software pipeline: three KV blocks of this wave (blocks w, w+4, ...) are in flight at any time; the tiles
+    // software pipeline: three KV blocks of this wave (blocks w, w+nw, ...) are in flight at any time; the tiles
     // rotate by code position (no register copies). Block ids are fetched 64 at a time, one per lane.
-    const u32 nmine = nb > w ? (nb - w + 3) / 4 : 0;       // blocks of this wave
+    const u32 nw = blockDim.x >> 6;
+    const u32 nmine = nb > w ? (nb - w + nw - 1) / nw : 0;   // blocks of this wave
     KVTile<HD> t0, t1, t2;
     u32 ids = 0;
     for (u32 base_it = 0; base_it < nmine; base_it += 63) {   // 63 = multiple of the pipeline depth within one id batch
-      const u32 mine = w + 4 * (base_it + lane);
+      const u32 mine = w + nw * (base_it + lane);
       ids = mine < nb ? bt[mine] : 0u;
       const u32 lim_it = min(nmine - base_it, 63u);
       auto ld = [&](KVTile<HD>& tl, u32 j) { if (j < lim_it) { const u64 bs = ((u64)__shfl(ids, j) * c.nkv + g) * tile; kv_load<HD>(Kc + bs, Vc + bs, tl); } };
-      auto us = [&](const KVTile<HD>& tl, u32 j) { if (j < lim_it) attn_block<HD, 1>(tl, q, (w + 4 * (base_it + j)) * 16, lim, acc); };
+      auto us = [&](const KVTile<HD>& tl, u32 j) { if (j < lim_it) attn_block<HD, 1>(tl, q, (w + nw * (base_it + j)) * 16, lim, acc); };
       ld(t0, 0); ld(t1, 1); ld(t2, 2);
       for (u32 j = 0; j < lim_it; j += 3) {
         us(t0, j); ld(t0, j + 3);
@@ -150,14 +152,15 @@ __device__ __forceinline__ void attn_decode(const DevCtx& c, u32 layer, AttnMfma
 #pragma unroll
     for (int d = 0; d < HD / 16; ++d)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) sh.o[w][lg * 4 + i][d * 16 + lc] = acc.o[0][d][i];
+      for (int i = 0; i < 4; ++i)
+        if (lg * 4 + i < G) sh.o[w][lg * 4 + i][d * 16 + lc] = acc.o[0][d][i];
     __syncthreads();
-    for (u32 idx = threadIdx.x; idx < G * HD; idx += BLK_THREADS) {
+    for (u32 idx = threadIdx.x; idx < G * HD; idx += blockDim.x) {
       const u32 h = idx / HD, dim = idx % HD;
-      const float M = fmaxf(fmaxf(sh.m[0][h], sh.m[1][h]), fmaxf(sh.m[2][h], sh.m[3][h]));
+      float M = -INFINITY;
+      for (u32 ww = 0; ww < nw; ++ww) M = fmaxf(M, sh.m[ww][h]);
       float L = 0.f, O = 0.f;
-#pragma unroll
-      for (int ww = 0; ww < 4; ++ww) {
+      for (u32 ww = 0; ww < nw; ++ww) {      // fixed order; a wave without blocks has m = -inf and contributes 0
         const float f = __expf(sh.m[ww][h] - M);
         L += sh.l[ww][h] * f;
         O += sh.o[ww][h][dim] * f;
@@ -177,7 +180,8 @@ __device__ __forceinline__ void attn_prefill(const DevCtx& c, u32 layer, u32 wg,
   const u64 tile = (u64)16 * HD;
   const u32 total_qt = c.cu_qtiles[B];
   const u32 per_tile = c.nkv * groups;
-  for (u64 item = (u64)wg * 4 + w; item < (u64)total_qt * per_tile; item += (u64)nwg * 4) {
+  const u32 nw = blockDim.x >> 6;
+  for (u64 item = (u64)wg * nw + w; item < (u64)total_qt * per_tile; item += (u64)nwg * nw) {
     const u32 qi = (u32)(item / per_tile), rem = (u32)(item % per_tile), g = rem / groups, hg = rem % groups;
     u32 lo = 0, hi = B;                       // sequence of query tile qi: last s with cu_qtiles[s] <= qi
     while (hi - lo > 1) {

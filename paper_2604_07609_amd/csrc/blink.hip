@@ -33,7 +33,12 @@ PHASE_KERNEL(k_embed, PH_EMBED)
 PHASE_KERNEL(k_norm1, PH_NORM1)
 PHASE_KERNEL(k_qkv, PH_QKV)
 PHASE_KERNEL(k_rope_kvwrite, PH_ROPE)
-PHASE_KERNEL(k_attention, PH_ATTN)
+// attention: the bf16 path runs 512 threads per workgroup (eight waves share the KV blocks of one sequence);
+// the fp32 path keeps 256
+__global__ void __launch_bounds__(512) k_attention(DevCtx c, u32 layer) {
+  __shared__ PhaseSharedOf<PH_ATTN>::type sh;
+  run_phase(c, PH_ATTN, layer, &sh, blockIdx.x, gridDim.x);
+}
 PHASE_KERNEL(k_oproj, PH_OPROJ)
 PHASE_KERNEL(k_norm2, PH_NORM2)
 PHASE_KERNEL(k_gateup, PH_GATEUP)
@@ -443,7 +448,8 @@ static int launch_phase(blink_engine* e, hipStream_t st, int ph, u32 layer, u64 
     b = e->phase_ev[2 * slot + 1];
     HIPCHK(hipEventRecord(a, st));
   }
-  hipLaunchKernelGGL(phase_kernel(ph), dim3(e->grid), dim3(BLK_THREADS), 0, st, e->ctx, layer);
+  const u32 threads = (ph == PH_ATTN && e->ctx.dtype == 1) ? 512u : (u32)BLK_THREADS;
+  hipLaunchKernelGGL(phase_kernel(ph), dim3(e->grid), dim3(threads), 0, st, e->ctx, layer);
   if (timed) HIPCHK(hipEventRecord(b, st));
   return 0;
 }

@@ -295,17 +295,30 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& a, MfmaShared& sh,
     for (int i = 0; i < 4; ++i)
 #pragma unroll
       for (int j = 0; j < 4; ++j) acc[i][j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll 2
-    for (u32 kt = 0; kt < KT; ++kt) {
-      bf16x8_t wv[4], xv[4];
+    // three k-steps of operand tiles in flight; the buffers rotate by code position (no register copies)
+    struct Step { bf16x8_t w[4], x[4]; };
+    Step s0, s1, s2;
+    auto ld = [&](Step& st, u32 kt) {
+      if (kt < KT) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) wv[i] = ld_tile(wp[i] + (u64)kt * 512);
+        for (int i = 0; i < 4; ++i) st.w[i] = ld_tile(wp[i] + (u64)kt * 512);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) xv[j] = ld_tile(a.Xp + (u64)kt * xk_stride + xoff[j]);
+        for (int j = 0; j < 4; ++j) st.x[j] = ld_tile(a.Xp + (u64)kt * xk_stride + xoff[j]);
+      }
+    };
+    auto mm = [&](const Step& st, u32 kt) {
+      if (kt < KT) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv[i], xv[j], acc[i][j], 0, 0, 0);
+          for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(st.w[i], st.x[j], acc[i][j], 0, 0, 0);
+      }
+    };
+    ld(s0, 0); ld(s1, 1); ld(s2, 2);
+    for (u32 kt = 0; kt < KT; kt += 3) {
+      mm(s0, kt); ld(s0, kt + 3);
+      mm(s1, kt + 1); ld(s1, kt + 4);
+      mm(s2, kt + 2); ld(s2, kt + 5);
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i)
