@@ -36,8 +36,9 @@ extern "C" {
 /* blink_config.flags */
 #define BLINK_FLAG_TRACE 1u          /* record one trace record per iteration (blink_get_trace) */
 #define BLINK_FLAG_EXIT_WHEN_IDLE 2u /* the loop stops by itself once nothing is running and nothing is pending */
-#define BLINK_FLAG_PERSISTENT 4u     /* one resident kernel runs the whole loop; without it the host enqueues a
-                                        fixed, decision-free kernel sequence per iteration (bring-up mode) */
+#define BLINK_FLAG_PERSISTENT 4u     /* reserved: one resident kernel running the whole loop behind grid barriers. Not
+                                        implemented (ignored): on MI355X a grid barrier costs 3-4x a kernel boundary.
+                                        The loop is a device-decided kernel chain that a host thread only pumps. */
 #define BLINK_FLAG_KEEP_LOGITS 8u    /* keep the logits of the last iteration readable via blink_debug_read */
 
 /* slot life cycle of the ring (section 4.2, "Ring buffer") */
@@ -73,8 +74,7 @@ typedef struct {
   int32_t device;              /* HIP device ordinal */
   uint32_t flags;              /* BLINK_FLAG_* */
   uint32_t trace_capacity;     /* trace records kept (0: 65536); older records are overwritten */
-  uint32_t idle_exit_us;       /* persistent mode: the resident kernel returns after this long without work so
-                                  that every wave ends (0: 200000); the launcher thread starts the next window */
+  uint32_t idle_exit_us;       /* reserved for BLINK_FLAG_PERSISTENT; ignored */
 } blink_config;
 
 typedef struct {
@@ -120,7 +120,7 @@ typedef struct {
   uint32_t committed_blocks;
   uint32_t device_error;       /* non-zero: the loop stopped on an internal error */
   uint32_t running;            /* 1 while the loop is active */
-  uint32_t windows;            /* persistent mode: resident-kernel launches so far */
+  uint32_t windows;            /* blink_run calls so far */
   uint64_t kv_bytes, weight_bytes, ring_bytes;
 } blink_stats;
 
@@ -162,6 +162,10 @@ int blink_wait(blink_engine* e);
  * with the host's shadow, fetches the new tokens and writes up to cap events: per request in index order.
  * A slot returns to EMPTY once its LAST event has been delivered. */
 int blink_poll_outputs(blink_engine* e, blink_event* buf, uint32_t cap, uint32_t* n_out);
+
+/* Ends the current window: sets the device stop flag, waits for the loop to end, clears the flag. All state
+ * stays in device memory; blink_run continues from the same point. */
+int blink_stop(blink_engine* e);
 
 /* Sets the device stop flag, waits for the loop to end, frees everything. The handle is invalid afterwards. */
 int blink_shutdown(blink_engine* e);

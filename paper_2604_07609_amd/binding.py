@@ -10,7 +10,7 @@ FLAG_TRACE, FLAG_EXIT_WHEN_IDLE, FLAG_PERSISTENT, FLAG_KEEP_LOGITS = 1, 2, 4, 8
 ERR_INVAL, ERR_TOO_LARGE, ERR_FULL, ERR_DEVICE, ERR_STATE = -1, -2, -3, -4, -5
 EVENT_FIRST, EVENT_LAST = 1, 2
 
-EXPORTS = ["blink_init", "blink_submit", "blink_run", "blink_wait", "blink_poll_outputs", "blink_shutdown",
+EXPORTS = ["blink_init", "blink_submit", "blink_run", "blink_wait", "blink_stop", "blink_poll_outputs", "blink_shutdown",
            "blink_get_trace", "blink_get_stats", "blink_debug_read", "blink_time_phase", "blink_get_phase_times",
            "blink_last_error"]
 
@@ -74,6 +74,7 @@ def load_library():
     lib.blink_submit.argtypes = [vp, vp, u32, u32, C.POINTER(Sampling), C.POINTER(u64)]
     lib.blink_run.argtypes = [vp, u64]
     lib.blink_wait.argtypes = [vp]
+    lib.blink_stop.argtypes = [vp]
     lib.blink_poll_outputs.argtypes = [vp, vp, u32, C.POINTER(u32)]
     lib.blink_shutdown.argtypes = [vp]
     lib.blink_get_trace.argtypes = [vp, vp, u64, C.POINTER(u64)]
@@ -126,6 +127,9 @@ class Engine:
 
     def wait(self):
         _check(self.lib, self.lib.blink_wait(self.h))
+
+    def stop(self):
+        _check(self.lib, self.lib.blink_stop(self.h))
 
     def poll(self, cap=4096):
         buf = np.zeros(cap, dtype=EVENT_DTYPE)

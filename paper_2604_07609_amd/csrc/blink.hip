@@ -617,6 +617,18 @@ extern "C" int blink_poll_outputs(blink_engine* e, blink_event* buf, uint32_t ca
   return BLINK_OK;
 }
 
+extern "C" int blink_stop(blink_engine* e) {
+  g_err.clear();
+  if (!e) return fail(BLINK_ERR_INVAL, "null engine");
+  if (e->shut) return fail(BLINK_ERR_STATE, "engine is shut down");
+  __atomic_store_n(&e->hctrl->stop, 1u, __ATOMIC_RELEASE);
+  if (e->launcher.joinable()) e->launcher.join();
+  __atomic_store_n(&e->hctrl->stop, 0u, __ATOMIC_RELEASE);
+  const int rc = e->loop_rc.load();
+  if (rc) return fail(rc, "the loop ended with an error (device error %u)", e->hmirror->error);
+  return BLINK_OK;
+}
+
 extern "C" int blink_shutdown(blink_engine* e) {
   g_err.clear();
   if (!e) return fail(BLINK_ERR_INVAL, "null engine");
