@@ -67,13 +67,15 @@ def decode_step_bytes(cfg, n_seqs, ctx_tokens):
     return w + kv_tok * (ctx_tokens + n_seqs) + 2 * 4 * n_seqs * V
 
 
-def cpu_baseline(cfg, eng, raw, reqs, budget_tokens):
+def cpu_baseline(cfg, eng, raw, reqs, budget_tokens, n_req=4, prompt_cap=None):
     """The oracle, as it stands, on a bounded sample of the same workload."""
     from oracle import model as M, serve as SV
     sample = []
-    for r in reqs[:4]:
+    for r in reqs[:n_req]:
         r = dict(r)
         r["max_new_tokens"] = min(r["max_new_tokens"], budget_tokens)
+        if prompt_cap:
+            r["prompt"] = r["prompt"][:prompt_cap]
         sample.append(r)
     t0 = time.perf_counter()
     ev, _ = SV.serve(cfg, M.Weights(cfg, raw), eng, sample)
@@ -84,8 +86,67 @@ def cpu_baseline(cfg, eng, raw, reqs, budget_tokens):
     except Exception:
         threads = os.cpu_count()
     return dict(value=len(ev) / dt, unit="output tokens/s", cores=int(threads), kind="oracle",
-                sample="first %d requests, prompts as drawn (%s tokens), max_new_tokens capped at %d: %d output tokens in %.1f s"
-                       % (len(sample), "+".join(str(len(r["prompt"])) for r in sample), budget_tokens, len(ev), dt))
+                sample="first %d requests, prompts %s(%s tokens), max_new_tokens capped at %d: %d output tokens in %.1f s"
+                       % (len(sample), "truncated " if prompt_cap else "as drawn ", "+".join(str(len(r["prompt"])) for r in sample),
+                          budget_tokens, len(ev), dt))
+
+
+def open_loop(B, cfg, eng, blob, reqs, seconds):
+    """The workload's own arrival process: a producer thread submits each request at its arrival time while the
+    loop runs; the main thread polls. Returns TTFT (host clocks: submit -> first event seen) and ITL (device
+    timestamps) percentiles and the output token rate over the run."""
+    import threading
+    reqs = [r for r in reqs if r["arrival_s"] <= seconds][: eng["ring_slots"]]
+    if not reqs:
+        return None
+    e = B.Engine(cfg, eng, blob, flags=0)
+    submit_t = {}
+    try:
+        e.run(0)
+        t_start = time.perf_counter()
+
+        def producer():
+            for i, r in enumerate(reqs):
+                dt = t_start + r["arrival_s"] - time.perf_counter()
+                if dt > 0:
+                    time.sleep(dt)
+                while True:
+                    try:
+                        submit_t[e.submit_request(r)] = time.perf_counter()
+                        break
+                    except B.BlinkError:
+                        time.sleep(0.0005)
+
+        th = threading.Thread(target=producer)
+        th.start()
+        evs, first_seen, done = [], {}, 0
+        deadline = time.perf_counter() + seconds + 120
+        while done < len(reqs) and time.perf_counter() < deadline:
+            ev = e.poll(8192)
+            now = time.perf_counter()
+            if ev.size:
+                evs.append(ev.copy())
+                for rid in ev["request_id"][(ev["flags"] & 1) != 0]:
+                    first_seen[int(rid)] = now
+                done += int(np.count_nonzero(ev["flags"] & 2))
+            else:
+                time.sleep(0.0002)
+        t_end = time.perf_counter()
+        th.join()
+        e.stop()
+    finally:
+        e.shutdown()
+    ev = np.concatenate(evs)
+    order = np.lexsort((ev["index"], ev["request_id"]))
+    evs = ev[order]
+    same = (evs["request_id"][1:] == evs["request_id"][:-1]) & (evs["index"][1:] == evs["index"][:-1] + 1)
+    itl = (evs["device_ns"][1:].astype(np.int64) - evs["device_ns"][:-1].astype(np.int64))[same] / 1e6
+    ttft = np.array([first_seen[r] - submit_t[r] for r in first_seen if r in submit_t]) * 1e3
+    pct = lambda a, q: round(float(np.percentile(a, q)), 3) if len(a) else None
+    return dict(requests=len(reqs), completed=done, seconds=round(t_end - t_start, 2), output_tokens=int(len(ev)),
+                output_tokens_per_s=round(len(ev) / (t_end - t_start), 1),
+                itl_ms=dict(p50=pct(itl, 50), p99=pct(itl, 99)), ttft_ms=dict(p50=pct(ttft, 50), p99=pct(ttft, 99)),
+                arrivals="as drawn (producer thread stands in for the SmartNIC)")
 
 
 def main():
@@ -98,6 +159,7 @@ def main():
     ap.add_argument("--requests", type=int, default=0)
     ap.add_argument("--max-batch", type=int, default=0, help="override the engine's batch slots")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--open-loop-seconds", type=float, default=8.0, help="0: skip the run with the workload's own arrivals")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -121,7 +183,6 @@ def main():
     t_gen = time.perf_counter() - t_gen
 
     e = B.Engine(cfg, eng, blob, flags=B.FLAG_TRACE | B.FLAG_EXIT_WHEN_IDLE, trace_capacity=max(65536, K + W + 16))
-    del blob
     try:
         for r in reqs:
             e.submit_request(r)
@@ -195,9 +256,15 @@ def main():
         "roofline": roofline,
         "setup_s": {"weights_and_workload": round(t_gen, 1)},
     }
+    if args.open_loop_seconds > 0:
+        out["open_loop"] = open_loop(B, cfg, eng, blob, reqs, args.open_loop_seconds)
+    del blob
     if not args.no_cpu_baseline:
         budget = args.cpu_sample_tokens or {"tiny": 32, "churn": 16, "llama3_8b": 2, "sched_stress": 16}[args.workload]
-        out["cpu_baseline"] = cpu_baseline(cfg, eng, raw, reqs, budget)
+        if args.workload == "llama3_8b":
+            out["cpu_baseline"] = cpu_baseline(cfg, eng, raw, reqs, budget, n_req=2, prompt_cap=32)
+        else:
+            out["cpu_baseline"] = cpu_baseline(cfg, eng, raw, reqs, budget)
     print(json.dumps(out))
 
 

@@ -98,6 +98,7 @@ __device__ __forceinline__ void attn_block(const KVTile<HD>& kv, const bf16x8_t 
   }
 }
 
+#define ATTN_CHUNK_BLOCKS 32   // KV blocks (512 tokens) per decode work item
 #define ATTN_WAVES 8          // the attention kernel of the bf16 path runs 512 threads per workgroup
 struct AttnMfmaShared {
   float m[ATTN_WAVES][16], l[ATTN_WAVES][16];
@@ -112,8 +113,18 @@ __device__ __forceinline__ void attn_decode(const DevCtx& c, u32 layer, AttnMfma
   const bf16_t* Kc = (const bf16_t*)c.kv + (u64)layer * c.kv_layer_stride;
   const bf16_t* Vc = Kc + c.kv_kv_stride;
   const u64 tile = (u64)16 * HD;
-  for (u32 item = wg; item < B * c.nkv; item += nwg) {
-    const u32 s = item / c.nkv, g = item % c.nkv;
+  // Work item: (512-token chunk of one sequence's context, kv head). Chunks balance the load between short and long
+  // contexts and give the chip enough items at small batch. A context of one chunk is finished here; longer ones
+  // leave per-chunk partial results that attn_decode_combine (the next kernel) merges in chunk order.
+  const u32 total_chunks = c.cu_chunks[B];
+  for (u32 item = wg; item < total_chunks * c.nkv; item += nwg) {
+    const u32 ci = item / c.nkv, g = item % c.nkv;
+    u32 lo = 0, hi = B;                       // sequence of chunk ci: last s with cu_chunks[s] <= ci
+    while (hi - lo > 1) {
+      const u32 mid = (lo + hi) / 2;
+      if (c.cu_chunks[mid] <= ci) lo = mid; else hi = mid;
+    }
+    const u32 s = lo, ch = ci - c.cu_chunks[s], nch = c.cu_chunks[s + 1] - c.cu_chunks[s];
     const u32 t = c.cu_seqlens[s];              // the sequence's single token of this iteration
     const u32 ctx = c.seq_len[s];
     const u32* bt = c.block_tables + (u64)c.seq_bslot[s] * c.max_blocks_per_seq;
@@ -127,26 +138,16 @@ __device__ __forceinline__ void attn_decode(const DevCtx& c, u32 layer, AttnMfma
     AttnAcc<HD, 1> acc;
     attn_init(acc);
     const u32 lim[1] = {ctx};
-    const u32 nb = (ctx + 15) / 16;
-    // software pipeline: three KV blocks of this wave (blocks w, w+nw, ...) are in flight at any time; the tiles
-    // rotate by code position (no register copies). Block ids are fetched 64 at a time, one per lane.
+    const u32 b_lo = ch * ATTN_CHUNK_BLOCKS, b_hi = min((ctx + 15) / 16, b_lo + ATTN_CHUNK_BLOCKS);
+    const u32 nb = b_hi - b_lo;                 // 1..32 blocks: at most four per wave
+    // every wave fetches its (up to four) blocks at once: all tiles in flight together
     const u32 nw = blockDim.x >> 6;
-    const u32 nmine = nb > w ? (nb - w + nw - 1) / nw : 0;   // blocks of this wave
-    KVTile<HD> t0, t1, t2;
-    u32 ids = 0;
-    for (u32 base_it = 0; base_it < nmine; base_it += 63) {   // 63 = multiple of the pipeline depth within one id batch
-      const u32 mine = w + nw * (base_it + lane);
-      ids = mine < nb ? bt[mine] : 0u;
-      const u32 lim_it = min(nmine - base_it, 63u);
-      auto ld = [&](KVTile<HD>& tl, u32 j) { if (j < lim_it) { const u64 bs = ((u64)__shfl(ids, j) * c.nkv + g) * tile; kv_load<HD>(Kc + bs, Vc + bs, tl); } };
-      auto us = [&](const KVTile<HD>& tl, u32 j) { if (j < lim_it) attn_block<HD, 1>(tl, q, (w + nw * (base_it + j)) * 16, lim, acc); };
-      ld(t0, 0); ld(t1, 1); ld(t2, 2);
-      for (u32 j = 0; j < lim_it; j += 3) {
-        us(t0, j); ld(t0, j + 3);
-        us(t1, j + 1); ld(t1, j + 4);
-        us(t2, j + 2); ld(t2, j + 5);
-      }
-    }
+    KVTile<HD> t0, t1, t2, t3;
+    const u32 i0 = w, i1 = w + nw, i2 = w + 2 * nw, i3 = w + 3 * nw;
+    auto ld = [&](KVTile<HD>& tl, u32 i) { if (i < nb) { const u64 bs = ((u64)bt[b_lo + i] * c.nkv + g) * tile; kv_load<HD>(Kc + bs, Vc + bs, tl); } };
+    auto us = [&](const KVTile<HD>& tl, u32 i) { if (i < nb) attn_block<HD, 1>(tl, q, (b_lo + i) * 16, lim, acc); };
+    ld(t0, i0); ld(t1, i1); ld(t2, i2); ld(t3, i3);
+    us(t0, i0); us(t1, i1); us(t2, i2); us(t3, i3);
     __syncthreads();   // the previous item's combine has finished reading LDS
     if (lg == 0) { sh.m[w][lc] = acc.m[0]; sh.l[w][lc] = acc.l[0]; }
 #pragma unroll
@@ -155,6 +156,8 @@ __device__ __forceinline__ void attn_decode(const DevCtx& c, u32 layer, AttnMfma
       for (int i = 0; i < 4; ++i)
         if (lg * 4 + i < G) sh.o[w][lg * 4 + i][d * 16 + lc] = acc.o[0][d][i];
     __syncthreads();
+    float* po = c.attn_part_o + ((u64)ci * c.nkv + g) * G * HD;
+    float* pml = c.attn_part_ml + ((u64)ci * c.nkv + g) * G * 2;
     for (u32 idx = threadIdx.x; idx < G * HD; idx += blockDim.x) {
       const u32 h = idx / HD, dim = idx % HD;
       float M = -INFINITY;
@@ -164,6 +167,36 @@ __device__ __forceinline__ void attn_decode(const DevCtx& c, u32 layer, AttnMfma
         const float f = __expf(sh.m[ww][h] - M);
         L += sh.l[ww][h] * f;
         O += sh.o[ww][h][dim] * f;
+      }
+      if (nch == 1) {
+        c.aq[packed_off(t, (g * G + h) * HD + dim, c.TBS)] = f32_to_bf16(O / L);
+      } else {
+        po[(u64)h * HD + dim] = O;
+        if (dim == 0) { pml[h * 2] = M; pml[h * 2 + 1] = L; }
+      }
+    }
+  }
+}
+
+// Merges the per-chunk partial results of contexts longer than one chunk, in chunk order. 256 threads.
+__device__ __forceinline__ void attn_decode_combine(const DevCtx& c, u32 wg, u32 nwg) {
+  if (c.meta->kind != 2u) return;
+  const u32 B = c.meta->n_seqs, G = c.nq / c.nkv, HD = c.hd;
+  for (u32 pair = wg; pair < B * c.nkv; pair += nwg) {
+    const u32 s = pair / c.nkv, g = pair % c.nkv;
+    const u32 c0 = c.cu_chunks[s], nch = c.cu_chunks[s + 1] - c0;
+    if (nch < 2) continue;
+    const u32 t = c.cu_seqlens[s];
+    for (u32 idx = threadIdx.x; idx < G * HD; idx += blockDim.x) {
+      const u32 h = idx / HD, dim = idx % HD;
+      float M = -INFINITY;
+      for (u32 p = 0; p < nch; ++p) M = fmaxf(M, c.attn_part_ml[(((u64)(c0 + p) * c.nkv + g) * G + h) * 2]);
+      float L = 0.f, O = 0.f;
+      for (u32 p = 0; p < nch; ++p) {
+        const u64 base = ((u64)(c0 + p) * c.nkv + g) * G;
+        const float f = __expf(c.attn_part_ml[(base + h) * 2] - M);
+        L += c.attn_part_ml[(base + h) * 2 + 1] * f;
+        O += c.attn_part_o[(base + h) * HD + dim] * f;
       }
       c.aq[packed_off(t, (g * G + h) * HD + dim, c.TBS)] = f32_to_bf16(O / L);
     }

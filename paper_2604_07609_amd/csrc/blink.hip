@@ -31,7 +31,14 @@ __global__ void __launch_bounds__(BLK_THREADS) k_sched(DevCtx c) {
   }
 PHASE_KERNEL(k_embed, PH_EMBED)
 PHASE_KERNEL(k_norm1, PH_NORM1)
-PHASE_KERNEL(k_qkv, PH_QKV)
+// The projections with few output rows (QKV, attention output, FFN down) run eight waves per workgroup on the bf16
+// path so that K is split eight ways and enough weight bytes are in flight; the fp32 path keeps four.
+#define PHASE_KERNEL8(name, PH)                                                  \
+  __global__ void __launch_bounds__(512) name(DevCtx c, u32 layer) {             \
+    __shared__ PhaseSharedOf<PH>::type sh;                                       \
+    run_phase(c, PH, layer, &sh, blockIdx.x, gridDim.x);                         \
+  }
+PHASE_KERNEL8(k_qkv, PH_QKV)
 PHASE_KERNEL(k_rope_kvwrite, PH_ROPE)
 // attention: the bf16 path runs 512 threads per workgroup (eight waves share the KV blocks of one sequence);
 // the fp32 path keeps 256
@@ -39,13 +46,14 @@ __global__ void __launch_bounds__(512) k_attention(DevCtx c, u32 layer) {
   __shared__ PhaseSharedOf<PH_ATTN>::type sh;
   run_phase(c, PH_ATTN, layer, &sh, blockIdx.x, gridDim.x);
 }
-PHASE_KERNEL(k_oproj, PH_OPROJ)
+PHASE_KERNEL8(k_oproj, PH_OPROJ)
 PHASE_KERNEL(k_norm2, PH_NORM2)
 PHASE_KERNEL(k_gateup, PH_GATEUP)
-PHASE_KERNEL(k_down, PH_DOWN)
+PHASE_KERNEL8(k_down, PH_DOWN)
 PHASE_KERNEL(k_final_norm, PH_FINAL_NORM)
 PHASE_KERNEL(k_lm_head, PH_LM_HEAD)
 PHASE_KERNEL(k_sample_publish, PH_SAMPLE)
+PHASE_KERNEL(k_attention_combine, PH_ATTN_COMBINE)
 
 typedef void (*phase_kernel_t)(DevCtx, u32);
 static phase_kernel_t phase_kernel(int ph) {
@@ -61,6 +69,7 @@ static phase_kernel_t phase_kernel(int ph) {
     case PH_DOWN: return k_down;
     case PH_FINAL_NORM: return k_final_norm;
     case PH_LM_HEAD: return k_lm_head;
+    case PH_ATTN_COMBINE: return k_attention_combine;
     default: return k_sample_publish;
   }
 }
@@ -233,6 +242,7 @@ static int init_impl(const blink_config* cfg, blink_engine* e) {
   if (int rc = dalloc(e, &c.cu_seqlens, c.max_batch + 1)) return rc;
   if (int rc = dalloc(e, &c.last_idx, c.max_batch)) return rc;
   if (int rc = dalloc(e, &c.cu_qtiles, c.max_batch + 1)) return rc;
+  if (int rc = dalloc(e, &c.cu_chunks, c.max_batch + 1)) return rc;
   if (int rc = dalloc(e, &c.input_ids, c.maxT)) return rc;
   if (int rc = dalloc(e, &c.positions, c.maxT)) return rc;
   if (int rc = dalloc(e, &c.slot_mapping, c.maxT)) return rc;
@@ -315,6 +325,11 @@ static int init_impl(const blink_config* cfg, blink_engine* e) {
     if (int rc = dalloc(e, &c.hq, tile_tokens * c.F)) return rc;
     if (int rc = dalloc(e, &c.ssq, tile_tokens * (c.d / 16))) return rc;
     if (int rc = dalloc(e, &c.qbuf, (u64)c.maxT * c.nq * c.hd)) return rc;
+    {
+      const u64 chunks = (u64)c.max_batch * ((c.max_seq_len + 511) / 512), G = c.nq / c.nkv;
+      if (int rc = dalloc(e, &c.attn_part_o, chunks * c.nkv * G * c.hd)) return rc;
+      if (int rc = dalloc(e, &c.attn_part_ml, chunks * c.nkv * G * 2)) return rc;
+    }
   }
   // ---- KV pool ----
   c.kv_kv_stride = (u64)c.n_blocks * c.nkv * c.bs * c.hd;
@@ -448,7 +463,8 @@ static int launch_phase(blink_engine* e, hipStream_t st, int ph, u32 layer, u64 
     b = e->phase_ev[2 * slot + 1];
     HIPCHK(hipEventRecord(a, st));
   }
-  const u32 threads = (ph == PH_ATTN && e->ctx.dtype == 1) ? 512u : (u32)BLK_THREADS;
+  const bool wide = ph == PH_ATTN || ph == PH_QKV || ph == PH_OPROJ || ph == PH_DOWN;
+  const u32 threads = (wide && e->ctx.dtype == 1) ? 512u : (u32)BLK_THREADS;
   hipLaunchKernelGGL(phase_kernel(ph), dim3(e->grid), dim3(threads), 0, st, e->ctx, layer);
   if (timed) HIPCHK(hipEventRecord(b, st));
   return 0;
@@ -459,8 +475,11 @@ static int enqueue_iteration_kernels(blink_engine* e, hipStream_t st, u64 enq_in
   hipLaunchKernelGGL(k_sched, dim3(1), dim3(BLK_THREADS), 0, st, c);
   if (int rc = launch_phase(e, st, PH_EMBED, 0, enq_index)) return rc;
   for (u32 l = 0; l < c.n_layers; ++l)
-    for (int ph = PH_LAYER_FIRST; ph <= PH_LAYER_LAST; ++ph)
+    for (int ph = PH_LAYER_FIRST; ph <= PH_LAYER_LAST; ++ph) {
       if (int rc = launch_phase(e, st, ph, l, enq_index)) return rc;
+      if (ph == PH_ATTN && c.dtype == 1)
+        if (int rc = launch_phase(e, st, PH_ATTN_COMBINE, l, enq_index)) return rc;
+    }
   if (int rc = launch_phase(e, st, PH_FINAL_NORM, 0, enq_index)) return rc;
   if (int rc = launch_phase(e, st, PH_LM_HEAD, 0, enq_index)) return rc;
   if (int rc = launch_phase(e, st, PH_SAMPLE, 0, enq_index)) return rc;
@@ -736,7 +755,7 @@ extern "C" int blink_time_phase(blink_engine* e, int32_t phase) {
   g_err.clear();
   if (!e) return fail(BLINK_ERR_INVAL, "null engine");
   if (e->loop_active.load()) return fail(BLINK_ERR_STATE, "stop the loop first");
-  if (phase < -1 || phase > PH_SAMPLE) return fail(BLINK_ERR_INVAL, "phase out of range");
+  if (phase < -1 || phase > PH_ATTN_COMBINE) return fail(BLINK_ERR_INVAL, "phase out of range");
   e->timed_phase = phase;
   return BLINK_OK;
 }

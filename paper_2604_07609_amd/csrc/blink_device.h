@@ -154,6 +154,7 @@ struct DevCtx {
   u32* cu_seqlens;      // [max_batch+1]
   u32* last_idx;        // [max_batch]
   u32* cu_qtiles;       // [max_batch+1] prefix sum of ceil(tokens/16) per sequence of the iteration
+  u32* cu_chunks;       // [max_batch+1] prefix sum of ceil(context/512) per sequence (decode attention work items)
   i32* input_ids;       // [maxT]
   i32* positions;       // [maxT]
   i32* slot_mapping;    // [maxT]
@@ -187,6 +188,9 @@ struct DevCtx {
   float* ssq;           // [token][d/16] partial sums of squares of the residual stream
   u32 TBS;              // token-block stride of the packed activation buffers
   u32 pad1;
+  // decode attention: partial (max, sum, output) of every 512-token chunk of a context longer than one chunk
+  float* attn_part_o;   // [chunk][kv head][G][hd]
+  float* attn_part_ml;  // [chunk][kv head][G][2]
 };
 
 __device__ __forceinline__ u64 dev_now_ns() { return wall_clock64() * 10ull; }  // 100 MHz constant clock

@@ -54,8 +54,9 @@ struct MfmaGemmArgs {
   u32 nq, nkv, hd, bs;
 };
 
+#define GEMM_MAX_WAVES 8
 struct MfmaShared {
-  float red[4][4][64][4];  // [wave][token block][lane][4]  (stream schedule)
+  float red[GEMM_MAX_WAVES][4][64][4];  // [wave][token block][lane][4]  (stream schedule; scratch of the norm scales)
   float rstd[128];
 };
 
@@ -78,10 +79,10 @@ __device__ __forceinline__ void compute_rstd(const MfmaGemmArgs& a, u32 t0, u32 
     // 256 threads: two threads per token for 128 tokens (or four for 64): each sums a contiguous run of the
     // token's partials with 16-byte loads (K/16 is a multiple of 2; runs are multiples of 4 when K % 256 == 0)
     const u32 parts = count <= 64 ? 4u : 2u, span = BLK_THREADS / parts;
-    const u32 tl = tid % span, part = tid / span;
+    const u32 tl = tid % span, part = tid / span;   // threads beyond the first 256 (8-wave launches) only join the barriers
     float s = 0.f;
     const u32 np = a.K / 16;
-    if (tl < count && t0 + tl < a.T) {
+    if (tid < BLK_THREADS && tl < count && t0 + tl < a.T) {
       const u32 tok = a.tok_index ? a.tok_index[t0 + tl] : t0 + tl;
       const float* pp = a.ssq_in + (u64)tok * np;
       const u32 lo = np * part / parts, hi = np * (part + 1) / parts;
@@ -97,7 +98,7 @@ __device__ __forceinline__ void compute_rstd(const MfmaGemmArgs& a, u32 t0, u32 
       }
     }
     float* scratch = &sh.red[0][0][0][0];
-    scratch[part * span + tl] = s;
+    if (tid < BLK_THREADS) scratch[part * span + tl] = s;
     __syncthreads();
     if (tid < count) {
       float tot = 0.f;
@@ -191,20 +192,24 @@ __device__ __forceinline__ bf16x8_t ld_tile_stream(const bf16_t* p) {
   return *(const bf16x8_t*)&v;
 }
 
-template <int U, int TW>
+template <int U, int NW, int TW>
 struct StreamBuf {
-  bf16x8_t w[U];
+  bf16x8_t w[U][NW];
   bf16x8_t x[U][TW];
 };
 
-template <int EPI, int TW>
+// NW consecutive 16-row weight tiles per workgroup: every activation tile a wave loads is used for NW MFMAs, which
+// divides the L2 traffic of the activation operand by NW (it is TW/NW times the weight bytes).
+template <int EPI, int NW, int TW>
 __device__ __forceinline__ void gemm_stream(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg) {
-  constexpr int U = TW == 1 ? 8 : (TW == 2 ? 6 : 4);   // k-tiles per batch of loads
+  constexpr int U = NW == 1 ? (TW == 1 ? 8 : (TW == 2 ? 6 : 4)) : ((NW * TW >= 8) ? 2 : (NW + TW >= 5 ? 3 : 4));   // k-tiles per batch
   const u32 lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const u32 NT = (a.N + 15) / 16, KT = a.K / 32;
-  const u32 kb = (u32)((u64)KT * w / 4), ke = (u32)((u64)KT * (w + 1) / 4);
-  const u32 nbatch = (ke - kb + U - 1) / U;
-  if (wg >= NT) return;
+  const u32 NG = (NT + NW - 1) / NW;                       // groups of NW tiles
+  const u32 KS = blockDim.x >> 6;                          // waves of the workgroup: each takes a slice of K
+  const u32 kb = (u32)((u64)KT * w / KS), ke = (u32)((u64)KT * (w + 1) / KS);
+  const u32 nbatch = (KT / KS + (KT % KS ? 1 : 0) + U - 1) / U;   // same count in every wave (loads past `ke` are zeros)
+  if (wg >= NG) return;
   // per-lane offsets (in elements) of this lane's 16 bytes inside the token blocks of one k-tile
   u32 xoff[TW];
 #pragma unroll
@@ -215,52 +220,67 @@ __device__ __forceinline__ void gemm_stream(const MfmaGemmArgs& a, MfmaShared& s
   }
   const u64 xk_stride = (u64)a.TBS * 512;
   const bf16x8_t zero = {0, 0, 0, 0, 0, 0, 0, 0};
-  auto issue = [&](StreamBuf<U, TW>& b, u32 nt, u32 kt0) {
-    const bf16_t* wp = a.Wp + ((u64)nt * KT) * 512 + lane * 8;
+  auto issue = [&](StreamBuf<U, NW, TW>& b, u32 ng, u32 kt0) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const u32 kt = kt0 + u;
       const bool ok = kt < ke;
-      b.w[u] = ok ? ld_tile_stream(wp + (u64)kt * 512) : zero;
+#pragma unroll
+      for (int i = 0; i < NW; ++i) {
+        const u32 nt = min(ng * NW + i, NT - 1);           // a tile past the end is computed and dropped
+        b.w[u][i] = ok ? ld_tile_stream(a.Wp + ((u64)nt * KT + kt) * 512 + lane * 8) : zero;
+      }
 #pragma unroll
       for (int tw = 0; tw < TW; ++tw) b.x[u][tw] = ok ? ld_tile(a.Xp + (u64)kt * xk_stride + xoff[tw]) : zero;
     }
   };
-  // Software pipeline over the flat sequence of (tile, batch) steps of this workgroup: while one buffer is consumed
-  // by the MFMAs, the loads of the following step (possibly the first batch of the next tile) fill the other.
-  // The two buffers swap roles by code position (no register copies, which would wait for the loads in flight).
-  StreamBuf<U, TW> bufA, bufB;
-  u32 nt = wg, b = 0;
-  floatx4_t acc[TW];
+  // Software pipeline over the flat sequence of (tile group, batch) steps of this workgroup: while one buffer is
+  // consumed by the MFMAs, the loads of the following step (possibly the first batch of the next group) fill the
+  // other. The two buffers swap roles by code position (no register copies, which would wait for loads in flight).
+  StreamBuf<U, NW, TW> bufA, bufB;
+  u32 ng = wg, b = 0;
+  floatx4_t acc[NW][TW];
 #pragma unroll
-  for (int tw = 0; tw < TW; ++tw) acc[tw] = floatx4_t{0.f, 0.f, 0.f, 0.f};
-  issue(bufA, nt, kb);               // the first loads are in flight while the norm scales are computed
+  for (int i = 0; i < NW; ++i)
+#pragma unroll
+    for (int tw = 0; tw < TW; ++tw) acc[i][tw] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+  issue(bufA, ng, kb);               // the first loads are in flight while the norm scales are computed
   compute_rstd(a, 0, 64, sh);
-  auto step = [&](StreamBuf<U, TW>& use, StreamBuf<U, TW>& fill) -> bool {
+  auto step = [&](StreamBuf<U, NW, TW>& use, StreamBuf<U, NW, TW>& fill) -> bool {
     const bool last = b + 1 >= nbatch;
-    const u32 nnt = last ? nt + nwg : nt;
-    if (nnt < NT) issue(fill, nnt, last ? kb : kb + (b + 1) * U);
-    if (b < nbatch) {
+    const u32 nng = last ? ng + nwg : ng;
+    if (nng < NG) issue(fill, nng, last ? kb : kb + (b + 1) * U);
+    {
 #pragma unroll
       for (int u = 0; u < U; ++u)
 #pragma unroll
-        for (int tw = 0; tw < TW; ++tw) acc[tw] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(use.w[u], use.x[u][tw], acc[tw], 0, 0, 0);
+        for (int i = 0; i < NW; ++i)
+#pragma unroll
+          for (int tw = 0; tw < TW; ++tw)
+            acc[i][tw] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(use.w[u][i], use.x[u][tw], acc[i][tw], 0, 0, 0);
     }
     if (!last) { ++b; return true; }
-    __syncthreads();   // the previous tile's reduction has been read
+    // reduce the four K-quarters through LDS, one weight tile of the group at a time
 #pragma unroll
-    for (int tw = 0; tw < TW; ++tw) *(floatx4_t*)&sh.red[w][tw][lane][0] = acc[tw];
-    __syncthreads();
-    if (w < TW) {      // wave w finishes token block w: sum the four K-quarters in a fixed order
-      const floatx4_t s = (*(floatx4_t*)&sh.red[0][w][lane][0] + *(floatx4_t*)&sh.red[1][w][lane][0]) +
-                          (*(floatx4_t*)&sh.red[2][w][lane][0] + *(floatx4_t*)&sh.red[3][w][lane][0]);
-      epilogue_tile<EPI>(a, s, nt, w * 16, &sh.rstd[w * 16]);
+    for (int i = 0; i < NW; ++i) {
+      __syncthreads();   // the previous reduction has been read
+#pragma unroll
+      for (int tw = 0; tw < TW; ++tw) *(floatx4_t*)&sh.red[w][tw][lane][0] = acc[i][tw];
+      __syncthreads();
+      if (w < TW && ng * NW + i < NT) {      // wave w finishes token block w: fixed summation order
+        floatx4_t s = (*(floatx4_t*)&sh.red[0][w][lane][0] + *(floatx4_t*)&sh.red[1][w][lane][0]) +
+                      (*(floatx4_t*)&sh.red[2][w][lane][0] + *(floatx4_t*)&sh.red[3][w][lane][0]);
+        if (KS == 8)
+          s += (*(floatx4_t*)&sh.red[4][w][lane][0] + *(floatx4_t*)&sh.red[5][w][lane][0]) +
+               (*(floatx4_t*)&sh.red[6][w][lane][0] + *(floatx4_t*)&sh.red[7][w][lane][0]);
+        epilogue_tile<EPI>(a, s, ng * NW + i, w * 16, &sh.rstd[w * 16]);
+      }
+#pragma unroll
+      for (int tw = 0; tw < TW; ++tw) acc[i][tw] = floatx4_t{0.f, 0.f, 0.f, 0.f};
     }
-#pragma unroll
-    for (int tw = 0; tw < TW; ++tw) acc[tw] = floatx4_t{0.f, 0.f, 0.f, 0.f};
-    nt = nnt;
+    ng = nng;
     b = 0;
-    return nt < NT;
+    return ng < NG;
   };
   for (;;) {
     if (!step(bufA, bufB)) break;
@@ -272,6 +292,7 @@ __device__ __forceinline__ void gemm_stream(const MfmaGemmArgs& a, MfmaShared& s
 template <int EPI>
 __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg) {
   const u32 lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const bool spare = w >= 4;                               // waves 4..7 of an 8-wave launch only join the barriers
   const u32 NT = (a.N + 15) / 16, KT = a.K / 32;
   const u32 nblocks = (NT + 7) / 8, tblocks = (a.T + 127) / 128;
   const u32 wn = w & 1, wt = w >> 1;
@@ -279,6 +300,7 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& a, MfmaShared& sh,
   for (u32 item = wg; item < nblocks * tblocks; item += nwg) {
     const u32 nb = item % nblocks, tb = item / nblocks;
     compute_rstd(a, tb * 128, 128, sh);
+    if (spare) continue;
     const u32 nt0 = nb * 8 + wn * 4;
     u32 xoff[4];
 #pragma unroll
@@ -330,13 +352,23 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& a, MfmaShared& sh,
   }
 }
 
+template <int EPI, int TW>
+__device__ __forceinline__ void gemm_stream_nw(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg) {
+  // enough tile groups to occupy the chip (one workgroup per group, >= 1.5 per CU) decides the group size
+  const u32 NT = (a.N + 15) / 16;
+  if (TW == 1) gemm_stream<EPI, 1, TW>(a, sh, wg, nwg);   // one token block: the activation traffic equals the weights'
+  else if (NT >= 1536) gemm_stream<EPI, 4, TW>(a, sh, wg, nwg);
+  else if (NT >= 768 || (blockDim.x == 512 && NT >= 256)) gemm_stream<EPI, 2, TW>(a, sh, wg, nwg);
+  else gemm_stream<EPI, 1, TW>(a, sh, wg, nwg);
+}
+
 template <int EPI>
 __device__ __forceinline__ void gemm_mfma(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg) {
   if (a.T == 0) return;
-  if (a.T <= 16) gemm_stream<EPI, 1>(a, sh, wg, nwg);
-  else if (a.T <= 32) gemm_stream<EPI, 2>(a, sh, wg, nwg);
-  else if (a.T <= 48) gemm_stream<EPI, 3>(a, sh, wg, nwg);
-  else if (a.T <= 64) gemm_stream<EPI, 4>(a, sh, wg, nwg);
+  if (a.T <= 16) gemm_stream_nw<EPI, 1>(a, sh, wg, nwg);
+  else if (a.T <= 32) gemm_stream_nw<EPI, 2>(a, sh, wg, nwg);
+  else if (a.T <= 48) gemm_stream_nw<EPI, 3>(a, sh, wg, nwg);
+  else if (a.T <= 64) gemm_stream_nw<EPI, 4>(a, sh, wg, nwg);
   else gemm_tile<EPI>(a, sh, wg, nwg);
 }
 

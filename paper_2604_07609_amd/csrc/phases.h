@@ -12,7 +12,8 @@
 enum {
   PH_EMBED = 0,
   PH_NORM1, PH_QKV, PH_ROPE, PH_ATTN, PH_OPROJ, PH_NORM2, PH_GATEUP, PH_DOWN,   // per layer
-  PH_FINAL_NORM, PH_LM_HEAD, PH_SAMPLE
+  PH_FINAL_NORM, PH_LM_HEAD, PH_SAMPLE,
+  PH_ATTN_COMBINE   // bf16 path only, directly after PH_ATTN of the same layer
 };
 #define PH_LAYER_FIRST PH_NORM1
 #define PH_LAYER_LAST PH_DOWN
@@ -38,6 +39,7 @@ template <> struct PhaseSharedOf<PH_NORM1> { typedef SmallPhaseShared type; };
 template <> struct PhaseSharedOf<PH_NORM2> { typedef SmallPhaseShared type; };
 template <> struct PhaseSharedOf<PH_FINAL_NORM> { typedef SmallPhaseShared type; };
 template <> struct PhaseSharedOf<PH_ROPE> { typedef SmallPhaseShared type; };
+template <> struct PhaseSharedOf<PH_ATTN_COMBINE> { typedef SmallPhaseShared type; };
 
 template <typename WT>
 __device__ __forceinline__ void run_phase_t(const DevCtx& c, int ph, u32 layer, void* shp, u32 wg, u32 nwg) {
@@ -91,6 +93,7 @@ __device__ __forceinline__ void run_phase_bf16(const DevCtx& c, int ph, u32 laye
       gemm_mfma<EPI_QKV_ROPE>(a, sh.mfma, wg, nwg);
       break;
     case PH_ATTN: phase_attention_mfma(c, layer, sh.attn_mfma, wg, nwg); break;
+    case PH_ATTN_COMBINE: attn_decode_combine(c, wg, nwg); break;
     case PH_OPROJ:
       a.Wp = P->wo; a.Xp = c.aq; a.N = c.d; a.K = c.nq * c.hd; a.x = c.x; a.ldx = c.d; a.g_next = c.layers[layer].g2;
       a.Xp_next = c.xq; a.ssq_out = c.ssq;

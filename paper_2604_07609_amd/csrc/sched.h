@@ -230,7 +230,7 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
   __syncthreads();
 
   // ---- (5) allocate + (6) metadata, batch slot ascending ----------------------------------------------------
-  u32 n_seqs = 0, n_tok = 0, n_alloc = 0, n_qt = 0, max_q = 0, max_ctx = 0;
+  u32 n_seqs = 0, n_tok = 0, n_alloc = 0, n_qt = 0, n_ch = 0, max_q = 0, max_ctx = 0;
   if (kind != KIND_IDLE) {
     for (u32 base = 0; base < c.max_batch; base += BLK_THREADS) {
       const u32 b = base + tid;
@@ -255,7 +255,9 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
         ctx = r.ctx_len;
         nb = r.n_blocks;
       }
-      u32 tots, tota, tott, totq;
+      u32 tots, tota, tott, totq, totc;
+      const u32 ctx_after = in ? (kind == KIND_DECODE ? ctx + 1 : ntok) : 0u;
+      const u32 coff = n_ch + block_excl_scan((ctx_after + 511) / 512, totc, sh.wave_part);
       const u32 qoff = n_qt + block_excl_scan((ntok + 15) / 16, totq, sh.wave_part2);
       const u32 si = n_seqs + block_excl_scan(in ? 1u : 0u, tots, sh.wave_part);
       const u32 aoff = n_alloc + block_excl_scan(nalloc, tota, sh.wave_part2);
@@ -268,6 +270,7 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
         c.seq_bslot[si] = b;
         c.cu_seqlens[si] = toff;
         c.cu_qtiles[si] = qoff;
+        c.cu_chunks[si] = coff;
         c.last_idx[si] = toff + ntok - 1;
         if (kind == KIND_DECODE) {
           c.input_ids[toff] = r.last_token;
@@ -292,12 +295,14 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
       n_alloc += tota;
       n_tok += tott;
       n_qt += totq;
+      n_ch += totc;
     }
     top -= n_alloc;
     __syncthreads();
     if (tid == 0) {
       c.cu_seqlens[n_seqs] = n_tok;
       c.cu_qtiles[n_seqs] = n_qt;
+      c.cu_chunks[n_seqs] = n_ch;
     }
     if (kind == KIND_PREFILL) {
       // token-level metadata of the prompts: one sequence after the other, threads over its tokens

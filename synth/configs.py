@@ -18,6 +18,11 @@ MODEL_CONFIGS = {
                      vocab=2500, dtype=1, rms_eps=1e-5, rope_theta=500000.0),
     "mini_gqa128": dict(n_layers=2, d_model=512, n_q_heads=4, n_kv_heads=1, head_dim=128, d_ffn=1152,
                         vocab=3001, dtype=1, rms_eps=1e-5, rope_theta=500000.0),
+    # wide FFN / vocabulary: the streaming GEMM takes 2 resp. 4 weight tiles per workgroup at these widths
+    "mini_wide2": dict(n_layers=1, d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=64, d_ffn=6400,
+                       vocab=13001, dtype=1, rms_eps=1e-5, rope_theta=10000.0),
+    "mini_wide4": dict(n_layers=1, d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=64, d_ffn=12288,
+                       vocab=24601, dtype=1, rms_eps=1e-5, rope_theta=10000.0),
 }
 
 # kv_num_blocks == 0 means "derived from the workload" (churn: 60 % of peak demand)
@@ -34,6 +39,10 @@ ENGINE_CONFIGS = {
                      max_prefill_tokens=256, ring_slots=32, eos_token_id=-1),
     "mini_gqa128": dict(kv_block_size=16, kv_num_blocks=64, max_batch=5, max_seq_len=200,
                         max_prefill_tokens=300, ring_slots=16, eos_token_id=-1),
+    "mini_wide2": dict(kv_block_size=16, kv_num_blocks=400, max_batch=64, max_seq_len=160,
+                       max_prefill_tokens=512, ring_slots=128, eos_token_id=-1),
+    "mini_wide4": dict(kv_block_size=16, kv_num_blocks=400, max_batch=64, max_seq_len=160,
+                       max_prefill_tokens=512, ring_slots=128, eos_token_id=-1),
 }
 
 

@@ -60,6 +60,36 @@ def test_bf16_wide_decode_batches(lib, max_batch, n_req):
     print("max_batch", max_batch, "worst relative logit error", worst)
 
 
+@pytest.mark.parametrize("name,max_batch,n_req", [("mini_wide2", 12, 14), ("mini_wide2", 40, 44), ("mini_wide4", 12, 14),
+                                                  ("mini_wide4", 30, 34), ("mini_wide4", 60, 64)])
+def test_bf16_wide_matrices(lib, name, max_batch, n_req):
+    """FFN and vocabulary wide enough for the streaming GEMM to take 2 resp. 4 weight tiles per workgroup, with a
+    ragged last group and a partial last tile, at 1..4 token blocks."""
+    cfg, eng, raw, blob = setup(name, 35)
+    eng = dict(eng, max_batch=max_batch)
+    reqs = synth.make_workload("mini", cfg["vocab"], 135 + max_batch, n_requests=n_req)
+    for r in reqs:
+        r["max_new_tokens"] = min(r["max_new_tokens"], 4)
+        r["prompt"] = r["prompt"][:40]
+    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2)
+    print(name, "max_batch", max_batch, "worst relative logit error", worst)
+
+
+@pytest.mark.parametrize("name", ["mini_gqa128", "mini_gqa"])
+def test_bf16_long_contexts(lib, name):
+    """Contexts of 500..1100 tokens: decode attention works in 512-token chunks whose partial results a second
+    kernel merges; prefill attention walks up to 65 KV blocks; one short context shares the batch."""
+    cfg, eng, raw, blob = setup(name, 37)
+    eng = dict(eng, max_seq_len=1300, kv_num_blocks=230, max_prefill_tokens=2048, max_batch=4)
+    rng = np.random.default_rng(5)
+    reqs = []
+    for i, P in enumerate([520, 1040, 7, 511]):
+        reqs.append(dict(arrival_s=0.0, prompt=rng.integers(0, cfg["vocab"], P).astype(np.int32), max_new_tokens=5,
+                         temperature=0.0, top_k=0, top_p=1.0, seed=i))
+    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2)
+    print(name, "long contexts: worst relative logit error", worst)
+
+
 def test_fp32_gqa_stepwise_logits(lib):
     cfg, eng, raw, blob = setup("mini_gqa", 51)
     cfg = dict(cfg, dtype=0)
