@@ -31,7 +31,7 @@ PHASE_NAMES = {2: "k_qkv", 5: "k_oproj", 7: "k_gateup", 8: "k_down", 10: "k_lm_h
 WORKLOADS = {
     "tiny": dict(model="tiny", workload="tiny", wseed=1000, rseed=2000, steps=30, warmup=3),
     "churn": dict(model="churn", workload="churn", wseed=1001, rseed=2001, steps=600, warmup=20),
-    "llama3_8b": dict(model="llama3_8b", workload="llama3_8b", wseed=1002, rseed=2002, steps=200, warmup=10),
+    "llama3_8b": dict(model="llama3_8b", workload="llama3_8b", wseed=1002, rseed=2002, steps=200, warmup=20),
     "sched_stress": dict(model="sched_stress", workload="sched_stress", wseed=1003, rseed=2003, steps=100, warmup=5),
 }
 
@@ -67,6 +67,18 @@ def decode_step_bytes(cfg, n_seqs, ctx_tokens):
     return w + kv_tok * (ctx_tokens + n_seqs) + 2 * 4 * n_seqs * V
 
 
+def read_traffic(kernel, workload):
+    """HBM bytes per launch from the committed counter summary (profiles/<kernel>_<workload>_hbm_traffic.md), or None."""
+    path = os.path.join(ROOT, "profiles", "%s_%s_hbm_traffic.md" % (kernel, workload))
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(cfg, eng, raw, reqs, budget_tokens, n_req=4, prompt_cap=None):
     """The oracle, as it stands, on a bounded sample of the same workload."""
     from oracle import model as M, serve as SV
@@ -77,6 +89,10 @@ def cpu_baseline(cfg, eng, raw, reqs, budget_tokens, n_req=4, prompt_cap=None):
         if prompt_cap:
             r["prompt"] = r["prompt"][:prompt_cap]
         sample.append(r)
+    # the oracle keeps its KV pool as dense fp64 arrays: size the pool to the sample, not to the engine's 64 GiB
+    bs = eng["kv_block_size"]
+    need = sum(max(1, -(-(len(r["prompt"]) + r["max_new_tokens"] - 1) // bs)) for r in sample)
+    eng = dict(eng, kv_num_blocks=need, max_batch=len(sample))
     t0 = time.perf_counter()
     ev, _ = SV.serve(cfg, M.Weights(cfg, raw), eng, sample)
     dt = time.perf_counter() - t0
@@ -154,7 +170,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0)
     ap.add_argument("--warmup", type=int, default=-1)
-    ap.add_argument("--workload", default=os.environ.get("BLINK_BENCH_WORKLOAD", "churn"), choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default=os.environ.get("BLINK_BENCH_WORKLOAD", "llama3_8b"), choices=sorted(WORKLOADS))
     ap.add_argument("--phase", type=int, default=7, help="forward phase whose kernel is timed for the roofline")
     ap.add_argument("--requests", type=int, default=0)
     ap.add_argument("--max-batch", type=int, default=0, help="override the engine's batch slots")
@@ -200,6 +216,7 @@ def main():
         ev = e.drain(16384)
         trace = e.trace(K + W + 16)
         phase_ms = e.phase_times_ms()
+        e.calibration_copy(64 << 20)    # one plain copy kernel of known size: scales the HBM counters of a --pmc run
     finally:
         e.shutdown()
 
@@ -216,19 +233,37 @@ def main():
     itl = (evs["device_ns"][1:].astype(np.int64) - evs["device_ns"][:-1].astype(np.int64))[same] / 1e6
     sched_us = (tr["t_sched_end_ns"].astype(np.int64) - tr["t_sched_begin_ns"].astype(np.int64)) / 1e3
     dec = tr["kind"] == 2
-    # roofline of the timed kernel: same launches as the timed region (the first `iters` enqueued iterations)
+    # Roofline of the timed kernel. Its launches in decode iterations stream the weight matrix once (HBM bound); its
+    # launches in prefill iterations are compute bound and are reported beside them against the MFMA peak.
     per_layer = 1 if args.phase in (10,) else cfg["n_layers"]
     pm = phase_ms[:iters]
-    n_launch = len(pm) * per_layer
-    bytes_total = float(sum(phase_bytes(cfg, args.phase, int(t["n_tokens"]), int(t["n_seqs"])) for t in tr[: len(pm)])) * per_layer
-    avg_us = 1e3 * float(pm.sum()) / max(1, n_launch)
-    achieved = bytes_total / max(1e-12, float(pm.sum()) * 1e-3) / 1e9
-    pm_dec = pm[dec[: len(pm)]] if len(pm) else pm
-    dec_bytes = float(sum(phase_bytes(cfg, args.phase, int(t["n_tokens"]), int(t["n_seqs"])) for t in tr[: len(pm)][dec[: len(pm)]])) * per_layer
-    roofline = dict(bound="hbm", kernel=PHASE_NAMES.get(args.phase, str(args.phase)), achieved=round(achieved, 2), peak=HBM_PEAK_GBS,
-                    unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None, launches=n_launch,
-                    avg_launch_us=round(avg_us, 3), algorithmic_bytes_per_launch=round(bytes_total / max(1, n_launch)),
-                    decode_only_GBs=round(dec_bytes / max(1e-12, float(pm_dec.sum()) * 1e-3) / 1e9, 2) if len(pm_dec) else None)
+    trp = tr[: len(pm)]
+    decp = dec[: len(pm)]
+
+    def klass(sel):
+        n = int(sel.sum()) * per_layer
+        if n == 0:
+            return None
+        ms = float(pm[sel].sum())
+        by = float(sum(phase_bytes(cfg, args.phase, int(t["n_tokens"]), int(t["n_seqs"])) for t in trp[sel])) * per_layer
+        return dict(launches=n, avg_launch_us=round(1e3 * ms / n, 3), bytes_per_launch=round(by / n), GBs=round(by / (ms * 1e-3) / 1e9, 2))
+
+    d_cls, p_cls, a_cls = klass(decp), klass(~decp), klass(np.ones(len(pm), dtype=bool))
+    kname = PHASE_NAMES.get(args.phase, str(args.phase))
+    traffic = read_traffic(kname, args.workload)
+    roofline = dict(bound="hbm", kernel=kname, launch_class="launches of decode iterations (T = batch <= 64: weight streaming)",
+                    achieved=d_cls["GBs"] if d_cls else None, peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(d_cls["GBs"] / HBM_PEAK_GBS, 4) if d_cls else None, traffic=traffic,
+                    launches=d_cls["launches"] if d_cls else 0, avg_launch_us=d_cls["avg_launch_us"] if d_cls else None,
+                    algorithmic_bytes_per_launch=d_cls["bytes_per_launch"] if d_cls else None,
+                    all_launches=a_cls)
+    if p_cls:
+        es = 2 if cfg["dtype"] == 1 else 4
+        wbytes = phase_bytes(cfg, args.phase, 0, 0)
+        flops = float(sum(2.0 * (wbytes / es) * int(t["n_tokens"]) for t in trp[~decp])) * per_layer
+        p_cls["TFLOPs"] = round(flops / (float(pm[~decp].sum()) * 1e-3) / 1e12, 1)
+        p_cls["mfma_peak_TFLOPs"] = 2500.0 if cfg["dtype"] == 1 else 157.3
+        roofline["prefill_launches"] = p_cls
     # whole-step view of the decode iterations: algorithmic bytes of the step over its duration on the device clock
     step_ns = np.diff(tr["t_sched_begin_ns"].astype(np.int64))
     ctx = np.zeros(len(tr))

@@ -11,7 +11,7 @@ ERR_INVAL, ERR_TOO_LARGE, ERR_FULL, ERR_DEVICE, ERR_STATE = -1, -2, -3, -4, -5
 EVENT_FIRST, EVENT_LAST = 1, 2
 
 EXPORTS = ["blink_init", "blink_submit", "blink_run", "blink_wait", "blink_stop", "blink_poll_outputs", "blink_shutdown",
-           "blink_get_trace", "blink_get_stats", "blink_debug_read", "blink_time_phase", "blink_get_phase_times",
+           "blink_get_trace", "blink_get_stats", "blink_debug_read", "blink_time_phase", "blink_get_phase_times", "blink_calibration_copy",
            "blink_last_error"]
 
 
@@ -81,6 +81,7 @@ def load_library():
     lib.blink_get_stats.argtypes = [vp, C.POINTER(Stats)]
     lib.blink_debug_read.argtypes = [vp, u32, vp, u64, C.POINTER(u64)]
     lib.blink_time_phase.argtypes = [vp, C.c_int32]
+    lib.blink_calibration_copy.argtypes = [vp, u64]
     lib.blink_get_phase_times.argtypes = [vp, vp, u64, C.POINTER(u64)]
     lib.blink_last_error.restype = C.c_char_p
     for n in EXPORTS[:-1]:
@@ -171,6 +172,9 @@ class Engine:
 
     def time_phase(self, phase):
         _check(self.lib, self.lib.blink_time_phase(self.h, int(phase)))
+
+    def calibration_copy(self, nbytes):
+        _check(self.lib, self.lib.blink_calibration_copy(self.h, int(nbytes)))
 
     def phase_times_ms(self, cap=1 << 20):
         buf = np.zeros(cap, dtype=np.float32)

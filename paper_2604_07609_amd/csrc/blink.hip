@@ -87,6 +87,11 @@ __global__ void __launch_bounds__(BLK_THREADS) k_pack_weights(const bf16_t* src,
   pack_weights(src, dst, N, K, pair_rows, perm_hd, (u64)blockIdx.x * blockDim.x + threadIdx.x, (u64)gridDim.x * blockDim.x);
 }
 
+// plain copy of `n16` 16-byte words: the known-size kernel that calibrates the HBM traffic counters
+__global__ void __launch_bounds__(BLK_THREADS) k_copy_calibration(const uint4* src, uint4* dst, u64 n16) {
+  for (u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (u64)gridDim.x * blockDim.x) dst[i] = src[i];
+}
+
 __global__ void k_open_window(SchedState* ss, u64 iter_limit) {
   ss->stopped = 0;
   ss->iter_limit = iter_limit;
@@ -767,6 +772,26 @@ extern "C" int blink_get_phase_times(blink_engine* e, float* ms_per_iteration, u
   const u64 n = std::min<u64>(cap, e->phase_ms.size());
   for (u64 i = 0; i < n; ++i) ms_per_iteration[i] = e->phase_ms[i];
   *n_out = n;
+  return BLINK_OK;
+}
+
+extern "C" int blink_calibration_copy(blink_engine* e, uint64_t bytes) {
+  g_err.clear();
+  if (!e) return fail(BLINK_ERR_INVAL, "null engine");
+  if (e->loop_active.load()) return fail(BLINK_ERR_STATE, "stop the loop first");
+  // source and destination: the two halves of the KV pool's first bytes would disturb state; use the packed
+  // activation buffers of the bf16 path or the fp32 activation buffers (scratch between iterations)
+  const DevCtx& c = e->ctx;
+  void* src = c.dtype == 1 ? (void*)c.hq : (void*)c.gu;
+  void* dst = c.dtype == 1 ? (void*)c.xq : (void*)c.h;
+  const u64 cap_src = c.dtype == 1 ? (u64)c.TBS * 16 * c.F * 2 : (u64)c.maxT * 2 * c.F * 4;
+  const u64 cap_dst = c.dtype == 1 ? (u64)c.TBS * 16 * c.d * 2 : (u64)c.maxT * c.d * 4;
+  const u64 cap = std::min(cap_src, cap_dst);
+  if (bytes == 0 || bytes > cap || (bytes & 15)) return fail(BLINK_ERR_INVAL, "bytes must be a multiple of 16 in (0, %llu]", (unsigned long long)cap);
+  HIPCHK(hipSetDevice(e->cfg.device));
+  hipLaunchKernelGGL(k_copy_calibration, dim3(e->grid * 4), dim3(BLK_THREADS), 0, e->compute, (const uint4*)src, (uint4*)dst, bytes / 16);
+  HIPCHK(hipGetLastError());
+  HIPCHK(hipStreamSynchronize(e->compute));
   return BLINK_OK;
 }
 
