@@ -37,21 +37,24 @@ WORKLOADS = {
 
 
 def phase_bytes(cfg, phase, n_tokens, n_seqs):
-    """Algorithmic HBM bytes of one launch of a GEMM phase: the weight matrix once, activations in and out."""
-    es = 2 if cfg["dtype"] == 1 else 4
+    """Algorithmic HBM bytes of one launch of a GEMM phase: the weight matrix once, plus the activations it reads
+    and writes once (bf16 path: bf16 operands, fp32 residual stream read + written; fp32 path: fp32 throughout)."""
+    bf = cfg["dtype"] == 1
+    es, ea = (2, 2) if bf else (4, 4)
     d, F, V = cfg["d_model"], cfg["d_ffn"], cfg["vocab"]
     qkv_n = (cfg["n_q_heads"] + 2 * cfg["n_kv_heads"]) * cfg["head_dim"]
     no = cfg["n_q_heads"] * cfg["head_dim"]
-    if phase == 2:
-        return es * qkv_n * d + 4 * n_tokens * (d + qkv_n)
-    if phase == 5:
-        return es * d * no + 4 * n_tokens * (no + 2 * d)
-    if phase == 7:
-        return es * 2 * F * d + 4 * n_tokens * (d + 2 * F)
+    T, B = n_tokens, n_seqs
+    if phase == 2:      # in: normalised x; out: q, k, v
+        return es * qkv_n * d + T * (ea * d + ea * qkv_n)
+    if phase == 5:      # in: attention output; residual read + write; bf16 path also writes the next packed operand
+        return es * d * no + T * (ea * no + 8 * d + (2 * d if bf else 0))
+    if phase == 7:      # in: normalised x; out: silu(gate)*up (bf16 path) or gate and up (fp32 path)
+        return es * 2 * F * d + T * (ea * d + (2 * F if bf else 8 * F))
     if phase == 8:
-        return es * d * F + 4 * n_tokens * (2 * F + 2 * d)
-    if phase == 10:
-        return es * V * d + 4 * n_seqs * (d + V)
+        return es * d * F + T * ((2 * F if bf else 8 * F) + 8 * d + (2 * d if bf else 0))
+    if phase == 10:     # logits are fp32
+        return es * V * d + B * (ea * d + 4 * V)
     raise ValueError(phase)
 
 
