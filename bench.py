@@ -110,6 +110,39 @@ def cpu_baseline(cfg, eng, raw, reqs, budget_tokens, n_req=4, prompt_cap=None):
                           budget_tokens, len(ev), dt))
 
 
+def _stress_worker(stop, mib):
+    """Host memory-bandwidth stressor: streaming copies between two buffers until told to stop."""
+    a = np.ones(mib << 17, dtype=np.float64)
+    b = np.empty_like(a)
+    while not stop.is_set():
+        np.copyto(b, a)
+        np.copyto(a, b)
+
+
+class Stressor:
+    """One streaming-copy process per host core (the synthetic stand-in for the paper's co-located tenants)."""
+
+    def __init__(self, n=None, mib=256):
+        import multiprocessing as mp
+        self.n = n or int(os.environ.get("OMP_NUM_THREADS", 0)) or os.cpu_count()
+        ctx = mp.get_context("spawn")
+        self.stop = ctx.Event()
+        self.procs = [ctx.Process(target=_stress_worker, args=(self.stop, mib), daemon=True) for _ in range(self.n)]
+
+    def __enter__(self):
+        for p in self.procs:
+            p.start()
+        time.sleep(1.0)
+        return self
+
+    def __exit__(self, *a):
+        self.stop.set()
+        for p in self.procs:
+            p.join(timeout=10)
+            if p.is_alive():
+                p.terminate()
+
+
 def open_loop(B, cfg, eng, blob, reqs, seconds):
     """The workload's own arrival process: a producer thread submits each request at its arrival time while the
     loop runs; the main thread polls. Returns TTFT (host clocks: submit -> first event seen) and ITL (device
@@ -179,6 +212,8 @@ def main():
     ap.add_argument("--max-batch", type=int, default=0, help="override the engine's batch slots")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--open-loop-seconds", type=float, default=8.0, help="0: skip the run with the workload's own arrivals")
+    ap.add_argument("--interference", action="store_true",
+                    help="repeat the open-loop run with a host memory-bandwidth stressor on every core and report the ratios")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -296,6 +331,18 @@ def main():
     }
     if args.open_loop_seconds > 0:
         out["open_loop"] = open_loop(B, cfg, eng, blob, reqs, args.open_loop_seconds)
+        if args.interference and out["open_loop"]:
+            with Stressor() as st:
+                stressed = open_loop(B, cfg, eng, blob, reqs, args.open_loop_seconds)
+            iso = out["open_loop"]
+            ratio = lambda a, b: round(a / b, 3) if a and b else None
+            out["interference"] = dict(stressor="%d processes, streaming copies of 2 x 256 MiB each" % st.n, stressed=stressed,
+                                       ratio_stressed_over_isolated=dict(
+                                           itl_p50=ratio(stressed["itl_ms"]["p50"], iso["itl_ms"]["p50"]),
+                                           itl_p99=ratio(stressed["itl_ms"]["p99"], iso["itl_ms"]["p99"]),
+                                           ttft_p50=ratio(stressed["ttft_ms"]["p50"], iso["ttft_ms"]["p50"]),
+                                           ttft_p99=ratio(stressed["ttft_ms"]["p99"], iso["ttft_ms"]["p99"]),
+                                           output_tokens_per_s=ratio(stressed["output_tokens_per_s"], iso["output_tokens_per_s"])))
     del blob
     if not args.no_cpu_baseline:
         budget = args.cpu_sample_tokens or {"tiny": 32, "churn": 16, "llama3_8b": 2, "sched_stress": 16}[args.workload]

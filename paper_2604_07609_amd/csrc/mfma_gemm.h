@@ -298,7 +298,9 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& a, MfmaShared& sh,
   const u32 wn = w & 1, wt = w >> 1;
   const u64 xk_stride = (u64)a.TBS * 512;
   for (u32 item = wg; item < nblocks * tblocks; item += nwg) {
-    const u32 nb = item % nblocks, tb = item / nblocks;
+    // token blocks vary fastest: the workgroups running together share a few weight row blocks (each read from HBM once
+    // and then from L2) and sweep all token blocks, whose operand is small enough to stay in L2 / the memory-side cache
+    const u32 tb = item % tblocks, nb = item / tblocks;
     compute_rstd(a, tb * 128, 128, sh);
     if (spare) continue;
     const u32 nt0 = nb * 8 + wn * 4;

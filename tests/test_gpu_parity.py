@@ -75,6 +75,20 @@ def test_bf16_wide_matrices(lib, name, max_batch, n_req):
     print(name, "max_batch", max_batch, "worst relative logit error", worst)
 
 
+def test_bf16_large_prefill_iterations(lib):
+    """Prefill iterations of ~1000 tokens over a wide FFN: the LDS-staged tile schedule of the GEMM with 256-row
+    workgroup tiles (gate/up) beside the 128-row and the direct schedules (the narrower matrices)."""
+    cfg, eng, raw, blob = setup("mini_wide4", 39)
+    eng = dict(eng, max_batch=40, max_prefill_tokens=1100, kv_num_blocks=200)
+    reqs = synth.make_workload("mini", cfg["vocab"], 139, n_requests=44)
+    rng = np.random.default_rng(9)
+    for r in reqs:
+        r["max_new_tokens"] = 3
+        r["prompt"] = rng.integers(0, cfg["vocab"], int(rng.integers(20, 36))).astype(np.int32)
+    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2)
+    print("large prefill: worst relative logit error", worst)
+
+
 @pytest.mark.parametrize("name", ["mini_gqa128", "mini_gqa"])
 def test_bf16_long_contexts(lib, name):
     """Contexts of 500..1100 tokens: decode attention works in 512-token chunks whose partial results a second
