@@ -182,9 +182,9 @@ int blink_debug_read(blink_engine* e, uint32_t what, void* buf, uint64_t cap_byt
  * summed duration in milliseconds of that kernel's launches (one per layer for per-layer phases). */
 int blink_time_phase(blink_engine* e, int32_t phase);
 int blink_get_phase_times(blink_engine* e, float* ms_per_iteration, uint64_t cap, uint64_t* n_out);
-/* Launches one plain device-to-device copy kernel of `bytes` bytes (a multiple of 16, at most the size of the
- * engine's activation scratch) on the compute stream and waits for it: a kernel of known traffic against which
- * hardware HBM counters are scaled. The loop must be stopped; scratch activations are overwritten. */
+/* Launches one plain device-to-device copy kernel of `bytes` bytes (a multiple of 16, at most
+ * 64 MiB, between two buffers set aside at init) on the compute stream and waits for it: a kernel of known traffic
+ * against which hardware HBM counters are scaled. The loop must be stopped. */
 int blink_calibration_copy(blink_engine* e, uint64_t bytes);
 /* Message of the last error on the calling thread ("" if none). The pointer stays valid until the next call. */
 const char* blink_last_error(void);

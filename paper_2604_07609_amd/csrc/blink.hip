@@ -148,6 +148,8 @@ struct blink_engine {
   std::atomic<int> loop_rc{0};
   std::atomic<u32> windows{0};
   bool shut = false;
+  char *calib_src = nullptr, *calib_dst = nullptr;   // buffers of blink_calibration_copy
+  u64 calib_bytes = 64ull << 20;
   u64 weight_bytes = 0, kv_bytes = 0, ring_bytes = 0;
   std::mutex dev_mu;   // serialises hipSetDevice-dependent host calls that allocate nothing
 
@@ -336,6 +338,8 @@ static int init_impl(const blink_config* cfg, blink_engine* e) {
       if (int rc = dalloc(e, &c.attn_part_ml, chunks * c.nkv * G * 2)) return rc;
     }
   }
+  if (int rc = dalloc(e, &e->calib_src, e->calib_bytes)) return rc;
+  if (int rc = dalloc(e, &e->calib_dst, e->calib_bytes)) return rc;
   // ---- KV pool ----
   c.kv_kv_stride = (u64)c.n_blocks * c.nkv * c.bs * c.hd;
   c.kv_layer_stride = 2 * c.kv_kv_stride;
@@ -779,14 +783,9 @@ extern "C" int blink_calibration_copy(blink_engine* e, uint64_t bytes) {
   g_err.clear();
   if (!e) return fail(BLINK_ERR_INVAL, "null engine");
   if (e->loop_active.load()) return fail(BLINK_ERR_STATE, "stop the loop first");
-  // source and destination: the two halves of the KV pool's first bytes would disturb state; use the packed
-  // activation buffers of the bf16 path or the fp32 activation buffers (scratch between iterations)
-  const DevCtx& c = e->ctx;
-  void* src = c.dtype == 1 ? (void*)c.hq : (void*)c.gu;
-  void* dst = c.dtype == 1 ? (void*)c.xq : (void*)c.h;
-  const u64 cap_src = c.dtype == 1 ? (u64)c.TBS * 16 * c.F * 2 : (u64)c.maxT * 2 * c.F * 4;
-  const u64 cap_dst = c.dtype == 1 ? (u64)c.TBS * 16 * c.d * 2 : (u64)c.maxT * c.d * 4;
-  const u64 cap = std::min(cap_src, cap_dst);
+  void* src = e->calib_src;
+  void* dst = e->calib_dst;
+  const u64 cap = e->calib_bytes;
   if (bytes == 0 || bytes > cap || (bytes & 15)) return fail(BLINK_ERR_INVAL, "bytes must be a multiple of 16 in (0, %llu]", (unsigned long long)cap);
   HIPCHK(hipSetDevice(e->cfg.device));
   hipLaunchKernelGGL(k_copy_calibration, dim3(e->grid * 4), dim3(BLK_THREADS), 0, e->compute, (const uint4*)src, (uint4*)dst, bytes / 16);
