@@ -99,7 +99,7 @@ __device__ __forceinline__ void attn_block(const KVTile<HD>& kv, const bf16x8_t 
 }
 
 #define ATTN_CHUNK_BLOCKS 32   // KV blocks (512 tokens) per decode work item
-#define ATTN_WAVES 8          // the attention kernel of the bf16 path runs 512 threads per workgroup
+#define ATTN_WAVES 8          // waves per workgroup of the attention kernel (512 threads: at most 256 registers per lane)
 struct AttnMfmaShared {
   float m[ATTN_WAVES][16], l[ATTN_WAVES][16];
   float o[ATTN_WAVES][8][128];   // [wave][q head of the group][dim]
@@ -139,15 +139,19 @@ __device__ __forceinline__ void attn_decode(const DevCtx& c, u32 layer, AttnMfma
     attn_init(acc);
     const u32 lim[1] = {ctx};
     const u32 b_lo = ch * ATTN_CHUNK_BLOCKS, b_hi = min((ctx + 15) / 16, b_lo + ATTN_CHUNK_BLOCKS);
-    const u32 nb = b_hi - b_lo;                 // 1..32 blocks: at most four per wave
-    // every wave fetches its (up to four) blocks at once: all tiles in flight together
+    const u32 nb = b_hi - b_lo;                 // 1..32 blocks: four per wave with eight waves
+    // every wave takes blocks w, w+nw, ... of the chunk (up to eight): four tiles are in flight at any time, a tile's
+    // registers are refilled as soon as it has been used (rotation by code position, no register copies)
     const u32 nw = blockDim.x >> 6;
     KVTile<HD> t0, t1, t2, t3;
-    const u32 i0 = w, i1 = w + nw, i2 = w + 2 * nw, i3 = w + 3 * nw;
-    auto ld = [&](KVTile<HD>& tl, u32 i) { if (i < nb) { const u64 bs = ((u64)bt[b_lo + i] * c.nkv + g) * tile; kv_load<HD>(Kc + bs, Vc + bs, tl); } };
-    auto us = [&](const KVTile<HD>& tl, u32 i) { if (i < nb) attn_block<HD, 1>(tl, q, (b_lo + i) * 16, lim, acc); };
-    ld(t0, i0); ld(t1, i1); ld(t2, i2); ld(t3, i3);
-    us(t0, i0); us(t1, i1); us(t2, i2); us(t3, i3);
+    auto ld = [&](KVTile<HD>& tl, u32 j) { const u32 i = w + j * nw; if (i < nb) { const u64 bs = ((u64)bt[b_lo + i] * c.nkv + g) * tile; kv_load<HD>(Kc + bs, Vc + bs, tl); } };
+    auto us = [&](const KVTile<HD>& tl, u32 j) { const u32 i = w + j * nw; if (i < nb) attn_block<HD, 1>(tl, q, (b_lo + i) * 16, lim, acc); };
+    ld(t0, 0); ld(t1, 1); ld(t2, 2); ld(t3, 3);
+    us(t0, 0); ld(t0, 4);
+    us(t1, 1); ld(t1, 5);
+    us(t2, 2); ld(t2, 6);
+    us(t3, 3); ld(t3, 7);
+    us(t0, 4); us(t1, 5); us(t2, 6); us(t3, 7);
     __syncthreads();   // the previous item's combine has finished reading LDS
     if (lg == 0) { sh.m[w][lc] = acc.m[0]; sh.l[w][lc] = acc.l[0]; }
 #pragma unroll
@@ -278,9 +282,9 @@ __device__ __forceinline__ void attn_prefill_hd(const DevCtx& c, u32 layer, u32 
     case 1: attn_prefill<HD, 1>(c, layer, wg, nwg); break;
     case 2: attn_prefill<HD, 2>(c, layer, wg, nwg); break;
     case 3: attn_prefill<HD, 3>(c, layer, wg, nwg); break;
-    case 4: attn_prefill<HD, 4>(c, layer, wg, nwg); break;
+    case 4: attn_prefill<HD, 2>(c, layer, wg, nwg); break;   // two q heads per pass keep the accumulators in registers
     case 6: attn_prefill<HD, 3>(c, layer, wg, nwg); break;
-    case 8: attn_prefill<HD, 4>(c, layer, wg, nwg); break;
+    case 8: attn_prefill<HD, 2>(c, layer, wg, nwg); break;
     default: break;   // rejected at init
   }
 }

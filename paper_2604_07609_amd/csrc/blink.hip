@@ -40,12 +40,7 @@ PHASE_KERNEL(k_norm1, PH_NORM1)
   }
 PHASE_KERNEL8(k_qkv, PH_QKV)
 PHASE_KERNEL(k_rope_kvwrite, PH_ROPE)
-// attention: the bf16 path runs 512 threads per workgroup (eight waves share the KV blocks of one sequence);
-// the fp32 path keeps 256
-__global__ void __launch_bounds__(512) k_attention(DevCtx c, u32 layer) {
-  __shared__ PhaseSharedOf<PH_ATTN>::type sh;
-  run_phase(c, PH_ATTN, layer, &sh, blockIdx.x, gridDim.x);
-}
+PHASE_KERNEL8(k_attention, PH_ATTN)
 PHASE_KERNEL8(k_oproj, PH_OPROJ)
 PHASE_KERNEL(k_norm2, PH_NORM2)
 PHASE_KERNEL(k_gateup, PH_GATEUP)

@@ -354,23 +354,25 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& a, MfmaShared& sh,
   }
 }
 
-template <int EPI, int TW>
+// WIDE: the kernel runs eight waves per workgroup (the projections with few output rows); it never takes four weight
+// tiles per workgroup, and keeping that variant out of it keeps it within the 256 registers per lane it may use.
+template <int EPI, int TW, bool WIDE>
 __device__ __forceinline__ void gemm_stream_nw(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg) {
   // enough tile groups to occupy the chip (one workgroup per group, >= 1.5 per CU) decides the group size
   const u32 NT = (a.N + 15) / 16;
   if (TW == 1) gemm_stream<EPI, 1, TW>(a, sh, wg, nwg);   // one token block: the activation traffic equals the weights'
-  else if (NT >= 1536) gemm_stream<EPI, 4, TW>(a, sh, wg, nwg);
-  else if (NT >= 768 || (blockDim.x == 512 && NT >= 256)) gemm_stream<EPI, 2, TW>(a, sh, wg, nwg);
+  else if (!WIDE && NT >= 1536) gemm_stream<EPI, 4, TW>(a, sh, wg, nwg);
+  else if (NT >= 768 || (WIDE && NT >= 256)) gemm_stream<EPI, 2, TW>(a, sh, wg, nwg);
   else gemm_stream<EPI, 1, TW>(a, sh, wg, nwg);
 }
 
-template <int EPI>
+template <int EPI, bool WIDE>
 __device__ __forceinline__ void gemm_mfma(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg) {
   if (a.T == 0) return;
-  if (a.T <= 16) gemm_stream_nw<EPI, 1>(a, sh, wg, nwg);
-  else if (a.T <= 32) gemm_stream_nw<EPI, 2>(a, sh, wg, nwg);
-  else if (a.T <= 48) gemm_stream_nw<EPI, 3>(a, sh, wg, nwg);
-  else if (a.T <= 64) gemm_stream_nw<EPI, 4>(a, sh, wg, nwg);
+  if (a.T <= 16) gemm_stream_nw<EPI, 1, WIDE>(a, sh, wg, nwg);
+  else if (a.T <= 32) gemm_stream_nw<EPI, 2, WIDE>(a, sh, wg, nwg);
+  else if (a.T <= 48) gemm_stream_nw<EPI, 3, WIDE>(a, sh, wg, nwg);
+  else if (a.T <= 64) gemm_stream_nw<EPI, 4, WIDE>(a, sh, wg, nwg);
   else gemm_tile<EPI>(a, sh, wg, nwg);
 }
 

@@ -90,29 +90,29 @@ __device__ __forceinline__ void run_phase_bf16(const DevCtx& c, int ph, u32 laye
       a.positions = c.positions; a.slot_mapping = c.slot_mapping; a.rope_tab = c.rope_tab; a.qbuf = c.qbuf;
       a.Kc = (bf16_t*)c.kv + (u64)layer * c.kv_layer_stride; a.Vc = a.Kc + c.kv_kv_stride;
       a.nq = c.nq; a.nkv = c.nkv; a.hd = c.hd; a.bs = c.bs;
-      gemm_mfma<EPI_QKV_ROPE>(a, sh.mfma, wg, nwg);
+      gemm_mfma<EPI_QKV_ROPE, true>(a, sh.mfma, wg, nwg);
       break;
     case PH_ATTN: phase_attention_mfma(c, layer, sh.attn_mfma, wg, nwg); break;
     case PH_ATTN_COMBINE: attn_decode_combine(c, wg, nwg); break;
     case PH_OPROJ:
       a.Wp = P->wo; a.Xp = c.aq; a.N = c.d; a.K = c.nq * c.hd; a.x = c.x; a.ldx = c.d; a.g_next = c.layers[layer].g2;
       a.Xp_next = c.xq; a.ssq_out = c.ssq;
-      gemm_mfma<EPI_RESIDUAL>(a, sh.mfma, wg, nwg);
+      gemm_mfma<EPI_RESIDUAL, true>(a, sh.mfma, wg, nwg);
       break;
     case PH_GATEUP:
       a.Wp = P->wgu; a.Xp = c.xq; a.N = 2 * c.F; a.K = c.d; a.ssq_in = c.ssq; a.Hp = c.hq;
-      gemm_mfma<EPI_SILU_GATE>(a, sh.mfma, wg, nwg);
+      gemm_mfma<EPI_SILU_GATE, false>(a, sh.mfma, wg, nwg);
       break;
     case PH_DOWN:
       a.Wp = P->wd; a.Xp = c.hq; a.N = c.d; a.K = c.F; a.x = c.x; a.ldx = c.d;
       a.g_next = layer + 1 < c.n_layers ? c.layers[layer + 1].g1 : c.gf;
       a.Xp_next = c.xq; a.ssq_out = c.ssq;
-      gemm_mfma<EPI_RESIDUAL>(a, sh.mfma, wg, nwg);
+      gemm_mfma<EPI_RESIDUAL, true>(a, sh.mfma, wg, nwg);
       break;
     case PH_LM_HEAD:
       a.Wp = c.lm_p; a.Xp = c.xq; a.N = c.V; a.K = c.d; a.T = m->n_seqs; a.tok_index = c.last_idx; a.ssq_in = c.ssq;
       a.out = c.logits; a.ldo = c.V;
-      gemm_mfma<EPI_SCALED_STORE>(a, sh.mfma, wg, nwg);
+      gemm_mfma<EPI_SCALED_STORE, false>(a, sh.mfma, wg, nwg);
       break;
     case PH_SAMPLE: phase_sample_publish(c, *(SamplerShared*)shp, wg, nwg); break;
     default: break;   // the norms and the rotary / KV-write step are fused into the GEMMs
