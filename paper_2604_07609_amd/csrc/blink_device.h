@@ -187,7 +187,7 @@ struct DevCtx {
   bf16_t* hq;           // packed silu(gate)*up, inner dimension F
   float* ssq;           // [token][d/16] partial sums of squares of the residual stream
   u32 TBS;              // token-block stride of the packed activation buffers
-  u32 pad1;
+  u32 tune_nw;          // tuning knob of the streaming GEMM (0: automatic)
   // decode attention: partial (max, sum, output) of every 512-token chunk of a context longer than one chunk
   float* attn_part_o;   // [chunk][kv head][G][hd]
   float* attn_part_ml;  // [chunk][kv head][G][2]

@@ -52,6 +52,7 @@ struct MfmaGemmArgs {
   bf16_t* Kc;              // this layer's K cache and V cache
   bf16_t* Vc;
   u32 nq, nkv, hd, bs;
+  u32 tune_nw;             // 0: automatic choice of weight tiles per workgroup; 1/2/4: forced (tuning experiments)
 };
 
 #define GEMM_MAX_WAVES 8
@@ -360,9 +361,18 @@ template <int EPI, int TW, bool WIDE>
 __device__ __forceinline__ void gemm_stream_nw(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg) {
   // enough tile groups to occupy the chip (one workgroup per group, >= 1.5 per CU) decides the group size
   const u32 NT = (a.N + 15) / 16;
-  if (TW == 1) gemm_stream<EPI, 1, TW>(a, sh, wg, nwg);   // one token block: the activation traffic equals the weights'
-  else if (!WIDE && NT >= 1536) gemm_stream<EPI, 4, TW>(a, sh, wg, nwg);
-  else if (NT >= 768 || (WIDE && NT >= 256)) gemm_stream<EPI, 2, TW>(a, sh, wg, nwg);
+  if (a.tune_nw == 1) gemm_stream<EPI, 1, TW>(a, sh, wg, nwg);
+  else if (a.tune_nw == 2) gemm_stream<EPI, 2, TW>(a, sh, wg, nwg);
+  else if (a.tune_nw == 4 && !WIDE) gemm_stream<EPI, 4, TW>(a, sh, wg, nwg);
+  // measured on MI355X (llama3_8b shapes): the eight-wave kernels gain from two tiles only with >= 320 row tiles
+  // (QKV), the four-wave kernels with one token block only for very tall matrices (LM head), and with several token
+  // blocks the activation re-reads make two and four tiles pay off from 768 and 1536 row tiles
+  else if (WIDE) {
+    if (NT >= 320) gemm_stream<EPI, 2, TW>(a, sh, wg, nwg); else gemm_stream<EPI, 1, TW>(a, sh, wg, nwg);
+  } else if (TW == 1) {
+    if (NT >= 4096) gemm_stream<EPI, 2, TW>(a, sh, wg, nwg); else gemm_stream<EPI, 1, TW>(a, sh, wg, nwg);
+  } else if (NT >= 1536) gemm_stream<EPI, 4, TW>(a, sh, wg, nwg);
+  else if (NT >= 768) gemm_stream<EPI, 2, TW>(a, sh, wg, nwg);
   else gemm_stream<EPI, 1, TW>(a, sh, wg, nwg);
 }
 

@@ -83,6 +83,7 @@ __device__ __forceinline__ void run_phase_bf16(const DevCtx& c, int ph, u32 laye
   a.T = m->n_tokens;
   a.TBS = c.TBS;
   a.eps = c.eps;
+  a.tune_nw = c.tune_nw;
   switch (ph) {
     case PH_EMBED: phase_embed_packed(c, wg, nwg); break;
     case PH_QKV:

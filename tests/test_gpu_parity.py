@@ -75,6 +75,21 @@ def test_bf16_wide_matrices(lib, name, max_batch, n_req):
     print(name, "max_batch", max_batch, "worst relative logit error", worst)
 
 
+@pytest.mark.parametrize("nw", [1, 2, 4])
+def test_bf16_forced_tiles_per_workgroup(lib, nw, monkeypatch):
+    """Every GEMM of the streaming schedule forced to 1, 2 or 4 weight tiles per workgroup (the automatic choice picks
+    by matrix height, which the small test models never reach for the eight-wave kernels)."""
+    monkeypatch.setenv("BLINK_TUNE_NW", str(nw))
+    cfg, eng, raw, blob = setup("mini_gqa", 43)          # qkv: 40 row tiles, vocab 2500: 157 tiles (odd: ragged groups)
+    eng = dict(eng, max_batch=36, kv_num_blocks=300, max_prefill_tokens=60, ring_slots=64)
+    reqs = synth.make_workload("mini", cfg["vocab"], 143, n_requests=40)
+    for r in reqs:
+        r["max_new_tokens"] = min(r["max_new_tokens"], 5)
+        r["prompt"] = r["prompt"][:24]
+    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2)
+    print("forced", nw, "tiles per workgroup: worst relative logit error", worst)
+
+
 def test_bf16_large_prefill_iterations(lib):
     """Prefill iterations of ~1000 tokens over a wide FFN: the LDS-staged tile schedule of the GEMM with 256-row
     workgroup tiles (gate/up) beside the 128-row and the direct schedules (the narrower matrices)."""
