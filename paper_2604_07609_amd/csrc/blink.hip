@@ -295,7 +295,7 @@ static int init_impl(const blink_config* cfg, blink_engine* e) {
     c.rope_tab = tab;
   }
   // ---- bf16 path: weights re-tiled into MFMA operand order, packed activation buffers ----
-  c.TBS = ((c.maxT + 127) / 128) * 8;
+  c.TBS = ((c.maxT + 255) / 256) * 16;   // whole 256-token workgroup tiles
   c.tune_nw = getenv("BLINK_TUNE_NW") ? (u32)atoi(getenv("BLINK_TUNE_NW")) : 0u;
   if (c.dtype == 1) {
     std::vector<LayerWP> lp(c.n_layers);

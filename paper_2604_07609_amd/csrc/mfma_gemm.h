@@ -52,13 +52,14 @@ struct MfmaGemmArgs {
   bf16_t* Kc;              // this layer's K cache and V cache
   bf16_t* Vc;
   u32 nq, nkv, hd, bs;
-  u32 tune_nw;             // 0: automatic choice of weight tiles per workgroup; 1/2/4: forced (tuning experiments)
+  u32 tune_nw;             // low byte: 0 automatic choice of weight tiles per workgroup, 1/2/4 forced; bit 8: force the
+                           // 256-token workgroup tile of the eight-wave prefill schedule (tests and tuning)
 };
 
 #define GEMM_MAX_WAVES 8
 struct MfmaShared {
   float red[GEMM_MAX_WAVES][4][64][4];  // [wave][token block][lane][4]  (stream schedule; scratch of the norm scales)
-  float rstd[128];
+  float rstd[256];
 };
 
 __device__ __forceinline__ u64 packed_off(u32 t, u32 k, u32 TBS) {
@@ -75,11 +76,11 @@ __device__ __forceinline__ void compute_rstd(const MfmaGemmArgs& a, u32 t0, u32 
   const u32 tid = threadIdx.x;
   __syncthreads();
   if (a.ssq_in == nullptr) {
-    if (tid < 128) sh.rstd[tid] = 1.0f;
+    if (tid < 256) sh.rstd[tid] = 1.0f;
   } else {
-    // 256 threads: two threads per token for 128 tokens (or four for 64): each sums a contiguous run of the
+    // 256 threads: one thread per token for 256 tokens, two for 128, four for 64: each sums a contiguous run of the
     // token's partials with 16-byte loads (K/16 is a multiple of 2; runs are multiples of 4 when K % 256 == 0)
-    const u32 parts = count <= 64 ? 4u : 2u, span = BLK_THREADS / parts;
+    const u32 parts = count <= 64 ? 4u : (count <= 128 ? 2u : 1u), span = BLK_THREADS / parts;
     const u32 tl = tid % span, part = tid / span;   // threads beyond the first 256 (8-wave launches) only join the barriers
     float s = 0.f;
     const u32 np = a.K / 16;
@@ -293,23 +294,29 @@ __device__ __forceinline__ void gemm_stream(const MfmaGemmArgs& a, MfmaShared& s
 template <int EPI>
 __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg) {
   const u32 lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const bool spare = w >= 4;                               // waves 4..7 of an 8-wave launch only join the barriers
   const u32 NT = (a.N + 15) / 16, KT = a.K / 32;
-  const u32 nblocks = (NT + 7) / 8, tblocks = (a.T + 127) / 128;
-  const u32 wn = w & 1, wt = w >> 1;
+  // workgroup tile: 128 rows x 128 tokens with four waves (2 x 2). An eight-wave launch takes 128 rows x 256 tokens
+  // (2 x 4 waves) when that still leaves enough tiles for the chip; otherwise its waves 4..7 only join the barriers.
+  const u32 nblocks = (NT + 7) / 8;
+  const bool eight = blockDim.x == 512 && (nblocks * ((a.T + 255) / 256) >= 384 || (a.tune_nw & 0x100u));
+  const u32 BT = eight ? 256u : 128u;
+  const u32 tblocks = (a.T + BT - 1) / BT;
+  const bool spare = !eight && w >= 4;
+  const u32 wn = w & 1, wt = eight ? (w >> 1) : ((w >> 1) & 1);
   const u64 xk_stride = (u64)a.TBS * 512;
   for (u32 item = wg; item < nblocks * tblocks; item += nwg) {
     // token blocks vary fastest: the workgroups running together share a few weight row blocks (each read from HBM once
     // and then from L2) and sweep all token blocks, whose operand is small enough to stay in L2 / the memory-side cache
     const u32 tb = item % tblocks, nb = item / tblocks;
-    compute_rstd(a, tb * 128, 128, sh);
+    compute_rstd(a, tb * BT, BT, sh);
     if (spare) continue;
     const u32 nt0 = nb * 8 + wn * 4;
     u32 xoff[4];
 #pragma unroll
     for (int tw = 0; tw < 4; ++tw) {
-      u32 tok = tb * 128 + wt * 64 + tw * 16 + (lane & 15);
+      u32 tok = tb * BT + wt * 64 + tw * 16 + (lane & 15);
       if (a.tok_index) tok = tok < a.T ? a.tok_index[tok] : 0;
+      else tok = min(tok, a.TBS * 16 - 1);                 // stay inside the operand buffer past the last token block
       xoff[tw] = ((tok >> 4) * 64 + (tok & 15) + 16 * (lane >> 4)) * 8;
     }
     const bf16_t* wp[4];
@@ -350,7 +357,7 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& a, MfmaShared& sh,
       if (nt0 + i < NT) {
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-          epilogue_tile<EPI>(a, acc[i][j], nt0 + i, tb * 128 + wt * 64 + j * 16, &sh.rstd[wt * 64 + j * 16]);
+          epilogue_tile<EPI>(a, acc[i][j], nt0 + i, tb * BT + wt * 64 + j * 16, &sh.rstd[wt * 64 + j * 16]);
       }
   }
 }
@@ -361,9 +368,10 @@ template <int EPI, int TW, bool WIDE>
 __device__ __forceinline__ void gemm_stream_nw(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg) {
   // enough tile groups to occupy the chip (one workgroup per group, >= 1.5 per CU) decides the group size
   const u32 NT = (a.N + 15) / 16;
-  if (a.tune_nw == 1) gemm_stream<EPI, 1, TW>(a, sh, wg, nwg);
-  else if (a.tune_nw == 2) gemm_stream<EPI, 2, TW>(a, sh, wg, nwg);
-  else if (a.tune_nw == 4 && !WIDE) gemm_stream<EPI, 4, TW>(a, sh, wg, nwg);
+  const u32 forced = a.tune_nw & 0xFFu;
+  if (forced == 1) gemm_stream<EPI, 1, TW>(a, sh, wg, nwg);
+  else if (forced == 2) gemm_stream<EPI, 2, TW>(a, sh, wg, nwg);
+  else if (forced == 4 && !WIDE) gemm_stream<EPI, 4, TW>(a, sh, wg, nwg);
   // measured on MI355X (llama3_8b shapes): the eight-wave kernels gain from two tiles only with >= 320 row tiles
   // (QKV), the four-wave kernels with one token block only for very tall matrices (LM head), and with several token
   // blocks the activation re-reads make two and four tiles pay off from 768 and 1536 row tiles
