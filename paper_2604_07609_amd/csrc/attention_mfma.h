@@ -98,7 +98,7 @@ __device__ __forceinline__ void attn_block(const KVTile<HD>& kv, const bf16x8_t 
   }
 }
 
-#define ATTN_CHUNK_BLOCKS 32   // KV blocks (512 tokens) per decode work item
+#define ATTN_CHUNK_BLOCKS (ATTN_CHUNK_TOKENS / 16)   // KV blocks per decode work item
 #define ATTN_WAVES 8          // waves per workgroup of the attention kernel (512 threads: at most 256 registers per lane)
 struct AttnMfmaShared {
   float m[ATTN_WAVES][16], l[ATTN_WAVES][16];
@@ -113,7 +113,7 @@ __device__ __forceinline__ void attn_decode(const DevCtx& c, u32 layer, AttnMfma
   const bf16_t* Kc = (const bf16_t*)c.kv + (u64)layer * c.kv_layer_stride;
   const bf16_t* Vc = Kc + c.kv_kv_stride;
   const u64 tile = (u64)16 * HD;
-  // Work item: (512-token chunk of one sequence's context, kv head). Chunks balance the load between short and long
+  // Work item: (chunk of ATTN_CHUNK_TOKENS of one sequence's context, kv head). Chunks balance the load between short and long
   // contexts and give the chip enough items at small batch. A context of one chunk is finished here; longer ones
   // leave per-chunk partial results that attn_decode_combine (the next kernel) merges in chunk order.
   const u32 total_chunks = c.cu_chunks[B];
@@ -139,7 +139,7 @@ __device__ __forceinline__ void attn_decode(const DevCtx& c, u32 layer, AttnMfma
     attn_init(acc);
     const u32 lim[1] = {ctx};
     const u32 b_lo = ch * ATTN_CHUNK_BLOCKS, b_hi = min((ctx + 15) / 16, b_lo + ATTN_CHUNK_BLOCKS);
-    const u32 nb = b_hi - b_lo;                 // 1..32 blocks: four per wave with eight waves
+    const u32 nb = b_hi - b_lo;                 // 1..64 blocks: up to eight per wave with eight waves
     // every wave takes blocks w, w+nw, ... of the chunk (up to eight): four tiles are in flight at any time, a tile's
     // registers are refilled as soon as it has been used (rotation by code position, no register copies)
     const u32 nw = blockDim.x >> 6;

@@ -329,7 +329,7 @@ static int init_impl(const blink_config* cfg, blink_engine* e) {
     if (int rc = dalloc(e, &c.ssq, tile_tokens * (c.d / 16))) return rc;
     if (int rc = dalloc(e, &c.qbuf, (u64)c.maxT * c.nq * c.hd)) return rc;
     {
-      const u64 chunks = (u64)c.max_batch * ((c.max_seq_len + 511) / 512), G = c.nq / c.nkv;
+      const u64 chunks = (u64)c.max_batch * ((c.max_seq_len + ATTN_CHUNK_TOKENS - 1) / ATTN_CHUNK_TOKENS), G = c.nq / c.nkv;
       if (int rc = dalloc(e, &c.attn_part_o, chunks * c.nkv * G * c.hd)) return rc;
       if (int rc = dalloc(e, &c.attn_part_ml, chunks * c.nkv * G * 2)) return rc;
     }

@@ -10,6 +10,7 @@ typedef int32_t i32;
 typedef uint16_t bf16_t;  // bf16 bit pattern
 
 #define BLK_THREADS 256
+#define ATTN_CHUNK_TOKENS 512    // context tokens per decode-attention work item (32 KV blocks)
 #define WAVE 64
 
 // ---- ring (section 4.2 "Ring buffer"): slots + input/output token arenas --------------------------
@@ -154,7 +155,7 @@ struct DevCtx {
   u32* cu_seqlens;      // [max_batch+1]
   u32* last_idx;        // [max_batch]
   u32* cu_qtiles;       // [max_batch+1] prefix sum of ceil(tokens/16) per sequence of the iteration
-  u32* cu_chunks;       // [max_batch+1] prefix sum of ceil(context/512) per sequence (decode attention work items)
+  u32* cu_chunks;       // [max_batch+1] prefix sum of ceil(context/ATTN_CHUNK_TOKENS) per sequence (decode attention work items)
   i32* input_ids;       // [maxT]
   i32* positions;       // [maxT]
   i32* slot_mapping;    // [maxT]
@@ -188,7 +189,7 @@ struct DevCtx {
   float* ssq;           // [token][d/16] partial sums of squares of the residual stream
   u32 TBS;              // token-block stride of the packed activation buffers
   u32 tune_nw;          // tuning knob of the streaming GEMM (0: automatic)
-  // decode attention: partial (max, sum, output) of every 512-token chunk of a context longer than one chunk
+  // decode attention: partial (max, sum, output) of every chunk of a context longer than one chunk
   float* attn_part_o;   // [chunk][kv head][G][hd]
   float* attn_part_ml;  // [chunk][kv head][G][2]
 };

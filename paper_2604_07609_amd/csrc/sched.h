@@ -257,7 +257,7 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
       }
       u32 tots, tota, tott, totq, totc;
       const u32 ctx_after = in ? (kind == KIND_DECODE ? ctx + 1 : ntok) : 0u;
-      const u32 coff = n_ch + block_excl_scan((ctx_after + 511) / 512, totc, sh.wave_part);
+      const u32 coff = n_ch + block_excl_scan((ctx_after + ATTN_CHUNK_TOKENS - 1) / ATTN_CHUNK_TOKENS, totc, sh.wave_part);
       const u32 qoff = n_qt + block_excl_scan((ntok + 15) / 16, totq, sh.wave_part2);
       const u32 si = n_seqs + block_excl_scan(in ? 1u : 0u, tots, sh.wave_part);
       const u32 aoff = n_alloc + block_excl_scan(nalloc, tota, sh.wave_part2);

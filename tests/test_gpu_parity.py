@@ -109,13 +109,13 @@ def test_bf16_large_prefill_iterations(lib, tile256, monkeypatch):
 
 @pytest.mark.parametrize("name", ["mini_gqa128", "mini_gqa"])
 def test_bf16_long_contexts(lib, name):
-    """Contexts of 500..1100 tokens: decode attention works in 512-token chunks whose partial results a second
+    """Contexts of 500..2100 tokens: decode attention works in 1024-token chunks whose partial results a second
     kernel merges; prefill attention walks up to 65 KV blocks; one short context shares the batch."""
     cfg, eng, raw, blob = setup(name, 37)
-    eng = dict(eng, max_seq_len=1300, kv_num_blocks=230, max_prefill_tokens=2048, max_batch=4)
+    eng = dict(eng, max_seq_len=2200, kv_num_blocks=330, max_prefill_tokens=4096, max_batch=4)
     rng = np.random.default_rng(5)
     reqs = []
-    for i, P in enumerate([520, 1040, 7, 511]):
+    for i, P in enumerate([1030, 2070, 7, 1023]):
         reqs.append(dict(arrival_s=0.0, prompt=rng.integers(0, cfg["vocab"], P).astype(np.int32), max_new_tokens=5,
                          temperature=0.0, top_k=0, top_p=1.0, seed=i))
     worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2)
