@@ -204,7 +204,7 @@ struct StreamBuf {
 // divides the L2 traffic of the activation operand by NW (it is TW/NW times the weight bytes).
 template <int EPI, int NW, int TW>
 __device__ __forceinline__ void gemm_stream(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg) {
-  constexpr int U = NW == 1 ? (TW == 1 ? 8 : (TW == 2 ? 6 : 4)) : ((NW * TW >= 8) ? 2 : (NW + TW >= 5 ? 3 : 4));   // k-tiles per batch
+  constexpr int U = NW == 1 ? (TW == 1 ? 8 : (TW == 2 ? 6 : 4)) : ((NW * TW >= 16) ? 3 : ((NW * TW >= 8) ? 2 : (NW + TW >= 5 ? 3 : 4)));   // k-tiles per batch
   const u32 lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const u32 NT = (a.N + 15) / 16, KT = a.K / 32;
   const u32 NG = (NT + NW - 1) / NW;                       // groups of NW tiles
