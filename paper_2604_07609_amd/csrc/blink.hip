@@ -23,9 +23,10 @@ __global__ void __launch_bounds__(BLK_THREADS) k_sched(DevCtx c) {
   sched_step(c, sh);
 }
 
-// one named kernel per phase so that profiles attribute time to the step of the forward pass
+// one named kernel per phase so that profiles attribute time to the step of the forward pass. Two workgroups per
+// compute unit (at most 256 registers per lane): the start and the end of one workgroup overlap the other's streaming.
 #define PHASE_KERNEL(name, PH)                                                   \
-  __global__ void __launch_bounds__(BLK_THREADS) name(DevCtx c, u32 layer) {     \
+  __global__ void __launch_bounds__(BLK_THREADS, 2) name(DevCtx c, u32 layer) {  \
     __shared__ PhaseSharedOf<PH>::type sh;                                       \
     run_phase(c, PH, layer, &sh, blockIdx.x, gridDim.x);                         \
   }

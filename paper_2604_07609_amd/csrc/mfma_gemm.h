@@ -202,9 +202,15 @@ struct StreamBuf {
 
 // NW consecutive 16-row weight tiles per workgroup: every activation tile a wave loads is used for NW MFMAs, which
 // divides the L2 traffic of the activation operand by NW (it is TW/NW times the weight bytes).
-template <int EPI, int NW, int TW>
+// k-tiles per batch of loads (two batches are in flight per wave). Measured on MI355X under the budget of 256 registers
+// per lane that lets two four-wave workgroups share a compute unit: the widest variants keep fewer k-tiles per batch.
+constexpr int stream_batch(int NW, int TW) {
+  return NW == 1 ? (TW == 1 ? 8 : (TW == 2 ? 6 : 4))
+       : NW == 4 ? (TW >= 3 ? 1 : 3)
+       : ((NW * TW >= 8) ? 2 : (NW + TW >= 5 ? 3 : 4));
+}
+template <int EPI, int NW, int TW, int U = stream_batch(NW, TW)>
 __device__ __forceinline__ void gemm_stream(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg) {
-  constexpr int U = NW == 1 ? (TW == 1 ? 8 : (TW == 2 ? 6 : 4)) : ((NW * TW >= 16) ? 3 : ((NW * TW >= 8) ? 2 : (NW + TW >= 5 ? 3 : 4)));   // k-tiles per batch
   const u32 lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const u32 NT = (a.N + 15) / 16, KT = a.K / 32;
   const u32 NG = (NT + NW - 1) / NW;                       // groups of NW tiles
