@@ -57,8 +57,12 @@ struct MfmaGemmArgs {
 };
 
 #define GEMM_MAX_WAVES 8
+#define GEMM_TILE_LDS 16384   // one k-step of a 128 x 128 workgroup tile: eight 1 KB weight tiles, then eight activation tiles
 struct MfmaShared {
-  float red[GEMM_MAX_WAVES][4][64][4];  // [wave][token block][lane][4]  (stream schedule; scratch of the norm scales)
+  union {
+    float red[GEMM_MAX_WAVES][4][64][4];       // [wave][token block][lane][4]  (stream schedule; scratch of the norm scales)
+    unsigned char tile[2][2 * GEMM_TILE_LDS];  // [four-wave half of the workgroup][k-step parity]  (tile schedule)
+  };
   float rstd[256];
 };
 
@@ -66,17 +70,17 @@ __device__ __forceinline__ u64 packed_off(u32 t, u32 k, u32 TBS) {
   return ((u64)((k >> 5) * TBS + (t >> 4)) * 64 + (t & 15) + 16 * ((k & 31) >> 3)) * 8 + (k & 7);
 }
 
+__device__ __forceinline__ bf16x8_t as_bf16x8(uint4 v) { return *(const bf16x8_t*)&v; }
 __device__ __forceinline__ bf16x8_t ld_tile(const bf16_t* p) {   // one lane's 16 bytes of a packed tile
-  const uint4 v = *(const uint4*)p;
-  return *(const bf16x8_t*)&v;
+  return as_bf16x8(*(const uint4*)p);
 }
 
-// rstd of `count` tokens starting at column t0 into sh.rstd[0..count)
-__device__ __forceinline__ void compute_rstd(const MfmaGemmArgs& a, u32 t0, u32 count, MfmaShared& sh) {
+// rstd of `count` tokens starting at column t0 into sh.rstd[off .. off + count)
+__device__ __forceinline__ void compute_rstd(const MfmaGemmArgs& a, u32 t0, u32 count, MfmaShared& sh, u32 off = 0) {
   const u32 tid = threadIdx.x;
   __syncthreads();
   if (a.ssq_in == nullptr) {
-    if (tid < 256) sh.rstd[tid] = 1.0f;
+    if (tid < count) sh.rstd[off + tid] = 1.0f;
   } else {
     // 256 threads: one thread per token for 256 tokens, two for 128, four for 64: each sums a contiguous run of the
     // token's partials with 16-byte loads (K/16 is a multiple of 2; runs are multiples of 4 when K % 256 == 0)
@@ -105,7 +109,7 @@ __device__ __forceinline__ void compute_rstd(const MfmaGemmArgs& a, u32 t0, u32 
     if (tid < count) {
       float tot = 0.f;
       for (u32 p = 0; p < parts; ++p) tot += scratch[p * span + tid];
-      sh.rstd[tid] = 1.0f / sqrtf(tot / (float)a.K + a.eps);
+      sh.rstd[off + tid] = 1.0f / sqrtf(tot / (float)a.K + a.eps);
     }
   }
   __syncthreads();
@@ -368,6 +372,91 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& a, MfmaShared& sh,
   }
 }
 
+// ---- tile schedule through LDS: T > 64 ---------------------------------------------------------------------------
+// 128 rows x 128 tokens per four waves (64 x 64 per wave). Every k-step, the four waves fetch the step's eight weight
+// tiles and eight activation tiles from global memory once (two steps ahead, in registers), store them into one of two
+// LDS buffers, and read their own four + four operand tiles of the *next* step from the other buffer into a second
+// register set while the MFMAs of the current step run: one barrier per k-step, global traffic half of what four
+// waves loading their operands directly would request. An eight-wave workgroup runs two such tiles side by side
+// (separate LDS buffers, common barriers).
+template <int EPI>
+__device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg) {
+  const u32 lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const u32 halves = blockDim.x >> 8, half = w >> 2, wl = w & 3, wn = wl & 1, wt = wl >> 1;
+  const u32 NT = (a.N + 15) / 16, KT = a.K / 32;
+  const u32 nblocks = (NT + 7) / 8, tblocks = (a.T + 127) / 128, total = nblocks * tblocks;
+  const u64 xk_stride = (u64)a.TBS * 512, w_stride = (u64)KT * 512;
+  unsigned char* const Lw = sh.tile[half] + (wl * 2) * 1024 + lane * 16;   // this wave stores tiles 2 wl, 2 wl + 1 of both operands
+  const unsigned char* const Lrw = sh.tile[half] + (wn * 4) * 1024 + lane * 16;
+  const unsigned char* const Lrx = sh.tile[half] + 8192 + (wt * 4) * 1024 + lane * 16;
+  for (u32 it = wg; it * halves < total; it += nwg) {
+    // token blocks vary fastest: the workgroups running together share a few weight row blocks
+    const u32 item = it * halves + half;
+    const bool valid = item < total;            // the spare half of the last pair computes a duplicate and drops it
+    const u32 tb = valid ? item % tblocks : 0, nb = valid ? item / tblocks : 0;
+    for (u32 h = 0; h < halves; ++h) {
+      const u32 ih = it * halves + h;
+      compute_rstd(a, ih < total ? (ih % tblocks) * 128 : 0, 128, sh, h * 128);   // ends with a barrier: LDS is free
+    }
+    const u32 nt0 = nb * 8 + wn * 4;
+    const bf16_t* const gw0 = a.Wp + (u64)min(nb * 8 + wl * 2, NT - 1) * w_stride + lane * 8;
+    const bf16_t* const gw1 = a.Wp + (u64)min(nb * 8 + wl * 2 + 1, NT - 1) * w_stride + lane * 8;
+    const bf16_t* const gx = a.Xp + (u64)(tb * 8 + wl * 2) * 512 + lane * 8;
+    floatx4_t acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[i][j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+    // staging registers as separate variables (arrays or structs of them may end up in scratch memory)
+    uint4 ga0, ga1, ga2, ga3, gb0, gb1, gb2, gb3;
+#define TL_GLOAD(g, kt) { const u32 kc_ = min((u32)(kt), KT - 1); const bf16_t* px_ = gx + (u64)kc_ * xk_stride;           \
+      g##0 = *(const uint4*)(gw0 + (u64)kc_ * 512); g##1 = *(const uint4*)(gw1 + (u64)kc_ * 512);                          \
+      g##2 = *(const uint4*)(px_); g##3 = *(const uint4*)(px_ + 512); }
+#define TL_STORE(g, buf) { unsigned char* p_ = Lw + (buf) * GEMM_TILE_LDS;                                                 \
+      *(uint4*)(p_) = g##0; *(uint4*)(p_ + 1024) = g##1; *(uint4*)(p_ + 8192) = g##2; *(uint4*)(p_ + 8192 + 1024) = g##3; }
+#define TL_RW(buf, i) as_bf16x8(*(const uint4*)(Lrw + (buf) * GEMM_TILE_LDS + (i) * 1024))
+#define TL_RX(buf, j) as_bf16x8(*(const uint4*)(Lrx + (buf) * GEMM_TILE_LDS + (j) * 1024))
+#define TL_MM(A, W, X) A = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W, X, A, 0, 0, 0);
+#define TL_ROW(i, o) TL_MM(acc[i][0], o.w##i, o.x0) TL_MM(acc[i][1], o.w##i, o.x1) TL_MM(acc[i][2], o.w##i, o.x2) TL_MM(acc[i][3], o.w##i, o.x3)
+#define TL_SB __builtin_amdgcn_sched_barrier(0);
+    // step k with its operands in `o`: reads the operands of step k+1 from LDS buffer rb into `n`, stores the staged data
+    // of step k+2 (in g) into LDS buffer wb and requests step k+4 into g
+#define TL_STEP(o, n, g, k, rb, wb)                                                                                       \
+    n.x0 = TL_RX(rb, 0); n.w0 = TL_RW(rb, 0); n.x1 = TL_RX(rb, 1); n.w1 = TL_RW(rb, 1); TL_STORE(g, wb)                   \
+    TL_SB TL_ROW(0, o) TL_ROW(1, o) TL_SB                                                                                 \
+    n.x2 = TL_RX(rb, 2); n.w2 = TL_RW(rb, 2); n.x3 = TL_RX(rb, 3); n.w3 = TL_RW(rb, 3); TL_GLOAD(g, (k) + 4)              \
+    TL_SB TL_ROW(2, o) TL_ROW(3, o) TL_SB                                                                                 \
+    __syncthreads();
+    struct Ops { bf16x8_t w0, w1, w2, w3, x0, x1, x2, x3; };
+    Ops oa, ob;
+    TL_GLOAD(ga, 0) TL_STORE(ga, 0) TL_GLOAD(gb, 1) TL_STORE(gb, 1) TL_GLOAD(ga, 2) TL_GLOAD(gb, 3)
+    __syncthreads();
+    oa.w0 = TL_RW(0, 0); oa.w1 = TL_RW(0, 1); oa.w2 = TL_RW(0, 2); oa.w3 = TL_RW(0, 3);
+    oa.x0 = TL_RX(0, 0); oa.x1 = TL_RX(0, 1); oa.x2 = TL_RX(0, 2); oa.x3 = TL_RX(0, 3);
+    for (u32 k = 0; k < KT; k += 2) {
+      TL_STEP(oa, ob, ga, k, 1, 0)
+      if (k + 1 < KT) { TL_STEP(ob, oa, gb, k + 1, 0, 1) }
+    }
+#undef TL_GLOAD
+#undef TL_STORE
+#undef TL_RW
+#undef TL_RX
+#undef TL_MM
+#undef TL_ROW
+#undef TL_SB
+#undef TL_STEP
+    if (valid) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (nt0 + i < NT) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            epilogue_tile<EPI>(a, acc[i][j], nt0 + i, tb * 128 + wt * 64 + j * 16, &sh.rstd[half * 128 + wt * 64 + j * 16]);
+        }
+    }
+  }
+}
+
 // WIDE: the kernel runs eight waves per workgroup (the projections with few output rows); it never takes four weight
 // tiles per workgroup, and keeping that variant out of it keeps it within the 256 registers per lane it may use.
 template <int EPI, int TW, bool WIDE>
@@ -397,7 +486,8 @@ __device__ __forceinline__ void gemm_mfma(const MfmaGemmArgs& a, MfmaShared& sh,
   else if (a.T <= 32) gemm_stream_nw<EPI, 2, WIDE>(a, sh, wg, nwg);
   else if (a.T <= 48) gemm_stream_nw<EPI, 3, WIDE>(a, sh, wg, nwg);
   else if (a.T <= 64) gemm_stream_nw<EPI, 4, WIDE>(a, sh, wg, nwg);
-  else gemm_tile<EPI>(a, sh, wg, nwg);
+  else if (a.tok_index || (a.tune_nw & 0x200u)) gemm_tile<EPI>(a, sh, wg, nwg);   // bit 9: direct-load tiles (tests and tuning)
+  else gemm_tile_lds<EPI>(a, sh, wg, nwg);
 }
 
 // ---- packing -----------------------------------------------------------------------------------------------------
