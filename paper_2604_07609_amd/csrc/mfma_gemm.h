@@ -75,41 +75,47 @@ __device__ __forceinline__ bf16x8_t ld_tile(const bf16_t* p) {   // one lane's 1
   return as_bf16x8(*(const uint4*)p);
 }
 
-// rstd of `count` tokens starting at column t0 into sh.rstd[off .. off + count)
+// rstd of `count` (<= 256) tokens starting at column t0 into sh.rstd[off .. off + count). Sixteen lanes share a token:
+// each reads every sixteenth 16-byte piece of the token's partial sums (256 contiguous bytes per token and load), up to
+// sixteen tokens' loads are in flight per lane, and a butterfly over the sixteen lanes finishes the sum.
 __device__ __forceinline__ void compute_rstd(const MfmaGemmArgs& a, u32 t0, u32 count, MfmaShared& sh, u32 off = 0) {
   const u32 tid = threadIdx.x;
-  __syncthreads();
+  __syncthreads();   // the previous readers of sh.rstd are done
   if (a.ssq_in == nullptr) {
     if (tid < count) sh.rstd[off + tid] = 1.0f;
-  } else {
-    // 256 threads: one thread per token for 256 tokens, two for 128, four for 64: each sums a contiguous run of the
-    // token's partials with 16-byte loads (K/16 is a multiple of 2; runs are multiples of 4 when K % 256 == 0)
-    const u32 parts = count <= 64 ? 4u : (count <= 128 ? 2u : 1u), span = BLK_THREADS / parts;
-    const u32 tl = tid % span, part = tid / span;   // threads beyond the first 256 (8-wave launches) only join the barriers
-    float s = 0.f;
-    const u32 np = a.K / 16;
-    if (tid < BLK_THREADS && tl < count && t0 + tl < a.T) {
-      const u32 tok = a.tok_index ? a.tok_index[t0 + tl] : t0 + tl;
-      const float* pp = a.ssq_in + (u64)tok * np;
-      const u32 lo = np * part / parts, hi = np * (part + 1) / parts;
-      if (((lo | hi) & 3u) == 0) {
-        float4 acc4 = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (u32 p = lo; p < hi; p += 4) {
-          const float4 v = *(const float4*)(pp + p);
-          acc4.x += v.x; acc4.y += v.y; acc4.z += v.z; acc4.w += v.w;
-        }
-        s = (acc4.x + acc4.y) + (acc4.z + acc4.w);
-      } else {
-        for (u32 p = lo; p < hi; ++p) s += pp[p];
+  } else if (tid < BLK_THREADS) {   // threads beyond the first 256 (8-wave launches) only join the barriers
+    const u32 np = a.K / 16, l16 = tid & 15, grp = tid >> 4;
+    const float* pp[16];
+    float s[16];
+#pragma unroll
+    for (int it = 0; it < 16; ++it) {
+      const u32 t = min(t0 + min(grp + 16 * it, count - 1), a.T - 1);   // clamped: results of padding tokens are dropped
+      pp[it] = a.ssq_in + (u64)(a.tok_index ? a.tok_index[t] : t) * np;
+      s[it] = 0.f;
+    }
+    const u32 passes = (count + 15) / 16;
+    if ((np & 3u) == 0) {
+      for (u32 q = l16 * 4; q < np; q += 64) {
+#pragma unroll
+        for (int it = 0; it < 16; ++it)
+          if ((u32)it < passes) {
+            const float4 v = *(const float4*)(pp[it] + q);
+            s[it] += (v.x + v.y) + (v.z + v.w);
+          }
+      }
+    } else {
+      for (u32 q = l16; q < np; q += 16) {
+#pragma unroll
+        for (int it = 0; it < 16; ++it)
+          if ((u32)it < passes) s[it] += pp[it][q];
       }
     }
-    float* scratch = &sh.red[0][0][0][0];
-    if (tid < BLK_THREADS) scratch[part * span + tl] = s;
-    __syncthreads();
-    if (tid < count) {
-      float tot = 0.f;
-      for (u32 p = 0; p < parts; ++p) tot += scratch[p * span + tid];
-      sh.rstd[off + tid] = 1.0f / sqrtf(tot / (float)a.K + a.eps);
+#pragma unroll
+    for (int it = 0; it < 16; ++it) {
+      float v = s[it];
+      v += __shfl_xor(v, 1); v += __shfl_xor(v, 2); v += __shfl_xor(v, 4); v += __shfl_xor(v, 8);
+      const u32 tl = grp + 16 * it;
+      if (l16 == 0 && tl < count) sh.rstd[off + tl] = 1.0f / sqrtf(v / (float)a.K + a.eps);
     }
   }
   __syncthreads();
@@ -372,6 +378,25 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& a, MfmaShared& sh,
   }
 }
 
+// Work item of a workgroup in the round that starts at item `base`. Workgroups are dealt to the eight XCDs round-robin
+// (workgroup id modulo 8), and each XCD has its own L2: the workgroups of one XCD take consecutive items, so that the
+// operand blocks those items share are fetched into that L2 once. Returns ~0u when the round has no item for `wg`.
+__device__ __forceinline__ u32 xcd_item(u32 base, u32 total, u32 wg, u32 nwg) {
+  const u32 cnt = min(nwg, total - base);
+  if (nwg & 7u) return wg < cnt ? base + wg : ~0u;
+  const u32 q = (cnt + 7) / 8, x = wg & 7u, l = wg >> 3, off = x * q + l;
+  return (l < q && off < cnt) ? base + off : ~0u;
+}
+
+// Tile order of the tile schedule: token blocks in groups of eight; inside a group the row blocks follow each other and
+// the token block varies fastest, so 64 consecutive tiles are 8 row blocks x 8 token blocks (16 operand blocks in all).
+__device__ __forceinline__ void tile_coords(u32 i, u32 nblocks, u32 tblocks, u32& nb, u32& tb) {
+  const u32 gsz = nblocks * 8, g = min(i / gsz, tblocks / 8), rem = i - g * gsz;
+  const u32 width = min(8u, tblocks - g * 8);
+  nb = rem / width;
+  tb = g * 8 + rem % width;
+}
+
 // ---- tile schedule through LDS: T > 64 ---------------------------------------------------------------------------
 // 128 rows x 128 tokens per four waves (64 x 64 per wave). Every k-step, the four waves fetch the step's eight weight
 // tiles and eight activation tiles from global memory once (two steps ahead, in registers), store them into one of two
@@ -389,15 +414,14 @@ __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared&
   unsigned char* const Lw = sh.tile[half] + (wl * 2) * 1024 + lane * 16;   // this wave stores tiles 2 wl, 2 wl + 1 of both operands
   const unsigned char* const Lrw = sh.tile[half] + (wn * 4) * 1024 + lane * 16;
   const unsigned char* const Lrx = sh.tile[half] + 8192 + (wt * 4) * 1024 + lane * 16;
-  for (u32 it = wg; it * halves < total; it += nwg) {
-    // token blocks vary fastest: the workgroups running together share a few weight row blocks
+  const u32 nitems = (total + halves - 1) / halves;
+  for (u32 base = 0; base < nitems; base += nwg) {
+    const u32 it = xcd_item(base, nitems, wg, nwg);
+    if (it == ~0u) continue;
     const u32 item = it * halves + half;
     const bool valid = item < total;            // the spare half of the last pair computes a duplicate and drops it
-    const u32 tb = valid ? item % tblocks : 0, nb = valid ? item / tblocks : 0;
-    for (u32 h = 0; h < halves; ++h) {
-      const u32 ih = it * halves + h;
-      compute_rstd(a, ih < total ? (ih % tblocks) * 128 : 0, 128, sh, h * 128);   // ends with a barrier: LDS is free
-    }
+    u32 tb = 0, nb = 0;
+    if (valid) tile_coords(item, nblocks, tblocks, nb, tb);
     const u32 nt0 = nb * 8 + wn * 4;
     const bf16_t* const gw0 = a.Wp + (u64)min(nb * 8 + wl * 2, NT - 1) * w_stride + lane * 8;
     const bf16_t* const gw1 = a.Wp + (u64)min(nb * 8 + wl * 2 + 1, NT - 1) * w_stride + lane * 8;
@@ -429,7 +453,14 @@ __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared&
     __syncthreads();
     struct Ops { bf16x8_t w0, w1, w2, w3, x0, x1, x2, x3; };
     Ops oa, ob;
-    TL_GLOAD(ga, 0) TL_STORE(ga, 0) TL_GLOAD(gb, 1) TL_STORE(gb, 1) TL_GLOAD(ga, 2) TL_GLOAD(gb, 3)
+    TL_GLOAD(ga, 0) TL_GLOAD(gb, 1)             // in flight while the norm scales are computed
+    for (u32 h = 0; h < halves; ++h) {
+      const u32 ih = it * halves + h;
+      u32 tbh = 0, nbh = 0;
+      if (ih < total) tile_coords(ih, nblocks, tblocks, nbh, tbh);
+      compute_rstd(a, tbh * 128, 128, sh, h * 128);   // its barriers: the LDS tiles are free
+    }
+    TL_STORE(ga, 0) TL_STORE(gb, 1) TL_GLOAD(ga, 2) TL_GLOAD(gb, 3)
     __syncthreads();
     oa.w0 = TL_RW(0, 0); oa.w1 = TL_RW(0, 1); oa.w2 = TL_RW(0, 2); oa.w3 = TL_RW(0, 3);
     oa.x0 = TL_RX(0, 0); oa.x1 = TL_RX(0, 1); oa.x2 = TL_RX(0, 2); oa.x3 = TL_RX(0, 3);
