@@ -52,8 +52,9 @@ struct MfmaGemmArgs {
   bf16_t* Kc;              // this layer's K cache and V cache
   bf16_t* Vc;
   u32 nq, nkv, hd, bs;
-  u32 tune_nw;             // low byte: 0 automatic choice of weight tiles per workgroup, 1/2/4 forced; bit 8: force the
-                           // 256-token workgroup tile of the eight-wave prefill schedule (tests and tuning)
+  u32 tune_nw;             // tests and tuning. Low byte: 0 automatic choice of weight tiles per workgroup, 1/2/4 forced.
+                           // Bit 9: tile schedule with direct loads instead of LDS staging (bit 8: its 256-token
+                           // workgroup tile in eight-wave kernels). Bit 10: no split of K between workgroup halves.
 };
 
 #define GEMM_MAX_WAVES 8
@@ -414,11 +415,17 @@ __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared&
   unsigned char* const Lw = sh.tile[half] + (wl * 2) * 1024 + lane * 16;   // this wave stores tiles 2 wl, 2 wl + 1 of both operands
   const unsigned char* const Lrw = sh.tile[half] + (wn * 4) * 1024 + lane * 16;
   const unsigned char* const Lrx = sh.tile[half] + 8192 + (wt * 4) * 1024 + lane * 16;
-  const u32 nitems = (total + halves - 1) / halves;
+  // With fewer tiles than eight-wave workgroups that can run at once (one per CU, two workgroups launched per CU), the two
+  // halves of a workgroup share one tile: each accumulates half of K, and the second half's sums are added to the
+  // first's through LDS before the epilogue (fixed order, so the result does not depend on timing).
+  const bool splitk = halves == 2 && (KT & 1u) == 0 && total <= nwg / 2 && !(a.tune_nw & 0x400u);   // bit 10: never (tests)
+  const u32 per_item = splitk ? 1u : halves;
+  const u32 k0 = (splitk && half) ? KT / 2 : 0u, kn = splitk ? KT / 2 : KT, klast = k0 + kn - 1;
+  const u32 nitems = (total + per_item - 1) / per_item;
   for (u32 base = 0; base < nitems; base += nwg) {
     const u32 it = xcd_item(base, nitems, wg, nwg);
     if (it == ~0u) continue;
-    const u32 item = it * halves + half;
+    const u32 item = splitk ? it : it * halves + half;
     const bool valid = item < total;            // the spare half of the last pair computes a duplicate and drops it
     u32 tb = 0, nb = 0;
     if (valid) tile_coords(item, nblocks, tblocks, nb, tb);
@@ -433,7 +440,7 @@ __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared&
       for (int j = 0; j < 4; ++j) acc[i][j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
     // staging registers as separate variables (arrays or structs of them may end up in scratch memory)
     uint4 ga0, ga1, ga2, ga3, gb0, gb1, gb2, gb3;
-#define TL_GLOAD(g, kt) { const u32 kc_ = min((u32)(kt), KT - 1); const bf16_t* px_ = gx + (u64)kc_ * xk_stride;           \
+#define TL_GLOAD(g, kt) { const u32 kc_ = min(k0 + (u32)(kt), klast); const bf16_t* px_ = gx + (u64)kc_ * xk_stride;           \
       g##0 = *(const uint4*)(gw0 + (u64)kc_ * 512); g##1 = *(const uint4*)(gw1 + (u64)kc_ * 512);                          \
       g##2 = *(const uint4*)(px_); g##3 = *(const uint4*)(px_ + 512); }
 #define TL_STORE(g, buf) { unsigned char* p_ = Lw + (buf) * GEMM_TILE_LDS;                                                 \
@@ -454,8 +461,8 @@ __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared&
     struct Ops { bf16x8_t w0, w1, w2, w3, x0, x1, x2, x3; };
     Ops oa, ob;
     TL_GLOAD(ga, 0) TL_GLOAD(gb, 1)             // in flight while the norm scales are computed
-    for (u32 h = 0; h < halves; ++h) {
-      const u32 ih = it * halves + h;
+    for (u32 h = 0; h < per_item; ++h) {
+      const u32 ih = it * per_item + h;
       u32 tbh = 0, nbh = 0;
       if (ih < total) tile_coords(ih, nblocks, tblocks, nbh, tbh);
       compute_rstd(a, tbh * 128, 128, sh, h * 128);   // its barriers: the LDS tiles are free
@@ -464,9 +471,9 @@ __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared&
     __syncthreads();
     oa.w0 = TL_RW(0, 0); oa.w1 = TL_RW(0, 1); oa.w2 = TL_RW(0, 2); oa.w3 = TL_RW(0, 3);
     oa.x0 = TL_RX(0, 0); oa.x1 = TL_RX(0, 1); oa.x2 = TL_RX(0, 2); oa.x3 = TL_RX(0, 3);
-    for (u32 k = 0; k < KT; k += 2) {
+    for (u32 k = 0; k < kn; k += 2) {
       TL_STEP(oa, ob, ga, k, 1, 0)
-      if (k + 1 < KT) { TL_STEP(ob, oa, gb, k + 1, 0, 1) }
+      if (k + 1 < kn) { TL_STEP(ob, oa, gb, k + 1, 0, 1) }
     }
 #undef TL_GLOAD
 #undef TL_STORE
@@ -476,13 +483,30 @@ __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared&
 #undef TL_ROW
 #undef TL_SB
 #undef TL_STEP
-    if (valid) {
+    if (splitk) {   // the last barrier of the k loop has passed: the LDS tiles (64 KB in all) are free
+      float* red = (float*)&sh.tile[0][0] + ((u64)wl * 16 * 64 + lane) * 4;
+      if (half == 1) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) *(floatx4_t*)(red + (i * 4 + j) * 256) = acc[i][j];
+      }
+      __syncthreads();
+      if (half == 0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc[i][j] += *(const floatx4_t*)(red + (i * 4 + j) * 256);
+      }
+    }
+    const u32 rstd_off = splitk ? 0u : half * 128;
+    if (valid && !(splitk && half)) {
 #pragma unroll
       for (int i = 0; i < 4; ++i)
         if (nt0 + i < NT) {
 #pragma unroll
           for (int j = 0; j < 4; ++j)
-            epilogue_tile<EPI>(a, acc[i][j], nt0 + i, tb * 128 + wt * 64 + j * 16, &sh.rstd[half * 128 + wt * 64 + j * 16]);
+            epilogue_tile<EPI>(a, acc[i][j], nt0 + i, tb * 128 + wt * 64 + j * 16, &sh.rstd[rstd_off + wt * 64 + j * 16]);
         }
     }
   }

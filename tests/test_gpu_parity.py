@@ -90,12 +90,13 @@ def test_bf16_forced_tiles_per_workgroup(lib, nw, monkeypatch):
     print("forced", nw, "tiles per workgroup: worst relative logit error", worst)
 
 
-@pytest.mark.parametrize("tile256", [0, 1])
-def test_bf16_large_prefill_iterations(lib, tile256, monkeypatch):
-    """Prefill iterations of ~1000 tokens (nine 128-token tiles with a ragged last one); the eight-wave kernels once
-    with their 128-token and once with their 256-token workgroup tile (the automatic choice needs llama-sized
-    matrices to pick the latter)."""
-    monkeypatch.setenv("BLINK_TUNE_NW", str(256 * tile256))
+@pytest.mark.parametrize("tune", [0, 0x400, 0x200, 0x300])
+def test_bf16_large_prefill_iterations(lib, tune, monkeypatch):
+    """Prefill iterations of ~1000 tokens (nine 128-token tiles with a ragged last one, ragged last row block) through
+    every variant of the tile schedule: LDS-staged tiles with the two halves of an eight-wave workgroup splitting K
+    (the automatic choice at this size) or taking a tile each, and direct-load tiles with the 128- and the 256-token
+    workgroup tile."""
+    monkeypatch.setenv("BLINK_TUNE_NW", str(tune))
     cfg, eng, raw, blob = setup("mini_wide4", 39)
     eng = dict(eng, max_batch=40, max_prefill_tokens=1100, kv_num_blocks=200)
     reqs = synth.make_workload("mini", cfg["vocab"], 139, n_requests=44)
