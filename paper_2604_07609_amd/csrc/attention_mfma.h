@@ -193,14 +193,35 @@ __device__ __forceinline__ void attn_decode_combine(const DevCtx& c, u32 wg, u32
     const u32 t = c.cu_seqlens[s];
     for (u32 idx = threadIdx.x; idx < G * HD; idx += blockDim.x) {
       const u32 h = idx / HD, dim = idx % HD;
-      float M = -INFINITY;
-      for (u32 p = 0; p < nch; ++p) M = fmaxf(M, c.attn_part_ml[(((u64)(c0 + p) * c.nkv + g) * G + h) * 2]);
-      float L = 0.f, O = 0.f;
-      for (u32 p = 0; p < nch; ++p) {
-        const u64 base = ((u64)(c0 + p) * c.nkv + g) * G;
-        const float f = __expf(c.attn_part_ml[(base + h) * 2] - M);
-        L += c.attn_part_ml[(base + h) * 2 + 1] * f;
-        O += c.attn_part_o[(base + h) * HD + dim] * f;
+      constexpr u32 MAXC = 12;   // chunks whose partial results are fetched together (one memory round trip)
+      float M = -INFINITY, L = 0.f, O = 0.f;
+      if (nch <= MAXC) {
+        float2 ml[MAXC];
+        float ov[MAXC];
+#pragma unroll
+        for (u32 p = 0; p < MAXC; ++p) {
+          const u64 base = ((u64)(c0 + min(p, nch - 1)) * c.nkv + g) * G;
+          ml[p] = *(const float2*)(c.attn_part_ml + (base + h) * 2);
+          ov[p] = c.attn_part_o[(base + h) * HD + dim];
+        }
+#pragma unroll
+        for (u32 p = 0; p < MAXC; ++p)
+          if (p < nch) M = fmaxf(M, ml[p].x);
+#pragma unroll
+        for (u32 p = 0; p < MAXC; ++p)
+          if (p < nch) {
+            const float f = __expf(ml[p].x - M);
+            L += ml[p].y * f;
+            O += ov[p] * f;
+          }
+      } else {
+        for (u32 p = 0; p < nch; ++p) M = fmaxf(M, c.attn_part_ml[(((u64)(c0 + p) * c.nkv + g) * G + h) * 2]);
+        for (u32 p = 0; p < nch; ++p) {
+          const u64 base = ((u64)(c0 + p) * c.nkv + g) * G;
+          const float f = __expf(c.attn_part_ml[(base + h) * 2] - M);
+          L += c.attn_part_ml[(base + h) * 2 + 1] * f;
+          O += c.attn_part_o[(base + h) * HD + dim] * f;
+        }
       }
       c.aq[packed_off(t, (g * G + h) * HD + dim, c.TBS)] = f32_to_bf16(O / L);
     }

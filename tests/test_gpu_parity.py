@@ -108,15 +108,19 @@ def test_bf16_large_prefill_iterations(lib, tune, monkeypatch):
     print("large prefill: worst relative logit error", worst)
 
 
-@pytest.mark.parametrize("name", ["mini_gqa128", "mini_gqa"])
-def test_bf16_long_contexts(lib, name):
-    """Contexts of 500..2100 tokens: decode attention works in 1024-token chunks whose partial results a second
-    kernel merges; prefill attention walks up to 65 KV blocks; one short context shares the batch."""
+@pytest.mark.parametrize("name,prompts", [("mini_gqa128", [1030, 2070, 7, 1023]), ("mini_gqa", [1030, 2070, 7, 1023]),
+                                          ("mini_gqa128", [6300, 40])])
+def test_bf16_long_contexts(lib, name, prompts):
+    """Contexts of 500..2100 tokens: decode attention works in 512-token chunks whose partial results a second
+    kernel merges (up to 12 chunks fetched together; the 6300-token context has 13 and takes the kernel's general
+    loop); prefill attention walks up to 394 KV blocks; one short context shares the batch."""
     cfg, eng, raw, blob = setup(name, 37)
-    eng = dict(eng, max_seq_len=2200, kv_num_blocks=330, max_prefill_tokens=4096, max_batch=4)
+    top = max(prompts)
+    eng = dict(eng, max_seq_len=top + 130, kv_num_blocks=(sum(prompts) + 16 * len(prompts)) // 16 + 40,
+               max_prefill_tokens=max(4096, top + 64), max_batch=4)
     rng = np.random.default_rng(5)
     reqs = []
-    for i, P in enumerate([1030, 2070, 7, 1023]):
+    for i, P in enumerate(prompts):
         reqs.append(dict(arrival_s=0.0, prompt=rng.integers(0, cfg["vocab"], P).astype(np.int32), max_new_tokens=5,
                          temperature=0.0, top_k=0, top_p=1.0, seed=i))
     worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2)
