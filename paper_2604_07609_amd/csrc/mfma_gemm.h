@@ -55,6 +55,7 @@ struct MfmaGemmArgs {
   u32 tune_nw;             // tests and tuning. Low byte: 0 automatic choice of weight tiles per workgroup, 1/2/4 forced.
                            // Bit 9: tile schedule with direct loads instead of LDS staging (bit 8: its 256-token
                            // workgroup tile in eight-wave kernels). Bit 10: no split of K between workgroup halves.
+                           // Bit 11: no 64 x 64 streaming items for 64 < T <= 256.
 };
 
 #define GEMM_MAX_WAVES 8
@@ -220,11 +221,15 @@ constexpr int stream_batch(int NW, int TW) {
        : NW == 4 ? (TW >= 3 ? 1 : 3)
        : ((NW * TW >= 8) ? 2 : (NW + TW >= 5 ? 3 : 4));
 }
-template <int EPI, int NW, int TW, int U = stream_batch(NW, TW)>
+// GRID2D (64 < T <= 256, four token blocks per item): the work items are (tile group, group of 64 tokens) pairs, the
+// token group varying fastest so that the workgroups running together share weight rows in L2; the weight loads are
+// ordinary (cached) ones then.
+template <int EPI, int NW, int TW, int U = stream_batch(NW, TW), bool GRID2D = false>
 __device__ __forceinline__ void gemm_stream(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg) {
   const u32 lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const u32 NT = (a.N + 15) / 16, KT = a.K / 32;
-  const u32 NG = (NT + NW - 1) / NW;                       // groups of NW tiles
+  const u32 TG = GRID2D ? (a.T + 63) / 64 : 1u;            // groups of 64 tokens
+  const u32 NG = ((NT + NW - 1) / NW) * TG;                // work items: groups of NW tiles x token groups
   const u32 KS = blockDim.x >> 6;                          // waves of the workgroup: each takes a slice of K
   const u32 kb = (u32)((u64)KT * w / KS), ke = (u32)((u64)KT * (w + 1) / KS);
   const u32 nbatch = (KT / KS + (KT % KS ? 1 : 0) + U - 1) / U;   // same count in every wave (loads past `ke` are zeros)
@@ -239,7 +244,9 @@ __device__ __forceinline__ void gemm_stream(const MfmaGemmArgs& a, MfmaShared& s
   }
   const u64 xk_stride = (u64)a.TBS * 512;
   const bf16x8_t zero = {0, 0, 0, 0, 0, 0, 0, 0};
-  auto issue = [&](StreamBuf<U, NW, TW>& b, u32 ng, u32 kt0) {
+  auto issue = [&](StreamBuf<U, NW, TW>& b, u32 item, u32 kt0) {
+    const u32 ng = item / TG;
+    const bf16_t* xg = a.Xp + (u64)(item % TG) * (TW * 512);   // the item's token group: TW consecutive token blocks
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const u32 kt = kt0 + u;
@@ -247,10 +254,11 @@ __device__ __forceinline__ void gemm_stream(const MfmaGemmArgs& a, MfmaShared& s
 #pragma unroll
       for (int i = 0; i < NW; ++i) {
         const u32 nt = min(ng * NW + i, NT - 1);           // a tile past the end is computed and dropped
-        b.w[u][i] = ok ? ld_tile_stream(a.Wp + ((u64)nt * KT + kt) * 512 + lane * 8) : zero;
+        const bf16_t* wp = a.Wp + ((u64)nt * KT + kt) * 512 + lane * 8;
+        b.w[u][i] = ok ? (GRID2D ? ld_tile(wp) : ld_tile_stream(wp)) : zero;
       }
 #pragma unroll
-      for (int tw = 0; tw < TW; ++tw) b.x[u][tw] = ok ? ld_tile(a.Xp + (u64)kt * xk_stride + xoff[tw]) : zero;
+      for (int tw = 0; tw < TW; ++tw) b.x[u][tw] = ok ? ld_tile(xg + (u64)kt * xk_stride + xoff[tw]) : zero;
     }
   };
   // Software pipeline over the flat sequence of (tile group, batch) steps of this workgroup: while one buffer is
@@ -264,7 +272,7 @@ __device__ __forceinline__ void gemm_stream(const MfmaGemmArgs& a, MfmaShared& s
 #pragma unroll
     for (int tw = 0; tw < TW; ++tw) acc[i][tw] = floatx4_t{0.f, 0.f, 0.f, 0.f};
   issue(bufA, ng, kb);               // the first loads are in flight while the norm scales are computed
-  compute_rstd(a, 0, 64, sh);
+  compute_rstd(a, 0, min(64 * TG, 256u), sh);
   auto step = [&](StreamBuf<U, NW, TW>& use, StreamBuf<U, NW, TW>& fill) -> bool {
     const bool last = b + 1 >= nbatch;
     const u32 nng = last ? ng + nwg : ng;
@@ -286,13 +294,14 @@ __device__ __forceinline__ void gemm_stream(const MfmaGemmArgs& a, MfmaShared& s
 #pragma unroll
       for (int tw = 0; tw < TW; ++tw) *(floatx4_t*)&sh.red[w][tw][lane][0] = acc[i][tw];
       __syncthreads();
-      if (w < TW && ng * NW + i < NT) {      // wave w finishes token block w: fixed summation order
+      const u32 nt = (ng / TG) * NW + i, tg = ng % TG;
+      if (w < TW && nt < NT) {               // wave w finishes token block w: fixed summation order
         floatx4_t s = (*(floatx4_t*)&sh.red[0][w][lane][0] + *(floatx4_t*)&sh.red[1][w][lane][0]) +
                       (*(floatx4_t*)&sh.red[2][w][lane][0] + *(floatx4_t*)&sh.red[3][w][lane][0]);
         if (KS == 8)
           s += (*(floatx4_t*)&sh.red[4][w][lane][0] + *(floatx4_t*)&sh.red[5][w][lane][0]) +
                (*(floatx4_t*)&sh.red[6][w][lane][0] + *(floatx4_t*)&sh.red[7][w][lane][0]);
-        epilogue_tile<EPI>(a, s, ng * NW + i, w * 16, &sh.rstd[w * 16]);
+        epilogue_tile<EPI>(a, s, nt, tg * 64 + w * 16, &sh.rstd[tg * 64 + w * 16]);
       }
 #pragma unroll
       for (int tw = 0; tw < TW; ++tw) acc[i][tw] = floatx4_t{0.f, 0.f, 0.f, 0.f};
@@ -432,7 +441,18 @@ __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared&
     const u32 nt0 = nb * 8 + wn * 4;
     const bf16_t* const gw0 = a.Wp + (u64)min(nb * 8 + wl * 2, NT - 1) * w_stride + lane * 8;
     const bf16_t* const gw1 = a.Wp + (u64)min(nb * 8 + wl * 2 + 1, NT - 1) * w_stride + lane * 8;
-    const bf16_t* const gx = a.Xp + (u64)(tb * 8 + wl * 2) * 512 + lane * 8;
+    // this lane's 16 bytes of the two activation tiles its wave fetches; through the token indirection (LM head) the
+    // sixteen tokens of a tile come from arbitrary columns of the operand
+    const bf16_t *gx0, *gx1;
+    if (a.tok_index) {
+      const u32 ta = tb * 128 + wl * 32 + (lane & 15);
+      const u32 s0 = a.tok_index[min(ta, a.T - 1)], s1 = a.tok_index[min(ta + 16, a.T - 1)];
+      gx0 = a.Xp + ((u64)(s0 >> 4) * 64 + (s0 & 15) + 16 * (lane >> 4)) * 8;
+      gx1 = a.Xp + ((u64)(s1 >> 4) * 64 + (s1 & 15) + 16 * (lane >> 4)) * 8;
+    } else {
+      gx0 = a.Xp + (u64)(tb * 8 + wl * 2) * 512 + lane * 8;
+      gx1 = gx0 + 512;
+    }
     floatx4_t acc[4][4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -440,9 +460,9 @@ __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared&
       for (int j = 0; j < 4; ++j) acc[i][j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
     // staging registers as separate variables (arrays or structs of them may end up in scratch memory)
     uint4 ga0, ga1, ga2, ga3, gb0, gb1, gb2, gb3;
-#define TL_GLOAD(g, kt) { const u32 kc_ = min(k0 + (u32)(kt), klast); const bf16_t* px_ = gx + (u64)kc_ * xk_stride;           \
+#define TL_GLOAD(g, kt) { const u32 kc_ = min(k0 + (u32)(kt), klast);                                                      \
       g##0 = *(const uint4*)(gw0 + (u64)kc_ * 512); g##1 = *(const uint4*)(gw1 + (u64)kc_ * 512);                          \
-      g##2 = *(const uint4*)(px_); g##3 = *(const uint4*)(px_ + 512); }
+      g##2 = *(const uint4*)(gx0 + (u64)kc_ * xk_stride); g##3 = *(const uint4*)(gx1 + (u64)kc_ * xk_stride); }
 #define TL_STORE(g, buf) { unsigned char* p_ = Lw + (buf) * GEMM_TILE_LDS;                                                 \
       *(uint4*)(p_) = g##0; *(uint4*)(p_ + 1024) = g##1; *(uint4*)(p_ + 8192) = g##2; *(uint4*)(p_ + 8192 + 1024) = g##3; }
 #define TL_RW(buf, i) as_bf16x8(*(const uint4*)(Lrw + (buf) * GEMM_TILE_LDS + (i) * 1024))
@@ -471,6 +491,7 @@ __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared&
     __syncthreads();
     oa.w0 = TL_RW(0, 0); oa.w1 = TL_RW(0, 1); oa.w2 = TL_RW(0, 2); oa.w3 = TL_RW(0, 3);
     oa.x0 = TL_RX(0, 0); oa.x1 = TL_RX(0, 1); oa.x2 = TL_RX(0, 2); oa.x3 = TL_RX(0, 3);
+    __syncthreads();   // step 0 overwrites buffer 0, which every wave has just read (later steps read a buffer one step ahead)
     for (u32 k = 0; k < kn; k += 2) {
       TL_STEP(oa, ob, ga, k, 1, 0)
       if (k + 1 < kn) { TL_STEP(ob, oa, gb, k + 1, 0, 1) }
@@ -541,7 +562,10 @@ __device__ __forceinline__ void gemm_mfma(const MfmaGemmArgs& a, MfmaShared& sh,
   else if (a.T <= 32) gemm_stream_nw<EPI, 2, WIDE>(a, sh, wg, nwg);
   else if (a.T <= 48) gemm_stream_nw<EPI, 3, WIDE>(a, sh, wg, nwg);
   else if (a.T <= 64) gemm_stream_nw<EPI, 4, WIDE>(a, sh, wg, nwg);
-  else if (a.tok_index || (a.tune_nw & 0x200u)) gemm_tile<EPI>(a, sh, wg, nwg);   // bit 9: direct-load tiles (tests and tuning)
+  else if (WIDE && !a.tok_index && a.T <= 256 && !(a.tune_nw & 0x800u) &&
+           ((a.N + 127) / 128) * ((a.T + 127) / 128) * 8 <= nwg)       // few 128 x 128 tiles: 64 x 64 items fill the chip
+    gemm_stream<EPI, 4, 4, 1, true>(a, sh, wg, nwg);                      // (bit 11 of the tuning word: never)
+  else if (a.tune_nw & 0x200u) gemm_tile<EPI>(a, sh, wg, nwg);   // bit 9: direct-load tiles (tests and tuning)
   else gemm_tile_lds<EPI>(a, sh, wg, nwg);
 }
 

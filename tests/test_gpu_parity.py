@@ -75,6 +75,23 @@ def test_bf16_wide_matrices(lib, name, max_batch, n_req):
     print(name, "max_batch", max_batch, "worst relative logit error", worst)
 
 
+@pytest.mark.parametrize("max_batch,tune", [(100, 0), (200, 0), (250, 0x800), (150, 0x200)])
+def test_bf16_decode_batches_beyond_64(lib, max_batch, tune, monkeypatch):
+    """Decode iterations of 65..256 tokens: the eight-wave projections run 64 x 64 streaming items over a
+    (rows, token groups) grid (or, with bit 11 of the tuning word, the tile schedule), the gate/up projection the
+    tile schedule, and the LM head the tile schedule through its token indirection (LDS-staged, or with bit 9
+    direct-load tiles)."""
+    monkeypatch.setenv("BLINK_TUNE_NW", str(tune))
+    cfg, eng, raw, blob = setup("mini_wide2", 35)
+    eng = dict(eng, max_batch=max_batch, kv_num_blocks=3 * max_batch + 64, ring_slots=512, max_prefill_tokens=2048)
+    reqs = synth.make_workload("mini", cfg["vocab"], 535 + max_batch, n_requests=max_batch + 9)
+    for r in reqs:
+        r["max_new_tokens"] = min(r["max_new_tokens"], 3)
+        r["prompt"] = r["prompt"][:20]
+    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2)
+    print("max_batch", max_batch, "worst relative logit error", worst)
+
+
 @pytest.mark.parametrize("nw", [1, 2, 4])
 def test_bf16_forced_tiles_per_workgroup(lib, nw, monkeypatch):
     """Every GEMM of the streaming schedule forced to 1, 2 or 4 weight tiles per workgroup (the automatic choice picks
