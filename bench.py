@@ -36,7 +36,7 @@ WORKLOADS = {
 }
 
 
-def phase_bytes(cfg, phase, n_tokens, n_seqs):
+def phase_bytes(cfg, phase, n_tokens, n_seqs, ctx_tokens=0):
     """Algorithmic HBM bytes of one launch of a GEMM phase: the weight matrix once, plus the activations it reads
     and writes once (bf16 path: bf16 operands, fp32 residual stream read + written; fp32 path: fp32 throughout)."""
     bf = cfg["dtype"] == 1
@@ -55,6 +55,9 @@ def phase_bytes(cfg, phase, n_tokens, n_seqs):
         return es * d * F + T * ((2 * F if bf else 8 * F) + 8 * d + (2 * d if bf else 0))
     if phase == 10:     # logits are fp32
         return es * V * d + B * (ea * d + 4 * V)
+    if phase == 4:      # decode attention: K and V of every context token once, the queries, the output
+        kv_tok = 2 * cfg["n_kv_heads"] * cfg["head_dim"] * es
+        return kv_tok * ctx_tokens + T * 2 * ea * no
     raise ValueError(phase)
 
 
@@ -207,7 +210,9 @@ def main():
     ap.add_argument("--steps", type=int, default=0)
     ap.add_argument("--warmup", type=int, default=-1)
     ap.add_argument("--workload", default=os.environ.get("BLINK_BENCH_WORKLOAD", "llama3_8b"), choices=sorted(WORKLOADS))
-    ap.add_argument("--phase", type=int, default=7, help="forward phase whose kernel is timed for the roofline")
+    ap.add_argument("--phase", type=int, default=-1,
+                    help="forward phase whose kernel is timed for the roofline (default: the dominant one of the workload: "
+                         "decode attention for llama3_8b at its batch of 256, the gate/up GEMM otherwise)")
     ap.add_argument("--requests", type=int, default=0)
     ap.add_argument("--max-batch", type=int, default=0, help="override the engine's batch slots")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -221,6 +226,8 @@ def main():
         sys.exit(2)
     import paper_2604_07609_amd as B
 
+    if args.phase < 0:
+        args.phase = 4 if args.workload == "llama3_8b" and not args.max_batch else 7
     wl = WORKLOADS[args.workload]
     K = args.steps or wl["steps"]
     W = args.warmup if args.warmup >= 0 else wl["warmup"]
@@ -283,19 +290,20 @@ def main():
         if n == 0:
             return None
         ms = float(pm[sel].sum())
-        by = float(sum(phase_bytes(cfg, args.phase, int(t["n_tokens"]), int(t["n_seqs"])) for t in trp[sel])) * per_layer
+        by = float(sum(phase_bytes(cfg, args.phase, int(t["n_tokens"]), int(t["n_seqs"]), int(t["ctx_tokens"])) for t in trp[sel])) * per_layer
         return dict(launches=n, avg_launch_us=round(1e3 * ms / n, 3), bytes_per_launch=round(by / n), GBs=round(by / (ms * 1e-3) / 1e9, 2))
 
     d_cls, p_cls, a_cls = klass(decp), klass(~decp), klass(np.ones(len(pm), dtype=bool))
     kname = PHASE_NAMES.get(args.phase, str(args.phase))
     traffic = read_traffic(kname, args.workload)
-    roofline = dict(bound="hbm", kernel=kname, launch_class="launches of decode iterations (T = batch <= 64: weight streaming)",
+    roofline = dict(bound="hbm", kernel=kname,
+                    launch_class="launches of decode iterations" + (" (paged KV of every context read once)" if args.phase == 4 else " (weights read once)"),
                     achieved=d_cls["GBs"] if d_cls else None, peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(d_cls["GBs"] / HBM_PEAK_GBS, 4) if d_cls else None, traffic=traffic,
                     launches=d_cls["launches"] if d_cls else 0, avg_launch_us=d_cls["avg_launch_us"] if d_cls else None,
                     algorithmic_bytes_per_launch=d_cls["bytes_per_launch"] if d_cls else None,
                     all_launches=a_cls)
-    if p_cls:
+    if p_cls and args.phase != 4:
         es = 2 if cfg["dtype"] == 1 else 4
         wbytes = phase_bytes(cfg, args.phase, 0, 0)
         flops = float(sum(2.0 * (wbytes / es) * int(t["n_tokens"]) for t in trp[~decp])) * per_layer
@@ -304,14 +312,14 @@ def main():
         roofline["prefill_launches"] = p_cls
     # whole-step view of the decode iterations: algorithmic bytes of the step over its duration on the device clock
     step_ns = np.diff(tr["t_sched_begin_ns"].astype(np.int64))
-    ctx = np.zeros(len(tr))
     dec_step = None
     if dec.sum() > 2:
-        # context tokens per decode iteration are not traced; bound them from below by 0 (weights only)
         idx = np.nonzero(dec[:-1])[0]
-        b = np.array([decode_step_bytes(cfg, int(tr["n_seqs"][i]), 0) for i in idx], dtype=np.float64)
-        dec_step = dict(median_us=round(float(np.median(step_ns[idx])) / 1e3, 2), weights_only_GBs=round(float(b.sum() / step_ns[idx].sum()), 2),
-                        mean_batch=round(float(tr["n_seqs"][idx].mean()), 2))
+        b = np.array([decode_step_bytes(cfg, int(tr["n_seqs"][i]), int(tr["ctx_tokens"][i])) for i in idx], dtype=np.float64)
+        gbs = float(b.sum() / step_ns[idx].sum())
+        dec_step = dict(median_us=round(float(np.median(step_ns[idx])) / 1e3, 2), algorithmic_GBs=round(gbs, 2),
+                        frac_of_hbm_peak=round(gbs / HBM_PEAK_GBS, 4), mean_batch=round(float(tr["n_seqs"][idx].mean()), 2),
+                        mean_context_tokens=round(float(tr["ctx_tokens"][idx].mean() / max(1.0, tr["n_seqs"][idx].mean())), 1))
     out = {
         "metric": "output tokens/sec at 1 GPU; p50/p99 ITL; on-GPU scheduling us/iteration",
         "value": round(toks / dt, 2), "unit": "output tokens/s", "n_gpus": 1, "steps": iters, "warmup": W,

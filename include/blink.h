@@ -107,6 +107,7 @@ typedef struct {
   uint32_t free_blocks;        /* after allocation */
   uint64_t first_admitted;     /* ticket, valid when n_admitted > 0 */
   uint64_t t_sched_begin_ns, t_sched_end_ns, t_forward_end_ns, t_publish_end_ns; /* device wall clock */
+  uint64_t ctx_tokens;         /* sum over the batch of the context lengths its attention reads (KV tokens) */
 } blink_trace_record;
 
 typedef struct {

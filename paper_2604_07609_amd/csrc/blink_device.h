@@ -95,6 +95,7 @@ struct TraceRec {       // mirrors blink_trace_record
   u32 n_admitted, n_seqs, n_tokens, free_blocks;
   u64 first_admitted;
   u64 t_sched_begin, t_sched_end, t_forward_end, t_publish_end;
+  u64 ctx_tokens;
 };
 
 // host-visible mirror in pinned host memory, written by the scheduler with system-scope stores

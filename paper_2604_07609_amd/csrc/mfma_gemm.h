@@ -424,10 +424,12 @@ __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared&
   unsigned char* const Lw = sh.tile[half] + (wl * 2) * 1024 + lane * 16;   // this wave stores tiles 2 wl, 2 wl + 1 of both operands
   const unsigned char* const Lrw = sh.tile[half] + (wn * 4) * 1024 + lane * 16;
   const unsigned char* const Lrx = sh.tile[half] + 8192 + (wt * 4) * 1024 + lane * 16;
-  // With fewer tiles than eight-wave workgroups that can run at once (one per CU, two workgroups launched per CU), the two
+  // When that takes fewer rounds of eight-wave workgroups (one runs per CU, two are launched per CU), the two
   // halves of a workgroup share one tile: each accumulates half of K, and the second half's sums are added to the
   // first's through LDS before the epilogue (fixed order, so the result does not depend on timing).
-  const bool splitk = halves == 2 && (KT & 1u) == 0 && total <= nwg / 2 && !(a.tune_nw & 0x400u);   // bit 10: never (tests)
+  // (rounds of workgroups, one per CU: a tile takes a workgroup half as long when its halves share it)
+  const u32 ncu = nwg / 2, rounds_split = (total + ncu - 1) / ncu, rounds_pair = ((total + 1) / 2 + ncu - 1) / ncu;
+  const bool splitk = halves == 2 && (KT & 1u) == 0 && rounds_split < 2 * rounds_pair && !(a.tune_nw & 0x400u);   // bit 10: never (tests)
   const u32 per_item = splitk ? 1u : halves;
   const u32 k0 = (splitk && half) ? KT / 2 : 0u, kn = splitk ? KT / 2 : KT, klast = k0 + kn - 1;
   const u32 nitems = (total + per_item - 1) / per_item;

@@ -231,6 +231,7 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
 
   // ---- (5) allocate + (6) metadata, batch slot ascending ----------------------------------------------------
   u32 n_seqs = 0, n_tok = 0, n_alloc = 0, n_qt = 0, n_ch = 0, max_q = 0, max_ctx = 0;
+  u64 n_ctx = 0;
   if (kind != KIND_IDLE) {
     for (u32 base = 0; base < c.max_batch; base += BLK_THREADS) {
       const u32 b = base + tid;
@@ -262,6 +263,8 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
       const u32 si = n_seqs + block_excl_scan(in ? 1u : 0u, tots, sh.wave_part);
       const u32 aoff = n_alloc + block_excl_scan(nalloc, tota, sh.wave_part2);
       const u32 toff = n_tok + block_excl_scan(ntok, tott, sh.wave_part);
+      u32 totx;
+      block_excl_scan(ctx_after, totx, sh.wave_part2);     // context tokens the attention of this iteration reads
       if (in) {
         RunEntry& r = c.run[b];
         u32* bt = c.block_tables + (u64)b * mbs;
@@ -289,8 +292,9 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
           r.in_iter = 0;
         }
       }
-      max_q = max(max_q, block_max(ntok, sh.wave_part2));
-      max_ctx = max(max_ctx, block_max(in ? (kind == KIND_DECODE ? ctx + 1 : ntok) : 0u, sh.wave_part));
+      max_q = max(max_q, block_max(ntok, sh.wave_part));
+      max_ctx = max(max_ctx, block_max(ctx_after, sh.wave_part2));
+      n_ctx += totx;
       n_seqs += tots;
       n_alloc += tota;
       n_tok += tott;
@@ -364,6 +368,7 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
         tr.t_sched_end = now;
         tr.t_forward_end = 0;
         tr.t_publish_end = 0;
+        tr.ctx_tokens = n_ctx;
       }
     } else {
       if (ss->idle_since_ns == 0) ss->idle_since_ns = now;

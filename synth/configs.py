@@ -31,7 +31,7 @@ ENGINE_CONFIGS = {
                  max_prefill_tokens=8192, ring_slots=64, eos_token_id=-1),
     "churn": dict(kv_block_size=16, kv_num_blocks=0, max_batch=64, max_seq_len=2048 + 256,
                   max_prefill_tokens=8192, ring_slots=512, eos_token_id=-1),
-    "llama3_8b": dict(kv_block_size=16, kv_num_blocks=32768, max_batch=64, max_seq_len=4096 + 1024,
+    "llama3_8b": dict(kv_block_size=16, kv_num_blocks=32768, max_batch=256, max_seq_len=4096 + 1024,
                       max_prefill_tokens=8192, ring_slots=2048, eos_token_id=-1),
     "sched_stress": dict(kv_block_size=16, kv_num_blocks=65536, max_batch=512, max_seq_len=64,
                          max_prefill_tokens=8192, ring_slots=4096, eos_token_id=-1),

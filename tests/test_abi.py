@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_sizes_match_header():
     from paper_2604_07609_amd import binding
     assert ctypes.sizeof(binding.Config) == 104 and ctypes.sizeof(binding.Sampling) == 24 and ctypes.sizeof(binding.Stats) == 88
-    assert binding.EVENT_DTYPE.itemsize == 32 and binding.TRACE_DTYPE.itemsize == 72
+    assert binding.EVENT_DTYPE.itemsize == 32 and binding.TRACE_DTYPE.itemsize == 80
 
 
 def test_argument_errors_without_gpu():
