@@ -100,9 +100,11 @@ __device__ __forceinline__ void attn_block(const KVTile<HD>& kv, const bf16x8_t 
 
 #define ATTN_CHUNK_BLOCKS (ATTN_CHUNK_TOKENS / 16)   // KV blocks per decode work item
 #define ATTN_WAVES 8          // waves per workgroup of the attention kernel (512 threads: at most 256 registers per lane)
+#define ATTN_META_MAX 512     // sequences whose batch metadata the decode kernel keeps in LDS
 struct AttnMfmaShared {
   float m[ATTN_WAVES][16], l[ATTN_WAVES][16];
   float o[ATTN_WAVES][8][128];   // [wave][q head of the group][dim]
+  u32 cu_chunks[ATTN_META_MAX + 1], tok[ATTN_META_MAX], ctx[ATTN_META_MAX], bslot[ATTN_META_MAX];
 };
 
 // ---- decode: one workgroup per (sequence, kv head); its waves take the KV blocks round-robin ----------------------
@@ -116,18 +118,29 @@ __device__ __forceinline__ void attn_decode(const DevCtx& c, u32 layer, AttnMfma
   // Work item: (chunk of ATTN_CHUNK_TOKENS of one sequence's context, kv head). Chunks balance the load between short and long
   // contexts and give the chip enough items at small batch. A context of one chunk is finished here; longer ones
   // leave per-chunk partial results that attn_decode_combine (the next kernel) merges in chunk order.
-  const u32 total_chunks = c.cu_chunks[B];
+  // The batch metadata an item needs is copied into LDS once: finding an item's sequence is a binary search, and every
+  // step of it in global memory would be a dependent load in front of the item's first KV load.
+  const bool staged = B <= ATTN_META_MAX;
+  if (staged) {
+    for (u32 i = threadIdx.x; i <= B; i += blockDim.x) {
+      sh.cu_chunks[i] = c.cu_chunks[i];
+      if (i < B) { sh.tok[i] = c.cu_seqlens[i]; sh.ctx[i] = c.seq_len[i]; sh.bslot[i] = c.seq_bslot[i]; }
+    }
+    __syncthreads();
+  }
+  auto cu = [&](u32 i) { return staged ? sh.cu_chunks[i] : c.cu_chunks[i]; };
+  const u32 total_chunks = cu(B);
   for (u32 item = wg; item < total_chunks * c.nkv; item += nwg) {
     const u32 ci = item / c.nkv, g = item % c.nkv;
     u32 lo = 0, hi = B;                       // sequence of chunk ci: last s with cu_chunks[s] <= ci
     while (hi - lo > 1) {
       const u32 mid = (lo + hi) / 2;
-      if (c.cu_chunks[mid] <= ci) lo = mid; else hi = mid;
+      if (cu(mid) <= ci) lo = mid; else hi = mid;
     }
-    const u32 s = lo, ch = ci - c.cu_chunks[s], nch = c.cu_chunks[s + 1] - c.cu_chunks[s];
-    const u32 t = c.cu_seqlens[s];              // the sequence's single token of this iteration
-    const u32 ctx = c.seq_len[s];
-    const u32* bt = c.block_tables + (u64)c.seq_bslot[s] * c.max_blocks_per_seq;
+    const u32 s = lo, ch = ci - cu(s), nch = cu(s + 1) - cu(s);
+    const u32 t = staged ? sh.tok[s] : c.cu_seqlens[s];              // the sequence's single token of this iteration
+    const u32 ctx = staged ? sh.ctx[s] : c.seq_len[s];
+    const u32* bt = c.block_tables + (u64)(staged ? sh.bslot[s] : c.seq_bslot[s]) * c.max_blocks_per_seq;
     bf16x8_t q[1][HD / 32];
 #pragma unroll
     for (int st = 0; st < HD / 32; ++st) {
