@@ -31,7 +31,7 @@ PHASE_NAMES = {2: "k_qkv", 5: "k_oproj", 7: "k_gateup", 8: "k_down", 10: "k_lm_h
 WORKLOADS = {
     "tiny": dict(model="tiny", workload="tiny", wseed=1000, rseed=2000, steps=30, warmup=3),
     "churn": dict(model="churn", workload="churn", wseed=1001, rseed=2001, steps=600, warmup=20),
-    "llama3_8b": dict(model="llama3_8b", workload="llama3_8b", wseed=1002, rseed=2002, steps=200, warmup=20),
+    "llama3_8b": dict(model="llama3_8b", workload="llama3_8b", wseed=1002, rseed=2002, steps=200, warmup=60),
     "sched_stress": dict(model="sched_stress", workload="sched_stress", wseed=1003, rseed=2003, steps=100, warmup=5),
 }
 
@@ -216,6 +216,9 @@ def main():
     ap.add_argument("--requests", type=int, default=0)
     ap.add_argument("--max-batch", type=int, default=0, help="override the engine's batch slots")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--dump-iterations", default="",
+                    help="write one line per iteration of the warm-up and the timed window (kind, sequences, tokens, context "
+                         "tokens, timed flag): lets a rocprofv3 trace of the same run be split by iteration kind")
     ap.add_argument("--open-loop-seconds", type=float, default=8.0, help="0: skip the run with the workload's own arrivals")
     ap.add_argument("--interference", action="store_true",
                     help="repeat the open-loop run with a host memory-bandwidth stressor on every core and report the ratios")
@@ -265,6 +268,12 @@ def main():
     finally:
         e.shutdown()
 
+    if args.dump_iterations:
+        with open(args.dump_iterations, "w") as f:
+            f.write("# iteration kind n_seqs n_tokens ctx_tokens timed\n")
+            for t in trace[trace["iteration"] < s1["iterations"]]:
+                f.write("%d %d %d %d %d %d\n" % (t["iteration"], t["kind"], t["n_seqs"], t["n_tokens"], t["ctx_tokens"],
+                                                 int(t["iteration"] >= s0["iterations"])))
     iters = int(s1["iterations"] - s0["iterations"])
     toks = int(s1["tokens_out"] - s0["tokens_out"])
     dt = t1 - t0

@@ -206,6 +206,16 @@ __device__ __forceinline__ bf16x8_t ld_tile_stream(const bf16_t* p) {
   return *(const bf16x8_t*)&v;
 }
 
+// Work item of a workgroup in the round that starts at item `base`. Workgroups are dealt to the eight XCDs round-robin
+// (workgroup id modulo 8), and each XCD has its own L2: the workgroups of one XCD take consecutive items, so that the
+// operand blocks those items share are fetched into that L2 once. Returns ~0u when the round has no item for `wg`.
+__device__ __forceinline__ u32 xcd_item(u32 base, u32 total, u32 wg, u32 nwg) {
+  const u32 cnt = min(nwg, total - base);
+  if (nwg & 7u) return wg < cnt ? base + wg : ~0u;
+  const u32 q = (cnt + 7) / 8, x = wg & 7u, l = wg >> 3, off = x * q + l;
+  return (l < q && off < cnt) ? base + off : ~0u;
+}
+
 template <int U, int NW, int TW>
 struct StreamBuf {
   bf16x8_t w[U][NW];
@@ -233,7 +243,15 @@ __device__ __forceinline__ void gemm_stream(const MfmaGemmArgs& a, MfmaShared& s
   const u32 KS = blockDim.x >> 6;                          // waves of the workgroup: each takes a slice of K
   const u32 kb = (u32)((u64)KT * w / KS), ke = (u32)((u64)KT * (w + 1) / KS);
   const u32 nbatch = (KT / KS + (KT % KS ? 1 : 0) + U - 1) / U;   // same count in every wave (loads past `ke` are zeros)
-  if (wg >= NG) return;
+  // GRID2D: the items of one round go to the XCDs in runs (the token groups of a tile group share the weight rows in
+  // one L2); otherwise item = workgroup + round * workgroups
+  u32 round = 0;
+  auto item_of = [&](u32 r) -> u32 {
+    const u32 base = r * nwg;
+    if (base >= NG) return ~0u;
+    return GRID2D ? xcd_item(base, NG, wg, nwg) : (base + wg < NG ? base + wg : ~0u);
+  };
+  if (item_of(0) == ~0u) return;
   // per-lane offsets (in elements) of this lane's 16 bytes inside the token blocks of one k-tile
   u32 xoff[TW];
 #pragma unroll
@@ -265,7 +283,7 @@ __device__ __forceinline__ void gemm_stream(const MfmaGemmArgs& a, MfmaShared& s
   // consumed by the MFMAs, the loads of the following step (possibly the first batch of the next group) fill the
   // other. The two buffers swap roles by code position (no register copies, which would wait for loads in flight).
   StreamBuf<U, NW, TW> bufA, bufB;
-  u32 ng = wg, b = 0;
+  u32 ng = item_of(0), b = 0;
   floatx4_t acc[NW][TW];
 #pragma unroll
   for (int i = 0; i < NW; ++i)
@@ -275,7 +293,7 @@ __device__ __forceinline__ void gemm_stream(const MfmaGemmArgs& a, MfmaShared& s
   compute_rstd(a, 0, min(64 * TG, 256u), sh);
   auto step = [&](StreamBuf<U, NW, TW>& use, StreamBuf<U, NW, TW>& fill) -> bool {
     const bool last = b + 1 >= nbatch;
-    const u32 nng = last ? ng + nwg : ng;
+    const u32 nng = last ? item_of(round + 1) : ng;
     if (nng < NG) issue(fill, nng, last ? kb : kb + (b + 1) * U);
     {
 #pragma unroll
@@ -308,6 +326,7 @@ __device__ __forceinline__ void gemm_stream(const MfmaGemmArgs& a, MfmaShared& s
     }
     ng = nng;
     b = 0;
+    ++round;
     return ng < NG;
   };
   for (;;) {
@@ -386,16 +405,6 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& a, MfmaShared& sh,
           epilogue_tile<EPI>(a, acc[i][j], nt0 + i, tb * BT + wt * 64 + j * 16, &sh.rstd[wt * 64 + j * 16]);
       }
   }
-}
-
-// Work item of a workgroup in the round that starts at item `base`. Workgroups are dealt to the eight XCDs round-robin
-// (workgroup id modulo 8), and each XCD has its own L2: the workgroups of one XCD take consecutive items, so that the
-// operand blocks those items share are fetched into that L2 once. Returns ~0u when the round has no item for `wg`.
-__device__ __forceinline__ u32 xcd_item(u32 base, u32 total, u32 wg, u32 nwg) {
-  const u32 cnt = min(nwg, total - base);
-  if (nwg & 7u) return wg < cnt ? base + wg : ~0u;
-  const u32 q = (cnt + 7) / 8, x = wg & 7u, l = wg >> 3, off = x * q + l;
-  return (l < q && off < cnt) ? base + off : ~0u;
 }
 
 // Tile order of the tile schedule: token blocks in groups of eight; inside a group the row blocks follow each other and

@@ -1,16 +1,18 @@
 """Turns rocprofv3 CSV output of a bench.py run into the short text summaries kept under profiles/.
 
-  python -m paper_2604_07609_amd.profile_summary trace  <kernel_trace.csv> <kernel> <workload> "<command>"
-  python -m paper_2604_07609_amd.profile_summary pmc    <fetch_counter.csv> <write_counter.csv> <kernel> <workload> "<cmd>"
+  python -m paper_2604_07609_amd.profile_summary trace <kernel_trace.csv> <iterations.txt> <kernel> <workload> "<command>"
+  python -m paper_2604_07609_amd.profile_summary pmc <fetch.csv> <write.csv> <iterations.txt> <kernel> <workload> "<cmd>"
 
-`trace`: per-kernel totals (what `--stats` prints) and, for the named kernel, the average duration of its launches
-split into the decode class (launches within 1.35x of the median: one weight-streaming pass) and the rest (prefill).
-`pmc`: HBM bytes per launch of the named kernel from FETCH_SIZE and WRITE_SIZE (KiB per dispatch), each scaled by
-what the same counter reads for the 64 MiB plain copy kernel that bench.py launches at its end.
+`iterations.txt` is what `bench.py --dump-iterations` wrote in the same run: the kind of every iteration. The dispatches
+in the CSV are cut into iterations at the scheduler kernel; iterations whose forward kernels do nothing (the launcher's
+look-ahead past the end of a window) are dropped, and the rest line up one to one with the lines of the file.
+`trace`: per-kernel totals (what `--stats` prints) and the named kernel's average launch duration in the decode and in
+the prefill iterations of the timed window. `pmc`: HBM bytes per launch of the named kernel in the timed decode
+iterations from FETCH_SIZE and WRITE_SIZE (KiB per dispatch), each scaled by what the same counter reads for the
+64 MiB plain copy kernel that bench.py launches at its end.
 """
 import collections
 import csv
-import statistics
 import sys
 
 COPY_BYTES = 64 << 20
@@ -20,7 +22,36 @@ def short(name):
     return name.split("(")[0]
 
 
-def trace_summary(path, kernel, workload, command):
+def read_kinds(path):
+    out = []
+    for line in open(path):
+        if line.startswith("#"):
+            continue
+        it, kind, n_seqs, n_tokens, ctx, timed = (int(x) for x in line.split())
+        out.append(dict(kind=kind, n_seqs=n_seqs, n_tokens=n_tokens, ctx_tokens=ctx, timed=timed))
+    return out
+
+
+def split_iterations(rows, value, order):
+    """rows -> list of iterations (lists of (kernel, value)); an iteration starts at k_sched. real_iterations drops the
+    look-ahead iterations, in which no forward kernel does anything: `value` of all their dispatches stays under a floor."""
+    rows = sorted(rows, key=order)
+    its, cur = [], None
+    for r in rows:
+        n = short(r["Kernel_Name"])
+        if n == "k_sched":
+            cur = []
+            its.append(cur)
+        elif cur is not None and n.startswith("k_") and n not in ("k_copy_calibration", "k_pack_weights", "k_rope_table", "k_open_window"):
+            cur.append((n, value(r)))
+    return its
+
+
+def real_iterations(its, floor):
+    return [it for it in its if max([v for _, v in it] or [0.0]) > floor]
+
+
+def trace_summary(path, kinds_path, kernel, workload, command):
     rows = [r for r in csv.DictReader(open(path))]
     dur = collections.defaultdict(list)
     for r in rows:
@@ -30,55 +61,49 @@ def trace_summary(path, kernel, workload, command):
            "| kernel | calls | total ms | avg us | % |", "|---|---|---|---|---|"]
     for k, v in sorted(dur.items(), key=lambda kv: -sum(kv[1]))[:14]:
         out.append("| %s | %d | %.1f | %.2f | %.1f |" % (k, len(v), sum(v) / 1e3, sum(v) / len(v), 100 * sum(v) / total))
-    v = [x for x in dur[kernel] if x > 8.0]          # launches of iterations past the end of a window do nothing
-    med = statistics.median(v)
-    dec = [x for x in v if x <= 1.35 * med]
-    pre = [x for x in v if x > 1.35 * med]
-    out += ["", "%s, launches that do work: %d, average %.2f us" % (kernel, len(v), sum(v) / len(v)),
-            "  decode class (<= 1.35 x median %.2f us): %d launches, average %.2f us" % (med, len(dec), sum(dec) / len(dec))]
-    if pre:
-        out.append("  prefill class: %d launches, average %.2f us" % (len(pre), sum(pre) / len(pre)))
-    out.append("  (bench.py reports the same two classes over its timed iterations only; warm-up launches are included here)")
+    kinds = read_kinds(kinds_path)
+    its = split_iterations(rows, lambda r: (int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3,
+                           lambda r: int(r["Start_Timestamp"]))
+    its = real_iterations(its, 8.0)                    # us: an empty launch takes 2-5 us under the profiler
+    out += ["", "iterations with work in the trace: %d; iterations bench.py recorded: %d" % (len(its), len(kinds))]
+    if len(its) == len(kinds):
+        for label, kind in (("decode", 2), ("prefill", 1)):
+            sel = [v for it, k in zip(its, kinds) if k["timed"] and k["kind"] == kind for n, v in it if n == kernel]
+            if sel:
+                out.append("%s, launches in the timed %s iterations: %d, average %.2f us" % (kernel, label, len(sel), sum(sel) / len(sel)))
+        out.append("(bench.py measures the same launches with HIP events and reports them as roofline.avg_launch_us)")
+    else:
+        out.append("(counts differ: no split by iteration kind)")
     return "\n".join(out) + "\n"
 
 
-def counter(path, kernel):
-    vals, copy = [], []
-    for r in csv.DictReader(open(path)):
-        n = short(r["Kernel_Name"])
-        if n == kernel:
-            vals.append(float(r["Counter_Value"]))
-        elif n == "k_copy_calibration":
-            copy.append(float(r["Counter_Value"]))
-    return vals, copy
-
-
-def pmc_summary(fetch_path, write_path, kernel, workload, command):
+def pmc_summary(fetch_path, write_path, kinds_path, kernel, workload, command):
     out = ["# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE: HBM traffic of %s on %s" % (kernel, workload), "",
            "commands (one counter per run): `%s`" % command, ""]
+    kinds = read_kinds(kinds_path)
     tot = 0.0
-    for label, path, copied in (("FETCH_SIZE", fetch_path, COPY_BYTES), ("WRITE_SIZE", write_path, COPY_BYTES)):
-        vals, copy = counter(path, kernel)
-        vals = [x for x in vals if x > 16.0]
-        med = statistics.median(vals)
-        dec = [x for x in vals if x <= 1.35 * med] if label == "FETCH_SIZE" else vals
-        factor = copied / 1024.0 / copy[0]
-        if label == "WRITE_SIZE":           # classify by the fetch classes is not possible across runs: use the median
-            per = med * 1024 * factor
-        else:
-            per = sum(dec) / len(dec) * 1024 * factor
+    for label, path in (("FETCH_SIZE", fetch_path), ("WRITE_SIZE", write_path)):
+        rows = [r for r in csv.DictReader(open(path))]
+        copy = [float(r["Counter_Value"]) for r in rows if short(r["Kernel_Name"]) == "k_copy_calibration"]
+        factor = COPY_BYTES / 1024.0 / copy[0]
+        its = split_iterations(rows, lambda r: float(r["Counter_Value"]), lambda r: int(r["Dispatch_Id"]))
+        its = real_iterations(its, 64.0)                 # KiB: an empty launch moves next to nothing
+        if len(its) != len(kinds):
+            out.append("%s: %d iterations with work in the counters, %d recorded by bench.py: no traffic figure" % (label, len(its), len(kinds)))
+            continue
+        sel = [v for it, k in zip(its, kinds) if k["timed"] and k["kind"] == 2 for n, v in it if n == kernel]
+        per = sum(sel) / len(sel) * 1024 * factor
         tot += per
-        out.append("%s: copy kernel of %d KiB reads %.1f KiB -> scale %.4f; %s decode class %s = %.1f KiB raw -> %.2f MB per launch"
-                   % (label, copied // 1024, copy[0], factor, kernel, "mean" if label == "FETCH_SIZE" else "median",
-                      per / 1024 / factor, per / 1e6))
+        out.append("%s: copy kernel of %d KiB counts %.1f KiB -> scale %.4f; %s in the timed decode iterations: %d launches, mean %.1f KiB raw -> %.2f MB per launch"
+                   % (label, COPY_BYTES // 1024, copy[0], factor, kernel, len(sel), sum(sel) / len(sel), per / 1e6))
     out += ["", "traffic_bytes_per_launch: %.0f" % tot]
     return "\n".join(out) + "\n"
 
 
 if __name__ == "__main__":
-    if sys.argv[1] == "trace":
-        sys.stdout.write(trace_summary(*sys.argv[2:6]))
-    elif sys.argv[1] == "pmc":
-        sys.stdout.write(pmc_summary(*sys.argv[2:7]))
+    if len(sys.argv) > 1 and sys.argv[1] == "trace":
+        sys.stdout.write(trace_summary(*sys.argv[2:7]))
+    elif len(sys.argv) > 1 and sys.argv[1] == "pmc":
+        sys.stdout.write(pmc_summary(*sys.argv[2:8]))
     else:
         sys.exit(__doc__)
