@@ -315,7 +315,8 @@ def main():
     if p_cls and args.phase != 4:
         es = 2 if cfg["dtype"] == 1 else 4
         wbytes = phase_bytes(cfg, args.phase, 0, 0)
-        flops = float(sum(2.0 * (wbytes / es) * int(t["n_tokens"]) for t in trp[~decp])) * per_layer
+        cols = "n_seqs" if args.phase == 10 else "n_tokens"     # the LM head runs on the last token of every sequence
+        flops = float(sum(2.0 * (wbytes / es) * int(t[cols]) for t in trp[~decp])) * per_layer
         p_cls["TFLOPs"] = round(flops / (float(pm[~decp].sum()) * 1e-3) / 1e12, 1)
         p_cls["mfma_peak_TFLOPs"] = 2500.0 if cfg["dtype"] == 1 else 157.3
         roofline["prefill_launches"] = p_cls
