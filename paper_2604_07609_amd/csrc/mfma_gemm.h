@@ -55,7 +55,8 @@ struct MfmaGemmArgs {
   u32 tune_nw;             // tests and tuning. Low byte: 0 automatic choice of weight tiles per workgroup, 1/2/4 forced.
                            // Bit 9: tile schedule with direct loads instead of LDS staging (bit 8: its 256-token
                            // workgroup tile in eight-wave kernels). Bit 10: no split of K between workgroup halves.
-                           // Bit 11: no 64 x 64 streaming items for 64 < T <= 256.
+                           // Bit 11: no 64 x 64 streaming items for 64 < T <= 256. Bits 12-14: 2, 3 or 4 force the
+                           // token tiles per wave of the LDS-staged tile schedule.
 };
 
 #define GEMM_MAX_WAVES 8
@@ -423,16 +424,23 @@ __device__ __forceinline__ void tile_coords(u32 i, u32 nblocks, u32 tblocks, u32
 // register set while the MFMAs of the current step run: one barrier per k-step, global traffic half of what four
 // waves loading their operands directly would request. An eight-wave workgroup runs two such tiles side by side
 // (separate LDS buffers, common barriers).
-template <int EPI>
+// TJ (2, 3 or 4): token tiles per wave; the workgroup tile is 128 rows x 32 TJ tokens. Narrower tiles cost more operand
+// traffic per flop but cut the tile grid finer: gemm_tile_pick takes the width whose rounds of workgroups finish first.
+template <int EPI, int TJ>
 __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg) {
+  constexpr u32 BT = 32 * TJ, XT = 2 * TJ;        // tokens and activation tiles of a workgroup tile
   const u32 lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const u32 halves = blockDim.x >> 8, half = w >> 2, wl = w & 3, wn = wl & 1, wt = wl >> 1;
   const u32 NT = (a.N + 15) / 16, KT = a.K / 32;
-  const u32 nblocks = (NT + 7) / 8, tblocks = (a.T + 127) / 128, total = nblocks * tblocks;
+  const u32 nblocks = (NT + 7) / 8, tblocks = (a.T + BT - 1) / BT, total = nblocks * tblocks;
   const u64 xk_stride = (u64)a.TBS * 512, w_stride = (u64)KT * 512;
-  unsigned char* const Lw = sh.tile[half] + (wl * 2) * 1024 + lane * 16;   // this wave stores tiles 2 wl, 2 wl + 1 of both operands
+  // LDS buffer of one k-step: weight tiles 0..7, then activation tiles 0..XT-1 (1 KB each). This wave stores weight
+  // tiles 2 wl, 2 wl + 1 and activation tiles wl and wl + 4 (the latter only if the tile has that many)
+  const bool x2 = TJ == 4 || wl + 4 < XT;     // known at compile time for full-width tiles: no branch around the load
+  unsigned char* const Lww = sh.tile[half] + (wl * 2) * 1024 + lane * 16;
+  unsigned char* const Lwx = sh.tile[half] + 8192 + wl * 1024 + lane * 16;
   const unsigned char* const Lrw = sh.tile[half] + (wn * 4) * 1024 + lane * 16;
-  const unsigned char* const Lrx = sh.tile[half] + 8192 + (wt * 4) * 1024 + lane * 16;
+  const unsigned char* const Lrx = sh.tile[half] + 8192 + (wt * TJ) * 1024 + lane * 16;
   // When that takes fewer rounds of eight-wave workgroups (one runs per CU, two are launched per CU), the two
   // halves of a workgroup share one tile: each accumulates half of K, and the second half's sums are added to the
   // first's through LDS before the epilogue (fixed order, so the result does not depend on timing).
@@ -453,40 +461,45 @@ __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared&
     const bf16_t* const gw0 = a.Wp + (u64)min(nb * 8 + wl * 2, NT - 1) * w_stride + lane * 8;
     const bf16_t* const gw1 = a.Wp + (u64)min(nb * 8 + wl * 2 + 1, NT - 1) * w_stride + lane * 8;
     // this lane's 16 bytes of the two activation tiles its wave fetches; through the token indirection (LM head) the
-    // sixteen tokens of a tile come from arbitrary columns of the operand
+    // sixteen tokens of a tile come from arbitrary columns of the operand. A tile past the operand's last token block
+    // (only in the last workgroup tile) is clamped: its columns are dropped by the epilogue.
     const bf16_t *gx0, *gx1;
     if (a.tok_index) {
-      const u32 ta = tb * 128 + wl * 32 + (lane & 15);
-      const u32 s0 = a.tok_index[min(ta, a.T - 1)], s1 = a.tok_index[min(ta + 16, a.T - 1)];
+      const u32 ta = tb * BT + wl * 16 + (lane & 15);
+      const u32 s0 = a.tok_index[min(ta, a.T - 1)], s1 = a.tok_index[min(ta + 64, a.T - 1)];
       gx0 = a.Xp + ((u64)(s0 >> 4) * 64 + (s0 & 15) + 16 * (lane >> 4)) * 8;
       gx1 = a.Xp + ((u64)(s1 >> 4) * 64 + (s1 & 15) + 16 * (lane >> 4)) * 8;
     } else {
-      gx0 = a.Xp + (u64)(tb * 8 + wl * 2) * 512 + lane * 8;
-      gx1 = gx0 + 512;
+      gx0 = a.Xp + (u64)min(tb * XT + wl, a.TBS - 1) * 512 + lane * 8;
+      gx1 = a.Xp + (u64)min(tb * XT + wl + 4, a.TBS - 1) * 512 + lane * 8;
     }
-    floatx4_t acc[4][4];
+    floatx4_t acc[4][TJ];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) acc[i][j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+      for (int j = 0; j < TJ; ++j) acc[i][j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
     // staging registers as separate variables (arrays or structs of them may end up in scratch memory)
     uint4 ga0, ga1, ga2, ga3, gb0, gb1, gb2, gb3;
+    ga3 = gb3 = make_uint4(0, 0, 0, 0);
 #define TL_GLOAD(g, kt) { const u32 kc_ = min(k0 + (u32)(kt), klast);                                                      \
       g##0 = *(const uint4*)(gw0 + (u64)kc_ * 512); g##1 = *(const uint4*)(gw1 + (u64)kc_ * 512);                          \
-      g##2 = *(const uint4*)(gx0 + (u64)kc_ * xk_stride); g##3 = *(const uint4*)(gx1 + (u64)kc_ * xk_stride); }
-#define TL_STORE(g, buf) { unsigned char* p_ = Lw + (buf) * GEMM_TILE_LDS;                                                 \
-      *(uint4*)(p_) = g##0; *(uint4*)(p_ + 1024) = g##1; *(uint4*)(p_ + 8192) = g##2; *(uint4*)(p_ + 8192 + 1024) = g##3; }
+      g##2 = *(const uint4*)(gx0 + (u64)kc_ * xk_stride); if (x2) g##3 = *(const uint4*)(gx1 + (u64)kc_ * xk_stride); }
+#define TL_STORE(g, buf) { *(uint4*)(Lww + (buf) * GEMM_TILE_LDS) = g##0; *(uint4*)(Lww + (buf) * GEMM_TILE_LDS + 1024) = g##1; \
+      *(uint4*)(Lwx + (buf) * GEMM_TILE_LDS) = g##2; if (x2) *(uint4*)(Lwx + (buf) * GEMM_TILE_LDS + 4096) = g##3; }
 #define TL_RW(buf, i) as_bf16x8(*(const uint4*)(Lrw + (buf) * GEMM_TILE_LDS + (i) * 1024))
-#define TL_RX(buf, j) as_bf16x8(*(const uint4*)(Lrx + (buf) * GEMM_TILE_LDS + (j) * 1024))
+#define TL_RX(buf, j) as_bf16x8(*(const uint4*)(Lrx + (buf) * GEMM_TILE_LDS + ((j) < TJ ? (j) : 0) * 1024))
 #define TL_MM(A, W, X) A = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W, X, A, 0, 0, 0);
-#define TL_ROW(i, o) TL_MM(acc[i][0], o.w##i, o.x0) TL_MM(acc[i][1], o.w##i, o.x1) TL_MM(acc[i][2], o.w##i, o.x2) TL_MM(acc[i][3], o.w##i, o.x3)
+#define TL_ROW(i, o) TL_MM(acc[i][0], o.w##i, o.x0) TL_MM(acc[i][1], o.w##i, o.x1)                                         \
+      if (TJ > 2) { TL_MM(acc[i][TJ > 2 ? 2 : 0], o.w##i, o.x2) } if (TJ > 3) { TL_MM(acc[i][TJ > 3 ? 3 : 0], o.w##i, o.x3) }
 #define TL_SB __builtin_amdgcn_sched_barrier(0);
     // step k with its operands in `o`: reads the operands of step k+1 from LDS buffer rb into `n`, stores the staged data
     // of step k+2 (in g) into LDS buffer wb and requests step k+4 into g
 #define TL_STEP(o, n, g, k, rb, wb)                                                                                       \
     n.x0 = TL_RX(rb, 0); n.w0 = TL_RW(rb, 0); n.x1 = TL_RX(rb, 1); n.w1 = TL_RW(rb, 1); TL_STORE(g, wb)                   \
     TL_SB TL_ROW(0, o) TL_ROW(1, o) TL_SB                                                                                 \
-    n.x2 = TL_RX(rb, 2); n.w2 = TL_RW(rb, 2); n.x3 = TL_RX(rb, 3); n.w3 = TL_RW(rb, 3); TL_GLOAD(g, (k) + 4)              \
+    if (TJ > 2) n.x2 = TL_RX(rb, 2);                                                                                      \
+    n.w2 = TL_RW(rb, 2); if (TJ > 3) n.x3 = TL_RX(rb, 3);                                                                  \
+    n.w3 = TL_RW(rb, 3); TL_GLOAD(g, (k) + 4)                                                                             \
     TL_SB TL_ROW(2, o) TL_ROW(3, o) TL_SB                                                                                 \
     __syncthreads();
     struct Ops { bf16x8_t w0, w1, w2, w3, x0, x1, x2, x3; };
@@ -496,7 +509,7 @@ __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared&
       const u32 ih = it * per_item + h;
       u32 tbh = 0, nbh = 0;
       if (ih < total) tile_coords(ih, nblocks, tblocks, nbh, tbh);
-      compute_rstd(a, tbh * 128, 128, sh, h * 128);   // its barriers: the LDS tiles are free
+      compute_rstd(a, tbh * BT, BT, sh, h * 128);   // its barriers: the LDS tiles are free
     }
     TL_STORE(ga, 0) TL_STORE(gb, 1) TL_GLOAD(ga, 2) TL_GLOAD(gb, 3)
     __syncthreads();
@@ -521,14 +534,14 @@ __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared&
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-          for (int j = 0; j < 4; ++j) *(floatx4_t*)(red + (i * 4 + j) * 256) = acc[i][j];
+          for (int j = 0; j < TJ; ++j) *(floatx4_t*)(red + (i * 4 + j) * 256) = acc[i][j];
       }
       __syncthreads();
       if (half == 0) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-          for (int j = 0; j < 4; ++j) acc[i][j] += *(const floatx4_t*)(red + (i * 4 + j) * 256);
+          for (int j = 0; j < TJ; ++j) acc[i][j] += *(const floatx4_t*)(red + (i * 4 + j) * 256);
       }
     }
     const u32 rstd_off = splitk ? 0u : half * 128;
@@ -537,11 +550,33 @@ __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared&
       for (int i = 0; i < 4; ++i)
         if (nt0 + i < NT) {
 #pragma unroll
-          for (int j = 0; j < 4; ++j)
-            epilogue_tile<EPI>(a, acc[i][j], nt0 + i, tb * 128 + wt * 64 + j * 16, &sh.rstd[rstd_off + wt * 64 + j * 16]);
+          for (int j = 0; j < TJ; ++j)
+            epilogue_tile<EPI>(a, acc[i][j], nt0 + i, tb * BT + (wt * TJ + j) * 16, &sh.rstd[rstd_off + (wt * TJ + j) * 16]);
         }
     }
   }
+}
+
+// Token width of the workgroup tiles (128, 96 or 64) for this GEMM: the one whose rounds of workgroups take the least
+// time. A round of a narrower tile is shorter in proportion to its width, at a measured penalty for the extra operand
+// traffic per flop (96 / 64 tokens: 12 % / 24 % in the four-wave kernels, 24 % / 50 % in the eight-wave ones).
+template <int EPI>
+__device__ __forceinline__ void gemm_tile_pick(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg) {
+  const u32 nblocks = ((a.N + 15) / 16 + 7) / 8, halves = blockDim.x >> 8, ncu = nwg / 2;
+  const u32 forced = (a.tune_nw >> 12) & 7u;       // bits 12-14 of the tuning word: 2, 3, 4 force the width (tests)
+  u32 best = 4, best_cost = ~0u;
+  for (u32 tj = 4; tj >= 2; --tj) {
+    const u32 total = nblocks * ((a.T + 32 * tj - 1) / (32 * tj));
+    u32 rounds2;                                     // in half rounds of an eight-wave workgroup
+    if (halves == 2) rounds2 = min(2 * (((total + 1) / 2 + ncu - 1) / ncu), (a.K & 32u) ? ~0u : (total + ncu - 1) / ncu);
+    else rounds2 = 2 * ((total + nwg - 1) / nwg);
+    const u32 cost = rounds2 * tj * (tj == 4 ? 100u : (halves == 2 ? (tj == 3 ? 124u : 150u) : (tj == 3 ? 112u : 124u)));
+    if (cost < best_cost) { best_cost = cost; best = tj; }
+  }
+  if (forced >= 2 && forced <= 4) best = forced;
+  if (best == 4) gemm_tile_lds<EPI, 4>(a, sh, wg, nwg);
+  else if (best == 3) gemm_tile_lds<EPI, 3>(a, sh, wg, nwg);
+  else gemm_tile_lds<EPI, 2>(a, sh, wg, nwg);
 }
 
 // WIDE: the kernel runs eight waves per workgroup (the projections with few output rows); it never takes four weight
@@ -577,7 +612,7 @@ __device__ __forceinline__ void gemm_mfma(const MfmaGemmArgs& a, MfmaShared& sh,
            ((a.N + 127) / 128) * ((a.T + 127) / 128) * 8 <= nwg)       // few 128 x 128 tiles: 64 x 64 items fill the chip
     gemm_stream<EPI, 4, 4, 1, true>(a, sh, wg, nwg);                      // (bit 11 of the tuning word: never)
   else if (a.tune_nw & 0x200u) gemm_tile<EPI>(a, sh, wg, nwg);   // bit 9: direct-load tiles (tests and tuning)
-  else gemm_tile_lds<EPI>(a, sh, wg, nwg);
+  else gemm_tile_pick<EPI>(a, sh, wg, nwg);
 }
 
 // ---- packing -----------------------------------------------------------------------------------------------------
