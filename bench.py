@@ -215,6 +215,7 @@ def main():
                          "decode attention for llama3_8b at its batch of 256, the gate/up GEMM otherwise)")
     ap.add_argument("--requests", type=int, default=0)
     ap.add_argument("--max-batch", type=int, default=0, help="override the engine's batch slots")
+    ap.add_argument("--kv-blocks", type=int, default=0, help="override the size of the KV pool (16-token blocks)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--dump-iterations", default="",
                     help="write one line per iteration of the warm-up and the timed window (kind, sequences, tokens, context "
@@ -240,6 +241,8 @@ def main():
     reqs = synth.make_workload(wl["workload"], cfg["vocab"], wl["rseed"], n_requests=args.requests or None)
     if args.max_batch:
         eng["max_batch"] = args.max_batch
+    if args.kv_blocks:
+        eng["kv_num_blocks"] = args.kv_blocks
     if eng["kv_num_blocks"] == 0:
         eng["kv_num_blocks"] = churn_pool_blocks(reqs, eng["kv_block_size"])
     reqs = reqs[: eng["ring_slots"]]
