@@ -103,7 +103,7 @@ __device__ __forceinline__ void attn_block(const KVTile<HD>& kv, const bf16x8_t 
 #define ATTN_META_MAX 512     // sequences whose batch metadata the decode kernel keeps in LDS
 struct AttnMfmaShared {
   float m[ATTN_WAVES][16], l[ATTN_WAVES][16];
-  float o[ATTN_WAVES][8][128];   // [wave][q head of the group][dim]
+  float o[ATTN_WAVES][16][128];  // [wave][q head of the group (decode) or query of the tile (prefill)][dim]
   u32 cu_chunks[ATTN_META_MAX + 1], tok[ATTN_META_MAX], ctx[ATTN_META_MAX], bslot[ATTN_META_MAX];
 };
 
@@ -241,28 +241,62 @@ __device__ __forceinline__ void attn_decode_combine(const DevCtx& c, u32 wg, u32
   }
 }
 
-// ---- prefill: one wave per (sequence, kv head, head group, tile of 16 query positions) -----------------------------
+// ---- prefill: WPI waves per (sequence, kv head, head group of CT q heads, tile of 16 query positions) -------------
+// The waves of an item take its KV blocks round-robin and merge their partial results through LDS (one pass per q
+// head of the group). WPI (1, 2, 4 or 8, the same for the whole launch) trades the length of the longest chain of
+// blocks a wave walks - the causal mask makes the last tile of a long prompt walk all of it - against merge work.
 template <int HD, int CT>
-__device__ __forceinline__ void attn_prefill(const DevCtx& c, u32 layer, u32 wg, u32 nwg) {
+__device__ __forceinline__ void attn_prefill(const DevCtx& c, u32 layer, AttnMfmaShared& sh, u32 wg, u32 nwg) {
   const u32 B = c.meta->n_seqs, G = c.nq / c.nkv, groups = G / CT;
   const u32 lane = threadIdx.x & 63, w = threadIdx.x >> 6, lg = lane >> 4, lc = lane & 15;
   const bf16_t* Kc = (const bf16_t*)c.kv + (u64)layer * c.kv_layer_stride;
   const bf16_t* Vc = Kc + c.kv_kv_stride;
   const u64 tile = (u64)16 * HD;
-  const u32 total_qt = c.cu_qtiles[B];
   const u32 per_tile = c.nkv * groups;
   const u32 nw = blockDim.x >> 6;
-  for (u64 item = (u64)wg * nw + w; item < (u64)total_qt * per_tile; item += (u64)nwg * nw) {
-    const u32 qi = (u32)(item / per_tile), rem = (u32)(item % per_tile), g = rem / groups, hg = rem % groups;
-    u32 lo = 0, hi = B;                       // sequence of query tile qi: last s with cu_qtiles[s] <= qi
-    while (hi - lo > 1) {
-      const u32 mid = (lo + hi) / 2;
-      if (c.cu_qtiles[mid] <= qi) lo = mid; else hi = mid;
+  // batch metadata in LDS (the item lookup is a binary search; see the decode kernel)
+  const bool staged = B <= ATTN_META_MAX;
+  if (staged) {
+    for (u32 i = threadIdx.x; i <= B; i += blockDim.x) {
+      sh.cu_chunks[i] = c.cu_qtiles[i];
+      if (i < B) { sh.tok[i] = c.cu_seqlens[i]; sh.ctx[i] = c.cu_seqlens[i + 1] - c.cu_seqlens[i]; sh.bslot[i] = c.seq_bslot[i]; }
     }
-    const u32 s = lo, p0 = (qi - c.cu_qtiles[s]) * 16;
-    const u32 t0 = c.cu_seqlens[s], P = c.cu_seqlens[s + 1] - t0;
-    const u32* bt = c.block_tables + (u64)c.seq_bslot[s] * c.max_blocks_per_seq;
-    const bool colv = p0 + lc < P;
+    __syncthreads();
+  }
+  auto cuq = [&](u32 i) { return staged ? sh.cu_chunks[i] : c.cu_qtiles[i]; };
+  const u64 total = (u64)cuq(B) * per_tile;
+  // waves per item: doubled while the longest chain (blocks of the longest prompt / WPI) is long and the items, each
+  // now taking WPI wave slots, still fit the waves that run at once about three times over
+  u32 WPI = 1;
+  {
+    const u32 chain = (c.meta->max_q_len + 15) / 16;
+    const u64 slots = (u64)(nwg / 2) * nw;
+    while (WPI < nw && WPI < 8 && chain > 12 * WPI && total * WPI * 2 <= slots * 3) WPI *= 2;
+    const u32 forced = (c.tune_nw >> 16) & 15u;      // bits 16-19 of the tuning word: 1, 2, 4, 8 force it (tests)
+    if (forced == 1 || forced == 2 || forced == 4 || forced == 8) WPI = min(forced, nw);
+  }
+  const u32 gpw = nw / WPI, grp = w / WPI, wi = w % WPI;
+  for (u64 base = (u64)wg * gpw; base < total; base += (u64)nwg * gpw) {
+    const u64 item = base + grp;
+    const bool valid = item < total;
+    u32 g = 0, hg = 0, p0 = 0, t0 = 0, P = 1, last = 0;
+    const u32* bt = c.block_tables;
+    if (valid) {
+      const u32 qi = (u32)(item / per_tile), rem = (u32)(item % per_tile);
+      g = rem / groups; hg = rem % groups;
+      u32 lo = 0, hi = B;                       // sequence of query tile qi: last s with cu_qtiles[s] <= qi
+      while (hi - lo > 1) {
+        const u32 mid = (lo + hi) / 2;
+        if (cuq(mid) <= qi) lo = mid; else hi = mid;
+      }
+      const u32 s = lo;
+      p0 = (qi - cuq(s)) * 16;
+      t0 = staged ? sh.tok[s] : c.cu_seqlens[s];
+      P = staged ? sh.ctx[s] : c.cu_seqlens[s + 1] - c.cu_seqlens[s];
+      bt = c.block_tables + (u64)(staged ? sh.bslot[s] : c.seq_bslot[s]) * c.max_blocks_per_seq;
+      last = min(p0 + 15, P - 1) / 16;
+    }
+    const bool colv = valid && p0 + lc < P;
     bf16x8_t q[CT][HD / 32];
     u32 lim[CT];
 #pragma unroll
@@ -277,32 +311,62 @@ __device__ __forceinline__ void attn_prefill(const DevCtx& c, u32 layer, u32 wg,
     }
     AttnAcc<HD, CT> acc;
     attn_init(acc);
-    const u32 last = min(p0 + 15, P - 1) / 16;
-    KVTile<HD> cur, nxt;
-    {
-      const u64 base = ((u64)bt[0] * c.nkv + g) * tile;
-      kv_load<HD>(Kc + base, Vc + base, cur);
+    // this wave's blocks: wi, wi + WPI, ...; two in flight, the tiles alternate by code position (a register copy
+    // would wait for the loads)
+    KVTile<HD> k0, k1;
+    auto ld = [&](KVTile<HD>& tl, u32 jb) {
+      if (valid && jb <= last) { const u64 bs = ((u64)bt[jb] * c.nkv + g) * tile; kv_load<HD>(Kc + bs, Vc + bs, tl); }
+    };
+    auto us = [&](const KVTile<HD>& tl, u32 jb) { if (valid && jb <= last) attn_block<HD, CT>(tl, q, jb * 16, lim, acc); };
+    ld(k0, wi); ld(k1, wi + WPI);
+    for (u32 jb = wi; jb <= last; jb += 2 * WPI) {
+      us(k0, jb); ld(k0, jb + 2 * WPI);
+      us(k1, jb + WPI); ld(k1, jb + 3 * WPI);
     }
-    for (u32 jb = 0; jb <= last; ++jb) {
-      if (jb < last) {
-        const u64 base = ((u64)bt[jb + 1] * c.nkv + g) * tile;
-        kv_load<HD>(Kc + base, Vc + base, nxt);
+    if (WPI == 1) {
+      if (valid) {
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {
+          float inv[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) inv[i] = 1.0f / __shfl(acc.l[ct], lg * 4 + i);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const u32 r = lg * 4 + i;
+            if (p0 + r < P) {
+#pragma unroll
+              for (int d = 0; d < HD / 16; ++d)
+                c.aq[packed_off(t0 + p0 + r, (g * G + hg * CT + ct) * HD + d * 16 + lc, c.TBS)] = f32_to_bf16(acc.o[ct][d][i] * inv[i]);
+            }
+          }
+        }
       }
-      attn_block<HD, CT>(cur, q, jb * 16, lim, acc);
-      cur = nxt;
-    }
+    } else {
+      // merge the WPI partial results of the item, one q head of the group per pass (fixed order of the waves)
 #pragma unroll
-    for (int ct = 0; ct < CT; ++ct) {
-      float inv[4];
+      for (int ct = 0; ct < CT; ++ct) {
+        __syncthreads();   // the previous pass has been read
+        if (lg == 0) { sh.m[w][lc] = acc.m[ct]; sh.l[w][lc] = acc.l[ct]; }
 #pragma unroll
-      for (int i = 0; i < 4; ++i) inv[i] = 1.0f / __shfl(acc.l[ct], lg * 4 + i);
+        for (int d = 0; d < HD / 16; ++d)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const u32 r = lg * 4 + i;
-        if (p0 + r < P) {
-#pragma unroll
-          for (int d = 0; d < HD / 16; ++d)
-            c.aq[packed_off(t0 + p0 + r, (g * G + hg * CT + ct) * HD + d * 16 + lc, c.TBS)] = f32_to_bf16(acc.o[ct][d][i] * inv[i]);
+          for (int i = 0; i < 4; ++i) sh.o[w][lg * 4 + i][d * 16 + lc] = acc.o[ct][d][i];
+        __syncthreads();
+        if (valid) {
+          const u32 w0 = grp * WPI;
+          for (u32 idx = wi * 64 + lane; idx < 16 * HD; idx += WPI * 64) {
+            const u32 r = idx / HD, dim = idx % HD;
+            if (p0 + r >= P) continue;
+            float M = -INFINITY;
+            for (u32 ww = 0; ww < WPI; ++ww) M = fmaxf(M, sh.m[w0 + ww][r]);
+            float L = 0.f, O = 0.f;
+            for (u32 ww = 0; ww < WPI; ++ww) {   // a wave without blocks has m = -inf and contributes 0
+              const float f = __expf(sh.m[w0 + ww][r] - M);
+              L += sh.l[w0 + ww][r] * f;
+              O += sh.o[w0 + ww][r][dim] * f;
+            }
+            c.aq[packed_off(t0 + p0 + r, (g * G + hg * CT + ct) * HD + dim, c.TBS)] = f32_to_bf16(O / L);
+          }
         }
       }
     }
@@ -310,15 +374,15 @@ __device__ __forceinline__ void attn_prefill(const DevCtx& c, u32 layer, u32 wg,
 }
 
 template <int HD>
-__device__ __forceinline__ void attn_prefill_hd(const DevCtx& c, u32 layer, u32 wg, u32 nwg) {
+__device__ __forceinline__ void attn_prefill_hd(const DevCtx& c, u32 layer, AttnMfmaShared& sh, u32 wg, u32 nwg) {
   const u32 G = c.nq / c.nkv;
   switch (G) {
-    case 1: attn_prefill<HD, 1>(c, layer, wg, nwg); break;
-    case 2: attn_prefill<HD, 2>(c, layer, wg, nwg); break;
-    case 3: attn_prefill<HD, 3>(c, layer, wg, nwg); break;
-    case 4: attn_prefill<HD, 2>(c, layer, wg, nwg); break;   // two q heads per pass keep the accumulators in registers
-    case 6: attn_prefill<HD, 3>(c, layer, wg, nwg); break;
-    case 8: attn_prefill<HD, 2>(c, layer, wg, nwg); break;
+    case 1: attn_prefill<HD, 1>(c, layer, sh, wg, nwg); break;
+    case 2: attn_prefill<HD, 2>(c, layer, sh, wg, nwg); break;
+    case 3: attn_prefill<HD, 3>(c, layer, sh, wg, nwg); break;
+    case 4: attn_prefill<HD, 2>(c, layer, sh, wg, nwg); break;   // two q heads per pass keep the accumulators in registers
+    case 6: attn_prefill<HD, 3>(c, layer, sh, wg, nwg); break;
+    case 8: attn_prefill<HD, 2>(c, layer, sh, wg, nwg); break;
     default: break;   // rejected at init
   }
 }
@@ -327,6 +391,6 @@ __device__ __forceinline__ void phase_attention_mfma(const DevCtx& c, u32 layer,
   if (c.meta->kind == 2u) {
     if (c.hd == 64) attn_decode<64>(c, layer, sh, wg, nwg); else attn_decode<128>(c, layer, sh, wg, nwg);
   } else {
-    if (c.hd == 64) attn_prefill_hd<64>(c, layer, wg, nwg); else attn_prefill_hd<128>(c, layer, wg, nwg);
+    if (c.hd == 64) attn_prefill_hd<64>(c, layer, sh, wg, nwg); else attn_prefill_hd<128>(c, layer, sh, wg, nwg);
   }
 }

@@ -144,6 +144,21 @@ def test_bf16_long_contexts(lib, name, prompts):
     print(name, "long contexts: worst relative logit error", worst)
 
 
+@pytest.mark.parametrize("name,wpi", [("mini_gqa128", 1), ("mini_gqa128", 2), ("mini_gqa", 4), ("mini_gqa128", 8), ("mini_gqa", 8)])
+def test_bf16_prefill_attention_waves_per_item(lib, name, wpi, monkeypatch):
+    """Prefill attention with 1, 2, 4 and 8 waves sharing the KV blocks of a query tile (the automatic choice depends on
+    the longest prompt and on the number of tiles): prompts of 7..1030 tokens in one prefill iteration, ragged tiles."""
+    monkeypatch.setenv("BLINK_TUNE_NW", str(wpi << 16))
+    cfg, eng, raw, blob = setup(name, 41)
+    prompts = [1030, 300, 7, 17, 160]
+    eng = dict(eng, max_seq_len=1100, kv_num_blocks=140, max_prefill_tokens=2048, max_batch=5)
+    rng = np.random.default_rng(15)
+    reqs = [dict(arrival_s=0.0, prompt=rng.integers(0, cfg["vocab"], P).astype(np.int32), max_new_tokens=3,
+                 temperature=0.0, top_k=0, top_p=1.0, seed=i) for i, P in enumerate(prompts)]
+    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2)
+    print(name, "waves per item", wpi, "worst relative logit error", worst)
+
+
 def test_fp32_gqa_stepwise_logits(lib):
     cfg, eng, raw, blob = setup("mini_gqa", 51)
     cfg = dict(cfg, dtype=0)
