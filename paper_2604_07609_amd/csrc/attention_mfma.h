@@ -111,7 +111,7 @@ struct AttnMfmaShared {
 template <int HD>
 __device__ __forceinline__ void attn_decode(const DevCtx& c, u32 layer, AttnMfmaShared& sh, u32 wg, u32 nwg) {
   const u32 B = c.meta->n_seqs, G = c.nq / c.nkv;
-  const u32 lane = threadIdx.x & 63, w = threadIdx.x >> 6, lg = lane >> 4, lc = lane & 15;
+  const u32 lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lg = lane >> 4, lc = lane & 15;   // w as a scalar: block-table reads become scalar loads
   const bf16_t* Kc = (const bf16_t*)c.kv + (u64)layer * c.kv_layer_stride;
   const bf16_t* Vc = Kc + c.kv_kv_stride;
   const u64 tile = (u64)16 * HD;
@@ -120,51 +120,69 @@ __device__ __forceinline__ void attn_decode(const DevCtx& c, u32 layer, AttnMfma
   // leave per-chunk partial results that attn_decode_combine (the next kernel) merges in chunk order.
   // The batch metadata an item needs is copied into LDS once: finding an item's sequence is a binary search, and every
   // step of it in global memory would be a dependent load in front of the item's first KV load.
-  const bool staged = B <= ATTN_META_MAX;
-  if (staged) {
-    for (u32 i = threadIdx.x; i <= B; i += blockDim.x) {
-      sh.cu_chunks[i] = c.cu_chunks[i];
-      if (i < B) { sh.tok[i] = c.cu_seqlens[i]; sh.ctx[i] = c.seq_len[i]; sh.bslot[i] = c.seq_bslot[i]; }
-    }
-    __syncthreads();
+  // (the library admits at most ATTN_META_MAX batch slots for a bf16 model)
+  for (u32 i = threadIdx.x; i <= B; i += blockDim.x) {
+    sh.cu_chunks[i] = c.cu_chunks[i];
+    if (i < B) { sh.tok[i] = c.cu_seqlens[i]; sh.ctx[i] = c.seq_len[i]; sh.bslot[i] = c.seq_bslot[i]; }
   }
-  auto cu = [&](u32 i) { return staged ? sh.cu_chunks[i] : c.cu_chunks[i]; };
+  __syncthreads();
+  auto cu = [&](u32 i) { return sh.cu_chunks[i]; };
   const u32 total_chunks = cu(B);
-  for (u32 item = wg; item < total_chunks * c.nkv; item += nwg) {
-    const u32 ci = item / c.nkv, g = item % c.nkv;
+  // Every wave takes blocks w, w + 8, w + 16, w + 24 of the item's chunk and keeps all four tiles in flight. The loads
+  // are unconditional and the block ids are fetched first, in one batch: a load inside a branch, or an id fetched
+  // between two tiles, makes the wave wait for everything in flight (loads complete in order). A slot past the
+  // chunk's end repeats one of the chunk's blocks (a cache hit) and its tile is not used.
+  static_assert(ATTN_CHUNK_BLOCKS == 4 * ATTN_WAVES, "four KV tiles per wave");
+  constexpr u32 nw = ATTN_WAVES;
+  const u32 total_items = total_chunks * c.nkv;
+  struct Item { u32 ci, g, nch, t, ctx, b_lo, nb; };
+  bf16x8_t q[1][HD / 32];
+  KVTile<HD> t0, t1, t2, t3;
+  // describes the item and requests its queries and tiles (into q and t0..t3, which the previous item no longer needs)
+  auto start = [&](u32 item) {
+    Item it;
+    it.ci = item / c.nkv; it.g = item % c.nkv;
     u32 lo = 0, hi = B;                       // sequence of chunk ci: last s with cu_chunks[s] <= ci
     while (hi - lo > 1) {
       const u32 mid = (lo + hi) / 2;
-      if (cu(mid) <= ci) lo = mid; else hi = mid;
+      if (cu(mid) <= it.ci) lo = mid; else hi = mid;
     }
-    const u32 s = lo, ch = ci - cu(s), nch = cu(s + 1) - cu(s);
-    const u32 t = staged ? sh.tok[s] : c.cu_seqlens[s];              // the sequence's single token of this iteration
-    const u32 ctx = staged ? sh.ctx[s] : c.seq_len[s];
-    const u32* bt = c.block_tables + (u64)(staged ? sh.bslot[s] : c.seq_bslot[s]) * c.max_blocks_per_seq;
-    bf16x8_t q[1][HD / 32];
+    const u32 s = lo, ch = it.ci - cu(s);
+    it.nch = cu(s + 1) - cu(s);
+    it.t = sh.tok[s];              // the sequence's single token of this iteration
+    it.ctx = sh.ctx[s];
+    const u32* bt = c.block_tables + (u64)sh.bslot[s] * c.max_blocks_per_seq;
+    it.b_lo = ch * ATTN_CHUNK_BLOCKS;
+    it.nb = min((it.ctx + 15) / 16, it.b_lo + ATTN_CHUNK_BLOCKS) - it.b_lo;   // 1..32 blocks: up to four per wave
+    const u32 wfirst = w < it.nb ? w : 0u;
+#define BLOCK_ID(j) bt[it.b_lo + ((w + (j) * nw < it.nb) ? w + (j) * nw : wfirst)]
+    const u32 id0 = BLOCK_ID(0), id1 = BLOCK_ID(1), id2 = BLOCK_ID(2), id3 = BLOCK_ID(3);
+#undef BLOCK_ID
+    // (columns past the group's heads repeat its last head: an unconditional load; their results are never stored)
 #pragma unroll
-    for (int st = 0; st < HD / 32; ++st) {
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (lc < G) v = *(const uint4*)(c.qbuf + ((u64)t * c.nq + g * G + lc) * HD + st * 32 + lg * 8);
-      q[0][st] = *(const bf16x8_t*)&v;
-    }
+    for (int st = 0; st < HD / 32; ++st)
+      q[0][st] = ld_tile(c.qbuf + ((u64)it.t * c.nq + it.g * G + min(lc, G - 1)) * HD + st * 32 + lg * 8);
+    const u64 b0 = ((u64)id0 * c.nkv + it.g) * tile, b1 = ((u64)id1 * c.nkv + it.g) * tile;
+    const u64 b2 = ((u64)id2 * c.nkv + it.g) * tile, b3 = ((u64)id3 * c.nkv + it.g) * tile;
+    kv_load<HD>(Kc + b0, Vc + b0, t0); kv_load<HD>(Kc + b1, Vc + b1, t1);
+    kv_load<HD>(Kc + b2, Vc + b2, t2); kv_load<HD>(Kc + b3, Vc + b3, t3);
+    return it;
+  };
+  u32 item = wg;
+  if (item >= total_items) return;
+  Item cur = start(item);
+  for (;;) {
     AttnAcc<HD, 1> acc;
     attn_init(acc);
-    const u32 lim[1] = {ctx};
-    const u32 b_lo = ch * ATTN_CHUNK_BLOCKS, b_hi = min((ctx + 15) / 16, b_lo + ATTN_CHUNK_BLOCKS);
-    const u32 nb = b_hi - b_lo;                 // 1..64 blocks: up to eight per wave with eight waves
-    // every wave takes blocks w, w+nw, ... of the chunk (up to eight): four tiles are in flight at any time, a tile's
-    // registers are refilled as soon as it has been used (rotation by code position, no register copies)
-    const u32 nw = blockDim.x >> 6;
-    KVTile<HD> t0, t1, t2, t3;
-    auto ld = [&](KVTile<HD>& tl, u32 j) { const u32 i = w + j * nw; if (i < nb) { const u64 bs = ((u64)bt[b_lo + i] * c.nkv + g) * tile; kv_load<HD>(Kc + bs, Vc + bs, tl); } };
-    auto us = [&](const KVTile<HD>& tl, u32 j) { const u32 i = w + j * nw; if (i < nb) attn_block<HD, 1>(tl, q, (b_lo + i) * 16, lim, acc); };
-    ld(t0, 0); ld(t1, 1); ld(t2, 2); ld(t3, 3);
-    us(t0, 0); ld(t0, 4);
-    us(t1, 1); ld(t1, 5);
-    us(t2, 2); ld(t2, 6);
-    us(t3, 3); ld(t3, 7);
-    us(t0, 4); us(t1, 5); us(t2, 6); us(t3, 7);
+    const u32 lim[1] = {cur.ctx};
+    auto us = [&](const KVTile<HD>& tl, u32 j) { const u32 i = w + j * nw; if (i < cur.nb) attn_block<HD, 1>(tl, q, (cur.b_lo + i) * 16, lim, acc); };
+    us(t0, 0); us(t1, 1); us(t2, 2); us(t3, 3);
+    // the next item's tiles are requested before this item's partial results are merged: the waves wait for each
+    // other in the merge, and without loads in flight the memory pipe of the compute unit would idle meanwhile
+    const u32 nitem = item + nwg;
+    const bool more = nitem < total_items;
+    Item nxt = cur;
+    if (more) nxt = start(nitem);
     __syncthreads();   // the previous item's combine has finished reading LDS
     if (lg == 0) { sh.m[w][lc] = acc.m[0]; sh.l[w][lc] = acc.l[0]; }
 #pragma unroll
@@ -173,8 +191,8 @@ __device__ __forceinline__ void attn_decode(const DevCtx& c, u32 layer, AttnMfma
       for (int i = 0; i < 4; ++i)
         if (lg * 4 + i < G) sh.o[w][lg * 4 + i][d * 16 + lc] = acc.o[0][d][i];
     __syncthreads();
-    float* po = c.attn_part_o + ((u64)ci * c.nkv + g) * G * HD;
-    float* pml = c.attn_part_ml + ((u64)ci * c.nkv + g) * G * 2;
+    float* po = c.attn_part_o + ((u64)cur.ci * c.nkv + cur.g) * G * HD;
+    float* pml = c.attn_part_ml + ((u64)cur.ci * c.nkv + cur.g) * G * 2;
     for (u32 idx = threadIdx.x; idx < G * HD; idx += blockDim.x) {
       const u32 h = idx / HD, dim = idx % HD;
       float M = -INFINITY;
@@ -185,13 +203,16 @@ __device__ __forceinline__ void attn_decode(const DevCtx& c, u32 layer, AttnMfma
         L += sh.l[ww][h] * f;
         O += sh.o[ww][h][dim] * f;
       }
-      if (nch == 1) {
-        c.aq[packed_off(t, (g * G + h) * HD + dim, c.TBS)] = f32_to_bf16(O / L);
+      if (cur.nch == 1) {
+        c.aq[packed_off(cur.t, (cur.g * G + h) * HD + dim, c.TBS)] = f32_to_bf16(O / L);
       } else {
         po[(u64)h * HD + dim] = O;
         if (dim == 0) { pml[h * 2] = M; pml[h * 2 + 1] = L; }
       }
     }
+    if (!more) break;
+    cur = nxt;
+    item = nitem;
   }
 }
 
@@ -248,22 +269,19 @@ __device__ __forceinline__ void attn_decode_combine(const DevCtx& c, u32 wg, u32
 template <int HD, int CT>
 __device__ __forceinline__ void attn_prefill(const DevCtx& c, u32 layer, AttnMfmaShared& sh, u32 wg, u32 nwg) {
   const u32 B = c.meta->n_seqs, G = c.nq / c.nkv, groups = G / CT;
-  const u32 lane = threadIdx.x & 63, w = threadIdx.x >> 6, lg = lane >> 4, lc = lane & 15;
+  const u32 lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lg = lane >> 4, lc = lane & 15;   // w as a scalar: block-table reads become scalar loads
   const bf16_t* Kc = (const bf16_t*)c.kv + (u64)layer * c.kv_layer_stride;
   const bf16_t* Vc = Kc + c.kv_kv_stride;
   const u64 tile = (u64)16 * HD;
   const u32 per_tile = c.nkv * groups;
   const u32 nw = blockDim.x >> 6;
   // batch metadata in LDS (the item lookup is a binary search; see the decode kernel)
-  const bool staged = B <= ATTN_META_MAX;
-  if (staged) {
-    for (u32 i = threadIdx.x; i <= B; i += blockDim.x) {
-      sh.cu_chunks[i] = c.cu_qtiles[i];
-      if (i < B) { sh.tok[i] = c.cu_seqlens[i]; sh.ctx[i] = c.cu_seqlens[i + 1] - c.cu_seqlens[i]; sh.bslot[i] = c.seq_bslot[i]; }
-    }
-    __syncthreads();
+  for (u32 i = threadIdx.x; i <= B; i += blockDim.x) {
+    sh.cu_chunks[i] = c.cu_qtiles[i];
+    if (i < B) { sh.tok[i] = c.cu_seqlens[i]; sh.ctx[i] = c.cu_seqlens[i + 1] - c.cu_seqlens[i]; sh.bslot[i] = c.seq_bslot[i]; }
   }
-  auto cuq = [&](u32 i) { return staged ? sh.cu_chunks[i] : c.cu_qtiles[i]; };
+  __syncthreads();
+  auto cuq = [&](u32 i) { return sh.cu_chunks[i]; };
   const u64 total = (u64)cuq(B) * per_tile;
   // waves per item: doubled while the longest chain (blocks of the longest prompt / WPI) is long and the items, each
   // now taking WPI wave slots, still fit the waves that run at once about three times over
@@ -291,9 +309,9 @@ __device__ __forceinline__ void attn_prefill(const DevCtx& c, u32 layer, AttnMfm
       }
       const u32 s = lo;
       p0 = (qi - cuq(s)) * 16;
-      t0 = staged ? sh.tok[s] : c.cu_seqlens[s];
-      P = staged ? sh.ctx[s] : c.cu_seqlens[s + 1] - c.cu_seqlens[s];
-      bt = c.block_tables + (u64)(staged ? sh.bslot[s] : c.seq_bslot[s]) * c.max_blocks_per_seq;
+      t0 = sh.tok[s];
+      P = sh.ctx[s];
+      bt = c.block_tables + (u64)sh.bslot[s] * c.max_blocks_per_seq;
       last = min(p0 + 15, P - 1) / 16;
     }
     const bool colv = valid && p0 + lc < P;

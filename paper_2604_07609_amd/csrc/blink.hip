@@ -392,6 +392,8 @@ extern "C" int blink_init(const blink_config* cfg, blink_engine** out) {
   if (cfg->kv_block_size != 16) return fail(BLINK_ERR_INVAL, "kv_block_size must be 16");
   if (!cfg->kv_num_blocks || !cfg->max_batch || cfg->max_batch > SCHED_MAX_BATCH)
     return fail(BLINK_ERR_INVAL, "kv_num_blocks must be positive and max_batch in [1, %d]", SCHED_MAX_BATCH);
+  if (cfg->dtype == 1 && cfg->max_batch > ATTN_META_MAX)
+    return fail(BLINK_ERR_INVAL, "bf16 models take at most %d batch slots (attention keeps the batch metadata in LDS)", ATTN_META_MAX);
   if (!cfg->max_seq_len || !cfg->max_prefill_tokens) return fail(BLINK_ERR_INVAL, "max_seq_len and max_prefill_tokens must be positive");
   if (!cfg->ring_slots || (cfg->ring_slots & (cfg->ring_slots - 1))) return fail(BLINK_ERR_INVAL, "ring_slots must be a power of two");
   if (cfg->weights_bytes != expected_weight_bytes(cfg))
