@@ -315,31 +315,44 @@ __device__ __forceinline__ void attn_prefill(const DevCtx& c, u32 layer, AttnMfm
       last = min(p0 + 15, P - 1) / 16;
     }
     const bool colv = valid && p0 + lc < P;
+    // queries of the tile (columns past the prompt's end repeat its last token: an unconditional load; they are
+    // masked down to key 0 and never stored)
     bf16x8_t q[CT][HD / 32];
     u32 lim[CT];
+    const u32 qrow = t0 + min(p0 + lc, P - 1);
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) {
       lim[ct] = colv ? p0 + lc + 1 : 1;
 #pragma unroll
-      for (int st = 0; st < HD / 32; ++st) {
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (colv) v = *(const uint4*)(c.qbuf + ((u64)(t0 + p0 + lc) * c.nq + g * G + hg * CT + ct) * HD + st * 32 + lg * 8);
-        q[ct][st] = *(const bf16x8_t*)&v;
-      }
+      for (int st = 0; st < HD / 32; ++st)
+        q[ct][st] = ld_tile(c.qbuf + ((u64)qrow * c.nq + g * G + hg * CT + ct) * HD + st * 32 + lg * 8);
     }
     AttnAcc<HD, CT> acc;
     attn_init(acc);
-    // this wave's blocks: wi, wi + WPI, ...; two in flight, the tiles alternate by code position (a register copy
-    // would wait for the loads)
-    KVTile<HD> k0, k1;
-    auto ld = [&](KVTile<HD>& tl, u32 jb) {
-      if (valid && jb <= last) { const u64 bs = ((u64)bt[jb] * c.nkv + g) * tile; kv_load<HD>(Kc + bs, Vc + bs, tl); }
-    };
-    auto us = [&](const KVTile<HD>& tl, u32 jb) { if (valid && jb <= last) attn_block<HD, CT>(tl, q, jb * 16, lim, acc); };
-    ld(k0, wi); ld(k1, wi + WPI);
-    for (u32 jb = wi; jb <= last; jb += 2 * WPI) {
-      us(k0, jb); ld(k0, jb + 2 * WPI);
-      us(k1, jb + WPI); ld(k1, jb + 3 * WPI);
+    // This wave's blocks: wi, wi + WPI, ...; two tiles in flight, alternating by code position (a register copy would
+    // wait for the loads). The block ids come through scalar loads (the table is read through the constant address
+    // space with a wave-uniform address), which do not queue behind the tile loads, and the tile loads are
+    // unconditional: past the last block they repeat it (a cache hit) and the tile is not used.
+    {
+      typedef const __attribute__((address_space(4))) u32 const_u32;
+      const u64 bta = (u64)bt;
+      // (the builtin returns int: each half goes through u32 before it is widened, or the low half is sign-extended)
+      const u32 bt_hi = (u32)__builtin_amdgcn_readfirstlane((u32)(bta >> 32)), bt_lo = (u32)__builtin_amdgcn_readfirstlane((u32)bta);
+      const_u32* btc = (const_u32*)(((u64)bt_hi << 32) | (u64)bt_lo);
+      const u32 lastu = __builtin_amdgcn_readfirstlane(last), gu = __builtin_amdgcn_readfirstlane(g);
+      KVTile<HD> k0, k1;
+      auto ld = [&](KVTile<HD>& tl, u32 jb) {
+        const u64 bs = ((u64)btc[min(jb, lastu)] * c.nkv + gu) * tile;
+        kv_load<HD>(Kc + bs, Vc + bs, tl);
+      };
+      auto us = [&](const KVTile<HD>& tl, u32 jb) { if (jb <= lastu) attn_block<HD, CT>(tl, q, jb * 16, lim, acc); };
+      if (valid) {
+        ld(k0, wi); ld(k1, wi + WPI);
+        for (u32 jb = wi; jb <= lastu; jb += 2 * WPI) {
+          us(k0, jb); ld(k0, jb + 2 * WPI);
+          us(k1, jb + WPI); ld(k1, jb + 3 * WPI);
+        }
+      }
     }
     if (WPI == 1) {
       if (valid) {
