@@ -151,11 +151,16 @@ __device__ __forceinline__ void attn_decode(const DevCtx& c, u32 layer, AttnMfma
     it.nch = cu(s + 1) - cu(s);
     it.t = sh.tok[s];              // the sequence's single token of this iteration
     it.ctx = sh.ctx[s];
-    const u32* bt = c.block_tables + (u64)sh.bslot[s] * c.max_blocks_per_seq;
+    // the block table row through the constant address space and a wave-uniform address: scalar loads, which do not
+    // queue behind the tile loads still in flight (the builtin returns int: each half goes through u32)
+    typedef const __attribute__((address_space(4))) u32 const_u32;
+    const u64 bta = (u64)(c.block_tables + (u64)sh.bslot[s] * c.max_blocks_per_seq);
+    const u32 bt_hi = (u32)__builtin_amdgcn_readfirstlane((u32)(bta >> 32)), bt_lo = (u32)__builtin_amdgcn_readfirstlane((u32)bta);
+    const_u32* bt = (const_u32*)(((u64)bt_hi << 32) | (u64)bt_lo);
     it.b_lo = ch * ATTN_CHUNK_BLOCKS;
     it.nb = min((it.ctx + 15) / 16, it.b_lo + ATTN_CHUNK_BLOCKS) - it.b_lo;   // 1..32 blocks: up to four per wave
     const u32 wfirst = w < it.nb ? w : 0u;
-#define BLOCK_ID(j) bt[it.b_lo + ((w + (j) * nw < it.nb) ? w + (j) * nw : wfirst)]
+#define BLOCK_ID(j) bt[__builtin_amdgcn_readfirstlane(it.b_lo + ((w + (j) * nw < it.nb) ? w + (j) * nw : wfirst))]
     const u32 id0 = BLOCK_ID(0), id1 = BLOCK_ID(1), id2 = BLOCK_ID(2), id3 = BLOCK_ID(3);
 #undef BLOCK_ID
     // (columns past the group's heads repeat its last head: an unconditional load; their results are never stored)
