@@ -98,6 +98,7 @@ def cpu_baseline(cfg, eng, raw, reqs, budget_tokens, n_req=4, prompt_cap=None):
     # the oracle keeps its KV pool as dense fp64 arrays: size the pool to the sample, not to the engine's 64 GiB
     bs = eng["kv_block_size"]
     need = sum(max(1, -(-(len(r["prompt"]) + r["max_new_tokens"] - 1) // bs)) for r in sample)
+    full_eng = eng
     eng = dict(eng, kv_num_blocks=need, max_batch=len(sample))
     t0 = time.perf_counter()
     ev, _ = SV.serve(cfg, M.Weights(cfg, raw), eng, sample)
@@ -107,7 +108,18 @@ def cpu_baseline(cfg, eng, raw, reqs, budget_tokens, n_req=4, prompt_cap=None):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = os.cpu_count()
+    # the scheduler alone (integer state machine, single thread) over the whole request set with a constant token in
+    # place of the model: the CPU figure that stands beside the on-GPU scheduling time per iteration
+    from oracle import scheduler as SC
+    sched = SC.Scheduler(full_eng["kv_num_blocks"], full_eng["kv_block_size"], full_eng["max_batch"], full_eng["max_prefill_tokens"],
+                         full_eng["ring_slots"], full_eng.get("eos_token_id", -1))
+    t0 = time.perf_counter()
+    sev = SV.run_schedule(sched, reqs, lambda plan: [1] * len(plan.tickets), max_iterations=400)
+    sdt = time.perf_counter() - t0
+    sched_us = 1e6 * sdt / max(1, sched.iteration)
     return dict(value=len(ev) / dt, unit="output tokens/s", cores=int(threads), kind="oracle",
+                scheduler_only_us_per_iteration=round(sched_us, 1),
+                scheduler_only_sample="%d iterations of the full request set, one thread, invariant checks included" % sched.iteration,
                 sample="first %d requests, prompts %s(%s tokens), max_new_tokens capped at %d: %d output tokens in %.1f s"
                        % (len(sample), "truncated " if prompt_cap else "as drawn ", "+".join(str(len(r["prompt"])) for r in sample),
                           budget_tokens, len(ev), dt))
