@@ -56,7 +56,8 @@ struct MfmaGemmArgs {
                            // Bit 9: tile schedule with direct loads instead of LDS staging (bit 8: its 256-token
                            // workgroup tile in eight-wave kernels). Bit 10: no split of K between workgroup halves.
                            // Bit 11: no 64 x 64 streaming items for 64 < T <= 256. Bits 12-14: 2, 3 or 4 force the
-                           // token tiles per wave of the LDS-staged tile schedule.
+                           // token tiles per wave of the LDS-staged tile schedule. Bit 20: eight-wave kernels never
+                           // take the pair of tiles with shared weight tiles.
 };
 
 #define GEMM_MAX_WAVES 8
@@ -557,6 +558,96 @@ __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared&
   }
 }
 
+// Eight waves on a pair of tiles that are neighbours along the tokens: 128 rows x (2 x 32 TJ) tokens. The halves of the
+// workgroup (four waves each, a tile each) share the eight weight tiles of every k-step in LDS, so the workgroup
+// fetches 8 + 2 XT operand tiles per step instead of 2 x (8 + XT): a quarter less traffic between L2 and the compute
+// unit, which is what bounds the tile schedule. Same pipeline as gemm_tile_lds.
+template <int EPI, int TJ>
+__device__ __forceinline__ void gemm_tile_lds_pair(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg) {
+  constexpr u32 BT = 32 * TJ, XT = 2 * TJ, LB = 2 * GEMM_TILE_LDS;   // one LDS buffer: 8 weight tiles + 2 XT activation tiles <= 24 KB
+  const u32 lane = threadIdx.x & 63, w = threadIdx.x >> 6;           // eight waves
+  const u32 half = w >> 2, wl = w & 3, wn = wl & 1, wt = wl >> 1;
+  const u32 NT = (a.N + 15) / 16, KT = a.K / 32;
+  const u32 nblocks = (NT + 7) / 8, tblocks = (a.T + BT - 1) / BT, tpairs = (tblocks + 1) / 2, total = nblocks * tpairs;
+  const u64 xk_stride = (u64)a.TBS * 512, w_stride = (u64)KT * 512;
+  // wave w stores weight tile w and activation tiles w and w + 8 of the pair's 2 XT (the latter only if there are that many)
+  const bool x2 = TJ == 4 || w + 8 < 2 * XT;
+  unsigned char* const L0 = &sh.tile[0][0];
+  unsigned char* const Lww = L0 + w * 1024 + lane * 16;
+  unsigned char* const Lwx = L0 + 8192 + w * 1024 + lane * 16;
+  const unsigned char* const Lrw = L0 + (wn * 4) * 1024 + lane * 16;
+  const unsigned char* const Lrx = L0 + 8192 + (half * XT + wt * TJ) * 1024 + lane * 16;
+  for (u32 base = 0; base < total; base += nwg) {
+    const u32 it = xcd_item(base, total, wg, nwg);
+    if (it == ~0u) continue;
+    u32 tp = 0, nb = 0;
+    tile_coords(it, nblocks, tpairs, nb, tp);
+    const u32 tb = tp * 2 + half;
+    const bool valid = tb < tblocks;            // an odd number of token blocks leaves the last pair's second half idle
+    const u32 nt0 = nb * 8 + wn * 4;
+    const bf16_t* const gw = a.Wp + (u64)min(nb * 8 + w, NT - 1) * w_stride + lane * 8;
+    // activation tile t of the pair (0 .. 2 XT - 1) is tile t of the 2 XT consecutive ones that start at tp * 2 XT
+    const bf16_t* const gx0 = a.Xp + (u64)min(tp * 2 * XT + w, a.TBS - 1) * 512 + lane * 8;
+    const bf16_t* const gx1 = a.Xp + (u64)min(tp * 2 * XT + w + 8, a.TBS - 1) * 512 + lane * 8;
+    floatx4_t acc[4][TJ];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < TJ; ++j) acc[i][j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+    uint4 ga0, ga1, ga2, gb0, gb1, gb2;
+    ga2 = gb2 = make_uint4(0, 0, 0, 0);
+#define TL_GLOAD(g, kt) { const u32 kc_ = min((u32)(kt), KT - 1);                                                         \
+      g##0 = *(const uint4*)(gw + (u64)kc_ * 512); g##1 = *(const uint4*)(gx0 + (u64)kc_ * xk_stride);                     \
+      if (x2) g##2 = *(const uint4*)(gx1 + (u64)kc_ * xk_stride); }
+#define TL_STORE(g, buf) { *(uint4*)(Lww + (buf) * LB) = g##0; *(uint4*)(Lwx + (buf) * LB) = g##1;                          \
+      if (x2) *(uint4*)(Lwx + (buf) * LB + 8192) = g##2; }
+#define TL_RW(buf, i) as_bf16x8(*(const uint4*)(Lrw + (buf) * LB + (i) * 1024))
+#define TL_RX(buf, j) as_bf16x8(*(const uint4*)(Lrx + (buf) * LB + ((j) < TJ ? (j) : 0) * 1024))
+#define TL_MM(A, W, X) A = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W, X, A, 0, 0, 0);
+#define TL_ROW(i, o) TL_MM(acc[i][0], o.w##i, o.x0) TL_MM(acc[i][1], o.w##i, o.x1)                                         \
+      if (TJ > 2) { TL_MM(acc[i][TJ > 2 ? 2 : 0], o.w##i, o.x2) } if (TJ > 3) { TL_MM(acc[i][TJ > 3 ? 3 : 0], o.w##i, o.x3) }
+#define TL_SB __builtin_amdgcn_sched_barrier(0);
+#define TL_STEP(o, n, g, k, rb, wb)                                                                                       \
+    n.x0 = TL_RX(rb, 0); n.w0 = TL_RW(rb, 0); n.x1 = TL_RX(rb, 1); n.w1 = TL_RW(rb, 1); TL_STORE(g, wb)                   \
+    TL_SB TL_ROW(0, o) TL_ROW(1, o) TL_SB                                                                                 \
+    if (TJ > 2) n.x2 = TL_RX(rb, 2);                                                                                      \
+    n.w2 = TL_RW(rb, 2); if (TJ > 3) n.x3 = TL_RX(rb, 3);                                                                  \
+    n.w3 = TL_RW(rb, 3); TL_GLOAD(g, (k) + 4)                                                                             \
+    TL_SB TL_ROW(2, o) TL_ROW(3, o) TL_SB                                                                                 \
+    __syncthreads();
+    struct Ops { bf16x8_t w0, w1, w2, w3, x0, x1, x2, x3; };
+    Ops oa, ob;
+    TL_GLOAD(ga, 0) TL_GLOAD(gb, 1)             // in flight while the norm scales are computed
+    compute_rstd(a, min(tp * 2 * BT, a.T - 1), min(2 * BT, 256u), sh, 0);   // both tiles' tokens; its barriers: the LDS tiles are free
+    TL_STORE(ga, 0) TL_STORE(gb, 1) TL_GLOAD(ga, 2) TL_GLOAD(gb, 3)
+    __syncthreads();
+    oa.w0 = TL_RW(0, 0); oa.w1 = TL_RW(0, 1); oa.w2 = TL_RW(0, 2); oa.w3 = TL_RW(0, 3);
+    oa.x0 = TL_RX(0, 0); oa.x1 = TL_RX(0, 1); oa.x2 = TL_RX(0, 2); oa.x3 = TL_RX(0, 3);
+    __syncthreads();   // step 0 overwrites buffer 0, which every wave has just read (later steps read a buffer one step ahead)
+    for (u32 k = 0; k < KT; k += 2) {
+      TL_STEP(oa, ob, ga, k, 1, 0)
+      if (k + 1 < KT) { TL_STEP(ob, oa, gb, k + 1, 0, 1) }
+    }
+#undef TL_GLOAD
+#undef TL_STORE
+#undef TL_RW
+#undef TL_RX
+#undef TL_MM
+#undef TL_ROW
+#undef TL_SB
+#undef TL_STEP
+    if (valid) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (nt0 + i < NT) {
+#pragma unroll
+          for (int j = 0; j < TJ; ++j)
+            epilogue_tile<EPI>(a, acc[i][j], nt0 + i, tb * BT + (wt * TJ + j) * 16, &sh.rstd[half * BT + (wt * TJ + j) * 16]);
+        }
+    }
+  }
+}
+
 // Token width of the workgroup tiles (128, 96 or 64) for this GEMM: the one whose rounds of workgroups take the least
 // time. A round of a narrower tile is shorter in proportion to its width, at a measured penalty for the extra operand
 // traffic per flop (96 / 64 tokens: 12 % / 24 % in the four-wave kernels, 24 % / 50 % in the eight-wave ones).
@@ -574,7 +665,20 @@ __device__ __forceinline__ void gemm_tile_pick(const MfmaGemmArgs& a, MfmaShared
     if (cost < best_cost) { best_cost = cost; best = tj; }
   }
   if (forced >= 2 && forced <= 4) best = forced;
-  if (best == 4) gemm_tile_lds<EPI, 4>(a, sh, wg, nwg);
+  // eight waves: a pair of tiles with shared weight tiles unless splitting K between the halves takes fewer rounds
+  // (the same rule as inside gemm_tile_lds); bit 20 of the tuning word: never the shared pair (tests)
+  bool pair = false;
+  if (halves == 2 && !a.tok_index && !(a.tune_nw & 0x100000u)) {
+    const u32 tblocks = (a.T + 32 * best - 1) / (32 * best), total = nblocks * tblocks;
+    const u32 rounds_split = (total + ncu - 1) / ncu, rounds_pair = ((total + 1) / 2 + ncu - 1) / ncu;
+    const bool splitk = (a.K & 32u) == 0 && rounds_split < 2 * rounds_pair && !(a.tune_nw & 0x400u);
+    pair = !splitk;
+  }
+  if (pair) {
+    if (best == 4) gemm_tile_lds_pair<EPI, 4>(a, sh, wg, nwg);
+    else if (best == 3) gemm_tile_lds_pair<EPI, 3>(a, sh, wg, nwg);
+    else gemm_tile_lds_pair<EPI, 2>(a, sh, wg, nwg);
+  } else if (best == 4) gemm_tile_lds<EPI, 4>(a, sh, wg, nwg);
   else if (best == 3) gemm_tile_lds<EPI, 3>(a, sh, wg, nwg);
   else gemm_tile_lds<EPI, 2>(a, sh, wg, nwg);
 }

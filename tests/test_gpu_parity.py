@@ -107,12 +107,13 @@ def test_bf16_forced_tiles_per_workgroup(lib, nw, monkeypatch):
     print("forced", nw, "tiles per workgroup: worst relative logit error", worst)
 
 
-@pytest.mark.parametrize("tune", [0, 0x400, 0x2000, 0x3000, 0x4000, 0x3400, 0x200, 0x300])
+@pytest.mark.parametrize("tune", [0, 0x400, 0x100400, 0x2000, 0x3000, 0x4000, 0x3400, 0x2400, 0x200, 0x300])
 def test_bf16_large_prefill_iterations(lib, tune, monkeypatch):
     """Prefill iterations of ~1000 tokens (nine 128-token tiles with a ragged last one, ragged last row block) through
     every variant of the tile schedule: LDS-staged tiles with the two halves of an eight-wave workgroup splitting K
-    (the automatic choice at this size) or taking a tile each, workgroup tiles of 64, 96 and 128 tokens, and
-    direct-load tiles with the 128- and the 256-token workgroup tile."""
+    (the automatic choice at this size) or taking a tile each (with the weight tiles of the pair shared in LDS, or,
+    with bit 20, separate), workgroup tiles of 64, 96 and 128 tokens, and direct-load tiles with the 128- and the
+    256-token workgroup tile."""
     monkeypatch.setenv("BLINK_TUNE_NW", str(tune))
     cfg, eng, raw, blob = setup("mini_wide4", 39)
     eng = dict(eng, max_batch=40, max_prefill_tokens=1100, kv_num_blocks=200)
