@@ -66,7 +66,7 @@ typedef struct {
   /* KV pool and scheduler */
   uint32_t kv_block_size;      /* tokens per KV block; 16 */
   uint32_t kv_num_blocks;      /* blocks in the pool */
-  uint32_t max_batch;          /* batch slots (running sequences), <= 1024 */
+  uint32_t max_batch;          /* batch slots (running sequences), <= 1024 (fp32 model) or <= 512 (bf16 model) */
   uint32_t max_seq_len;        /* prompt + generated tokens of one request */
   uint32_t max_prefill_tokens; /* prompt tokens per prefill iteration (the first admitted request is exempt) */
   uint32_t ring_slots;         /* power of two */

@@ -230,6 +230,15 @@ def test_end_of_sequence_token(lib):
     parity.check_against_oracle(cfg, M.Weights(cfg, raw), eng2, reqs, ev2, trace2, rtol=2e-2)
 
 
+def test_init_rejects_more_bf16_batch_slots_than_attention_stages(lib):
+    """A bf16 model takes at most 512 batch slots (the attention kernels keep the batch metadata in LDS); fp32 up to 1024."""
+    cfg, eng, raw, blob = setup("mini_gqa", 91)
+    with pytest.raises(lib.BlinkError) as ei:
+        lib.Engine(cfg, dict(eng, max_batch=513, kv_num_blocks=2048), blob)
+    assert ei.value.code == lib.ERR_INVAL
+    lib.Engine(cfg, dict(eng, max_batch=512, kv_num_blocks=2048), blob).shutdown()
+
+
 def test_submit_errors_and_ring_backpressure(lib):
     cfg, eng, raw, blob = setup("mini_gqa", 91)
     eng = dict(eng, ring_slots=4)
