@@ -52,6 +52,22 @@ __device__ __forceinline__ void kv_load(const bf16_t* Kt, const bf16_t* Vt, KVTi
   }
 }
 
+// max / sum over the four lanes l, l^16, l^32, l^48 with the lane-swap instructions of gfx950 (vector ALU; a shuffle
+// goes through the LDS crossbar). With both operands equal, v_permlane16_swap returns (x[l & ~16], x[l | 16]) and
+// v_permlane32_swap (x[l & ~32], x[l | 32]) in every lane: the pair a lane and its partner hold.
+__device__ __forceinline__ float quad_max(float v) {
+  auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  v = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float quad_sum(float v) {
+  auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  v = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+  auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
 template <int HD, int CT>
 __device__ __forceinline__ void attn_block(const KVTile<HD>& kv, const bf16x8_t (&q)[CT][HD / 32], u32 j0,
                                            const u32 (&lim)[CT], AttnAcc<HD, CT>& a) {
@@ -69,8 +85,7 @@ __device__ __forceinline__ void attn_block(const KVTile<HD>& kv, const bf16x8_t 
       if (j0 + lg * 4 + i >= lim[c]) s4[i] = -INFINITY;
       bm = fmaxf(bm, s4[i]);
     }
-    bm = fmaxf(bm, __shfl_xor(bm, 16));
-    bm = fmaxf(bm, __shfl_xor(bm, 32));
+    bm = quad_max(bm);
     const float mn = fmaxf(a.m[c], bm);
     float p[4], ps = 0.f;
 #pragma unroll
@@ -78,8 +93,7 @@ __device__ __forceinline__ void attn_block(const KVTile<HD>& kv, const bf16x8_t 
       p[i] = __expf(s4[i] - mn);      // exp(-inf) = 0 for masked keys
       ps += p[i];
     }
-    ps += __shfl_xor(ps, 16);
-    ps += __shfl_xor(ps, 32);
+    ps = quad_sum(ps);
     const float corr = __expf(a.m[c] - mn);
     a.l[c] = a.l[c] * corr + ps;
     a.m[c] = mn;
