@@ -280,6 +280,7 @@ def main():
         trace = e.trace(K + W + 16)
         phase_ms = e.phase_times_ms()
         e.calibration_copy(64 << 20)    # one plain copy kernel of known size: scales the HBM counters of a --pmc run
+        copy_gbs, mfma_tflops = e.calibration_rates()
     finally:
         e.shutdown()
 
@@ -345,6 +346,23 @@ def main():
         dec_step = dict(median_us=round(float(np.median(step_ns[idx])) / 1e3, 2), algorithmic_GBs=round(gbs, 2),
                         frac_of_hbm_peak=round(gbs / HBM_PEAK_GBS, 4), mean_batch=round(float(tr["n_seqs"][idx].mean()), 2),
                         mean_context_tokens=round(float(tr["ctx_tokens"][idx].mean() / max(1.0, tr["n_seqs"][idx].mean())), 1))
+    # whole-step view of the prefill iterations: flops of the dense projections (2 x weights x tokens; the LM head on
+    # the last token of every sequence; the causal attention products are left out, so this is a lower bound) over
+    # the iterations' duration on the device clock, against the MFMA peak of the arithmetic type
+    pre_step = None
+    pre = tr["kind"] == 1
+    if pre[:-1].sum() > 0:
+        idx = np.nonzero(pre[:-1])[0]
+        d, F, V, L = cfg["d_model"], cfg["d_ffn"], cfg["vocab"], cfg["n_layers"]
+        qkv_n = (cfg["n_q_heads"] + 2 * cfg["n_kv_heads"]) * cfg["head_dim"]
+        layer_params = qkv_n * d + d * cfg["n_q_heads"] * cfg["head_dim"] + 3 * F * d
+        fl = float(sum(2.0 * (L * layer_params * int(tr["n_tokens"][i]) + V * d * int(tr["n_seqs"][i])) for i in idx))
+        secs = float(step_ns[idx].sum()) * 1e-9
+        peak = 2500.0 if cfg["dtype"] == 1 else 157.3
+        pre_step = dict(iterations=int(len(idx)), mean_tokens=round(float(tr["n_tokens"][idx].mean()), 1),
+                        prompt_tokens_per_s=round(float(tr["n_tokens"][idx].sum()) / secs, 1),
+                        projection_TFLOPs=round(fl / secs / 1e12, 1), mfma_peak_TFLOPs=peak,
+                        frac_of_mfma_peak=round(fl / secs / 1e12 / peak, 4))
     out = {
         "metric": "output tokens/sec at 1 GPU; p50/p99 ITL; on-GPU scheduling us/iteration",
         "value": round(toks / dt, 2), "unit": "output tokens/s", "n_gpus": 1, "steps": iters, "warmup": W,
@@ -359,7 +377,10 @@ def main():
         "iterations": {"prefill": int((tr["kind"] == 1).sum()), "decode": int(dec.sum()),
                        "prefill_tokens": int(s1["tokens_prefilled"] - s0["tokens_prefilled"])},
         "decode_step": dec_step,
+        "prefill_step": pre_step,
         "roofline": roofline,
+        "measured_ceilings": {"copy_kernel_GBs": round(copy_gbs, 1), "mfma_bf16_loop_TFLOPs": round(mfma_tflops, 1),
+                              "note": "plain kernels on this device: a 1 GiB copy (read + written) and a register-only MFMA loop"},
         "setup_s": {"weights_and_workload": round(t_gen, 1)},
     }
     if args.open_loop_seconds > 0:

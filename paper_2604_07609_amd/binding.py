@@ -12,7 +12,7 @@ EVENT_FIRST, EVENT_LAST = 1, 2
 
 EXPORTS = ["blink_init", "blink_submit", "blink_run", "blink_wait", "blink_stop", "blink_poll_outputs", "blink_shutdown",
            "blink_get_trace", "blink_get_stats", "blink_debug_read", "blink_time_phase", "blink_get_phase_times", "blink_calibration_copy",
-           "blink_last_error"]
+           "blink_calibration_rates", "blink_last_error"]
 
 
 class DBG:
@@ -83,6 +83,7 @@ def load_library():
     lib.blink_debug_read.argtypes = [vp, u32, vp, u64, C.POINTER(u64)]
     lib.blink_time_phase.argtypes = [vp, C.c_int32]
     lib.blink_calibration_copy.argtypes = [vp, u64]
+    lib.blink_calibration_rates.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.blink_get_phase_times.argtypes = [vp, vp, u64, C.POINTER(u64)]
     lib.blink_last_error.restype = C.c_char_p
     for n in EXPORTS[:-1]:
@@ -176,6 +177,12 @@ class Engine:
 
     def calibration_copy(self, nbytes):
         _check(self.lib, self.lib.blink_calibration_copy(self.h, int(nbytes)))
+
+    def calibration_rates(self):
+        """(GB/s of a plain 1 GiB copy kernel, read + written; TFLOP/s of a register-only bf16 MFMA loop) on this device."""
+        c, m = C.c_double(), C.c_double()
+        _check(self.lib, self.lib.blink_calibration_rates(self.h, C.byref(c), C.byref(m)))
+        return c.value, m.value
 
     def phase_times_ms(self, cap=1 << 20):
         buf = np.zeros(cap, dtype=np.float32)

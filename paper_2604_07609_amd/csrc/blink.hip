@@ -88,6 +88,26 @@ __global__ void __launch_bounds__(BLK_THREADS) k_copy_calibration(const uint4* s
   for (u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (u64)gridDim.x * blockDim.x) dst[i] = src[i];
 }
 
+// register-only MFMA loop (sixteen independent 16x16x32 bf16 products per round and wave): the rate the matrix cores
+// sustain on this chip at its clocks, beside which the GEMM kernels' rates are read
+__global__ void __launch_bounds__(BLK_THREADS) k_mfma_calibration(float* dst, u32 rounds) {
+  const u32 lane = threadIdx.x & 63;
+  bf16x8_t x, y;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) { x[i] = (__bf16)(0.001f * (float)((lane + i) & 7)); y[i] = (__bf16)(0.002f * (float)((lane * 3 + i) & 7)); }
+  floatx4_t acc[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) acc[i] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+  for (u32 r = 0; r < rounds; ++r) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, y, acc[i], 0, 0, 0);
+  }
+  floatx4_t s = acc[0];
+#pragma unroll
+  for (int i = 1; i < 16; ++i) s += acc[i];
+  dst[(u64)blockIdx.x * blockDim.x + threadIdx.x] = s[0] + s[1] + s[2] + s[3];
+}
+
 __global__ void k_open_window(SchedState* ss, u64 iter_limit) {
   ss->stopped = 0;
   ss->iter_limit = iter_limit;
@@ -790,6 +810,49 @@ extern "C" int blink_calibration_copy(blink_engine* e, uint64_t bytes) {
   hipLaunchKernelGGL(k_copy_calibration, dim3(e->grid * 4), dim3(BLK_THREADS), 0, e->compute, (const uint4*)src, (uint4*)dst, bytes / 16);
   HIPCHK(hipGetLastError());
   HIPCHK(hipStreamSynchronize(e->compute));
+  return BLINK_OK;
+}
+
+extern "C" int blink_calibration_rates(blink_engine* e, double* copy_gbs, double* mfma_bf16_tflops) {
+  g_err.clear();
+  if (!e || !copy_gbs || !mfma_bf16_tflops) return fail(BLINK_ERR_INVAL, "null argument");
+  if (e->loop_active.load()) return fail(BLINK_ERR_STATE, "stop the loop first");
+  HIPCHK(hipSetDevice(e->cfg.device));
+  hipEvent_t t0, t1;
+  HIPCHK(hipEventCreate(&t0));
+  HIPCHK(hipEventCreate(&t1));
+  // copy buffers of 1 GiB each, held only during this call: far larger than the 256 MB last-level cache, so the rate is HBM's
+  const u64 copy_bytes = 1ull << 30, n16 = copy_bytes / 16;
+  char *src = nullptr, *dst = nullptr;
+  if (hipMalloc((void**)&src, copy_bytes) != hipSuccess || hipMalloc((void**)&dst, copy_bytes) != hipSuccess) {
+    if (src) (void)hipFree(src);
+    (void)hipEventDestroy(t0);
+    (void)hipEventDestroy(t1);
+    (void)hipGetLastError();
+    return fail(BLINK_ERR_DEVICE, "no room for the two 1 GiB copy buffers");
+  }
+  const u32 rounds = 4096, wgs = e->grid * 2;        // the MFMA loop writes one float per lane: 1 MiB of the 64 MiB buffer
+  float best_copy = 0.f, best_mfma = 0.f;
+  int rc = hipMemsetAsync(src, 0, copy_bytes, e->compute) == hipSuccess ? BLINK_OK : BLINK_ERR_DEVICE;
+  for (int rep = 0; rep < 4 && rc == BLINK_OK; ++rep) {   // the first repetition warms up; the best of the rest counts
+    float ms = 0.f;
+    if (hipEventRecord(t0, e->compute) != hipSuccess) { rc = BLINK_ERR_DEVICE; break; }
+    hipLaunchKernelGGL(k_copy_calibration, dim3(e->grid * 4), dim3(BLK_THREADS), 0, e->compute, (const uint4*)src, (uint4*)dst, n16);
+    if (hipEventRecord(t1, e->compute) != hipSuccess || hipEventSynchronize(t1) != hipSuccess || hipEventElapsedTime(&ms, t0, t1) != hipSuccess) { rc = BLINK_ERR_DEVICE; break; }
+    if (rep && (best_copy == 0.f || ms < best_copy)) best_copy = ms;
+    if (hipEventRecord(t0, e->compute) != hipSuccess) { rc = BLINK_ERR_DEVICE; break; }
+    hipLaunchKernelGGL(k_mfma_calibration, dim3(wgs), dim3(BLK_THREADS), 0, e->compute, (float*)e->calib_dst, rounds);
+    if (hipEventRecord(t1, e->compute) != hipSuccess || hipEventSynchronize(t1) != hipSuccess || hipEventElapsedTime(&ms, t0, t1) != hipSuccess) { rc = BLINK_ERR_DEVICE; break; }
+    if (rep && (best_mfma == 0.f || ms < best_mfma)) best_mfma = ms;
+  }
+  (void)hipStreamSynchronize(e->compute);
+  (void)hipFree(src);
+  (void)hipFree(dst);
+  (void)hipEventDestroy(t0);
+  (void)hipEventDestroy(t1);
+  if (rc != BLINK_OK || hipGetLastError() != hipSuccess) return fail(BLINK_ERR_DEVICE, "calibration kernels failed");
+  *copy_gbs = 2.0 * (double)(n16 * 16) / ((double)best_copy * 1e-3) / 1e9;   // bytes read + bytes written
+  *mfma_bf16_tflops = (double)wgs * (BLK_THREADS / 64) * rounds * 16.0 * (2.0 * 16 * 16 * 32) / ((double)best_mfma * 1e-3) / 1e12;
   return BLINK_OK;
 }
 

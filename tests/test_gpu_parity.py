@@ -239,6 +239,18 @@ def test_init_rejects_more_bf16_batch_slots_than_attention_stages(lib):
     lib.Engine(cfg, dict(eng, max_batch=512, kv_num_blocks=2048), blob).shutdown()
 
 
+def test_calibration_rates_are_within_the_published_peaks(lib):
+    """The plain copy kernel and the register-only MFMA loop: positive, and not above the chip's HBM and bf16 MFMA peaks."""
+    cfg, eng, raw, blob = setup("mini_gqa", 91)
+    e = lib.Engine(cfg, eng, blob)
+    try:
+        copy_gbs, mfma_tflops = e.calibration_rates()
+    finally:
+        e.shutdown()
+    assert 500.0 < copy_gbs < 8000.0 * 1.05
+    assert 100.0 < mfma_tflops < 2500.0 * 1.05
+
+
 def test_submit_errors_and_ring_backpressure(lib):
     cfg, eng, raw, blob = setup("mini_gqa", 91)
     eng = dict(eng, ring_slots=4)
