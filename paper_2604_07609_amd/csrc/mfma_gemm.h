@@ -55,9 +55,9 @@ struct MfmaGemmArgs {
   u32 tune_nw;             // tests and tuning. Low byte: 0 automatic choice of weight tiles per workgroup, 1/2/4 forced.
                            // Bit 9: tile schedule with direct loads instead of LDS staging (bit 8: its 256-token
                            // workgroup tile in eight-wave kernels). Bit 10: no split of K between workgroup halves.
-                           // Bit 11: no 64 x 64 streaming items for 64 < T <= 256. Bits 12-14: 2, 3 or 4 force the
+                           // Bit 11: no 64 x 64 streaming items for 64 < T <= 256. Bits 12-14: 2, 3, 4 or 6 force the
                            // token tiles per wave of the LDS-staged tile schedule. Bit 20: eight-wave kernels never
-                           // take the pair of tiles with shared weight tiles.
+                           // take the pair of tiles with shared weight tiles. Bit 21: never 192-token tiles.
 };
 
 #define GEMM_MAX_WAVES 8
@@ -67,7 +67,7 @@ struct MfmaShared {
     float red[GEMM_MAX_WAVES][4][64][4];       // [wave][token block][lane][4]  (stream schedule; scratch of the norm scales)
     unsigned char tile[2][2 * GEMM_TILE_LDS];  // [four-wave half of the workgroup][k-step parity]  (tile schedule)
   };
-  float rstd[256];
+  float rstd[384];   // norm scales of the tokens of a workgroup tile (or pair of tiles)
 };
 
 __device__ __forceinline__ u64 packed_off(u32 t, u32 k, u32 TBS) {
@@ -430,14 +430,18 @@ __device__ __forceinline__ void tile_coords(u32 i, u32 nblocks, u32 tblocks, u32
 template <int EPI, int TJ>
 __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg) {
   constexpr u32 BT = 32 * TJ, XT = 2 * TJ;        // tokens and activation tiles of a workgroup tile
+  // bytes of one LDS buffer; the 192-token tile (TJ = 6, 20 KB per buffer) takes both halves' space and so runs in
+  // four-wave workgroups only
+  constexpr u32 TLB = TJ > 4 ? (8 + XT) * 1024 : GEMM_TILE_LDS;
   const u32 lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const u32 halves = blockDim.x >> 8, half = w >> 2, wl = w & 3, wn = wl & 1, wt = wl >> 1;
   const u32 NT = (a.N + 15) / 16, KT = a.K / 32;
   const u32 nblocks = (NT + 7) / 8, tblocks = (a.T + BT - 1) / BT, total = nblocks * tblocks;
   const u64 xk_stride = (u64)a.TBS * 512, w_stride = (u64)KT * 512;
   // LDS buffer of one k-step: weight tiles 0..7, then activation tiles 0..XT-1 (1 KB each). This wave stores weight
-  // tiles 2 wl, 2 wl + 1 and activation tiles wl and wl + 4 (the latter only if the tile has that many)
-  const bool x2 = TJ == 4 || wl + 4 < XT;     // known at compile time for full-width tiles: no branch around the load
+  // tiles 2 wl, 2 wl + 1 and activation tiles wl, wl + 4 and wl + 8 (the latter two only if the tile has that many)
+  const bool x2 = TJ >= 4 || wl + 4 < XT;     // known at compile time for full-width tiles: no branch around the load
+  constexpr bool x3 = TJ > 4;
   unsigned char* const Lww = sh.tile[half] + (wl * 2) * 1024 + lane * 16;
   unsigned char* const Lwx = sh.tile[half] + 8192 + wl * 1024 + lane * 16;
   const unsigned char* const Lrw = sh.tile[half] + (wn * 4) * 1024 + lane * 16;
@@ -447,7 +451,7 @@ __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared&
   // first's through LDS before the epilogue (fixed order, so the result does not depend on timing).
   // (rounds of workgroups, one per CU: a tile takes a workgroup half as long when its halves share it)
   const u32 ncu = nwg / 2, rounds_split = (total + ncu - 1) / ncu, rounds_pair = ((total + 1) / 2 + ncu - 1) / ncu;
-  const bool splitk = halves == 2 && (KT & 1u) == 0 && rounds_split < 2 * rounds_pair && !(a.tune_nw & 0x400u);   // bit 10: never (tests)
+  const bool splitk = TJ <= 4 && halves == 2 && (KT & 1u) == 0 && rounds_split < 2 * rounds_pair && !(a.tune_nw & 0x400u);   // bit 10: never (tests)
   const u32 per_item = splitk ? 1u : halves;
   const u32 k0 = (splitk && half) ? KT / 2 : 0u, kn = splitk ? KT / 2 : KT, klast = k0 + kn - 1;
   const u32 nitems = (total + per_item - 1) / per_item;
@@ -464,15 +468,17 @@ __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared&
     // this lane's 16 bytes of the two activation tiles its wave fetches; through the token indirection (LM head) the
     // sixteen tokens of a tile come from arbitrary columns of the operand. A tile past the operand's last token block
     // (only in the last workgroup tile) is clamped: its columns are dropped by the epilogue.
-    const bf16_t *gx0, *gx1;
+    const bf16_t *gx0, *gx1, *gx2;
     if (a.tok_index) {
       const u32 ta = tb * BT + wl * 16 + (lane & 15);
-      const u32 s0 = a.tok_index[min(ta, a.T - 1)], s1 = a.tok_index[min(ta + 64, a.T - 1)];
+      const u32 s0 = a.tok_index[min(ta, a.T - 1)], s1 = a.tok_index[min(ta + 64, a.T - 1)], s2 = a.tok_index[min(ta + 128, a.T - 1)];
       gx0 = a.Xp + ((u64)(s0 >> 4) * 64 + (s0 & 15) + 16 * (lane >> 4)) * 8;
       gx1 = a.Xp + ((u64)(s1 >> 4) * 64 + (s1 & 15) + 16 * (lane >> 4)) * 8;
+      gx2 = a.Xp + ((u64)(s2 >> 4) * 64 + (s2 & 15) + 16 * (lane >> 4)) * 8;
     } else {
       gx0 = a.Xp + (u64)min(tb * XT + wl, a.TBS - 1) * 512 + lane * 8;
       gx1 = a.Xp + (u64)min(tb * XT + wl + 4, a.TBS - 1) * 512 + lane * 8;
+      gx2 = a.Xp + (u64)min(tb * XT + wl + 8, a.TBS - 1) * 512 + lane * 8;
     }
     floatx4_t acc[4][TJ];
 #pragma unroll
@@ -480,18 +486,21 @@ __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared&
 #pragma unroll
       for (int j = 0; j < TJ; ++j) acc[i][j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
     // staging registers as separate variables (arrays or structs of them may end up in scratch memory)
-    uint4 ga0, ga1, ga2, ga3, gb0, gb1, gb2, gb3;
-    ga3 = gb3 = make_uint4(0, 0, 0, 0);
+    uint4 ga0, ga1, ga2, ga3, ga4, gb0, gb1, gb2, gb3, gb4;
+    ga3 = gb3 = ga4 = gb4 = make_uint4(0, 0, 0, 0);
 #define TL_GLOAD(g, kt) { const u32 kc_ = min(k0 + (u32)(kt), klast);                                                      \
       g##0 = *(const uint4*)(gw0 + (u64)kc_ * 512); g##1 = *(const uint4*)(gw1 + (u64)kc_ * 512);                          \
-      g##2 = *(const uint4*)(gx0 + (u64)kc_ * xk_stride); if (x2) g##3 = *(const uint4*)(gx1 + (u64)kc_ * xk_stride); }
-#define TL_STORE(g, buf) { *(uint4*)(Lww + (buf) * GEMM_TILE_LDS) = g##0; *(uint4*)(Lww + (buf) * GEMM_TILE_LDS + 1024) = g##1; \
-      *(uint4*)(Lwx + (buf) * GEMM_TILE_LDS) = g##2; if (x2) *(uint4*)(Lwx + (buf) * GEMM_TILE_LDS + 4096) = g##3; }
-#define TL_RW(buf, i) as_bf16x8(*(const uint4*)(Lrw + (buf) * GEMM_TILE_LDS + (i) * 1024))
-#define TL_RX(buf, j) as_bf16x8(*(const uint4*)(Lrx + (buf) * GEMM_TILE_LDS + ((j) < TJ ? (j) : 0) * 1024))
+      g##2 = *(const uint4*)(gx0 + (u64)kc_ * xk_stride); if (x2) g##3 = *(const uint4*)(gx1 + (u64)kc_ * xk_stride);         \
+      if (x3) g##4 = *(const uint4*)(gx2 + (u64)kc_ * xk_stride); }
+#define TL_STORE(g, buf) { *(uint4*)(Lww + (buf) * TLB) = g##0; *(uint4*)(Lww + (buf) * TLB + 1024) = g##1;                      \
+      *(uint4*)(Lwx + (buf) * TLB) = g##2; if (x2) *(uint4*)(Lwx + (buf) * TLB + 4096) = g##3;                             \
+      if (x3) *(uint4*)(Lwx + (buf) * TLB + 8192) = g##4; }
+#define TL_RW(buf, i) as_bf16x8(*(const uint4*)(Lrw + (buf) * TLB + (i) * 1024))
+#define TL_RX(buf, j) as_bf16x8(*(const uint4*)(Lrx + (buf) * TLB + ((j) < TJ ? (j) : 0) * 1024))
 #define TL_MM(A, W, X) A = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W, X, A, 0, 0, 0);
 #define TL_ROW(i, o) TL_MM(acc[i][0], o.w##i, o.x0) TL_MM(acc[i][1], o.w##i, o.x1)                                         \
-      if (TJ > 2) { TL_MM(acc[i][TJ > 2 ? 2 : 0], o.w##i, o.x2) } if (TJ > 3) { TL_MM(acc[i][TJ > 3 ? 3 : 0], o.w##i, o.x3) }
+      if (TJ > 2) { TL_MM(acc[i][TJ > 2 ? 2 : 0], o.w##i, o.x2) } if (TJ > 3) { TL_MM(acc[i][TJ > 3 ? 3 : 0], o.w##i, o.x3) }            \
+      if (TJ > 4) { TL_MM(acc[i][TJ > 4 ? 4 : 0], o.w##i, o.x4) TL_MM(acc[i][TJ > 4 ? 5 : 0], o.w##i, o.x5) }
 #define TL_SB __builtin_amdgcn_sched_barrier(0);
     // step k with its operands in `o`: reads the operands of step k+1 from LDS buffer rb into `n`, stores the staged data
     // of step k+2 (in g) into LDS buffer wb and requests step k+4 into g
@@ -500,10 +509,11 @@ __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared&
     TL_SB TL_ROW(0, o) TL_ROW(1, o) TL_SB                                                                                 \
     if (TJ > 2) n.x2 = TL_RX(rb, 2);                                                                                      \
     n.w2 = TL_RW(rb, 2); if (TJ > 3) n.x3 = TL_RX(rb, 3);                                                                  \
+    if (TJ > 4) { n.x4 = TL_RX(rb, 4); n.x5 = TL_RX(rb, 5); }                                                             \
     n.w3 = TL_RW(rb, 3); TL_GLOAD(g, (k) + 4)                                                                             \
     TL_SB TL_ROW(2, o) TL_ROW(3, o) TL_SB                                                                                 \
     __syncthreads();
-    struct Ops { bf16x8_t w0, w1, w2, w3, x0, x1, x2, x3; };
+    struct Ops { bf16x8_t w0, w1, w2, w3, x0, x1, x2, x3, x4, x5; };
     Ops oa, ob;
     TL_GLOAD(ga, 0) TL_GLOAD(gb, 1)             // in flight while the norm scales are computed
     for (u32 h = 0; h < per_item; ++h) {
@@ -515,7 +525,7 @@ __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared&
     TL_STORE(ga, 0) TL_STORE(gb, 1) TL_GLOAD(ga, 2) TL_GLOAD(gb, 3)
     __syncthreads();
     oa.w0 = TL_RW(0, 0); oa.w1 = TL_RW(0, 1); oa.w2 = TL_RW(0, 2); oa.w3 = TL_RW(0, 3);
-    oa.x0 = TL_RX(0, 0); oa.x1 = TL_RX(0, 1); oa.x2 = TL_RX(0, 2); oa.x3 = TL_RX(0, 3);
+    oa.x0 = TL_RX(0, 0); oa.x1 = TL_RX(0, 1); oa.x2 = TL_RX(0, 2); oa.x3 = TL_RX(0, 3); oa.x4 = TL_RX(0, 4); oa.x5 = TL_RX(0, 5);
     __syncthreads();   // step 0 overwrites buffer 0, which every wave has just read (later steps read a buffer one step ahead)
     for (u32 k = 0; k < kn; k += 2) {
       TL_STEP(oa, ob, ga, k, 1, 0)
@@ -535,14 +545,14 @@ __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared&
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-          for (int j = 0; j < TJ; ++j) *(floatx4_t*)(red + (i * 4 + j) * 256) = acc[i][j];
+          for (int j = 0; j < TJ; ++j) *(floatx4_t*)(red + (i * 4 + (j & 3)) * 256) = acc[i][j];   // (never taken with TJ > 4)
       }
       __syncthreads();
       if (half == 0) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-          for (int j = 0; j < TJ; ++j) acc[i][j] += *(const floatx4_t*)(red + (i * 4 + j) * 256);
+          for (int j = 0; j < TJ; ++j) acc[i][j] += *(const floatx4_t*)(red + (i * 4 + (j & 3)) * 256);
       }
     }
     const u32 rstd_off = splitk ? 0u : half * 128;
@@ -564,14 +574,15 @@ __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared&
 // unit, which is what bounds the tile schedule. Same pipeline as gemm_tile_lds.
 template <int EPI, int TJ>
 __device__ __forceinline__ void gemm_tile_lds_pair(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg) {
-  constexpr u32 BT = 32 * TJ, XT = 2 * TJ, LB = 2 * GEMM_TILE_LDS;   // one LDS buffer: 8 weight tiles + 2 XT activation tiles <= 24 KB
+  constexpr u32 BT = 32 * TJ, XT = 2 * TJ, LB = 2 * GEMM_TILE_LDS;   // one LDS buffer: 8 weight tiles + 2 XT activation tiles <= 32 KB
   const u32 lane = threadIdx.x & 63, w = threadIdx.x >> 6;           // eight waves
   const u32 half = w >> 2, wl = w & 3, wn = wl & 1, wt = wl >> 1;
   const u32 NT = (a.N + 15) / 16, KT = a.K / 32;
   const u32 nblocks = (NT + 7) / 8, tblocks = (a.T + BT - 1) / BT, tpairs = (tblocks + 1) / 2, total = nblocks * tpairs;
   const u64 xk_stride = (u64)a.TBS * 512, w_stride = (u64)KT * 512;
-  // wave w stores weight tile w and activation tiles w and w + 8 of the pair's 2 XT (the latter only if there are that many)
-  const bool x2 = TJ == 4 || w + 8 < 2 * XT;
+  // wave w stores weight tile w and activation tiles w, w + 8 and w + 16 of the pair's 2 XT (those that exist)
+  const bool x2 = TJ >= 4 || w + 8 < 2 * XT;
+  constexpr bool x3 = TJ > 4;
   unsigned char* const L0 = &sh.tile[0][0];
   unsigned char* const Lww = L0 + w * 1024 + lane * 16;
   unsigned char* const Lwx = L0 + 8192 + w * 1024 + lane * 16;
@@ -589,40 +600,45 @@ __device__ __forceinline__ void gemm_tile_lds_pair(const MfmaGemmArgs& a, MfmaSh
     // activation tile t of the pair (0 .. 2 XT - 1) is tile t of the 2 XT consecutive ones that start at tp * 2 XT
     const bf16_t* const gx0 = a.Xp + (u64)min(tp * 2 * XT + w, a.TBS - 1) * 512 + lane * 8;
     const bf16_t* const gx1 = a.Xp + (u64)min(tp * 2 * XT + w + 8, a.TBS - 1) * 512 + lane * 8;
+    const bf16_t* const gx2 = a.Xp + (u64)min(tp * 2 * XT + w + 16, a.TBS - 1) * 512 + lane * 8;
     floatx4_t acc[4][TJ];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
       for (int j = 0; j < TJ; ++j) acc[i][j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
-    uint4 ga0, ga1, ga2, gb0, gb1, gb2;
-    ga2 = gb2 = make_uint4(0, 0, 0, 0);
+    uint4 ga0, ga1, ga2, ga3, gb0, gb1, gb2, gb3;
+    ga2 = gb2 = ga3 = gb3 = make_uint4(0, 0, 0, 0);
 #define TL_GLOAD(g, kt) { const u32 kc_ = min((u32)(kt), KT - 1);                                                         \
       g##0 = *(const uint4*)(gw + (u64)kc_ * 512); g##1 = *(const uint4*)(gx0 + (u64)kc_ * xk_stride);                     \
-      if (x2) g##2 = *(const uint4*)(gx1 + (u64)kc_ * xk_stride); }
+      if (x2) g##2 = *(const uint4*)(gx1 + (u64)kc_ * xk_stride); if (x3) g##3 = *(const uint4*)(gx2 + (u64)kc_ * xk_stride); }
 #define TL_STORE(g, buf) { *(uint4*)(Lww + (buf) * LB) = g##0; *(uint4*)(Lwx + (buf) * LB) = g##1;                          \
-      if (x2) *(uint4*)(Lwx + (buf) * LB + 8192) = g##2; }
+      if (x2) *(uint4*)(Lwx + (buf) * LB + 8192) = g##2; if (x3) *(uint4*)(Lwx + (buf) * LB + 16384) = g##3; }
 #define TL_RW(buf, i) as_bf16x8(*(const uint4*)(Lrw + (buf) * LB + (i) * 1024))
 #define TL_RX(buf, j) as_bf16x8(*(const uint4*)(Lrx + (buf) * LB + ((j) < TJ ? (j) : 0) * 1024))
 #define TL_MM(A, W, X) A = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W, X, A, 0, 0, 0);
 #define TL_ROW(i, o) TL_MM(acc[i][0], o.w##i, o.x0) TL_MM(acc[i][1], o.w##i, o.x1)                                         \
-      if (TJ > 2) { TL_MM(acc[i][TJ > 2 ? 2 : 0], o.w##i, o.x2) } if (TJ > 3) { TL_MM(acc[i][TJ > 3 ? 3 : 0], o.w##i, o.x3) }
+      if (TJ > 2) { TL_MM(acc[i][TJ > 2 ? 2 : 0], o.w##i, o.x2) } if (TJ > 3) { TL_MM(acc[i][TJ > 3 ? 3 : 0], o.w##i, o.x3) }            \
+      if (TJ > 4) { TL_MM(acc[i][TJ > 4 ? 4 : 0], o.w##i, o.x4) TL_MM(acc[i][TJ > 4 ? 5 : 0], o.w##i, o.x5) }
 #define TL_SB __builtin_amdgcn_sched_barrier(0);
 #define TL_STEP(o, n, g, k, rb, wb)                                                                                       \
     n.x0 = TL_RX(rb, 0); n.w0 = TL_RW(rb, 0); n.x1 = TL_RX(rb, 1); n.w1 = TL_RW(rb, 1); TL_STORE(g, wb)                   \
     TL_SB TL_ROW(0, o) TL_ROW(1, o) TL_SB                                                                                 \
     if (TJ > 2) n.x2 = TL_RX(rb, 2);                                                                                      \
     n.w2 = TL_RW(rb, 2); if (TJ > 3) n.x3 = TL_RX(rb, 3);                                                                  \
+    if (TJ > 4) { n.x4 = TL_RX(rb, 4); n.x5 = TL_RX(rb, 5); }                                                             \
     n.w3 = TL_RW(rb, 3); TL_GLOAD(g, (k) + 4)                                                                             \
     TL_SB TL_ROW(2, o) TL_ROW(3, o) TL_SB                                                                                 \
     __syncthreads();
-    struct Ops { bf16x8_t w0, w1, w2, w3, x0, x1, x2, x3; };
+    struct Ops { bf16x8_t w0, w1, w2, w3, x0, x1, x2, x3, x4, x5; };
     Ops oa, ob;
     TL_GLOAD(ga, 0) TL_GLOAD(gb, 1)             // in flight while the norm scales are computed
-    compute_rstd(a, min(tp * 2 * BT, a.T - 1), min(2 * BT, 256u), sh, 0);   // both tiles' tokens; its barriers: the LDS tiles are free
+    // both tiles' tokens (at most 256 per call); its barriers: the LDS tiles are free
+    if (2 * BT <= 256) compute_rstd(a, min(tp * 2 * BT, a.T - 1), 2 * BT, sh, 0);
+    else { compute_rstd(a, min(tp * 2 * BT, a.T - 1), BT, sh, 0); compute_rstd(a, min(tp * 2 * BT + BT, a.T - 1), BT, sh, BT); }
     TL_STORE(ga, 0) TL_STORE(gb, 1) TL_GLOAD(ga, 2) TL_GLOAD(gb, 3)
     __syncthreads();
     oa.w0 = TL_RW(0, 0); oa.w1 = TL_RW(0, 1); oa.w2 = TL_RW(0, 2); oa.w3 = TL_RW(0, 3);
-    oa.x0 = TL_RX(0, 0); oa.x1 = TL_RX(0, 1); oa.x2 = TL_RX(0, 2); oa.x3 = TL_RX(0, 3);
+    oa.x0 = TL_RX(0, 0); oa.x1 = TL_RX(0, 1); oa.x2 = TL_RX(0, 2); oa.x3 = TL_RX(0, 3); oa.x4 = TL_RX(0, 4); oa.x5 = TL_RX(0, 5);
     __syncthreads();   // step 0 overwrites buffer 0, which every wave has just read (later steps read a buffer one step ahead)
     for (u32 k = 0; k < KT; k += 2) {
       TL_STEP(oa, ob, ga, k, 1, 0)
@@ -648,37 +664,48 @@ __device__ __forceinline__ void gemm_tile_lds_pair(const MfmaGemmArgs& a, MfmaSh
   }
 }
 
-// Token width of the workgroup tiles (128, 96 or 64) for this GEMM: the one whose rounds of workgroups take the least
-// time. A round of a narrower tile is shorter in proportion to its width, at a measured penalty for the extra operand
-// traffic per flop (96 / 64 tokens: 12 % / 24 % in the four-wave kernels, 24 % / 50 % in the eight-wave ones).
+// Token width of the workgroup tiles (192, 128, 96 or 64) for this GEMM: the one whose rounds of workgroups take the
+// least time. A round of a narrower tile is shorter in proportion to its width, at a measured cost for the extra
+// operand traffic per flop (relative to 128 tokens: 192 tokens 6 % less; 96 / 64 tokens 12 % / 24 % more in the
+// four-wave kernels, 24 % / 50 % more in the eight-wave ones). Eight waves take 192 tokens only as a shared-weight
+// pair (its two LDS buffers fill the 64 KB; two separate tiles of that width would not fit).
 template <int EPI>
 __device__ __forceinline__ void gemm_tile_pick(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg) {
   const u32 nblocks = ((a.N + 15) / 16 + 7) / 8, halves = blockDim.x >> 8, ncu = nwg / 2;
-  const u32 forced = (a.tune_nw >> 12) & 7u;       // bits 12-14 of the tuning word: 2, 3, 4 force the width (tests)
+  const u32 forced = (a.tune_nw >> 12) & 7u;       // bits 12-14 of the tuning word: 2, 3, 4, 6 force the width (tests)
+  const bool pair_ok = halves == 2 && !a.tok_index && !(a.tune_nw & 0x100000u);   // bit 20: never the shared pair (tests)
+  const bool wide_ok = halves == 1 || pair_ok;
   u32 best = 4, best_cost = ~0u;
-  for (u32 tj = 4; tj >= 2; --tj) {
+  for (u32 tj = 6; tj >= 2; --tj) {
+    if (tj == 5 || (tj == 6 && (!wide_ok || (a.tune_nw & 0x200000u)))) continue;   // bit 21: never 192 tokens (tests)
     const u32 total = nblocks * ((a.T + 32 * tj - 1) / (32 * tj));
     u32 rounds2;                                     // in half rounds of an eight-wave workgroup
-    if (halves == 2) rounds2 = min(2 * (((total + 1) / 2 + ncu - 1) / ncu), (a.K & 32u) ? ~0u : (total + ncu - 1) / ncu);
-    else rounds2 = 2 * ((total + nwg - 1) / nwg);
-    const u32 cost = rounds2 * tj * (tj == 4 ? 100u : (halves == 2 ? (tj == 3 ? 124u : 150u) : (tj == 3 ? 112u : 124u)));
+    if (halves == 2) {
+      const u32 r_pair = 2 * (((total + 1) / 2 + ncu - 1) / ncu), r_split = (a.K & 32u) ? ~0u : (total + ncu - 1) / ncu;
+      rounds2 = tj == 6 ? r_pair : min(r_pair, r_split);
+    } else rounds2 = 2 * ((total + nwg - 1) / nwg);
+    const u32 pen = tj == 6 ? 94u : tj == 4 ? 100u : (halves == 2 ? (tj == 3 ? 124u : 150u) : (tj == 3 ? 112u : 124u));
+    const u32 cost = rounds2 * tj * pen;
     if (cost < best_cost) { best_cost = cost; best = tj; }
   }
   if (forced >= 2 && forced <= 4) best = forced;
+  if (forced == 6 && wide_ok) best = 6;
   // eight waves: a pair of tiles with shared weight tiles unless splitting K between the halves takes fewer rounds
-  // (the same rule as inside gemm_tile_lds); bit 20 of the tuning word: never the shared pair (tests)
+  // (the same rule as inside gemm_tile_lds)
   bool pair = false;
-  if (halves == 2 && !a.tok_index && !(a.tune_nw & 0x100000u)) {
+  if (pair_ok) {
     const u32 tblocks = (a.T + 32 * best - 1) / (32 * best), total = nblocks * tblocks;
     const u32 rounds_split = (total + ncu - 1) / ncu, rounds_pair = ((total + 1) / 2 + ncu - 1) / ncu;
     const bool splitk = (a.K & 32u) == 0 && rounds_split < 2 * rounds_pair && !(a.tune_nw & 0x400u);
-    pair = !splitk;
+    pair = best == 6 || !splitk;
   }
   if (pair) {
-    if (best == 4) gemm_tile_lds_pair<EPI, 4>(a, sh, wg, nwg);
+    if (best == 6) gemm_tile_lds_pair<EPI, 6>(a, sh, wg, nwg);
+    else if (best == 4) gemm_tile_lds_pair<EPI, 4>(a, sh, wg, nwg);
     else if (best == 3) gemm_tile_lds_pair<EPI, 3>(a, sh, wg, nwg);
     else gemm_tile_lds_pair<EPI, 2>(a, sh, wg, nwg);
-  } else if (best == 4) gemm_tile_lds<EPI, 4>(a, sh, wg, nwg);
+  } else if (best == 6) gemm_tile_lds<EPI, 6>(a, sh, wg, nwg);
+  else if (best == 4) gemm_tile_lds<EPI, 4>(a, sh, wg, nwg);
   else if (best == 3) gemm_tile_lds<EPI, 3>(a, sh, wg, nwg);
   else gemm_tile_lds<EPI, 2>(a, sh, wg, nwg);
 }
