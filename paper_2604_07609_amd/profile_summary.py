@@ -42,7 +42,7 @@ def split_iterations(rows, value, order):
         if n == "k_sched":
             cur = []
             its.append(cur)
-        elif cur is not None and n.startswith("k_") and n not in ("k_copy_calibration", "k_pack_weights", "k_rope_table", "k_open_window"):
+        elif cur is not None and n.startswith("k_") and n not in ("k_copy_calibration", "k_mfma_calibration", "k_pack_weights", "k_rope_table", "k_open_window"):
             cur.append((n, value(r)))
     return its
 
@@ -84,7 +84,9 @@ def pmc_summary(fetch_path, write_path, kinds_path, kernel, workload, command):
     tot = 0.0
     for label, path in (("FETCH_SIZE", fetch_path), ("WRITE_SIZE", write_path)):
         rows = [r for r in csv.DictReader(open(path))]
-        copy = [float(r["Counter_Value"]) for r in rows if short(r["Kernel_Name"]) == "k_copy_calibration"]
+        # the first launch of the copy kernel is the 64 MiB one (the rate measurement after it copies 1 GiB per launch)
+        copy = [float(r["Counter_Value"]) for r in sorted(rows, key=lambda r: int(r["Dispatch_Id"]))
+                if short(r["Kernel_Name"]) == "k_copy_calibration"]
         factor = COPY_BYTES / 1024.0 / copy[0]
         its = split_iterations(rows, lambda r: float(r["Counter_Value"]), lambda r: int(r["Dispatch_Id"]))
         its = real_iterations(its, 64.0)                 # KiB: an empty launch moves next to nothing
