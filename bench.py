@@ -290,6 +290,11 @@ def main():
             for t in trace[trace["iteration"] < s1["iterations"]]:
                 f.write("%d %d %d %d %d %d\n" % (t["iteration"], t["kind"], t["n_seqs"], t["n_tokens"], t["ctx_tokens"],
                                                  int(t["iteration"] >= s0["iterations"])))
+        if len(phase_ms):       # the timed phase's summed launch time of every timed iteration, in enqueue order
+            with open(args.dump_iterations + ".phase_ms", "w") as f:
+                tt = trace[(trace["iteration"] >= s0["iterations"]) & (trace["iteration"] < s1["iterations"])]
+                for t, ms in zip(tt, phase_ms):
+                    f.write("%d %d %d %d %.4f\n" % (t["iteration"], t["kind"], t["n_seqs"], t["n_tokens"], ms))
     iters = int(s1["iterations"] - s0["iterations"])
     toks = int(s1["tokens_out"] - s0["tokens_out"])
     dt = t1 - t0

@@ -76,9 +76,14 @@ __device__ __forceinline__ void attn_block(const KVTile<HD>& kv, const bf16x8_t 
   const short4_t (&vb)[HD / 16] = kv.vb;
 #pragma unroll
   for (int c = 0; c < CT; ++c) {
-    floatx4_t s4 = floatx4_t{0.f, 0.f, 0.f, 0.f};
+    // two independent accumulation chains (a product waits for the one before it in its chain)
+    floatx4_t s4 = floatx4_t{0.f, 0.f, 0.f, 0.f}, s4b = floatx4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int s = 0; s < HD / 32; ++s) s4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[s], q[c][s], s4, 0, 0, 0);
+    for (int s = 0; s < HD / 32; s += 2) {
+      s4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[s], q[c][s], s4, 0, 0, 0);
+      s4b = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[s + 1], q[c][s + 1], s4b, 0, 0, 0);
+    }
+    s4 += s4b;
     float bm = -INFINITY;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -100,9 +105,13 @@ __device__ __forceinline__ void attn_block(const KVTile<HD>& kv, const bf16x8_t 
     float c4[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) c4[i] = __shfl(corr, lg * 4 + i);
-    short4_t pa;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) pa[i] = (short)f32_to_bf16(p[i]);
+    // probabilities to bf16: the hardware conversion (round to nearest even), two values per instruction
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    typedef float floatx2_t __attribute__((ext_vector_type(2)));
+    union { bf16x2_t h[2]; short4_t v; } pk;
+    pk.h[0] = __builtin_convertvector(floatx2_t{p[0], p[1]}, bf16x2_t);
+    pk.h[1] = __builtin_convertvector(floatx2_t{p[2], p[3]}, bf16x2_t);
+    const short4_t pa = pk.v;
 #pragma unroll
     for (int d = 0; d < HD / 16; ++d) {
 #pragma unroll
@@ -303,12 +312,12 @@ __device__ __forceinline__ void attn_prefill(const DevCtx& c, u32 layer, AttnMfm
   auto cuq = [&](u32 i) { return sh.cu_chunks[i]; };
   const u64 total = (u64)cuq(B) * per_tile;
   // waves per item: doubled while the longest chain (blocks of the longest prompt / WPI) is long and the items, each
-  // now taking WPI wave slots, still fit the waves that run at once about three times over
+  // now taking WPI wave slots, still fit the waves that run at once
   u32 WPI = 1;
   {
     const u32 chain = (c.meta->max_q_len + 15) / 16;
     const u64 slots = (u64)(nwg / 2) * nw;
-    while (WPI < nw && WPI < 8 && chain > 12 * WPI && total * WPI * 2 <= slots * 3) WPI *= 2;
+    while (WPI < nw && WPI < 8 && chain > 12 * WPI && total * WPI <= slots) WPI *= 2;
     const u32 forced = (c.tune_nw >> 16) & 15u;      // bits 16-19 of the tuning word: 1, 2, 4, 8 force it (tests)
     if (forced == 1 || forced == 2 || forced == 4 || forced == 8) WPI = min(forced, nw);
   }
@@ -319,7 +328,9 @@ __device__ __forceinline__ void attn_prefill(const DevCtx& c, u32 layer, AttnMfm
     u32 g = 0, hg = 0, p0 = 0, t0 = 0, P = 1, last = 0;
     const u32* bt = c.block_tables;
     if (valid) {
-      const u32 qi = (u32)(item / per_tile), rem = (u32)(item % per_tile);
+      // query tiles in descending order: the causal mask makes the later tiles of a prompt walk more blocks, and the
+      // workgroups that start first should take the longest chains (the short ones then fill the gaps)
+      const u32 qi = cuq(B) - 1 - (u32)(item / per_tile), rem = (u32)(item % per_tile);
       g = rem / groups; hg = rem % groups;
       u32 lo = 0, hi = B;                       // sequence of query tile qi: last s with cu_qtiles[s] <= qi
       while (hi - lo > 1) {
