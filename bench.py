@@ -233,6 +233,8 @@ def main():
                     help="write one line per iteration of the warm-up and the timed window (kind, sequences, tokens, context "
                          "tokens, timed flag): lets a rocprofv3 trace of the same run be split by iteration kind")
     ap.add_argument("--open-loop-seconds", type=float, default=8.0, help="0: skip the run with the workload's own arrivals")
+    ap.add_argument("--rates", default="", help="comma-separated arrival rates (requests/s): one more open-loop run at each, "
+                    "with the workload's lengths and arrival times redrawn at that rate")
     ap.add_argument("--interference", action="store_true",
                     help="repeat the open-loop run with a host memory-bandwidth stressor on every core and report the ratios")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0)
@@ -402,6 +404,14 @@ def main():
                                            ttft_p50=ratio(stressed["ttft_ms"]["p50"], iso["ttft_ms"]["p50"]),
                                            ttft_p99=ratio(stressed["ttft_ms"]["p99"], iso["ttft_ms"]["p99"]),
                                            output_tokens_per_s=ratio(stressed["output_tokens_per_s"], iso["output_tokens_per_s"])))
+    if args.rates and args.open_loop_seconds > 0:
+        sweep = []
+        for rate in [float(x) for x in args.rates.split(",") if x]:
+            rr = synth.make_workload(wl["workload"], cfg["vocab"], wl["rseed"], n_requests=args.requests or None, rate=rate)
+            res = open_loop(B, cfg, eng, blob, rr, args.open_loop_seconds)
+            if res:
+                sweep.append(dict(rate_req_per_s=rate, **res))
+        out["open_loop_sweep"] = sweep
     del blob
     if not args.no_cpu_baseline:
         budget = args.cpu_sample_tokens or {"tiny": 32, "churn": 16, "llama3_8b": 2, "sched_stress": 16}[args.workload]
