@@ -56,8 +56,8 @@ struct MfmaGemmArgs {
                            // Bit 9: tile schedule with direct loads instead of LDS staging (bit 8: its 256-token
                            // workgroup tile in eight-wave kernels). Bit 10: no split of K between workgroup halves.
                            // Bit 11: no 64 x 64 streaming items for 64 < T <= 256. Bits 12-14: 2, 3, 4 or 6 force the
-                           // token tiles per wave of the LDS-staged tile schedule. Bit 20: eight-wave kernels never
-                           // take the pair of tiles with shared weight tiles. Bit 21: never 192-token tiles.
+                           // token tiles per wave of the LDS-staged tile schedule, 7 its 256-token tile. Bit 20: eight-wave kernels never
+                           // take the pair of tiles with shared weight tiles. Bit 21: no tiles wider than 128 tokens.
 };
 
 #define GEMM_MAX_WAVES 8
@@ -664,32 +664,135 @@ __device__ __forceinline__ void gemm_tile_lds_pair(const MfmaGemmArgs& a, MfmaSh
   }
 }
 
-// Token width of the workgroup tiles (192, 128, 96 or 64) for this GEMM: the one whose rounds of workgroups take the
-// least time. A round of a narrower tile is shorter in proportion to its width, at a measured cost for the extra
-// operand traffic per flop (relative to 128 tokens: 192 tokens 6 % less; 96 / 64 tokens 12 % / 24 % more in the
-// four-wave kernels, 24 % / 50 % more in the eight-wave ones). Eight waves take 192 tokens only as a shared-weight
-// pair (its two LDS buffers fill the 64 KB; two separate tiles of that width would not fit).
+// Four waves on 128 rows x 256 tokens (64 x 128 per wave: 128 accumulator registers). The registers leave room for one
+// set of operands only, so a wave reads its 4 + 8 operand tiles of a k-step from LDS at the start of the step and
+// begins its 32 MFMAs as they arrive; the global data of the following steps are staged as in gemm_tile_lds (two
+// register sets, two steps ahead, one barrier per step, two LDS buffers of 24 KB). Per MFMA it moves a quarter less
+// through LDS and out of L2 than the 128-token tile.
+template <int EPI>
+__device__ __forceinline__ void gemm_tile_lds_wide(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg) {
+  constexpr u32 TJ = 8, BT = 32 * TJ, XT = 2 * TJ, LB = (8 + XT) * 1024;
+  const u32 lane = threadIdx.x & 63, w = (threadIdx.x >> 6) & 3, wn = w & 1, wt = w >> 1;
+  const u32 NT = (a.N + 15) / 16, KT = a.K / 32;
+  const u32 nblocks = (NT + 7) / 8, tblocks = (a.T + BT - 1) / BT, total = nblocks * tblocks;
+  const u64 xk_stride = (u64)a.TBS * 512, w_stride = (u64)KT * 512;
+  // LDS buffer of one k-step: weight tiles 0..7, then activation tiles 0..15. This wave stores weight tiles 2 w, 2 w + 1
+  // and activation tiles w, w + 4, w + 8, w + 12
+  unsigned char* const L0 = &sh.tile[0][0];
+  unsigned char* const Lww = L0 + (w * 2) * 1024 + lane * 16;
+  unsigned char* const Lwx = L0 + 8192 + w * 1024 + lane * 16;
+  const unsigned char* const Lrw = L0 + (wn * 4) * 1024 + lane * 16;
+  const unsigned char* const Lrx = L0 + 8192 + (wt * TJ) * 1024 + lane * 16;
+  for (u32 base = 0; base < total; base += nwg) {
+    const u32 it = xcd_item(base, total, wg, nwg);
+    if (it == ~0u) continue;
+    u32 tb = 0, nb = 0;
+    tile_coords(it, nblocks, tblocks, nb, tb);
+    const u32 nt0 = nb * 8 + wn * 4;
+    const bf16_t* const gw0 = a.Wp + (u64)min(nb * 8 + w * 2, NT - 1) * w_stride + lane * 8;
+    const bf16_t* const gw1 = a.Wp + (u64)min(nb * 8 + w * 2 + 1, NT - 1) * w_stride + lane * 8;
+    // this lane's 16 bytes of the four activation tiles its wave fetches (see gemm_tile_lds: token indirection, clamping)
+    const bf16_t *gx0, *gx1, *gx2, *gx3;
+    if (a.tok_index) {
+      const u32 ta = tb * BT + w * 16 + (lane & 15);
+      const u32 s0 = a.tok_index[min(ta, a.T - 1)], s1 = a.tok_index[min(ta + 64, a.T - 1)];
+      const u32 s2 = a.tok_index[min(ta + 128, a.T - 1)], s3 = a.tok_index[min(ta + 192, a.T - 1)];
+      gx0 = a.Xp + ((u64)(s0 >> 4) * 64 + (s0 & 15) + 16 * (lane >> 4)) * 8;
+      gx1 = a.Xp + ((u64)(s1 >> 4) * 64 + (s1 & 15) + 16 * (lane >> 4)) * 8;
+      gx2 = a.Xp + ((u64)(s2 >> 4) * 64 + (s2 & 15) + 16 * (lane >> 4)) * 8;
+      gx3 = a.Xp + ((u64)(s3 >> 4) * 64 + (s3 & 15) + 16 * (lane >> 4)) * 8;
+    } else {
+      gx0 = a.Xp + (u64)min(tb * XT + w, a.TBS - 1) * 512 + lane * 8;
+      gx1 = a.Xp + (u64)min(tb * XT + w + 4, a.TBS - 1) * 512 + lane * 8;
+      gx2 = a.Xp + (u64)min(tb * XT + w + 8, a.TBS - 1) * 512 + lane * 8;
+      gx3 = a.Xp + (u64)min(tb * XT + w + 12, a.TBS - 1) * 512 + lane * 8;
+    }
+    floatx4_t acc[4][TJ];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < TJ; ++j) acc[i][j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+    uint4 ga0, ga1, ga2, ga3, ga4, ga5, gb0, gb1, gb2, gb3, gb4, gb5;   // separate variables, see gemm_tile_lds
+#define TW_GLOAD(g, kt) { const u32 kc_ = min((u32)(kt), KT - 1);                                                          \
+      g##0 = *(const uint4*)(gw0 + (u64)kc_ * 512); g##1 = *(const uint4*)(gw1 + (u64)kc_ * 512);                          \
+      g##2 = *(const uint4*)(gx0 + (u64)kc_ * xk_stride); g##3 = *(const uint4*)(gx1 + (u64)kc_ * xk_stride);              \
+      g##4 = *(const uint4*)(gx2 + (u64)kc_ * xk_stride); g##5 = *(const uint4*)(gx3 + (u64)kc_ * xk_stride); }
+#define TW_STORE(g, buf) { *(uint4*)(Lww + (buf) * LB) = g##0; *(uint4*)(Lww + (buf) * LB + 1024) = g##1;                   \
+      *(uint4*)(Lwx + (buf) * LB) = g##2; *(uint4*)(Lwx + (buf) * LB + 4096) = g##3;                                       \
+      *(uint4*)(Lwx + (buf) * LB + 8192) = g##4; *(uint4*)(Lwx + (buf) * LB + 12288) = g##5; }
+#define TW_RW(buf, i) as_bf16x8(*(const uint4*)(Lrw + (buf) * LB + (i) * 1024))
+#define TW_RX(buf, j) as_bf16x8(*(const uint4*)(Lrx + (buf) * LB + (j) * 1024))
+#define TW_MM(A, W, X) A = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W, X, A, 0, 0, 0);
+#define TW_COL(j, xx) TW_MM(acc[0][j], w0_, xx) TW_MM(acc[1][j], w1_, xx) TW_MM(acc[2][j], w2_, xx) TW_MM(acc[3][j], w3_, xx)
+    // step k: operands from buffer rb; the staged data of step k+1 (in g) go to buffer wb; g then requests step k+3
+#define TW_STEP(g, k, rb, wb) {                                                                                         \
+      const bf16x8_t w0_ = TW_RW(rb, 0), w1_ = TW_RW(rb, 1), w2_ = TW_RW(rb, 2), w3_ = TW_RW(rb, 3);                       \
+      const bf16x8_t x0_ = TW_RX(rb, 0), x1_ = TW_RX(rb, 1), x2_ = TW_RX(rb, 2), x3_ = TW_RX(rb, 3);                       \
+      const bf16x8_t x4_ = TW_RX(rb, 4), x5_ = TW_RX(rb, 5), x6_ = TW_RX(rb, 6), x7_ = TW_RX(rb, 7);                       \
+      TW_STORE(g, wb) TW_GLOAD(g, (k) + 3)                                                                               \
+      TW_COL(0, x0_) TW_COL(1, x1_) TW_COL(2, x2_) TW_COL(3, x3_) TW_COL(4, x4_) TW_COL(5, x5_) TW_COL(6, x6_) TW_COL(7, x7_) \
+      __syncthreads(); }
+    TW_GLOAD(ga, 0)                              // in flight while the norm scales are computed
+    compute_rstd(a, tb * BT, BT, sh, 0);         // its barriers: the LDS tiles are free
+    TW_STORE(ga, 0) TW_GLOAD(gb, 1) TW_GLOAD(ga, 2)
+    __syncthreads();
+    for (u32 k = 0; k < KT; k += 2) {
+      TW_STEP(gb, k, 0, 1)
+      if (k + 1 < KT) { TW_STEP(ga, k + 1, 1, 0) }
+    }
+#undef TW_GLOAD
+#undef TW_STORE
+#undef TW_RW
+#undef TW_RX
+#undef TW_MM
+#undef TW_COL
+#undef TW_STEP
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (nt0 + i < NT) {
+#pragma unroll
+        for (int j = 0; j < TJ; ++j)
+          epilogue_tile<EPI>(a, acc[i][j], nt0 + i, tb * BT + (wt * TJ + j) * 16, &sh.rstd[(wt * TJ + j) * 16]);
+      }
+  }
+}
+
+// Token width of the workgroup tiles (256, 192, 128, 96 or 64) for this GEMM: the one whose rounds of workgroups take
+// the least time. A round of a narrower tile is shorter in proportion to its width, at a measured cost for the extra
+// operand traffic per flop (relative to 128 tokens: 256 tokens 12 % less, 192 tokens 6 % less; 96 / 64 tokens 12 % /
+// 24 % more in the four-wave kernels, 24 % / 50 % more in the eight-wave ones). Eight waves take 192 tokens only as a
+// shared-weight pair (its two LDS buffers fill the 64 KB; two separate tiles of that width would not fit) and never
+// the 256-token tile (their pair of 128-token tiles already shares the weights of 256 tokens).
 template <int EPI>
 __device__ __forceinline__ void gemm_tile_pick(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg) {
   const u32 nblocks = ((a.N + 15) / 16 + 7) / 8, halves = blockDim.x >> 8, ncu = nwg / 2;
-  const u32 forced = (a.tune_nw >> 12) & 7u;       // bits 12-14 of the tuning word: 2, 3, 4, 6 force the width (tests)
+  const u32 forced = (a.tune_nw >> 12) & 7u;       // bits 12-14 of the tuning word: 2, 3, 4, 6 force the width, 7 the 256-token tile (tests)
   const bool pair_ok = halves == 2 && !a.tok_index && !(a.tune_nw & 0x100000u);   // bit 20: never the shared pair (tests)
   const bool wide_ok = halves == 1 || pair_ok;
   u32 best = 4, best_cost = ~0u;
-  for (u32 tj = 6; tj >= 2; --tj) {
-    if (tj == 5 || (tj == 6 && (!wide_ok || (a.tune_nw & 0x200000u)))) continue;   // bit 21: never 192 tokens (tests)
+  for (u32 tj = 8; tj >= 2; --tj) {
+    if (tj == 5 || tj == 7 || (tj == 8 && (halves != 1 || (a.tune_nw & 0x200000u))) ||
+        (tj == 6 && (!wide_ok || (a.tune_nw & 0x200000u)))) continue;   // bit 21: never wider than 128 tokens (tests)
     const u32 total = nblocks * ((a.T + 32 * tj - 1) / (32 * tj));
-    u32 rounds2;                                     // in half rounds of an eight-wave workgroup
+    u32 rounds2;                                     // eight waves: in half rounds of a workgroup
     if (halves == 2) {
       const u32 r_pair = 2 * (((total + 1) / 2 + ncu - 1) / ncu), r_split = (a.K & 32u) ? ~0u : (total + ncu - 1) / ncu;
       rounds2 = tj == 6 ? r_pair : min(r_pair, r_split);
-    } else rounds2 = 2 * ((total + nwg - 1) / nwg);
-    const u32 pen = tj == 6 ? 94u : tj == 4 ? 100u : (halves == 2 ? (tj == 3 ? 124u : 150u) : (tj == 3 ? 112u : 124u));
+    } else {
+      // four waves: two workgroups share a compute unit (workgroups w and w + ncu, by the order of dispatch). With b
+      // tiles on the less loaded of the two and a on the other, the unit works 2 b tile times at the shared rate and
+      // a - b (0 or 1) alone, where a tile takes 1.25 of its shared time (measured: a single round of 256-token tiles
+      // on half of the slots against a full round of 128-token tiles). In quarters of a tile time:
+      const u32 n_lo = total / nwg, extra = total % nwg, hi = n_lo + (extra > 0 ? 1u : 0u), lo = n_lo + (extra > ncu ? 1u : 0u);
+      rounds2 = 8 * lo + 5 * (hi - lo);
+    }
+    const u32 pen = tj == 8 ? 88u : tj == 6 ? 94u : tj == 4 ? 100u : (halves == 2 ? (tj == 3 ? 124u : 150u) : (tj == 3 ? 112u : 124u));
     const u32 cost = rounds2 * tj * pen;
     if (cost < best_cost) { best_cost = cost; best = tj; }
   }
   if (forced >= 2 && forced <= 4) best = forced;
   if (forced == 6 && wide_ok) best = 6;
+  if (forced == 7 && halves == 1) best = 8;
   // eight waves: a pair of tiles with shared weight tiles unless splitting K between the halves takes fewer rounds
   // (the same rule as inside gemm_tile_lds)
   bool pair = false;
@@ -704,7 +807,8 @@ __device__ __forceinline__ void gemm_tile_pick(const MfmaGemmArgs& a, MfmaShared
     else if (best == 4) gemm_tile_lds_pair<EPI, 4>(a, sh, wg, nwg);
     else if (best == 3) gemm_tile_lds_pair<EPI, 3>(a, sh, wg, nwg);
     else gemm_tile_lds_pair<EPI, 2>(a, sh, wg, nwg);
-  } else if (best == 6) gemm_tile_lds<EPI, 6>(a, sh, wg, nwg);
+  } else if (best == 8) gemm_tile_lds_wide<EPI>(a, sh, wg, nwg);
+  else if (best == 6) gemm_tile_lds<EPI, 6>(a, sh, wg, nwg);
   else if (best == 4) gemm_tile_lds<EPI, 4>(a, sh, wg, nwg);
   else if (best == 3) gemm_tile_lds<EPI, 3>(a, sh, wg, nwg);
   else gemm_tile_lds<EPI, 2>(a, sh, wg, nwg);

@@ -75,12 +75,13 @@ def test_bf16_wide_matrices(lib, name, max_batch, n_req):
     print(name, "max_batch", max_batch, "worst relative logit error", worst)
 
 
-@pytest.mark.parametrize("max_batch,tune", [(100, 0), (200, 0), (250, 0x800), (150, 0x200), (250, 0x6800), (140, 0x6000)])
+@pytest.mark.parametrize("max_batch,tune", [(100, 0), (200, 0), (250, 0x800), (150, 0x200), (250, 0x6800), (140, 0x6000), (250, 0x7000), (120, 0x7000)])
 def test_bf16_decode_batches_beyond_64(lib, max_batch, tune, monkeypatch):
     """Decode iterations of 65..256 tokens: the eight-wave projections run 64 x 64 streaming items over a
     (rows, token groups) grid (or, with bit 11 of the tuning word, the tile schedule), the gate/up projection the
     tile schedule, and the LM head the tile schedule through its token indirection (LDS-staged, or with bit 9
-    direct-load tiles; 0x6000 forces 192-token tiles, which the LM head reads through the indirection too)."""
+    direct-load tiles; 0x6000 forces 192-token tiles and 0x7000 the 256-token tile of the four-wave kernels, both of which the LM head
+    reads through the indirection too)."""
     monkeypatch.setenv("BLINK_TUNE_NW", str(tune))
     cfg, eng, raw, blob = setup("mini_wide2", 35)
     eng = dict(eng, max_batch=max_batch, kv_num_blocks=3 * max_batch + 64, ring_slots=512, max_prefill_tokens=2048)
@@ -108,13 +109,14 @@ def test_bf16_forced_tiles_per_workgroup(lib, nw, monkeypatch):
 
 
 @pytest.mark.parametrize("tune", [0, 0x400, 0x100400, 0x2000, 0x3000, 0x4000, 0x3400, 0x2400, 0x200, 0x300, 0x6000, 0x106000,
-                                  0x200000])
+                                  0x200000, 0x7000])
 def test_bf16_large_prefill_iterations(lib, tune, monkeypatch):
     """Prefill iterations of ~1000 tokens (nine 128-token tiles with a ragged last one, ragged last row block) through
     every variant of the tile schedule: LDS-staged tiles with the two halves of an eight-wave workgroup splitting K
     (the automatic choice at this size) or taking a tile each (with the weight tiles of the pair shared in LDS, or,
     with bit 20, separate), workgroup tiles of 64, 96, 128 and 192 tokens (bits 12-14 = 6: four-wave kernels take the 192-token tile,
-    eight-wave kernels the pair of two of them, or with bit 20 fall back to 128 tokens; bit 21: never 192), and
+    eight-wave kernels the pair of two of them, or with bit 20 fall back to 128 tokens; = 7: the four-wave kernels'
+    256-token tile; bit 21: never wider than 128), and
     direct-load tiles with the 128- and the 256-token workgroup tile."""
     monkeypatch.setenv("BLINK_TUNE_NW", str(tune))
     cfg, eng, raw, blob = setup("mini_wide4", 39)
