@@ -781,10 +781,11 @@ __device__ __forceinline__ void gemm_tile_pick(const MfmaGemmArgs& a, MfmaShared
     } else {
       // four waves: two workgroups share a compute unit (workgroups w and w + ncu, by the order of dispatch). With b
       // tiles on the less loaded of the two and a on the other, the unit works 2 b tile times at the shared rate and
-      // a - b (0 or 1) alone, where a tile takes 1.25 of its shared time (measured: a single round of 256-token tiles
-      // on half of the slots against a full round of 128-token tiles). In quarters of a tile time:
+      // a - b (0 or 1) alone, where a tile takes 1.25 to 1.5 of its shared time (measured: a single round of 256-token
+      // tiles on half of the slots against a full round of 128-token tiles; small matrices sit at the upper end, and
+      // 1.5 is what the count uses). In quarters of a tile time:
       const u32 n_lo = total / nwg, extra = total % nwg, hi = n_lo + (extra > 0 ? 1u : 0u), lo = n_lo + (extra > ncu ? 1u : 0u);
-      rounds2 = 8 * lo + 5 * (hi - lo);
+      rounds2 = 8 * lo + 6 * (hi - lo);
     }
     const u32 pen = tj == 8 ? 88u : tj == 6 ? 94u : tj == 4 ? 100u : (halves == 2 ? (tj == 3 ? 124u : 150u) : (tj == 3 ? 112u : 124u));
     const u32 cost = rounds2 * tj * pen;
