@@ -2,6 +2,7 @@
 
   python -m paper_2604_07609_amd.profile_summary trace <kernel_trace.csv> <iterations.txt> <kernel> <workload> "<command>"
   python -m paper_2604_07609_amd.profile_summary pmc <fetch.csv> <write.csv> <iterations.txt> <kernel> <workload> "<cmd>"
+  python -m paper_2604_07609_amd.profile_summary sq <counters.csv> <iterations.txt> <workload> "<command>"
 
 `iterations.txt` is what `bench.py --dump-iterations` wrote in the same run: the kind of every iteration. The dispatches
 in the CSV are cut into iterations at the scheduler kernel; iterations whose forward kernels do nothing (the launcher's
@@ -9,7 +10,9 @@ look-ahead past the end of a window) are dropped, and the rest line up one to on
 `trace`: per-kernel totals (what `--stats` prints) and the named kernel's average launch duration in the decode and in
 the prefill iterations of the timed window. `pmc`: HBM bytes per launch of the named kernel in the timed decode
 iterations from FETCH_SIZE and WRITE_SIZE (KiB per dispatch), each scaled by what the same counter reads for the
-64 MiB plain copy kernel that bench.py launches at its end.
+64 MiB plain copy kernel that bench.py launches at its end. `sq`: the sequencers' wait and issue counters (SQ_WAVE_CYCLES,
+SQ_WAIT_ANY, SQ_WAIT_INST_ANY, SQ_WAIT_INST_LDS, SQ_ACTIVE_INST_VALU, SQ_VALU_MFMA_BUSY_CYCLES, SQ_ACTIVE_INST_VMEM in
+one --pmc run) per kernel and iteration kind, the MFMA share also relative to the register-only MFMA loop of the same run.
 """
 import collections
 import csv
@@ -77,6 +80,54 @@ def trace_summary(path, kinds_path, kernel, workload, command):
     return "\n".join(out) + "\n"
 
 
+def sq_summary(path, kinds_path, workload, command):
+    """Issue-side counters of the sequencers, per kernel and iteration kind, as shares of the wave cycles; the MFMA share is
+    also given relative to the register-only MFMA loop bench.py runs at its end (the matrix cores' ceiling at this
+    occupancy)."""
+    names = ["SQ_WAIT_ANY", "SQ_WAIT_INST_ANY", "SQ_WAIT_INST_LDS", "SQ_ACTIVE_INST_VALU", "SQ_VALU_MFMA_BUSY_CYCLES", "SQ_ACTIVE_INST_VMEM"]
+    rows = [r for r in csv.DictReader(open(path))]
+    disp = {}
+    for r in rows:
+        d = disp.setdefault(int(r["Dispatch_Id"]), {"Kernel_Name": r["Kernel_Name"], "Dispatch_Id": r["Dispatch_Id"]})
+        d[r["Counter_Name"]] = float(r["Counter_Value"])
+    ds = [disp[k] for k in sorted(disp)]
+    ref = [d["SQ_VALU_MFMA_BUSY_CYCLES"] / d["SQ_WAVE_CYCLES"] for d in ds if short(d["Kernel_Name"]) == "k_mfma_calibration"]
+    ref = sum(ref) / len(ref) if ref else None
+    its, cur = [], None
+    for d in ds:
+        n = short(d["Kernel_Name"])
+        if n == "k_sched":
+            cur = []
+            its.append(cur)
+        elif cur is not None and n.startswith("k_") and n not in ("k_copy_calibration", "k_mfma_calibration", "k_pack_weights", "k_rope_table", "k_open_window"):
+            cur.append((n, d))
+    its = [it for it in its if max([d.get("SQ_VALU_MFMA_BUSY_CYCLES", 0.0) for _, d in it] or [0.0]) > 0.0]   # look-ahead iterations issue no MFMA
+    kinds = read_kinds(kinds_path)
+    out = ["# rocprofv3 --pmc (SQ counters): where the waves of each kernel spend their cycles, %s" % workload, "", "command: `%s`" % command, "",
+           "Shares of SQ_WAVE_CYCLES over the launches of the timed iterations. MFMA / loop = the MFMA share relative to the",
+           "register-only MFMA loop of the same run (%s of its wave cycles): the matrix cores' utilisation over the kernel's time." % ("%.2f" % ref if ref else "n/a"), ""]
+    if len(its) != len(kinds):
+        return "\n".join(out + ["%d iterations with work in the counters, %d recorded by bench.py: no table" % (len(its), len(kinds))]) + "\n"
+    out += ["| kernel | iterations | launches | wait (any) | wait (instruction) | wait (LDS) | VALU active | MFMA busy | MFMA / loop |", "|---|---|---|---|---|---|---|---|---|"]
+    for kernel in ("k_qkv", "k_attention", "k_oproj", "k_gateup", "k_down", "k_lm_head"):
+        for kind, label in ((1, "prefill"), (2, "decode")):
+            tot, n = collections.Counter(), 0
+            for it, k in zip(its, kinds):
+                if k["timed"] and k["kind"] == kind:
+                    for nm, d in it:
+                        if nm == kernel:
+                            n += 1
+                            for c in names + ["SQ_WAVE_CYCLES"]:
+                                tot[c] += d.get(c, 0.0)
+            if n:
+                wc = tot["SQ_WAVE_CYCLES"]
+                out.append("| %s | %s | %d | %.2f | %.2f | %.2f | %.2f | %.2f | %s |" % (
+                    kernel, label, n, tot["SQ_WAIT_ANY"] / wc, tot["SQ_WAIT_INST_ANY"] / wc, tot["SQ_WAIT_INST_LDS"] / wc,
+                    tot["SQ_ACTIVE_INST_VALU"] / wc, tot["SQ_VALU_MFMA_BUSY_CYCLES"] / wc,
+                    "%.2f" % (tot["SQ_VALU_MFMA_BUSY_CYCLES"] / wc / ref) if ref else "n/a"))
+    return "\n".join(out) + "\n"
+
+
 def pmc_summary(fetch_path, write_path, kinds_path, kernel, workload, command):
     out = ["# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE: HBM traffic of %s on %s" % (kernel, workload), "",
            "commands (one counter per run): `%s`" % command, ""]
@@ -107,5 +158,7 @@ if __name__ == "__main__":
         sys.stdout.write(trace_summary(*sys.argv[2:7]))
     elif len(sys.argv) > 1 and sys.argv[1] == "pmc":
         sys.stdout.write(pmc_summary(*sys.argv[2:8]))
+    elif len(sys.argv) > 1 and sys.argv[1] == "sq":
+        sys.stdout.write(sq_summary(*sys.argv[2:6]))
     else:
         sys.exit(__doc__)
