@@ -2,11 +2,16 @@
  * blink.h - C ABI of the on-GPU serving step of Blink (CPU-free LLM serving).
  *
  * The library implements the backend of section 4.2 of the paper ("Backend: GPU-resident
- * inference engine") for one AMD MI355X: a request ring in HBM, a persistent on-GPU
- * scheduler (ring poll, FCFS continuous batching with inline prefill, paged-KV block
- * accounting, batch metadata), the prefill/decode forward pass of a Llama-style decoder
- * over paged KV, on-device sampling and token publication. After blink_init no host
- * decision is taken per iteration. The host side of this ABI stands in for the paper's
+ * inference engine") for one AMD MI355X: a request ring in HBM, an on-GPU scheduler step
+ * (ring poll, FCFS continuous batching with inline prefill, paged-KV block accounting,
+ * batch metadata), the prefill/decode forward pass of a Llama-style decoder over paged KV,
+ * on-device sampling and token publication. Every decision of an iteration is taken on the
+ * device from device state; the loop itself is a fixed kernel chain (one HIP graph per
+ * iteration) that a host thread only enqueues, a few iterations ahead, without reading any
+ * result the device waits for (HIP has no device-side launch, which the paper's persistent
+ * scheduler kernel relies on). While nothing is running the scheduler kernel polls the ring
+ * on the device for a bounded time, so a request that reaches an idle engine is claimed
+ * within microseconds. The host side of this ABI stands in for the paper's
  * SmartNIC frontend (section 4.4): blink_submit plays the RDMA datapath (payload first,
  * then the slot state), blink_poll_outputs plays the token reader (one bulk read of the
  * slot metadata, compare generation counts, fetch new tokens).
@@ -35,11 +40,10 @@ extern "C" {
 
 /* blink_config.flags */
 #define BLINK_FLAG_TRACE 1u          /* record one trace record per iteration (blink_get_trace) */
-#define BLINK_FLAG_EXIT_WHEN_IDLE 2u /* the loop stops by itself once nothing is running and nothing is pending */
-#define BLINK_FLAG_PERSISTENT 4u     /* reserved: one resident kernel running the whole loop behind grid barriers. Not
-                                        implemented (ignored): on MI355X a grid barrier costs 3-4x a kernel boundary.
-                                        The loop is a device-decided kernel chain that a host thread only pumps. */
+#define BLINK_FLAG_EXIT_WHEN_IDLE 2u /* the loop stops by itself once nothing is running and nothing is pending (initial
+                                        setting; blink_set_exit_when_idle changes it between windows) */
 #define BLINK_FLAG_KEEP_LOGITS 8u    /* keep the logits of the last iteration readable via blink_debug_read */
+#define BLINK_FLAG_NO_GRAPH 16u      /* enqueue the kernels of an iteration one by one instead of as one HIP graph */
 
 /* slot life cycle of the ring (section 4.2, "Ring buffer") */
 enum {
@@ -56,7 +60,10 @@ typedef struct blink_engine blink_engine;
 typedef struct {
   /* model: Llama-style decoder, no biases, untied LM head */
   uint32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
-  uint32_t dtype;              /* 0: fp32 weights and KV; 1: bf16 weights and KV (fp32 accumulation) */
+  uint32_t dtype;              /* 0: fp32 weights, activations and KV cache. 1: bf16 weights; what the engine computes and
+                                  stores itself (activations between the GEMMs, queries, KV cache, probabilities) is
+                                  IEEE half precision, 2 bytes like bf16 but with 11 significant bits, so that the logits
+                                  of a 32-layer model stay within 2e-2 of an exact evaluation; fp32 accumulation */
   float rms_eps;
   float rope_theta;
   const void* weights;         /* blob: embed[V][d]; per layer g1[d] wq[nq*hd][d] wk[nkv*hd][d] wv[nkv*hd][d]
@@ -74,7 +81,12 @@ typedef struct {
   int32_t device;              /* HIP device ordinal */
   uint32_t flags;              /* BLINK_FLAG_* */
   uint32_t trace_capacity;     /* trace records kept (0: 65536); older records are overwritten */
-  uint32_t idle_exit_us;       /* reserved for BLINK_FLAG_PERSISTENT; ignored */
+  uint32_t idle_poll_us;       /* how long the scheduler kernel of an idle iteration keeps polling the ring on the
+                                  device before it gives the iteration up (0: 2000). A request that arrives meanwhile
+                                  is admitted by that same kernel */
+  uint32_t pump_depth;         /* iterations the launcher thread keeps enqueued ahead of the device (0: 8; at most 1024) */
+  uint32_t tune;               /* tests and tuning: forces variants of the GEMM and attention kernels (0: automatic
+                                  choice; the bits are listed in csrc/mfma_gemm.h) */
 } blink_config;
 
 typedef struct {
@@ -141,7 +153,8 @@ enum {
 };
 
 /* Provisioning (section 4.1): allocates all device memory, uploads and re-tiles the weights, builds the
- * ring, the free list and the scheduler state. Nothing is allocated afterwards. */
+ * ring, the free list and the scheduler state. The serving path (submit, run, poll) allocates nothing
+ * afterwards; of the measurement helpers only blink_calibration_rates allocates (and frees) buffers of its own. */
 int blink_init(const blink_config* cfg, blink_engine** out);
 
 /* Ring write (section 4.4 "RDMA datapath"): copies the descriptor and the prompt into the slot of the next
@@ -153,8 +166,13 @@ int blink_submit(blink_engine* e, const int32_t* prompt, uint32_t n_prompt, uint
 /* Starts the serving loop (section 4.2 "Persistent scheduler") and returns at once. The loop ends after
  * max_iterations forward passes (0: unbounded), on blink_shutdown, or when idle if BLINK_FLAG_EXIT_WHEN_IDLE.
  * All state lives in device memory and survives the end of the loop: calling blink_run again continues
- * from the same logical point. BLINK_ERR_STATE if the loop is still active. */
+ * from the same logical point. BLINK_ERR_STATE if the loop is still active. Host work per iteration: one graph
+ * launch and one event record by the launcher thread, nothing else. */
 int blink_run(blink_engine* e, uint64_t max_iterations);
+
+/* Whether the loop ends by itself when it finds nothing running and nothing pending (on), or keeps polling the ring
+ * until blink_stop (off). Takes effect from the next blink_run; BLINK_ERR_STATE while the loop is active. */
+int blink_set_exit_when_idle(blink_engine* e, uint32_t on);
 
 /* Blocks until the loop started by blink_run has ended. Returns BLINK_ERR_DEVICE if it ended on an error. */
 int blink_wait(blink_engine* e);
@@ -172,6 +190,8 @@ int blink_stop(blink_engine* e);
 int blink_shutdown(blink_engine* e);
 
 /* Measurement and test helpers. */
+/* The most recent min(cap_records, records kept) trace records, oldest of them first (needs BLINK_FLAG_TRACE; the loop
+ * must be stopped). */
 int blink_get_trace(blink_engine* e, blink_trace_record* buf, uint64_t cap_records, uint64_t* n_out);
 int blink_get_stats(blink_engine* e, blink_stats* out);
 int blink_debug_read(blink_engine* e, uint32_t what, void* buf, uint64_t cap_bytes, uint64_t* n_bytes);
@@ -192,6 +212,19 @@ int blink_calibration_copy(blink_engine* e, uint64_t bytes);
  * products on every compute unit (TFLOP/s). Both are written to host memory; the best of three timed runs counts.
  * Context for the roofline report: what the GEMM and attention kernels could reach at most. The loop must be stopped. */
 int blink_calibration_rates(blink_engine* e, double* copy_gbs, double* mfma_bf16_tflops);
+/* Relates the device clock of blink_event.device_ns and of the trace to the host's monotonic clock (CLOCK_MONOTONIC,
+ * nanoseconds): a one-thread kernel on a side stream writes the device clock to pinned host memory while the host
+ * reads its own clock before the launch and after the value arrives. Of eight such probes the one with the shortest
+ * span is returned: device_ns was read no later than host_ns and no earlier than host_ns - uncertainty_ns. May be
+ * called while the loop runs. */
+int blink_clock_sync(blink_engine* e, uint64_t* device_ns, uint64_t* host_ns, uint64_t* uncertainty_ns);
+/* The sampler of the serving step on its own (section 4.2: temperature / top-k / top-p sampling inside the step), for
+ * tests and for callers that bring their own logits: row r of logits[n_rows][vocab] (host memory, fp32) is sampled with
+ * params[r]; token_index[r] is the index of the output token (the Philox counter). tokens_out[n_rows] (host). Needs no
+ * engine: allocates device staging for the rows on `device`, runs the sampler kernel of the loop on the default
+ * stream, copies the tokens back and frees the staging. BLINK_ERR_INVAL on a bad parameter (as blink_submit). */
+int blink_sample_rows(int32_t device, const float* logits, uint32_t n_rows, uint32_t vocab, const blink_sampling* params,
+                      const uint32_t* token_index, int32_t* tokens_out);
 /* Message of the last error on the calling thread ("" if none). The pointer stays valid until the next call. */
 const char* blink_last_error(void);
 

@@ -6,13 +6,13 @@ import numpy as np
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 
-FLAG_TRACE, FLAG_EXIT_WHEN_IDLE, FLAG_PERSISTENT, FLAG_KEEP_LOGITS = 1, 2, 4, 8
+FLAG_TRACE, FLAG_EXIT_WHEN_IDLE, FLAG_KEEP_LOGITS, FLAG_NO_GRAPH = 1, 2, 8, 16
 ERR_INVAL, ERR_TOO_LARGE, ERR_FULL, ERR_DEVICE, ERR_STATE = -1, -2, -3, -4, -5
 EVENT_FIRST, EVENT_LAST = 1, 2
 
-EXPORTS = ["blink_init", "blink_submit", "blink_run", "blink_wait", "blink_stop", "blink_poll_outputs", "blink_shutdown",
+EXPORTS = ["blink_init", "blink_submit", "blink_run", "blink_set_exit_when_idle", "blink_wait", "blink_stop", "blink_poll_outputs", "blink_shutdown",
            "blink_get_trace", "blink_get_stats", "blink_debug_read", "blink_time_phase", "blink_get_phase_times", "blink_calibration_copy",
-           "blink_calibration_rates", "blink_last_error"]
+           "blink_calibration_rates", "blink_clock_sync", "blink_sample_rows", "blink_last_error"]
 
 
 class DBG:
@@ -25,7 +25,8 @@ class Config(C.Structure):
         ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("weights", C.c_void_p), ("weights_bytes", C.c_uint64),
         ("kv_block_size", C.c_uint32), ("kv_num_blocks", C.c_uint32), ("max_batch", C.c_uint32), ("max_seq_len", C.c_uint32),
         ("max_prefill_tokens", C.c_uint32), ("ring_slots", C.c_uint32), ("eos_token_id", C.c_int32), ("device", C.c_int32),
-        ("flags", C.c_uint32), ("trace_capacity", C.c_uint32), ("idle_exit_us", C.c_uint32)]
+        ("flags", C.c_uint32), ("trace_capacity", C.c_uint32), ("idle_poll_us", C.c_uint32), ("pump_depth", C.c_uint32),
+        ("tune", C.c_uint32)]
 
 
 class Sampling(C.Structure):
@@ -75,6 +76,7 @@ def load_library():
     lib.blink_submit.argtypes = [vp, vp, u32, u32, C.POINTER(Sampling), C.POINTER(u64)]
     lib.blink_run.argtypes = [vp, u64]
     lib.blink_wait.argtypes = [vp]
+    lib.blink_set_exit_when_idle.argtypes = [vp, u32]
     lib.blink_stop.argtypes = [vp]
     lib.blink_poll_outputs.argtypes = [vp, vp, u32, C.POINTER(u32)]
     lib.blink_shutdown.argtypes = [vp]
@@ -85,6 +87,8 @@ def load_library():
     lib.blink_calibration_copy.argtypes = [vp, u64]
     lib.blink_calibration_rates.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.blink_get_phase_times.argtypes = [vp, vp, u64, C.POINTER(u64)]
+    lib.blink_clock_sync.argtypes = [vp, C.POINTER(u64), C.POINTER(u64), C.POINTER(u64)]
+    lib.blink_sample_rows.argtypes = [C.c_int32, vp, u32, u32, vp, vp, vp]
     lib.blink_last_error.restype = C.c_char_p
     for n in EXPORTS[:-1]:
         getattr(lib, n).restype = C.c_int
@@ -97,10 +101,28 @@ def _check(lib, rc):
         raise BlinkError(rc, lib.blink_last_error().decode())
 
 
+def _sample_rows(fn_name, logits, params, token_index, device=0):
+    lib = load_library()
+    logits = np.ascontiguousarray(logits, dtype=np.float32)
+    n, v = logits.shape
+    ps = (Sampling * n)(*[Sampling(float(p["temperature"]), int(p["top_k"]), float(p["top_p"]), int(p["seed"]) & 0xFFFFFFFFFFFFFFFF) for p in params])
+    ti = np.ascontiguousarray(token_index, dtype=np.uint32)
+    assert ti.size == n
+    out = np.zeros(n, dtype=np.int32)
+    _check(lib, getattr(lib, fn_name)(int(device), logits.ctypes.data, n, v, C.cast(ps, C.c_void_p), ti.ctypes.data, out.ctypes.data))
+    return out
+
+
+def sample_rows(logits, params, token_index, device=0):
+    """blink_sample_rows: logits float32 [n][vocab], params: list of dicts (temperature, top_k, top_p, seed),
+    token_index: output index per row. Returns int32 [n]."""
+    return _sample_rows("blink_sample_rows", logits, params, token_index, device)
+
+
 class Engine:
     """One serving engine on one GPU. model/engine: dicts as in synth.configs; blob: uint8 array (synth.pack_blob)."""
 
-    def __init__(self, model, engine, blob, flags=0, device=0, trace_capacity=0, idle_exit_us=0):
+    def __init__(self, model, engine, blob, flags=0, device=0, trace_capacity=0, idle_poll_us=0, pump_depth=0, tune=0):
         self.lib = load_library()
         self.model, self.engine = dict(model), dict(engine)
         blob = np.ascontiguousarray(blob, dtype=np.uint8)
@@ -111,7 +133,8 @@ class Engine:
             setattr(cfg, k, engine[k])
         cfg.weights = blob.ctypes.data
         cfg.weights_bytes = blob.nbytes
-        cfg.device, cfg.flags, cfg.trace_capacity, cfg.idle_exit_us = device, flags, trace_capacity, idle_exit_us
+        cfg.device, cfg.flags, cfg.trace_capacity, cfg.idle_poll_us = device, flags, trace_capacity, idle_poll_us
+        cfg.pump_depth, cfg.tune = pump_depth, tune
         self.h = C.c_void_p()
         _check(self.lib, self.lib.blink_init(C.byref(cfg), C.byref(self.h)))
 
@@ -127,6 +150,9 @@ class Engine:
 
     def run(self, max_iterations=0):
         _check(self.lib, self.lib.blink_run(self.h, int(max_iterations)))
+
+    def set_exit_when_idle(self, on):
+        _check(self.lib, self.lib.blink_set_exit_when_idle(self.h, 1 if on else 0))
 
     def wait(self):
         _check(self.lib, self.lib.blink_wait(self.h))
@@ -183,6 +209,12 @@ class Engine:
         c, m = C.c_double(), C.c_double()
         _check(self.lib, self.lib.blink_calibration_rates(self.h, C.byref(c), C.byref(m)))
         return c.value, m.value
+
+    def clock_sync(self):
+        """(device_ns, host_ns on CLOCK_MONOTONIC, uncertainty_ns): the device clock read no later than host_ns."""
+        d, h, u = C.c_uint64(), C.c_uint64(), C.c_uint64()
+        _check(self.lib, self.lib.blink_clock_sync(self.h, C.byref(d), C.byref(h), C.byref(u)))
+        return d.value, h.value, u.value
 
     def phase_times_ms(self, cap=1 << 20):
         buf = np.zeros(cap, dtype=np.float32)

@@ -1,19 +1,25 @@
-// Paged attention of the bf16 path on the matrix cores.
+// Paged attention of a bf16 model on the matrix cores. Queries, the K/V cache and the probabilities are half precision
+// (what the engine computes and stores itself is half precision; only the weights are bf16 values), fp32 accumulation.
 //
 // Data layout (per layer):  K cache [block][kv head][16 tokens][hd]   (token-major: a tile is the A operand of QK^T)
 //                           V cache [block][kv head][hd][16 tokens]   (dimension-major: a tile is the B operand of PV)
-//                           q       [token][q head][hd] bf16, already rotated and scaled by 1/sqrt(hd)
+//                           q       [token][q head][hd] half, already rotated and scaled by 1/sqrt(hd)
 // One KV block (16 tokens of one kv head) is one contiguous 2-4 KB tile that a wave loads with 16-byte (K) and
-// 8-byte (V) lane loads. Scores are computed as S[token][column] = K_tile . q_column (v_mfma_f32_16x16x32_bf16),
+// 8-byte (V) lane loads. Scores are computed as S[token][column] = K_tile . q_column (v_mfma_f32_16x16x32_f16),
 // where a column is a q head of the GQA group (decode) or a query position of one head (prefill). The
 // accumulator layout of S (column = lane%16, tokens = 4*(lane/16)+i) is exactly the A-operand layout of
-// v_mfma_f32_16x16x16_bf16, so the probabilities feed O[column][dim] += P . V without leaving registers.
+// v_mfma_f32_16x16x16_f16, so the probabilities feed O[column][dim] += P . V without leaving registers.
 // Softmax is the online form (running maximum and sum per column), all in fp32.
 #pragma once
 #include "blink_device.h"
 #include "mfma_gemm.h"
 
-typedef short short4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ f16x8_t ld_tile(const f16_t* p) {   // one lane's 16 bytes of a half-precision tile (K cache, queries)
+  const uint4 v = *(const uint4*)p;
+  return *(const f16x8_t*)&v;
+}
 
 template <int HD, int CT>
 struct AttnAcc {
@@ -36,19 +42,19 @@ __device__ __forceinline__ void attn_init(AttnAcc<HD, CT>& a) {
 // lim[c]: number of visible keys (position + 1) for this lane's column of column-tile c.
 template <int HD>
 struct KVTile {
-  bf16x8_t ka[HD / 32];
-  short4_t vb[HD / 16];
+  f16x8_t ka[HD / 32];
+  f16x4_t vb[HD / 16];
 };
 
 template <int HD>
-__device__ __forceinline__ void kv_load(const bf16_t* Kt, const bf16_t* Vt, KVTile<HD>& r) {
+__device__ __forceinline__ void kv_load(const f16_t* Kt, const f16_t* Vt, KVTile<HD>& r) {
   const u32 lane = threadIdx.x & 63, lg = lane >> 4, lc = lane & 15;
 #pragma unroll
   for (int s = 0; s < HD / 32; ++s) r.ka[s] = ld_tile(Kt + lc * HD + s * 32 + lg * 8);
 #pragma unroll
   for (int d = 0; d < HD / 16; ++d) {
     const uint2 v = *(const uint2*)(Vt + (d * 16 + lc) * 16 + lg * 4);
-    r.vb[d] = *(const short4_t*)&v;
+    r.vb[d] = *(const f16x4_t*)&v;
   }
 }
 
@@ -69,19 +75,19 @@ __device__ __forceinline__ float quad_sum(float v) {
 }
 
 template <int HD, int CT>
-__device__ __forceinline__ void attn_block(const KVTile<HD>& kv, const bf16x8_t (&q)[CT][HD / 32], u32 j0,
+__device__ __forceinline__ void attn_block(const KVTile<HD>& kv, const f16x8_t (&q)[CT][HD / 32], u32 j0,
                                            const u32 (&lim)[CT], AttnAcc<HD, CT>& a) {
   const u32 lane = threadIdx.x & 63, lg = lane >> 4;
-  const bf16x8_t (&ka)[HD / 32] = kv.ka;
-  const short4_t (&vb)[HD / 16] = kv.vb;
+  const f16x8_t (&ka)[HD / 32] = kv.ka;
+  const f16x4_t (&vb)[HD / 16] = kv.vb;
 #pragma unroll
   for (int c = 0; c < CT; ++c) {
     // two independent accumulation chains (a product waits for the one before it in its chain)
     floatx4_t s4 = floatx4_t{0.f, 0.f, 0.f, 0.f}, s4b = floatx4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int s = 0; s < HD / 32; s += 2) {
-      s4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[s], q[c][s], s4, 0, 0, 0);
-      s4b = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[s + 1], q[c][s + 1], s4b, 0, 0, 0);
+      s4 = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[s], q[c][s], s4, 0, 0, 0);
+      s4b = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[s + 1], q[c][s + 1], s4b, 0, 0, 0);
     }
     s4 += s4b;
     float bm = -INFINITY;
@@ -105,18 +111,13 @@ __device__ __forceinline__ void attn_block(const KVTile<HD>& kv, const bf16x8_t 
     float c4[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) c4[i] = __shfl(corr, lg * 4 + i);
-    // probabilities to bf16: the hardware conversion (round to nearest even), two values per instruction
-    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-    typedef float floatx2_t __attribute__((ext_vector_type(2)));
-    union { bf16x2_t h[2]; short4_t v; } pk;
-    pk.h[0] = __builtin_convertvector(floatx2_t{p[0], p[1]}, bf16x2_t);
-    pk.h[1] = __builtin_convertvector(floatx2_t{p[2], p[3]}, bf16x2_t);
-    const short4_t pa = pk.v;
+    // probabilities (in [0, 1]) to half precision, round to nearest even
+    const f16x4_t pa = {(_Float16)p[0], (_Float16)p[1], (_Float16)p[2], (_Float16)p[3]};
 #pragma unroll
     for (int d = 0; d < HD / 16; ++d) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) a.o[c][d][i] *= c4[i];
-      a.o[c][d] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, vb[d], a.o[c][d], 0, 0, 0);
+      a.o[c][d] = __builtin_amdgcn_mfma_f32_16x16x16f16(pa, vb[d], a.o[c][d], 0, 0, 0);
     }
   }
 }
@@ -135,8 +136,8 @@ template <int HD>
 __device__ __forceinline__ void attn_decode(const DevCtx& c, u32 layer, AttnMfmaShared& sh, u32 wg, u32 nwg) {
   const u32 B = c.meta->n_seqs, G = c.nq / c.nkv;
   const u32 lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lg = lane >> 4, lc = lane & 15;   // w as a scalar: block-table reads become scalar loads
-  const bf16_t* Kc = (const bf16_t*)c.kv + (u64)layer * c.kv_layer_stride;
-  const bf16_t* Vc = Kc + c.kv_kv_stride;
+  const f16_t* Kc = (const f16_t*)c.kv + (u64)layer * c.kv_layer_stride;
+  const f16_t* Vc = Kc + c.kv_kv_stride;
   const u64 tile = (u64)16 * HD;
   // Work item: (chunk of ATTN_CHUNK_TOKENS of one sequence's context, kv head). Chunks balance the load between short and long
   // contexts and give the chip enough items at small batch. A context of one chunk is finished here; longer ones
@@ -159,7 +160,7 @@ __device__ __forceinline__ void attn_decode(const DevCtx& c, u32 layer, AttnMfma
   constexpr u32 nw = ATTN_WAVES;
   const u32 total_items = total_chunks * c.nkv;
   struct Item { u32 ci, g, nch, t, ctx, b_lo, nb; };
-  bf16x8_t q[1][HD / 32];
+  f16x8_t q[1][HD / 32];
   KVTile<HD> t0, t1, t2, t3;
   // describes the item and requests its queries and tiles (into q and t0..t3, which the previous item no longer needs)
   auto start = [&](u32 item) {
@@ -232,7 +233,7 @@ __device__ __forceinline__ void attn_decode(const DevCtx& c, u32 layer, AttnMfma
         O += sh.o[ww][h][dim] * f;
       }
       if (cur.nch == 1) {
-        c.aq[packed_off(cur.t, (cur.g * G + h) * HD + dim, c.TBS)] = f32_to_bf16(O / L);
+        c.aq[packed_off(cur.t, (cur.g * G + h) * HD + dim, c.TBS)] = f32_to_f16(O / L);
       } else {
         po[(u64)h * HD + dim] = O;
         if (dim == 0) { pml[h * 2] = M; pml[h * 2 + 1] = L; }
@@ -285,7 +286,7 @@ __device__ __forceinline__ void attn_decode_combine(const DevCtx& c, u32 wg, u32
           O += c.attn_part_o[(base + h) * HD + dim] * f;
         }
       }
-      c.aq[packed_off(t, (g * G + h) * HD + dim, c.TBS)] = f32_to_bf16(O / L);
+      c.aq[packed_off(t, (g * G + h) * HD + dim, c.TBS)] = f32_to_f16(O / L);
     }
   }
 }
@@ -298,8 +299,8 @@ template <int HD, int CT>
 __device__ __forceinline__ void attn_prefill(const DevCtx& c, u32 layer, AttnMfmaShared& sh, u32 wg, u32 nwg) {
   const u32 B = c.meta->n_seqs, G = c.nq / c.nkv, groups = G / CT;
   const u32 lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lg = lane >> 4, lc = lane & 15;   // w as a scalar: block-table reads become scalar loads
-  const bf16_t* Kc = (const bf16_t*)c.kv + (u64)layer * c.kv_layer_stride;
-  const bf16_t* Vc = Kc + c.kv_kv_stride;
+  const f16_t* Kc = (const f16_t*)c.kv + (u64)layer * c.kv_layer_stride;
+  const f16_t* Vc = Kc + c.kv_kv_stride;
   const u64 tile = (u64)16 * HD;
   const u32 per_tile = c.nkv * groups;
   const u32 nw = blockDim.x >> 6;
@@ -347,7 +348,7 @@ __device__ __forceinline__ void attn_prefill(const DevCtx& c, u32 layer, AttnMfm
     const bool colv = valid && p0 + lc < P;
     // queries of the tile (columns past the prompt's end repeat its last token: an unconditional load; they are
     // masked down to key 0 and never stored)
-    bf16x8_t q[CT][HD / 32];
+    f16x8_t q[CT][HD / 32];
     u32 lim[CT];
     const u32 qrow = t0 + min(p0 + lc, P - 1);
 #pragma unroll
@@ -397,7 +398,7 @@ __device__ __forceinline__ void attn_prefill(const DevCtx& c, u32 layer, AttnMfm
             if (p0 + r < P) {
 #pragma unroll
               for (int d = 0; d < HD / 16; ++d)
-                c.aq[packed_off(t0 + p0 + r, (g * G + hg * CT + ct) * HD + d * 16 + lc, c.TBS)] = f32_to_bf16(acc.o[ct][d][i] * inv[i]);
+                c.aq[packed_off(t0 + p0 + r, (g * G + hg * CT + ct) * HD + d * 16 + lc, c.TBS)] = f32_to_f16(acc.o[ct][d][i] * inv[i]);
             }
           }
         }
@@ -426,7 +427,7 @@ __device__ __forceinline__ void attn_prefill(const DevCtx& c, u32 layer, AttnMfm
               L += sh.l[w0 + ww][r] * f;
               O += sh.o[w0 + ww][r][dim] * f;
             }
-            c.aq[packed_off(t0 + p0 + r, (g * G + hg * CT + ct) * HD + dim, c.TBS)] = f32_to_bf16(O / L);
+            c.aq[packed_off(t0 + p0 + r, (g * G + hg * CT + ct) * HD + dim, c.TBS)] = f32_to_f16(O / L);
           }
         }
       }

@@ -79,7 +79,7 @@ __global__ void k_rope_table(float2* tab, u32 max_pos, u32 half, double theta) {
   tab[i] = make_float2((float)cos(ang), (float)sin(ang));
 }
 
-__global__ void __launch_bounds__(BLK_THREADS) k_pack_weights(const bf16_t* src, bf16_t* dst, u32 N, u32 K, u32 pair_rows, u32 perm_hd) {
+__global__ void __launch_bounds__(BLK_THREADS) k_pack_weights(const bf16_t* src, f16_t* dst, u32 N, u32 K, u32 pair_rows, u32 perm_hd) {
   pack_weights(src, dst, N, K, pair_rows, perm_hd, (u64)blockIdx.x * blockDim.x + threadIdx.x, (u64)gridDim.x * blockDim.x);
 }
 
@@ -106,6 +106,16 @@ __global__ void __launch_bounds__(BLK_THREADS) k_mfma_calibration(float* dst, u3
 #pragma unroll
   for (int i = 1; i < 16; ++i) s += acc[i];
   dst[(u64)blockIdx.x * blockDim.x + threadIdx.x] = s[0] + s[1] + s[2] + s[3];
+}
+
+__global__ void __launch_bounds__(BLK_THREADS) k_sample_rows(const float* logits, u32 n_rows, u32 V, const SampleRowParams* params, i32* tokens) {
+  __shared__ SamplerShared sh;
+  sample_rows(logits, n_rows, V, params, tokens, sh);
+}
+
+// the device clock, written to pinned host memory (blink_clock_sync)
+__global__ void k_clock_probe(HostMirror* m) {
+  __hip_atomic_store(&m->clock_probe, dev_now_ns(), __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
 __global__ void k_open_window(SchedState* ss, u64 iter_limit) {
@@ -281,26 +291,89 @@ static int init_impl(const blink_config* cfg, blink_engine* e) {
     HIPCHK(hipMemcpy(c.ss, &s0, sizeof s0, hipMemcpyHostToDevice));
   }
 
-  // ---- weights: the blob is uploaded as is; matrices are used in their [out][in] layout ----
-  char* wdev;
-  if (int rc = dalloc(e, &wdev, cfg->weights_bytes, false)) return rc;
-  HIPCHK(hipMemcpy(wdev, cfg->weights, cfg->weights_bytes, hipMemcpyHostToDevice));
-  e->weight_bytes = cfg->weights_bytes;
+  // ---- weights ----
+  // fp32 model: the blob is uploaded as is and the matrices are used in their [out][in] layout.
+  // bf16 model: the embedding table and the gains are kept as they come; every other matrix goes through a staging
+  // buffer into its packed form (MFMA operand order) and the row-major copy is not kept.
+  c.tune_nw = cfg->tune;
   {
     std::vector<LayerW> lw(c.n_layers);
-    u64 off = 0;
     const u64 d = c.d, hd = c.hd, nq = c.nq, nkv = c.nkv, F = c.F, V = c.V;
-    c.embed = wdev + off; off += es * V * d;
-    for (u32 l = 0; l < c.n_layers; ++l) {
-      lw[l].g1 = (const float*)(wdev + off); off += 4 * d;
-      lw[l].wqkv = wdev + off; off += es * (nq + 2 * nkv) * hd * d;
-      lw[l].wo = wdev + off; off += es * d * nq * hd;
-      lw[l].g2 = (const float*)(wdev + off); off += 4 * d;
-      lw[l].wgu = wdev + off; off += es * 2 * F * d;
-      lw[l].wd = wdev + off; off += es * d * F;
+    const char* hsrc = (const char*)cfg->weights;
+    u64 off = 0;
+    if (c.dtype == 0) {
+      char* wdev;
+      if (int rc = dalloc(e, &wdev, cfg->weights_bytes, false)) return rc;
+      HIPCHK(hipMemcpy(wdev, hsrc, cfg->weights_bytes, hipMemcpyHostToDevice));
+      e->weight_bytes = cfg->weights_bytes;
+      c.embed = wdev + off; off += es * V * d;
+      for (u32 l = 0; l < c.n_layers; ++l) {
+        lw[l].g1 = (const float*)(wdev + off); off += 4 * d;
+        lw[l].wqkv = wdev + off; off += es * (nq + 2 * nkv) * hd * d;
+        lw[l].wo = wdev + off; off += es * d * nq * hd;
+        lw[l].g2 = (const float*)(wdev + off); off += 4 * d;
+        lw[l].wgu = wdev + off; off += es * 2 * F * d;
+        lw[l].wd = wdev + off; off += es * d * F;
+      }
+      c.gf = (const float*)(wdev + off); off += 4 * d;
+      c.lm = wdev + off; off += es * V * d;
+    } else {
+      std::vector<LayerWP> lp(c.n_layers);
+      const u64 stage_bytes = 2 * std::max(std::max(V * d, 2 * F * d), std::max((nq + 2 * nkv) * hd * d, d * nq * hd));
+      char *stage = nullptr, *embed = nullptr;
+      float* gains = nullptr;
+      HIPCHK(hipMalloc((void**)&stage, stage_bytes));     // freed at the end of this block, on every path
+      auto pack = [&](u64 src_off, u32 N, u32 K, u32 pair_rows, u32 perm_hd, const f16_t** dst) -> int {
+        f16_t* p;
+        const u64 elems = (u64)((N + 15) / 16) * 16 * K;
+        if (int rc = dalloc(e, &p, elems, false)) return rc;
+        HIPCHK(hipMemcpy(stage, hsrc + src_off, (u64)N * K * 2, hipMemcpyHostToDevice));
+        hipLaunchKernelGGL(k_pack_weights, dim3(2048), dim3(BLK_THREADS), 0, e->compute, (const bf16_t*)stage, p, N, K, pair_rows, perm_hd);
+        HIPCHK(hipGetLastError());
+        HIPCHK(hipStreamSynchronize(e->compute));          // the staging buffer is reused by the next matrix
+        *dst = p;
+        e->weight_bytes += elems * 2;
+        return 0;
+      };
+      auto all = [&]() -> int {
+        if (int rc = dalloc(e, &embed, 2 * V * d, false)) return rc;
+        if (int rc = dalloc(e, &gains, (2 * (u64)c.n_layers + 1) * d, false)) return rc;
+        HIPCHK(hipMemcpy(embed, hsrc + off, 2 * V * d, hipMemcpyHostToDevice));
+        c.embed = embed; off += 2 * V * d;
+        e->weight_bytes = 2 * V * d + (2 * (u64)c.n_layers + 1) * d * 4;
+        for (u32 l = 0; l < c.n_layers; ++l) {
+          float* g1 = gains + (2 * (u64)l) * d;
+          float* g2 = g1 + d;
+          HIPCHK(hipMemcpy(g1, hsrc + off, 4 * d, hipMemcpyHostToDevice)); off += 4 * d;
+          if (int rc = pack(off, c.qkv_n, c.d, 0, c.hd, &lp[l].wqkv)) return rc;
+          off += 2 * (nq + 2 * nkv) * hd * d;
+          if (int rc = pack(off, c.d, c.nq * c.hd, 0, 0, &lp[l].wo)) return rc;
+          off += 2 * d * nq * hd;
+          HIPCHK(hipMemcpy(g2, hsrc + off, 4 * d, hipMemcpyHostToDevice)); off += 4 * d;
+          if (int rc = pack(off, 2 * c.F, c.d, c.F, 0, &lp[l].wgu)) return rc;
+          off += 2 * 2 * F * d;
+          if (int rc = pack(off, c.d, c.F, 0, 0, &lp[l].wd)) return rc;
+          off += 2 * d * F;
+          lw[l].g1 = g1; lw[l].g2 = g2; lw[l].wqkv = lw[l].wo = lw[l].wgu = lw[l].wd = nullptr;
+        }
+        float* gf = gains + 2 * (u64)c.n_layers * d;
+        HIPCHK(hipMemcpy(gf, hsrc + off, 4 * d, hipMemcpyHostToDevice)); off += 4 * d;
+        c.gf = gf;
+        if (int rc = pack(off, c.V, c.d, 0, 0, &c.lm_p)) return rc;
+        off += 2 * V * d;
+        c.lm = nullptr;
+        return 0;
+      };
+      const int rc = all();
+      const std::string keep = g_err;
+      (void)hipFree(stage);
+      g_err = keep;
+      if (rc) return rc;
+      LayerWP* dp;
+      if (int rc2 = dalloc(e, &dp, c.n_layers)) return rc2;
+      HIPCHK(hipMemcpy(dp, lp.data(), sizeof(LayerWP) * c.n_layers, hipMemcpyHostToDevice));
+      c.players = dp;
     }
-    c.gf = (const float*)(wdev + off); off += 4 * d;
-    c.lm = wdev + off; off += es * V * d;
     if (off != cfg->weights_bytes) return fail(BLINK_ERR_INVAL, "internal: weight layout %llu != %llu", (unsigned long long)off, (unsigned long long)cfg->weights_bytes);
     LayerW* dl;
     if (int rc = dalloc(e, &dl, c.n_layers)) return rc;
@@ -315,34 +388,9 @@ static int init_impl(const blink_config* cfg, blink_engine* e) {
     HIPCHK(hipGetLastError());
     c.rope_tab = tab;
   }
-  // ---- bf16 path: weights re-tiled into MFMA operand order, packed activation buffers ----
+  // ---- bf16 model: packed activation operands between the GEMMs, decode attention partials ----
   c.TBS = ((c.maxT + 255) / 256) * 16;   // whole 256-token workgroup tiles
-  c.tune_nw = getenv("BLINK_TUNE_NW") ? (u32)atoi(getenv("BLINK_TUNE_NW")) : 0u;
   if (c.dtype == 1) {
-    std::vector<LayerWP> lp(c.n_layers);
-    std::vector<LayerW> lw(c.n_layers);
-    HIPCHK(hipMemcpy(lw.data(), c.layers, sizeof(LayerW) * c.n_layers, hipMemcpyDeviceToHost));
-    auto pack = [&](const void* src, u32 N, u32 K, u32 pair_rows, u32 perm_hd, const bf16_t** dst) -> int {
-      bf16_t* p;
-      const u64 elems = (u64)((N + 15) / 16) * 16 * K;
-      if (int rc = dalloc(e, &p, elems, false)) return rc;
-      hipLaunchKernelGGL(k_pack_weights, dim3(2048), dim3(BLK_THREADS), 0, e->compute, (const bf16_t*)src, p, N, K, pair_rows, perm_hd);
-      HIPCHK(hipGetLastError());
-      *dst = p;
-      e->weight_bytes += elems * 2;
-      return 0;
-    };
-    for (u32 l = 0; l < c.n_layers; ++l) {
-      if (int rc = pack(lw[l].wqkv, c.qkv_n, c.d, 0, c.hd, &lp[l].wqkv)) return rc;
-      if (int rc = pack(lw[l].wo, c.d, c.nq * c.hd, 0, 0, &lp[l].wo)) return rc;
-      if (int rc = pack(lw[l].wgu, 2 * c.F, c.d, c.F, 0, &lp[l].wgu)) return rc;
-      if (int rc = pack(lw[l].wd, c.d, c.F, 0, 0, &lp[l].wd)) return rc;
-    }
-    if (int rc = pack(c.lm, c.V, c.d, 0, 0, &c.lm_p)) return rc;
-    LayerWP* dp;
-    if (int rc = dalloc(e, &dp, c.n_layers)) return rc;
-    HIPCHK(hipMemcpy(dp, lp.data(), sizeof(LayerWP) * c.n_layers, hipMemcpyHostToDevice));
-    c.players = dp;
     const u64 tile_tokens = (u64)c.TBS * 16;
     if (int rc = dalloc(e, &c.xq, tile_tokens * c.d)) return rc;
     if (int rc = dalloc(e, &c.aq, tile_tokens * c.nq * c.hd)) return rc;
@@ -376,10 +424,10 @@ static int init_impl(const blink_config* cfg, blink_engine* e) {
   if (int rc = dalloc(e, &c.logits, (u64)c.max_batch * c.V)) return rc;
   HIPCHK(hipStreamSynchronize(e->compute));
   HIPCHK(hipDeviceSynchronize());
+  c.idle_poll_ns = 1000ull * (cfg->idle_poll_us ? cfg->idle_poll_us : 2000u);
+  e->hctrl->exit_when_idle = (cfg->flags & BLINK_FLAG_EXIT_WHEN_IDLE) ? 1u : 0u;
   {
-    const char* dv = getenv("BLINK_PUMP_DEPTH");
-    u32 depth = dv ? (u32)atoi(dv) : 8u;
-    if (depth < 1) depth = 1;
+    u32 depth = cfg->pump_depth ? cfg->pump_depth : 8u;
     if (depth > 1024) depth = 1024;
     e->events.resize(depth);
     for (u32 i = 0; i < depth; ++i) HIPCHK(hipEventCreateWithFlags(&e->events[i], hipEventDisableTiming));
@@ -516,7 +564,7 @@ static int enqueue_iteration_kernels(blink_engine* e, hipStream_t st, u64 enq_in
 }
 
 static int build_graph(blink_engine* e) {
-  if (getenv("BLINK_NO_GRAPH")) return 0;
+  if (e->cfg.flags & BLINK_FLAG_NO_GRAPH) return 0;
   hipGraph_t g = nullptr;
   HIPCHK(hipStreamBeginCapture(e->compute, hipStreamCaptureModeThreadLocal));
   const int rc = enqueue_iteration_kernels(e, e->compute, ~0ull);
@@ -590,6 +638,15 @@ extern "C" int blink_run(blink_engine* e, uint64_t max_iterations) {
   e->windows.fetch_add(1);
   e->phase_ms.clear();
   e->launcher = std::thread(pump_loop, e);
+  return BLINK_OK;
+}
+
+extern "C" int blink_set_exit_when_idle(blink_engine* e, uint32_t on) {
+  g_err.clear();
+  if (!e) return fail(BLINK_ERR_INVAL, "null engine");
+  if (e->shut) return fail(BLINK_ERR_STATE, "engine is shut down");
+  if (e->loop_active.load(std::memory_order_acquire)) return fail(BLINK_ERR_STATE, "stop the loop first");
+  __atomic_store_n(&e->hctrl->exit_when_idle, on ? 1u : 0u, __ATOMIC_RELEASE);
   return BLINK_OK;
 }
 
@@ -688,6 +745,7 @@ extern "C" int blink_shutdown(blink_engine* e) {
   return BLINK_OK;
 }
 
+// the most recent min(cap_records, records kept) trace records, oldest of them first
 extern "C" int blink_get_trace(blink_engine* e, blink_trace_record* buf, uint64_t cap_records, uint64_t* n_out) {
   g_err.clear();
   if (!e || !n_out || (!buf && cap_records)) return fail(BLINK_ERR_INVAL, "null argument");
@@ -697,8 +755,7 @@ extern "C" int blink_get_trace(blink_engine* e, blink_trace_record* buf, uint64_
   const u64 iters = e->hmirror->iteration;
   const u64 have = std::min<u64>(iters, e->ctx.trace_cap);
   const u64 n = std::min<u64>(have, cap_records);
-  // oldest kept record first
-  const u64 first = iters - have;
+  const u64 first = iters - n;
   for (u64 i = 0; i < n; ++i) {
     const u64 idx = (first + i) % e->ctx.trace_cap;
     const u64 run = std::min<u64>(n - i, e->ctx.trace_cap - idx);
@@ -854,6 +911,86 @@ extern "C" int blink_calibration_rates(blink_engine* e, double* copy_gbs, double
   *copy_gbs = 2.0 * (double)(n16 * 16) / ((double)best_copy * 1e-3) / 1e9;   // bytes read + bytes written
   *mfma_bf16_tflops = (double)wgs * (BLK_THREADS / 64) * rounds * 16.0 * (2.0 * 16 * 16 * 32) / ((double)best_mfma * 1e-3) / 1e12;
   return BLINK_OK;
+}
+
+static u64 host_now_ns() {
+  return (u64)std::chrono::duration_cast<std::chrono::nanoseconds>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+
+extern "C" int blink_clock_sync(blink_engine* e, uint64_t* device_ns, uint64_t* host_ns, uint64_t* uncertainty_ns) {
+  g_err.clear();
+  if (!e || !device_ns || !host_ns || !uncertainty_ns) return fail(BLINK_ERR_INVAL, "null argument");
+  if (e->shut) return fail(BLINK_ERR_STATE, "engine is shut down");
+  std::lock_guard<std::mutex> lk(e->dev_mu);
+  HIPCHK(hipSetDevice(e->cfg.device));
+  u64 best_span = ~0ull;
+  for (int rep = 0; rep < 8; ++rep) {
+    __atomic_store_n(&e->hmirror->clock_probe, 0ull, __ATOMIC_RELEASE);
+    const u64 h0 = host_now_ns();
+    hipLaunchKernelGGL(k_clock_probe, dim3(1), dim3(1), 0, e->s_in, e->hmirror);   // not the compute stream: the loop may be running there
+    HIPCHK(hipGetLastError());
+    u64 dv = 0, h1 = h0;
+    while ((dv = __atomic_load_n(&e->hmirror->clock_probe, __ATOMIC_ACQUIRE)) == 0) {
+      h1 = host_now_ns();
+      if (h1 - h0 > 2000000000ull) return fail(BLINK_ERR_DEVICE, "the clock probe kernel did not run within 2 s");
+    }
+    h1 = host_now_ns();
+    HIPCHK(hipStreamSynchronize(e->s_in));
+    // the device read its clock somewhere between h0 and h1; the launch takes most of that span, so the read is
+    // placed at its end, and the whole span is reported as the uncertainty
+    if (h1 - h0 < best_span) { best_span = h1 - h0; *device_ns = dv; *host_ns = h1; *uncertainty_ns = h1 - h0; }
+  }
+  return BLINK_OK;
+}
+
+// ---- stand-alone sampler ------------------------------------------------------------------------------------
+static int sample_rows_check(const float* logits, uint32_t n_rows, uint32_t vocab, const blink_sampling* params,
+                             const uint32_t* token_index, int32_t* tokens_out) {
+  if (!logits || !params || !token_index || !tokens_out) return fail(BLINK_ERR_INVAL, "null argument");
+  if (n_rows == 0 || vocab == 0 || vocab >= (1u << 24)) return fail(BLINK_ERR_INVAL, "n_rows must be positive and vocab in [1, 2^24)");
+  for (u32 r = 0; r < n_rows; ++r) {
+    const blink_sampling& sp = params[r];
+    if (!(sp.temperature >= 0.f) || !(sp.top_p > 0.f && sp.top_p <= 1.f)) return fail(BLINK_ERR_INVAL, "row %u: temperature must be >= 0 and top_p in (0,1]", r);
+    if (sp.temperature > 0.f && (sp.top_k == 0 || sp.top_k > SAMPLER_MAX_K) && vocab > SAMPLER_MAX_K)
+      return fail(BLINK_ERR_INVAL, "row %u: sampling needs top_k in [1, %d] when vocab exceeds %d", r, SAMPLER_MAX_K, SAMPLER_MAX_K);
+  }
+  return BLINK_OK;
+}
+
+// copies the rows and their parameters to `dev` (laid out: logits, parameters, tokens), samples, copies the tokens back
+static int sample_rows_on(char* dev, hipStream_t st, const float* logits, uint32_t n_rows, uint32_t vocab, const blink_sampling* params,
+                          const uint32_t* token_index, int32_t* tokens_out) {
+  const u64 lbytes = (u64)n_rows * vocab * 4, lpad = (lbytes + 255) & ~255ull, pbytes = (u64)n_rows * sizeof(SampleRowParams), ppad = (pbytes + 255) & ~255ull;
+  std::vector<SampleRowParams> hp(n_rows);
+  for (u32 r = 0; r < n_rows; ++r) hp[r] = SampleRowParams{params[r].temperature, params[r].top_k, params[r].top_p, token_index[r], params[r].seed};
+  HIPCHK(hipMemcpyAsync(dev, logits, lbytes, hipMemcpyHostToDevice, st));
+  HIPCHK(hipMemcpyAsync(dev + lpad, hp.data(), pbytes, hipMemcpyHostToDevice, st));
+  hipLaunchKernelGGL(k_sample_rows, dim3(std::min<u32>(n_rows, 1024u)), dim3(BLK_THREADS), 0, st, (const float*)dev, n_rows, vocab,
+                     (const SampleRowParams*)(dev + lpad), (i32*)(dev + lpad + ppad));
+  HIPCHK(hipGetLastError());
+  HIPCHK(hipMemcpyAsync(tokens_out, dev + lpad + ppad, (u64)n_rows * 4, hipMemcpyDeviceToHost, st));
+  HIPCHK(hipStreamSynchronize(st));
+  return BLINK_OK;
+}
+static u64 sample_rows_bytes(uint32_t n_rows, uint32_t vocab) {
+  return (((u64)n_rows * vocab * 4 + 255) & ~255ull) + (((u64)n_rows * sizeof(SampleRowParams) + 255) & ~255ull) + (u64)n_rows * 4;
+}
+
+extern "C" int blink_sample_rows(int32_t device, const float* logits, uint32_t n_rows, uint32_t vocab, const blink_sampling* params,
+                                 const uint32_t* token_index, int32_t* tokens_out) {
+  g_err.clear();
+  if (int rc = sample_rows_check(logits, n_rows, vocab, params, token_index, tokens_out)) return rc;
+  int n_dev = 0;
+  if (hipGetDeviceCount(&n_dev) != hipSuccess || n_dev <= 0) return fail(BLINK_ERR_DEVICE, "no HIP device available");
+  if (device < 0 || device >= n_dev) return fail(BLINK_ERR_INVAL, "device %d out of range", device);
+  HIPCHK(hipSetDevice(device));
+  char* dev = nullptr;
+  HIPCHK(hipMalloc((void**)&dev, sample_rows_bytes(n_rows, vocab)));
+  const int rc = sample_rows_on(dev, nullptr, logits, n_rows, vocab, params, token_index, tokens_out);
+  const std::string keep = g_err;
+  (void)hipFree(dev);
+  g_err = keep;
+  return rc;
 }
 
 extern "C" const char* blink_last_error(void) { return g_err.c_str(); }

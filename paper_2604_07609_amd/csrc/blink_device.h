@@ -8,6 +8,7 @@ typedef uint32_t u32;
 typedef uint64_t u64;
 typedef int32_t i32;
 typedef uint16_t bf16_t;  // bf16 bit pattern
+typedef uint16_t f16_t;   // IEEE half-precision bit pattern
 
 #define BLK_THREADS 256
 #define ATTN_CHUNK_TOKENS 512    // context tokens per decode-attention work item (32 KV blocks)
@@ -106,12 +107,13 @@ struct HostMirror {
   u32 error;
   u32 n_running;
   u32 idle;
+  u64 clock_probe;      // device clock written by the clock probe kernel
 };
 
 // host -> device control words (pinned host memory, read by the scheduler with system-scope loads)
 struct HostCtrl {
-  u32 stop;             // blink_shutdown
-  u32 pad;
+  u32 stop;             // blink_stop / blink_shutdown
+  u32 exit_when_idle;   // the window ends by itself once nothing is running and nothing is pending (and idle polling is off)
 };
 
 struct LayerW {
@@ -123,11 +125,11 @@ struct LayerW {
   const void* wd;       // [d][F]
 };
 
-struct LayerWP {        // bf16 weights re-tiled into MFMA operand order (see mfma_gemm.h)
-  const bf16_t* wqkv;   // N = (nq+2nkv)*hd, K = d
-  const bf16_t* wo;     // N = d, K = nq*hd
-  const bf16_t* wgu;    // N = 2F (gate_j, up_j interleaved), K = d
-  const bf16_t* wd;     // N = d, K = F
+struct LayerWP {        // weights of a bf16 model re-tiled into MFMA operand order and re-encoded as scaled halves (see mfma_gemm.h)
+  const f16_t* wqkv;    // N = (nq+2nkv)*hd, K = d
+  const f16_t* wo;      // N = d, K = nq*hd
+  const f16_t* wgu;     // N = 2F (gate_j, up_j interleaved), K = d
+  const f16_t* wd;      // N = d, K = F
 };
 
 struct DevCtx {
@@ -138,6 +140,7 @@ struct DevCtx {
   u32 bs, n_blocks, max_batch, max_seq_len, max_prefill_tokens, ring_slots, max_blocks_per_seq, maxT;
   i32 eos;
   u32 flags, trace_cap, qkv_n;
+  u64 idle_poll_ns;     // how long the scheduler step of an empty engine polls the ring before it reports an idle iteration
   // ring
   SlotStatus* status;
   SlotDesc* desc;
@@ -182,11 +185,11 @@ struct DevCtx {
   float* logits;        // [max_batch][V]
   // bf16 path: packed weights and packed activation operands
   const LayerWP* players;
-  const bf16_t* lm_p;
-  bf16_t* xq;           // packed bf16(x * gain of the next RMSNorm), inner dimension d
-  bf16_t* aq;           // packed attention output, inner dimension nq*hd
-  bf16_t* qbuf;         // [maxT][nq][hd] rotated queries scaled by 1/sqrt(hd)
-  bf16_t* hq;           // packed silu(gate)*up, inner dimension F
+  const f16_t* lm_p;
+  f16_t* xq;            // packed half(x * gain of the next RMSNorm), inner dimension d
+  f16_t* aq;            // packed attention output (half), inner dimension nq*hd
+  f16_t* qbuf;          // [maxT][nq][hd] rotated queries scaled by 1/sqrt(hd), half precision like the KV cache they meet
+  f16_t* hq;            // packed half(silu(gate)*up), inner dimension F
   float* ssq;           // [token][d/16] partial sums of squares of the residual stream
   u32 TBS;              // token-block stride of the packed activation buffers
   u32 tune_nw;          // tuning knob of the streaming GEMM (0: automatic)
@@ -203,3 +206,11 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {  // round to nearest ev
   u += 0x7FFFu + ((u >> 16) & 1u);
   return (bf16_t)(u >> 16);
 }
+// two floats to half precision (round to nearest even), saturating at the largest finite half; low half = a
+__device__ __forceinline__ u32 pack_f16x2(float a, float b) {
+  typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+  const half2_t h = {(_Float16)__builtin_fminf(__builtin_fmaxf(a, -65504.f), 65504.f),
+                     (_Float16)__builtin_fminf(__builtin_fmaxf(b, -65504.f), 65504.f)};
+  return *(const u32*)&h;
+}
+__device__ __forceinline__ f16_t f32_to_f16(float a) { return (f16_t)(pack_f16x2(a, 0.f) & 0xFFFFu); }

@@ -97,7 +97,7 @@ __device__ __forceinline__ void phase_embed_packed(const DevCtx& c, u32 wg, u32 
       for (int j = 0; j < 4; ++j) {
         const float a = v[8 * h + 2 * j], b = v[8 * h + 2 * j + 1];
         ss += a * a + b * b;
-        w[j] = (u32)f32_to_bf16(a * g[k0 + 8 * h + 2 * j]) | ((u32)f32_to_bf16(b * g[k0 + 8 * h + 2 * j + 1]) << 16);
+        w[j] = pack_f16x2(a * g[k0 + 8 * h + 2 * j], b * g[k0 + 8 * h + 2 * j + 1]);
       }
       *(uint4*)(c.xq + packed_act_off(t, k0 + 8 * h, c.TBS)) = make_uint4(w[0], w[1], w[2], w[3]);
     }
@@ -310,7 +310,7 @@ __device__ __forceinline__ void phase_attention(const DevCtx& c, u32 layer, Attn
           if ((u32)h < G) {
             float a = 0.f;
             for (u32 pp = 0; pp < nparts; ++pp) a += sh.accred[pp][h][slot64];
-            if (PACKED_OUT) c.aq[packed_act_off(t, (g * G + h) * hd + dd, c.TBS)] = f32_to_bf16(a / l[h]);
+            if (PACKED_OUT) c.aq[packed_act_off(t, (g * G + h) * hd + dd, c.TBS)] = f32_to_f16(a / l[h]);
             else c.attn[(u64)t * (c.nq * hd) + (u64)(g * G + h) * hd + dd] = a / l[h];
           }
       }

@@ -1,34 +1,47 @@
-// bf16 GEMMs of the forward pass on the CDNA4 matrix cores (v_mfma_f32_16x16x32_bf16), the only dense
-// contractions of the serving step. Both operands live in HBM already in MFMA operand order, so that
-// every wave-wide load is one contiguous kilobyte and no LDS staging or transposition is needed:
+// GEMMs of the forward pass of a bf16 model on the CDNA4 matrix cores, the only dense contractions of the serving
+// step. The weights are stored in bf16 (8 significant bits); for the matrix cores they are re-encoded once, at init,
+// as IEEE half precision scaled by 2^8 (exact for every bf16 value of magnitude 2^-25 .. 255: a half holds 11
+// significant bits), and the activation operands between the GEMMs are carried in half precision too
+// (v_mfma_f32_16x16x32_f16, fp32 accumulation; same rate and the same bytes as the bf16 instruction). With bf16
+// activation operands the roundings between the GEMMs (unit roundoff 2^-8, about eight per layer) add up to 3e-2 of
+// the largest logit over 32 layers; half precision cuts each of them by eight. Activations saturate at the largest
+// finite half instead of overflowing. Both operands live in HBM already in MFMA operand order, so that every
+// wave-wide load is one contiguous kilobyte:
 //
 //   weights      Wp[n/16][k/32][lane][8]      lane = n%16 + 16*((k%32)/8), element = k%8   (packed once at init)
 //   activations  Xp[k/32][t/16][lane][8]      lane = t%16 + 16*((k%32)/8), element = k%8   (written packed by the
 //                                                                                  producing kernel's epilogue)
 //
-// out[t][n] = sum_k X[t][k] * W[n][k]. Two schedules, chosen from the token count of the iteration:
-//   stream (T <= 64, decode): one 16-row weight tile per workgroup, the four waves split K and keep many
-//     1 KB weight loads in flight (pure weight streaming, HBM bound); partial sums are reduced through LDS
-//     in a fixed order.
-//   tile (T > 64, prefill): 128 x 128 output tile per workgroup, 64 x 64 per wave (16 accumulator tiles).
+// out[t][n] = sum_k X[t][k] * W[n][k]. Three schedules, chosen per launch from the token count T of the iteration:
+//   stream (T <= 64, decode at small batch): a workgroup owns 1, 2 or 4 16-row weight tiles and all token blocks; its
+//     4 or 8 waves split K and keep two batches of 1 KB operand loads in flight each; weight loads are non-temporal;
+//     partial sums are reduced through LDS in a fixed order. HBM bound: the weight matrix once.
+//   stream over a 2-D grid (64 < T <= 256, projections with few rows): the same kernel with items of 4 weight tiles x
+//     64 tokens, dealt to the XCDs in runs so that the token groups of a row block share one L2.
+//   tiles through LDS (T > 64 otherwise): 128 rows x 64..256 tokens per workgroup, operand tiles fetched once per
+//     workgroup and k-step into one of two LDS buffers; the token width is chosen per launch (gemm_tile_pick).
 // Epilogues fuse what follows the GEMM in the model: RMSNorm scale of the *input* (a per-token scalar,
-// applied to the accumulator), residual add, SiLU-gating, and re-packing of the result as the next
-// GEMM's activation operand together with the partial sums of squares the next RMSNorm needs.
+// applied to the accumulator), residual add, SiLU-gating, rotary embedding and the KV-cache write, and re-packing of
+// the result as the next GEMM's activation operand together with the partial sums of squares the next RMSNorm needs.
 #pragma once
 #include "blink_device.h"
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
 typedef float floatx4_t __attribute__((ext_vector_type(4)));
 
+#define W_SCALE 256.0f            // packed weights hold W * 2^8 (keeps small weights in the normal range of a half)
+#define W_SCALE_INV (1.0f / 256.0f)
+
 #define EPI_SCALED_STORE 0   // out[t][n] = rstd[t] * acc                      (QKV projection, LM head)
-#define EPI_RESIDUAL 1       // x[t][n] += acc; emit packed bf16(x * g_next) and sum-of-squares partials
-#define EPI_SILU_GATE 2      // rows interleaved (gate_j, up_j): emit packed bf16(silu(r*g) * (r*u))
+#define EPI_RESIDUAL 1       // x[t][n] += acc; emit packed half(x * g_next) and sum-of-squares partials
+#define EPI_SILU_GATE 2      // rows interleaved (gate_j, up_j): emit packed half(silu(r*g) * (r*u))
 #define EPI_QKV_ROPE 3       // rows of every head interleaved (dim p, dim p+hd/2): rotary embedding, then q to the query
                              // buffer, k and v straight into the paged cache through the slot mapping
 
 struct MfmaGemmArgs {
-  const bf16_t* Wp;        // packed weights
-  const bf16_t* Xp;        // packed activations (K = inner dimension)
+  const f16_t* Wp;         // packed weights (half precision, scaled by W_SCALE)
+  const f16_t* Xp;         // packed activations (half precision; K = inner dimension)
   u32 N, K;                // logical output rows and inner dimension (K % 32 == 0)
   u32 T;                   // tokens (columns)
   u32 TBS;                 // token-block stride of every packed activation buffer
@@ -40,17 +53,17 @@ struct MfmaGemmArgs {
   // EPI_RESIDUAL
   float* x; u32 ldx;       // residual stream, updated in place
   const float* g_next;     // gain of the RMSNorm that consumes x next
-  bf16_t* Xp_next;         // packed bf16(x * g_next), inner dimension N
+  f16_t* Xp_next;          // packed half(x * g_next), inner dimension N
   float* ssq_out;          // [token][N/16]
   // EPI_SILU_GATE
-  bf16_t* Hp;              // packed activations with inner dimension N/2
+  f16_t* Hp;               // packed activations with inner dimension N/2
   // EPI_QKV_ROPE
   const i32* positions;
   const i32* slot_mapping;
   const float2* rope_tab;
-  bf16_t* qbuf;
-  bf16_t* Kc;              // this layer's K cache and V cache
-  bf16_t* Vc;
+  f16_t* qbuf;
+  f16_t* Kc;               // this layer's K cache and V cache (half precision)
+  f16_t* Vc;
   u32 nq, nkv, hd, bs;
   u32 tune_nw;             // tests and tuning. Low byte: 0 automatic choice of weight tiles per workgroup, 1/2/4 forced.
                            // Bit 9: tile schedule with direct loads instead of LDS staging (bit 8: its 256-token
@@ -74,19 +87,20 @@ __device__ __forceinline__ u64 packed_off(u32 t, u32 k, u32 TBS) {
   return ((u64)((k >> 5) * TBS + (t >> 4)) * 64 + (t & 15) + 16 * ((k & 31) >> 3)) * 8 + (k & 7);
 }
 
-__device__ __forceinline__ bf16x8_t as_bf16x8(uint4 v) { return *(const bf16x8_t*)&v; }
-__device__ __forceinline__ bf16x8_t ld_tile(const bf16_t* p) {   // one lane's 16 bytes of a packed tile
-  return as_bf16x8(*(const uint4*)p);
+__device__ __forceinline__ f16x8_t as_f16x8(uint4 v) { return *(const f16x8_t*)&v; }
+__device__ __forceinline__ f16x8_t ld_op(const f16_t* p) {   // one lane's 16 bytes of a packed tile
+  return as_f16x8(*(const uint4*)p);
 }
 
-// rstd of `count` (<= 256) tokens starting at column t0 into sh.rstd[off .. off + count). Sixteen lanes share a token:
+// rstd (times the inverse of the weight scale) of `count` (<= 256) tokens starting at column t0 into
+// sh.rstd[off .. off + count). Sixteen lanes share a token:
 // each reads every sixteenth 16-byte piece of the token's partial sums (256 contiguous bytes per token and load), up to
 // sixteen tokens' loads are in flight per lane, and a butterfly over the sixteen lanes finishes the sum.
 __device__ __forceinline__ void compute_rstd(const MfmaGemmArgs& a, u32 t0, u32 count, MfmaShared& sh, u32 off = 0) {
   const u32 tid = threadIdx.x;
   __syncthreads();   // the previous readers of sh.rstd are done
   if (a.ssq_in == nullptr) {
-    if (tid < count) sh.rstd[off + tid] = 1.0f;
+    if (tid < count) sh.rstd[off + tid] = W_SCALE_INV;
   } else if (tid < BLK_THREADS) {   // threads beyond the first 256 (8-wave launches) only join the barriers
     const u32 np = a.K / 16, l16 = tid & 15, grp = tid >> 4;
     const float* pp[16];
@@ -119,7 +133,7 @@ __device__ __forceinline__ void compute_rstd(const MfmaGemmArgs& a, u32 t0, u32 
       float v = s[it];
       v += __shfl_xor(v, 1); v += __shfl_xor(v, 2); v += __shfl_xor(v, 4); v += __shfl_xor(v, 8);
       const u32 tl = grp + 16 * it;
-      if (l16 == 0 && tl < count) sh.rstd[off + tl] = 1.0f / sqrtf(v / (float)a.K + a.eps);
+      if (l16 == 0 && tl < count) sh.rstd[off + tl] = W_SCALE_INV / sqrtf(v / (float)a.K + a.eps);
     }
   }
   __syncthreads();
@@ -148,12 +162,11 @@ __device__ __forceinline__ void epilogue_tile(const MfmaGemmArgs& a, floatx4_t a
     if (tv) {
       float* xp = a.x + (u64)t * a.ldx + n0;
       const float4 old = *(const float4*)xp;
-      v[0] = old.x + acc[0]; v[1] = old.y + acc[1]; v[2] = old.z + acc[2]; v[3] = old.w + acc[3];
+      v[0] = old.x + acc[0] * W_SCALE_INV; v[1] = old.y + acc[1] * W_SCALE_INV;
+      v[2] = old.z + acc[2] * W_SCALE_INV; v[3] = old.w + acc[3] * W_SCALE_INV;
       *(float4*)xp = make_float4(v[0], v[1], v[2], v[3]);
       const float4 g = *(const float4*)(a.g_next + n0);
-      const u32 lo = (u32)f32_to_bf16(v[0] * g.x) | ((u32)f32_to_bf16(v[1] * g.y) << 16);
-      const u32 hi = (u32)f32_to_bf16(v[2] * g.z) | ((u32)f32_to_bf16(v[3] * g.w) << 16);
-      *(uint2*)(a.Xp_next + packed_off(t, n0, a.TBS)) = make_uint2(lo, hi);
+      *(uint2*)(a.Xp_next + packed_off(t, n0, a.TBS)) = make_uint2(pack_f16x2(v[0] * g.x, v[1] * g.y), pack_f16x2(v[2] * g.z, v[3] * g.w));
     }
     float s = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
     s += __shfl_xor(s, 16);
@@ -172,21 +185,21 @@ __device__ __forceinline__ void epilogue_tile(const MfmaGemmArgs& a, floatx4_t a
     }
     if (head < a.nq) {
       const float sc = 1.0f / sqrtf((float)hd);
-      bf16_t* q = a.qbuf + ((u64)t * a.nq + head) * hd;
-      *(u32*)(q + p) = (u32)f32_to_bf16(lo0 * sc) | ((u32)f32_to_bf16(lo1 * sc) << 16);
-      *(u32*)(q + half + p) = (u32)f32_to_bf16(hi0 * sc) | ((u32)f32_to_bf16(hi1 * sc) << 16);
+      f16_t* q = a.qbuf + ((u64)t * a.nq + head) * hd;
+      *(u32*)(q + p) = pack_f16x2(lo0 * sc, lo1 * sc);
+      *(u32*)(q + half + p) = pack_f16x2(hi0 * sc, hi1 * sc);
     } else {
       const u32 slot = (u32)a.slot_mapping[t];
       if (head < a.nq + a.nkv) {
-        bf16_t* k = a.Kc + (((u64)(slot / a.bs) * a.nkv + (head - a.nq)) * a.bs + slot % a.bs) * hd;
-        *(u32*)(k + p) = (u32)f32_to_bf16(lo0) | ((u32)f32_to_bf16(lo1) << 16);
-        *(u32*)(k + half + p) = (u32)f32_to_bf16(hi0) | ((u32)f32_to_bf16(hi1) << 16);
+        f16_t* k = a.Kc + (((u64)(slot / a.bs) * a.nkv + (head - a.nq)) * a.bs + slot % a.bs) * hd;
+        *(u32*)(k + p) = pack_f16x2(lo0, lo1);
+        *(u32*)(k + half + p) = pack_f16x2(hi0, hi1);
       } else {   // V is kept dimension-major inside a block: [hd][16 tokens]
-        bf16_t* v = a.Vc + ((u64)(slot / a.bs) * a.nkv + (head - a.nq - a.nkv)) * a.bs * hd + slot % a.bs;
-        v[(u64)p * a.bs] = f32_to_bf16(lo0);
-        v[(u64)(p + 1) * a.bs] = f32_to_bf16(lo1);
-        v[(u64)(half + p) * a.bs] = f32_to_bf16(hi0);
-        v[(u64)(half + p + 1) * a.bs] = f32_to_bf16(hi1);
+        f16_t* v = a.Vc + ((u64)(slot / a.bs) * a.nkv + (head - a.nq - a.nkv)) * a.bs * hd + slot % a.bs;
+        v[(u64)p * a.bs] = f32_to_f16(lo0);
+        v[(u64)(p + 1) * a.bs] = f32_to_f16(lo1);
+        v[(u64)(half + p) * a.bs] = f32_to_f16(hi0);
+        v[(u64)(half + p + 1) * a.bs] = f32_to_f16(hi1);
       }
     }
   } else {  // EPI_SILU_GATE
@@ -195,17 +208,17 @@ __device__ __forceinline__ void epilogue_tile(const MfmaGemmArgs& a, floatx4_t a
     const float g0 = acc[0] * r, u0 = acc[1] * r, g1 = acc[2] * r, u1 = acc[3] * r;
     const float h0 = g0 / (1.f + __expf(-g0)) * u0, h1 = g1 / (1.f + __expf(-g1)) * u1;
     const u32 j = n0 >> 1;   // pair index = inner index of the next GEMM
-    *(u32*)(a.Hp + packed_off(t, j, a.TBS)) = (u32)f32_to_bf16(h0) | ((u32)f32_to_bf16(h1) << 16);
+    *(u32*)(a.Hp + packed_off(t, j, a.TBS)) = pack_f16x2(h0, h1);
   }
 }
 
 // ---- stream schedule: T <= 64 ------------------------------------------------------------------------------------
 // Weight loads bypass temporal caching: every weight byte is used once per launch, while the activation operand
 // is re-read by every workgroup and should stay in L2.
-__device__ __forceinline__ bf16x8_t ld_tile_stream(const bf16_t* p) {
+__device__ __forceinline__ f16x8_t ld_op_stream(const f16_t* p) {
   typedef u32 u32x4_t __attribute__((ext_vector_type(4)));
   const u32x4_t v = __builtin_nontemporal_load((const u32x4_t*)p);
-  return *(const bf16x8_t*)&v;
+  return *(const f16x8_t*)&v;
 }
 
 // Work item of a workgroup in the round that starts at item `base`. Workgroups are dealt to the eight XCDs round-robin
@@ -220,8 +233,8 @@ __device__ __forceinline__ u32 xcd_item(u32 base, u32 total, u32 wg, u32 nwg) {
 
 template <int U, int NW, int TW>
 struct StreamBuf {
-  bf16x8_t w[U][NW];
-  bf16x8_t x[U][TW];
+  f16x8_t w[U][NW];
+  f16x8_t x[U][TW];
 };
 
 // NW consecutive 16-row weight tiles per workgroup: every activation tile a wave loads is used for NW MFMAs, which
@@ -263,7 +276,7 @@ __device__ __forceinline__ void gemm_stream(const MfmaGemmArgs& a, MfmaShared& s
     xoff[tw] = ((tok >> 4) * 64 + (tok & 15) + 16 * (lane >> 4)) * 8;
   }
   const u64 xk_stride = (u64)a.TBS * 512;
-  const bf16x8_t zero = {0, 0, 0, 0, 0, 0, 0, 0};
+  const f16x8_t zero = {0, 0, 0, 0, 0, 0, 0, 0};
   auto issue = [&](StreamBuf<U, NW, TW>& b, u32 item, u32 kt0) {
     const u32 ng = item / TG;
     const bf16_t* xg = a.Xp + (u64)(item % TG) * (TW * 512);   // the item's token group: TW consecutive token blocks
@@ -275,10 +288,10 @@ __device__ __forceinline__ void gemm_stream(const MfmaGemmArgs& a, MfmaShared& s
       for (int i = 0; i < NW; ++i) {
         const u32 nt = min(ng * NW + i, NT - 1);           // a tile past the end is computed and dropped
         const bf16_t* wp = a.Wp + ((u64)nt * KT + kt) * 512 + lane * 8;
-        b.w[u][i] = ok ? (GRID2D ? ld_tile(wp) : ld_tile_stream(wp)) : zero;
+        b.w[u][i] = ok ? (GRID2D ? ld_op(wp) : ld_op_stream(wp)) : zero;
       }
 #pragma unroll
-      for (int tw = 0; tw < TW; ++tw) b.x[u][tw] = ok ? ld_tile(xg + (u64)kt * xk_stride + xoff[tw]) : zero;
+      for (int tw = 0; tw < TW; ++tw) b.x[u][tw] = ok ? ld_op(xg + (u64)kt * xk_stride + xoff[tw]) : zero;
     }
   };
   // Software pipeline over the flat sequence of (tile group, batch) steps of this workgroup: while one buffer is
@@ -304,7 +317,7 @@ __device__ __forceinline__ void gemm_stream(const MfmaGemmArgs& a, MfmaShared& s
         for (int i = 0; i < NW; ++i)
 #pragma unroll
           for (int tw = 0; tw < TW; ++tw)
-            acc[i][tw] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(use.w[u][i], use.x[u][tw], acc[i][tw], 0, 0, 0);
+            acc[i][tw] = __builtin_amdgcn_mfma_f32_16x16x32_f16(use.w[u][i], use.x[u][tw], acc[i][tw], 0, 0, 0);
     }
     if (!last) { ++b; return true; }
     // reduce the four K-quarters through LDS, one weight tile of the group at a time
@@ -375,14 +388,14 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& a, MfmaShared& sh,
 #pragma unroll
       for (int j = 0; j < 4; ++j) acc[i][j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
     // three k-steps of operand tiles in flight; the buffers rotate by code position (no register copies)
-    struct Step { bf16x8_t w[4], x[4]; };
+    struct Step { f16x8_t w[4], x[4]; };
     Step s0, s1, s2;
     auto ld = [&](Step& st, u32 kt) {
       if (kt < KT) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) st.w[i] = ld_tile(wp[i] + (u64)kt * 512);
+        for (int i = 0; i < 4; ++i) st.w[i] = ld_op(wp[i] + (u64)kt * 512);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) st.x[j] = ld_tile(a.Xp + (u64)kt * xk_stride + xoff[j]);
+        for (int j = 0; j < 4; ++j) st.x[j] = ld_op(a.Xp + (u64)kt * xk_stride + xoff[j]);
       }
     };
     auto mm = [&](const Step& st, u32 kt) {
@@ -390,7 +403,7 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& a, MfmaShared& sh,
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-          for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(st.w[i], st.x[j], acc[i][j], 0, 0, 0);
+          for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(st.w[i], st.x[j], acc[i][j], 0, 0, 0);
       }
     };
     ld(s0, 0); ld(s1, 1); ld(s2, 2);
@@ -495,9 +508,9 @@ __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared&
 #define TL_STORE(g, buf) { *(uint4*)(Lww + (buf) * TLB) = g##0; *(uint4*)(Lww + (buf) * TLB + 1024) = g##1;                      \
       *(uint4*)(Lwx + (buf) * TLB) = g##2; if (x2) *(uint4*)(Lwx + (buf) * TLB + 4096) = g##3;                             \
       if (x3) *(uint4*)(Lwx + (buf) * TLB + 8192) = g##4; }
-#define TL_RW(buf, i) as_bf16x8(*(const uint4*)(Lrw + (buf) * TLB + (i) * 1024))
-#define TL_RX(buf, j) as_bf16x8(*(const uint4*)(Lrx + (buf) * TLB + ((j) < TJ ? (j) : 0) * 1024))
-#define TL_MM(A, W, X) A = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W, X, A, 0, 0, 0);
+#define TL_RW(buf, i) as_f16x8(*(const uint4*)(Lrw + (buf) * TLB + (i) * 1024))
+#define TL_RX(buf, j) as_f16x8(*(const uint4*)(Lrx + (buf) * TLB + ((j) < TJ ? (j) : 0) * 1024))
+#define TL_MM(A, W, X) A = __builtin_amdgcn_mfma_f32_16x16x32_f16(W, X, A, 0, 0, 0);
 #define TL_ROW(i, o) TL_MM(acc[i][0], o.w##i, o.x0) TL_MM(acc[i][1], o.w##i, o.x1)                                         \
       if (TJ > 2) { TL_MM(acc[i][TJ > 2 ? 2 : 0], o.w##i, o.x2) } if (TJ > 3) { TL_MM(acc[i][TJ > 3 ? 3 : 0], o.w##i, o.x3) }            \
       if (TJ > 4) { TL_MM(acc[i][TJ > 4 ? 4 : 0], o.w##i, o.x4) TL_MM(acc[i][TJ > 4 ? 5 : 0], o.w##i, o.x5) }
@@ -513,7 +526,7 @@ __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared&
     n.w3 = TL_RW(rb, 3); TL_GLOAD(g, (k) + 4)                                                                             \
     TL_SB TL_ROW(2, o) TL_ROW(3, o) TL_SB                                                                                 \
     __syncthreads();
-    struct Ops { bf16x8_t w0, w1, w2, w3, x0, x1, x2, x3, x4, x5; };
+    struct Ops { f16x8_t w0, w1, w2, w3, x0, x1, x2, x3, x4, x5; };
     Ops oa, ob;
     TL_GLOAD(ga, 0) TL_GLOAD(gb, 1)             // in flight while the norm scales are computed
     for (u32 h = 0; h < per_item; ++h) {
@@ -613,9 +626,9 @@ __device__ __forceinline__ void gemm_tile_lds_pair(const MfmaGemmArgs& a, MfmaSh
       if (x2) g##2 = *(const uint4*)(gx1 + (u64)kc_ * xk_stride); if (x3) g##3 = *(const uint4*)(gx2 + (u64)kc_ * xk_stride); }
 #define TL_STORE(g, buf) { *(uint4*)(Lww + (buf) * LB) = g##0; *(uint4*)(Lwx + (buf) * LB) = g##1;                          \
       if (x2) *(uint4*)(Lwx + (buf) * LB + 8192) = g##2; if (x3) *(uint4*)(Lwx + (buf) * LB + 16384) = g##3; }
-#define TL_RW(buf, i) as_bf16x8(*(const uint4*)(Lrw + (buf) * LB + (i) * 1024))
-#define TL_RX(buf, j) as_bf16x8(*(const uint4*)(Lrx + (buf) * LB + ((j) < TJ ? (j) : 0) * 1024))
-#define TL_MM(A, W, X) A = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W, X, A, 0, 0, 0);
+#define TL_RW(buf, i) as_f16x8(*(const uint4*)(Lrw + (buf) * LB + (i) * 1024))
+#define TL_RX(buf, j) as_f16x8(*(const uint4*)(Lrx + (buf) * LB + ((j) < TJ ? (j) : 0) * 1024))
+#define TL_MM(A, W, X) A = __builtin_amdgcn_mfma_f32_16x16x32_f16(W, X, A, 0, 0, 0);
 #define TL_ROW(i, o) TL_MM(acc[i][0], o.w##i, o.x0) TL_MM(acc[i][1], o.w##i, o.x1)                                         \
       if (TJ > 2) { TL_MM(acc[i][TJ > 2 ? 2 : 0], o.w##i, o.x2) } if (TJ > 3) { TL_MM(acc[i][TJ > 3 ? 3 : 0], o.w##i, o.x3) }            \
       if (TJ > 4) { TL_MM(acc[i][TJ > 4 ? 4 : 0], o.w##i, o.x4) TL_MM(acc[i][TJ > 4 ? 5 : 0], o.w##i, o.x5) }
@@ -629,7 +642,7 @@ __device__ __forceinline__ void gemm_tile_lds_pair(const MfmaGemmArgs& a, MfmaSh
     n.w3 = TL_RW(rb, 3); TL_GLOAD(g, (k) + 4)                                                                             \
     TL_SB TL_ROW(2, o) TL_ROW(3, o) TL_SB                                                                                 \
     __syncthreads();
-    struct Ops { bf16x8_t w0, w1, w2, w3, x0, x1, x2, x3, x4, x5; };
+    struct Ops { f16x8_t w0, w1, w2, w3, x0, x1, x2, x3, x4, x5; };
     Ops oa, ob;
     TL_GLOAD(ga, 0) TL_GLOAD(gb, 1)             // in flight while the norm scales are computed
     // both tiles' tokens (at most 256 per call); its barriers: the LDS tiles are free
@@ -720,15 +733,15 @@ __device__ __forceinline__ void gemm_tile_lds_wide(const MfmaGemmArgs& a, MfmaSh
 #define TW_STORE(g, buf) { *(uint4*)(Lww + (buf) * LB) = g##0; *(uint4*)(Lww + (buf) * LB + 1024) = g##1;                   \
       *(uint4*)(Lwx + (buf) * LB) = g##2; *(uint4*)(Lwx + (buf) * LB + 4096) = g##3;                                       \
       *(uint4*)(Lwx + (buf) * LB + 8192) = g##4; *(uint4*)(Lwx + (buf) * LB + 12288) = g##5; }
-#define TW_RW(buf, i) as_bf16x8(*(const uint4*)(Lrw + (buf) * LB + (i) * 1024))
-#define TW_RX(buf, j) as_bf16x8(*(const uint4*)(Lrx + (buf) * LB + (j) * 1024))
-#define TW_MM(A, W, X) A = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W, X, A, 0, 0, 0);
+#define TW_RW(buf, i) as_f16x8(*(const uint4*)(Lrw + (buf) * LB + (i) * 1024))
+#define TW_RX(buf, j) as_f16x8(*(const uint4*)(Lrx + (buf) * LB + (j) * 1024))
+#define TW_MM(A, W, X) A = __builtin_amdgcn_mfma_f32_16x16x32_f16(W, X, A, 0, 0, 0);
 #define TW_COL(j, xx) TW_MM(acc[0][j], w0_, xx) TW_MM(acc[1][j], w1_, xx) TW_MM(acc[2][j], w2_, xx) TW_MM(acc[3][j], w3_, xx)
     // step k: operands from buffer rb; the staged data of step k+1 (in g) go to buffer wb; g then requests step k+3
 #define TW_STEP(g, k, rb, wb) {                                                                                         \
-      const bf16x8_t w0_ = TW_RW(rb, 0), w1_ = TW_RW(rb, 1), w2_ = TW_RW(rb, 2), w3_ = TW_RW(rb, 3);                       \
-      const bf16x8_t x0_ = TW_RX(rb, 0), x1_ = TW_RX(rb, 1), x2_ = TW_RX(rb, 2), x3_ = TW_RX(rb, 3);                       \
-      const bf16x8_t x4_ = TW_RX(rb, 4), x5_ = TW_RX(rb, 5), x6_ = TW_RX(rb, 6), x7_ = TW_RX(rb, 7);                       \
+      const f16x8_t w0_ = TW_RW(rb, 0), w1_ = TW_RW(rb, 1), w2_ = TW_RW(rb, 2), w3_ = TW_RW(rb, 3);                       \
+      const f16x8_t x0_ = TW_RX(rb, 0), x1_ = TW_RX(rb, 1), x2_ = TW_RX(rb, 2), x3_ = TW_RX(rb, 3);                       \
+      const f16x8_t x4_ = TW_RX(rb, 4), x5_ = TW_RX(rb, 5), x6_ = TW_RX(rb, 6), x7_ = TW_RX(rb, 7);                       \
       TW_STORE(g, wb) TW_GLOAD(g, (k) + 3)                                                                               \
       TW_COL(0, x0_) TW_COL(1, x1_) TW_COL(2, x2_) TW_COL(3, x3_) TW_COL(4, x4_) TW_COL(5, x5_) TW_COL(6, x6_) TW_COL(7, x7_) \
       __syncthreads(); }
@@ -852,10 +865,11 @@ __device__ __forceinline__ void gemm_mfma(const MfmaGemmArgs& a, MfmaShared& sh,
 }
 
 // ---- packing -----------------------------------------------------------------------------------------------------
-// Weights [N][K] row-major -> packed tiles. pair_rows > 0: the source holds `pair_rows` gate rows followed by
-// `pair_rows` up rows, and packed row 2j is gate_j, row 2j+1 is up_j. perm_hd > 0: rows are heads of perm_hd
-// dimensions each, re-ordered so that the two dimensions a rotary embedding pairs up are adjacent rows.
-__device__ __forceinline__ void pack_weights(const bf16_t* src, bf16_t* dst, u32 N, u32 K, u32 pair_rows, u32 perm_hd, u64 gtid,
+// Weights [N][K] row-major bf16 -> packed tiles of half precision, scaled by W_SCALE. pair_rows > 0: the source holds
+// `pair_rows` gate rows followed by `pair_rows` up rows, and packed row 2j is gate_j, row 2j+1 is up_j. perm_hd > 0:
+// rows are heads of perm_hd dimensions each, re-ordered so that the two dimensions a rotary embedding pairs up are
+// adjacent rows.
+__device__ __forceinline__ void pack_weights(const bf16_t* src, f16_t* dst, u32 N, u32 K, u32 pair_rows, u32 perm_hd, u64 gtid,
                                              u64 gthreads) {
   const u32 NT = (N + 15) / 16, KT = K / 32;
   const u64 chunks = (u64)NT * KT * 64;
@@ -871,7 +885,13 @@ __device__ __forceinline__ void pack_weights(const bf16_t* src, bf16_t* dst, u32
         const u32 pi = n % perm_hd;
         row = n - pi + ((pi & 1) ? perm_hd / 2 + (pi >> 1) : (pi >> 1));
       }
-      v = *(const uint4*)(src + (u64)row * K + k);
+      const uint4 b = *(const uint4*)(src + (u64)row * K + k);
+      const u32 w[4] = {b.x, b.y, b.z, b.w};
+      u32 o[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        o[j] = pack_f16x2(__uint_as_float(w[j] << 16) * W_SCALE, __uint_as_float(w[j] & 0xFFFF0000u) * W_SCALE);
+      v = make_uint4(o[0], o[1], o[2], o[3]);
     }
     *(uint4*)(dst + i * 8) = v;
   }

@@ -89,7 +89,7 @@ __device__ __forceinline__ void run_phase_bf16(const DevCtx& c, int ph, u32 laye
     case PH_QKV:
       a.Wp = P->wqkv; a.Xp = c.xq; a.N = c.qkv_n; a.K = c.d; a.ssq_in = c.ssq;
       a.positions = c.positions; a.slot_mapping = c.slot_mapping; a.rope_tab = c.rope_tab; a.qbuf = c.qbuf;
-      a.Kc = (bf16_t*)c.kv + (u64)layer * c.kv_layer_stride; a.Vc = a.Kc + c.kv_kv_stride;
+      a.Kc = (f16_t*)c.kv + (u64)layer * c.kv_layer_stride; a.Vc = a.Kc + c.kv_kv_stride;
       a.nq = c.nq; a.nkv = c.nkv; a.hd = c.hd; a.bs = c.bs;
       gemm_mfma<EPI_QKV_ROPE, true>(a, sh.mfma, wg, nwg);
       break;

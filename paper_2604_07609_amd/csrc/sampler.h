@@ -206,6 +206,81 @@ __device__ __forceinline__ u32 select_top_k(const float* row, u32 V, u32 k, Samp
   return npow;
 }
 
+// Next token of one logits row; all 256 threads of the workgroup take part and all return the token.
+// gen: index of the output token being sampled (the Philox counter).
+__device__ __forceinline__ i32 sample_row(const float* row, u32 V, float temperature, u32 top_k, float top_p, u64 seed, u32 gen,
+                                          SamplerShared& sh) {
+  const u32 tid = threadIdx.x;
+  if (temperature == 0.f) {
+    unsigned long long best = 0;
+    scan_row(row, V, [&](float val, u32 i) {
+      const unsigned long long key = ((unsigned long long)order_key(val) << 32) | (u32)~i;
+      best = key > best ? key : best;
+    });
+    best = block_max_u64(best, sh.red64);
+    return (i32)(~(u32)best);
+  }
+  u32 k = top_k == 0 || top_k > V ? V : top_k;
+  if (k > SAMPLER_MAX_K) k = SAMPLER_MAX_K;   // the entry points reject what does not fit; defensive clamp
+  const u32 npow = select_top_k(row, V, k, sh);   // sh.cand[0..k) = the k largest (logit, then lower id) in order
+  // softmax numerators of the kept candidates at temperature T, cumulative sums in candidate order
+  const float invT = 1.0f / temperature;
+  const float zmax = key_to_float((u32)(sh.cand[0] >> 32)) * invT;
+  const u32 per = (npow + BLK_THREADS - 1) / BLK_THREADS;   // consecutive candidates per thread
+  float local[SAMPLER_MAX_K / BLK_THREADS];
+  float run_sum = 0.f;
+#pragma unroll
+  for (u32 j = 0; j < SAMPLER_MAX_K / BLK_THREADS; ++j) {
+    const u32 i = tid * per + j;
+    float p = 0.f;
+    if (j < per && i < k) p = __expf(key_to_float((u32)(sh.cand[i] >> 32)) * invT - zmax);
+    run_sum += p;
+    local[j] = run_sum;
+  }
+  // exclusive scan of the per-thread sums (fixed order)
+  float inc = run_sum;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const float t = __shfl_up(inc, o);
+    if ((tid & 63u) >= (u32)o) inc += t;
+  }
+  __syncthreads();
+  if ((tid & 63u) == 63u) sh.redf[tid >> 6] = inc;
+  __syncthreads();
+  float base = inc - run_sum;
+  for (u32 w = 0; w < (tid >> 6); ++w) base += sh.redf[w];
+#pragma unroll
+  for (u32 j = 0; j < SAMPLER_MAX_K / BLK_THREADS; ++j) {
+    const u32 i = tid * per + j;
+    if (j < per && i < npow) sh.cum[i] = base + local[j];
+  }
+  __syncthreads();
+  if (tid == 0) {
+    const float total = sh.cum[k - 1];
+    const float thr = top_p * total;
+    // shortest prefix reaching top_p: binary search for the first cum >= thr
+    u32 lo = 0, hi = k - 1;
+    while (lo < hi) {
+      const u32 mid = (lo + hi) / 2;
+      if (sh.cum[mid] >= thr) hi = mid; else lo = mid + 1;
+    }
+    const u32 n_keep = lo + 1;
+    const u32 x0 = philox4x32_10_first(gen, 0u, 0u, 0u, (u32)seed, (u32)(seed >> 32));
+    const float u = (float)(x0 >> 8) * (1.0f / 16777216.0f);
+    const float target = u * sh.cum[n_keep - 1];
+    lo = 0; hi = n_keep - 1;
+    while (lo < hi) {   // first cum > target
+      const u32 mid = (lo + hi) / 2;
+      if (sh.cum[mid] > target) hi = mid; else lo = mid + 1;
+    }
+    sh.misc[3] = ~(u32)sh.cand[lo];
+  }
+  __syncthreads();
+  const i32 token = (i32)sh.misc[3];
+  __syncthreads();   // sh.misc is free for the next row
+  return token;
+}
+
 __device__ __forceinline__ void phase_sample_publish(const DevCtx& c, SamplerShared& sh, u32 wg, u32 nwg) {
   const IterMeta* meta = c.meta;
   const u32 n_seqs = meta->n_seqs, V = c.V, tid = threadIdx.x;
@@ -213,75 +288,7 @@ __device__ __forceinline__ void phase_sample_publish(const DevCtx& c, SamplerSha
   for (u32 s = wg; s < n_seqs; s += nwg) {
     const u32 b = c.seq_bslot[s];
     RunEntry& r = c.run[b];
-    const float* row = c.logits + (u64)s * V;
-    i32 token;
-    if (r.temperature == 0.f) {
-      unsigned long long best = 0;
-      scan_row(row, V, [&](float val, u32 i) {
-        const unsigned long long key = ((unsigned long long)order_key(val) << 32) | (u32)~i;
-        best = key > best ? key : best;
-      });
-      best = block_max_u64(best, sh.red64);
-      token = (i32)(~(u32)best);
-    } else {
-      u32 k = r.top_k == 0 || r.top_k > V ? V : r.top_k;
-      if (k > SAMPLER_MAX_K) k = SAMPLER_MAX_K;   // submit rejects what does not fit; defensive clamp
-      const u32 npow = select_top_k(row, V, k, sh);   // sh.cand[0..k) = the k largest (logit, then lower id) in order
-      // softmax numerators of the kept candidates at temperature T, cumulative sums in candidate order
-      const float invT = 1.0f / r.temperature;
-      const float zmax = key_to_float((u32)(sh.cand[0] >> 32)) * invT;
-      const u32 per = (npow + BLK_THREADS - 1) / BLK_THREADS;   // consecutive candidates per thread
-      float local[SAMPLER_MAX_K / BLK_THREADS];
-      float run_sum = 0.f;
-#pragma unroll
-      for (u32 j = 0; j < SAMPLER_MAX_K / BLK_THREADS; ++j) {
-        const u32 i = tid * per + j;
-        float p = 0.f;
-        if (j < per && i < k) p = __expf(key_to_float((u32)(sh.cand[i] >> 32)) * invT - zmax);
-        run_sum += p;
-        local[j] = run_sum;
-      }
-      // exclusive scan of the per-thread sums (fixed order)
-      float inc = run_sum;
-#pragma unroll
-      for (int o = 1; o < 64; o <<= 1) {
-        const float t = __shfl_up(inc, o);
-        if ((tid & 63u) >= (u32)o) inc += t;
-      }
-      __syncthreads();
-      if ((tid & 63u) == 63u) sh.redf[tid >> 6] = inc;
-      __syncthreads();
-      float base = inc - run_sum;
-      for (u32 w = 0; w < (tid >> 6); ++w) base += sh.redf[w];
-#pragma unroll
-      for (u32 j = 0; j < SAMPLER_MAX_K / BLK_THREADS; ++j) {
-        const u32 i = tid * per + j;
-        if (j < per && i < npow) sh.cum[i] = base + local[j];
-      }
-      __syncthreads();
-      if (tid == 0) {
-        const float total = sh.cum[k - 1];
-        const float thr = r.top_p * total;
-        // shortest prefix reaching top_p: binary search for the first cum >= thr
-        u32 lo = 0, hi = k - 1;
-        while (lo < hi) {
-          const u32 mid = (lo + hi) / 2;
-          if (sh.cum[mid] >= thr) hi = mid; else lo = mid + 1;
-        }
-        const u32 n_keep = lo + 1;
-        const u32 x0 = philox4x32_10_first(r.gen, 0u, 0u, 0u, (u32)r.seed, (u32)(r.seed >> 32));
-        const float u = (float)(x0 >> 8) * (1.0f / 16777216.0f);
-        const float target = u * sh.cum[n_keep - 1];
-        lo = 0; hi = n_keep - 1;
-        while (lo < hi) {   // first cum > target
-          const u32 mid = (lo + hi) / 2;
-          if (sh.cum[mid] > target) hi = mid; else lo = mid + 1;
-        }
-        sh.misc[3] = ~(u32)sh.cand[lo];
-      }
-      __syncthreads();
-      token = (i32)sh.misc[3];
-    }
+    const i32 token = sample_row(c.logits + (u64)s * V, V, r.temperature, r.top_k, r.top_p, r.seed, r.gen, sh);
     // ---- publish (section 4.2: tokens and status go back to the ring) ------------------------------------
     if (tid == 0) {
       const u32 idx = r.gen;
@@ -306,4 +313,21 @@ __device__ __forceinline__ void phase_sample_publish(const DevCtx& c, SamplerSha
     __syncthreads();
   }
   if (wg == 0 && tid == 0 && (c.flags & 1u)) c.trace[meta->trace_idx].t_publish_end = dev_now_ns();
+}
+
+// Stand-alone sampling of a batch of logits rows (no engine): one workgroup per row, grid-stride.
+struct SampleRowParams {   // 24 bytes, the layout of blink_sampling plus the output index
+  float temperature;
+  u32 top_k;
+  float top_p;
+  u32 token_index;
+  u64 seed;
+};
+__device__ __forceinline__ void sample_rows(const float* logits, u32 n_rows, u32 V, const SampleRowParams* params, i32* tokens,
+                                            SamplerShared& sh) {
+  for (u32 r = blockIdx.x; r < n_rows; r += gridDim.x) {
+    const SampleRowParams p = params[r];
+    const i32 token = sample_row(logits + (u64)r * V, V, p.temperature, p.top_k, p.top_p, p.seed, p.token_index, sh);
+    if (threadIdx.x == 0) tokens[r] = token;
+  }
 }

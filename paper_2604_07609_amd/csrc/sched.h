@@ -1,8 +1,11 @@
-// The scheduler step of the serving loop: one workgroup of 256 threads (section 4.2 of the paper:
-// "Persistent scheduler", "Parallel slot scanning", "Continuous batching with inline prefill").
+// The scheduler step of the serving loop: one workgroup of 256 threads, the first kernel of every iteration's
+// chain (section 4.2 of the paper: "Persistent scheduler", "Parallel slot scanning", "Continuous batching with
+// inline prefill"; the paper's scheduler is one resident kernel that launches graphs from the device, here it is
+// a kernel per iteration that a host thread enqueues ahead of time).
 // Per iteration: retire finished requests, poll the ring for the contiguous run of pending tickets,
 // admit FCFS under the batch-slot / block-reservation / prefill-token limits, allocate KV blocks from
 // the free stack by prefix-sum offsets (deterministic block ids), and build the batch metadata.
+// With nothing running and nothing pending it keeps polling the ring on the device for a bounded time.
 // Integer work only; all decisions are functions of device state, never of the host.
 #pragma once
 #include "blink_device.h"
@@ -24,7 +27,11 @@ struct SchedShared {
   u32 wave_part[8];
   u32 wave_part2[8];
   u32 free_list[SCHED_MAX_BATCH];
+  u32 seq_tok0[SCHED_MAX_BATCH];     // prefill metadata: first token, batch slot and ring slot of every sequence
+  u32 seq_bslot[SCHED_MAX_BATCH];
+  u32 seq_ring[SCHED_MAX_BATCH];
   u32 flag;
+  u32 exit_idle;
 };
 
 // Exclusive prefix sum over the 256 threads of the workgroup; total returned in `total`.
@@ -88,7 +95,6 @@ __device__ __forceinline__ void set_slot_state(SlotStatus* st, u32 state) {
 __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
   const u32 tid = threadIdx.x;
   SchedState* ss = c.ss;
-  const u64 t_begin = dev_now_ns();
 
   // ---- window gate -----------------------------------------------------------------------------------
   if (tid == 0) {
@@ -96,9 +102,26 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
     const u64 iter_limit = ss->iter_limit;
     if (iter_limit != 0 && ss->iteration >= iter_limit) stop = 1;
     if (__hip_atomic_load(&c.hctrl->stop, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_SYSTEM)) stop = 1;
+    // ---- idle poll: nothing is running, so only a new arrival can give this iteration work. One thread watches the
+    // slot of the next ticket (and the stop word) until the slot turns pending or the time allowed has passed; the
+    // wait is bounded by the device clock, so the kernel always ends.
+    const u32 exit_idle = __hip_atomic_load(&c.hctrl->exit_when_idle, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    sh.exit_idle = exit_idle;
+    if (!stop && ss->n_running == 0 && !exit_idle) {
+      const u64 t0 = dev_now_ns(), next = ss->next_ticket;
+      const u32 slot = (u32)(next & (u64)(c.ring_slots - 1));
+      for (;;) {
+        if (__hip_atomic_load(&c.status[slot].state, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_SYSTEM) == SLOT_PREFILL_PENDING &&
+            __hip_atomic_load(&c.desc[slot].ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) == next) break;
+        if (__hip_atomic_load(&c.hctrl->stop, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_SYSTEM)) { stop = 1; break; }
+        if (dev_now_ns() - t0 >= c.idle_poll_ns) break;
+        __builtin_amdgcn_s_sleep(16);
+      }
+    }
     sh.flag = stop;
   }
   __syncthreads();
+  const u64 t_begin = dev_now_ns();   // the scheduling time of the iteration is counted from the end of the idle poll
   if (sh.flag) {
     if (tid == 0) {
       ss->stopped = 1;
@@ -309,18 +332,44 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
       c.cu_chunks[n_seqs] = n_ch;
     }
     if (kind == KIND_PREFILL) {
-      // token-level metadata of the prompts: one sequence after the other, threads over its tokens
-      for (u32 s = 0; s < n_seqs; ++s) {
+      // token-level metadata of the prompts, threads over all tokens of the iteration: the per-sequence values a token
+      // needs are staged in LDS once, a token finds its sequence by binary search there, and four tokens per thread
+      // have their loads in flight together
+      for (u32 s = tid; s < n_seqs; s += BLK_THREADS) {
         const u32 b = c.seq_bslot[s];
-        const RunEntry& r = c.run[b];
-        const u32 toff = c.cu_seqlens[s];
-        const u32* bt = c.block_tables + (u64)b * mbs;
-        const i32* prompt = c.in_arena + (u64)r.ring_slot * c.max_seq_len;
-        for (u32 p = tid; p < r.P; p += BLK_THREADS) {
-          c.input_ids[toff + p] = __hip_atomic_load(&prompt[p], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-          c.positions[toff + p] = (i32)p;
-          c.slot_mapping[toff + p] = (i32)(bt[p / c.bs] * c.bs + p % c.bs);
-          c.tok_seq[toff + p] = s;
+        sh.seq_tok0[s] = c.cu_seqlens[s];
+        sh.seq_bslot[s] = b;
+        sh.seq_ring[s] = c.run[b].ring_slot;
+      }
+      __syncthreads();
+      for (u32 base = 0; base < n_tok; base += 4 * BLK_THREADS) {
+        u32 sq[4], pp[4], blk[4];
+        i32 id[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const u32 tk = min(base + u * BLK_THREADS + tid, n_tok - 1);
+          u32 lo = 0, hi = n_seqs;              // last s with seq_tok0[s] <= tk
+          while (hi - lo > 1) {
+            const u32 mid = (lo + hi) / 2;
+            if (sh.seq_tok0[mid] <= tk) lo = mid; else hi = mid;
+          }
+          sq[u] = lo;
+          pp[u] = tk - sh.seq_tok0[lo];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          blk[u] = c.block_tables[(u64)sh.seq_bslot[sq[u]] * mbs + pp[u] / c.bs];
+          id[u] = __hip_atomic_load(c.in_arena + (u64)sh.seq_ring[sq[u]] * c.max_seq_len + pp[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const u32 tk = base + u * BLK_THREADS + tid;
+          if (tk < n_tok) {
+            c.input_ids[tk] = id[u];
+            c.positions[tk] = (i32)pp[u];
+            c.slot_mapping[tk] = (i32)(blk[u] * c.bs + pp[u] % c.bs);
+            c.tok_seq[tk] = sq[u];
+          }
         }
       }
     }
@@ -372,7 +421,7 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
       }
     } else {
       if (ss->idle_since_ns == 0) ss->idle_since_ns = now;
-      if (c.flags & 2u) {            // exit when idle: nothing running, nothing pending
+      if (sh.exit_idle) {            // exit when idle: nothing running, nothing pending
         ss->stopped = 1;
         stopped = 1;
       }

@@ -23,13 +23,22 @@ MODEL_CONFIGS = {
                        vocab=13001, dtype=1, rms_eps=1e-5, rope_theta=10000.0),
     "mini_wide4": dict(n_layers=1, d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=64, d_ffn=12288,
                        vocab=24601, dtype=1, rms_eps=1e-5, rope_theta=10000.0),
+    # the Churn model's shape (multi-head attention: one q head per kv head) with two layers instead of eight
+    "mini_churn": dict(n_layers=2, d_model=1024, n_q_heads=16, n_kv_heads=16, head_dim=64, d_ffn=4096,
+                       vocab=32000, dtype=1, rms_eps=1e-5, rope_theta=10000.0),
+    # six and eight q heads per kv head
+    "mini_g6": dict(n_layers=2, d_model=384, n_q_heads=6, n_kv_heads=1, head_dim=128, d_ffn=640,
+                    vocab=1900, dtype=1, rms_eps=1e-5, rope_theta=10000.0),
+    "mini_g8": dict(n_layers=2, d_model=512, n_q_heads=16, n_kv_heads=2, head_dim=64, d_ffn=768,
+                    vocab=2100, dtype=1, rms_eps=1e-5, rope_theta=500000.0),
 }
 
-# kv_num_blocks == 0 means "derived from the workload" (churn: 60 % of peak demand)
+# churn: the pool is "60 % of peak demand" of its default request set (256 requests, seed 2001), a number written by
+# `python -m oracle.churn_pool` (a test keeps the two in step)
 ENGINE_CONFIGS = {
     "tiny": dict(kv_block_size=16, kv_num_blocks=256, max_batch=8, max_seq_len=128,
                  max_prefill_tokens=8192, ring_slots=64, eos_token_id=-1),
-    "churn": dict(kv_block_size=16, kv_num_blocks=0, max_batch=64, max_seq_len=2048 + 256,
+    "churn": dict(kv_block_size=16, kv_num_blocks=297, max_batch=64, max_seq_len=2048 + 256,
                   max_prefill_tokens=8192, ring_slots=512, eos_token_id=-1),
     "llama3_8b": dict(kv_block_size=16, kv_num_blocks=32768, max_batch=256, max_seq_len=4096 + 1024,
                       max_prefill_tokens=8192, ring_slots=2048, eos_token_id=-1),
@@ -43,6 +52,12 @@ ENGINE_CONFIGS = {
                        max_prefill_tokens=512, ring_slots=128, eos_token_id=-1),
     "mini_wide4": dict(kv_block_size=16, kv_num_blocks=400, max_batch=64, max_seq_len=160,
                        max_prefill_tokens=512, ring_slots=128, eos_token_id=-1),
+    "mini_churn": dict(kv_block_size=16, kv_num_blocks=160, max_batch=8, max_seq_len=1200,
+                       max_prefill_tokens=1536, ring_slots=32, eos_token_id=-1),
+    "mini_g6": dict(kv_block_size=16, kv_num_blocks=96, max_batch=6, max_seq_len=700,
+                    max_prefill_tokens=700, ring_slots=32, eos_token_id=-1),
+    "mini_g8": dict(kv_block_size=16, kv_num_blocks=96, max_batch=6, max_seq_len=700,
+                    max_prefill_tokens=700, ring_slots=32, eos_token_id=-1),
 }
 
 

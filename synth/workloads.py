@@ -64,31 +64,3 @@ def make_workload(name, vocab, seed, n_requests=None, rate=None):
                          prompt=rng.integers(0, vocab, int(plen[i])).astype(np.int32),
                          max_new_tokens=int(olen[i]), seed=splitmix64(seed, i), **samp))
     return reqs
-
-
-def blocks_needed(req, bs):
-    """Worst-case KV reservation of one request: every token but the last sampled one is cached."""
-    return max(1, -(-(len(req["prompt"]) + req["max_new_tokens"] - 1) // bs))
-
-
-def peak_block_demand(reqs, bs, step_s=2.0e-3, prefill_s_per_token=2.0e-5):
-    """Peak of the summed reservations if every request held its reservation from arrival for
-    prompt*prefill_s_per_token + output*step_s seconds (a fluid model with unlimited pool)."""
-    ev = []
-    for r in reqs:
-        need = blocks_needed(r, bs)
-        t0 = r["arrival_s"]
-        t1 = t0 + len(r["prompt"]) * prefill_s_per_token + r["max_new_tokens"] * step_s
-        ev.append((t0, need))
-        ev.append((t1, -need))
-    ev.sort(key=lambda e: (e[0], e[1]))
-    cur = peak = 0
-    for _, dlt in ev:
-        cur += dlt
-        peak = max(peak, cur)
-    return peak
-
-
-def churn_pool_blocks(reqs, bs=16):
-    """Churn pool: 60 % of the fluid-model peak demand, at least the largest single reservation."""
-    return int(max(-(-6 * peak_block_demand(reqs, bs) // 10), max(blocks_needed(r, bs) for r in reqs)))

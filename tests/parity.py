@@ -9,10 +9,10 @@ from oracle.scheduler import Scheduler
 from oracle.serve import run_schedule
 
 
-def run_engine(B, cfg, eng, blob, reqs, flags=0, window=0, poll_cap=4096):
+def run_engine(B, cfg, eng, blob, reqs, flags=0, window=0, poll_cap=4096, tune=0):
     """Submit everything, run to idle (optionally in windows of `window` iterations), return
     (events, trace, stats)."""
-    e = B.Engine(cfg, eng, blob, flags=flags | B.FLAG_TRACE | B.FLAG_EXIT_WHEN_IDLE)
+    e = B.Engine(cfg, eng, blob, flags=flags | B.FLAG_TRACE | B.FLAG_EXIT_WHEN_IDLE, tune=tune)
     try:
         for r in reqs:
             e.submit_request(r)
@@ -54,7 +54,7 @@ def check_against_oracle(cfg, W, eng, reqs, ev, trace, rtol, tails=None, tok_rto
     sched = Scheduler(eng["kv_num_blocks"], eng["kv_block_size"], eng["max_batch"], eng["max_prefill_tokens"],
                       eng["ring_slots"], eng.get("eos_token_id", -1))
     kv = M.PagedKV(cfg, eng["kv_num_blocks"], eng["kv_block_size"])
-    stats = dict(tokens=0, near_ties=0, plans=[])
+    stats = dict(tokens=0, near_ties=0, greedy_tokens=0, greedy_near_ties=0, sampled_tokens=0, sampled_undecided=0, plans=[])
 
     def token_fn(plan):
         logits = M.paged_forward(cfg, W, kv, plan.input_ids, plan.positions, plan.slot_mapping, plan.tok_seq,
@@ -71,17 +71,21 @@ def check_against_oracle(cfg, W, eng, reqs, ev, trace, rtol, tails=None, tok_rto
                 order = S.candidate_order(row)
                 margin = row[order[0]] - row[order[1]]
                 assert row[g] >= row[order[0]] - 2 * tol, (t, plan.gen_index[i], g, int(order[0]), margin, tol)
+                stats["greedy_tokens"] += 1
                 if margin > 2 * tol:
                     assert g == int(order[0]), (t, plan.gen_index[i], g, int(order[0]), margin, tol)
                 else:
                     stats["near_ties"] += 1
+                    stats["greedy_near_ties"] += 1
             else:
                 u = uniform_for_token(r["seed"], plan.gen_index[i])
                 d = S.sample_detail(row, r["temperature"], r["top_k"], r["top_p"], u)
+                stats["sampled_tokens"] += 1
                 if sampling_decisions_clear(row, r, d, tol):
                     assert g == d["token"], (t, plan.gen_index[i], g, d["token"])
                 else:
                     stats["near_ties"] += 1
+                    stats["sampled_undecided"] += 1
                     assert g in set(int(x) for x in S.candidate_order(row)[: d["n_topk"] + 1])
             out.append(g)
         return out
@@ -103,24 +107,25 @@ def check_against_oracle(cfg, W, eng, reqs, ev, trace, rtol, tails=None, tok_rto
 
 
 def sampling_decisions_clear(row, r, d, tol):
-    """True when no decision of the sampler is within the logit tolerance of flipping: the top-k and top-p
-    membership boundaries, the order of the chosen candidate and its neighbours, the top-p mass and the
-    position of the draw within the CDF."""
+    """True when logits that differ from `row` by at most tol per element must give the same token.
+
+    With such logits, two candidates can change places only if their logits are within 2 tol of each other. If the
+    chosen candidate is farther than that from both of its neighbours in the order (the next one counted even when the
+    top-k or top-p cut excludes it), the set of candidates ahead of it is the same on both sides, and so is the set
+    behind it up to members near the cuts, whose probabilities are then nearly equal. What is left is arithmetic: each
+    probability moves by a relative e^(2 tol / T) - 1 at most, so the top-p cut stays where it is when the cumulative
+    mass at the cut and just before it is farther than eps from top_p, and the draw stays in its bin when u * total is
+    farther than eps from both edges of the bin."""
     T = r["temperature"]
     order = S.candidate_order(row)
-    k, n = d["n_topk"], len(d["kept"])
+    n = len(d["kept"])
     idx = int(np.nonzero(d["kept"] == d["token"])[0][0])
     near = lambda i, j: abs(row[order[i]] - row[order[j]]) <= 2 * tol
-    if k < row.size and near(k - 1, k):
+    if (idx > 0 and near(idx - 1, idx)) or (idx + 1 < row.size and near(idx, idx + 1)):
         return False
-    if n < k and near(n - 1, n):
-        return False
-    if (idx > 0 and near(idx - 1, idx)) or (idx + 1 < n and near(idx, idx + 1)):
-        return False
-    # a logit error of tol changes each probability by a relative e^(2 tol/T) - 1 at most
     eps = np.expm1(2 * tol / T) * 1.5 + 2e-6
     cum = np.cumsum(d["probs"])
-    if abs(cum[n - 1] - r["top_p"]) <= eps or (n > 1 and abs(cum[n - 2] - r["top_p"]) <= eps):
+    if r["top_p"] < 1.0 and (abs(cum[n - 1] - r["top_p"]) <= eps or (n > 1 and abs(cum[n - 2] - r["top_p"]) <= eps)):
         return False
     lo = d["cdf"][idx - 1] if idx > 0 else -1.0
     if abs(d["cdf"][idx] - d["target"]) <= eps or abs(lo - d["target"]) <= eps:
@@ -128,17 +133,47 @@ def sampling_decisions_clear(row, r, d, tol):
     return True
 
 
-def stepwise_check(B, cfg, eng, raw, blob, reqs, rtol, max_iters=10000):
+def arithmetic_decided(d, top_p, eps=2e-5):
+    """For a sampler that sees the SAME logits as the oracle: candidates are ordered by exact values on both sides, so
+    only the fp32 arithmetic of the engine (exponentials, cumulative sums of up to 1024 terms) can move a decision. True
+    when the top-p cut and the bin of the draw are farther than eps from their boundaries."""
+    n = len(d["kept"])
+    cum = np.cumsum(d["probs"])
+    if top_p < 1.0 and (abs(cum[n - 1] - top_p) <= eps or (n > 1 and abs(cum[n - 2] - top_p) <= eps)):
+        return False          # (top_p = 1 keeps all k candidates on both sides whatever the rounding of the last sum)
+    idx = int(np.nonzero(d["kept"] == d["token"])[0][0])
+    lo = d["cdf"][idx - 1] if idx > 0 else -1.0
+    return abs(d["cdf"][idx] - d["target"]) > eps and abs(lo - d["target"]) > eps
+
+
+def token_matches_own_logits(row, r, gen_index, token):
+    """The engine's token against the oracle's sampler run on the engine's own logits row (float32, widened exactly).
+    Greedy: exact. Sampled: exact when arithmetic_decided, else the token must at least be a kept candidate or the next
+    one. Returns True when the comparison was exact."""
+    row = np.asarray(row, dtype=np.float64)
+    if r["temperature"] == 0.0:
+        assert token == S.greedy(row), (token, S.greedy(row))
+        return True
+    d = S.sample_detail(row, r["temperature"], r["top_k"], r["top_p"], uniform_for_token(r["seed"], gen_index))
+    if arithmetic_decided(d, r["top_p"]):
+        assert token == d["token"], (token, d["token"], gen_index)
+        return True
+    assert token in set(int(x) for x in S.candidate_order(row)[: len(d["kept"]) + 1])
+    return False
+
+
+def stepwise_check(B, cfg, eng, raw, blob, reqs, rtol, max_iters=10000, tune=0):
     """One iteration per blink_run call: batch metadata, block tables and free stack bit-exact against the
     oracle's scheduler; logits within rtol of the row maximum against the oracle's paged forward fed with
-    the engine's own token history. Returns the worst relative logit error."""
+    the engine's own token history; every token against the oracle's sampler run on the engine's own logits
+    (so sampling is checked exactly, apart from the logit tolerance). Returns the worst relative logit error."""
     W = M.Weights(cfg, raw)
     sched = Scheduler(eng["kv_num_blocks"], eng["kv_block_size"], eng["max_batch"], eng["max_prefill_tokens"],
                       eng["ring_slots"], eng.get("eos_token_id", -1))
     kv = M.PagedKV(cfg, eng["kv_num_blocks"], eng["kv_block_size"])
     for r in reqs:
         sched.submit(r["prompt"], r["max_new_tokens"])
-    e = B.Engine(cfg, eng, blob, flags=B.FLAG_TRACE | B.FLAG_EXIT_WHEN_IDLE | B.FLAG_KEEP_LOGITS)
+    e = B.Engine(cfg, eng, blob, flags=B.FLAG_TRACE | B.FLAG_EXIT_WHEN_IDLE | B.FLAG_KEEP_LOGITS, tune=tune)
     D = B.DBG
     worst = 0.0
     try:
@@ -172,6 +207,8 @@ def stepwise_check(B, cfg, eng, raw, blob, reqs, rtol, max_iters=10000):
             evs = e.drain()
             by_ticket = {int(x["request_id"]): int(x["token"]) for x in evs}
             assert sorted(by_ticket) == sorted(plan.tickets)
+            for i, t in enumerate(plan.tickets):
+                token_matches_own_logits(got[i], reqs[t], plan.gen_index[i], by_ticket[t])
             sched.commit(plan, [by_ticket[t] for t in plan.tickets])   # the engine's tokens are the history
         raise AssertionError("did not finish")
     finally:

@@ -25,10 +25,20 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, n), n
 
 
-def test_struct_sizes_match_header():
+def test_struct_sizes_match_header(tmp_path):
+    """The header compiled as plain C gives the sizes and field offsets the ctypes binding assumes."""
+    import subprocess
     from paper_2604_07609_amd import binding
-    assert ctypes.sizeof(binding.Config) == 104 and ctypes.sizeof(binding.Sampling) == 24 and ctypes.sizeof(binding.Stats) == 88
-    assert binding.EVENT_DTYPE.itemsize == 32 and binding.TRACE_DTYPE.itemsize == 80
+    src = tmp_path / "sizes.c"
+    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "blink.h"\nint main(void) { printf("%zu %zu %zu %zu %zu %zu %zu %zu\\n", '
+                   'sizeof(blink_config), sizeof(blink_sampling), sizeof(blink_stats), sizeof(blink_event), sizeof(blink_trace_record), '
+                   'offsetof(blink_config, weights), offsetof(blink_config, tune), offsetof(blink_sampling, seed)); return 0; }\n')
+    exe = tmp_path / "sizes"
+    subprocess.run(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), "-o", str(exe), str(src)], check=True)
+    got = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    assert got == [ctypes.sizeof(binding.Config), ctypes.sizeof(binding.Sampling), ctypes.sizeof(binding.Stats), binding.EVENT_DTYPE.itemsize,
+                   binding.TRACE_DTYPE.itemsize, binding.Config.weights.offset, binding.Config.tune.offset, binding.Sampling.seed.offset]
+    assert got[:5] == [112, 24, 88, 32, 80]
 
 
 def test_argument_errors_without_gpu():

@@ -9,6 +9,15 @@ from tests import parity
 
 pytestmark = pytest.mark.gpu
 
+# Token checks of bf16 models: a greedy token must be the oracle's argmax when the oracle's top-1 margin exceeds
+# 2 * TOK_RTOL * max|logit|, a sampled token the oracle's when no decision is that close. The bound on the logits
+# themselves stays the stated 2e-2; this one follows the logit error the kernels are measured at (below 1e-3 of the row
+# maximum for these models, printed by the stepwise tests), with head-room. The stepwise tests check every token exactly
+# against the oracle's sampler on the engine's own logits; here the logits are not available, so a token counts as
+# undecided when an error of TOK_RTOL could move it (for sampled tokens, whose candidates lie close together, that is
+# a large share whatever the kernels do, so only the greedy share is bounded tightly).
+TOK_RTOL = 2e-3
+
 
 def setup(name, seed, gain_jitter=0.1):
     cfg, eng = synth.model_config(name), synth.engine_config(name)
@@ -33,16 +42,16 @@ def test_bf16_gqa_end_to_end(lib, name, seed):
     ev, trace, st = parity.run_engine(lib, cfg, eng, blob, reqs)
     assert st["free_blocks"] == eng["kv_num_blocks"] and st["committed_blocks"] == 0 and st["n_running"] == 0
     assert len(ev) == sum(r["max_new_tokens"] for r in reqs)
-    res = parity.check_against_oracle(cfg, M.Weights(cfg, raw), eng, reqs, ev, trace, rtol=2e-2, tok_rtol=1e-2)
+    res = parity.check_against_oracle(cfg, M.Weights(cfg, raw), eng, reqs, ev, trace, rtol=2e-2, tok_rtol=TOK_RTOL)
     print(name, "tokens", res["tokens"], "near ties", res["near_ties"], "prefill iterations", st["prefill_iterations"])
     assert st["prefill_iterations"] >= 2          # the pool / batch limit forced queueing
-    assert res["near_ties"] < res["tokens"] // 2
+    assert res["near_ties"] <= res["tokens"] // 8
 
 
 @pytest.mark.parametrize("name,seed", [("mini_gqa", 41), ("mini_gqa128", 42)])
 def test_bf16_gqa_stepwise_logits(lib, name, seed):
     cfg, eng, raw, blob = setup(name, seed)
-    reqs = synth.make_workload("mini", cfg["vocab"], seed + 100, n_requests=9)
+    reqs = sampled(synth.make_workload("mini", cfg["vocab"], seed + 100, n_requests=9), seed)   # every other request samples
     worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2)
     print(name, "worst relative logit error", worst)
 
@@ -76,41 +85,41 @@ def test_bf16_wide_matrices(lib, name, max_batch, n_req):
 
 
 @pytest.mark.parametrize("max_batch,tune", [(100, 0), (200, 0), (250, 0x800), (150, 0x200), (250, 0x6800), (140, 0x6000), (250, 0x7000), (120, 0x7000)])
-def test_bf16_decode_batches_beyond_64(lib, max_batch, tune, monkeypatch):
+def test_bf16_decode_batches_beyond_64(lib, max_batch, tune):
     """Decode iterations of 65..256 tokens: the eight-wave projections run 64 x 64 streaming items over a
     (rows, token groups) grid (or, with bit 11 of the tuning word, the tile schedule), the gate/up projection the
     tile schedule, and the LM head the tile schedule through its token indirection (LDS-staged, or with bit 9
     direct-load tiles; 0x6000 forces 192-token tiles and 0x7000 the 256-token tile of the four-wave kernels, both of which the LM head
     reads through the indirection too)."""
-    monkeypatch.setenv("BLINK_TUNE_NW", str(tune))
+    tune_word = tune
     cfg, eng, raw, blob = setup("mini_wide2", 35)
     eng = dict(eng, max_batch=max_batch, kv_num_blocks=3 * max_batch + 64, ring_slots=512, max_prefill_tokens=2048)
     reqs = synth.make_workload("mini", cfg["vocab"], 535 + max_batch, n_requests=max_batch + 9)
     for r in reqs:
         r["max_new_tokens"] = min(r["max_new_tokens"], 3)
         r["prompt"] = r["prompt"][:20]
-    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2)
+    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2, tune=tune_word)
     print("max_batch", max_batch, "worst relative logit error", worst)
 
 
 @pytest.mark.parametrize("nw", [1, 2, 4])
-def test_bf16_forced_tiles_per_workgroup(lib, nw, monkeypatch):
+def test_bf16_forced_tiles_per_workgroup(lib, nw):
     """Every GEMM of the streaming schedule forced to 1, 2 or 4 weight tiles per workgroup (the automatic choice picks
     by matrix height, which the small test models never reach for the eight-wave kernels)."""
-    monkeypatch.setenv("BLINK_TUNE_NW", str(nw))
+    tune_word = nw
     cfg, eng, raw, blob = setup("mini_gqa", 43)          # qkv: 40 row tiles, vocab 2500: 157 tiles (odd: ragged groups)
     eng = dict(eng, max_batch=36, kv_num_blocks=300, max_prefill_tokens=60, ring_slots=64)
     reqs = synth.make_workload("mini", cfg["vocab"], 143, n_requests=40)
     for r in reqs:
         r["max_new_tokens"] = min(r["max_new_tokens"], 5)
         r["prompt"] = r["prompt"][:24]
-    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2)
+    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2, tune=tune_word)
     print("forced", nw, "tiles per workgroup: worst relative logit error", worst)
 
 
 @pytest.mark.parametrize("tune", [0, 0x400, 0x100400, 0x2000, 0x3000, 0x4000, 0x3400, 0x2400, 0x200, 0x300, 0x6000, 0x106000,
                                   0x200000, 0x7000])
-def test_bf16_large_prefill_iterations(lib, tune, monkeypatch):
+def test_bf16_large_prefill_iterations(lib, tune):
     """Prefill iterations of ~1000 tokens (nine 128-token tiles with a ragged last one, ragged last row block) through
     every variant of the tile schedule: LDS-staged tiles with the two halves of an eight-wave workgroup splitting K
     (the automatic choice at this size) or taking a tile each (with the weight tiles of the pair shared in LDS, or,
@@ -118,7 +127,7 @@ def test_bf16_large_prefill_iterations(lib, tune, monkeypatch):
     eight-wave kernels the pair of two of them, or with bit 20 fall back to 128 tokens; = 7: the four-wave kernels'
     256-token tile; bit 21: never wider than 128), and
     direct-load tiles with the 128- and the 256-token workgroup tile."""
-    monkeypatch.setenv("BLINK_TUNE_NW", str(tune))
+    tune_word = tune
     cfg, eng, raw, blob = setup("mini_wide4", 39)
     eng = dict(eng, max_batch=40, max_prefill_tokens=1100, kv_num_blocks=200)
     reqs = synth.make_workload("mini", cfg["vocab"], 139, n_requests=44)
@@ -126,7 +135,7 @@ def test_bf16_large_prefill_iterations(lib, tune, monkeypatch):
     for r in reqs:
         r["max_new_tokens"] = 3
         r["prompt"] = rng.integers(0, cfg["vocab"], int(rng.integers(20, 36))).astype(np.int32)
-    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2)
+    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2, tune=tune_word)
     print("large prefill: worst relative logit error", worst)
 
 
@@ -150,17 +159,17 @@ def test_bf16_long_contexts(lib, name, prompts):
 
 
 @pytest.mark.parametrize("name,wpi", [("mini_gqa128", 1), ("mini_gqa128", 2), ("mini_gqa", 4), ("mini_gqa128", 8), ("mini_gqa", 8)])
-def test_bf16_prefill_attention_waves_per_item(lib, name, wpi, monkeypatch):
+def test_bf16_prefill_attention_waves_per_item(lib, name, wpi):
     """Prefill attention with 1, 2, 4 and 8 waves sharing the KV blocks of a query tile (the automatic choice depends on
     the longest prompt and on the number of tiles): prompts of 7..1030 tokens in one prefill iteration, ragged tiles."""
-    monkeypatch.setenv("BLINK_TUNE_NW", str(wpi << 16))
+    tune_word = wpi << 16
     cfg, eng, raw, blob = setup(name, 41)
     prompts = [1030, 300, 7, 17, 160]
     eng = dict(eng, max_seq_len=1100, kv_num_blocks=140, max_prefill_tokens=2048, max_batch=5)
     rng = np.random.default_rng(15)
     reqs = [dict(arrival_s=0.0, prompt=rng.integers(0, cfg["vocab"], P).astype(np.int32), max_new_tokens=3,
                  temperature=0.0, top_k=0, top_p=1.0, seed=i) for i, P in enumerate(prompts)]
-    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2)
+    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2, tune=tune_word)
     print(name, "waves per item", wpi, "worst relative logit error", worst)
 
 
@@ -181,10 +190,9 @@ def test_sampled_requests(lib, name, seed):
     reqs = sampled(base, seed)
     ev, trace, st = parity.run_engine(lib, cfg, eng, blob, reqs)
     res = parity.check_against_oracle(cfg, M.Weights(cfg, raw), eng, reqs, ev, trace, rtol=2e-2 if cfg["dtype"] else 1e-4,
-                                      tok_rtol=1e-2 if cfg["dtype"] else 1e-5)
+                                      tok_rtol=TOK_RTOL if cfg["dtype"] else 1e-5)
     print(name, "sampled: tokens", res["tokens"], "undecided", res["near_ties"])
-    if cfg["dtype"] == 0:
-        assert res["near_ties"] < res["tokens"] // 5
+    assert res["greedy_near_ties"] <= max(2, res["greedy_tokens"] // 8) and res["sampled_undecided"] <= (3 * res["sampled_tokens"]) // 5
     # the same request gives the same stream whatever it is batched with: resubmit alone
     one = [reqs[0]]
     ev1, _, _ = parity.run_engine(lib, cfg, eng, blob, one)
@@ -303,3 +311,47 @@ def test_scheduler_stress_schedule_is_bit_exact(lib):
     print("sched stress: iterations", len(trace), "tokens", res["tokens"], "near ties", res["near_ties"])
     sched_us = (trace["t_sched_end_ns"] - trace["t_sched_begin_ns"]) / 1e3
     print("scheduler step us: median %.1f p99 %.1f" % (np.median(sched_us), np.percentile(sched_us, 99)))
+
+
+def _fixed_prompts(cfg, prompts, max_new, seed):
+    rng = np.random.default_rng(seed)
+    return [dict(arrival_s=0.0, prompt=rng.integers(0, cfg["vocab"], P).astype(np.int32), max_new_tokens=max_new,
+                 temperature=0.0, top_k=0, top_p=1.0, seed=i) for i, P in enumerate(prompts)]
+
+
+def test_churn_shape_mha_stepwise(lib):
+    """The Churn model's shape (d 1024, 16 x 64 multi-head attention: one q head per kv head, vocabulary 32000) with two
+    layers: every prefill and decode iteration against the oracle. Contexts on both sides of the 512-token boundary of
+    the decode attention's chunks (a 509-token prompt crosses it while decoding; 530 and 1040 start beyond it)."""
+    cfg, eng, raw, blob = setup("mini_churn", 45)
+    reqs = _fixed_prompts(cfg, [530, 509, 7, 1040, 17, 300], 6, 21)
+    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2)
+    print("churn shape (MHA): worst relative logit error", worst)
+
+
+def test_churn_shape_mha_end_to_end(lib):
+    """Same model, the mini request mix behind a pool that forces queueing: schedule bit-exact, tokens teacher-forced."""
+    cfg, eng, raw, blob = setup("mini_churn", 46)
+    eng = dict(eng, kv_num_blocks=24, max_batch=5)
+    reqs = synth.make_workload("mini", cfg["vocab"], 146, n_requests=12)
+    ev, trace, st = parity.run_engine(lib, cfg, eng, blob, reqs)
+    assert st["free_blocks"] == eng["kv_num_blocks"] and st["committed_blocks"] == 0 and st["n_running"] == 0
+    res = parity.check_against_oracle(cfg, M.Weights(cfg, raw), eng, reqs, ev, trace, rtol=2e-2, tok_rtol=TOK_RTOL)
+    print("churn shape end to end: tokens", res["tokens"], "near ties", res["near_ties"], "prefill iterations", st["prefill_iterations"])
+    assert st["prefill_iterations"] >= 3
+    assert res["near_ties"] <= res["tokens"] // 8
+
+
+@pytest.mark.parametrize("name", ["mini_g6", "mini_g8"])
+def test_gqa_groups_of_six_and_eight(lib, name):
+    """Six and eight q heads per kv head (the prefill kernel takes them three resp. two per pass, the decode kernel as
+    columns of one score tile): prompts of 1..600 tokens, so decode contexts span one and two chunks."""
+    cfg, eng, raw, blob = setup(name, 47)
+    reqs = _fixed_prompts(cfg, [600, 40, 17, 1, 130], 5, 23)
+    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2)
+    print(name, "worst relative logit error", worst)
+    reqs = synth.make_workload("mini", cfg["vocab"], 147, n_requests=10)
+    ev, trace, st = parity.run_engine(lib, cfg, eng, blob, reqs)
+    res = parity.check_against_oracle(cfg, M.Weights(cfg, raw), eng, reqs, ev, trace, rtol=2e-2, tok_rtol=TOK_RTOL)
+    print(name, "end to end: tokens", res["tokens"], "near ties", res["near_ties"])
+    assert res["near_ties"] <= res["tokens"] // 8

@@ -66,12 +66,14 @@ def test_arrivals_during_the_loop_replay_against_oracle(lib):
     assert st["free_blocks"] == eng["kv_num_blocks"] and st["n_running"] == 0
     tails = [int(t) for t in trace["tail"]]
     assert tails == sorted(tails) and tails[-1] <= len(reqs)
-    res = parity.check_against_oracle(cfg, M.Weights(cfg, raw), eng, reqs, ev, trace, rtol=2e-2, tails=tails, tok_rtol=1e-2)
+    res = parity.check_against_oracle(cfg, M.Weights(cfg, raw), eng, reqs, ev, trace, rtol=2e-2, tails=tails, tok_rtol=2e-3)
     # per request: consecutive indices, device timestamps increasing
     for t in range(len(reqs)):
         mine = ev[ev["request_id"] == t]
         assert list(mine["index"]) == list(range(reqs[t]["max_new_tokens"]))
         assert np.all(np.diff(mine["device_ns"].astype(np.int64)) > 0)
     print("real-time: iterations", len(trace), "distinct tails", len(set(tails)), "ring-full retries", full_hits[0],
-          "near ties", res["near_ties"])
+          "greedy near ties", res["greedy_near_ties"], "of", res["greedy_tokens"], "sampled undecided", res["sampled_undecided"], "of",
+          res["sampled_tokens"])
     assert len(set(tails)) > 3
+    assert res["greedy_near_ties"] <= max(2, res["greedy_tokens"] // 8) and res["sampled_undecided"] <= (3 * res["sampled_tokens"]) // 5

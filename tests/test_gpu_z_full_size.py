@@ -11,23 +11,26 @@ The oracle cannot run such a batch (one forward pass over the fp64 weights takes
   request's logits do not depend on what else is in the batch, so its rows of the engine's logits must agree with
   the oracle's.
 
-Tolerance (relative to the row's largest |logit|). Every MFMA operand is rounded to bf16 (unit roundoff 2^-9, about
-eight roundings per layer), and the result is sensitive to them: two correct fp32 summation orders of the same
-projection (K split over eight waves or walked in one chain) already move the logits of a one-layer model of this
-shape by 2-3e-3, because sums that differ in the last bits round to different bf16 neighbours here and there. The
-errors accumulate like a random walk over the layers: measured against the oracle 0.7e-2 at 1 layer, 1.4e-2 at 4,
-1.6e-2 at 8, 2.4e-2 at 16 and 3.3e-2 at 32 layers. The bound of the other bf16 tests, 2e-2, therefore holds up to
-8 layers; here it is scaled by sqrt(layers / 8) = 2, i.e. 4e-2."""
+Tolerance: the stated one for bf16 models, 2e-2 of the row's largest |logit|. The weights and the KV cache are bf16;
+the activation operands between the GEMMs are carried in half precision (with bf16 operands there the rounding
+errors of 32 layers add up to 3.3e-2, measured), so what remains are the bf16 roundings inside the attention
+(queries, cached keys and values, probabilities). The probes are sampled requests (temperature, top-k, top-p, Philox
+seed as in the benchmark): every token is checked against the oracle's sampler run on the engine's own logits row of
+128256 entries (exact, up to the fp32 arithmetic of the cumulative sums), and against the oracle's sampler on the oracle's
+logits wherever no decision lies within twice the measured logit error of flipping (with candidates as dense as they are
+in a vocabulary of this size, few tokens pass that second filter; the count is printed)."""
 import numpy as np
 import pytest
 
 import synth
-from oracle import model as M
+from oracle import model as M, sampling as S
+from oracle.philox import uniform_for_token
 from oracle.scheduler import Scheduler
+from tests import parity
 
 pytestmark = pytest.mark.gpu
 
-N_PROBES, PROBE_LEN, NEW_TOKENS, N_DRAWN = 2, 16, 3, 80
+N_PROBES, PROBE_LEN, NEW_TOKENS, N_DRAWN = 2, 16, 5, 80
 
 
 def test_llama3_8b_shape_schedule_exact_and_probe_logits(lib):
@@ -57,6 +60,7 @@ def test_llama3_8b_shape_schedule_exact_and_probe_logits(lib):
     D = lib.DBG
     e = lib.Engine(cfg, eng, blob, flags=lib.FLAG_TRACE | lib.FLAG_EXIT_WHEN_IDLE | lib.FLAG_KEEP_LOGITS)
     worst, kinds, probe_steps, biggest = 0.0, [], 0, 0
+    sampled_checked = sampled_undecided = sampled_exact = 0
     try:
         for r in reqs:
             e.submit_request(r)
@@ -95,7 +99,22 @@ def test_llama3_8b_shape_schedule_exact_and_probe_logits(lib):
                 rows = got[[plan.tickets.index(t) for t in in_batch]]
                 err = np.abs(rows - ref).max(axis=1) / np.abs(ref).max(axis=1)
                 worst = max(worst, float(err.max()))
-                assert err.max() < 2e-2 * (cfg["n_layers"] / 8) ** 0.5, (it, plan.kind, len(plan.input_ids), err)
+                assert err.max() < 2e-2, (it, plan.kind, len(plan.input_ids), err)
+                for j, t in enumerate(in_batch):
+                    # the sampled token at V = 128256: exactly, against the oracle's sampler run on the engine's own logits
+                    # (sampler parity given the same logits) ...
+                    r = reqs[t]
+                    assert r["temperature"] > 0
+                    sampled_exact += int(parity.token_matches_own_logits(rows[j], r, sp.gen_index[j], by_ticket[t]))
+                    # ... and against the oracle's sampler on the oracle's logits wherever an error of twice the one just
+                    # measured for this row cannot move a decision
+                    d = S.sample_detail(ref[j], r["temperature"], r["top_k"], r["top_p"], uniform_for_token(r["seed"], sp.gen_index[j]))
+                    tol = 2.0 * float(np.abs(rows[j] - ref[j]).max())
+                    if parity.sampling_decisions_clear(ref[j], r, d, tol):
+                        assert by_ticket[t] == d["token"], (it, t, by_ticket[t], d["token"])
+                        sampled_checked += 1
+                    else:
+                        sampled_undecided += 1
                 small.commit(sp, [by_ticket[t] for t in in_batch])
                 probe_steps += 1
             sched.commit(plan, [by_ticket[t] for t in plan.tickets])
@@ -106,4 +125,7 @@ def test_llama3_8b_shape_schedule_exact_and_probe_logits(lib):
     assert probe_steps == NEW_TOKENS
     assert kinds[0][0] == 1 and kinds[0][2] > 2048 and biggest > eng["max_prefill_tokens"] // 2   # the probes' prefill shared a large iteration
     assert any(k == 2 and n > 64 for k, n, _ in kinds)                      # decode iterations beyond 64 sequences
-    print("full size: iterations", kinds, "worst relative logit error of the probes", worst)
+    print("full size: iterations", kinds, "worst relative logit error of the probes", worst,
+          "sampled probe tokens: equal to the oracle's sampler on the engine's logits", sampled_exact, "of", N_PROBES * NEW_TOKENS,
+          "; on the oracle's logits: equal", sampled_checked, "undecided", sampled_undecided)
+    assert sampled_exact >= N_PROBES * NEW_TOKENS - 2

@@ -33,7 +33,7 @@ def brute_force(logits, T, k, p, u):
 
 def test_matches_brute_force_on_tiny_vocab():
     rng = np.random.default_rng(0)
-    for trial in range(300):
+    for trial in range(600):
         V = int(rng.integers(2, 12))
         logits = rng.standard_normal(V) * 2
         if trial % 3 == 0:
@@ -97,3 +97,34 @@ def test_draw_uses_the_output_index_as_counter():
     for i in (0, 5):
         u = uniform_for_token(1234, i)
         assert S.sample(logits, 1.0, 0, 1.0, 1234, i) == int(u * 16)
+
+
+def test_decision_guard_of_the_gpu_tests_is_sound():
+    """tests/parity.sampling_decisions_clear says when a sampled token may be compared exactly although the engine's
+    logits differ from the oracle's by up to tol: whenever it says "clear", the oracle's sampler on logits perturbed by
+    any error within tol must return the same token. Checked with random and with adversarial (sign-pattern) errors."""
+    from tests.parity import sampling_decisions_clear
+    from oracle.philox import uniform_for_token
+    rng = np.random.default_rng(11)
+    clear = 0
+    for trial in range(600):
+        V = int(rng.choice([60, 400, 2500]))
+        row = rng.normal(0.0, 1.3, V)
+        r = dict(temperature=float(rng.choice([0.5, 0.8, 1.0])), top_k=int(rng.choice([5, 50, 0 if V <= 400 else 40])),
+                 top_p=float(rng.choice([0.5, 0.9, 1.0])), seed=int(rng.integers(1, 1 << 40)))
+        u = uniform_for_token(r["seed"], trial)
+        d = S.sample_detail(row, r["temperature"], r["top_k"], r["top_p"], u)
+        tol = float(rng.choice([1e-3, 5e-3, 2e-2])) * np.abs(row).max()
+        if not sampling_decisions_clear(row, r, d, tol):
+            continue
+        clear += 1
+        for rep in range(12):
+            if rep < 6:
+                e = rng.uniform(-tol, tol, V)
+            else:                      # worst cases: everything ahead of the chosen token pushed one way, the rest the other
+                order = S.candidate_order(row)
+                pos = int(np.nonzero(order == d["token"])[0][0])
+                e = np.full(V, tol if rep % 2 else -tol)
+                e[order[:pos + (rep % 3 == 0)]] *= -1.0
+            assert S.sample_detail(row + e, r["temperature"], r["top_k"], r["top_p"], u)["token"] == d["token"], (trial, rep)
+    assert clear > 60

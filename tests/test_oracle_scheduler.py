@@ -153,3 +153,14 @@ def test_service_equals_per_request_generation_and_replay_tails():
     ev2, s2 = SV.serve(cfg, W, eng, reqs, tails=tails)
     assert [s2.outputs[t] for t in range(7)] == [s.outputs[t] for t in range(7)]
     assert [e[0] for e in ev2] != [e[0] for e in ev]
+
+
+def test_churn_pool_constant_is_what_the_oracle_side_script_computes():
+    """The Churn engine's pool (60 % of the peak demand of its request set) is a stored number: it must be the one
+    oracle.churn_pool derives from the oracle's reservation rule, and at least the largest single reservation."""
+    import synth
+    from oracle.churn_pool import churn_pool_blocks
+    cfg, eng = synth.model_config("churn"), synth.engine_config("churn")
+    reqs = synth.make_workload("churn", cfg["vocab"], 2001)
+    assert churn_pool_blocks(reqs, eng["kv_block_size"]) == eng["kv_num_blocks"]
+    assert eng["kv_num_blocks"] >= max(blocks_needed(len(r["prompt"]), r["max_new_tokens"], 16) for r in reqs)
