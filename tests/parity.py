@@ -86,7 +86,7 @@ def check_against_oracle(cfg, W, eng, reqs, ev, trace, rtol, tails=None, tok_rto
                 else:
                     stats["near_ties"] += 1
                     stats["sampled_undecided"] += 1
-                    assert g in set(int(x) for x in S.candidate_order(row)[: d["n_topk"] + 1])
+                    assert sampled_token_plausible(row, r, d, g, tol), (t, plan.gen_index[i], g, d["token"])
             out.append(g)
         return out
 
@@ -131,6 +131,32 @@ def sampling_decisions_clear(row, r, d, tol):
     if abs(d["cdf"][idx] - d["target"]) <= eps or abs(lo - d["target"]) <= eps:
         return False
     return True
+
+
+def sampled_token_plausible(row, r, d, g, tol):
+    """Necessary condition for token g to be what a correct sampler returns on logits within tol of `row` (used for the
+    sampled tokens whose decisions are not clear, instead of skipping them). On such logits the candidates ahead of g
+    are those ahead of it in the oracle's order, give or take the candidates within 2 tol of g; every probability moves
+    by a relative e^(2 tol / T) - 1 at most; the top-p cut moves by at most the candidates next to it. So the draw
+    u * total must fall into g's bin widened by the mass of g's near neighbours and by eps, g's bin must start before
+    top_p, and g must be among the top-k or within 2 tol of its boundary."""
+    T, top_p = r["temperature"], r["top_p"]
+    order = S.candidate_order(row)
+    k, n = d["n_topk"], len(d["kept"])
+    pos = int(np.nonzero(order == g)[0][0])
+    if pos >= k:
+        return abs(row[order[k - 1]] - row[g]) <= 2 * tol
+    p = d["probs"]
+    cum = np.cumsum(p)
+    eps = np.expm1(2 * tol / T) * 1.5 + 2e-6
+    near = np.abs(row[order[:k]] - row[g]) <= 2 * tol
+    m_near = float(p[near].sum() - p[pos])
+    lo, hi = (cum[pos - 1] if pos > 0 else 0.0) - m_near - eps, cum[pos] + m_near + eps
+    if lo >= top_p:
+        return False
+    u = d["target"] / d["total"]
+    tot_lo, tot_hi = cum[max(n - 2, 0)] - eps, cum[min(n, k - 1)] + eps      # the cut may sit one candidate earlier or later
+    return lo <= u * tot_hi and u * tot_lo <= hi
 
 
 def arithmetic_decided(d, top_p, eps=2e-5):

@@ -14,8 +14,10 @@ pytestmark = pytest.mark.gpu
 # themselves stays the stated 2e-2; this one follows the logit error the kernels are measured at (below 1e-3 of the row
 # maximum for these models, printed by the stepwise tests), with head-room. The stepwise tests check every token exactly
 # against the oracle's sampler on the engine's own logits; here the logits are not available, so a token counts as
-# undecided when an error of TOK_RTOL could move it (for sampled tokens, whose candidates lie close together, that is
-# a large share whatever the kernels do, so only the greedy share is bounded tightly).
+# undecided when an error of TOK_RTOL could move it. A sampled token that is undecided (with candidates as close
+# together as these models' are, most) must still fall into the bin of the draw widened by what that error can
+# move (parity.sampled_token_plausible, which rejects nine of ten tokens drawn with a wrong uniform); the greedy
+# near-ties are bounded.
 TOK_RTOL = 2e-3
 
 
@@ -191,8 +193,10 @@ def test_sampled_requests(lib, name, seed):
     ev, trace, st = parity.run_engine(lib, cfg, eng, blob, reqs)
     res = parity.check_against_oracle(cfg, M.Weights(cfg, raw), eng, reqs, ev, trace, rtol=2e-2 if cfg["dtype"] else 1e-4,
                                       tok_rtol=TOK_RTOL if cfg["dtype"] else 1e-5)
-    print(name, "sampled: tokens", res["tokens"], "undecided", res["near_ties"])
-    assert res["greedy_near_ties"] <= max(2, res["greedy_tokens"] // 8) and res["sampled_undecided"] <= (3 * res["sampled_tokens"]) // 5
+    print(name, "sampled: greedy near ties", res["greedy_near_ties"], "of", res["greedy_tokens"], "; sampled tokens undecided (checked by CDF bin)",
+          res["sampled_undecided"], "of", res["sampled_tokens"])
+    # (every sampled token that is not decided has passed the plausibility check of its CDF bin instead)
+    assert res["greedy_near_ties"] <= max(2, res["greedy_tokens"] // 8)
     # the same request gives the same stream whatever it is batched with: resubmit alone
     one = [reqs[0]]
     ev1, _, _ = parity.run_engine(lib, cfg, eng, blob, one)

@@ -102,29 +102,39 @@ def test_draw_uses_the_output_index_as_counter():
 def test_decision_guard_of_the_gpu_tests_is_sound():
     """tests/parity.sampling_decisions_clear says when a sampled token may be compared exactly although the engine's
     logits differ from the oracle's by up to tol: whenever it says "clear", the oracle's sampler on logits perturbed by
-    any error within tol must return the same token. Checked with random and with adversarial (sign-pattern) errors."""
-    from tests.parity import sampling_decisions_clear
+    any error within tol must return the same token. For the other tokens the GPU tests require
+    sampled_token_plausible: it must accept every token the sampler returns on perturbed logits (no false alarms) and
+    reject most wrong tokens. Checked with random and with adversarial (sign-pattern) errors."""
+    from tests.parity import sampling_decisions_clear, sampled_token_plausible
     from oracle.philox import uniform_for_token
     rng = np.random.default_rng(11)
-    clear = 0
+    clear = wrong = wrong_rejected = 0
     for trial in range(600):
         V = int(rng.choice([60, 400, 2500]))
-        row = rng.normal(0.0, 1.3, V)
-        r = dict(temperature=float(rng.choice([0.5, 0.8, 1.0])), top_k=int(rng.choice([5, 50, 0 if V <= 400 else 40])),
+        row = rng.normal(0.0, float(rng.choice([0.4, 1.3])), V)
+        r = dict(temperature=float(rng.choice([0.3, 0.8, 1.0])), top_k=int(rng.choice([5, 50, 0 if V <= 400 else 40])),
                  top_p=float(rng.choice([0.5, 0.9, 1.0])), seed=int(rng.integers(1, 1 << 40)))
         u = uniform_for_token(r["seed"], trial)
         d = S.sample_detail(row, r["temperature"], r["top_k"], r["top_p"], u)
         tol = float(rng.choice([1e-3, 5e-3, 2e-2])) * np.abs(row).max()
-        if not sampling_decisions_clear(row, r, d, tol):
-            continue
-        clear += 1
+        is_clear = sampling_decisions_clear(row, r, d, tol)
+        clear += int(is_clear)
+        order = S.candidate_order(row)
+        pos = int(np.nonzero(order == d["token"])[0][0])
         for rep in range(12):
             if rep < 6:
                 e = rng.uniform(-tol, tol, V)
             else:                      # worst cases: everything ahead of the chosen token pushed one way, the rest the other
-                order = S.candidate_order(row)
-                pos = int(np.nonzero(order == d["token"])[0][0])
                 e = np.full(V, tol if rep % 2 else -tol)
                 e[order[:pos + (rep % 3 == 0)]] *= -1.0
-            assert S.sample_detail(row + e, r["temperature"], r["top_k"], r["top_p"], u)["token"] == d["token"], (trial, rep)
+            g = S.sample_detail(row + e, r["temperature"], r["top_k"], r["top_p"], u)["token"]
+            if is_clear:
+                assert g == d["token"], (trial, rep)
+            assert sampled_token_plausible(row, r, d, g, tol), (trial, rep, g, d["token"])
+        # a token from elsewhere in the distribution (what a wrong uniform, seed or counter would give) is mostly rejected
+        other = S.sample_detail(row, r["temperature"], r["top_k"], r["top_p"], float(rng.random()))["token"]
+        if other != d["token"] and tol <= 5e-3 * np.abs(row).max():
+            wrong += 1
+            wrong_rejected += int(not sampled_token_plausible(row, r, d, other, tol))
     assert clear > 60
+    assert wrong > 100 and wrong_rejected > 0.7 * wrong, (wrong, wrong_rejected)
