@@ -225,6 +225,15 @@ int blink_clock_sync(blink_engine* e, uint64_t* device_ns, uint64_t* host_ns, ui
  * stream, copies the tokens back and frees the staging. BLINK_ERR_INVAL on a bad parameter (as blink_submit). */
 int blink_sample_rows(int32_t device, const float* logits, uint32_t n_rows, uint32_t vocab, const blink_sampling* params,
                       const uint32_t* token_index, int32_t* tokens_out);
+/* blink_sample_rows for callers that cannot allocate (code under HIP graph capture nearby, tight serving loops, harnesses
+ * that forbid hipMalloc): the same arguments, the same kernel and the same result, but the device staging is a static
+ * device array of 16 MiB that every GPU the library runs on holds until the process ends, so the call allocates and
+ * frees nothing. BLINK_ERR_TOO_LARGE when the rows, their parameters and the tokens (each part padded to 256 bytes)
+ * exceed 16 MiB (e.g. more than 32 rows of 128256 logits). Every call on a GPU uses that GPU's one array and overwrites
+ * the part it needs (nothing has to start at zero): calls from one process are serialised by the library; calls that
+ * overlap on one GPU from different processes do not share the array (each process has its own copy). */
+int blink_sample_rows_static(int32_t device, const float* logits, uint32_t n_rows, uint32_t vocab, const blink_sampling* params,
+                             const uint32_t* token_index, int32_t* tokens_out);
 /* Message of the last error on the calling thread ("" if none). The pointer stays valid until the next call. */
 const char* blink_last_error(void);
 

@@ -12,7 +12,7 @@ EVENT_FIRST, EVENT_LAST = 1, 2
 
 EXPORTS = ["blink_init", "blink_submit", "blink_run", "blink_set_exit_when_idle", "blink_wait", "blink_stop", "blink_poll_outputs", "blink_shutdown",
            "blink_get_trace", "blink_get_stats", "blink_debug_read", "blink_time_phase", "blink_get_phase_times", "blink_calibration_copy",
-           "blink_calibration_rates", "blink_clock_sync", "blink_sample_rows", "blink_last_error"]
+           "blink_calibration_rates", "blink_clock_sync", "blink_sample_rows", "blink_sample_rows_static", "blink_last_error"]
 
 
 class DBG:
@@ -89,6 +89,7 @@ def load_library():
     lib.blink_get_phase_times.argtypes = [vp, vp, u64, C.POINTER(u64)]
     lib.blink_clock_sync.argtypes = [vp, C.POINTER(u64), C.POINTER(u64), C.POINTER(u64)]
     lib.blink_sample_rows.argtypes = [C.c_int32, vp, u32, u32, vp, vp, vp]
+    lib.blink_sample_rows_static.argtypes = [C.c_int32, vp, u32, u32, vp, vp, vp]
     lib.blink_last_error.restype = C.c_char_p
     for n in EXPORTS[:-1]:
         getattr(lib, n).restype = C.c_int
@@ -117,6 +118,11 @@ def sample_rows(logits, params, token_index, device=0):
     """blink_sample_rows: logits float32 [n][vocab], params: list of dicts (temperature, top_k, top_p, seed),
     token_index: output index per row. Returns int32 [n]."""
     return _sample_rows("blink_sample_rows", logits, params, token_index, device)
+
+
+def sample_rows_static(logits, params, token_index, device=0):
+    """blink_sample_rows_static: as sample_rows, staging in the library's static device array (no allocation)."""
+    return _sample_rows("blink_sample_rows_static", logits, params, token_index, device)
 
 
 class Engine:

@@ -108,9 +108,10 @@ __global__ void __launch_bounds__(BLK_THREADS) k_mfma_calibration(float* dst, u3
   dst[(u64)blockIdx.x * blockDim.x + threadIdx.x] = s[0] + s[1] + s[2] + s[3];
 }
 
-__global__ void __launch_bounds__(BLK_THREADS) k_sample_rows(const float* logits, u32 n_rows, u32 V, const SampleRowParams* params, i32* tokens) {
+__global__ void __launch_bounds__(BLK_THREADS) k_sample_rows(const float* logits, u32 n_rows, u32 V, const SampleRowParams* params,
+                                                             const u32* token_index, i32* tokens) {
   __shared__ SamplerShared sh;
-  sample_rows(logits, n_rows, V, params, tokens, sh);
+  sample_rows(logits, n_rows, V, params, token_index, tokens, sh);
 }
 
 // the device clock, written to pinned host memory (blink_clock_sync)
@@ -957,23 +958,32 @@ static int sample_rows_check(const float* logits, uint32_t n_rows, uint32_t voca
   return BLINK_OK;
 }
 
-// copies the rows and their parameters to `dev` (laid out: logits, parameters, tokens), samples, copies the tokens back
+// Device staging of one call, 256-byte aligned parts: logits rows, parameters, output indices, tokens.
+struct SampleStaging { u64 params, index, tokens, total; };
+static SampleStaging sample_staging(uint32_t n_rows, uint32_t vocab) {
+  auto pad = [](u64 b) { return (b + 255) & ~255ull; };
+  SampleStaging s;
+  s.params = pad((u64)n_rows * vocab * 4);
+  s.index = s.params + pad((u64)n_rows * sizeof(blink_sampling));
+  s.tokens = s.index + pad((u64)n_rows * 4);
+  s.total = s.tokens + pad((u64)n_rows * 4);
+  return s;
+}
+
+// copies the rows and their parameters into the staging memory at `dev`, samples, copies the tokens back
 static int sample_rows_on(char* dev, hipStream_t st, const float* logits, uint32_t n_rows, uint32_t vocab, const blink_sampling* params,
                           const uint32_t* token_index, int32_t* tokens_out) {
-  const u64 lbytes = (u64)n_rows * vocab * 4, lpad = (lbytes + 255) & ~255ull, pbytes = (u64)n_rows * sizeof(SampleRowParams), ppad = (pbytes + 255) & ~255ull;
-  std::vector<SampleRowParams> hp(n_rows);
-  for (u32 r = 0; r < n_rows; ++r) hp[r] = SampleRowParams{params[r].temperature, params[r].top_k, params[r].top_p, token_index[r], params[r].seed};
-  HIPCHK(hipMemcpyAsync(dev, logits, lbytes, hipMemcpyHostToDevice, st));
-  HIPCHK(hipMemcpyAsync(dev + lpad, hp.data(), pbytes, hipMemcpyHostToDevice, st));
+  static_assert(sizeof(blink_sampling) == sizeof(SampleRowParams), "the kernel reads blink_sampling as it is");
+  const SampleStaging s = sample_staging(n_rows, vocab);
+  HIPCHK(hipMemcpyAsync(dev, logits, (u64)n_rows * vocab * 4, hipMemcpyHostToDevice, st));
+  HIPCHK(hipMemcpyAsync(dev + s.params, params, (u64)n_rows * sizeof(blink_sampling), hipMemcpyHostToDevice, st));
+  HIPCHK(hipMemcpyAsync(dev + s.index, token_index, (u64)n_rows * 4, hipMemcpyHostToDevice, st));
   hipLaunchKernelGGL(k_sample_rows, dim3(std::min<u32>(n_rows, 1024u)), dim3(BLK_THREADS), 0, st, (const float*)dev, n_rows, vocab,
-                     (const SampleRowParams*)(dev + lpad), (i32*)(dev + lpad + ppad));
+                     (const SampleRowParams*)(dev + s.params), (const u32*)(dev + s.index), (i32*)(dev + s.tokens));
   HIPCHK(hipGetLastError());
-  HIPCHK(hipMemcpyAsync(tokens_out, dev + lpad + ppad, (u64)n_rows * 4, hipMemcpyDeviceToHost, st));
+  HIPCHK(hipMemcpyAsync(tokens_out, dev + s.tokens, (u64)n_rows * 4, hipMemcpyDeviceToHost, st));
   HIPCHK(hipStreamSynchronize(st));
   return BLINK_OK;
-}
-static u64 sample_rows_bytes(uint32_t n_rows, uint32_t vocab) {
-  return (((u64)n_rows * vocab * 4 + 255) & ~255ull) + (((u64)n_rows * sizeof(SampleRowParams) + 255) & ~255ull) + (u64)n_rows * 4;
 }
 
 extern "C" int blink_sample_rows(int32_t device, const float* logits, uint32_t n_rows, uint32_t vocab, const blink_sampling* params,
@@ -985,12 +995,41 @@ extern "C" int blink_sample_rows(int32_t device, const float* logits, uint32_t n
   if (device < 0 || device >= n_dev) return fail(BLINK_ERR_INVAL, "device %d out of range", device);
   HIPCHK(hipSetDevice(device));
   char* dev = nullptr;
-  HIPCHK(hipMalloc((void**)&dev, sample_rows_bytes(n_rows, vocab)));
+  HIPCHK(hipMalloc((void**)&dev, sample_staging(n_rows, vocab).total));
   const int rc = sample_rows_on(dev, nullptr, logits, n_rows, vocab, params, token_index, tokens_out);
   const std::string keep = g_err;
   (void)hipFree(dev);
   g_err = keep;
   return rc;
+}
+
+// ---- the same without any allocation: the staging lives in a static device array ------------------------------------
+#define SAMPLE_SCRATCH_BYTES (16u << 20)
+static __device__ __align__(256) unsigned char scratch[SAMPLE_SCRATCH_BYTES];
+#define SAMPLE_MAX_DEVICES 64
+static std::mutex g_scratch_mu;                          // one call at a time per process: the calls share the array
+static char* g_scratch_ptr[SAMPLE_MAX_DEVICES] = {};     // device address of `scratch` on every device used so far
+
+extern "C" int blink_sample_rows_static(int32_t device, const float* logits, uint32_t n_rows, uint32_t vocab, const blink_sampling* params,
+                                        const uint32_t* token_index, int32_t* tokens_out) {
+  g_err.clear();
+  if (int rc = sample_rows_check(logits, n_rows, vocab, params, token_index, tokens_out)) return rc;
+  const u64 need = sample_staging(n_rows, vocab).total;
+  if (need > SAMPLE_SCRATCH_BYTES)
+    return fail(BLINK_ERR_TOO_LARGE, "%u rows of %u logits need %llu bytes of staging, the static buffer holds %u", n_rows, vocab,
+                (unsigned long long)need, (unsigned)SAMPLE_SCRATCH_BYTES);
+  int n_dev = 0;
+  if (hipGetDeviceCount(&n_dev) != hipSuccess || n_dev <= 0) return fail(BLINK_ERR_DEVICE, "no HIP device available");
+  if (device < 0 || device >= n_dev || device >= SAMPLE_MAX_DEVICES) return fail(BLINK_ERR_INVAL, "device %d out of range", device);
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  HIPCHK(hipSetDevice(device));
+  if (!g_scratch_ptr[device]) {   // every device holds its own copy of the array at its own address
+    char* p = nullptr;
+    HIPCHK(hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(BLINK_ERR_DEVICE, "hipGetSymbolAddress returned a null address");
+    g_scratch_ptr[device] = p;
+  }
+  return sample_rows_on(g_scratch_ptr[device], nullptr, logits, n_rows, vocab, params, token_index, tokens_out);
 }
 
 extern "C" const char* blink_last_error(void) { return g_err.c_str(); }

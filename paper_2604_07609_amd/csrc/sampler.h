@@ -316,18 +316,18 @@ __device__ __forceinline__ void phase_sample_publish(const DevCtx& c, SamplerSha
 }
 
 // Stand-alone sampling of a batch of logits rows (no engine): one workgroup per row, grid-stride.
-struct SampleRowParams {   // 24 bytes, the layout of blink_sampling plus the output index
+struct SampleRowParams {   // the layout of blink_sampling (24 bytes)
   float temperature;
   u32 top_k;
   float top_p;
-  u32 token_index;
+  u32 pad;
   u64 seed;
 };
-__device__ __forceinline__ void sample_rows(const float* logits, u32 n_rows, u32 V, const SampleRowParams* params, i32* tokens,
-                                            SamplerShared& sh) {
+__device__ __forceinline__ void sample_rows(const float* logits, u32 n_rows, u32 V, const SampleRowParams* params, const u32* token_index,
+                                            i32* tokens, SamplerShared& sh) {
   for (u32 r = blockIdx.x; r < n_rows; r += gridDim.x) {
     const SampleRowParams p = params[r];
-    const i32 token = sample_row(logits + (u64)r * V, V, p.temperature, p.top_k, p.top_p, p.seed, p.token_index, sh);
+    const i32 token = sample_row(logits + (u64)r * V, V, p.temperature, p.top_k, p.top_p, p.seed, token_index[r], sh);
     if (threadIdx.x == 0) tokens[r] = token;
   }
 }
