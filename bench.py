@@ -114,10 +114,9 @@ def cpu_baseline(cfg, eng, raw, reqs, budget_tokens, n_req=4, prompt_cap=None):
     # the scheduler alone (integer state machine, single thread) over the whole request set with a constant token in
     # place of the model: the CPU figure that stands beside the on-GPU scheduling time per iteration
     from oracle import scheduler as SC
-    sched = SC.Scheduler(full_eng["kv_num_blocks"], full_eng["kv_block_size"], full_eng["max_batch"], full_eng["max_prefill_tokens"],
-                         full_eng["ring_slots"], full_eng.get("eos_token_id", -1))
+    sched = SC.Scheduler.from_engine(full_eng)
     t0 = time.perf_counter()
-    sev = SV.run_schedule(sched, reqs, lambda plan: [1] * len(plan.tickets), max_iterations=400)
+    sev = SV.run_schedule(sched, reqs, lambda plan: [1] * len(plan.sample_seq), max_iterations=400)
     sdt = time.perf_counter() - t0
     sched_us = 1e6 * sdt / max(1, sched.iteration)
     return dict(value=len(ev) / dt, unit="output tokens/s", cores=int(threads), kind="oracle",
@@ -287,6 +286,11 @@ def main():
     ap.add_argument("--phase", type=int, default=-1,
                     help="forward phase whose kernel is timed for the roofline (default: the dominant one of the workload: "
                          "decode attention for llama3_8b at its batch of 256, the gate/up GEMM otherwise)")
+    ap.add_argument("--phases", default="", help="comma-separated forward phases (see blink_time_phase): after the roofline window, "
+                    "--steps more iterations per phase with that phase's launches bracketed by HIP events; reports the average "
+                    "launch duration in decode and in prefill iterations as kernel_times_us")
+    ap.add_argument("--no-graph", action="store_true", help="enqueue the kernels one by one in every window (BLINK_FLAG_NO_GRAPH)")
+    ap.add_argument("--tune", type=lambda x: int(x, 0), default=0, help="blink_config.tune")
     ap.add_argument("--requests", type=int, default=0)
     ap.add_argument("--max-batch", type=int, default=0, help="override the engine's batch slots")
     ap.add_argument("--kv-blocks", type=int, default=0, help="override the size of the KV pool (16-token blocks)")
@@ -330,7 +334,7 @@ def main():
 
     # One engine serves every leg. First the legs that leave it idle again (claim latency, the workload's own arrivals,
     # isolated and under the host stressor), then the saturation run that is timed.
-    e = B.Engine(cfg, eng, blob, flags=B.FLAG_TRACE, trace_capacity=1 << 18)
+    e = B.Engine(cfg, eng, blob, flags=B.FLAG_TRACE | (B.FLAG_NO_GRAPH if args.no_graph else 0), trace_capacity=1 << 18, tune=args.tune)
     claim = iso = stressed = stress_n = None
     sweep = []
     try:
@@ -383,6 +387,24 @@ def main():
         e.time_phase(-1)
         e.drain(16384)
         phase_ms = e.phase_times_ms()
+        kernel_times = {}
+        for ph in [int(x) for x in args.phases.split(",") if x]:
+            sa = e.stats()
+            e.time_phase(ph)
+            e.run(K)
+            e.wait()
+            e.time_phase(-1)
+            e.drain(16384)
+            sb = e.stats()
+            pms = e.phase_times_ms()
+            trx = e.trace(int(sb["iterations"] - sa["iterations"]))[: len(pms)]
+            n_l = 1 if ph in (0, 9, 10, 11) else cfg["n_layers"]
+            row = {}
+            for label, kind in (("decode", 2), ("prefill", 1)):
+                sel = trx["kind"] == kind
+                if sel.any():
+                    row[label] = round(1e3 * float(pms[: len(trx)][sel].sum()) / (int(sel.sum()) * n_l), 2)
+            kernel_times[str(ph)] = row
         trace = e.trace(1 << 18)
         e.calibration_copy(64 << 20)    # one plain copy kernel of known size: scales the HBM counters of a --pmc run
         copy_gbs, mfma_tflops = e.calibration_rates()
@@ -393,10 +415,10 @@ def main():
 
     if args.dump_iterations:
         with open(args.dump_iterations, "w") as f:
-            f.write("# iteration kind n_seqs n_tokens ctx_tokens timed(1: timed window, 2: window with HIP events around the timed kernel)\n")
+            f.write("# iteration kind n_seqs n_tokens ctx_tokens timed(1: timed window, 2: window with HIP events around the timed kernel) chain\n")
             for t in trace[trace["iteration"] < s2["iterations"]]:
                 flag = 1 if s0["iterations"] <= t["iteration"] < s1["iterations"] else (2 if t["iteration"] >= s1["iterations"] else 0)
-                f.write("%d %d %d %d %d %d\n" % (t["iteration"], t["kind"], t["n_seqs"], t["n_tokens"], t["ctx_tokens"], flag))
+                f.write("%d %d %d %d %d %d %d\n" % (t["iteration"], t["kind"], t["n_seqs"], t["n_tokens"], t["ctx_tokens"], flag, t["chain"]))
     iters = int(s1["iterations"] - s0["iterations"])
     toks = int(s1["tokens_out"] - s0["tokens_out"])
     dt = t1 - t0
@@ -499,6 +521,9 @@ def main():
                               "note": "plain kernels on this device: a 1 GiB copy (read + written) and a register-only MFMA loop"},
         "setup_s": {"weights_and_workload": round(t_gen, 1)},
     }
+    if kernel_times:
+        out["kernel_times_us"] = dict(kernel_times, note="average launch duration by phase number (blink_time_phase), HIP events, "
+                                      "in the decode and the prefill iterations of a window of its own")
     if int(dec.sum()) == 0 and args.workload in ("llama3_8b", "churn"):
         out["warning"] = "the timed window holds no decode iteration"
         print("bench.py: the timed window holds no decode iteration (steps=%d): ITL and the decode roofline are empty" % K, file=sys.stderr)

@@ -120,6 +120,9 @@ typedef struct {
   uint64_t first_admitted;     /* ticket, valid when n_admitted > 0 */
   uint64_t t_sched_begin_ns, t_sched_end_ns, t_forward_end_ns, t_publish_end_ns; /* device wall clock */
   uint64_t ctx_tokens;         /* sum over the batch of the context lengths its attention reads (KV tokens) */
+  uint64_t chain;              /* ordinal of the scheduler kernel launch that ran this iteration, counted since init over
+                                  all launches (idle polls and launches past the end of a window included): lines a
+                                  profiler's list of dispatches up with the iterations */
 } blink_trace_record;
 
 typedef struct {
@@ -197,7 +200,9 @@ int blink_get_stats(blink_engine* e, blink_stats* out);
 int blink_debug_read(blink_engine* e, uint32_t what, void* buf, uint64_t cap_bytes, uint64_t* n_bytes);
 /* Kernel timing for the roofline report. blink_time_phase selects one phase of the forward pass (0 embedding;
  * per layer: 1 norm, 2 QKV GEMM, 3 rotary + KV write, 4 attention, 5 output GEMM, 6 norm, 7 gate/up GEMM,
- * 8 down GEMM; 9 final norm, 10 LM head, 11 sample + publish; -1 none). While a phase is selected, the loop
+ * 8 down GEMM; 9 final norm, 10 LM head, 11 sample + publish; bf16 models also 12 merge of the decode attention's
+ * chunks, 13 / 14 / 15 second kernel of the QKV / output / down GEMM when K is split across workgroups; -1 none). A
+ * bf16 model has no kernels for phases 1, 3, 6 and 9 (fused into the GEMMs). While a phase is selected, the loop
  * brackets every launch of that phase's kernel with HIP events on the compute stream. After the loop has
  * stopped, blink_get_phase_times returns, per iteration enqueued in the last window and in enqueue order, the
  * summed duration in milliseconds of that kernel's launches (one per layer for per-layer phases). */

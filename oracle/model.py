@@ -177,7 +177,7 @@ def paged_forward(cfg, W, kv, input_ids, positions, slot_mapping, tok_seq, block
             slots = bt[p // bs] * bs + p % bs
             attn[t] = _attend(cfg, q[t], kv.K[l][slots], kv.V[l][slots])
         x = _post_attention(cfg, W, l, x, attn)
-    return _head(cfg, W, x[np.asarray(last_idx)])
+    return _head(cfg, W, x[np.asarray(last_idx, dtype=np.int64)])
 
 
 def generate_bruteforce(cfg, W, prompt, n_new, pick):

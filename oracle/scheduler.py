@@ -20,6 +20,16 @@ The paper gives no KV-block algorithm; the reading taken here:
     the free list is a stack whose first pops return 0,1,2,..; (6) build the batch metadata.
   * After the forward pass and sampling: append the token, finish a request when it has
     max_new tokens or emitted the end-of-sequence id (which is emitted and counted).
+
+Chunked prefill with mixed iterations (`chunked=True`), the first extension the paper names in its discussion
+(section 7: the scheduler already tracks per-request progress). The paper gives no algorithm; the reading taken here
+is the usual token-budget one: an iteration carries at most max_prefill_tokens tokens. Every running request that has
+its whole prompt cached decodes (one token each, never paused). The remaining budget goes to prompts in ticket order:
+first to the one request that may be part-way through its prompt, then to new admissions, each taking
+min(prompt tokens left, budget left); a request is admitted only while budget is left (so it processes at least one
+token in the iteration that admits it, and at most one request is ever part-way), a batch slot is free and its
+reservation fits. A request samples its first token in the iteration that processes the last token of its prompt;
+blocks are allocated as the cached length grows. Decodes are not paused in this mode.
 """
 import numpy as np
 
@@ -37,7 +47,7 @@ IDLE, PREFILL, DECODE = 0, 1, 2
 
 
 class Running:
-    __slots__ = ("ticket", "P", "max_new", "gen", "ctx_len", "reserved", "blocks", "finished", "last_token")
+    __slots__ = ("ticket", "P", "max_new", "gen", "ctx_len", "reserved", "blocks", "finished", "last_token", "prefilled")
 
 
 class Plan:
@@ -58,8 +68,16 @@ class Plan:
         self.tok_seq = []
         self.last_idx = []
         self.block_tables = []  # per sequence, list of block ids
-        self.gen_index = []     # index of the output token each sequence samples in this iteration
+        self.gen_index = []     # index of the output token each sampling sequence samples in this iteration
+        self.sample_seq = []    # indices (into tickets / batch_slots) of the sequences that sample a token in this iteration;
+                                # last_idx and gen_index have one entry per sampling sequence. Without chunked prefill every
+                                # sequence of an iteration samples
+        self.pos0 = []          # position of the first token each sequence processes in this iteration
         self.free_blocks_after = 0
+
+    @property
+    def sample_tickets(self):
+        return [self.tickets[i] for i in self.sample_seq]
 
 
 def blocks_needed(P, max_new, bs):
@@ -68,7 +86,10 @@ def blocks_needed(P, max_new, bs):
 
 class Scheduler:
     def __init__(self, n_blocks, block_size, max_batch, max_prefill_tokens, ring_slots, eos_token_id=-1,
-                 free_list=None):
+                 free_list=None, chunked=False):
+        self.chunked = chunked
+        if chunked:
+            assert max_prefill_tokens > max_batch, "the token budget must leave room for a prompt token beside the decodes"
         self.n_blocks, self.bs, self.max_batch = n_blocks, block_size, max_batch
         self.max_prefill_tokens, self.ring_slots, self.eos = max_prefill_tokens, ring_slots, eos_token_id
         # stack: pop from the end. Default order makes the first pops return 0, 1, 2, ...
@@ -81,6 +102,12 @@ class Scheduler:
         self.state = {}             # ticket -> slot state
         self.transitions = []       # (ticket, from, to)
         self.outputs = {}           # ticket -> list of tokens
+
+    @classmethod
+    def from_engine(cls, eng):
+        """From an engine configuration dict (synth.configs)."""
+        return cls(eng["kv_num_blocks"], eng["kv_block_size"], eng["max_batch"], eng["max_prefill_tokens"], eng["ring_slots"],
+                   eng.get("eos_token_id", -1), chunked=bool(eng.get("chunked_prefill", False)))
 
     # ---- ring side -------------------------------------------------------------------
     def submit(self, prompt, max_new):
@@ -98,6 +125,8 @@ class Scheduler:
 
     # ---- one iteration: steps (1)-(6) -------------------------------------------------
     def step(self, tail):
+        if self.chunked:
+            return self._step_chunked(tail)
         bs = self.bs
         plan = Plan()
         plan.tail = tail
@@ -125,7 +154,7 @@ class Scheduler:
                 break
             r = Running()
             r.ticket, r.P, r.max_new, r.gen, r.ctx_len = t, P, max_new, 0, 0
-            r.reserved, r.blocks, r.finished, r.last_token = need, [], False, -1
+            r.reserved, r.blocks, r.finished, r.last_token, r.prefilled = need, [], False, -1, P
             b = free_slots[0]
             self.running[b] = r
             self.committed += need
@@ -180,15 +209,109 @@ class Scheduler:
             plan.last_idx.append(len(plan.input_ids) - 1)
             plan.block_tables.append(list(r.blocks))
             plan.gen_index.append(r.gen)
+            plan.sample_seq.append(si)
+            plan.pos0.append(pos[0])
+        plan.free_blocks_after = len(self.free)
+        return plan
+
+    # ---- one iteration with chunked prefill: decodes and prompt chunks share a token budget ---------------------
+    def _step_chunked(self, tail):
+        bs, budget = self.bs, self.max_prefill_tokens
+        plan = Plan()
+        plan.tail = tail
+        # (1) retire
+        for b in range(self.max_batch):
+            r = self.running[b]
+            if r is not None and r.finished:
+                self.free.extend(r.blocks)
+                self.committed -= r.reserved
+                self.running[b] = None
+        # tokens of this iteration per batch slot: one per decoding request, then prompt chunks in ticket order
+        chunk = {}
+        used = 0
+        for b in range(self.max_batch):
+            r = self.running[b]
+            if r is not None and r.prefilled == r.P:
+                chunk[b] = 1
+                used += 1
+        partway = sorted((r.ticket, b) for b, r in enumerate(self.running) if r is not None and r.prefilled < r.P)
+        assert len(partway) <= 1, "at most one request is part-way through its prompt"
+        for _, b in partway:
+            r = self.running[b]
+            chunk[b] = min(r.P - r.prefilled, budget - used)
+            used += chunk[b]
+        # (2)+(3) admit in ticket order while token budget, a batch slot and the block reservation allow
+        while self.next_ticket < tail and used < budget:
+            t = self.next_ticket
+            prompt, max_new = self.requests[t]
+            P = prompt.size
+            need = blocks_needed(P, max_new, bs)
+            free_slots = [b for b in range(self.max_batch) if self.running[b] is None]
+            if not free_slots or self.committed + need > self.n_blocks:
+                break
+            r = Running()
+            r.ticket, r.P, r.max_new, r.gen, r.ctx_len = t, P, max_new, 0, 0
+            r.reserved, r.blocks, r.finished, r.last_token, r.prefilled = need, [], False, -1, 0
+            b = free_slots[0]
+            self.running[b] = r
+            self.committed += need
+            chunk[b] = min(P, budget - used)
+            used += chunk[b]
+            plan.admitted.append(t)
+            self._set(t, PREFILL_PROCESSING)
+            self.next_ticket = t + 1
+        slots = sorted(chunk)
+        if not slots:
+            plan.kind = IDLE
+            return plan
+        # (4) kind: an iteration with prompt tokens in it counts as a prefill iteration
+        plan.kind = PREFILL if any(self.running[b].prefilled < self.running[b].P for b in slots) else DECODE
+        plan.iteration = self.iteration
+        self.iteration += 1
+        # (5) allocate, (6) metadata, batch slot ascending
+        for si, b in enumerate(slots):
+            r = self.running[b]
+            if r.prefilled < r.P:
+                n = chunk[b]
+                pos = list(range(r.prefilled, r.prefilled + n))
+                toks = list(self.requests[r.ticket][0][r.prefilled:r.prefilled + n])
+                while len(r.blocks) * bs < r.prefilled + n:
+                    r.blocks.append(self.free.pop())
+                r.prefilled += n
+                r.ctx_len = r.prefilled
+                samples = r.prefilled == r.P
+            else:
+                if r.ctx_len == len(r.blocks) * bs:
+                    r.blocks.append(self.free.pop())
+                toks = [r.last_token]
+                pos = [r.ctx_len]
+                r.ctx_len += 1
+                samples = True
+            plan.batch_slots.append(b)
+            plan.tickets.append(r.ticket)
+            plan.seq_lens.append(r.ctx_len)
+            plan.input_ids += [int(x) for x in toks]
+            plan.positions += pos
+            plan.slot_mapping += [r.blocks[p // bs] * bs + p % bs for p in pos]
+            plan.tok_seq += [si] * len(pos)
+            plan.cu_seqlens.append(len(plan.input_ids))
+            plan.block_tables.append(list(r.blocks))
+            plan.pos0.append(pos[0])
+            if samples:
+                plan.sample_seq.append(si)
+                plan.last_idx.append(len(plan.input_ids) - 1)
+                plan.gen_index.append(r.gen)
+        assert len(plan.input_ids) <= budget
         plan.free_blocks_after = len(self.free)
         return plan
 
     # ---- steps (7)-(8): tokens of the iteration ----------------------------------------
     def commit(self, plan, tokens):
-        """tokens[i]: sampled token of sequence i of the plan. Returns events
+        """tokens[i]: sampled token of the i-th sampling sequence of the plan. Returns events
         (ticket, index, token, is_first, is_last) in batch-slot order."""
         events = []
-        for b, tok in zip(plan.batch_slots, tokens):
+        assert len(tokens) == len(plan.sample_seq)
+        for b, tok in zip([plan.batch_slots[i] for i in plan.sample_seq], tokens):
             r = self.running[b]
             tok = int(tok)
             self.outputs[r.ticket].append(tok)

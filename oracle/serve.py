@@ -45,8 +45,7 @@ def serve(cfg, W, eng, requests, tails=None, max_iterations=None, on_plan=None, 
     """Full service. eng: engine config dict (kv_block_size, kv_num_blocks, max_batch,
     max_prefill_tokens, ring_slots, eos_token_id). Returns (events, scheduler).
     keep_logits: optional list that receives (iteration, logits[n_seq][V]) per iteration."""
-    sched = Scheduler(eng["kv_num_blocks"], eng["kv_block_size"], eng["max_batch"], eng["max_prefill_tokens"],
-                      eng["ring_slots"], eng.get("eos_token_id", -1))
+    sched = Scheduler.from_engine(eng)
     kv = M.PagedKV(cfg, eng["kv_num_blocks"], eng["kv_block_size"])
 
     def token_fn(plan):
@@ -55,7 +54,7 @@ def serve(cfg, W, eng, requests, tails=None, max_iterations=None, on_plan=None, 
         if keep_logits is not None:
             keep_logits.append((plan.iteration, logits))
         out = []
-        for i, t in enumerate(plan.tickets):
+        for i, t in enumerate(plan.sample_tickets):
             r = requests[t]
             out.append(S.sample(logits[i], r["temperature"], r["top_k"], r["top_p"], r["seed"], plan.gen_index[i]))
         return out

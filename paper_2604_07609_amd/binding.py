@@ -45,7 +45,8 @@ EVENT_DTYPE = np.dtype([("request_id", "<u8"), ("index", "<u4"), ("token", "<i4"
                         ("device_ns", "<u8")], align=True)
 TRACE_DTYPE = np.dtype([("iteration", "<u4"), ("kind", "<u4"), ("tail", "<u8"), ("n_admitted", "<u4"), ("n_seqs", "<u4"),
                         ("n_tokens", "<u4"), ("free_blocks", "<u4"), ("first_admitted", "<u8"), ("t_sched_begin_ns", "<u8"),
-                        ("t_sched_end_ns", "<u8"), ("t_forward_end_ns", "<u8"), ("t_publish_end_ns", "<u8"), ("ctx_tokens", "<u8")],
+                        ("t_sched_end_ns", "<u8"), ("t_forward_end_ns", "<u8"), ("t_publish_end_ns", "<u8"), ("ctx_tokens", "<u8"),
+                        ("chain", "<u8")],
                        align=True)
 
 

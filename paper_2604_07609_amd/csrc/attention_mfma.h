@@ -245,39 +245,58 @@ __device__ __forceinline__ void attn_decode(const DevCtx& c, u32 layer, AttnMfma
   }
 }
 
-// Merges the per-chunk partial results of contexts longer than one chunk, in chunk order. 256 threads.
+// Merges the per-chunk partial results of contexts longer than one chunk, in chunk order. One wave per (sequence, kv
+// head); a lane takes E output elements at a time and has the partial results of all their chunks in flight together
+// (the kernel is a chain of dependent loads: how many of them wait at once is what its duration depends on).
+template <u32 MAXC, u32 E>
+__device__ __forceinline__ void attn_combine_pair(const DevCtx& c, u32 c0, u32 nch, u32 t, u32 g, u32 G, u32 HD) {
+  const u32 lane = threadIdx.x & 63, n = G * HD;
+  for (u32 i0 = lane; i0 < n; i0 += 64 * E) {
+    float2 ml[E][MAXC];
+    float ov[E][MAXC];
+#pragma unroll
+    for (u32 e = 0; e < E; ++e) {
+      const u32 idx = min(i0 + 64 * e, n - 1), h = idx / HD, dim = idx % HD;
+#pragma unroll
+      for (u32 p = 0; p < MAXC; ++p) {
+        const u64 base = ((u64)(c0 + min(p, nch - 1)) * c.nkv + g) * G;
+        ml[e][p] = *(const float2*)(c.attn_part_ml + (base + h) * 2);
+        ov[e][p] = c.attn_part_o[(base + h) * HD + dim];
+      }
+    }
+#pragma unroll
+    for (u32 e = 0; e < E; ++e) {
+      const u32 idx = i0 + 64 * e;
+      float M = -INFINITY, L = 0.f, O = 0.f;
+#pragma unroll
+      for (u32 p = 0; p < MAXC; ++p)
+        if (p < nch) M = fmaxf(M, ml[e][p].x);
+#pragma unroll
+      for (u32 p = 0; p < MAXC; ++p)
+        if (p < nch) {
+          const float f = __expf(ml[e][p].x - M);
+          L += ml[e][p].y * f;
+          O += ov[e][p] * f;
+        }
+      if (idx < n) c.aq[packed_off(t, g * n + idx, c.TBS)] = f32_to_f16(O / L);
+    }
+  }
+}
+
 __device__ __forceinline__ void attn_decode_combine(const DevCtx& c, u32 wg, u32 nwg) {
   if (c.meta->kind != 2u) return;
-  const u32 B = c.meta->n_seqs, G = c.nq / c.nkv, HD = c.hd;
-  for (u32 pair = wg; pair < B * c.nkv; pair += nwg) {
+  const u32 B = c.meta->n_seqs, G = c.nq / c.nkv, HD = c.hd, lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  for (u32 pair = wg * nw + w; pair < B * c.nkv; pair += nwg * nw) {
     const u32 s = pair / c.nkv, g = pair % c.nkv;
     const u32 c0 = c.cu_chunks[s], nch = c.cu_chunks[s + 1] - c0;
     if (nch < 2) continue;
     const u32 t = c.cu_seqlens[s];
-    for (u32 idx = threadIdx.x; idx < G * HD; idx += blockDim.x) {
-      const u32 h = idx / HD, dim = idx % HD;
-      constexpr u32 MAXC = 12;   // chunks whose partial results are fetched together (one memory round trip)
-      float M = -INFINITY, L = 0.f, O = 0.f;
-      if (nch <= MAXC) {
-        float2 ml[MAXC];
-        float ov[MAXC];
-#pragma unroll
-        for (u32 p = 0; p < MAXC; ++p) {
-          const u64 base = ((u64)(c0 + min(p, nch - 1)) * c.nkv + g) * G;
-          ml[p] = *(const float2*)(c.attn_part_ml + (base + h) * 2);
-          ov[p] = c.attn_part_o[(base + h) * HD + dim];
-        }
-#pragma unroll
-        for (u32 p = 0; p < MAXC; ++p)
-          if (p < nch) M = fmaxf(M, ml[p].x);
-#pragma unroll
-        for (u32 p = 0; p < MAXC; ++p)
-          if (p < nch) {
-            const float f = __expf(ml[p].x - M);
-            L += ml[p].y * f;
-            O += ov[p] * f;
-          }
-      } else {
+    if (nch <= 4) attn_combine_pair<4, 4>(c, c0, nch, t, g, G, HD);
+    else if (nch <= 12) attn_combine_pair<12, 1>(c, c0, nch, t, g, G, HD);
+    else {
+      for (u32 idx = lane; idx < G * HD; idx += 64) {
+        const u32 h = idx / HD, dim = idx % HD;
+        float M = -INFINITY, L = 0.f, O = 0.f;
         for (u32 p = 0; p < nch; ++p) M = fmaxf(M, c.attn_part_ml[(((u64)(c0 + p) * c.nkv + g) * G + h) * 2]);
         for (u32 p = 0; p < nch; ++p) {
           const u64 base = ((u64)(c0 + p) * c.nkv + g) * G;
@@ -285,8 +304,8 @@ __device__ __forceinline__ void attn_decode_combine(const DevCtx& c, u32 wg, u32
           L += c.attn_part_ml[(base + h) * 2 + 1] * f;
           O += c.attn_part_o[(base + h) * HD + dim] * f;
         }
+        c.aq[packed_off(t, (g * G + h) * HD + dim, c.TBS)] = f32_to_f16(O / L);
       }
-      c.aq[packed_off(t, (g * G + h) * HD + dim, c.TBS)] = f32_to_f16(O / L);
     }
   }
 }

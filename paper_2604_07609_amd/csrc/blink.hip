@@ -50,6 +50,9 @@ PHASE_KERNEL(k_final_norm, PH_FINAL_NORM)
 PHASE_KERNEL(k_lm_head, PH_LM_HEAD)
 PHASE_KERNEL(k_sample_publish, PH_SAMPLE)
 PHASE_KERNEL(k_attention_combine, PH_ATTN_COMBINE)
+PHASE_KERNEL(k_qkv_reduce, PH_QKV_RED)
+PHASE_KERNEL(k_oproj_reduce, PH_OPROJ_RED)
+PHASE_KERNEL(k_down_reduce, PH_DOWN_RED)
 
 typedef void (*phase_kernel_t)(DevCtx, u32);
 static phase_kernel_t phase_kernel(int ph) {
@@ -66,6 +69,9 @@ static phase_kernel_t phase_kernel(int ph) {
     case PH_FINAL_NORM: return k_final_norm;
     case PH_LM_HEAD: return k_lm_head;
     case PH_ATTN_COMBINE: return k_attention_combine;
+    case PH_QKV_RED: return k_qkv_reduce;
+    case PH_OPROJ_RED: return k_oproj_reduce;
+    case PH_DOWN_RED: return k_down_reduce;
     default: return k_sample_publish;
   }
 }
@@ -166,7 +172,7 @@ struct blink_engine {
   SlotStatus* stage_empty = nullptr;   // pinned zero status
   // loop
   std::thread launcher;
-  hipGraphExec_t iter_graph = nullptr;
+  hipGraphExec_t iter_graph = nullptr;        // the kernel chain of one iteration
   int timed_phase = -1;                 // phase whose launches are bracketed by HIP events (-1: none)
   std::vector<hipEvent_t> phase_ev;     // [depth][n_layers][2]
   std::vector<float> phase_ms;          // per enqueued iteration of the current window: summed duration
@@ -398,6 +404,12 @@ static int init_impl(const blink_config* cfg, blink_engine* e) {
     if (int rc = dalloc(e, &c.hq, tile_tokens * c.F)) return rc;
     if (int rc = dalloc(e, &c.ssq, tile_tokens * (c.d / 16))) return rc;
     if (int rc = dalloc(e, &c.qbuf, (u64)c.maxT * c.nq * c.hd)) return rc;
+    if (c.max_batch > 64 && ((cfg->tune >> 28) & 3u) == 2u) {   // the chain with K split across workgroups: up to eight K slices of the widest split GEMM at 256 tokens
+      c.splitk_ok = 1;
+      const u64 rows = ((std::max<u64>(c.qkv_n, c.d) + 127) / 128) * 128;
+      c.gemm_part_cap = 8ull * rows * 256;
+      if (int rc = dalloc(e, &c.gemm_part, c.gemm_part_cap, false)) return rc;
+    }
     {
       const u64 chunks = (u64)c.max_batch * ((c.max_seq_len + ATTN_CHUNK_TOKENS - 1) / ATTN_CHUNK_TOKENS), G = c.nq / c.nkv;
       if (int rc = dalloc(e, &c.attn_part_o, chunks * c.nkv * G * c.hd)) return rc;
@@ -530,36 +542,47 @@ extern "C" int blink_submit(blink_engine* e, const int32_t* prompt, uint32_t n_p
 // The host thread is a pump: it enqueues the fixed kernel chain of one iteration, several iterations ahead,
 // and never reads a result the device waits for. Every decision (what runs, on which shapes, when the window
 // ends) is taken on the device; an iteration enqueued after the window has ended costs a few empty kernels.
-static int launch_phase(blink_engine* e, hipStream_t st, int ph, u32 layer, u64 enq_index) {
+static bool has_split_chain(const blink_engine* e) { return e->ctx.dtype == 1 && e->ctx.splitk_ok != 0; }
+
+static bool phase_per_layer(int ph) { return (ph >= PH_LAYER_FIRST && ph <= PH_LAYER_LAST) || ph >= PH_ATTN_COMBINE; }
+
+static int launch_phase(blink_engine* e, const DevCtx& ctx, hipStream_t st, int ph, u32 layer, u64 enq_index) {
   if (e->ctx.dtype == 1 && (ph == PH_NORM1 || ph == PH_NORM2 || ph == PH_FINAL_NORM || ph == PH_ROPE)) return 0;   // fused into the GEMMs
   const bool timed = e->timed_phase == ph && enq_index != ~0ull;
   hipEvent_t a = nullptr, b = nullptr;
   if (timed) {
-    const u64 slot = (enq_index % e->events.size()) * e->ctx.n_layers + (ph >= PH_LAYER_FIRST && ph <= PH_LAYER_LAST ? layer : 0);
+    const u64 slot = (enq_index % e->events.size()) * e->ctx.n_layers + (phase_per_layer(ph) ? layer : 0);
     a = e->phase_ev[2 * slot];
     b = e->phase_ev[2 * slot + 1];
     HIPCHK(hipEventRecord(a, st));
   }
   const bool wide = ph == PH_ATTN || ph == PH_QKV || ph == PH_OPROJ || ph == PH_DOWN;
   const u32 threads = (wide && e->ctx.dtype == 1) ? 512u : (u32)BLK_THREADS;
-  hipLaunchKernelGGL(phase_kernel(ph), dim3(e->grid), dim3(threads), 0, st, e->ctx, layer);
+  hipLaunchKernelGGL(phase_kernel(ph), dim3(e->grid), dim3(threads), 0, st, ctx, layer);
   if (timed) HIPCHK(hipEventRecord(b, st));
   return 0;
 }
 
+// The kernel chain of one iteration. An engine made with bits 28-29 of blink_config.tune = 2 runs the chain that lets
+// the narrow GEMMs split K across workgroups when the iteration has 65..256 tokens; it carries a reduce kernel behind
+// each of them (three more launches per layer, which do nothing in other iterations). Measured on the llama3_8b shape at
+// 256 tokens, the second kernel costs what the split saves (QKV 60 -> 32 + 21 us, attention output 32 -> 26 + 14 us,
+// down 69 -> 54 + 14 us), so the default chain does not split.
 static int enqueue_iteration_kernels(blink_engine* e, hipStream_t st, u64 enq_index) {
+  const bool split = has_split_chain(e);
   const DevCtx& c = e->ctx;
   hipLaunchKernelGGL(k_sched, dim3(1), dim3(BLK_THREADS), 0, st, c);
-  if (int rc = launch_phase(e, st, PH_EMBED, 0, enq_index)) return rc;
+  if (int rc = launch_phase(e, c, st, PH_EMBED, 0, enq_index)) return rc;
   for (u32 l = 0; l < c.n_layers; ++l)
     for (int ph = PH_LAYER_FIRST; ph <= PH_LAYER_LAST; ++ph) {
-      if (int rc = launch_phase(e, st, ph, l, enq_index)) return rc;
-      if (ph == PH_ATTN && c.dtype == 1)
-        if (int rc = launch_phase(e, st, PH_ATTN_COMBINE, l, enq_index)) return rc;
+      if (int rc = launch_phase(e, c, st, ph, l, enq_index)) return rc;
+      const int after = ph == PH_ATTN ? PH_ATTN_COMBINE : ph == PH_QKV ? PH_QKV_RED : ph == PH_OPROJ ? PH_OPROJ_RED : ph == PH_DOWN ? PH_DOWN_RED : -1;
+      if (c.dtype == 1 && after >= 0 && (after == PH_ATTN_COMBINE || split))
+        if (int rc = launch_phase(e, c, st, after, l, enq_index)) return rc;
     }
-  if (int rc = launch_phase(e, st, PH_FINAL_NORM, 0, enq_index)) return rc;
-  if (int rc = launch_phase(e, st, PH_LM_HEAD, 0, enq_index)) return rc;
-  if (int rc = launch_phase(e, st, PH_SAMPLE, 0, enq_index)) return rc;
+  if (int rc = launch_phase(e, c, st, PH_FINAL_NORM, 0, enq_index)) return rc;
+  if (int rc = launch_phase(e, c, st, PH_LM_HEAD, 0, enq_index)) return rc;
+  if (int rc = launch_phase(e, c, st, PH_SAMPLE, 0, enq_index)) return rc;
   HIPCHK(hipGetLastError());
   return 0;
 }
@@ -588,7 +611,7 @@ static int enqueue_iteration(blink_engine* e, u64 enq_index) {
 // durations of the timed phase for the iteration enqueued at enq_index (its events have completed)
 static void harvest_phase_times(blink_engine* e, u64 enq_index) {
   if (e->timed_phase < 0) return;
-  const bool per_layer = e->timed_phase >= PH_LAYER_FIRST && e->timed_phase <= PH_LAYER_LAST;
+  const bool per_layer = phase_per_layer(e->timed_phase);
   const u32 n = per_layer ? e->ctx.n_layers : 1;
   float sum = 0.f;
   for (u32 l = 0; l < n; ++l) {
@@ -841,7 +864,7 @@ extern "C" int blink_time_phase(blink_engine* e, int32_t phase) {
   g_err.clear();
   if (!e) return fail(BLINK_ERR_INVAL, "null engine");
   if (e->loop_active.load()) return fail(BLINK_ERR_STATE, "stop the loop first");
-  if (phase < -1 || phase > PH_ATTN_COMBINE) return fail(BLINK_ERR_INVAL, "phase out of range");
+  if (phase < -1 || phase > PH_DOWN_RED) return fail(BLINK_ERR_INVAL, "phase out of range");
   e->timed_phase = phase;
   return BLINK_OK;
 }

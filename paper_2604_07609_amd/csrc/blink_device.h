@@ -76,6 +76,7 @@ struct SchedState {
   u32 error;
   u32 pad;
   u64 iter_limit;       // the window ends once `iteration` reaches this (0: no limit); set at blink_run
+  u64 chains;           // scheduler kernels run so far (iterations, idle polls and launches past the end of a window)
 };
 
 // batch metadata of the current iteration (what the scheduler populates before the forward pass)
@@ -97,6 +98,7 @@ struct TraceRec {       // mirrors blink_trace_record
   u64 first_admitted;
   u64 t_sched_begin, t_sched_end, t_forward_end, t_publish_end;
   u64 ctx_tokens;
+  u64 chain;
 };
 
 // host-visible mirror in pinned host memory, written by the scheduler with system-scope stores
@@ -193,6 +195,10 @@ struct DevCtx {
   float* ssq;           // [token][d/16] partial sums of squares of the residual stream
   u32 TBS;              // token-block stride of the packed activation buffers
   u32 tune_nw;          // tuning knob of the streaming GEMM (0: automatic)
+  // GEMMs with K split across workgroups (decode iterations of 65..256 tokens): the slices' fp32 partial sums
+  float* gemm_part;
+  u64 gemm_part_cap;    // floats
+  u32 splitk_ok;        // 1: the engine's kernel chain carries the reduce kernels (a chain without them never splits)
   // decode attention: partial (max, sum, output) of every chunk of a context longer than one chunk
   float* attn_part_o;   // [chunk][kv head][G][hd]
   float* attn_part_ml;  // [chunk][kv head][G][2]

@@ -65,12 +65,18 @@ struct MfmaGemmArgs {
   f16_t* Kc;               // this layer's K cache and V cache (half precision)
   f16_t* Vc;
   u32 nq, nkv, hd, bs;
+  // K split across workgroups (decode iterations of 65..256 tokens in the projections with few rows): the tile kernel
+  // leaves fp32 partial sums per K slice here, gemm_splitk_reduce adds them in slice order and runs the epilogue
+  float* part;             // [slice][row tile][token block of 16][lane][4]; null: never split
+  u64 part_cap;            // floats
   u32 tune_nw;             // tests and tuning. Low byte: 0 automatic choice of weight tiles per workgroup, 1/2/4 forced.
                            // Bit 9: tile schedule with direct loads instead of LDS staging (bit 8: its 256-token
                            // workgroup tile in eight-wave kernels). Bit 10: no split of K between workgroup halves.
                            // Bit 11: no 64 x 64 streaming items for 64 < T <= 256. Bits 12-14: 2, 3, 4 or 6 force the
                            // token tiles per wave of the LDS-staged tile schedule, 7 its 256-token tile. Bit 20: eight-wave kernels never
                            // take the pair of tiles with shared weight tiles. Bit 21: no tiles wider than 128 tokens.
+                           // Bits 24-27: K slices of the split across workgroups (1: never split; 0: automatic).
+                           // (Bits 28-29 are read at init: 2 builds the kernel chain with the reduce kernels; only it splits K.)
 };
 
 #define GEMM_MAX_WAVES 8
@@ -431,6 +437,24 @@ __device__ __forceinline__ void tile_coords(u32 i, u32 nblocks, u32 tblocks, u32
   tb = g * 8 + rem % width;
 }
 
+// ---- K split across workgroups ---------------------------------------------------------------------------------------
+// With 65..256 tokens a projection of 4096..6144 rows has only 64..96 tiles of 128 x 128, a quarter of the tile slots of
+// the chip (two four-wave tiles per compute unit). Splitting K into S slices gives every slot an item; the partial sums
+// (fp32, in the accumulators' own layout: 1 KB per 16 x 16 tile and slice, written and read with 16-byte lane accesses)
+// stay in the L2s and the memory-side cache, and a second kernel adds them in slice order (fixed: the result does not
+// depend on timing) and runs the epilogue. Returns the number of slices for this launch, 0 for "not split"; the GEMM
+// kernel and its reduce kernel are launched with the same grid and derive the same number.
+__device__ __forceinline__ u32 splitk_slices(const MfmaGemmArgs& a, u32 nwg, u32 gemm_threads) {
+  if (a.part == nullptr || a.T <= 64 || a.T > 256 || a.tok_index != nullptr || gemm_threads != 512) return 0;
+  const u32 KT = a.K / 32, nblocks = ((a.N + 15) / 16 + 7) / 8, tblocks = (a.T + 127) / 128, tiles = nblocks * tblocks;
+  const u32 forced = (a.tune_nw >> 24) & 15u;
+  u32 S = forced ? forced : min(8u, max(1u, nwg / tiles));   // tile slots resident at once: one eight-wave workgroup per CU, nwg = 2 per CU
+  // both halves of a workgroup run the same number of k-steps (they share the barriers): slices of equal length, or an
+  // even number of tiles (then the two halves' items always lie in one slice); at least eight k-steps per slice
+  while (S > 1 && (KT / S < 8 || ((tiles & 1u) && KT % S) || (u64)S * nblocks * 8 * tblocks * 8 * 256 > a.part_cap)) --S;
+  return S > 1 ? S : 0u;
+}
+
 // ---- tile schedule through LDS: T > 64 ---------------------------------------------------------------------------
 // 128 rows x 128 tokens per four waves (64 x 64 per wave). Every k-step, the four waves fetch the step's eight weight
 // tiles and eight activation tiles from global memory once (two steps ahead, in registers), store them into one of two
@@ -440,8 +464,10 @@ __device__ __forceinline__ void tile_coords(u32 i, u32 nblocks, u32 tblocks, u32
 // (separate LDS buffers, common barriers).
 // TJ (2, 3 or 4): token tiles per wave; the workgroup tile is 128 rows x 32 TJ tokens. Narrower tiles cost more operand
 // traffic per flop but cut the tile grid finer: gemm_tile_pick takes the width whose rounds of workgroups finish first.
-template <int EPI, int TJ>
-__device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg) {
+// PART: K is split into `slices` slices across work items (splitk_slices); an item accumulates one slice of one tile and
+// stores the raw sums to a.part instead of running the epilogue.
+template <int EPI, int TJ, bool PART = false>
+__device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg, u32 slices = 1) {
   constexpr u32 BT = 32 * TJ, XT = 2 * TJ;        // tokens and activation tiles of a workgroup tile
   // bytes of one LDS buffer; the 192-token tile (TJ = 6, 20 KB per buffer) takes both halves' space and so runs in
   // four-wave workgroups only
@@ -464,17 +490,20 @@ __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared&
   // first's through LDS before the epilogue (fixed order, so the result does not depend on timing).
   // (rounds of workgroups, one per CU: a tile takes a workgroup half as long when its halves share it)
   const u32 ncu = nwg / 2, rounds_split = (total + ncu - 1) / ncu, rounds_pair = ((total + 1) / 2 + ncu - 1) / ncu;
-  const bool splitk = TJ <= 4 && halves == 2 && (KT & 1u) == 0 && rounds_split < 2 * rounds_pair && !(a.tune_nw & 0x400u);   // bit 10: never (tests)
+  const bool splitk = !PART && TJ <= 4 && halves == 2 && (KT & 1u) == 0 && rounds_split < 2 * rounds_pair && !(a.tune_nw & 0x400u);   // bit 10: never (tests)
   const u32 per_item = splitk ? 1u : halves;
-  const u32 k0 = (splitk && half) ? KT / 2 : 0u, kn = splitk ? KT / 2 : KT, klast = k0 + kn - 1;
-  const u32 nitems = (total + per_item - 1) / per_item;
+  const u32 S = PART ? slices : 1u, all_items = total * S;      // items in slice-major order: tile = item % total
+  const u32 nitems = (all_items + per_item - 1) / per_item;
   for (u32 base = 0; base < nitems; base += nwg) {
     const u32 it = xcd_item(base, nitems, wg, nwg);
     if (it == ~0u) continue;
     const u32 item = splitk ? it : it * halves + half;
-    const bool valid = item < total;            // the spare half of the last pair computes a duplicate and drops it
+    const bool valid = item < all_items;        // the spare half of the last pair computes a duplicate and drops it
+    const u32 ks = min(item, all_items - 1) / total;   // (the spare half walks its partner's slice: same number of k-steps)
+    const u32 k0 = PART ? (u32)((u64)KT * ks / S) : ((splitk && half) ? KT / 2 : 0u);
+    const u32 kn = PART ? (u32)((u64)KT * (ks + 1) / S) - k0 : (splitk ? KT / 2 : KT), klast = k0 + kn - 1;
     u32 tb = 0, nb = 0;
-    if (valid) tile_coords(item, nblocks, tblocks, nb, tb);
+    if (valid) tile_coords(item % total, nblocks, tblocks, nb, tb);
     const u32 nt0 = nb * 8 + wn * 4;
     const bf16_t* const gw0 = a.Wp + (u64)min(nb * 8 + wl * 2, NT - 1) * w_stride + lane * 8;
     const bf16_t* const gw1 = a.Wp + (u64)min(nb * 8 + wl * 2 + 1, NT - 1) * w_stride + lane * 8;
@@ -529,12 +558,14 @@ __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared&
     struct Ops { f16x8_t w0, w1, w2, w3, x0, x1, x2, x3, x4, x5; };
     Ops oa, ob;
     TL_GLOAD(ga, 0) TL_GLOAD(gb, 1)             // in flight while the norm scales are computed
-    for (u32 h = 0; h < per_item; ++h) {
-      const u32 ih = it * per_item + h;
-      u32 tbh = 0, nbh = 0;
-      if (ih < total) tile_coords(ih, nblocks, tblocks, nbh, tbh);
-      compute_rstd(a, tbh * BT, BT, sh, h * 128);   // its barriers: the LDS tiles are free
-    }
+    if (PART) __syncthreads();                  // the previous item's last reads of the LDS tiles are done (the norm scales belong to the reduce kernel)
+    else
+      for (u32 h = 0; h < per_item; ++h) {
+        const u32 ih = it * per_item + h;
+        u32 tbh = 0, nbh = 0;
+        if (ih < total) tile_coords(ih, nblocks, tblocks, nbh, tbh);
+        compute_rstd(a, tbh * BT, BT, sh, h * 128);   // its barriers: the LDS tiles are free
+      }
     TL_STORE(ga, 0) TL_STORE(gb, 1) TL_GLOAD(ga, 2) TL_GLOAD(gb, 3)
     __syncthreads();
     oa.w0 = TL_RW(0, 0); oa.w1 = TL_RW(0, 1); oa.w2 = TL_RW(0, 2); oa.w3 = TL_RW(0, 3);
@@ -568,6 +599,17 @@ __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared&
           for (int j = 0; j < TJ; ++j) acc[i][j] += *(const floatx4_t*)(red + (i * 4 + (j & 3)) * 256);
       }
     }
+    if (PART) {
+      if (valid) {
+        const u32 NTp = nblocks * 8, TBp = tblocks * (BT / 16);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < TJ; ++j)
+            *(floatx4_t*)(a.part + ((((u64)ks * NTp + nt0 + i) * TBp + tb * (BT / 16) + wt * TJ + j) * 64 + lane) * 4) = acc[i][j];
+      }
+      continue;
+    }
     const u32 rstd_off = splitk ? 0u : half * 128;
     if (valid && !(splitk && half)) {
 #pragma unroll
@@ -577,6 +619,41 @@ __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared&
           for (int j = 0; j < TJ; ++j)
             epilogue_tile<EPI>(a, acc[i][j], nt0 + i, tb * BT + (wt * TJ + j) * 16, &sh.rstd[rstd_off + (wt * TJ + j) * 16]);
         }
+    }
+  }
+}
+
+// Second kernel of a GEMM whose K was split across workgroups: adds the slices' partial sums in slice order and runs the
+// epilogue. Work item: (block of 16 tokens, group of row tiles); every wave takes two row tiles of the group and has
+// all their slices' loads in flight together. Launched with four waves per workgroup and the grid of the GEMM kernel.
+template <int EPI>
+__device__ __forceinline__ void gemm_splitk_reduce(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg, u32 gemm_threads) {
+  const u32 S = splitk_slices(a, nwg, gemm_threads);   // gemm_threads: block size of the GEMM kernel (this kernel runs four waves)
+  if (S == 0) return;
+  const u32 NT = (a.N + 15) / 16, nblocks = (NT + 7) / 8, tblocks = (a.T + 127) / 128;
+  const u32 lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  const u32 NTp = nblocks * 8, TBp = tblocks * 8, TB16 = (a.T + 15) / 16;
+  constexpr u32 RPW = 2;
+  const u32 groups = (NT + nw * RPW - 1) / (nw * RPW);
+  for (u32 item = wg; item < TB16 * groups; item += nwg) {
+    const u32 tb = item % TB16, g = item / TB16;
+    floatx4_t v[RPW][8];
+#pragma unroll
+    for (u32 r = 0; r < RPW; ++r) {
+      const u32 nt = min((g * nw + w) * RPW + r, NT - 1);
+#pragma unroll
+      for (u32 s = 0; s < 8; ++s)
+        v[r][s] = *(const floatx4_t*)(a.part + ((((u64)min(s, S - 1) * NTp + nt) * TBp + tb) * 64 + lane) * 4);
+    }
+    compute_rstd(a, tb * 16, 16, sh);       // (its barriers also separate the items' uses of sh.rstd)
+#pragma unroll
+    for (u32 r = 0; r < RPW; ++r) {
+      const u32 nt = (g * nw + w) * RPW + r;
+      floatx4_t sum = v[r][0];
+#pragma unroll
+      for (u32 s = 1; s < 8; ++s)
+        if (s < S) sum += v[r][s];
+      if (nt < NT) epilogue_tile<EPI>(a, sum, nt, tb * 16, &sh.rstd[0]);
     }
   }
 }
@@ -853,6 +930,10 @@ __device__ __forceinline__ void gemm_stream_nw(const MfmaGemmArgs& a, MfmaShared
 template <int EPI, bool WIDE>
 __device__ __forceinline__ void gemm_mfma(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg) {
   if (a.T == 0) return;
+  if (WIDE) {
+    const u32 S = splitk_slices(a, nwg, blockDim.x);
+    if (S) { gemm_tile_lds<EPI, 4, true>(a, sh, wg, nwg, S); return; }
+  }
   if (a.T <= 16) gemm_stream_nw<EPI, 1, WIDE>(a, sh, wg, nwg);
   else if (a.T <= 32) gemm_stream_nw<EPI, 2, WIDE>(a, sh, wg, nwg);
   else if (a.T <= 48) gemm_stream_nw<EPI, 3, WIDE>(a, sh, wg, nwg);

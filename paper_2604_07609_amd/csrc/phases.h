@@ -13,7 +13,8 @@ enum {
   PH_EMBED = 0,
   PH_NORM1, PH_QKV, PH_ROPE, PH_ATTN, PH_OPROJ, PH_NORM2, PH_GATEUP, PH_DOWN,   // per layer
   PH_FINAL_NORM, PH_LM_HEAD, PH_SAMPLE,
-  PH_ATTN_COMBINE   // bf16 path only, directly after PH_ATTN of the same layer
+  PH_ATTN_COMBINE,  // bf16 path only, directly after PH_ATTN of the same layer
+  PH_QKV_RED, PH_OPROJ_RED, PH_DOWN_RED   // bf16 path, chains with K split across workgroups: second kernel of that GEMM
 };
 #define PH_LAYER_FIRST PH_NORM1
 #define PH_LAYER_LAST PH_DOWN
@@ -84,31 +85,42 @@ __device__ __forceinline__ void run_phase_bf16(const DevCtx& c, int ph, u32 laye
   a.TBS = c.TBS;
   a.eps = c.eps;
   a.tune_nw = c.tune_nw;
+  a.part = c.splitk_ok ? c.gemm_part : nullptr;
+  a.part_cap = c.gemm_part_cap;
+  if (ph == PH_QKV_RED || ph == PH_OPROJ_RED || ph == PH_DOWN_RED) {
+    if (a.part == nullptr || a.T <= 64 || a.T > 256) return;    // this iteration's GEMMs did not split K
+  }
   switch (ph) {
     case PH_EMBED: phase_embed_packed(c, wg, nwg); break;
     case PH_QKV:
+    case PH_QKV_RED:
       a.Wp = P->wqkv; a.Xp = c.xq; a.N = c.qkv_n; a.K = c.d; a.ssq_in = c.ssq;
       a.positions = c.positions; a.slot_mapping = c.slot_mapping; a.rope_tab = c.rope_tab; a.qbuf = c.qbuf;
       a.Kc = (f16_t*)c.kv + (u64)layer * c.kv_layer_stride; a.Vc = a.Kc + c.kv_kv_stride;
       a.nq = c.nq; a.nkv = c.nkv; a.hd = c.hd; a.bs = c.bs;
-      gemm_mfma<EPI_QKV_ROPE, true>(a, sh.mfma, wg, nwg);
+      if (ph == PH_QKV) gemm_mfma<EPI_QKV_ROPE, true>(a, sh.mfma, wg, nwg);
+      else gemm_splitk_reduce<EPI_QKV_ROPE>(a, sh.mfma, wg, nwg, 512);
       break;
     case PH_ATTN: phase_attention_mfma(c, layer, sh.attn_mfma, wg, nwg); break;
     case PH_ATTN_COMBINE: attn_decode_combine(c, wg, nwg); break;
     case PH_OPROJ:
+    case PH_OPROJ_RED:
       a.Wp = P->wo; a.Xp = c.aq; a.N = c.d; a.K = c.nq * c.hd; a.x = c.x; a.ldx = c.d; a.g_next = c.layers[layer].g2;
       a.Xp_next = c.xq; a.ssq_out = c.ssq;
-      gemm_mfma<EPI_RESIDUAL, true>(a, sh.mfma, wg, nwg);
+      if (ph == PH_OPROJ) gemm_mfma<EPI_RESIDUAL, true>(a, sh.mfma, wg, nwg);
+      else gemm_splitk_reduce<EPI_RESIDUAL>(a, sh.mfma, wg, nwg, 512);
       break;
     case PH_GATEUP:
       a.Wp = P->wgu; a.Xp = c.xq; a.N = 2 * c.F; a.K = c.d; a.ssq_in = c.ssq; a.Hp = c.hq;
       gemm_mfma<EPI_SILU_GATE, false>(a, sh.mfma, wg, nwg);
       break;
     case PH_DOWN:
+    case PH_DOWN_RED:
       a.Wp = P->wd; a.Xp = c.hq; a.N = c.d; a.K = c.F; a.x = c.x; a.ldx = c.d;
       a.g_next = layer + 1 < c.n_layers ? c.layers[layer + 1].g1 : c.gf;
       a.Xp_next = c.xq; a.ssq_out = c.ssq;
-      gemm_mfma<EPI_RESIDUAL, true>(a, sh.mfma, wg, nwg);
+      if (ph == PH_DOWN) gemm_mfma<EPI_RESIDUAL, true>(a, sh.mfma, wg, nwg);
+      else gemm_splitk_reduce<EPI_RESIDUAL>(a, sh.mfma, wg, nwg, 512);
       break;
     case PH_LM_HEAD:
       a.Wp = c.lm_p; a.Xp = c.xq; a.N = c.V; a.K = c.d; a.T = m->n_seqs; a.tok_index = c.last_idx; a.ssq_in = c.ssq;

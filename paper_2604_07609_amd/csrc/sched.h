@@ -32,6 +32,7 @@ struct SchedShared {
   u32 seq_ring[SCHED_MAX_BATCH];
   u32 flag;
   u32 exit_idle;
+  u64 chain;
 };
 
 // Exclusive prefix sum over the 256 threads of the workgroup; total returned in `total`.
@@ -98,6 +99,9 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
 
   // ---- window gate -----------------------------------------------------------------------------------
   if (tid == 0) {
+    const u64 chain = ss->chains;
+    ss->chains = chain + 1;
+    sh.chain = chain;
     u32 stop = ss->stopped | ss->error;
     const u64 iter_limit = ss->iter_limit;
     if (iter_limit != 0 && ss->iteration >= iter_limit) stop = 1;
@@ -418,6 +422,7 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
         tr.t_forward_end = 0;
         tr.t_publish_end = 0;
         tr.ctx_tokens = n_ctx;
+        tr.chain = sh.chain;
       }
     } else {
       if (ss->idle_since_ns == 0) ss->idle_since_ns = now;

@@ -4,9 +4,10 @@
   python -m paper_2604_07609_amd.profile_summary pmc <fetch.csv> <write.csv> <iterations.txt> <kernel> <workload> "<cmd>"
   python -m paper_2604_07609_amd.profile_summary sq <counters.csv> <iterations.txt> <workload> "<command>"
 
-`iterations.txt` is what `bench.py --dump-iterations` wrote in the same run: the kind of every iteration. The dispatches
-in the CSV are cut into iterations at the scheduler kernel; iterations whose forward kernels do nothing (the launcher's
-look-ahead past the end of a window) are dropped, and the rest line up one to one with the lines of the file.
+`iterations.txt` is what `bench.py --dump-iterations` wrote in the same run: the kind of every iteration and the ordinal
+of the scheduler kernel launch that ran it. The dispatches in the CSV are cut into chains at the scheduler kernel; the
+n-th chain of the profile is the one whose scheduler launch has ordinal n, so every iteration finds its dispatches
+whatever the launcher enqueued past the end of a window.
 `trace`: per-kernel totals (what `--stats` prints) and the named kernel's average launch duration in the decode and in
 the prefill iterations of the timed window. `pmc`: HBM bytes per launch of the named kernel in the timed decode
 iterations from FETCH_SIZE and WRITE_SIZE (KiB per dispatch), each scaled by what the same counter reads for the
@@ -30,14 +31,13 @@ def read_kinds(path):
     for line in open(path):
         if line.startswith("#"):
             continue
-        it, kind, n_seqs, n_tokens, ctx, timed = (int(x) for x in line.split())
-        out.append(dict(kind=kind, n_seqs=n_seqs, n_tokens=n_tokens, ctx_tokens=ctx, timed=timed))
+        it, kind, n_seqs, n_tokens, ctx, timed, chain = (int(x) for x in line.split())
+        out.append(dict(kind=kind, n_seqs=n_seqs, n_tokens=n_tokens, ctx_tokens=ctx, timed=timed, chain=chain))
     return out
 
 
 def split_iterations(rows, value, order):
-    """rows -> list of iterations (lists of (kernel, value)); an iteration starts at k_sched. real_iterations drops the
-    look-ahead iterations, in which no forward kernel does anything: `value` of all their dispatches stays under a floor."""
+    """rows -> list of chains (lists of (kernel, value)) in launch order; a chain starts at k_sched."""
     rows = sorted(rows, key=order)
     its, cur = [], None
     for r in rows:
@@ -50,8 +50,11 @@ def split_iterations(rows, value, order):
     return its
 
 
-def real_iterations(its, floor):
-    return [it for it in its if max([v for _, v in it] or [0.0]) > floor]
+def real_iterations(its, kinds):
+    """The chains of the recorded iterations, in the order of `kinds`; [] when a chain is missing from the profile."""
+    if any(k["chain"] >= len(its) for k in kinds):
+        return []
+    return [its[k["chain"]] for k in kinds]
 
 
 def trace_summary(path, kinds_path, kernel, workload, command):
@@ -67,14 +70,32 @@ def trace_summary(path, kinds_path, kernel, workload, command):
     kinds = read_kinds(kinds_path)
     its = split_iterations(rows, lambda r: (int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3,
                            lambda r: int(r["Start_Timestamp"]))
-    its = real_iterations(its, 8.0)                    # us: an empty launch takes 2-5 us under the profiler
-    out += ["", "iterations with work in the trace: %d; iterations bench.py recorded: %d" % (len(its), len(kinds))]
+    its = real_iterations(its, kinds)
+    out += ["", "iterations found in the trace by their scheduler launch: %d; iterations bench.py recorded: %d" % (len(its), len(kinds))]
     if len(its) == len(kinds):
         for label, kind in (("decode", 2), ("prefill", 1)):
             sel = [v for it, k in zip(its, kinds) if k["timed"] and k["kind"] == kind for n, v in it if n == kernel]
             if sel:
                 out.append("%s, launches in the timed %s iterations: %d, average %.2f us" % (kernel, label, len(sel), sum(sel) / len(sel)))
         out.append("(bench.py measures the same launches with HIP events and reports them as roofline.avg_launch_us)")
+        out += ["", "every kernel of the chain, average us per launch in the timed iterations (and launches per iteration):", "",
+                "| kernel | decode | prefill |", "|---|---|---|"]
+        names = []
+        for it in its:
+            for n, _ in it:
+                if n not in names:
+                    names.append(n)
+        for nm in names:
+            cells = []
+            for kind in (2, 1):
+                sel = [v for it, k in zip(its, kinds) if k["timed"] and k["kind"] == kind for n, v in it if n == nm]
+                nit = sum(1 for k in kinds if k["timed"] and k["kind"] == kind)
+                cells.append("%.2f (x%d)" % (sum(sel) / len(sel), round(len(sel) / max(1, nit))) if sel else "-")
+            out.append("| %s | %s | %s |" % (nm, cells[0], cells[1]))
+        for label, kind in (("decode", 2), ("prefill", 1)):
+            tot = [sum(v for _, v in it) for it, k in zip(its, kinds) if k["timed"] and k["kind"] == kind]
+            if tot:
+                out.append("sum of kernel time per timed %s iteration: %.1f us on average" % (label, sum(tot) / len(tot)))
     else:
         out.append("(counts differ: no split by iteration kind)")
     return "\n".join(out) + "\n"
@@ -101,8 +122,8 @@ def sq_summary(path, kinds_path, workload, command):
             its.append(cur)
         elif cur is not None and n.startswith("k_") and n not in ("k_copy_calibration", "k_mfma_calibration", "k_pack_weights", "k_rope_table", "k_open_window"):
             cur.append((n, d))
-    its = [it for it in its if max([d.get("SQ_VALU_MFMA_BUSY_CYCLES", 0.0) for _, d in it] or [0.0]) > 0.0]   # look-ahead iterations issue no MFMA
     kinds = read_kinds(kinds_path)
+    its = real_iterations(its, kinds)
     out = ["# rocprofv3 --pmc (SQ counters): where the waves of each kernel spend their cycles, %s" % workload, "", "command: `%s`" % command, "",
            "Shares of SQ_WAVE_CYCLES over the launches of the timed iterations. MFMA / loop = the MFMA share relative to the",
            "register-only MFMA loop of the same run (%s of its wave cycles): the matrix cores' utilisation over the kernel's time." % ("%.2f" % ref if ref else "n/a"), ""]
@@ -140,7 +161,7 @@ def pmc_summary(fetch_path, write_path, kinds_path, kernel, workload, command):
                 if short(r["Kernel_Name"]) == "k_copy_calibration"]
         factor = COPY_BYTES / 1024.0 / copy[0]
         its = split_iterations(rows, lambda r: float(r["Counter_Value"]), lambda r: int(r["Dispatch_Id"]))
-        its = real_iterations(its, 64.0)                 # KiB: an empty launch moves next to nothing
+        its = real_iterations(its, kinds)
         if len(its) != len(kinds):
             out.append("%s: %d iterations with work in the counters, %d recorded by bench.py: no traffic figure" % (label, len(its), len(kinds)))
             continue

@@ -51,8 +51,7 @@ def check_against_oracle(cfg, W, eng, reqs, ev, trace, rtol, tails=None, tok_rto
     gpu = {}
     for x in ev:
         gpu[(int(x["request_id"]), int(x["index"]))] = int(x["token"])
-    sched = Scheduler(eng["kv_num_blocks"], eng["kv_block_size"], eng["max_batch"], eng["max_prefill_tokens"],
-                      eng["ring_slots"], eng.get("eos_token_id", -1))
+    sched = Scheduler.from_engine(eng)
     kv = M.PagedKV(cfg, eng["kv_num_blocks"], eng["kv_block_size"])
     stats = dict(tokens=0, near_ties=0, greedy_tokens=0, greedy_near_ties=0, sampled_tokens=0, sampled_undecided=0, plans=[])
 
@@ -61,7 +60,7 @@ def check_against_oracle(cfg, W, eng, reqs, ev, trace, rtol, tails=None, tok_rto
                                  plan.block_tables, plan.last_idx)
         stats["plans"].append(plan)
         out = []
-        for i, t in enumerate(plan.tickets):
+        for i, t in enumerate(plan.sample_tickets):
             r = reqs[t]
             g = gpu[(t, plan.gen_index[i])]
             row = logits[i]
@@ -92,7 +91,7 @@ def check_against_oracle(cfg, W, eng, reqs, ev, trace, rtol, tails=None, tok_rto
 
     events = run_schedule(sched, reqs, token_fn, tails=tails)
     exp = [(it, t, idx, tok, first, last) for (it, t, idx, tok, first, last) in events]
-    got = sorted(event_tuples(ev), key=lambda e: (e[0], next(i for i, b in enumerate(stats["plans"][e[0]].tickets) if b == e[1])))
+    got = sorted(event_tuples(ev), key=lambda e: (e[0], next(i for i, b in enumerate(stats["plans"][e[0]].sample_tickets) if b == e[1])))
     assert got == exp
     assert len(trace) == len(stats["plans"])
     for tr, pl in zip(trace, stats["plans"]):
@@ -194,8 +193,7 @@ def stepwise_check(B, cfg, eng, raw, blob, reqs, rtol, max_iters=10000, tune=0):
     the engine's own token history; every token against the oracle's sampler run on the engine's own logits
     (so sampling is checked exactly, apart from the logit tolerance). Returns the worst relative logit error."""
     W = M.Weights(cfg, raw)
-    sched = Scheduler(eng["kv_num_blocks"], eng["kv_block_size"], eng["max_batch"], eng["max_prefill_tokens"],
-                      eng["ring_slots"], eng.get("eos_token_id", -1))
+    sched = Scheduler.from_engine(eng)
     kv = M.PagedKV(cfg, eng["kv_num_blocks"], eng["kv_block_size"])
     for r in reqs:
         sched.submit(r["prompt"], r["max_new_tokens"])
@@ -226,16 +224,17 @@ def stepwise_check(B, cfg, eng, raw, blob, reqs, rtol, max_iters=10000, tune=0):
                 assert list(bt[b][: len(blocks)]) == blocks
             ref = M.paged_forward(cfg, W, kv, plan.input_ids, plan.positions, plan.slot_mapping, plan.tok_seq,
                                   plan.block_tables, plan.last_idx)
-            got = e.debug_read(D.LOGITS, np.float32).reshape(len(plan.tickets), cfg["vocab"])
-            err = np.abs(got - ref).max(axis=1) / np.abs(ref).max(axis=1)
-            worst = max(worst, float(err.max()))
-            assert err.max() < rtol, (it, err)
             evs = e.drain()
             by_ticket = {int(x["request_id"]): int(x["token"]) for x in evs}
-            assert sorted(by_ticket) == sorted(plan.tickets)
-            for i, t in enumerate(plan.tickets):
-                token_matches_own_logits(got[i], reqs[t], plan.gen_index[i], by_ticket[t])
-            sched.commit(plan, [by_ticket[t] for t in plan.tickets])   # the engine's tokens are the history
+            assert sorted(by_ticket) == sorted(plan.sample_tickets)
+            if plan.sample_seq:
+                got = e.debug_read(D.LOGITS, np.float32).reshape(len(plan.sample_seq), cfg["vocab"])
+                err = np.abs(got - ref).max(axis=1) / np.abs(ref).max(axis=1)
+                worst = max(worst, float(err.max()))
+                assert err.max() < rtol, (it, err)
+                for i, t in enumerate(plan.sample_tickets):
+                    token_matches_own_logits(got[i], reqs[t], plan.gen_index[i], by_ticket[t])
+            sched.commit(plan, [by_ticket[t] for t in plan.sample_tickets])   # the engine's tokens are the history
         raise AssertionError("did not finish")
     finally:
         e.shutdown()

@@ -359,3 +359,21 @@ def test_gqa_groups_of_six_and_eight(lib, name):
     res = parity.check_against_oracle(cfg, M.Weights(cfg, raw), eng, reqs, ev, trace, rtol=2e-2, tok_rtol=TOK_RTOL)
     print(name, "end to end: tokens", res["tokens"], "near ties", res["near_ties"])
     assert res["near_ties"] <= res["tokens"] // 8
+
+
+@pytest.mark.parametrize("max_batch,tune", [(250, 2 << 28), (250, (3 << 24) | (2 << 28)), (100, (2 << 24) | (2 << 28)),
+                                            (150, (8 << 24) | (2 << 28))])
+def test_bf16_gemms_with_k_split_across_workgroups(lib, max_batch, tune):
+    """Decode iterations of 65..256 tokens in a model wide enough (d 1024, FFN 4096) for the QKV, attention-output and
+    down projections to split K across workgroups: partial sums per K slice, then the reduce kernel with the epilogue
+    (rotary + KV write, residual + next norm's operand). Bits 24-27 of the tuning word force the number of slices (3:
+    slices of unequal length; 8: capped per GEMM by its K), bits 28-29 = 2 select the kernel chain with the reduce kernels
+    (not the default: at these sizes the second kernel costs what the split saves)."""
+    cfg, eng, raw, blob = setup("mini_churn", 49)
+    eng = dict(eng, max_batch=max_batch, kv_num_blocks=3 * max_batch + 64, ring_slots=512, max_prefill_tokens=4096, max_seq_len=64)
+    reqs = synth.make_workload("mini", cfg["vocab"], 549 + max_batch, n_requests=max_batch + 5)
+    for r in reqs:
+        r["max_new_tokens"] = min(r["max_new_tokens"], 3)
+        r["prompt"] = r["prompt"][:12]
+    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2, tune=tune)
+    print("K split across workgroups: max_batch", max_batch, "tune", hex(tune), "worst relative logit error", worst)

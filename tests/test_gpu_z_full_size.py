@@ -46,8 +46,7 @@ def test_llama3_8b_shape_schedule_exact_and_probe_logits(lib):
         r["arrival_s"] = 0.0
     assert max(len(r["prompt"]) for r in reqs) > 2048 and sum(len(r["prompt"]) for r in reqs) > 3 * eng["max_prefill_tokens"]
 
-    sched = Scheduler(eng["kv_num_blocks"], eng["kv_block_size"], eng["max_batch"], eng["max_prefill_tokens"],
-                      eng["ring_slots"], eng.get("eos_token_id", -1))
+    sched = Scheduler.from_engine(eng)
     for r in reqs:
         sched.submit(r["prompt"], r["max_new_tokens"])
     # the probes alone, for the oracle's model: two requests, a pool that just holds them

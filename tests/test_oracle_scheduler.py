@@ -164,3 +164,112 @@ def test_churn_pool_constant_is_what_the_oracle_side_script_computes():
     reqs = synth.make_workload("churn", cfg["vocab"], 2001)
     assert churn_pool_blocks(reqs, eng["kv_block_size"]) == eng["kv_num_blocks"]
     assert eng["kv_num_blocks"] >= max(blocks_needed(len(r["prompt"]), r["max_new_tokens"], 16) for r in reqs)
+
+
+# ---- chunked prefill with mixed iterations ---------------------------------------------------------------------------
+
+def test_chunked_hand_worked_three_requests_budget_24():
+    """bs 16, 8 blocks, 3 batch slots, 24 tokens per iteration; requests (P, max_new) = (20,2), (30,2), (5,3), all there
+    at the start. Worked by hand from the rules of the chunked mode:
+      it 0: admit A (20 tokens, the whole prompt) and B (the 4 tokens the budget still holds); A samples.
+      it 1: A decodes (1 token), B takes the other 23; nothing is admitted (budget spent); A's second token ends it.
+      it 2: A retires (blocks 0,1 back; slot 0 free); B takes its last 3 tokens; C is admitted into slot 0 with its 5
+            tokens; the sequences run in batch-slot order, so C (slot 0) comes before B (slot 1); both sample.
+      it 3: B and C decode; B ends.   it 4: B retires; C decodes its third token and ends."""
+    s = Scheduler(8, 16, 3, 24, 8, chunked=True)
+    plans = []
+    SV.run_schedule(s, [req(20, 2), req(30, 2), req(5, 3)], lambda pl: [7] * len(pl.sample_seq), on_plan=plans.append)
+    # (kind, tickets, batch slots, first position per sequence, tokens per sequence, sampling tickets, block tables, free after)
+    exp = [
+        (PREFILL, [0, 1], [0, 1], [0, 0], [20, 4], [0], [[0, 1], [2]], 5),
+        (PREFILL, [0, 1], [0, 1], [20, 4], [1, 23], [0], [[0, 1], [2, 3]], 4),
+        (PREFILL, [2, 1], [0, 1], [0, 27], [5, 3], [2, 1], [[1], [2, 3]], 5),     # stack after the retire: .., 0, 1 -> pop gives 1
+        (DECODE, [2, 1], [0, 1], [5, 30], [1, 1], [2, 1], [[1], [2, 3]], 5),
+        (DECODE, [2], [0], [6], [1], [2], [[1]], 7),
+    ]
+    assert len(plans) == len(exp)
+    for pl, e in zip(plans, exp):
+        per_seq = [pl.cu_seqlens[i + 1] - pl.cu_seqlens[i] for i in range(len(pl.tickets))]
+        got = (pl.kind, pl.tickets, pl.batch_slots, pl.pos0, per_seq, pl.sample_tickets, pl.block_tables, pl.free_blocks_after)
+        assert got == e, (pl.iteration, got, e)
+    assert plans[0].admitted == [0, 1] and plans[1].admitted == [] and plans[2].admitted == [2]
+    assert plans[1].positions == [20] + list(range(4, 27)) and plans[1].slot_mapping == [20] + list(range(36, 48)) + list(range(48, 59))
+    assert plans[1].input_ids == [7] + [int(x) for x in req(30, 2)["prompt"][4:27]]
+    assert plans[2].positions == list(range(5)) + [27, 28, 29] and plans[2].last_idx == [4, 7] and plans[2].gen_index == [0, 0]
+    assert plans[3].input_ids == [7, 7] and plans[3].gen_index == [1, 1]
+    assert [len(s.outputs[t]) for t in range(3)] == [2, 2, 3]
+    s.step(3)
+    assert s.free == [7, 6, 5, 4, 0, 2, 3, 1] and s.committed == 0
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_chunked_invariants_under_random_load(seed):
+    """Blocks are conserved, the budget holds, at most one request is part-way through its prompt at the start of an
+    iteration, a decoding request gets a token in EVERY iteration until it ends (nothing pauses), prompts are processed
+    in order without gaps, admissions are in ticket order, and every request emits exactly its count."""
+    rng = np.random.default_rng(seed)
+    n = 50
+    reqs = [req(int(rng.integers(1, 90)), int(rng.integers(1, 12))) for _ in range(n)]
+    need_max = max(blocks_needed(len(r["prompt"]), r["max_new_tokens"], 16) for r in reqs)
+    budget = 40
+    s = Scheduler(max(need_max, 14), 16, 5, budget, 16, chunked=True)
+    done_prompt, last_decode_iter, admitted_order = {}, {}, []
+    plans = []
+
+    def on_plan(pl):
+        plans.append(pl)
+        assert 0 < len(pl.input_ids) <= budget
+        part = [b for b in range(s.max_batch) if s.running[b] is not None and 0 < s.running[b].prefilled < s.running[b].P]
+        assert len(part) <= 1
+        admitted_order.extend(pl.admitted)
+        for i, t in enumerate(pl.tickets):
+            ntok = pl.cu_seqlens[i + 1] - pl.cu_seqlens[i]
+            P = len(reqs[t]["prompt"])
+            if done_prompt.get(t, 0) < P:                  # a prompt chunk: continues exactly where the last one ended
+                assert pl.pos0[i] == done_prompt.get(t, 0) and ntok >= 1
+                assert pl.input_ids[pl.cu_seqlens[i]:pl.cu_seqlens[i + 1]] == [int(x) for x in reqs[t]["prompt"][pl.pos0[i]:pl.pos0[i] + ntok]]
+                done_prompt[t] = pl.pos0[i] + ntok
+                assert (i in pl.sample_seq) == (done_prompt[t] == P)
+                if done_prompt[t] == P:
+                    last_decode_iter[t] = pl.iteration
+            else:                                          # a decode: one token, in the iteration right after its last one
+                assert ntok == 1 and i in pl.sample_seq and pl.iteration == last_decode_iter[t] + 1
+                last_decode_iter[t] = pl.iteration
+
+    SV.run_schedule(s, reqs, lambda pl: [int(rng.integers(0, 50)) for _ in pl.sample_seq], on_plan=on_plan)
+    assert admitted_order == list(range(n))
+    assert [len(s.outputs[t]) for t in range(n)] == [r["max_new_tokens"] for r in reqs]
+    s.step(n)
+    assert sorted(s.free) == list(range(s.n_blocks)) and s.committed == 0
+    assert any(pl.kind == PREFILL and len(pl.sample_seq) > 1 and len(pl.tickets) > len(pl.admitted) for pl in plans)   # mixed iterations occurred
+
+
+def test_chunked_equals_unchunked_when_everything_fits_one_iteration():
+    """With a budget that holds all prompts at once the chunked schedule is the plain one, iteration by iteration
+    (and the plain scheduler is pinned above)."""
+    reqs = [req(20, 3), req(10, 5, first=7), req(33, 2, first=11)]
+    a, b = Scheduler(16, 16, 4, 8192, 8), Scheduler(16, 16, 4, 8192, 8, chunked=True)
+    pa, pb = [], []
+    SV.run_schedule(a, reqs, lambda pl: [5] * len(pl.sample_seq), on_plan=pa.append)
+    SV.run_schedule(b, reqs, lambda pl: [5] * len(pl.sample_seq), on_plan=pb.append)
+    assert len(pa) == len(pb)
+    for x, y in zip(pa, pb):
+        for f in ("kind", "tickets", "batch_slots", "input_ids", "positions", "slot_mapping", "tok_seq", "cu_seqlens", "last_idx",
+                  "block_tables", "gen_index", "sample_seq", "free_blocks_after", "admitted"):
+            assert getattr(x, f) == getattr(y, f), (x.iteration, f)
+
+
+def test_chunked_service_equals_per_request_generation():
+    """The model side of chunking: a prompt fed through the paged forward pass in several chunks, mixed with other
+    requests' decode tokens, gives the token streams of every request generated alone with a contiguous cache."""
+    cfg = dict(synth.model_config("tiny"), n_layers=2, vocab=97, d_model=64, n_q_heads=4, n_kv_heads=2, head_dim=16, d_ffn=96)
+    raw = synth.make_weights(cfg, 5, gain_jitter=0.1)
+    W = M.Weights(cfg, raw)
+    rng = np.random.default_rng(3)
+    reqs = [dict(prompt=rng.integers(0, 97, P).astype(np.int32), max_new_tokens=n, temperature=0.0, top_k=0, top_p=1.0, seed=0)
+            for P, n in ((37, 4), (5, 6), (50, 3), (18, 5))]
+    eng = dict(kv_block_size=16, kv_num_blocks=24, max_batch=3, max_prefill_tokens=20, ring_slots=8, eos_token_id=-1, chunked_prefill=True)
+    ev, sched = SV.serve(cfg, W, eng, reqs)
+    assert max(len(p) for p in [r["prompt"] for r in reqs]) > 2 * eng["max_prefill_tokens"]     # prompts span three iterations
+    for t, r in enumerate(reqs):
+        assert sched.outputs[t] == SV.generate_reference(cfg, W, r), t
