@@ -44,6 +44,12 @@ extern "C" {
                                         setting; blink_set_exit_when_idle changes it between windows) */
 #define BLINK_FLAG_KEEP_LOGITS 8u    /* keep the logits of the last iteration readable via blink_debug_read */
 #define BLINK_FLAG_NO_GRAPH 16u      /* enqueue the kernels of an iteration one by one instead of as one HIP graph */
+#define BLINK_FLAG_CHUNKED_PREFILL 32u /* mixed iterations (section 7 of the paper, "chunked prefill"): every iteration runs all
+                                        decoding requests (one token each, never paused) and fills the rest of its token
+                                        budget, max_prefill_tokens, with prompt tokens in ticket order; a prompt longer than
+                                        what is left continues in the next iteration, and a request samples its first token
+                                        in the iteration that processes the last token of its prompt. Without the flag an
+                                        admission makes a prefill-only iteration and running decodes pause (section 4.2) */
 
 /* slot life cycle of the ring (section 4.2, "Ring buffer") */
 enum {
@@ -75,7 +81,8 @@ typedef struct {
   uint32_t kv_num_blocks;      /* blocks in the pool */
   uint32_t max_batch;          /* batch slots (running sequences), <= 1024 (fp32 model) or <= 512 (bf16 model) */
   uint32_t max_seq_len;        /* prompt + generated tokens of one request */
-  uint32_t max_prefill_tokens; /* prompt tokens per prefill iteration (the first admitted request is exempt) */
+  uint32_t max_prefill_tokens; /* prompt tokens per prefill iteration (the first admitted request is exempt); with
+                                  BLINK_FLAG_CHUNKED_PREFILL: tokens per iteration, decodes included (must exceed max_batch) */
   uint32_t ring_slots;         /* power of two */
   int32_t eos_token_id;        /* -1: none */
   int32_t device;              /* HIP device ordinal */
@@ -111,7 +118,7 @@ typedef struct {
 /* one record per iteration (section 4.2 loop: scan, claim, batch, launch, publish) */
 typedef struct {
   uint32_t iteration;
-  uint32_t kind;               /* 1 prefill, 2 decode */
+  uint32_t kind;               /* 1 prefill (the iteration processes prompt tokens), 2 decode */
   uint64_t tail;               /* tickets below this were visible to the poll of this iteration */
   uint32_t n_admitted;
   uint32_t n_seqs;
@@ -142,7 +149,8 @@ typedef struct {
 
 /* blink_debug_read selectors (tests only; call while the loop is stopped) */
 enum {
-  BLINK_DBG_LOGITS = 1,        /* float[n_seqs][vocab] of the last iteration (needs BLINK_FLAG_KEEP_LOGITS) */
+  BLINK_DBG_LOGITS = 1,        /* float[sampling sequences][vocab] of the last iteration, in batch-slot order (needs
+                                  BLINK_FLAG_KEEP_LOGITS); every sequence samples unless a prompt chunk leaves its prompt incomplete */
   BLINK_DBG_FREE_STACK = 2,    /* uint32 free_top, then uint32[free_top] block ids, bottom first */
   BLINK_DBG_INPUT_IDS = 3,     /* int32[n_tokens] of the last iteration */
   BLINK_DBG_POSITIONS = 4,     /* int32[n_tokens] */

@@ -6,7 +6,7 @@ import numpy as np
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 
-FLAG_TRACE, FLAG_EXIT_WHEN_IDLE, FLAG_KEEP_LOGITS, FLAG_NO_GRAPH = 1, 2, 8, 16
+FLAG_TRACE, FLAG_EXIT_WHEN_IDLE, FLAG_KEEP_LOGITS, FLAG_NO_GRAPH, FLAG_CHUNKED_PREFILL = 1, 2, 8, 16, 32
 ERR_INVAL, ERR_TOO_LARGE, ERR_FULL, ERR_DEVICE, ERR_STATE = -1, -2, -3, -4, -5
 EVENT_FIRST, EVENT_LAST = 1, 2
 
@@ -140,6 +140,8 @@ class Engine:
             setattr(cfg, k, engine[k])
         cfg.weights = blob.ctypes.data
         cfg.weights_bytes = blob.nbytes
+        if engine.get("chunked_prefill"):
+            flags |= FLAG_CHUNKED_PREFILL
         cfg.device, cfg.flags, cfg.trace_capacity, cfg.idle_poll_us = device, flags, trace_capacity, idle_poll_us
         cfg.pump_depth, cfg.tune = pump_depth, tune
         self.h = C.c_void_p()

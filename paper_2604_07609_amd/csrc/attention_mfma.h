@@ -98,14 +98,18 @@ __device__ __forceinline__ void attn_block(const KVTile<HD>& kv, const f16x8_t (
     }
     bm = quad_max(bm);
     const float mn = fmaxf(a.m[c], bm);
+    // A column that has seen no visible key yet (a prompt chunk that starts inside a KV block: the tile's early queries
+    // do not see its second block) keeps m = -inf; the exponentials then take 0 as their reference, so that they give 0
+    // instead of exp(-inf + inf)
+    const float mref = mn == -INFINITY ? 0.f : mn;
     float p[4], ps = 0.f;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      p[i] = __expf(s4[i] - mn);      // exp(-inf) = 0 for masked keys
+      p[i] = __expf(s4[i] - mref);    // exp(-inf) = 0 for masked keys
       ps += p[i];
     }
     ps = quad_sum(ps);
-    const float corr = __expf(a.m[c] - mn);
+    const float corr = __expf(a.m[c] - mref);
     a.l[c] = a.l[c] * corr + ps;
     a.m[c] = mn;
     float c4[4];
@@ -128,7 +132,7 @@ __device__ __forceinline__ void attn_block(const KVTile<HD>& kv, const f16x8_t (
 struct AttnMfmaShared {
   float m[ATTN_WAVES][16], l[ATTN_WAVES][16];
   float o[ATTN_WAVES][16][128];  // [wave][q head of the group (decode) or query of the tile (prefill)][dim]
-  u32 cu_chunks[ATTN_META_MAX + 1], tok[ATTN_META_MAX], ctx[ATTN_META_MAX], bslot[ATTN_META_MAX];
+  u32 cu_chunks[ATTN_META_MAX + 1], tok[ATTN_META_MAX], ctx[ATTN_META_MAX], bslot[ATTN_META_MAX], pos0[ATTN_META_MAX];
 };
 
 // ---- decode: one workgroup per (sequence, kv head); its waves take the KV blocks round-robin ----------------------
@@ -284,8 +288,8 @@ __device__ __forceinline__ void attn_combine_pair(const DevCtx& c, u32 c0, u32 n
 }
 
 __device__ __forceinline__ void attn_decode_combine(const DevCtx& c, u32 wg, u32 nwg) {
-  if (c.meta->kind != 2u) return;
   const u32 B = c.meta->n_seqs, G = c.nq / c.nkv, HD = c.hd, lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  if (c.cu_chunks[B] == 0) return;     // no sequence decodes in this iteration
   for (u32 pair = wg * nw + w; pair < B * c.nkv; pair += nwg * nw) {
     const u32 s = pair / c.nkv, g = pair % c.nkv;
     const u32 c0 = c.cu_chunks[s], nch = c.cu_chunks[s + 1] - c0;
@@ -326,7 +330,10 @@ __device__ __forceinline__ void attn_prefill(const DevCtx& c, u32 layer, AttnMfm
   // batch metadata in LDS (the item lookup is a binary search; see the decode kernel)
   for (u32 i = threadIdx.x; i <= B; i += blockDim.x) {
     sh.cu_chunks[i] = c.cu_qtiles[i];
-    if (i < B) { sh.tok[i] = c.cu_seqlens[i]; sh.ctx[i] = c.cu_seqlens[i + 1] - c.cu_seqlens[i]; sh.bslot[i] = c.seq_bslot[i]; }
+    if (i < B) {
+      sh.tok[i] = c.cu_seqlens[i]; sh.ctx[i] = c.cu_seqlens[i + 1] - c.cu_seqlens[i]; sh.bslot[i] = c.seq_bslot[i];
+      sh.pos0[i] = c.seq_pos0[i];     // position of the sequence's first token of this iteration (a later chunk of a prompt starts beyond 0)
+    }
   }
   __syncthreads();
   auto cuq = [&](u32 i) { return sh.cu_chunks[i]; };
@@ -335,7 +342,7 @@ __device__ __forceinline__ void attn_prefill(const DevCtx& c, u32 layer, AttnMfm
   // now taking WPI wave slots, still fit the waves that run at once
   u32 WPI = 1;
   {
-    const u32 chain = (c.meta->max_q_len + 15) / 16;
+    const u32 chain = (c.meta->max_ctx + 15) / 16;
     const u64 slots = (u64)(nwg / 2) * nw;
     while (WPI < nw && WPI < 8 && chain > 12 * WPI && total * WPI <= slots) WPI *= 2;
     const u32 forced = (c.tune_nw >> 16) & 15u;      // bits 16-19 of the tuning word: 1, 2, 4, 8 force it (tests)
@@ -345,7 +352,7 @@ __device__ __forceinline__ void attn_prefill(const DevCtx& c, u32 layer, AttnMfm
   for (u64 base = (u64)wg * gpw; base < total; base += (u64)nwg * gpw) {
     const u64 item = base + grp;
     const bool valid = item < total;
-    u32 g = 0, hg = 0, p0 = 0, t0 = 0, P = 1, last = 0;
+    u32 g = 0, hg = 0, p0 = 0, t0 = 0, P = 1, last = 0, a0 = 0;   // p0: first query of the tile within the sequence's tokens of this iteration; a0: its position
     const u32* bt = c.block_tables;
     if (valid) {
       // query tiles in descending order: the causal mask makes the later tiles of a prompt walk more blocks, and the
@@ -361,8 +368,9 @@ __device__ __forceinline__ void attn_prefill(const DevCtx& c, u32 layer, AttnMfm
       p0 = (qi - cuq(s)) * 16;
       t0 = sh.tok[s];
       P = sh.ctx[s];
+      a0 = sh.pos0[s] + p0;
       bt = c.block_tables + (u64)sh.bslot[s] * c.max_blocks_per_seq;
-      last = min(p0 + 15, P - 1) / 16;
+      last = (a0 + min(15u, P - 1 - p0)) / 16;
     }
     const bool colv = valid && p0 + lc < P;
     // queries of the tile (columns past the prompt's end repeat its last token: an unconditional load; they are
@@ -372,7 +380,7 @@ __device__ __forceinline__ void attn_prefill(const DevCtx& c, u32 layer, AttnMfm
     const u32 qrow = t0 + min(p0 + lc, P - 1);
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) {
-      lim[ct] = colv ? p0 + lc + 1 : 1;
+      lim[ct] = colv ? a0 + lc + 1 : 1;
 #pragma unroll
       for (int st = 0; st < HD / 32; ++st)
         q[ct][st] = ld_tile(c.qbuf + ((u64)qrow * c.nq + g * G + hg * CT + ct) * HD + st * 32 + lg * 8);
@@ -468,10 +476,17 @@ __device__ __forceinline__ void attn_prefill_hd(const DevCtx& c, u32 layer, Attn
   }
 }
 
+// The sequences of an iteration that decode (one token, work items = chunks of their context) and those that process
+// prompt tokens (work items = tiles of 16 queries) each have their kernel part; a mixed iteration (chunked prefill) runs
+// both in the one launch, every workgroup first its share of the decode items, then of the query tiles.
 __device__ __forceinline__ void phase_attention_mfma(const DevCtx& c, u32 layer, AttnMfmaShared& sh, u32 wg, u32 nwg) {
-  if (c.meta->kind == 2u) {
+  const u32 B = c.meta->n_seqs;
+  const bool dec = c.cu_chunks[B] != 0, pre = c.cu_qtiles[B] != 0;
+  if (dec) {
     if (c.hd == 64) attn_decode<64>(c, layer, sh, wg, nwg); else attn_decode<128>(c, layer, sh, wg, nwg);
-  } else {
+  }
+  if (dec && pre) __syncthreads();   // the batch metadata in LDS is staged again for the other part
+  if (pre) {
     if (c.hd == 64) attn_prefill_hd<64>(c, layer, sh, wg, nwg); else attn_prefill_hd<128>(c, layer, sh, wg, nwg);
   }
 }

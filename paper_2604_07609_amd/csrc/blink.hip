@@ -281,6 +281,9 @@ static int init_impl(const blink_config* cfg, blink_engine* e) {
   if (int rc = dalloc(e, &c.seq_len, c.max_batch)) return rc;
   if (int rc = dalloc(e, &c.cu_seqlens, c.max_batch + 1)) return rc;
   if (int rc = dalloc(e, &c.last_idx, c.max_batch)) return rc;
+  if (int rc = dalloc(e, &c.sample_bslot, c.max_batch)) return rc;
+  if (int rc = dalloc(e, &c.seq_pos0, c.max_batch)) return rc;
+  if (int rc = dalloc(e, &c.seq_ring, c.max_batch)) return rc;
   if (int rc = dalloc(e, &c.cu_qtiles, c.max_batch + 1)) return rc;
   if (int rc = dalloc(e, &c.cu_chunks, c.max_batch + 1)) return rc;
   if (int rc = dalloc(e, &c.input_ids, c.maxT)) return rc;
@@ -476,6 +479,8 @@ extern "C" int blink_init(const blink_config* cfg, blink_engine** out) {
   if (cfg->dtype == 1 && cfg->max_batch > ATTN_META_MAX)
     return fail(BLINK_ERR_INVAL, "bf16 models take at most %d batch slots (attention keeps the batch metadata in LDS)", ATTN_META_MAX);
   if (!cfg->max_seq_len || !cfg->max_prefill_tokens) return fail(BLINK_ERR_INVAL, "max_seq_len and max_prefill_tokens must be positive");
+  if ((cfg->flags & BLINK_FLAG_CHUNKED_PREFILL) && cfg->max_prefill_tokens <= cfg->max_batch)
+    return fail(BLINK_ERR_INVAL, "chunked prefill: max_prefill_tokens (the token budget of an iteration) must exceed max_batch");
   if (!cfg->ring_slots || (cfg->ring_slots & (cfg->ring_slots - 1))) return fail(BLINK_ERR_INVAL, "ring_slots must be a power of two");
   if (cfg->weights_bytes != expected_weight_bytes(cfg))
     return fail(BLINK_ERR_INVAL, "weights_bytes is %llu, the model needs %llu", (unsigned long long)cfg->weights_bytes,
@@ -826,7 +831,7 @@ extern "C" int blink_debug_read(blink_engine* e, uint32_t what, void* buf, uint6
   const void* src = nullptr;
   u64 n = 0;
   switch (what) {
-    case BLINK_DBG_LOGITS: src = c.logits; n = (u64)m.n_seqs * c.V * 4; break;
+    case BLINK_DBG_LOGITS: src = c.logits; n = (u64)m.n_samples * c.V * 4; break;
     case BLINK_DBG_FREE_STACK: {
       n = 4 + (u64)s.free_top * 4;
       if (n > cap_bytes) return fail(BLINK_ERR_INVAL, "buffer too small: need %llu bytes", (unsigned long long)n);

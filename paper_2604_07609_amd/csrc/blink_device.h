@@ -58,6 +58,8 @@ struct RunEntry {     // one batch slot
   float top_p;
   u32 in_iter;        // 1 when admitted in the current iteration
   u32 paused;         // 1 while its slot state is DECODE_PAUSED
+  u32 prefilled;      // prompt tokens whose K/V are in the cache (== P once the request decodes)
+  u32 chunk;          // chunked prefill: prompt tokens the admitting iteration processes
   u32 pad;
   u64 seed;
 };
@@ -89,6 +91,8 @@ struct IterMeta {
   u32 max_ctx;          // longest context after this iteration
   u32 trace_idx;
   u32 skip;             // 1: the window has ended, phases do nothing (the rest describes the last real iteration)
+  u32 n_samples;        // sequences that sample a token in this iteration (all of them unless a prompt chunk leaves its prompt incomplete)
+  u32 pad;
 };
 
 struct TraceRec {       // mirrors blink_trace_record
@@ -159,7 +163,10 @@ struct DevCtx {
   u32* seq_bslot;       // [max_batch]
   u32* seq_len;         // [max_batch]
   u32* cu_seqlens;      // [max_batch+1]
-  u32* last_idx;        // [max_batch]
+  u32* last_idx;        // [max_batch] token index of the last token of every sampling sequence
+  u32* sample_bslot;    // [max_batch] batch slot of every sampling sequence
+  u32* seq_pos0;        // [max_batch] position of the first token every sequence processes in this iteration
+  u32* seq_ring;        // [max_batch] ring slot of a sequence that processes prompt tokens, ~0 for a decoding one
   u32* cu_qtiles;       // [max_batch+1] prefix sum of ceil(tokens/16) per sequence of the iteration
   u32* cu_chunks;       // [max_batch+1] prefix sum of ceil(context/ATTN_CHUNK_TOKENS) per sequence (decode attention work items)
   i32* input_ids;       // [maxT]

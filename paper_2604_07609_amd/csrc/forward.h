@@ -106,10 +106,10 @@ __device__ __forceinline__ void phase_embed_packed(const DevCtx& c, u32 wg, u32 
 }
 
 // ---- RMSNorm: out[r] = in[row(r)] * g / sqrt(mean(in^2) + eps); one workgroup per row -------------------------
-// rows == nullptr: row(r) = r, n_rows = n_tokens; else row(r) = rows[r], n_rows = n_seqs (last positions).
+// rows == nullptr: row(r) = r, n_rows = n_tokens; else row(r) = rows[r], n_rows = sampling sequences (their last positions).
 __device__ __forceinline__ void phase_rmsnorm(const DevCtx& c, const float* in, const float* g, float* out, const u32* rows, float* red,
                               u32 wg, u32 nwg) {
-  const u32 n = rows ? c.meta->n_seqs : c.meta->n_tokens, d = c.d;
+  const u32 n = rows ? c.meta->n_samples : c.meta->n_tokens, d = c.d;
   for (u32 r = wg; r < n; r += nwg) {
     const float* x = in + (u64)(rows ? rows[r] : r) * d;
     float ss = 0.f;

@@ -46,7 +46,7 @@ template <typename WT>
 __device__ __forceinline__ void run_phase_t(const DevCtx& c, int ph, u32 layer, void* shp, u32 wg, u32 nwg) {
   PhaseShared& sh = *(PhaseShared*)shp;   // only the member that belongs to phase `ph` is touched
   const IterMeta* m = c.meta;
-  const u32 T = m->n_tokens, B = m->n_seqs;
+  const u32 T = m->n_tokens, B = m->n_samples;     // B: the sequences that sample in this iteration (rows of the logits)
   const LayerW* L = c.layers + layer;
   switch (ph) {
     case PH_EMBED: phase_embed<WT>(c, wg, nwg); break;
@@ -123,7 +123,7 @@ __device__ __forceinline__ void run_phase_bf16(const DevCtx& c, int ph, u32 laye
       else gemm_splitk_reduce<EPI_RESIDUAL>(a, sh.mfma, wg, nwg, 512);
       break;
     case PH_LM_HEAD:
-      a.Wp = c.lm_p; a.Xp = c.xq; a.N = c.V; a.K = c.d; a.T = m->n_seqs; a.tok_index = c.last_idx; a.ssq_in = c.ssq;
+      a.Wp = c.lm_p; a.Xp = c.xq; a.N = c.V; a.K = c.d; a.T = m->n_samples; a.tok_index = c.last_idx; a.ssq_in = c.ssq;
       a.out = c.logits; a.ldo = c.V;
       gemm_mfma<EPI_SCALED_STORE, false>(a, sh.mfma, wg, nwg);
       break;

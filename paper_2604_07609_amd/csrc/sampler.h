@@ -283,10 +283,10 @@ __device__ __forceinline__ i32 sample_row(const float* row, u32 V, float tempera
 
 __device__ __forceinline__ void phase_sample_publish(const DevCtx& c, SamplerShared& sh, u32 wg, u32 nwg) {
   const IterMeta* meta = c.meta;
-  const u32 n_seqs = meta->n_seqs, V = c.V, tid = threadIdx.x;
+  const u32 n_seqs = meta->n_samples, V = c.V, tid = threadIdx.x;      // the sequences that sample in this iteration
   if (wg == 0 && tid == 0 && (c.flags & 1u)) c.trace[meta->trace_idx].t_forward_end = dev_now_ns();
   for (u32 s = wg; s < n_seqs; s += nwg) {
-    const u32 b = c.seq_bslot[s];
+    const u32 b = c.sample_bslot[s];
     RunEntry& r = c.run[b];
     const i32 token = sample_row(c.logits + (u64)s * V, V, r.temperature, r.top_k, r.top_p, r.seed, r.gen, sh);
     // ---- publish (section 4.2: tokens and status go back to the ring) ------------------------------------

@@ -30,6 +30,7 @@ struct SchedShared {
   u32 seq_tok0[SCHED_MAX_BATCH];     // prefill metadata: first token, batch slot and ring slot of every sequence
   u32 seq_bslot[SCHED_MAX_BATCH];
   u32 seq_ring[SCHED_MAX_BATCH];
+  u32 seq_pos0[SCHED_MAX_BATCH];
   u32 flag;
   u32 exit_idle;
   u64 chain;
@@ -173,6 +174,28 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
   }
   __syncthreads();
 
+  // ---- chunked prefill: the token budget of the iteration goes first to the running requests (one token per decoding
+  // request, then the one request that may be part-way through its prompt); admissions take what is left ----------
+  const bool chunked = (c.flags & 32u) != 0;
+  const u32 budget = c.max_prefill_tokens;
+  u32 used = 0, chunk_part = 0;
+  if (chunked) {
+    u32 n_dec = 0, part_rem = 0;
+    for (u32 base = 0; base < c.max_batch; base += BLK_THREADS) {
+      const u32 b = base + tid;
+      const bool v = b < c.max_batch && c.run[b].valid;
+      const u32 rem = v ? c.run[b].P - c.run[b].prefilled : 0u;
+      u32 td, tr;
+      block_excl_scan(v && rem == 0 ? 1u : 0u, td, sh.wave_part);
+      block_excl_scan(rem, tr, sh.wave_part2);       // at most one running request has prompt tokens left
+      n_dec += td;
+      part_rem += tr;
+    }
+    chunk_part = min(part_rem, budget - min(budget, n_dec));
+    used = n_dec + chunk_part;
+    __syncthreads();
+  }
+
   // ---- (2) poll the ring + (3) admit FCFS, 256 candidate tickets at a time ----------------------------------
   u32 admitted = 0, tokens_admitted = 0;
   u64 tail = next0;
@@ -205,8 +228,10 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
     const u32 sn = block_excl_scan(need, totn, sh.wave_part) + need;     // inclusive
     const u32 sp = block_excl_scan(cand ? P : 0u, totp, sh.wave_part2) + (cand ? P : 0u);
     const u32 ord = admitted + tid;                                        // admission order within the iteration
+    // tokens of the budget already spoken for when this candidate's turn comes (chunked mode)
+    const u64 before = (u64)used + tokens_admitted + (sp - (cand ? P : 0u));
     const bool ok = cand && ord < n_free && (u64)committed + sn <= (u64)c.n_blocks &&
-                    (ord == 0 || (u64)tokens_admitted + sp <= (u64)c.max_prefill_tokens);
+                    (chunked ? before < (u64)budget : (ord == 0 || (u64)tokens_admitted + sp <= (u64)c.max_prefill_tokens));
     const u32 adm = block_prefix_count(ok, sh.wave_part);
     if (tid < adm) {
       const u32 b = sh.free_list[ord];
@@ -228,6 +253,8 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
       r.seed = c.desc[slot].seed;
       r.in_iter = 1;
       r.paused = 0;
+      r.prefilled = chunked ? 0u : P;       // without chunking the whole prompt is processed in this iteration
+      r.chunk = chunked ? (u32)min((u64)P, (u64)budget - before) : P;
       // claim by compare-and-swap (section 4.2 "Ring buffer")
       u32 expect = SLOT_PREFILL_PENDING;
       if (!__hip_atomic_compare_exchange_strong(&c.status[slot].state, &expect, SLOT_PREFILL_PROCESSING, __ATOMIC_ACQ_REL,
@@ -252,46 +279,57 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
   }
   nrun += admitted;
 
-  // ---- (4) kind --------------------------------------------------------------------------------------------
-  const u32 kind = admitted > 0 ? KIND_PREFILL : (nrun > 0 ? KIND_DECODE : KIND_IDLE);
+  // ---- (4) kind: an iteration with prompt tokens in it counts as a prefill iteration ---------------------------
+  const u32 kind = (admitted > 0 || chunk_part > 0) ? KIND_PREFILL : (nrun > 0 ? KIND_DECODE : KIND_IDLE);
   __syncthreads();
 
   // ---- (5) allocate + (6) metadata, batch slot ascending ----------------------------------------------------
-  u32 n_seqs = 0, n_tok = 0, n_alloc = 0, n_qt = 0, n_ch = 0, max_q = 0, max_ctx = 0;
+  // Sequences of the iteration: without chunking the newly admitted (prefill iteration) or all running (decode
+  // iteration); with chunking all running, each with its share of the token budget. A sequence samples a token
+  // unless its prompt is still incomplete after this iteration.
+  u32 n_seqs = 0, n_tok = 0, n_alloc = 0, n_qt = 0, n_ch = 0, n_smp = 0, n_dec_seq = 0, max_q = 0, max_ctx = 0;
   u64 n_ctx = 0;
   if (kind != KIND_IDLE) {
     for (u32 base = 0; base < c.max_batch; base += BLK_THREADS) {
       const u32 b = base + tid;
-      bool in = false;
-      u32 nalloc = 0, ntok = 0, ctx = 0, nb = 0;
+      bool in = false, pref = false, smp = false;
+      u32 nalloc = 0, ntok = 0, pos0 = 0, nb = 0;
       if (b < c.max_batch && c.run[b].valid) {
         RunEntry& r = c.run[b];
-        if (kind == KIND_PREFILL) {
-          in = r.in_iter != 0;
-          if (in) {
-            nalloc = (r.P + c.bs - 1) / c.bs;
-            ntok = r.P;
-          } else if (!r.paused) {
+        nb = r.n_blocks;
+        if (chunked) {
+          in = true;
+          pref = r.prefilled < r.P;
+          ntok = pref ? (r.in_iter ? r.chunk : chunk_part) : 1u;
+          pos0 = pref ? r.prefilled : r.ctx_len;
+          smp = !pref || r.prefilled + ntok == r.P;
+        } else if (kind == KIND_PREFILL) {
+          in = pref = smp = r.in_iter != 0;
+          ntok = r.P;
+          if (!in && !r.paused) {
             set_slot_state(&c.status[r.ring_slot], SLOT_DECODE_PAUSED);   // running decodes wait for the prefill
             r.paused = 1;
           }
         } else {
-          in = true;
-          nalloc = (r.ctx_len == r.n_blocks * c.bs) ? 1u : 0u;
+          in = smp = true;
           ntok = 1;
+          pos0 = r.ctx_len;
         }
-        ctx = r.ctx_len;
-        nb = r.n_blocks;
+        if (in) nalloc = (pos0 + ntok + c.bs - 1) / c.bs - nb;
+        else ntok = 0;
       }
-      u32 tots, tota, tott, totq, totc;
-      const u32 ctx_after = in ? (kind == KIND_DECODE ? ctx + 1 : ntok) : 0u;
-      const u32 coff = n_ch + block_excl_scan((ctx_after + ATTN_CHUNK_TOKENS - 1) / ATTN_CHUNK_TOKENS, totc, sh.wave_part);
-      const u32 qoff = n_qt + block_excl_scan((ntok + 15) / 16, totq, sh.wave_part2);
+      u32 tots, tota, tott, totq, totc, totm, totx;
+      const u32 ctx_after = in ? pos0 + ntok : 0u;
+      const u32 coff = n_ch + block_excl_scan((in && !pref) ? (ctx_after + ATTN_CHUNK_TOKENS - 1) / ATTN_CHUNK_TOKENS : 0u, totc, sh.wave_part);
+      const u32 qoff = n_qt + block_excl_scan(pref ? (ntok + 15) / 16 : 0u, totq, sh.wave_part2);
       const u32 si = n_seqs + block_excl_scan(in ? 1u : 0u, tots, sh.wave_part);
       const u32 aoff = n_alloc + block_excl_scan(nalloc, tota, sh.wave_part2);
       const u32 toff = n_tok + block_excl_scan(ntok, tott, sh.wave_part);
-      u32 totx;
-      block_excl_scan(ctx_after, totx, sh.wave_part2);     // context tokens the attention of this iteration reads
+      const u32 mi = n_smp + block_excl_scan(smp ? 1u : 0u, totm, sh.wave_part2);
+      block_excl_scan(ctx_after, totx, sh.wave_part);     // context tokens the attention of this iteration reads
+      u32 totd;
+      block_excl_scan((in && !pref) ? 1u : 0u, totd, sh.wave_part2);
+      n_dec_seq += totd;
       if (in) {
         RunEntry& r = c.run[b];
         u32* bt = c.block_tables + (u64)b * mbs;
@@ -301,32 +339,37 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
         c.cu_seqlens[si] = toff;
         c.cu_qtiles[si] = qoff;
         c.cu_chunks[si] = coff;
-        c.last_idx[si] = toff + ntok - 1;
-        if (kind == KIND_DECODE) {
+        c.seq_pos0[si] = pos0;
+        c.seq_ring[si] = pref ? r.ring_slot : ~0u;
+        c.seq_len[si] = ctx_after;
+        if (smp) {
+          c.last_idx[mi] = toff + ntok - 1;
+          c.sample_bslot[mi] = b;
+        }
+        if (!pref) {
           c.input_ids[toff] = r.last_token;
-          c.positions[toff] = (i32)ctx;
-          c.slot_mapping[toff] = (i32)(bt[ctx / c.bs] * c.bs + ctx % c.bs);
+          c.positions[toff] = (i32)pos0;
+          c.slot_mapping[toff] = (i32)(bt[pos0 / c.bs] * c.bs + pos0 % c.bs);
           c.tok_seq[toff] = si;
-          r.ctx_len = ctx + 1;
-          c.seq_len[si] = ctx + 1;
           if (r.paused) {
             set_slot_state(&c.status[r.ring_slot], SLOT_DECODE_PROCESSING);
             r.paused = 0;
           }
         } else {
-          r.ctx_len = r.P;
-          c.seq_len[si] = r.P;
+          r.prefilled = pos0 + ntok;
           r.in_iter = 0;
         }
+        r.ctx_len = ctx_after;
       }
-      max_q = max(max_q, block_max(ntok, sh.wave_part));
-      max_ctx = max(max_ctx, block_max(ctx_after, sh.wave_part2));
+      max_q = max(max_q, block_max(ntok, sh.wave_part2));
+      max_ctx = max(max_ctx, block_max(ctx_after, sh.wave_part));
       n_ctx += totx;
       n_seqs += tots;
       n_alloc += tota;
       n_tok += tott;
       n_qt += totq;
       n_ch += totc;
+      n_smp += totm;
     }
     top -= n_alloc;
     __syncthreads();
@@ -343,7 +386,8 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
         const u32 b = c.seq_bslot[s];
         sh.seq_tok0[s] = c.cu_seqlens[s];
         sh.seq_bslot[s] = b;
-        sh.seq_ring[s] = c.run[b].ring_slot;
+        sh.seq_ring[s] = c.seq_ring[s];      // ~0u for a decoding sequence: its one token is already written
+        sh.seq_pos0[s] = c.seq_pos0[s];
       }
       __syncthreads();
       for (u32 base = 0; base < n_tok; base += 4 * BLK_THREADS) {
@@ -358,17 +402,19 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
             if (sh.seq_tok0[mid] <= tk) lo = mid; else hi = mid;
           }
           sq[u] = lo;
-          pp[u] = tk - sh.seq_tok0[lo];
+          pp[u] = sh.seq_pos0[lo] + (tk - sh.seq_tok0[lo]);       // position in the prompt = in the context
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
+          const u32 ring = sh.seq_ring[sq[u]];
           blk[u] = c.block_tables[(u64)sh.seq_bslot[sq[u]] * mbs + pp[u] / c.bs];
-          id[u] = __hip_atomic_load(c.in_arena + (u64)sh.seq_ring[sq[u]] * c.max_seq_len + pp[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+          id[u] = __hip_atomic_load(c.in_arena + (u64)(ring == ~0u ? 0u : ring) * c.max_seq_len + (ring == ~0u ? 0u : pp[u]), __ATOMIC_RELAXED,
+                                    __HIP_MEMORY_SCOPE_SYSTEM);
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
           const u32 tk = base + u * BLK_THREADS + tid;
-          if (tk < n_tok) {
+          if (tk < n_tok && sh.seq_ring[sq[u]] != ~0u) {
             c.input_ids[tk] = id[u];
             c.positions[tk] = (i32)pp[u];
             c.slot_mapping[tk] = (i32)(blk[u] * c.bs + pp[u] % c.bs);
@@ -391,6 +437,7 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
     m->kind = kind;
     m->skip = 0;
     m->n_seqs = n_seqs;
+    m->n_samples = n_smp;
     m->n_tokens = n_tok;
     m->max_q_len = max_q;
     m->max_ctx = max_ctx;
@@ -399,11 +446,11 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
       const u64 it = ss->iteration;
       m->iteration = (u32)it;
       ss->iteration = it + 1;
-      ss->tokens_out += n_seqs;
+      ss->tokens_out += n_smp;
       ss->idle_since_ns = 0;
       if (kind == KIND_PREFILL) {
         ss->prefill_iterations += 1;
-        ss->tokens_prefilled += n_tok;
+        ss->tokens_prefilled += n_tok - n_dec_seq;
       }
       const u32 ti = (u32)(it % c.trace_cap);
       m->trace_idx = ti;

@@ -377,3 +377,58 @@ def test_bf16_gemms_with_k_split_across_workgroups(lib, max_batch, tune):
         r["prompt"] = r["prompt"][:12]
     worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2, tune=tune)
     print("K split across workgroups: max_batch", max_batch, "tune", hex(tune), "worst relative logit error", worst)
+
+
+# ---- chunked prefill: mixed prefill + decode iterations under a token budget ------------------------------------------
+
+@pytest.mark.parametrize("name,budget,dtype", [("mini_gqa128", 48, 1), ("mini_gqa", 70, 1), ("mini_churn", 100, 1), ("mini_gqa", 40, 0)])
+def test_chunked_prefill_stepwise(lib, name, budget, dtype):
+    """Every iteration of a run with chunked prefill against the oracle's chunked scheduler and paged forward pass:
+    prompts of 1..99 tokens cut into chunks of at most `budget` tokens minus the running decodes, chunks that start in the
+    middle of a KV block and of a 16-query tile, iterations that mix decode tokens and prompt chunks, iterations in which
+    no sequence samples, sampled and greedy requests."""
+    cfg, eng, raw, blob = setup(name, 53)
+    if dtype == 0:
+        cfg = dict(cfg, dtype=0)
+        raw = synth.make_weights(cfg, 53, gain_jitter=0.1)
+        blob = synth.pack_blob(cfg, raw)
+    eng = dict(eng, chunked_prefill=True, max_prefill_tokens=budget, max_batch=6, kv_num_blocks=96, max_seq_len=160, ring_slots=32)
+    reqs = sampled(synth.make_workload("mini", cfg["vocab"], 153, n_requests=11), 53, every=3)
+    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2 if dtype else 1e-4)
+    print("chunked prefill", name, "budget", budget, "worst relative logit error", worst)
+
+
+def test_chunked_prefill_long_prompts_and_contexts(lib):
+    """Prompts of 1030 and 600 tokens in chunks of at most 256 tokens while other requests decode: prompt chunks attend
+    to the chunks cached before them (up to 65 KV blocks back), decode contexts cross the 512-token chunk boundary."""
+    cfg, eng, raw, blob = setup("mini_gqa128", 55)
+    eng = dict(eng, chunked_prefill=True, max_prefill_tokens=256, max_batch=4, kv_num_blocks=140, max_seq_len=1100, ring_slots=16)
+    reqs = _fixed_prompts(cfg, [505, 1030, 40, 600, 7], 6, 25)
+    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2)
+    print("chunked prefill, long prompts: worst relative logit error", worst)
+
+
+def test_chunked_prefill_end_to_end_and_windows(lib):
+    """Queueing behind a small pool with chunked prefill: schedule bit-exact, tokens teacher-forced; and the same run in
+    windows of 3 iterations gives the same events and trace."""
+    cfg, eng, raw, blob = setup("mini_gqa", 57)
+    eng = dict(eng, chunked_prefill=True, max_prefill_tokens=64, kv_num_blocks=40, max_batch=5)
+    reqs = synth.make_workload("mini", cfg["vocab"], 157, n_requests=14)
+    ev, trace, st = parity.run_engine(lib, cfg, eng, blob, reqs)
+    assert st["free_blocks"] == eng["kv_num_blocks"] and st["committed_blocks"] == 0 and st["n_running"] == 0
+    assert len(ev) == sum(r["max_new_tokens"] for r in reqs)
+    res = parity.check_against_oracle(cfg, M.Weights(cfg, raw), eng, reqs, ev, trace, rtol=2e-2, tok_rtol=TOK_RTOL)
+    mixed = sum(1 for pl in res["plans"] if pl.kind == 1 and len(pl.tickets) > len(pl.admitted))
+    print("chunked end to end: iterations", len(trace), "of which mixed", mixed, "tokens", res["tokens"], "near ties", res["near_ties"])
+    assert mixed >= 3 and res["near_ties"] <= res["tokens"] // 8
+    ev2, trace2, _ = parity.run_engine(lib, cfg, eng, blob, reqs, window=3)
+    assert sorted(parity.event_tuples(ev)) == sorted(parity.event_tuples(ev2))
+    for f in ("iteration", "kind", "tail", "n_admitted", "n_seqs", "n_tokens", "free_blocks"):
+        assert list(trace[f]) == list(trace2[f])
+
+
+def test_chunked_prefill_needs_a_budget_beyond_the_batch(lib):
+    cfg, eng, raw, blob = setup("mini_gqa", 91)
+    with pytest.raises(lib.BlinkError) as ei:
+        lib.Engine(cfg, dict(eng, chunked_prefill=True, max_prefill_tokens=eng["max_batch"]), blob)
+    assert ei.value.code == lib.ERR_INVAL
