@@ -227,6 +227,63 @@ def open_loop(B, e, reqs, seconds):
                 arrivals="as drawn (producer thread stands in for the SmartNIC)")
 
 
+def chunked_leg(B, cfg, eng, blob, reqs, K, W, args):
+    """The same saturation run with chunked prefill (mixed prefill + decode iterations under the engine's token budget,
+    the extension the paper names first): untimed fill until an iteration admits nothing, W warm-up iterations, K timed."""
+    eng = dict(eng, chunked_prefill=True, max_prefill_tokens=max(args.chunk_budget, eng["max_batch"] + 1))
+    e = B.Engine(cfg, eng, blob, flags=B.FLAG_TRACE | B.FLAG_EXIT_WHEN_IDLE | (B.FLAG_NO_GRAPH if args.no_graph else 0), trace_capacity=1 << 16,
+                 tune=args.tune)
+    try:
+        for r in reqs:
+            e.submit_request(r)
+        base, fill = e.stats(), 0
+        while fill < 4000:
+            e.run(4)
+            e.wait()
+            e.drain(16384)
+            st = e.stats()
+            fill = int(st["iterations"] - base["iterations"])
+            if np.any(e.trace(4)["n_admitted"] == 0) or st["n_running"] == 0:
+                break
+        if W:
+            e.run(W)
+            e.wait()
+        e.drain(16384)
+        s0 = e.stats()
+        t0 = time.perf_counter()
+        e.run(K)
+        e.wait()
+        t1 = time.perf_counter()
+        s1 = e.stats()
+        ev = e.drain(16384)
+        tr = e.trace(int(s1["iterations"] - s0["iterations"]))
+    finally:
+        e.shutdown()
+    iters = int(s1["iterations"] - s0["iterations"])
+    ev = ev[ev["iteration"] >= s0["iterations"]]
+    order = np.lexsort((ev["index"], ev["request_id"]))
+    evs = ev[order]
+    same = (evs["request_id"][1:] == evs["request_id"][:-1]) & (evs["index"][1:] == evs["index"][:-1] + 1)
+    itl = (evs["device_ns"][1:].astype(np.int64) - evs["device_ns"][:-1].astype(np.int64))[same] / 1e6
+    sched_us = (tr["t_sched_end_ns"].astype(np.int64) - tr["t_sched_begin_ns"].astype(np.int64)) / 1e3
+    pct = lambda a, q: round(float(np.percentile(a, q)), 4) if len(a) else None
+    d, F, V, L = cfg["d_model"], cfg["d_ffn"], cfg["vocab"], cfg["n_layers"]
+    qkv_n = (cfg["n_q_heads"] + 2 * cfg["n_kv_heads"]) * cfg["head_dim"]
+    layer_params = qkv_n * d + d * cfg["n_q_heads"] * cfg["head_dim"] + 3 * F * d
+    toks_out = int(s1["tokens_out"] - s0["tokens_out"])
+    flops = 2.0 * (L * layer_params * float(tr["n_tokens"].sum()) + V * d * toks_out)
+    dt = t1 - t0
+    return dict(value=round(toks_out / dt, 2), unit="output tokens/s", steps=iters, ms_per_step=round(1e3 * dt / max(1, iters), 4),
+                token_budget_per_iteration=eng["max_prefill_tokens"], fill_iterations_before_warmup=fill,
+                mean_tokens_per_iteration=round(float(tr["n_tokens"].mean()), 1) if len(tr) else None,
+                mean_sequences_per_iteration=round(float(tr["n_seqs"].mean()), 1) if len(tr) else None,
+                prompt_tokens_per_s=round(float(s1["tokens_prefilled"] - s0["tokens_prefilled"]) / dt, 1),
+                projection_TFLOPs=round(flops / dt / 1e12, 1),
+                frac_of_mfma_peak=round(flops / dt / 1e12 / (2500.0 if cfg["dtype"] == 1 else 157.3), 4),
+                itl_ms=dict(p50=pct(itl, 50), p99=pct(itl, 99), n=int(len(itl))),
+                sched_us_per_iteration=dict(median=pct(sched_us, 50), p99=pct(sched_us, 99)))
+
+
 def claim_latency(B, e, vocab, n=24):
     """An idle engine (its scheduler kernel polling the ring on the device) receives one short request at a time:
     time from the entry of blink_submit, and from its return, to the end of the scheduler step that admitted the request
@@ -295,6 +352,9 @@ def main():
     ap.add_argument("--max-batch", type=int, default=0, help="override the engine's batch slots")
     ap.add_argument("--kv-blocks", type=int, default=0, help="override the size of the KV pool (16-token blocks)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-chunked-leg", action="store_true", help="skip the second saturation run with chunked prefill")
+    ap.add_argument("--chunk-budget", type=int, default=2048, help="tokens per iteration of the run with chunked prefill")
+    ap.add_argument("--only-chunked-leg", action="store_true", help="tuning: skip everything else")
     ap.add_argument("--dump-iterations", default="",
                     help="write one line per iteration of the warm-up and the timed window (kind, sequences, tokens, context "
                          "tokens, timed flag): lets a rocprofv3 trace of the same run be split by iteration kind")
@@ -332,6 +392,9 @@ def main():
     blob = synth.pack_blob(cfg, raw)
     t_gen = time.perf_counter() - t_gen
 
+    if args.only_chunked_leg:
+        print(json.dumps(chunked_leg(B, cfg, eng, blob, reqs, K, W, args)))
+        return
     # One engine serves every leg. First the legs that leave it idle again (claim latency, the workload's own arrivals,
     # isolated and under the host stressor), then the saturation run that is timed.
     e = B.Engine(cfg, eng, blob, flags=B.FLAG_TRACE | (B.FLAG_NO_GRAPH if args.no_graph else 0), trace_capacity=1 << 18, tune=args.tune)
@@ -412,6 +475,9 @@ def main():
         e.shutdown()
         if stressor:
             stressor.close()
+    chunked = None
+    if not args.no_chunked_leg and eng["max_prefill_tokens"] > eng["max_batch"]:
+        chunked = chunked_leg(B, cfg, eng, blob, reqs, K, W, args)
 
     if args.dump_iterations:
         with open(args.dump_iterations, "w") as f:
@@ -527,6 +593,8 @@ def main():
     if int(dec.sum()) == 0 and args.workload in ("llama3_8b", "churn"):
         out["warning"] = "the timed window holds no decode iteration"
         print("bench.py: the timed window holds no decode iteration (steps=%d): ITL and the decode roofline are empty" % K, file=sys.stderr)
+    if chunked:
+        out["chunked_prefill"] = chunked
     if claim:
         out["claim_latency"] = claim
     if iso:
