@@ -229,7 +229,8 @@ def open_loop(B, e, reqs, seconds):
 
 def chunked_leg(B, cfg, eng, blob, reqs, K, W, args):
     """The same saturation run with chunked prefill (mixed prefill + decode iterations under the engine's token budget,
-    the extension the paper names first): untimed fill until an iteration admits nothing, W warm-up iterations, K timed."""
+    the extension the paper names first): untimed fill until the batch slots are taken (or admission has stalled for eight
+    iterations), W warm-up iterations, K timed."""
     eng = dict(eng, chunked_prefill=True, max_prefill_tokens=max(args.chunk_budget, eng["max_batch"] + 1))
     e = B.Engine(cfg, eng, blob, flags=B.FLAG_TRACE | B.FLAG_EXIT_WHEN_IDLE | (B.FLAG_NO_GRAPH if args.no_graph else 0), trace_capacity=1 << 16,
                  tune=args.tune)
@@ -243,7 +244,9 @@ def chunked_leg(B, cfg, eng, blob, reqs, K, W, args):
             e.drain(16384)
             st = e.stats()
             fill = int(st["iterations"] - base["iterations"])
-            if np.any(e.trace(4)["n_admitted"] == 0) or st["n_running"] == 0:
+            # full: every batch slot taken, or nothing admitted for eight iterations (pool-limited), or everything admitted
+            if st["n_running"] == eng["max_batch"] or st["n_running"] == 0 or st["next_ticket"] == base["next_ticket"] + len(reqs) \
+                    or (fill >= 8 and not np.any(e.trace(8)["n_admitted"] > 0)):
                 break
         if W:
             e.run(W)
@@ -257,6 +260,19 @@ def chunked_leg(B, cfg, eng, blob, reqs, K, W, args):
         s1 = e.stats()
         ev = e.drain(16384)
         tr = e.trace(int(s1["iterations"] - s0["iterations"]))
+        kernel_times = {}
+        for ph in [int(x) for x in args.phases.split(",") if x]:
+            sa = e.stats()
+            e.time_phase(ph)
+            e.run(K)
+            e.wait()
+            e.time_phase(-1)
+            e.drain(16384)
+            pms = e.phase_times_ms()
+            n_it = min(len(pms), int(e.stats()["iterations"] - sa["iterations"]))
+            n_l = 1 if ph in (0, 9, 10, 11) else cfg["n_layers"]
+            if n_it:
+                kernel_times[str(ph)] = round(1e3 * float(pms[:n_it].sum()) / (n_it * n_l), 2)
     finally:
         e.shutdown()
     iters = int(s1["iterations"] - s0["iterations"])
@@ -281,7 +297,8 @@ def chunked_leg(B, cfg, eng, blob, reqs, K, W, args):
                 projection_TFLOPs=round(flops / dt / 1e12, 1),
                 frac_of_mfma_peak=round(flops / dt / 1e12 / (2500.0 if cfg["dtype"] == 1 else 157.3), 4),
                 itl_ms=dict(p50=pct(itl, 50), p99=pct(itl, 99), n=int(len(itl))),
-                sched_us_per_iteration=dict(median=pct(sched_us, 50), p99=pct(sched_us, 99)))
+                sched_us_per_iteration=dict(median=pct(sched_us, 50), p99=pct(sched_us, 99)),
+                **({"kernel_times_us": kernel_times} if kernel_times else {}))
 
 
 def claim_latency(B, e, vocab, n=24):

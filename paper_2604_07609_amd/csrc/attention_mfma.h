@@ -342,7 +342,7 @@ __device__ __forceinline__ void attn_prefill(const DevCtx& c, u32 layer, AttnMfm
   // now taking WPI wave slots, still fit the waves that run at once
   u32 WPI = 1;
   {
-    const u32 chain = (c.meta->max_ctx + 15) / 16;
+    const u32 chain = (c.meta->max_pref_ctx + 15) / 16;
     const u64 slots = (u64)(nwg / 2) * nw;
     while (WPI < nw && WPI < 8 && chain > 12 * WPI && total * WPI <= slots) WPI *= 2;
     const u32 forced = (c.tune_nw >> 16) & 15u;      // bits 16-19 of the tuning word: 1, 2, 4, 8 force it (tests)
@@ -482,11 +482,19 @@ __device__ __forceinline__ void attn_prefill_hd(const DevCtx& c, u32 layer, Attn
 __device__ __forceinline__ void phase_attention_mfma(const DevCtx& c, u32 layer, AttnMfmaShared& sh, u32 wg, u32 nwg) {
   const u32 B = c.meta->n_seqs;
   const bool dec = c.cu_chunks[B] != 0, pre = c.cu_qtiles[B] != 0;
+  // In a mixed iteration every other workgroup takes its query tiles first: the decode items stream the KV cache from
+  // HBM while the query tiles mostly wait on L2 and the softmax, so the two parts are spread over the launch instead
+  // of all workgroups hitting HBM first and L2 afterwards.
+  const bool pre_first = dec && pre && (wg & 1u) && !(c.tune_nw & 0x40000000u);   // bit 30 of the tuning word: decode part first everywhere (A/B)
+  if (pre_first) {
+    if (c.hd == 64) attn_prefill_hd<64>(c, layer, sh, wg, nwg); else attn_prefill_hd<128>(c, layer, sh, wg, nwg);
+    __syncthreads();
+  }
   if (dec) {
     if (c.hd == 64) attn_decode<64>(c, layer, sh, wg, nwg); else attn_decode<128>(c, layer, sh, wg, nwg);
   }
-  if (dec && pre) __syncthreads();   // the batch metadata in LDS is staged again for the other part
-  if (pre) {
+  if (dec && pre && !pre_first) __syncthreads();   // the batch metadata in LDS is staged again for the other part
+  if (pre && !pre_first) {
     if (c.hd == 64) attn_prefill_hd<64>(c, layer, sh, wg, nwg); else attn_prefill_hd<128>(c, layer, sh, wg, nwg);
   }
 }

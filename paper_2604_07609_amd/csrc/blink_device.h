@@ -92,7 +92,7 @@ struct IterMeta {
   u32 trace_idx;
   u32 skip;             // 1: the window has ended, phases do nothing (the rest describes the last real iteration)
   u32 n_samples;        // sequences that sample a token in this iteration (all of them unless a prompt chunk leaves its prompt incomplete)
-  u32 pad;
+  u32 max_pref_ctx;     // longest context after this iteration among the sequences that process prompt tokens
 };
 
 struct TraceRec {       // mirrors blink_trace_record

@@ -287,7 +287,7 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
   // Sequences of the iteration: without chunking the newly admitted (prefill iteration) or all running (decode
   // iteration); with chunking all running, each with its share of the token budget. A sequence samples a token
   // unless its prompt is still incomplete after this iteration.
-  u32 n_seqs = 0, n_tok = 0, n_alloc = 0, n_qt = 0, n_ch = 0, n_smp = 0, n_dec_seq = 0, max_q = 0, max_ctx = 0;
+  u32 n_seqs = 0, n_tok = 0, n_alloc = 0, n_qt = 0, n_ch = 0, n_smp = 0, n_dec_seq = 0, max_q = 0, max_ctx = 0, max_pref = 0;
   u64 n_ctx = 0;
   if (kind != KIND_IDLE) {
     for (u32 base = 0; base < c.max_batch; base += BLK_THREADS) {
@@ -363,6 +363,7 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
       }
       max_q = max(max_q, block_max(ntok, sh.wave_part2));
       max_ctx = max(max_ctx, block_max(ctx_after, sh.wave_part));
+      max_pref = max(max_pref, block_max(pref ? ctx_after : 0u, sh.wave_part2));
       n_ctx += totx;
       n_seqs += tots;
       n_alloc += tota;
@@ -441,6 +442,7 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
     m->n_tokens = n_tok;
     m->max_q_len = max_q;
     m->max_ctx = max_ctx;
+    m->max_pref_ctx = max_pref;
     u32 stopped = 0;
     if (kind != KIND_IDLE) {
       const u64 it = ss->iteration;
