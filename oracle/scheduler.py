@@ -30,6 +30,17 @@ min(prompt tokens left, budget left); a request is admitted only while budget is
 token in the iteration that admits it, and at most one request is ever part-way), a batch slot is free and its
 reservation fits. A request samples its first token in the iteration that processes the last token of its prompt;
 blocks are allocated as the cached length grows. Decodes are not paused in this mode.
+
+On-demand KV growth with preemption (`preempt=True`; the paper's slot life cycle has DECODE_PAUSED "to support
+preemption", section 4.2, and says no more). The reading taken here replaces the worst-case reservation: a request is
+admitted when the blocks of the tokens it must prefill are free NOW (beside those promised to requests admitted before it
+in the same iteration); decoding requests take a block from the free stack when their context fills their blocks. When a
+decode iteration needs more blocks than are free, running requests are preempted, the most recently submitted (highest
+ticket) first, until the rest fits: a victim gives back all its blocks (in block-table order), leaves its batch slot and
+goes to DECODE_PAUSED. Preempted requests are resumed before any new request is admitted, lowest ticket first, by
+recomputation: the resumed request prefills its prompt followed by the tokens it has generated so far and samples its
+next output token from the last position, so its stream continues where it stopped. The oldest running request is never
+short of blocks once the others are gone, because a request that could not fit the pool alone is refused at submission.
 """
 import numpy as np
 
@@ -58,6 +69,8 @@ class Plan:
         self.iteration = 0
         self.tail = 0
         self.admitted = []      # tickets admitted this iteration, in order
+        self.resumed = []       # preemption mode: tickets resumed this iteration (before the admissions), in order
+        self.preempted = []     # preemption mode: tickets preempted this iteration, in order (highest ticket first)
         self.batch_slots = []   # batch slot of each sequence in this iteration, ascending
         self.tickets = []
         self.seq_lens = []      # context length of each sequence after this iteration's tokens
@@ -86,8 +99,10 @@ def blocks_needed(P, max_new, bs):
 
 class Scheduler:
     def __init__(self, n_blocks, block_size, max_batch, max_prefill_tokens, ring_slots, eos_token_id=-1,
-                 free_list=None, chunked=False):
-        self.chunked = chunked
+                 free_list=None, chunked=False, preempt=False):
+        self.chunked, self.preempt = chunked, preempt
+        assert not (chunked and preempt), "preemption is defined for the plain (pause-and-resume) mode only"
+        self.preempted = []         # Running records of preempted requests (no blocks, no batch slot)
         if chunked:
             assert max_prefill_tokens > max_batch, "the token budget must leave room for a prompt token beside the decodes"
         self.n_blocks, self.bs, self.max_batch = n_blocks, block_size, max_batch
@@ -107,7 +122,7 @@ class Scheduler:
     def from_engine(cls, eng):
         """From an engine configuration dict (synth.configs)."""
         return cls(eng["kv_num_blocks"], eng["kv_block_size"], eng["max_batch"], eng["max_prefill_tokens"], eng["ring_slots"],
-                   eng.get("eos_token_id", -1), chunked=bool(eng.get("chunked_prefill", False)))
+                   eng.get("eos_token_id", -1), chunked=bool(eng.get("chunked_prefill", False)), preempt=bool(eng.get("preemption", False)))
 
     # ---- ring side -------------------------------------------------------------------
     def submit(self, prompt, max_new):
@@ -127,6 +142,8 @@ class Scheduler:
     def step(self, tail):
         if self.chunked:
             return self._step_chunked(tail)
+        if self.preempt:
+            return self._step_preempt(tail)
         bs = self.bs
         plan = Plan()
         plan.tail = tail
@@ -192,6 +209,118 @@ class Scheduler:
                 toks = list(self.requests[r.ticket][0])
                 pos = list(range(r.P))
                 r.ctx_len = r.P
+            else:
+                if r.ctx_len == len(r.blocks) * bs:
+                    r.blocks.append(self.free.pop())
+                toks = [r.last_token]
+                pos = [r.ctx_len]
+                r.ctx_len += 1
+            plan.batch_slots.append(b)
+            plan.tickets.append(r.ticket)
+            plan.seq_lens.append(r.ctx_len)
+            plan.input_ids += [int(x) for x in toks]
+            plan.positions += pos
+            plan.slot_mapping += [r.blocks[p // bs] * bs + p % bs for p in pos]
+            plan.tok_seq += [si] * len(pos)
+            plan.cu_seqlens.append(len(plan.input_ids))
+            plan.last_idx.append(len(plan.input_ids) - 1)
+            plan.block_tables.append(list(r.blocks))
+            plan.gen_index.append(r.gen)
+            plan.sample_seq.append(si)
+            plan.pos0.append(pos[0])
+        plan.free_blocks_after = len(self.free)
+        return plan
+
+    # ---- one iteration with on-demand KV growth and preemption ------------------------------------------------------
+    def _step_preempt(self, tail):
+        bs = self.bs
+        plan = Plan()
+        plan.tail = tail
+        # (1) retire
+        for b in range(self.max_batch):
+            r = self.running[b]
+            if r is not None and r.finished:
+                self.free.extend(r.blocks)
+                self.running[b] = None
+        # (2)+(3) resume the preempted (lowest ticket first), then admit new tickets, strictly in that order: the first that
+        # does not fit stops everything behind it. A request fits when a batch slot is free and the blocks of the tokens
+        # it prefills are free beside those promised earlier in this iteration; the prefill-token budget as in the plain mode
+        promised = admitted_tokens = 0
+        new_slots = []
+        while True:
+            cand = min(self.preempted, key=lambda r: r.ticket) if self.preempted else None
+            if cand is None:
+                if self.next_ticket >= tail:
+                    break
+                t = self.next_ticket
+                prompt, max_new = self.requests[t]
+                cand = Running()
+                cand.ticket, cand.P, cand.max_new, cand.gen = t, prompt.size, max_new, 0
+                cand.finished, cand.last_token = False, -1
+            n_tok = cand.P + cand.gen                       # tokens to prefill: the prompt and what was generated so far
+            need = -(-n_tok // bs)
+            free_slots = [b for b in range(self.max_batch) if self.running[b] is None]
+            if not free_slots or promised + need > len(self.free):
+                break
+            if new_slots and admitted_tokens + n_tok > self.max_prefill_tokens:
+                break
+            cand.ctx_len, cand.reserved, cand.blocks, cand.prefilled = 0, 0, [], n_tok
+            b = free_slots[0]
+            self.running[b] = cand
+            promised += need
+            admitted_tokens += n_tok
+            new_slots.append(b)
+            if cand in self.preempted:
+                self.preempted.remove(cand)
+                plan.resumed.append(cand.ticket)            # stays DECODE_PAUSED until its next token is published
+            else:
+                plan.admitted.append(cand.ticket)
+                self._set(cand.ticket, PREFILL_PROCESSING)
+                self.next_ticket = cand.ticket + 1
+        # (4) kind
+        if new_slots:
+            plan.kind = PREFILL
+            slots = sorted(new_slots)
+            for b in range(self.max_batch):   # running decodes are paused for this iteration
+                r = self.running[b]
+                if r is not None and b not in new_slots and self.state[r.ticket] == DECODE_PROCESSING:
+                    self._set(r.ticket, DECODE_PAUSED)
+        else:
+            if not any(r is not None for r in self.running):
+                plan.kind = IDLE
+                return plan
+            plan.kind = DECODE
+            # preempt, highest ticket first, until the blocks this iteration needs are free
+            def needed():
+                return sum(1 for r in self.running if r is not None and r.ctx_len == len(r.blocks) * bs)
+            while needed() > len(self.free):
+                b = max((b for b in range(self.max_batch) if self.running[b] is not None), key=lambda b: self.running[b].ticket)
+                r = self.running[b]
+                self.free.extend(r.blocks)
+                r.blocks = []
+                self.running[b] = None
+                self.preempted.append(r)
+                plan.preempted.append(r.ticket)
+                if self.state[r.ticket] == DECODE_PROCESSING:
+                    self._set(r.ticket, DECODE_PAUSED)
+            slots = [b for b in range(self.max_batch) if self.running[b] is not None]
+            assert slots, "the oldest request always fits the pool alone"
+            for b in slots:
+                r = self.running[b]
+                if self.state[r.ticket] == DECODE_PAUSED:
+                    self._set(r.ticket, DECODE_PROCESSING)
+        plan.iteration = self.iteration
+        self.iteration += 1
+        # (5) allocate, (6) metadata
+        for si, b in enumerate(slots):
+            r = self.running[b]
+            if plan.kind == PREFILL:
+                n_tok = r.P + r.gen
+                for _ in range(-(-n_tok // bs)):
+                    r.blocks.append(self.free.pop())
+                toks = list(self.requests[r.ticket][0]) + list(self.outputs[r.ticket][:r.gen])
+                pos = list(range(n_tok))
+                r.ctx_len = n_tok
             else:
                 if r.ctx_len == len(r.blocks) * bs:
                     r.blocks.append(self.free.pop())
@@ -319,8 +448,8 @@ class Scheduler:
             r.gen += 1
             r.last_token = tok
             done = r.gen == r.max_new or tok == self.eos
-            if self.state[r.ticket] == PREFILL_PROCESSING and not done:
-                self._set(r.ticket, DECODE_PROCESSING)
+            if self.state[r.ticket] in (PREFILL_PROCESSING, DECODE_PAUSED) and not done:
+                self._set(r.ticket, DECODE_PROCESSING)     # (DECODE_PAUSED: a preempted request that has just been recomputed)
             if done:
                 r.finished = True
                 self._set(r.ticket, DECODE_COMPLETED)
@@ -333,11 +462,14 @@ class Scheduler:
         allb = held + self.free
         assert len(allb) == self.n_blocks, "block leaked or duplicated"
         assert len(set(allb)) == self.n_blocks, "block id appears twice"
-        assert sum(r.reserved for r in self.running if r is not None) == self.committed
-        assert len(held) <= self.committed <= self.n_blocks
+        if not self.preempt:
+            assert sum(r.reserved for r in self.running if r is not None) == self.committed
+            assert len(held) <= self.committed <= self.n_blocks
+        for r in self.preempted:
+            assert not r.blocks and self.state[r.ticket] == DECODE_PAUSED
         for r in self.running:
             if r is not None:
-                assert len(r.blocks) <= r.reserved
+                assert self.preempt or len(r.blocks) <= r.reserved
                 assert len(r.blocks) * self.bs >= r.ctx_len
         for (_, a, b) in self.transitions:
             assert (a, b) in LEGAL_EDGES, (a, b)

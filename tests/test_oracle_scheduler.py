@@ -273,3 +273,105 @@ def test_chunked_service_equals_per_request_generation():
     assert max(len(p) for p in [r["prompt"] for r in reqs]) > 2 * eng["max_prefill_tokens"]     # prompts span three iterations
     for t, r in enumerate(reqs):
         assert sched.outputs[t] == SV.generate_reference(cfg, W, r), t
+
+
+# ---- on-demand KV growth with preemption --------------------------------------------------------------------------------
+
+def test_preemption_hand_worked_three_requests_pool_of_four():
+    """bs 16, 4 blocks, 3 batch slots; requests (P, max_new) = (16,20), (16,4), (10,3), all there at the start. By hand:
+      it 0: all three fit (one block each, no worst-case reservation): blocks A [0], B [1], C [2]; one block left.
+      it 1: A and B have filled their block and need one more each, one is free: the highest ticket, C, is preempted
+            (its block 2 goes back on top of the stack); A takes 2, B takes 3.
+      it 2, 3: C needs one block to come back and none is free: it waits (and no one else could be admitted either);
+            A and B decode; B emits its fourth token in it 3.
+      it 4: B retires (1, 3 back), C resumes into slot 1 by recomputing its 10 prompt tokens + its one output token, block 3;
+            it samples output index 1; A is paused for this prefill iteration.
+      it 5: A and C decode; C ends. Then A decodes alone, takes block 3 when its context reaches 32, and ends."""
+    s = Scheduler(4, 16, 3, 8192, 8, preempt=True)
+    plans = []
+    SV.run_schedule(s, [req(16, 20), req(16, 4), req(10, 3)], lambda pl: [7] * len(pl.sample_seq), on_plan=plans.append)
+    exp = [   # kind, tickets, batch slots, admitted, resumed, preempted, block tables, free after, gen index
+        (PREFILL, [0, 1, 2], [0, 1, 2], [0, 1, 2], [], [], [[0], [1], [2]], 1, [0, 0, 0]),
+        (DECODE, [0, 1], [0, 1], [], [], [2], [[0, 2], [1, 3]], 0, [1, 1]),
+        (DECODE, [0, 1], [0, 1], [], [], [], [[0, 2], [1, 3]], 0, [2, 2]),
+        (DECODE, [0, 1], [0, 1], [], [], [], [[0, 2], [1, 3]], 0, [3, 3]),
+        (PREFILL, [2], [1], [], [2], [], [[3]], 1, [1]),
+        (DECODE, [0, 2], [0, 1], [], [], [], [[0, 2], [3]], 1, [4, 2]),
+    ]
+    for pl, e in zip(plans, exp):
+        got = (pl.kind, pl.tickets, pl.batch_slots, pl.admitted, pl.resumed, pl.preempted, pl.block_tables, pl.free_blocks_after, pl.gen_index)
+        assert got == e, (pl.iteration, got, e)
+    assert plans[4].input_ids == [int(x) for x in req(10, 3)["prompt"]] + [7] and plans[4].positions == list(range(11))
+    assert plans[4].slot_mapping == list(range(48, 59)) and plans[4].last_idx == [10]
+    assert [len(s.outputs[t]) for t in range(3)] == [20, 4, 3]
+    grow = next(pl for pl in plans if pl.tickets == [0] and len(pl.block_tables[0]) == 3)
+    assert grow.positions == [32] and grow.block_tables == [[0, 2, 3]]
+    s.step(3)
+    assert sorted(s.free) == [0, 1, 2, 3] and not s.preempted
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_preemption_invariants_under_random_load(seed):
+    """A pool far below the worst-case demand: blocks are conserved, every request emits exactly its count with output
+    indices 0,1,2,.. in order (a stream continues where it stopped), a resumed request prefills its prompt followed by
+    its own outputs, only the highest tickets are preempted, resumptions come before admissions, and preemptions occur."""
+    rng = np.random.default_rng(seed)
+    n = 40
+    reqs = [req(int(rng.integers(1, 60)), int(rng.integers(4, 40))) for _ in range(n)]
+    need_max = max(blocks_needed(len(r["prompt"]), r["max_new_tokens"], 16) for r in reqs)
+    s = Scheduler(need_max + 3, 16, 6, 200, 16, preempt=True)
+    next_index = {t: 0 for t in range(n)}
+    stats = dict(preempted=0, resumed=0)
+
+    def on_plan(pl):
+        stats["preempted"] += len(pl.preempted)
+        stats["resumed"] += len(pl.resumed)
+        running_tickets = [r.ticket for r in s.running if r is not None]
+        for v in pl.preempted:
+            assert all(v > t for t in running_tickets)          # the victims were the most recently submitted
+        if pl.admitted:
+            assert not s.preempted                               # nobody waits preempted while a new ticket is admitted
+        for i, t in zip(pl.sample_seq, pl.sample_tickets):
+            assert pl.gen_index[pl.sample_seq.index(i)] == next_index[t]
+            next_index[t] += 1
+        for i, t in enumerate(pl.tickets):
+            if t in pl.resumed:
+                toks = pl.input_ids[pl.cu_seqlens[i]:pl.cu_seqlens[i + 1]]
+                assert toks == [int(x) for x in reqs[t]["prompt"]] + s.outputs[t]
+
+    SV.run_schedule(s, reqs, lambda pl: [int(rng.integers(0, 50)) for _ in pl.sample_seq], on_plan=on_plan)
+    assert [len(s.outputs[t]) for t in range(n)] == [r["max_new_tokens"] for r in reqs]
+    assert stats["preempted"] > 0 and stats["preempted"] == stats["resumed"]
+    s.step(n)
+    assert sorted(s.free) == list(range(s.n_blocks)) and not s.preempted
+
+
+def test_preemption_mode_equals_plain_mode_when_the_pool_never_binds():
+    reqs = [req(20, 3), req(10, 5, first=7), req(33, 2, first=11), req(5, 9, first=3)]
+    a, b = Scheduler(64, 16, 3, 8192, 8), Scheduler(64, 16, 3, 8192, 8, preempt=True)
+    pa, pb = [], []
+    SV.run_schedule(a, reqs, lambda pl: [5] * len(pl.sample_seq), on_plan=pa.append)
+    SV.run_schedule(b, reqs, lambda pl: [5] * len(pl.sample_seq), on_plan=pb.append)
+    assert len(pa) == len(pb)
+    for x, y in zip(pa, pb):
+        for f in ("kind", "tickets", "batch_slots", "input_ids", "positions", "slot_mapping", "tok_seq", "cu_seqlens", "last_idx",
+                  "block_tables", "gen_index", "sample_seq", "free_blocks_after", "admitted"):
+            assert getattr(x, f) == getattr(y, f), (x.iteration, f)
+        assert not y.preempted and not y.resumed
+
+
+def test_preempted_service_equals_per_request_generation():
+    """The model side of recomputation: a request that is preempted and later resumed by prefilling prompt + outputs so
+    far continues with exactly the tokens it would have generated alone."""
+    cfg = dict(synth.model_config("tiny"), n_layers=2, vocab=97, d_model=64, n_q_heads=4, n_kv_heads=2, head_dim=16, d_ffn=96)
+    raw = synth.make_weights(cfg, 6, gain_jitter=0.1)
+    W = M.Weights(cfg, raw)
+    rng = np.random.default_rng(4)
+    reqs = [dict(prompt=rng.integers(0, 97, P).astype(np.int32), max_new_tokens=n, temperature=0.0, top_k=0, top_p=1.0, seed=0)
+            for P, n in ((16, 30), (16, 12), (10, 20), (30, 8))]
+    eng = dict(kv_block_size=16, kv_num_blocks=5, max_batch=3, max_prefill_tokens=100, ring_slots=8, eos_token_id=-1, preemption=True)
+    seen = []
+    ev, sched = SV.serve(cfg, W, eng, reqs, on_plan=lambda pl: seen.extend(pl.preempted))
+    assert seen                                                   # somebody was preempted
+    for t, r in enumerate(reqs):
+        assert sched.outputs[t] == SV.generate_reference(cfg, W, r), t
