@@ -51,6 +51,14 @@ extern "C" {
                                         in the iteration that processes the last token of its prompt. Without the flag an
                                         admission makes a prefill-only iteration and running decodes pause (section 4.2) */
 
+#define BLINK_FLAG_PREEMPTION 64u    /* on-demand KV growth (section 4.2: the DECODE_PAUSED state exists "to support preemption"):
+                                        no worst-case reservation; a request is admitted when the blocks of its prompt are free,
+                                        decoding requests take blocks as their contexts grow, and when a decode iteration needs
+                                        more blocks than are free the most recently submitted running requests are preempted
+                                        (blocks back to the free list, DECODE_PAUSED) and later resumed, before any new
+                                        admission and lowest ticket first, by recomputing prompt + tokens generated so far.
+                                        Not together with BLINK_FLAG_CHUNKED_PREFILL */
+
 /* slot life cycle of the ring (section 4.2, "Ring buffer") */
 enum {
   BLINK_SLOT_EMPTY = 0,
@@ -130,6 +138,8 @@ typedef struct {
   uint64_t chain;              /* ordinal of the scheduler kernel launch that ran this iteration, counted since init over
                                   all launches (idle polls and launches past the end of a window included): lines a
                                   profiler's list of dispatches up with the iterations */
+  uint32_t n_resumed;          /* preempted requests resumed in this iteration (they prefill before the admitted ones) */
+  uint32_t n_preempted;        /* requests preempted in this iteration */
 } blink_trace_record;
 
 typedef struct {

@@ -6,7 +6,7 @@ import numpy as np
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 
-FLAG_TRACE, FLAG_EXIT_WHEN_IDLE, FLAG_KEEP_LOGITS, FLAG_NO_GRAPH, FLAG_CHUNKED_PREFILL = 1, 2, 8, 16, 32
+FLAG_TRACE, FLAG_EXIT_WHEN_IDLE, FLAG_KEEP_LOGITS, FLAG_NO_GRAPH, FLAG_CHUNKED_PREFILL, FLAG_PREEMPTION = 1, 2, 8, 16, 32, 64
 ERR_INVAL, ERR_TOO_LARGE, ERR_FULL, ERR_DEVICE, ERR_STATE = -1, -2, -3, -4, -5
 EVENT_FIRST, EVENT_LAST = 1, 2
 
@@ -46,7 +46,7 @@ EVENT_DTYPE = np.dtype([("request_id", "<u8"), ("index", "<u4"), ("token", "<i4"
 TRACE_DTYPE = np.dtype([("iteration", "<u4"), ("kind", "<u4"), ("tail", "<u8"), ("n_admitted", "<u4"), ("n_seqs", "<u4"),
                         ("n_tokens", "<u4"), ("free_blocks", "<u4"), ("first_admitted", "<u8"), ("t_sched_begin_ns", "<u8"),
                         ("t_sched_end_ns", "<u8"), ("t_forward_end_ns", "<u8"), ("t_publish_end_ns", "<u8"), ("ctx_tokens", "<u8"),
-                        ("chain", "<u8")],
+                        ("chain", "<u8"), ("n_resumed", "<u4"), ("n_preempted", "<u4")],
                        align=True)
 
 
@@ -142,6 +142,8 @@ class Engine:
         cfg.weights_bytes = blob.nbytes
         if engine.get("chunked_prefill"):
             flags |= FLAG_CHUNKED_PREFILL
+        if engine.get("preemption"):
+            flags |= FLAG_PREEMPTION
         cfg.device, cfg.flags, cfg.trace_capacity, cfg.idle_poll_us = device, flags, trace_capacity, idle_poll_us
         cfg.pump_depth, cfg.tune = pump_depth, tune
         self.h = C.c_void_p()

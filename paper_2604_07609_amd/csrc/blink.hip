@@ -274,6 +274,7 @@ static int init_impl(const blink_config* cfg, blink_engine* e) {
   // ---- scheduler state ----
   if (int rc = dalloc(e, &c.ss, 1)) return rc;
   if (int rc = dalloc(e, &c.run, c.max_batch)) return rc;
+  if (int rc = dalloc(e, &c.preq, c.max_batch)) return rc;
   if (int rc = dalloc(e, &c.block_tables, (u64)c.max_batch * c.max_blocks_per_seq)) return rc;
   if (int rc = dalloc(e, &c.free_stack, c.n_blocks)) return rc;
   if (int rc = dalloc(e, &c.meta, 1)) return rc;
@@ -479,6 +480,8 @@ extern "C" int blink_init(const blink_config* cfg, blink_engine** out) {
   if (cfg->dtype == 1 && cfg->max_batch > ATTN_META_MAX)
     return fail(BLINK_ERR_INVAL, "bf16 models take at most %d batch slots (attention keeps the batch metadata in LDS)", ATTN_META_MAX);
   if (!cfg->max_seq_len || !cfg->max_prefill_tokens) return fail(BLINK_ERR_INVAL, "max_seq_len and max_prefill_tokens must be positive");
+  if ((cfg->flags & BLINK_FLAG_CHUNKED_PREFILL) && (cfg->flags & BLINK_FLAG_PREEMPTION))
+    return fail(BLINK_ERR_INVAL, "preemption is built for the plain (pause-and-resume) mode, not together with chunked prefill");
   if ((cfg->flags & BLINK_FLAG_CHUNKED_PREFILL) && cfg->max_prefill_tokens <= cfg->max_batch)
     return fail(BLINK_ERR_INVAL, "chunked prefill: max_prefill_tokens (the token budget of an iteration) must exceed max_batch");
   if (!cfg->ring_slots || (cfg->ring_slots & (cfg->ring_slots - 1))) return fail(BLINK_ERR_INVAL, "ring_slots must be a power of two");

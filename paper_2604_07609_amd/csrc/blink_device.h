@@ -78,6 +78,8 @@ struct SchedState {
   u32 error;
   u32 pad;
   u64 iter_limit;       // the window ends once `iteration` reaches this (0: no limit); set at blink_run
+  u32 n_preempted;      // preempted requests waiting to be resumed (entries of DevCtx::preq)
+  u32 pad2;
   u64 chains;           // scheduler kernels run so far (iterations, idle polls and launches past the end of a window)
 };
 
@@ -103,6 +105,7 @@ struct TraceRec {       // mirrors blink_trace_record
   u64 t_sched_begin, t_sched_end, t_forward_end, t_publish_end;
   u64 ctx_tokens;
   u64 chain;
+  u32 n_resumed, n_preempted;
 };
 
 // host-visible mirror in pinned host memory, written by the scheduler with system-scope stores
@@ -157,6 +160,7 @@ struct DevCtx {
   // scheduler
   SchedState* ss;
   RunEntry* run;
+  RunEntry* preq;       // [max_batch] preemption mode: the preempted requests (no blocks, no batch slot), unordered
   u32* block_tables;    // [max_batch][max_blocks_per_seq]
   u32* free_stack;      // [n_blocks]
   IterMeta* meta;

@@ -299,6 +299,7 @@ __device__ __forceinline__ void phase_sample_publish(const DevCtx& c, SamplerSha
       o->device_ns = dev_now_ns();
       r.gen = idx + 1;
       r.last_token = token;
+      r.paused = 0;             // the status word written below says PROCESSING or COMPLETED (a resumed request was PAUSED until now)
       const bool done = (idx + 1 == r.max_new) || (token == c.eos);
       u32 state = SLOT_DECODE_PROCESSING;
       if (done) {

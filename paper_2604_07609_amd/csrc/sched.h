@@ -31,9 +31,11 @@ struct SchedShared {
   u32 seq_bslot[SCHED_MAX_BATCH];
   u32 seq_ring[SCHED_MAX_BATCH];
   u32 seq_pos0[SCHED_MAX_BATCH];
+  u32 seq_P[SCHED_MAX_BATCH];        // prompt length: positions beyond it take the request's own output tokens (a resumed request)
   u32 flag;
   u32 exit_idle;
   u64 chain;
+  u64 part64[8];
 };
 
 // Exclusive prefix sum over the 256 threads of the workgroup; total returned in `total`.
@@ -68,6 +70,22 @@ __device__ __forceinline__ u32 block_max(u32 v, u32* part) {
   u32 m = 0;
 #pragma unroll
   for (u32 i = 0; i < BLK_THREADS / WAVE; ++i) m = max(m, part[i]);
+  return m;
+}
+
+// Maximum of a 64-bit key over the 256 threads of the workgroup (part: 8 x u64 of LDS).
+__device__ __forceinline__ u64 block_max64(u64 v, u64* part) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const u64 t = __shfl_xor(v, o);
+    v = t > v ? t : v;
+  }
+  __syncthreads();
+  if ((threadIdx.x & 63u) == 0) part[threadIdx.x >> 6] = v;
+  __syncthreads();
+  u64 m = part[0];
+#pragma unroll
+  for (u32 i = 1; i < BLK_THREADS / WAVE; ++i) m = part[i] > m ? part[i] : m;
   return m;
 }
 
@@ -196,11 +214,52 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
     __syncthreads();
   }
 
+  // ---- preemption mode: the preempted requests come back first, lowest ticket first, one at a time (a rare path); the
+  // first that does not fit stops every admission behind it. A request fits when a batch slot is free and the blocks of
+  // the tokens it prefills (its prompt and what it has generated so far) are free beside those promised before it.
+  const bool preempt = (c.flags & 64u) != 0;
+  u32 resumed = 0, promised = 0, tokens_admitted = 0, n_pre = preempt ? ss->n_preempted : 0u;
+  bool blocked = false;
+  while (n_pre > 0 && !blocked) {
+    u64 key = 0;                                   // smallest ticket = largest inverted ticket; low bits: the entry's index
+    for (u32 i = tid; i < n_pre; i += BLK_THREADS) {
+      const u64 k = ((~c.preq[i].ticket) << 12) | i;
+      key = k > key ? k : key;
+    }
+    key = block_max64(key, sh.part64);
+    const u32 idx = (u32)(key & 0xFFFu);
+    const RunEntry cand = c.preq[idx];
+    const u32 ntok = cand.P + cand.gen, need = (ntok + c.bs - 1) / c.bs;
+    __syncthreads();                               // everyone has read the entry before it is overwritten below
+    if (resumed >= n_free || promised + need > top || (resumed > 0 && (u64)tokens_admitted + ntok > (u64)c.max_prefill_tokens)) {
+      blocked = true;
+      break;
+    }
+    if (tid == 0) {
+      RunEntry& r = c.run[sh.free_list[resumed]];
+      r = cand;
+      r.valid = 1;
+      r.ctx_len = 0;
+      r.n_blocks = 0;
+      r.reserved = 0;
+      r.in_iter = 1;
+      r.prefilled = ntok;
+      r.chunk = ntok;
+      c.preq[idx] = c.preq[n_pre - 1];             // the last entry fills the hole
+    }
+    __syncthreads();
+    promised += need;
+    tokens_admitted += ntok;
+    ++resumed;
+    --n_pre;
+  }
+
   // ---- (2) poll the ring + (3) admit FCFS, 256 candidate tickets at a time ----------------------------------
-  u32 admitted = 0, tokens_admitted = 0;
+  u32 admitted = 0;
   u64 tail = next0;
   u64 first_admitted = 0;
   for (;;) {
+    if (blocked) break;                            // a preempted request waits: nobody overtakes it
     const u64 t = next0 + admitted + tid;
     const u32 slot = (u32)(t & (u64)(c.ring_slots - 1));
     bool pend = false;
@@ -221,16 +280,16 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
     }
     u32 need = 0;
     if (cand) {
-      need = (P + max_new - 1 + c.bs - 1) / c.bs;
+      need = preempt ? (P + c.bs - 1) / c.bs : (P + max_new - 1 + c.bs - 1) / c.bs;   // blocks of the prompt now, or the worst-case reservation
       if (need == 0) need = 1;
     }
     u32 totn, totp;
     const u32 sn = block_excl_scan(need, totn, sh.wave_part) + need;     // inclusive
     const u32 sp = block_excl_scan(cand ? P : 0u, totp, sh.wave_part2) + (cand ? P : 0u);
-    const u32 ord = admitted + tid;                                        // admission order within the iteration
+    const u32 ord = resumed + admitted + tid;                              // admission order within the iteration
     // tokens of the budget already spoken for when this candidate's turn comes (chunked mode)
     const u64 before = (u64)used + tokens_admitted + (sp - (cand ? P : 0u));
-    const bool ok = cand && ord < n_free && (u64)committed + sn <= (u64)c.n_blocks &&
+    const bool ok = cand && ord < n_free && (preempt ? (u64)promised + sn <= (u64)top : (u64)committed + sn <= (u64)c.n_blocks) &&
                     (chunked ? before < (u64)budget : (ord == 0 || (u64)tokens_admitted + sp <= (u64)c.max_prefill_tokens));
     const u32 adm = block_prefix_count(ok, sh.wave_part);
     if (tid < adm) {
@@ -243,7 +302,7 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
       r.max_new = max_new;
       r.gen = 0;
       r.ctx_len = 0;
-      r.reserved = need;
+      r.reserved = preempt ? 0u : need;
       r.n_blocks = 0;
       r.finished = 0;
       r.last_token = -1;
@@ -269,7 +328,7 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
     }
     __syncthreads();
     if (adm > 0) {
-      committed += sh.wave_part2[0];
+      if (preempt) promised += sh.wave_part2[0]; else committed += sh.wave_part2[0];
       tokens_admitted += sh.wave_part2[1];
       if (admitted == 0) first_admitted = next0;
     }
@@ -277,11 +336,55 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
     __syncthreads();
     if (adm < BLK_THREADS) break;   // stopped inside this chunk (nothing pending, or a limit was hit)
   }
-  nrun += admitted;
+  nrun += admitted + resumed;
 
   // ---- (4) kind: an iteration with prompt tokens in it counts as a prefill iteration ---------------------------
-  const u32 kind = (admitted > 0 || chunk_part > 0) ? KIND_PREFILL : (nrun > 0 ? KIND_DECODE : KIND_IDLE);
+  const u32 kind = (admitted + resumed > 0 || chunk_part > 0) ? KIND_PREFILL : (nrun > 0 ? KIND_DECODE : KIND_IDLE);
   __syncthreads();
+
+  // ---- preemption mode, decode iteration: when the sequences whose context has filled their blocks need more blocks
+  // than are free, the most recently submitted running request (highest ticket) gives up its blocks (back to the stack
+  // in block-table order), its batch slot and its place (DECODE_PAUSED), one request at a time until the rest fits ---
+  u32 n_preempted_now = 0;
+  if (preempt && kind == KIND_DECODE) {
+    u32 need_total = 0;
+    for (u32 base = 0; base < c.max_batch; base += BLK_THREADS) {
+      const u32 b = base + tid;
+      u32 tn;
+      block_excl_scan((b < c.max_batch && c.run[b].valid && c.run[b].ctx_len == c.run[b].n_blocks * c.bs) ? 1u : 0u, tn, sh.wave_part);
+      need_total += tn;
+    }
+    while (need_total > top && nrun > 1) {
+      u64 key = 0;
+      for (u32 b = tid; b < c.max_batch; b += BLK_THREADS)
+        if (c.run[b].valid) {
+          const u64 k = ((c.run[b].ticket + 1) << 12) | b;
+          key = k > key ? k : key;
+        }
+      key = block_max64(key, sh.part64);
+      const u32 b = (u32)(key & 0xFFFu);
+      const RunEntry v = c.run[b];
+      __syncthreads();
+      for (u32 j = tid; j < v.n_blocks; j += BLK_THREADS) c.free_stack[top + j] = c.block_tables[(u64)b * mbs + j];
+      if (tid == 0) {
+        RunEntry& q = c.preq[n_pre];
+        q = v;
+        q.valid = 0;
+        q.n_blocks = 0;
+        q.ctx_len = 0;
+        q.paused = 1;
+        c.run[b].valid = 0;
+        if (!v.paused) set_slot_state(&c.status[v.ring_slot], SLOT_DECODE_PAUSED);
+      }
+      __syncthreads();
+      top += v.n_blocks;
+      need_total -= (v.ctx_len == v.n_blocks * c.bs) ? 1u : 0u;
+      ++n_pre;
+      --nrun;
+      ++n_preempted_now;
+    }
+    if (need_total > top && tid == 0) ss->error = 3;     // cannot happen: a request that does not fit the pool alone is refused at submission
+  }
 
   // ---- (5) allocate + (6) metadata, batch slot ascending ----------------------------------------------------
   // Sequences of the iteration: without chunking the newly admitted (prefill iteration) or all running (decode
@@ -305,7 +408,7 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
           smp = !pref || r.prefilled + ntok == r.P;
         } else if (kind == KIND_PREFILL) {
           in = pref = smp = r.in_iter != 0;
-          ntok = r.P;
+          ntok = r.P + r.gen;                 // (gen > 0: a preempted request recomputes its prompt and its own outputs)
           if (!in && !r.paused) {
             set_slot_state(&c.status[r.ring_slot], SLOT_DECODE_PAUSED);   // running decodes wait for the prefill
             r.paused = 1;
@@ -389,6 +492,7 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
         sh.seq_bslot[s] = b;
         sh.seq_ring[s] = c.seq_ring[s];      // ~0u for a decoding sequence: its one token is already written
         sh.seq_pos0[s] = c.seq_pos0[s];
+        sh.seq_P[s] = c.run[b].P;
       }
       __syncthreads();
       for (u32 base = 0; base < n_tok; base += 4 * BLK_THREADS) {
@@ -409,8 +513,9 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
         for (int u = 0; u < 4; ++u) {
           const u32 ring = sh.seq_ring[sq[u]];
           blk[u] = c.block_tables[(u64)sh.seq_bslot[sq[u]] * mbs + pp[u] / c.bs];
-          id[u] = __hip_atomic_load(c.in_arena + (u64)(ring == ~0u ? 0u : ring) * c.max_seq_len + (ring == ~0u ? 0u : pp[u]), __ATOMIC_RELAXED,
-                                    __HIP_MEMORY_SCOPE_SYSTEM);
+          const u32 rs = ring == ~0u ? 0u : ring, P = sh.seq_P[sq[u]];
+          if (ring != ~0u && pp[u] >= P) id[u] = c.out_arena[(u64)rs * c.max_seq_len + (pp[u] - P)].token;
+          else id[u] = __hip_atomic_load(c.in_arena + (u64)rs * c.max_seq_len + (ring == ~0u ? 0u : pp[u]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -434,6 +539,7 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
     ss->committed = committed;
     ss->n_running = nrun;
     ss->next_ticket = next0 + admitted;
+    if (preempt) ss->n_preempted = n_pre;
     IterMeta* m = c.meta;
     m->kind = kind;
     m->skip = 0;
@@ -472,6 +578,8 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
         tr.t_publish_end = 0;
         tr.ctx_tokens = n_ctx;
         tr.chain = sh.chain;
+        tr.n_resumed = resumed;
+        tr.n_preempted = n_preempted_now;
       }
     } else {
       if (ss->idle_since_ns == 0) ss->idle_since_ns = now;

@@ -100,6 +100,7 @@ def check_against_oracle(cfg, W, eng, reqs, ev, trace, rtol, tails=None, tok_rto
                                            len(pl.admitted)), pl.iteration
         if pl.admitted:
             assert int(tr["first_admitted"]) == pl.admitted[0]
+        assert (int(tr["n_resumed"]), int(tr["n_preempted"])) == (len(pl.resumed), len(pl.preempted)), pl.iteration
     sched.step(len(reqs))
     stats["sched"] = sched
     return stats
