@@ -4,8 +4,9 @@
 A "step" is one iteration of the serving loop: scheduler step (retire, ring poll, FCFS admission, KV block
 allocation, batch metadata), forward pass over paged KV (prefill or decode), sampling, publication.
 The whole request set of the workload is resident in the HBM ring before the timed region starts
-(saturation load). An untimed fill phase runs until the device has admitted all it can (its first decode
-iteration: the batch is as full as batch slots and KV pool allow), then W warm-up iterations run untimed, then
+(saturation load). An untimed fill phase runs until the device has filled its batch and replaced one batch worth
+of requests by later ones (steady state: prefill and decode iterations alternate as requests finish), then W
+warm-up iterations run untimed, then
 exactly K iterations are timed on the product path (one HIP graph launch per iteration); K further iterations
 run with the dominant kernel's launches bracketed by HIP events for the roofline figure.
 
@@ -229,12 +230,16 @@ def open_loop(B, e, reqs, seconds):
 
 def chunked_leg(B, cfg, eng, blob, reqs, K, W, args):
     """The same saturation run with chunked prefill (mixed prefill + decode iterations under the engine's token budget,
-    the extension the paper names first): untimed fill until the batch slots are taken (or admission has stalled for eight
-    iterations), W warm-up iterations, K timed."""
+    the extension the paper names first): untimed fill until one batch worth of requests has been replaced by later ones,
+    W warm-up iterations, K timed."""
     eng = dict(eng, chunked_prefill=True, max_prefill_tokens=max(args.chunk_budget, eng["max_batch"] + 1))
     e = B.Engine(cfg, eng, blob, flags=B.FLAG_TRACE | B.FLAG_EXIT_WHEN_IDLE | (B.FLAG_NO_GRAPH if args.no_graph else 0), trace_capacity=1 << 16,
                  tune=args.tune)
+    ol = None
     try:
+        if args.open_loop_seconds > 0:
+            ol = open_loop(B, e, reqs, args.open_loop_seconds)     # the workload's own arrivals first (leaves the engine idle)
+        e.set_exit_when_idle(True)
         for r in reqs:
             e.submit_request(r)
         base, fill = e.stats(), 0
@@ -244,9 +249,8 @@ def chunked_leg(B, cfg, eng, blob, reqs, K, W, args):
             e.drain(16384)
             st = e.stats()
             fill = int(st["iterations"] - base["iterations"])
-            # full: every batch slot taken, or nothing admitted for eight iterations (pool-limited), or everything admitted
-            if st["n_running"] == eng["max_batch"] or st["n_running"] == 0 or st["next_ticket"] == base["next_ticket"] + len(reqs) \
-                    or (fill >= 8 and not np.any(e.trace(8)["n_admitted"] > 0)):
+            # steady: one batch worth of requests has been replaced by later ones (or everything has been admitted)
+            if st["n_running"] == 0 or st["next_ticket"] - base["next_ticket"] >= min(len(reqs), 2 * eng["max_batch"]):
                 break
         if W:
             e.run(W)
@@ -298,7 +302,7 @@ def chunked_leg(B, cfg, eng, blob, reqs, K, W, args):
                 frac_of_mfma_peak=round(flops / dt / 1e12 / (2500.0 if cfg["dtype"] == 1 else 157.3), 4),
                 itl_ms=dict(p50=pct(itl, 50), p99=pct(itl, 99), n=int(len(itl))),
                 sched_us_per_iteration=dict(median=pct(sched_us, 50), p99=pct(sched_us, 99)),
-                **({"kernel_times_us": kernel_times} if kernel_times else {}))
+                **({"open_loop": ol} if ol else {}), **({"kernel_times_us": kernel_times} if kernel_times else {}))
 
 
 def claim_latency(B, e, vocab, n=24):
@@ -365,6 +369,8 @@ def main():
                     "launch duration in decode and in prefill iterations as kernel_times_us")
     ap.add_argument("--no-graph", action="store_true", help="enqueue the kernels one by one in every window (BLINK_FLAG_NO_GRAPH)")
     ap.add_argument("--tune", type=lambda x: int(x, 0), default=0, help="blink_config.tune")
+    ap.add_argument("--preemption", action="store_true", help="on-demand KV growth with preemption instead of worst-case reservations "
+                    "(BLINK_FLAG_PREEMPTION; the chunked-prefill leg is skipped)")
     ap.add_argument("--requests", type=int, default=0)
     ap.add_argument("--max-batch", type=int, default=0, help="override the engine's batch slots")
     ap.add_argument("--kv-blocks", type=int, default=0, help="override the size of the KV pool (16-token blocks)")
@@ -405,6 +411,9 @@ def main():
         eng["max_batch"] = args.max_batch
     if args.kv_blocks:
         eng["kv_num_blocks"] = args.kv_blocks
+    if args.preemption:
+        eng["preemption"] = True
+        args.no_chunked_leg = True
     reqs = reqs[: eng["ring_slots"]]
     blob = synth.pack_blob(cfg, raw)
     t_gen = time.perf_counter() - t_gen
@@ -435,17 +444,21 @@ def main():
         sat0 = e.stats()
         for r in reqs:
             e.submit_request(r)
-        # untimed fill: admission is strict FCFS and a decode iteration only runs when nothing more can be admitted, so the
-        # first decode iteration in the trace means the batch is as full as batch slots and KV pool allow
-        fill = 0
-        while fill < 4000:
-            e.run(4)
+        # untimed fill, decided from device state: until the batch has filled (admission is strict FCFS and a decode
+        # iteration only runs when nothing more can be admitted, so a decode iteration in the trace means the batch is as
+        # full as batch slots and KV pool allow) AND one batch worth of requests has been replaced by later ones (the
+        # first cohort starts together and finishes nothing for a while: timed straight after the fill, a short window
+        # would see almost only decode iterations), or everything has been admitted
+        fill, turn = 0, min(len(reqs), 2 * eng["max_batch"])
+        seen_decode = False
+        while fill < 20000:
+            e.run(8)
             e.wait()
             e.drain(16384)
             st = e.stats()
             fill = int(st["iterations"] - sat0["iterations"])
-            tr_f = e.trace(8)
-            if np.any(tr_f["kind"][-4:] == 2) or st["n_running"] == 0:
+            seen_decode = seen_decode or bool(np.any(e.trace(8)["kind"] == 2))
+            if st["n_running"] == 0 or (seen_decode and st["next_ticket"] - sat0["next_ticket"] >= turn):
                 break
         if W:
             e.run(W)
@@ -585,7 +598,7 @@ def main():
         "dtype": "bf16" if cfg["dtype"] == 1 else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "requests_resident": len(reqs), "arrivals": "all resident at t=0 (saturation)",
                    "max_batch": eng["max_batch"], "kv_blocks": eng["kv_num_blocks"],
-                   "fill_iterations_before_warmup": fill,
+                   "fill_iterations_before_warmup": fill, "preemption": bool(eng.get("preemption", False)),
                    "arithmetic": ("bf16 weights and KV cache; projections on the half-precision matrix-core path (weights re-encoded "
                                   "exactly, activations between GEMMs in half precision), attention products in bf16, fp32 accumulation")
                                  if cfg["dtype"] == 1 else "fp32",

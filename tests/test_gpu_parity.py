@@ -483,3 +483,18 @@ def test_preemption_and_chunked_prefill_exclude_each_other(lib):
     with pytest.raises(lib.BlinkError) as ei:
         lib.Engine(cfg, dict(eng, preemption=True, chunked_prefill=True, max_prefill_tokens=300), blob)
     assert ei.value.code == lib.ERR_INVAL
+
+
+def test_preemption_several_victims_in_one_iteration(lib):
+    """Five requests whose contexts all fill their first block in the same decode iteration, one block free: two requests
+    are preempted at once (highest tickets first), and later two come back in the same prefill iteration, lowest ticket first."""
+    cfg, eng, raw, blob = setup("mini_gqa", 63)
+    eng = dict(eng, preemption=True, kv_num_blocks=6, max_batch=5, max_seq_len=64, ring_slots=16, max_prefill_tokens=256)
+    reqs = _fixed_prompts(cfg, [16, 16, 16, 16, 16], 12, 27)
+    from oracle.scheduler import Scheduler
+    from oracle.serve import run_schedule
+    plans = []
+    run_schedule(Scheduler.from_engine(eng), reqs, lambda pl: [1] * len(pl.sample_seq), on_plan=plans.append)
+    assert max(len(pl.preempted) for pl in plans) >= 2 and max(len(pl.resumed) for pl in plans) >= 2
+    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2)
+    print("several victims: worst relative logit error", worst, "iterations", len(plans))
