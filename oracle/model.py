@@ -7,6 +7,14 @@ projection + residual -> RMSNorm -> SiLU-gated FFN + residual; final RMSNorm and
 LM head. No biases. All arithmetic is fp64 on the stored weight values, with no rounding of
 activations or cached K/V.
 
+Mixture-of-experts variant (n_experts > 0; the second workload of the paper's evaluation, section 6, is such a model
+and the paper fixes nothing about it either): the FFN of every layer is replaced by n_experts SiLU-gated FFNs of width
+d_ffn and a router matrix [n_experts][d]. Per token: router logits r = h Wr^T; the n_active largest are selected (ties to
+the lower expert id); their weights are the softmax over the selected logits (softmax over all experts, then
+renormalised over the selected ones, is the same thing); the layer adds sum_j w_j FFN_{e_j}(h). The selection is an
+integer decision taken from floating-point values: a caller may force it (`routing`) and receives the oracle's own choice
+and its margin (`route_log`), so that a test can require agreement wherever the margin exceeds the tolerance.
+
 Three variants compute the same function:
   forward_dense: the definition. All positions at once, dense causal attention, no cache.
   CachedModel:   contiguous per-sequence KV cache, prefill then one token at a time.
@@ -80,10 +88,42 @@ def _attend(cfg, q, K, V):
     return out
 
 
-def _post_attention(cfg, W, l, x, attn):
+def route(cfg, r):
+    """r: router logits [E] of one token. Returns (selected expert ids in order of decreasing logit, ties to the lower
+    id; margin between the last selected and the first rejected logit, inf when all experts are selected)."""
+    E, k = cfg["n_experts"], cfg["n_active"]
+    order = np.lexsort((np.arange(E), -r))
+    margin = float(r[order[k - 1]] - r[order[k]]) if k < E else np.inf
+    return order[:k], margin
+
+
+def moe_ffn(cfg, W, l, h, routing=None, route_log=None):
+    """h: normalised input [T][d]. routing: optional [T][n_active] expert ids to use instead of the own selection."""
+    T = h.shape[0]
+    r = h @ W[f"l{l}.wr"].T
+    out = np.zeros_like(h)
+    own, margins = [], []
+    for t in range(T):
+        sel, margin = route(cfg, r[t])
+        own.append(sel)
+        margins.append(margin)
+        if routing is not None:
+            sel = np.asarray(routing[t], dtype=np.int64)
+        w = np.exp(r[t, sel] - r[t, sel].max())
+        w /= w.sum()
+        for wj, e in zip(w, sel):
+            out[t] += wj * ((silu(W[f"l{l}.wg"][e] @ h[t]) * (W[f"l{l}.wu"][e] @ h[t])) @ W[f"l{l}.wd"][e].T)
+    if route_log is not None:
+        route_log.append(dict(layer=l, own=np.array(own), margin=np.array(margins), scale=np.abs(r).max(axis=1)))
+    return out
+
+
+def _post_attention(cfg, W, l, x, attn, routing=None, route_log=None):
     T = x.shape[0]
     x = x + attn.reshape(T, -1) @ W[f"l{l}.wo"].T
     h = rmsnorm(x, W[f"l{l}.g2"], cfg["rms_eps"])
+    if cfg.get("n_experts", 0):
+        return x + moe_ffn(cfg, W, l, h, None if routing is None else routing[l], route_log)
     return x + (silu(h @ W[f"l{l}.wg"].T) * (h @ W[f"l{l}.wu"].T)) @ W[f"l{l}.wd"].T
 
 
@@ -153,13 +193,15 @@ class PagedKV:
         self.bs = bs
 
 
-def paged_forward(cfg, W, kv, input_ids, positions, slot_mapping, tok_seq, block_tables, last_idx):
+def paged_forward(cfg, W, kv, input_ids, positions, slot_mapping, tok_seq, block_tables, last_idx, routing=None, route_log=None):
     """One iteration over T tokens of several sequences.
 
     input_ids, positions, slot_mapping, tok_seq: length T (tok_seq = index of the token's
     sequence within this iteration). block_tables[s]: block ids of sequence s. last_idx[s]:
     index in 0..T of the last token of sequence s. Token t at position p writes its K/V to
     slot_mapping[t] and attends to the cached positions 0..p of its sequence.
+    routing (mixture-of-experts models): optional [layer][T][n_active] expert ids to use; route_log: optional list
+    that receives one record per layer with the oracle's own selection and its margins.
     Returns logits [n_seq][V] of the last token of every sequence.
     """
     input_ids = np.asarray(input_ids)
@@ -176,7 +218,7 @@ def paged_forward(cfg, W, kv, input_ids, positions, slot_mapping, tok_seq, block
             p = np.arange(positions[t] + 1)
             slots = bt[p // bs] * bs + p % bs
             attn[t] = _attend(cfg, q[t], kv.K[l][slots], kv.V[l][slots])
-        x = _post_attention(cfg, W, l, x, attn)
+        x = _post_attention(cfg, W, l, x, attn, routing, route_log)
     return _head(cfg, W, x[np.asarray(last_idx, dtype=np.int64)])
 
 

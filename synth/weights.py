@@ -3,7 +3,8 @@
 Every matrix is stored row-major as [out_features][in_features]. Order of tensors in the
 blob (see tensor_order): embed [V][d]; per layer g1 [d], wq [nq*hd][d], wk [nkv*hd][d],
 wv [nkv*hd][d], wo [d][nq*hd], g2 [d], wg [F][d], wu [F][d], wd [d][F]; then gf [d],
-lm [V][d]. Norm gains (g1, g2, gf) are always fp32. Matrices are fp32 (dtype 0) or bf16
+lm [V][d]. A mixture-of-experts model (n_experts = E > 0, d_ffn = width of one expert) has per layer, in place of
+wg, wu, wd: the router wr [E][d], then wg [E][F][d], wu [E][F][d], wd [E][d][F]. Norm gains (g1, g2, gf) are always fp32. Matrices are fp32 (dtype 0) or bf16
 bit patterns (dtype 1, uint16, produced by round-to-nearest-even of the fp32 draw): those
 bits are the weights for every consumer.
 """
@@ -26,11 +27,15 @@ def tensor_order(cfg):
     """[(name, shape, is_gain)] in blob order."""
     d, hd = cfg["d_model"], cfg["head_dim"]
     nq, nkv, F, V = cfg["n_q_heads"], cfg["n_kv_heads"], cfg["d_ffn"], cfg["vocab"]
+    E = cfg.get("n_experts", 0)
     out = [("embed", (V, d), False)]
     for l in range(cfg["n_layers"]):
         out += [(f"l{l}.g1", (d,), True), (f"l{l}.wq", (nq * hd, d), False), (f"l{l}.wk", (nkv * hd, d), False),
-                (f"l{l}.wv", (nkv * hd, d), False), (f"l{l}.wo", (d, nq * hd), False), (f"l{l}.g2", (d,), True),
-                (f"l{l}.wg", (F, d), False), (f"l{l}.wu", (F, d), False), (f"l{l}.wd", (d, F), False)]
+                (f"l{l}.wv", (nkv * hd, d), False), (f"l{l}.wo", (d, nq * hd), False), (f"l{l}.g2", (d,), True)]
+        if E:   # mixture of experts: router, then the experts' matrices stacked
+            out += [(f"l{l}.wr", (E, d), False), (f"l{l}.wg", (E, F, d), False), (f"l{l}.wu", (E, F, d), False), (f"l{l}.wd", (E, d, F), False)]
+        else:
+            out += [(f"l{l}.wg", (F, d), False), (f"l{l}.wu", (F, d), False), (f"l{l}.wd", (d, F), False)]
     out += [("gf", (d,), True), ("lm", (V, d), False)]
     return out
 

@@ -177,3 +177,81 @@ def test_bruteforce_generation_equals_cached_generation():
     a = SV.generate_reference(CFG, W, req)
     b = M.generate_bruteforce(CFG, W, req["prompt"], 6, lambda lg, i: int(np.argmax(lg)))
     assert a == b
+
+
+# ---- mixture of experts ------------------------------------------------------------------------------------------------
+
+def _moe_cfg(E=6, k=2):
+    return dict(synth.model_config("tiny"), n_layers=2, vocab=61, d_model=32, n_q_heads=4, n_kv_heads=2, head_dim=8, d_ffn=24,
+                n_experts=E, n_active=k)
+
+
+def test_moe_with_one_expert_is_the_dense_model():
+    """One expert, one active: the router's weight is softmax over a single logit = 1, so the layer is the plain FFN with
+    that expert's matrices (the dense model is pinned above)."""
+    cfg = _moe_cfg(1, 1)
+    raw = synth.make_weights(cfg, 3, gain_jitter=0.1)
+    dense_cfg = dict(cfg, n_experts=0, n_active=0)
+    dense_raw = {k: (v[0] if k.endswith((".wg", ".wu", ".wd")) else v) for k, v in raw.items() if not k.endswith(".wr")}
+    toks = np.arange(11) % 61
+    a = M.forward_dense(cfg, M.Weights(cfg, raw), toks)
+    b = M.forward_dense(dense_cfg, M.Weights(dense_cfg, dense_raw), toks)
+    assert np.abs(a - b).max() < 1e-12
+
+
+def test_moe_all_experts_active_with_a_zero_router_is_the_mean_of_the_experts():
+    cfg = _moe_cfg(4, 4)
+    raw = synth.make_weights(cfg, 4)
+    for l in range(2):
+        raw[f"l{l}.wr"] = np.zeros_like(raw[f"l{l}.wr"])
+    W = M.Weights(cfg, raw)
+    h = np.random.default_rng(0).normal(size=(5, 32))
+    got = M.moe_ffn(cfg, W, 0, h)
+    want = np.mean([(M.silu(h @ W["l0.wg"][e].T) * (h @ W["l0.wu"][e].T)) @ W["l0.wd"][e].T for e in range(4)], axis=0)
+    assert np.abs(got - want).max() < 1e-12
+
+
+def test_moe_routing_by_hand_ties_and_forced_selection():
+    """Router logits written by hand: the two largest win, a tie goes to the lower expert id, the weights are the softmax
+    over the two selected logits (1 : e^-1 here); forcing another selection changes the output accordingly; relabelling
+    the experts does not change the layer."""
+    cfg = _moe_cfg(5, 2)
+    sel, margin = M.route(cfg, np.array([0.5, 2.0, 1.0, 2.0, 1.0]))
+    assert list(sel) == [1, 3] and margin == 1.0
+    sel, margin = M.route(cfg, np.array([1.0, 0.0, 1.0, 1.0, -1.0]))
+    assert list(sel) == [0, 2] and margin == 0.0
+    raw = synth.make_weights(cfg, 5)
+    W = M.Weights(cfg, raw)
+    rng = np.random.default_rng(1)
+    h = rng.normal(size=(1, 32))
+    wr = np.zeros((5, 32))
+    wr[1] = 2.0 * h[0] / (h[0] @ h[0])          # logit 2 for expert 1
+    wr[4] = 1.0 * h[0] / (h[0] @ h[0])          # logit 1 for expert 4, 0 for the rest
+    W._cache["l0.wr"] = wr
+    f = lambda e: (M.silu(W["l0.wg"][e] @ h[0]) * (W["l0.wu"][e] @ h[0])) @ W["l0.wd"][e].T
+    w1, w4 = 1.0 / (1.0 + np.exp(-1.0)), np.exp(-1.0) / (1.0 + np.exp(-1.0))
+    log = []
+    assert np.abs(M.moe_ffn(cfg, W, 0, h, route_log=log)[0] - (w1 * f(1) + w4 * f(4))).max() < 1e-12
+    assert list(log[0]["own"][0]) == [1, 4] and abs(log[0]["margin"][0] - 1.0) < 1e-12
+    forced = M.moe_ffn(cfg, W, 0, h, routing=[[1, 0]])[0]       # expert 0 has logit 0: weights 1 : e^-2
+    assert np.abs(forced - (f(1) + np.exp(-2.0) * f(0)) / (1.0 + np.exp(-2.0))).max() < 1e-12
+    perm = np.array([3, 0, 4, 1, 2])
+    for n in ("wg", "wu", "wd"):
+        W._cache[f"l1.{n}"] = W[f"l0.{n}"][perm]
+    W._cache["l1.wr"] = wr[perm]
+    assert np.abs(M.moe_ffn(cfg, W, 1, h) - M.moe_ffn(cfg, W, 0, h)).max() < 1e-12
+
+
+def test_moe_dense_equals_cached_equals_paged():
+    cfg = _moe_cfg()
+    raw = synth.make_weights(cfg, 6, gain_jitter=0.1)
+    W = M.Weights(cfg, raw)
+    toks = np.random.default_rng(2).integers(0, 61, 23)
+    dense = M.forward_dense(cfg, W, toks)
+    m = M.CachedModel(cfg, W)
+    got = [m.step(toks[:9])] + [m.step([t]) for t in toks[9:]]
+    assert np.abs(np.array(got) - dense[8:]).max() < 1e-12
+    kv = M.PagedKV(cfg, 4, 8)
+    bt = [[2, 0, 3]]
+    lg = M.paged_forward(cfg, W, kv, list(toks), list(range(23)), [bt[0][p // 8] * 8 + p % 8 for p in range(23)], [0] * 23, bt, [22])
+    assert np.abs(lg[0] - dense[22]).max() < 1e-12
