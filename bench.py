@@ -30,14 +30,24 @@ if ROOT not in sys.path:
 import synth  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0
-PHASE_NAMES = {2: "k_qkv", 5: "k_oproj", 7: "k_gateup", 8: "k_down", 10: "k_lm_head", 4: "k_attention"}
+PHASE_NAMES = {2: "k_qkv", 5: "k_oproj", 7: "k_gateup", 8: "k_down", 10: "k_lm_head", 4: "k_attention",
+               16: "k_moe_router", 17: "k_moe_route", 18: "k_moe_gateup", 19: "k_moe_down", 20: "k_moe_combine"}
 
 WORKLOADS = {
     "tiny": dict(model="tiny", workload="tiny", wseed=1000, rseed=2000, steps=30, warmup=3),
     "churn": dict(model="churn", workload="churn", wseed=1001, rseed=2001, steps=600, warmup=20),
     "llama3_8b": dict(model="llama3_8b", workload="llama3_8b", wseed=1002, rseed=2002, steps=200, warmup=60),
     "sched_stress": dict(model="sched_stress", workload="sched_stress", wseed=1003, rseed=2003, steps=100, warmup=5),
+    # the mixture-of-experts model of the paper's evaluation (section 6) under the same request mix as the dense model
+    "moe_30b_a3b": dict(model="moe_30b_a3b", workload="llama3_8b", wseed=1004, rseed=2002, steps=100, warmup=20),
 }
+
+
+def experts_hit(cfg, n_tokens):
+    """Expected number of distinct experts that n_tokens tokens select under uniform routing (the synthetic router's):
+    the experts whose matrices a grouped GEMM has to read."""
+    E, k = cfg["n_experts"], cfg["n_active"]
+    return E * (1.0 - (1.0 - k / E) ** n_tokens)
 
 
 def phase_bytes(cfg, phase, n_tokens, n_seqs, ctx_tokens=0):
@@ -49,6 +59,12 @@ def phase_bytes(cfg, phase, n_tokens, n_seqs, ctx_tokens=0):
     qkv_n = (cfg["n_q_heads"] + 2 * cfg["n_kv_heads"]) * cfg["head_dim"]
     no = cfg["n_q_heads"] * cfg["head_dim"]
     T, B = n_tokens, n_seqs
+    if phase == 16:     # router: its matrix, the normalised x in, fp32 logits out
+        return es * cfg["n_experts"] * d + T * (ea * d + 4 * cfg["n_experts"])
+    if phase == 18:     # grouped gate/up: the matrices of the experts hit, x gathered per (token, expert) pair, the pairs' hidden rows out
+        return es * 2 * F * d * experts_hit(cfg, T) + T * cfg["n_active"] * (ea * d + 2 * F)
+    if phase == 19:     # grouped down: the matrices of the experts hit, the pairs' hidden rows in, fp32 outputs of the pairs out
+        return es * d * F * experts_hit(cfg, T) + T * cfg["n_active"] * (2 * F + 4 * d)
     if phase == 2:      # in: normalised x; out: q, k, v
         return es * qkv_n * d + T * (ea * d + ea * qkv_n)
     if phase == 5:      # in: attention output; residual read + write; bf16 path also writes the next packed operand
@@ -72,7 +88,11 @@ def decode_step_bytes(cfg, n_seqs, ctx_tokens):
     d, F, V, L = cfg["d_model"], cfg["d_ffn"], cfg["vocab"], cfg["n_layers"]
     qkv_n = (cfg["n_q_heads"] + 2 * cfg["n_kv_heads"]) * cfg["head_dim"]
     no = cfg["n_q_heads"] * cfg["head_dim"]
-    w = es * (L * (qkv_n * d + d * no + 2 * F * d + d * F) + V * d)
+    if cfg.get("n_experts", 0):   # the router and the matrices of the experts this batch selects (expected count, uniform routing)
+        ffn = cfg["n_experts"] * d + 3 * F * d * experts_hit(cfg, n_seqs)
+    else:
+        ffn = 3 * F * d
+    w = es * (L * (qkv_n * d + d * no + ffn) + V * d)
     kv_tok = 2 * cfg["n_kv_heads"] * cfg["head_dim"] * es * L
     return w + kv_tok * (ctx_tokens + n_seqs) + 2 * 4 * n_seqs * V
 
@@ -371,6 +391,8 @@ def main():
     ap.add_argument("--tune", type=lambda x: int(x, 0), default=0, help="blink_config.tune")
     ap.add_argument("--preemption", action="store_true", help="on-demand KV growth with preemption instead of worst-case reservations "
                     "(BLINK_FLAG_PREEMPTION; the chunked-prefill leg is skipped)")
+    ap.add_argument("--layers", type=int, default=0, help="tuning: build the model with this many layers instead of its own "
+                    "(reported in config; not the workload's model any more)")
     ap.add_argument("--requests", type=int, default=0)
     ap.add_argument("--max-batch", type=int, default=0, help="override the engine's batch slots")
     ap.add_argument("--kv-blocks", type=int, default=0, help="override the size of the KV pool (16-token blocks)")
@@ -395,15 +417,19 @@ def main():
         sys.exit(2)
     if args.interference is None:
         args.interference = args.workload == "llama3_8b"
+    if args.workload == "moe_30b_a3b":
+        args.no_chunked_leg = True
     stressor = Stressor() if (args.interference and args.open_loop_seconds > 0) else None   # before the GPU is touched
     import paper_2604_07609_amd as B
 
     if args.phase < 0:
-        args.phase = 4 if args.workload == "llama3_8b" and not args.max_batch else 7
+        args.phase = 18 if args.workload == "moe_30b_a3b" else 4 if args.workload == "llama3_8b" and not args.max_batch else 7
     wl = WORKLOADS[args.workload]
     K = args.steps or wl["steps"]
     W = args.warmup if args.warmup >= 0 else wl["warmup"]
     cfg, eng = synth.model_config(wl["model"]), synth.engine_config(wl["model"])
+    if args.layers:
+        cfg["n_layers"] = args.layers
     t_gen = time.perf_counter()
     raw = synth.make_weights(cfg, wl["wseed"], threads=min(16, os.cpu_count() or 8))
     reqs = synth.make_workload(wl["workload"], cfg["vocab"], wl["rseed"], n_requests=args.requests or None)
@@ -558,7 +584,10 @@ def main():
                            "launches bracketed by HIP events on the compute stream" % len(pm))
     if p_cls and args.phase != 4:
         es = 2 if cfg["dtype"] == 1 else 4
-        wbytes = phase_bytes(cfg, args.phase, 0, 0)
+        if args.phase in (18, 19):    # grouped GEMMs: every (token, expert) pair meets one expert's matrices
+            wbytes = es * (2 if args.phase == 18 else 1) * cfg["d_ffn"] * cfg["d_model"] * cfg["n_active"]
+        else:
+            wbytes = phase_bytes(cfg, args.phase, 0, 0)
         cols = "n_seqs" if args.phase == 10 else "n_tokens"     # the LM head runs on the last token of every sequence
         flops = float(sum(2.0 * (wbytes / es) * int(t[cols]) for t in trp[~decp])) * per_layer
         p_cls["TFLOPs"] = round(flops / (float(pm[~decp].sum()) * 1e-3) / 1e12, 1)
@@ -583,7 +612,8 @@ def main():
         idx = np.nonzero(pre[:-1])[0]
         d, F, V, L = cfg["d_model"], cfg["d_ffn"], cfg["vocab"], cfg["n_layers"]
         qkv_n = (cfg["n_q_heads"] + 2 * cfg["n_kv_heads"]) * cfg["head_dim"]
-        layer_params = qkv_n * d + d * cfg["n_q_heads"] * cfg["head_dim"] + 3 * F * d
+        ffn_active = cfg["n_experts"] * d + cfg["n_active"] * 3 * F * d if cfg.get("n_experts", 0) else 3 * F * d
+        layer_params = qkv_n * d + d * cfg["n_q_heads"] * cfg["head_dim"] + ffn_active
         fl = float(sum(2.0 * (L * layer_params * int(tr["n_tokens"][i]) + V * d * int(tr["n_seqs"][i])) for i in idx))
         secs = float(step_ns[idx].sum()) * 1e-9
         peak = 2500.0 if cfg["dtype"] == 1 else 157.3
@@ -596,7 +626,7 @@ def main():
         "value": round(toks / dt, 2), "unit": "output tokens/s", "n_gpus": 1, "steps": iters, "warmup": W,
         "ms_per_step": round(1e3 * dt / max(1, iters), 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg["dtype"] == 1 else "f32", "data": "synthetic",
-        "config": {"workload": args.workload, "requests_resident": len(reqs), "arrivals": "all resident at t=0 (saturation)",
+        "config": {"workload": args.workload, "layers": cfg["n_layers"], "requests_resident": len(reqs), "arrivals": "all resident at t=0 (saturation)",
                    "max_batch": eng["max_batch"], "kv_blocks": eng["kv_num_blocks"],
                    "fill_iterations_before_warmup": fill, "preemption": bool(eng.get("preemption", False)),
                    "arithmetic": ("bf16 weights and KV cache; projections on the half-precision matrix-core path (weights re-encoded "
@@ -642,8 +672,18 @@ def main():
         out["open_loop_sweep"] = sweep
     del blob
     if not args.no_cpu_baseline:
-        budget = args.cpu_sample_tokens or {"tiny": 32, "churn": 16, "llama3_8b": 4, "sched_stress": 16}[args.workload]
-        if args.workload == "llama3_8b":
+        budget = args.cpu_sample_tokens or {"tiny": 32, "churn": 16, "llama3_8b": 4, "sched_stress": 16, "moe_30b_a3b": 4}[args.workload]
+        if args.workload == "moe_30b_a3b":
+            # the oracle widens every tensor it touches to fp64 and keeps it: all layers' experts would take 8 bytes x 29 G
+            # parameters of host memory. It runs the model cut to its first layers (same embedding and LM head), and the
+            # rate is scaled by the layer ratio (the layers dominate its time)
+            keep = min(4, cfg["n_layers"])
+            cut = dict(cfg, n_layers=keep)
+            cb = cpu_baseline(cut, eng, raw, reqs, budget, n_req=2, prompt_cap=32)
+            cb["value"] *= keep / cfg["n_layers"]
+            cb["sample"] += "; model cut to its first %d of %d layers, rate scaled by %d/%d" % (keep, cfg["n_layers"], keep, cfg["n_layers"])
+            out["cpu_baseline"] = cb
+        elif args.workload == "llama3_8b":
             out["cpu_baseline"] = cpu_baseline(cfg, eng, raw, reqs, budget, n_req=2, prompt_cap=32)
         else:
             out["cpu_baseline"] = cpu_baseline(cfg, eng, raw, reqs, budget)

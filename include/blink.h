@@ -102,6 +102,12 @@ typedef struct {
   uint32_t pump_depth;         /* iterations the launcher thread keeps enqueued ahead of the device (0: 8; at most 1024) */
   uint32_t tune;               /* tests and tuning: forces variants of the GEMM and attention kernels (0: automatic
                                   choice; the bits are listed in csrc/mfma_gemm.h) */
+  /* mixture-of-experts FFN (the second model of the paper's evaluation, section 6, is of this kind); bf16 models only */
+  uint32_t n_experts;          /* 0: dense FFN. E > 0 (at most 256): every layer has a router wr[E][d] and E experts of
+                                  width d_ffn; the blob then holds, in place of wg wu wd: wr[E][d] wg[E][F][d] wu[E][F][d]
+                                  wd[E][d][F] */
+  uint32_t n_active;           /* experts per token (1 .. min(8, n_experts)): the n_active largest router logits, ties to
+                                  the lower expert id; their outputs are weighted by the softmax over those logits */
 } blink_config;
 
 typedef struct {
@@ -170,7 +176,9 @@ enum {
   BLINK_DBG_SEQ_LENS = 8,      /* uint32[n_seqs] */
   BLINK_DBG_CU_SEQLENS = 9,    /* uint32[n_seqs + 1] */
   BLINK_DBG_SLOT_STATES = 10,  /* uint32[ring_slots] */
-  BLINK_DBG_HIDDEN = 11        /* float[n_tokens][d_model]: residual stream after the last layer */
+  BLINK_DBG_HIDDEN = 11,       /* float[n_tokens][d_model]: residual stream after the last layer */
+  BLINK_DBG_ROUTING = 12       /* mixture of experts: uint32[n_layers][n_tokens][n_active], the experts every token of the
+                                  last iteration was routed to, in selection order */
 };
 
 /* Provisioning (section 4.1): allocates all device memory, uploads and re-tiles the weights, builds the
@@ -219,7 +227,9 @@ int blink_debug_read(blink_engine* e, uint32_t what, void* buf, uint64_t cap_byt
 /* Kernel timing for the roofline report. blink_time_phase selects one phase of the forward pass (0 embedding;
  * per layer: 1 norm, 2 QKV GEMM, 3 rotary + KV write, 4 attention, 5 output GEMM, 6 norm, 7 gate/up GEMM,
  * 8 down GEMM; 9 final norm, 10 LM head, 11 sample + publish; bf16 models also 12 merge of the decode attention's
- * chunks, 13 / 14 / 15 second kernel of the QKV / output / down GEMM when K is split across workgroups; -1 none). A
+ * chunks, 13 / 14 / 15 second kernel of the QKV / output / down GEMM when K is split across workgroups; a
+ * mixture-of-experts model runs, in place of 7 and 8: 16 router GEMM, 17 expert selection, 18 grouped gate/up GEMMs,
+ * 19 grouped down GEMMs, 20 weighted sum + residual; -1 none). A
  * bf16 model has no kernels for phases 1, 3, 6 and 9 (fused into the GEMMs). While a phase is selected, the loop
  * brackets every launch of that phase's kernel with HIP events on the compute stream. After the loop has
  * stopped, blink_get_phase_times returns, per iteration enqueued in the last window and in enqueue order, the

@@ -114,7 +114,10 @@ def moe_ffn(cfg, W, l, h, routing=None, route_log=None):
         for wj, e in zip(w, sel):
             out[t] += wj * ((silu(W[f"l{l}.wg"][e] @ h[t]) * (W[f"l{l}.wu"][e] @ h[t])) @ W[f"l{l}.wd"][e].T)
     if route_log is not None:
-        route_log.append(dict(layer=l, own=np.array(own), margin=np.array(margins), scale=np.abs(r).max(axis=1)))
+        own = np.array(own)
+        picked = np.take_along_axis(r, own, axis=1)     # the selected logits, in selection order
+        gaps = (picked[:, :-1] - picked[:, 1:]).min(axis=1) if own.shape[1] > 1 else np.full(T, np.inf)
+        route_log.append(dict(layer=l, own=own, margin=np.array(margins), gaps=gaps, scale=np.abs(r).max(axis=1)))
     return out
 
 

@@ -17,7 +17,7 @@ EXPORTS = ["blink_init", "blink_submit", "blink_run", "blink_set_exit_when_idle"
 
 class DBG:
     LOGITS, FREE_STACK, INPUT_IDS, POSITIONS, SLOT_MAPPING, SEQ_BATCH_SLOT, BLOCK_TABLES, SEQ_LENS, CU_SEQLENS, \
-        SLOT_STATES, HIDDEN = range(1, 12)
+        SLOT_STATES, HIDDEN, ROUTING = range(1, 13)
 
 
 class Config(C.Structure):
@@ -26,7 +26,7 @@ class Config(C.Structure):
         ("kv_block_size", C.c_uint32), ("kv_num_blocks", C.c_uint32), ("max_batch", C.c_uint32), ("max_seq_len", C.c_uint32),
         ("max_prefill_tokens", C.c_uint32), ("ring_slots", C.c_uint32), ("eos_token_id", C.c_int32), ("device", C.c_int32),
         ("flags", C.c_uint32), ("trace_capacity", C.c_uint32), ("idle_poll_us", C.c_uint32), ("pump_depth", C.c_uint32),
-        ("tune", C.c_uint32)]
+        ("tune", C.c_uint32), ("n_experts", C.c_uint32), ("n_active", C.c_uint32)]
 
 
 class Sampling(C.Structure):
@@ -146,6 +146,7 @@ class Engine:
             flags |= FLAG_PREEMPTION
         cfg.device, cfg.flags, cfg.trace_capacity, cfg.idle_poll_us = device, flags, trace_capacity, idle_poll_us
         cfg.pump_depth, cfg.tune = pump_depth, tune
+        cfg.n_experts, cfg.n_active = model.get("n_experts", 0), model.get("n_active", 0)
         self.h = C.c_void_p()
         _check(self.lib, self.lib.blink_init(C.byref(cfg), C.byref(self.h)))
 
@@ -203,6 +204,7 @@ class Engine:
             m, e = self.model, self.engine
             max_t = max(e["max_prefill_tokens"], e["max_seq_len"], e["max_batch"])
             max_bytes = 8 + 4 * max(e["max_batch"] * m["vocab"], e["kv_num_blocks"] + 1, max_t * m["d_model"],
+                                    m["n_layers"] * max_t * m.get("n_active", 0),
                                     e["max_batch"] * ((e["max_seq_len"] + 15) // 16), e["ring_slots"])
         buf = np.zeros(max_bytes, dtype=np.uint8)
         n = C.c_uint64()

@@ -53,6 +53,11 @@ PHASE_KERNEL(k_attention_combine, PH_ATTN_COMBINE)
 PHASE_KERNEL(k_qkv_reduce, PH_QKV_RED)
 PHASE_KERNEL(k_oproj_reduce, PH_OPROJ_RED)
 PHASE_KERNEL(k_down_reduce, PH_DOWN_RED)
+PHASE_KERNEL(k_moe_router, PH_ROUTER)
+PHASE_KERNEL(k_moe_route, PH_ROUTE)
+PHASE_KERNEL(k_moe_gateup, PH_MOE_GATEUP)
+PHASE_KERNEL(k_moe_down, PH_MOE_DOWN)
+PHASE_KERNEL(k_moe_combine, PH_MOE_COMBINE)
 
 typedef void (*phase_kernel_t)(DevCtx, u32);
 static phase_kernel_t phase_kernel(int ph) {
@@ -72,6 +77,11 @@ static phase_kernel_t phase_kernel(int ph) {
     case PH_QKV_RED: return k_qkv_reduce;
     case PH_OPROJ_RED: return k_oproj_reduce;
     case PH_DOWN_RED: return k_down_reduce;
+    case PH_ROUTER: return k_moe_router;
+    case PH_ROUTE: return k_moe_route;
+    case PH_MOE_GATEUP: return k_moe_gateup;
+    case PH_MOE_DOWN: return k_moe_down;
+    case PH_MOE_COMBINE: return k_moe_combine;
     default: return k_sample_publish;
   }
 }
@@ -212,7 +222,9 @@ static int halloc(blink_engine* e, T** p, u64 count) {
 static u64 expected_weight_bytes(const blink_config* c) {
   const u64 es = c->dtype == 1 ? 2 : 4;
   const u64 d = c->d_model, hd = c->head_dim, nq = c->n_q_heads, nkv = c->n_kv_heads, F = c->d_ffn, V = c->vocab;
-  const u64 per_layer = 4 * d + 4 * d + es * ((nq + 2 * nkv) * hd * d + d * nq * hd + 2 * F * d + d * F);
+  const u64 E = c->n_experts;
+  const u64 ffn = E ? E * d + E * 3 * F * d : 3 * F * d;   // router and E experts, or the one dense FFN
+  const u64 per_layer = 4 * d + 4 * d + es * ((nq + 2 * nkv) * hd * d + d * nq * hd + ffn);
   return es * V * d * 2 + c->n_layers * per_layer + 4 * d;
 }
 
@@ -249,6 +261,7 @@ static int init_impl(const blink_config* cfg, blink_engine* e) {
   c.maxT = std::max(std::max(cfg->max_prefill_tokens, cfg->max_seq_len), cfg->max_batch);
   c.eos = cfg->eos_token_id; c.flags = cfg->flags; c.trace_cap = cfg->trace_capacity ? cfg->trace_capacity : 65536u;
   c.qkv_n = (c.nq + 2 * c.nkv) * c.hd;
+  c.n_experts = cfg->n_experts; c.n_active = cfg->n_experts ? cfg->n_active : 0;
   const u64 es = c.dtype == 1 ? 2 : 4;
 
   // ---- ring ----
@@ -330,20 +343,44 @@ static int init_impl(const blink_config* cfg, blink_engine* e) {
       c.lm = wdev + off; off += es * V * d;
     } else {
       std::vector<LayerWP> lp(c.n_layers);
-      const u64 stage_bytes = 2 * std::max(std::max(V * d, 2 * F * d), std::max((nq + 2 * nkv) * hd * d, d * nq * hd));
+      const u64 stage_bytes = 2 * std::max(std::max(std::max(V * d, 2 * F * d), (u64)c.n_experts * d), std::max((nq + 2 * nkv) * hd * d, d * nq * hd));
       char *stage = nullptr, *embed = nullptr;
       float* gains = nullptr;
       HIPCHK(hipMalloc((void**)&stage, stage_bytes));     // freed at the end of this block, on every path
+      // src_off2 != 0: the second half of the rows is stored there (an expert's up matrix lies apart from its gate matrix)
+      auto pack_to = [&](f16_t* p, u64 src_off, u64 src_off2, u32 N, u32 K, u32 pair_rows, u32 perm_hd) -> int {
+        if (src_off2) {
+          HIPCHK(hipMemcpy(stage, hsrc + src_off, (u64)N * K, hipMemcpyHostToDevice));
+          HIPCHK(hipMemcpy(stage + (u64)N * K, hsrc + src_off2, (u64)N * K, hipMemcpyHostToDevice));
+        } else {
+          HIPCHK(hipMemcpy(stage, hsrc + src_off, (u64)N * K * 2, hipMemcpyHostToDevice));
+        }
+        hipLaunchKernelGGL(k_pack_weights, dim3(2048), dim3(BLK_THREADS), 0, e->compute, (const bf16_t*)stage, p, N, K, pair_rows, perm_hd);
+        HIPCHK(hipGetLastError());
+        HIPCHK(hipStreamSynchronize(e->compute));          // the staging buffer is reused by the next matrix
+        return 0;
+      };
       auto pack = [&](u64 src_off, u32 N, u32 K, u32 pair_rows, u32 perm_hd, const f16_t** dst) -> int {
         f16_t* p;
         const u64 elems = (u64)((N + 15) / 16) * 16 * K;
         if (int rc = dalloc(e, &p, elems, false)) return rc;
-        HIPCHK(hipMemcpy(stage, hsrc + src_off, (u64)N * K * 2, hipMemcpyHostToDevice));
-        hipLaunchKernelGGL(k_pack_weights, dim3(2048), dim3(BLK_THREADS), 0, e->compute, (const bf16_t*)stage, p, N, K, pair_rows, perm_hd);
-        HIPCHK(hipGetLastError());
-        HIPCHK(hipStreamSynchronize(e->compute));          // the staging buffer is reused by the next matrix
+        if (int rc = pack_to(p, src_off, 0, N, K, pair_rows, perm_hd)) return rc;
         *dst = p;
         e->weight_bytes += elems * 2;
+        return 0;
+      };
+      // the experts of one layer: packed one after the other (2F x d gate/up pairs, then d x F down matrices)
+      auto pack_experts = [&](u64 off_g, u64 off_u, u64 off_d, LayerWP& lp_l) -> int {
+        const u64 E = c.n_experts;
+        f16_t *pgu, *pd;
+        if (int rc = dalloc(e, &pgu, E * 2 * F * d, false)) return rc;
+        if (int rc = dalloc(e, &pd, E * d * F, false)) return rc;
+        for (u64 x = 0; x < E; ++x) {
+          if (int rc = pack_to(pgu + x * 2 * F * d, off_g + x * 2 * F * d, off_u + x * 2 * F * d, 2 * c.F, c.d, c.F, 0)) return rc;
+          if (int rc = pack_to(pd + x * d * F, off_d + x * 2 * d * F, 0, c.d, c.F, 0, 0)) return rc;
+        }
+        lp_l.wgu = pgu; lp_l.wd = pd;
+        e->weight_bytes += E * 3 * F * d * 2;
         return 0;
       };
       auto all = [&]() -> int {
@@ -361,10 +398,18 @@ static int init_impl(const blink_config* cfg, blink_engine* e) {
           if (int rc = pack(off, c.d, c.nq * c.hd, 0, 0, &lp[l].wo)) return rc;
           off += 2 * d * nq * hd;
           HIPCHK(hipMemcpy(g2, hsrc + off, 4 * d, hipMemcpyHostToDevice)); off += 4 * d;
-          if (int rc = pack(off, 2 * c.F, c.d, c.F, 0, &lp[l].wgu)) return rc;
-          off += 2 * 2 * F * d;
-          if (int rc = pack(off, c.d, c.F, 0, 0, &lp[l].wd)) return rc;
-          off += 2 * d * F;
+          if (c.n_experts) {
+            const u64 E = c.n_experts;
+            if (int rc = pack(off, c.n_experts, c.d, 0, 0, &lp[l].wr)) return rc;
+            off += 2 * E * d;
+            if (int rc = pack_experts(off, off + 2 * E * F * d, off + 4 * E * F * d, lp[l])) return rc;
+            off += 2 * 3 * E * F * d;
+          } else {
+            if (int rc = pack(off, 2 * c.F, c.d, c.F, 0, &lp[l].wgu)) return rc;
+            off += 2 * 2 * F * d;
+            if (int rc = pack(off, c.d, c.F, 0, 0, &lp[l].wd)) return rc;
+            off += 2 * d * F;
+          }
           lw[l].g1 = g1; lw[l].g2 = g2; lw[l].wqkv = lw[l].wo = lw[l].wgu = lw[l].wd = nullptr;
         }
         float* gf = gains + 2 * (u64)c.n_layers * d;
@@ -405,7 +450,20 @@ static int init_impl(const blink_config* cfg, blink_engine* e) {
     const u64 tile_tokens = (u64)c.TBS * 16;
     if (int rc = dalloc(e, &c.xq, tile_tokens * c.d)) return rc;
     if (int rc = dalloc(e, &c.aq, tile_tokens * c.nq * c.hd)) return rc;
-    if (int rc = dalloc(e, &c.hq, tile_tokens * c.F)) return rc;
+    if (c.n_experts) {
+      // every (token, selected expert) pair is a column of the grouped GEMMs; the columns of one expert start at a
+      // multiple of 16, and a workgroup tile may read up to 255 columns past the last one
+      const u64 cols = (u64)c.maxT * c.n_active + 16ull * c.n_experts + 256 + 16;
+      c.moe_TBS = (u32)((cols + 15) / 16);
+      if (int rc = dalloc(e, &c.hq_moe, (u64)c.moe_TBS * 16 * c.F)) return rc;
+      if (int rc = dalloc(e, &c.y_moe, (u64)c.moe_TBS * 16 * c.d, false)) return rc;
+      if (int rc = dalloc(e, &c.moe_logits, (u64)c.maxT * c.n_experts, false)) return rc;
+      if (int rc = dalloc(e, &c.moe_count, c.n_experts)) return rc;
+      if (int rc = dalloc(e, &c.moe_list, (u64)c.n_experts * c.maxT)) return rc;
+      if (int rc = dalloc(e, &c.moe_sel, (u64)c.n_layers * c.maxT * c.n_active)) return rc;
+      if (int rc = dalloc(e, &c.moe_pos, (u64)c.maxT * c.n_active)) return rc;
+      if (int rc = dalloc(e, &c.moe_w, (u64)c.maxT * c.n_active)) return rc;
+    } else if (int rc = dalloc(e, &c.hq, tile_tokens * c.F)) return rc;
     if (int rc = dalloc(e, &c.ssq, tile_tokens * (c.d / 16))) return rc;
     if (int rc = dalloc(e, &c.qbuf, (u64)c.maxT * c.nq * c.hd)) return rc;
     if (c.max_batch > 64 && ((cfg->tune >> 28) & 3u) == 2u) {   // the chain with K split across workgroups: up to eight K slices of the widest split GEMM at 256 tokens
@@ -472,6 +530,11 @@ extern "C" int blink_init(const blink_config* cfg, blink_engine** out) {
     const u32 G = cfg->n_q_heads / cfg->n_kv_heads;
     if (!(G == 1 || G == 2 || G == 3 || G == 4 || G == 6 || G == 8))
       return fail(BLINK_ERR_INVAL, "bf16 path: n_q_heads / n_kv_heads must be 1, 2, 3, 4, 6 or 8");
+  }
+  if (cfg->n_experts) {
+    if (cfg->dtype != 1) return fail(BLINK_ERR_INVAL, "mixture-of-experts models are built for dtype 1 (bf16 weights) only");
+    if (cfg->n_experts > MOE_MAX_EXPERTS || !cfg->n_active || cfg->n_active > MOE_MAX_ACTIVE || cfg->n_active > cfg->n_experts)
+      return fail(BLINK_ERR_INVAL, "n_experts must be at most %d and n_active in [1, min(%d, n_experts)]", MOE_MAX_EXPERTS, MOE_MAX_ACTIVE);
   }
   if (cfg->vocab >= (1u << 24)) return fail(BLINK_ERR_INVAL, "vocab must be below 2^24");
   if (cfg->kv_block_size != 16) return fail(BLINK_ERR_INVAL, "kv_block_size must be 16");
@@ -583,6 +646,12 @@ static int enqueue_iteration_kernels(blink_engine* e, hipStream_t st, u64 enq_in
   if (int rc = launch_phase(e, c, st, PH_EMBED, 0, enq_index)) return rc;
   for (u32 l = 0; l < c.n_layers; ++l)
     for (int ph = PH_LAYER_FIRST; ph <= PH_LAYER_LAST; ++ph) {
+      if (c.n_experts && (ph == PH_GATEUP || ph == PH_DOWN)) {    // mixture of experts: five kernels in place of the two
+        if (ph == PH_DOWN) continue;
+        for (int mp = PH_ROUTER; mp <= PH_MOE_COMBINE; ++mp)
+          if (int rc = launch_phase(e, c, st, mp, l, enq_index)) return rc;
+        continue;
+      }
       if (int rc = launch_phase(e, c, st, ph, l, enq_index)) return rc;
       const int after = ph == PH_ATTN ? PH_ATTN_COMBINE : ph == PH_QKV ? PH_QKV_RED : ph == PH_OPROJ ? PH_OPROJ_RED : ph == PH_DOWN ? PH_DOWN_RED : -1;
       if (c.dtype == 1 && after >= 0 && (after == PH_ATTN_COMBINE || split))
@@ -860,6 +929,16 @@ extern "C" int blink_debug_read(blink_engine* e, uint32_t what, void* buf, uint6
       return BLINK_OK;
     }
     case BLINK_DBG_HIDDEN: src = c.x; n = (u64)m.n_tokens * c.d * 4; break;
+    case BLINK_DBG_ROUTING: {
+      if (!c.n_experts) return fail(BLINK_ERR_INVAL, "not a mixture-of-experts model");
+      const u64 row = (u64)m.n_tokens * c.n_active * 4;
+      n = row * c.n_layers;
+      if (n > cap_bytes) return fail(BLINK_ERR_INVAL, "buffer too small: need %llu bytes", (unsigned long long)n);
+      for (u32 l = 0; l < c.n_layers && row; ++l)
+        HIPCHK(hipMemcpy((char*)buf + l * row, c.moe_sel + (u64)l * c.maxT * c.n_active, row, hipMemcpyDeviceToHost));
+      *n_bytes = n;
+      return BLINK_OK;
+    }
     default: return fail(BLINK_ERR_INVAL, "unknown selector %u", what);
   }
   if (n > cap_bytes) return fail(BLINK_ERR_INVAL, "buffer too small: need %llu bytes", (unsigned long long)n);
@@ -872,7 +951,7 @@ extern "C" int blink_time_phase(blink_engine* e, int32_t phase) {
   g_err.clear();
   if (!e) return fail(BLINK_ERR_INVAL, "null engine");
   if (e->loop_active.load()) return fail(BLINK_ERR_STATE, "stop the loop first");
-  if (phase < -1 || phase > PH_DOWN_RED) return fail(BLINK_ERR_INVAL, "phase out of range");
+  if (phase < -1 || phase > PH_MOE_COMBINE) return fail(BLINK_ERR_INVAL, "phase out of range");
   e->timed_phase = phase;
   return BLINK_OK;
 }

@@ -137,13 +137,15 @@ struct LayerW {
 struct LayerWP {        // weights of a bf16 model re-tiled into MFMA operand order and re-encoded as scaled halves (see mfma_gemm.h)
   const f16_t* wqkv;    // N = (nq+2nkv)*hd, K = d
   const f16_t* wo;      // N = d, K = nq*hd
-  const f16_t* wgu;     // N = 2F (gate_j, up_j interleaved), K = d
-  const f16_t* wd;      // N = d, K = F
+  const f16_t* wgu;     // N = 2F (gate_j, up_j interleaved), K = d; mixture of experts: the experts' matrices one after the other
+  const f16_t* wd;      // N = d, K = F; mixture of experts: one per expert, one after the other
+  const f16_t* wr;      // mixture of experts: router, N = n_experts, K = d
 };
 
 struct DevCtx {
   // model
   u32 n_layers, d, nq, nkv, hd, F, V, dtype;
+  u32 n_experts, n_active;   // mixture of experts (0: dense FFN); F is then the width of one expert
   float eps, theta;
   // engine
   u32 bs, n_blocks, max_batch, max_seq_len, max_prefill_tokens, ring_slots, max_blocks_per_seq, maxT;
@@ -206,6 +208,16 @@ struct DevCtx {
   float* ssq;           // [token][d/16] partial sums of squares of the residual stream
   u32 TBS;              // token-block stride of the packed activation buffers
   u32 tune_nw;          // tuning knob of the streaming GEMM (0: automatic)
+  // mixture of experts
+  float* moe_logits;    // [maxT][n_experts] router logits
+  u32* moe_count;       // [n_experts] tokens routed to every expert in the current layer
+  u32* moe_list;        // [n_experts][maxT] their token indices (order inside a list depends on timing, results do not)
+  u32* moe_sel;         // [n_layers][maxT * n_active] selected expert of every (token, slot), kept per layer for tests
+  u32* moe_pos;         // [maxT * n_active] place of the pair in its expert's list
+  float* moe_w;         // [maxT * n_active] softmax weight of the pair
+  f16_t* hq_moe;        // packed silu(gate)*up of all pairs, columns grouped by expert (groups padded to 16), inner dimension F
+  float* y_moe;         // [columns][d] expert outputs of all pairs
+  u32 moe_TBS;          // token-block stride of hq_moe
   // GEMMs with K split across workgroups (decode iterations of 65..256 tokens): the slices' fp32 partial sums
   float* gemm_part;
   u64 gemm_part_cap;    // floats

@@ -44,7 +44,10 @@ struct MfmaGemmArgs {
   const f16_t* Xp;         // packed activations (half precision; K = inner dimension)
   u32 N, K;                // logical output rows and inner dimension (K % 32 == 0)
   u32 T;                   // tokens (columns)
-  u32 TBS;                 // token-block stride of every packed activation buffer
+  u32 TBS;                 // token-block stride of the packed activation buffers (the operand Xp and, unless TBS_out is set, the outputs)
+  u32 TBS_out;             // 0, or the token-block stride of the packed output Hp when it differs from the operand's
+  u32 col0;                // output column of token 0 (EPI_SCALED_STORE row of `out`, EPI_SILU_GATE column of Hp): a grouped
+                           // GEMM writes each group's columns behind the previous group's
   const u32* tok_index;    // optional indirection: column t reads token tok_index[t] of Xp / ssq_in (LM head)
   const float* ssq_in;     // [token][K/16] partial sums of squares of the un-normalised input (null: no scaling)
   float eps;
@@ -155,7 +158,7 @@ __device__ __forceinline__ void epilogue_tile(const MfmaGemmArgs& a, floatx4_t a
   if (EPI == EPI_SCALED_STORE) {
     if (!tv) return;
     const float r = rstd16[lane & 15];
-    float* o = a.out + (u64)t * a.ldo + n0;
+    float* o = a.out + (u64)(t + a.col0) * a.ldo + n0;
     if (n0 + 3 < a.N && (a.ldo & 3) == 0) {
       *(float4*)o = make_float4(acc[0] * r, acc[1] * r, acc[2] * r, acc[3] * r);
     } else {
@@ -214,7 +217,7 @@ __device__ __forceinline__ void epilogue_tile(const MfmaGemmArgs& a, floatx4_t a
     const float g0 = acc[0] * r, u0 = acc[1] * r, g1 = acc[2] * r, u1 = acc[3] * r;
     const float h0 = g0 / (1.f + __expf(-g0)) * u0, h1 = g1 / (1.f + __expf(-g1)) * u1;
     const u32 j = n0 >> 1;   // pair index = inner index of the next GEMM
-    *(u32*)(a.Hp + packed_off(t, j, a.TBS)) = pack_f16x2(h0, h1);
+    *(u32*)(a.Hp + packed_off(t + a.col0, j, a.TBS_out ? a.TBS_out : a.TBS)) = pack_f16x2(h0, h1);
   }
 }
 

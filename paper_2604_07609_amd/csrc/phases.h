@@ -8,13 +8,15 @@
 #include "mfma_gemm.h"
 #include "attention_mfma.h"
 #include "sampler.h"
+#include "moe.h"
 
 enum {
   PH_EMBED = 0,
   PH_NORM1, PH_QKV, PH_ROPE, PH_ATTN, PH_OPROJ, PH_NORM2, PH_GATEUP, PH_DOWN,   // per layer
   PH_FINAL_NORM, PH_LM_HEAD, PH_SAMPLE,
   PH_ATTN_COMBINE,  // bf16 path only, directly after PH_ATTN of the same layer
-  PH_QKV_RED, PH_OPROJ_RED, PH_DOWN_RED   // bf16 path, chains with K split across workgroups: second kernel of that GEMM
+  PH_QKV_RED, PH_OPROJ_RED, PH_DOWN_RED,  // bf16 path, chains with K split across workgroups: second kernel of that GEMM
+  PH_ROUTER, PH_ROUTE, PH_MOE_GATEUP, PH_MOE_DOWN, PH_MOE_COMBINE   // mixture of experts: in place of PH_GATEUP and PH_DOWN
 };
 #define PH_LAYER_FIRST PH_NORM1
 #define PH_LAYER_LAST PH_DOWN
@@ -41,6 +43,10 @@ template <> struct PhaseSharedOf<PH_NORM2> { typedef SmallPhaseShared type; };
 template <> struct PhaseSharedOf<PH_FINAL_NORM> { typedef SmallPhaseShared type; };
 template <> struct PhaseSharedOf<PH_ROPE> { typedef SmallPhaseShared type; };
 template <> struct PhaseSharedOf<PH_ATTN_COMBINE> { typedef SmallPhaseShared type; };
+template <> struct PhaseSharedOf<PH_ROUTE> { typedef SmallPhaseShared type; };
+template <> struct PhaseSharedOf<PH_MOE_GATEUP> { typedef MoeShared type; };
+template <> struct PhaseSharedOf<PH_MOE_DOWN> { typedef MoeShared type; };
+template <> struct PhaseSharedOf<PH_MOE_COMBINE> { typedef MoeShared type; };
 
 template <typename WT>
 __device__ __forceinline__ void run_phase_t(const DevCtx& c, int ph, u32 layer, void* shp, u32 wg, u32 nwg) {
@@ -103,6 +109,16 @@ __device__ __forceinline__ void run_phase_bf16(const DevCtx& c, int ph, u32 laye
       break;
     case PH_ATTN: phase_attention_mfma(c, layer, sh.attn_mfma, wg, nwg); break;
     case PH_ATTN_COMBINE: attn_decode_combine(c, wg, nwg); break;
+    case PH_ROUTER:     // router logits of every token; its first workgroup also clears the experts' counters for this layer
+      if (wg == 0)
+        for (u32 e = threadIdx.x; e < c.n_experts; e += blockDim.x) c.moe_count[e] = 0;
+      a.Wp = P->wr; a.Xp = c.xq; a.N = c.n_experts; a.K = c.d; a.ssq_in = c.ssq; a.out = c.moe_logits; a.ldo = c.n_experts;
+      gemm_mfma<EPI_SCALED_STORE, false>(a, sh.mfma, wg, nwg);
+      break;
+    case PH_ROUTE: moe_route(c, layer, wg, nwg); break;
+    case PH_MOE_GATEUP: moe_gateup(c, layer, *(MoeShared*)shp, wg, nwg); break;
+    case PH_MOE_DOWN: moe_down(c, layer, *(MoeShared*)shp, wg, nwg); break;
+    case PH_MOE_COMBINE: moe_combine(c, layer, *(MoeShared*)shp, wg, nwg); break;
     case PH_OPROJ:
     case PH_OPROJ_RED:
       a.Wp = P->wo; a.Xp = c.aq; a.N = c.d; a.K = c.nq * c.hd; a.x = c.x; a.ldx = c.d; a.g_next = c.layers[layer].g2;

@@ -34,6 +34,9 @@ MODEL_CONFIGS = {
     # mixture of experts: d_ffn is the width of one expert
     "mini_moe": dict(n_layers=2, d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=64, d_ffn=96, n_experts=8, n_active=2,
                      vocab=1500, dtype=1, rms_eps=1e-5, rope_theta=10000.0),
+    # sixteen experts, four active, wide enough that a prefill iteration gives an expert more than 64 tokens
+    "mini_moe16": dict(n_layers=2, d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=64, d_ffn=160, n_experts=16, n_active=4,
+                       vocab=2100, dtype=1, rms_eps=1e-5, rope_theta=10000.0),
     # the shape of the paper's mixture-of-experts model (30 B parameters, 3 B active per token): 128 experts of width 768, 8 active
     "moe_30b_a3b": dict(n_layers=48, d_model=2048, n_q_heads=32, n_kv_heads=4, head_dim=128, d_ffn=768, n_experts=128, n_active=8,
                         vocab=151936, dtype=1, rms_eps=1e-6, rope_theta=1000000.0),
@@ -66,6 +69,8 @@ ENGINE_CONFIGS = {
                     max_prefill_tokens=700, ring_slots=32, eos_token_id=-1),
     "mini_moe": dict(kv_block_size=16, kv_num_blocks=96, max_batch=6, max_seq_len=160,
                      max_prefill_tokens=256, ring_slots=32, eos_token_id=-1),
+    "mini_moe16": dict(kv_block_size=16, kv_num_blocks=400, max_batch=48, max_seq_len=700,
+                       max_prefill_tokens=900, ring_slots=128, eos_token_id=-1),
     "moe_30b_a3b": dict(kv_block_size=16, kv_num_blocks=32768, max_batch=256, max_seq_len=4096 + 1024,
                         max_prefill_tokens=8192, ring_slots=2048, eos_token_id=-1),
 }

@@ -188,7 +188,31 @@ def token_matches_own_logits(row, r, gen_index, token):
     return False
 
 
-def stepwise_check(B, cfg, eng, raw, blob, reqs, rtol, max_iters=10000, tune=0):
+ROUTE_MARGIN = 2e-3   # of the largest router logit of the token: beyond it the half-precision logits decide like exact ones
+
+
+def check_routing(cfg, routing, route_log, stats):
+    """The engine's expert selection against the oracle's own (computed on the same history of routings): always k
+    distinct experts in range; the same set wherever the oracle's margin between the last selected and the first
+    rejected logit is clear of the engine's arithmetic; the same order wherever the selected logits are that far apart."""
+    E, k = cfg["n_experts"], cfg["n_active"]
+    assert len(route_log) == cfg["n_layers"]
+    for rl in route_log:
+        sel = routing[rl["layer"]]
+        assert sel.shape == rl["own"].shape
+        assert sel.max() < E
+        assert all(len(set(row)) == k for row in sel.tolist())
+        clear = rl["margin"] > ROUTE_MARGIN * rl["scale"]
+        stats["pairs"] += len(clear)
+        stats["unclear"] += int((~clear).sum())
+        same_set = np.sort(sel, axis=1) == np.sort(rl["own"], axis=1)
+        assert same_set.all(axis=1)[clear].all(), (rl["layer"], np.nonzero(~same_set.all(axis=1) & clear))
+        if "gaps" in rl:
+            ordered = clear & (rl["gaps"] > ROUTE_MARGIN * rl["scale"])
+            assert (sel == rl["own"])[ordered].all(), rl["layer"]
+
+
+def stepwise_check(B, cfg, eng, raw, blob, reqs, rtol, max_iters=10000, tune=0, tokens_out=None):
     """One iteration per blink_run call: batch metadata, block tables and free stack bit-exact against the
     oracle's scheduler; logits within rtol of the row maximum against the oracle's paged forward fed with
     the engine's own token history; every token against the oracle's sampler run on the engine's own logits
@@ -201,6 +225,7 @@ def stepwise_check(B, cfg, eng, raw, blob, reqs, rtol, max_iters=10000, tune=0):
     e = B.Engine(cfg, eng, blob, flags=B.FLAG_TRACE | B.FLAG_EXIT_WHEN_IDLE | B.FLAG_KEEP_LOGITS, tune=tune)
     D = B.DBG
     worst = 0.0
+    moe_stats = dict(pairs=0, unclear=0)
     try:
         for r in reqs:
             e.submit_request(r)
@@ -211,6 +236,7 @@ def stepwise_check(B, cfg, eng, raw, blob, reqs, rtol, max_iters=10000, tune=0):
             sched.check_invariants()
             if plan.kind == 0:
                 assert e.stats()["iterations"] == it
+                assert moe_stats["unclear"] <= 0.08 * moe_stats["pairs"], moe_stats
                 return worst
             assert list(e.debug_read(D.INPUT_IDS, np.int32)) == plan.input_ids
             assert list(e.debug_read(D.POSITIONS, np.int32)) == plan.positions
@@ -223,8 +249,14 @@ def stepwise_check(B, cfg, eng, raw, blob, reqs, rtol, max_iters=10000, tune=0):
             bt = e.debug_read(D.BLOCK_TABLES, np.uint32).reshape(eng["max_batch"], -1)
             for b, blocks in zip(plan.batch_slots, plan.block_tables):
                 assert list(bt[b][: len(blocks)]) == blocks
+            routing, route_log = None, None
+            if cfg.get("n_experts", 0):   # mixture of experts: the oracle follows the engine's routing and reports its own
+                routing = e.debug_read(D.ROUTING, np.uint32).reshape(cfg["n_layers"], len(plan.input_ids), cfg["n_active"])
+                route_log = []
             ref = M.paged_forward(cfg, W, kv, plan.input_ids, plan.positions, plan.slot_mapping, plan.tok_seq,
-                                  plan.block_tables, plan.last_idx)
+                                  plan.block_tables, plan.last_idx, routing=routing, route_log=route_log)
+            if routing is not None:
+                check_routing(cfg, routing, route_log, moe_stats)
             evs = e.drain()
             by_ticket = {int(x["request_id"]): int(x["token"]) for x in evs}
             assert sorted(by_ticket) == sorted(plan.sample_tickets)
@@ -235,6 +267,9 @@ def stepwise_check(B, cfg, eng, raw, blob, reqs, rtol, max_iters=10000, tune=0):
                 assert err.max() < rtol, (it, err)
                 for i, t in enumerate(plan.sample_tickets):
                     token_matches_own_logits(got[i], reqs[t], plan.gen_index[i], by_ticket[t])
+            if tokens_out is not None:
+                for t in plan.sample_tickets:
+                    tokens_out.setdefault(t, []).append(by_ticket[t])
             sched.commit(plan, [by_ticket[t] for t in plan.sample_tickets])   # the engine's tokens are the history
         raise AssertionError("did not finish")
     finally:

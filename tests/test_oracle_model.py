@@ -255,3 +255,32 @@ def test_moe_dense_equals_cached_equals_paged():
     bt = [[2, 0, 3]]
     lg = M.paged_forward(cfg, W, kv, list(toks), list(range(23)), [bt[0][p // 8] * 8 + p % 8 for p in range(23)], [0] * 23, bt, [22])
     assert np.abs(lg[0] - dense[22]).max() < 1e-12
+
+
+def test_routing_check_accepts_the_own_routing_and_rejects_planted_mistakes():
+    """tests/parity.check_routing (used by the GPU tests of the expert selection): the oracle's own routing passes; a
+    clearly rejected expert in place of a selected one, two clearly ordered experts swapped, or one expert twice, fail.
+    The report's `gaps` is the smallest difference between consecutive selected logits."""
+    from tests.parity import check_routing, ROUTE_MARGIN
+    cfg = _moe_cfg(6, 3)
+    raw = synth.make_weights(cfg, 8, std=0.3)
+    W = M.Weights(cfg, raw)
+    h = np.random.default_rng(3).normal(size=(40, 32))
+    logs = []
+    for l in range(2):
+        M.moe_ffn(cfg, W, l, h, route_log=logs)
+    own = np.stack([lg["own"] for lg in logs])
+    r = h @ W["l0.wr"].T
+    picked = np.take_along_axis(r, logs[0]["own"], axis=1)
+    assert np.allclose(logs[0]["gaps"], np.minimum(picked[:, 0] - picked[:, 1], picked[:, 1] - picked[:, 2]))
+    stats = dict(pairs=0, unclear=0)
+    check_routing(cfg, own, logs, stats)
+    assert stats["pairs"] == 80
+    t = int(np.argmax(np.minimum(logs[0]["margin"], logs[0]["gaps"]) / logs[0]["scale"]))     # the clearest token of layer 0
+    assert min(logs[0]["margin"][t], logs[0]["gaps"][t]) > ROUTE_MARGIN * logs[0]["scale"][t]
+    rejected = [e for e in range(6) if e not in own[0, t]][0]
+    for wrong in ([own[0, t, 0], own[0, t, 1], rejected], [own[0, t, 1], own[0, t, 0], own[0, t, 2]], [own[0, t, 0]] * 3):
+        bad = own.copy()
+        bad[0, t] = wrong
+        with pytest.raises(AssertionError):
+            check_routing(cfg, bad, logs, dict(pairs=0, unclear=0))
