@@ -463,6 +463,7 @@ static int init_impl(const blink_config* cfg, blink_engine* e) {
       if (int rc = dalloc(e, &c.moe_sel, (u64)c.n_layers * c.maxT * c.n_active)) return rc;
       if (int rc = dalloc(e, &c.moe_pos, (u64)c.maxT * c.n_active)) return rc;
       if (int rc = dalloc(e, &c.moe_w, (u64)c.maxT * c.n_active)) return rc;
+      if (int rc = dalloc(e, &c.moe_rstd, c.maxT)) return rc;
     } else if (int rc = dalloc(e, &c.hq, tile_tokens * c.F)) return rc;
     if (int rc = dalloc(e, &c.ssq, tile_tokens * (c.d / 16))) return rc;
     if (int rc = dalloc(e, &c.qbuf, (u64)c.maxT * c.nq * c.hd)) return rc;

@@ -13,20 +13,44 @@
 #define MOE_MAX_EXPERTS 256
 #define MOE_MAX_ACTIVE 8
 
+#define MOE_WAVE_MAX_TOKENS 64   // experts with at most this many tokens are run by independent waves (see moe_wave_item)
+
 struct MoeShared {
   MfmaShared mfma;
   u32 cnt[MOE_MAX_EXPERTS];
   u32 off[MOE_MAX_EXPERTS + 1];   // first column of every expert's group: counts padded to whole 16-token blocks
+  u32 small_e[MOE_MAX_EXPERTS];   // experts with 1..MOE_WAVE_MAX_TOKENS tokens, and the first wave item of each
+  u32 small_base[MOE_MAX_EXPERTS + 1];
+  u32 big_e[MOE_MAX_EXPERTS];     // experts with more tokens: one GEMM of the workgroup schedules each
+  u32 n_small, n_big;
+  float wrstd[4][64];             // per wave: norm scales of the tokens of its current item
 };
 
-// counts -> LDS, offsets by a serial prefix sum (at most 256 terms); every workgroup of the grouped kernels does this
-__device__ __forceinline__ void moe_offsets(const DevCtx& c, u32* cnt, u32* off) {
-  for (u32 e = threadIdx.x; e < c.n_experts; e += blockDim.x) cnt[e] = c.moe_count[e];
+// counts -> LDS, offsets by a serial prefix sum (at most 256 terms); every workgroup of the grouped kernels does this.
+// NT > 0 (row tiles of an expert's matrix): also the split of the experts into those run by independent waves, with their
+// wave items (moe_wave_rows row tiles each), and the rest.
+__device__ __forceinline__ u32 moe_wave_rows(u32 n_tokens) { return n_tokens <= 32 ? 4u : 2u; }
+
+__device__ __forceinline__ void moe_offsets(const DevCtx& c, MoeShared& sh, u32 NT = 0) {
+  for (u32 e = threadIdx.x; e < c.n_experts; e += blockDim.x) sh.cnt[e] = c.moe_count[e];
   __syncthreads();
   if (threadIdx.x == 0) {
-    u32 o = 0;
-    for (u32 e = 0; e < c.n_experts; ++e) { off[e] = o; o += (cnt[e] + 15u) & ~15u; }
-    off[c.n_experts] = o;
+    u32 o = 0, ns = 0, nb = 0, base = 0;
+    for (u32 e = 0; e < c.n_experts; ++e) {
+      const u32 n = sh.cnt[e];
+      sh.off[e] = o;
+      o += (n + 15u) & ~15u;
+      if (NT && n) {
+        if (n <= MOE_WAVE_MAX_TOKENS) {
+          const u32 nw = moe_wave_rows(n);
+          sh.small_e[ns] = e; sh.small_base[ns] = base; base += (NT + nw - 1) / nw; ++ns;
+        }
+        else sh.big_e[nb++] = e;
+      }
+    }
+    sh.off[c.n_experts] = o;
+    sh.small_base[ns] = base;
+    sh.n_small = ns; sh.n_big = nb;
   }
   __syncthreads();
 }
@@ -36,6 +60,14 @@ __device__ __forceinline__ void moe_route(const DevCtx& c, u32 layer, u32 wg, u3
   const u32 T = c.meta->n_tokens, E = c.n_experts, k = c.n_active;
   const u32 lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = blockDim.x >> 6;
   for (u32 t = wg * nw + w; t < T; t += nwg * nw) {
+    {   // the norm scale of the token (times the inverse of the weight scale), for the waves of the grouped gate/up GEMM
+      const u32 np = c.d / 16;
+      float v = 0.f;
+      for (u32 q = lane; q < np; q += 64) v += c.ssq[(u64)t * np + q];
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+      if (lane == 0) c.moe_rstd[t] = W_SCALE_INV / sqrtf(v / (float)c.d + c.eps);
+    }
     const float* r = c.moe_logits + (u64)t * E;
     unsigned long long key[MOE_MAX_EXPERTS / 64];
 #pragma unroll
@@ -74,40 +106,138 @@ __device__ __forceinline__ void moe_route(const DevCtx& c, u32 layer, u32 wg, u3
   }
 }
 
-// ---- grouped GEMMs: every expert's token list is one GEMM of the existing schedules; the workgroups start each expert's
-// items at a different place so that the experts' items interleave over the grid ---------------------------------------
-__device__ __forceinline__ void moe_gateup(const DevCtx& c, u32 layer, MoeShared& sh, u32 wg, u32 nwg) {
-  moe_offsets(c, sh.cnt, sh.off);
+// ---- grouped GEMMs -----------------------------------------------------------------------------------------------------
+// An expert with at most MOE_WAVE_MAX_TOKENS tokens (every expert of a decode iteration, as a rule) is bound by the
+// bytes of its matrices. Its GEMM is cut into wave items of four (two, beyond 32 tokens) 16-row weight tiles x all its
+// tokens x the whole of K;
+// the waves of the grid take the items of all such experts round-robin and run them on their own: no barrier, no
+// shared memory traffic, the loads of two batches of k-tiles in flight per wave. A wave streams its rows of tiles
+// (contiguous in the packed layout) with loads that bypass temporal caching and reads the tokens' operand tiles, which
+// the neighbouring waves (same expert, next rows) read too, through the caches.
+template <bool GATEUP, int TW>
+__device__ __forceinline__ void moe_wave_item(const DevCtx& c, const LayerWP* P, MoeShared& sh, u32 e, u32 g) {
+  constexpr int NW = TW <= 2 ? 4 : 2, U = 2;
+  constexpr int EPI = GATEUP ? EPI_SILU_GATE : EPI_SCALED_STORE;
+  const u32 lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const u32 cnt = sh.cnt[e], col0 = sh.off[e];
+  const u32 K = GATEUP ? c.d : c.F, N = GATEUP ? 2 * c.F : c.d, KT = K / 32, NT = N / 16;
+  const f16_t* Wp = GATEUP ? P->wgu + (u64)e * (2 * c.F) * c.d : P->wd + (u64)e * c.d * c.F;
+  const f16_t* wp[NW];
+#pragma unroll
+  for (int i = 0; i < NW; ++i) wp[i] = Wp + (u64)min(g * NW + i, NT - 1) * KT * 512 + lane * 8;
+  const f16_t* xp[TW];
+  const u64 xk_stride = (u64)(GATEUP ? c.TBS : c.moe_TBS) * 512;
+#pragma unroll
+  for (int tw = 0; tw < TW; ++tw) {
+    if (GATEUP) {
+      const u32 tok = c.moe_list[(u64)e * c.maxT + min(tw * 16 + (lane & 15), cnt - 1)];
+      xp[tw] = c.xq + (u64)((tok >> 4) * 64 + (tok & 15) + 16 * (lane >> 4)) * 8;
+      if (lane < 16) sh.wrstd[w][tw * 16 + lane] = c.moe_rstd[tok];
+    } else {
+      xp[tw] = c.hq_moe + (u64)(col0 / 16 + tw) * 512 + lane * 8;
+    }
+  }
+  struct Buf { f16x8_t w[U][NW], x[U][TW]; };
+  const f16x8_t zero = {0, 0, 0, 0, 0, 0, 0, 0};
+  auto issue = [&](Buf& b, u32 kt0) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const u32 kt = kt0 + u;
+      const bool ok = kt < KT;
+#pragma unroll
+      for (int i = 0; i < NW; ++i) b.w[u][i] = ok ? ld_op_stream(wp[i] + (u64)kt * 512) : zero;
+#pragma unroll
+      for (int tw = 0; tw < TW; ++tw) b.x[u][tw] = ok ? ld_op(xp[tw] + (u64)kt * xk_stride) : zero;
+    }
+  };
+  floatx4_t acc[NW][TW];
+#pragma unroll
+  for (int i = 0; i < NW; ++i)
+#pragma unroll
+    for (int tw = 0; tw < TW; ++tw) acc[i][tw] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+  auto mm = [&](const Buf& b) {
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int i = 0; i < NW; ++i)
+#pragma unroll
+        for (int tw = 0; tw < TW; ++tw) acc[i][tw] = __builtin_amdgcn_mfma_f32_16x16x32_f16(b.w[u][i], b.x[u][tw], acc[i][tw], 0, 0, 0);
+  };
+  Buf bufA, bufB;
+  issue(bufA, 0);
+  for (u32 kt0 = 0; kt0 < KT; kt0 += 2 * U) {
+    issue(bufB, kt0 + U);
+    mm(bufA);
+    issue(bufA, kt0 + 2 * U);
+    mm(bufB);
+  }
+  MfmaGemmArgs a{};
+  a.T = cnt; a.N = N; a.col0 = col0; a.TBS = c.TBS;
+  if (GATEUP) { a.Hp = c.hq_moe; a.TBS_out = c.moe_TBS; }
+  else { a.out = c.y_moe; a.ldo = c.d; }
+#pragma unroll
+  for (int i = 0; i < NW; ++i)
+    if (g * NW + i < NT) {
+#pragma unroll
+      for (int tw = 0; tw < TW; ++tw) epilogue_tile<EPI>(a, acc[i][tw], g * NW + i, tw * 16, &sh.wrstd[w][tw * 16]);
+    }
+}
+
+// Experts with more tokens run as one GEMM of the workgroup schedules each (shared operand tiles in LDS); the workgroups
+// start each expert's items at a different place so that the experts' items interleave over the grid.
+template <bool GATEUP>
+__device__ __forceinline__ void moe_grouped(const DevCtx& c, u32 layer, MoeShared& sh, u32 wg, u32 nwg) {
   const LayerWP* P = c.players + layer;
-  const u32 Fe = c.F;
-  for (u32 e = 0; e < c.n_experts; ++e) {
-    if (sh.cnt[e] == 0) continue;
+  const u32 Fe = c.F, N = GATEUP ? 2 * Fe : c.d;
+  moe_offsets(c, sh, N / 16);
+  const u32 lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  if (!GATEUP) sh.wrstd[w][lane] = W_SCALE_INV;      // each wave reads only its own row
+  const u32 total = sh.small_base[sh.n_small];
+  for (u32 i = wg * nw + w; i < total; i += nwg * nw) {
+    u32 lo = 0, hi = sh.n_small;                     // the expert of item i: last s with small_base[s] <= i
+    while (hi - lo > 1) {
+      const u32 mid = (lo + hi) >> 1;
+      if (sh.small_base[mid] <= i) lo = mid; else hi = mid;
+    }
+    const u32 e = sh.small_e[lo], g = i - sh.small_base[lo];
+    switch ((sh.cnt[e] + 15) / 16) {
+      case 1: moe_wave_item<GATEUP, 1>(c, P, sh, e, g); break;
+      case 2: moe_wave_item<GATEUP, 2>(c, P, sh, e, g); break;
+      case 3: moe_wave_item<GATEUP, 3>(c, P, sh, e, g); break;
+      default: moe_wave_item<GATEUP, 4>(c, P, sh, e, g); break;
+    }
+  }
+  for (u32 b = 0; b < sh.n_big; ++b) {
+    const u32 e = sh.big_e[b];
     MfmaGemmArgs a{};
-    a.T = sh.cnt[e]; a.TBS = c.TBS; a.eps = c.eps; a.tune_nw = c.tune_nw;
-    a.Wp = P->wgu + (u64)e * (2 * Fe) * c.d; a.Xp = c.xq; a.N = 2 * Fe; a.K = c.d; a.ssq_in = c.ssq;
-    a.tok_index = c.moe_list + (u64)e * c.maxT;
-    a.Hp = c.hq_moe; a.TBS_out = c.moe_TBS; a.col0 = sh.off[e];
-    gemm_mfma<EPI_SILU_GATE, false>(a, sh.mfma, (wg + nwg - (e * 97u) % nwg) % nwg, nwg);
+    a.T = sh.cnt[e]; a.eps = c.eps; a.tune_nw = c.tune_nw; a.col0 = sh.off[e];
+    // the other experts' GEMMs fill the chip: take the widest tile the expert's tokens fill instead of a narrower one
+    // that would spread this one GEMM over more workgroups (bits 12-14 of the tuning word, unless the caller forces them)
+    if (((a.tune_nw >> 12) & 7u) == 0)
+      a.tune_nw |= (a.T <= 64 ? 2u : a.T <= 96 ? 3u : a.T <= 128 ? 4u : a.T <= 192 ? 6u : 7u) << 12;
+    if (GATEUP) {
+      a.TBS = c.TBS; a.Wp = P->wgu + (u64)e * (2 * Fe) * c.d; a.Xp = c.xq; a.N = 2 * Fe; a.K = c.d; a.ssq_in = c.ssq;
+      a.tok_index = c.moe_list + (u64)e * c.maxT;
+      a.Hp = c.hq_moe; a.TBS_out = c.moe_TBS;
+      gemm_mfma<EPI_SILU_GATE, false>(a, sh.mfma, (wg + nwg - (b * 97u) % nwg) % nwg, nwg);
+    } else {
+      a.TBS = c.moe_TBS; a.Wp = P->wd + (u64)e * c.d * Fe; a.Xp = c.hq_moe + (u64)(sh.off[e] / 16) * 512; a.N = c.d; a.K = Fe;
+      a.out = c.y_moe; a.ldo = c.d;
+      gemm_mfma<EPI_SCALED_STORE, false>(a, sh.mfma, (wg + nwg - (b * 61u) % nwg) % nwg, nwg);
+    }
   }
 }
 
+__device__ __forceinline__ void moe_gateup(const DevCtx& c, u32 layer, MoeShared& sh, u32 wg, u32 nwg) {
+  moe_grouped<true>(c, layer, sh, wg, nwg);
+}
 __device__ __forceinline__ void moe_down(const DevCtx& c, u32 layer, MoeShared& sh, u32 wg, u32 nwg) {
-  moe_offsets(c, sh.cnt, sh.off);
-  const LayerWP* P = c.players + layer;
-  const u32 Fe = c.F;
-  for (u32 e = 0; e < c.n_experts; ++e) {
-    if (sh.cnt[e] == 0) continue;
-    MfmaGemmArgs a{};
-    a.T = sh.cnt[e]; a.TBS = c.moe_TBS; a.eps = c.eps; a.tune_nw = c.tune_nw;
-    a.Wp = P->wd + (u64)e * c.d * Fe; a.Xp = c.hq_moe + (u64)(sh.off[e] / 16) * 512; a.N = c.d; a.K = Fe;
-    a.out = c.y_moe; a.ldo = c.d; a.col0 = sh.off[e];
-    gemm_mfma<EPI_SCALED_STORE, false>(a, sh.mfma, (wg + nwg - (e * 61u) % nwg) % nwg, nwg);
-  }
+  moe_grouped<false>(c, layer, sh, wg, nwg);
 }
 
 // ---- x[t] += sum_j w_j * y[column of (t, j)], in selection order; packed operand and norm partials of the next GEMM ----
 __device__ __forceinline__ void moe_combine(const DevCtx& c, u32 layer, MoeShared& sh, u32 wg, u32 nwg) {
-  moe_offsets(c, sh.cnt, sh.off);
+  moe_offsets(c, sh);
   const u32 T = c.meta->n_tokens, d = c.d, per_row = d / 16, k = c.n_active;
   const float* g = layer + 1 < c.n_layers ? c.layers[layer + 1].g1 : c.gf;
   for (u64 i = (u64)wg * blockDim.x + threadIdx.x; i < (u64)T * per_row; i += (u64)nwg * blockDim.x) {

@@ -113,7 +113,10 @@ __device__ __forceinline__ void run_phase_bf16(const DevCtx& c, int ph, u32 laye
       if (wg == 0)
         for (u32 e = threadIdx.x; e < c.n_experts; e += blockDim.x) c.moe_count[e] = 0;
       a.Wp = P->wr; a.Xp = c.xq; a.N = c.n_experts; a.K = c.d; a.ssq_in = c.ssq; a.out = c.moe_logits; a.ldo = c.n_experts;
-      gemm_mfma<EPI_SCALED_STORE, false>(a, sh.mfma, wg, nwg);
+      // few rows: with 65..256 tokens the (row tile, 64 tokens) items of the streaming schedule spread the matrix over
+      // more workgroups than its single 128-row block of the tiled schedules would
+      if (a.T > 64 && a.T <= 256) gemm_stream<EPI_SCALED_STORE, 1, 4, stream_batch(1, 4), true>(a, sh.mfma, wg, nwg);
+      else gemm_mfma<EPI_SCALED_STORE, false>(a, sh.mfma, wg, nwg);
       break;
     case PH_ROUTE: moe_route(c, layer, wg, nwg); break;
     case PH_MOE_GATEUP: moe_gateup(c, layer, *(MoeShared*)shp, wg, nwg); break;

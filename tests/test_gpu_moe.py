@@ -32,11 +32,12 @@ def test_moe_stepwise(lib):
     assert free_run_tokens(lib, cfg, eng, blob, reqs) == toks
 
 
-@pytest.mark.parametrize("prompts,max_new", [([530, 260, 7, 90], 4), ([33] * 40 + [17] * 8, 5)])
+@pytest.mark.parametrize("prompts,max_new", [([530, 260, 7, 90], 4), ([33] * 40 + [17] * 8, 5), ([100, 60, 30], 4)])
 def test_moe16_stepwise(lib, prompts, max_new):
     """Sixteen experts, four active. Long prompts: an expert gets well over 64 tokens of a prefill iteration (the tiled
     GEMM schedules, groups that start at every multiple of 16). 48 short requests: decode iterations of 48 tokens,
-    12 per expert on average (streaming schedule with one to four token blocks per expert, some experts empty)."""
+    12 per expert on average (independent waves with one to four token blocks per expert, some experts empty). Three
+    prompts of 190 tokens in all: the router GEMM on its 65..256-token schedule."""
     cfg, eng, raw, blob = setup("mini_moe16", 142)
     reqs = _fixed_prompts(cfg, prompts, max_new, 242)
     toks = {}
