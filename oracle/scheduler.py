@@ -41,8 +41,54 @@ goes to DECODE_PAUSED. Preempted requests are resumed before any new request is 
 recomputation: the resumed request prefills its prompt followed by the tokens it has generated so far and samples its
 next output token from the last position, so its stream continues where it stopped. The oldest running request is never
 short of blocks once the others are gone, because a request that could not fit the pool alone is refused at submission.
+
+Prefix caching (`prefix_cache=True`; section 7 of the paper: the paged cache provides reusable blocks, and a hash
+table inside the scheduler can map token prefixes to blocks. It says no more). The reading taken here, for the plain mode:
+  * Unit: a full block of PROMPT tokens. Block j of a prompt has the key h_j = mix64(h_{j-1} xor g_j), h_{-1} a constant,
+    g_j a hash of the block's 16 token ids (prefix_block_hash, prefix_chain): the key covers the whole prefix up to and
+    including block j. The table maps key -> physical block; two prefixes with equal 64-bit keys are taken as equal.
+  * Admission of a request matches the leading blocks of its prompt against the table as it stands at the start of the
+    iteration, stopping at the first miss and never matching the block that holds the last prompt token (at least one
+    token is computed). The m matched blocks head its block table, its prefill computes the tokens from 16 m on, and
+    it reserves its worst case minus m. Matched blocks are reference-counted; cached blocks in use count once against
+    the pool (pinned), beside the private reservations. In the FCFS admission test a matched block that is idle at
+    the start of the iteration is charged to every candidate that matches it (conservative inside one iteration).
+    The prefill-token budget counts computed tokens.
+  * After the allocation of a prefill iteration every admitted request, in batch-slot order, enters its own full prompt
+    blocks beyond the matched ones into the table (reference count 1, moved from its private reservation to the
+    pinned count) unless the key is already there; a block whose key is present stays private.
+  * The free list is a double-ended queue. Retirement pushes private blocks on top in block-table order as before;
+    a cached block whose reference count drops to zero stays in the table and goes to the BOTTOM, the request's
+    blocks in reverse block-table order (so the head of a prefix lies deepest). Allocation pops from the top: private
+    blocks are reused first, idle cached blocks oldest first, and a prefix loses its tail before its head. Popping
+    an idle cached block evicts it from the table. A match on an idle block takes it out of the queue by moving
+    the top element into its place.
 """
 import numpy as np
+
+MASK64 = (1 << 64) - 1
+PREFIX_H0 = 0x243F6A8885A308D3
+
+
+def mix64(z):
+    """The finalizer of splitmix64 (Steele, Lea and Flood's generator) on a 64-bit integer."""
+    z &= MASK64
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & MASK64
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & MASK64
+    return z ^ (z >> 31)
+
+
+def prefix_block_hash(tokens):
+    """g of one block: polynomial in the token ids modulo 2^64, then mixed."""
+    a = 0
+    for t in tokens:
+        a = (a * 0x9E3779B97F4A7C15 + int(t) + 1) & MASK64
+    return mix64(a)
+
+
+def prefix_chain(h_prev, tokens):
+    return mix64(h_prev ^ prefix_block_hash(tokens))
+
 
 EMPTY, PREFILL_PENDING, PREFILL_PROCESSING, DECODE_PROCESSING, DECODE_COMPLETED, DECODE_PAUSED = range(6)
 
@@ -58,7 +104,11 @@ IDLE, PREFILL, DECODE = 0, 1, 2
 
 
 class Running:
-    __slots__ = ("ticket", "P", "max_new", "gen", "ctx_len", "reserved", "blocks", "finished", "last_token", "prefilled")
+    __slots__ = ("ticket", "P", "max_new", "gen", "ctx_len", "reserved", "blocks", "finished", "last_token", "prefilled",
+                 "h_end", "n_matched")
+
+    def prefilled_blocks(self, bs):
+        return self.n_matched
 
 
 class Plan:
@@ -99,8 +149,15 @@ def blocks_needed(P, max_new, bs):
 
 class Scheduler:
     def __init__(self, n_blocks, block_size, max_batch, max_prefill_tokens, ring_slots, eos_token_id=-1,
-                 free_list=None, chunked=False, preempt=False):
-        self.chunked, self.preempt = chunked, preempt
+                 free_list=None, chunked=False, preempt=False, prefix_cache=False):
+        self.chunked, self.preempt, self.prefix_cache = chunked, preempt, prefix_cache
+        assert not (prefix_cache and (chunked or preempt)), "prefix caching is defined for the plain mode only"
+        self.table = {}             # prefix caching: key -> block
+        self.bkey = {}              # block -> key, for the cached blocks
+        self.ref = [0] * n_blocks   # running requests that hold the cached block
+        self.pinned = 0             # cached blocks with a reference
+        self.cache_hits = 0         # blocks matched so far
+        self.evictions = 0
         assert not (chunked and preempt), "preemption is defined for the plain (pause-and-resume) mode only"
         self.preempted = []         # Running records of preempted requests (no blocks, no batch slot)
         if chunked:
@@ -122,7 +179,8 @@ class Scheduler:
     def from_engine(cls, eng):
         """From an engine configuration dict (synth.configs)."""
         return cls(eng["kv_num_blocks"], eng["kv_block_size"], eng["max_batch"], eng["max_prefill_tokens"], eng["ring_slots"],
-                   eng.get("eos_token_id", -1), chunked=bool(eng.get("chunked_prefill", False)), preempt=bool(eng.get("preemption", False)))
+                   eng.get("eos_token_id", -1), chunked=bool(eng.get("chunked_prefill", False)), preempt=bool(eng.get("preemption", False)),
+                   prefix_cache=bool(eng.get("prefix_cache", False)))
 
     # ---- ring side -------------------------------------------------------------------
     def submit(self, prompt, max_new):
@@ -144,6 +202,8 @@ class Scheduler:
             return self._step_chunked(tail)
         if self.preempt:
             return self._step_preempt(tail)
+        if self.prefix_cache:
+            return self._step_cached(tail)
         bs = self.bs
         plan = Plan()
         plan.tail = tail
@@ -228,6 +288,151 @@ class Scheduler:
             plan.gen_index.append(r.gen)
             plan.sample_seq.append(si)
             plan.pos0.append(pos[0])
+        plan.free_blocks_after = len(self.free)
+        return plan
+
+    # ---- one iteration with prefix caching ---------------------------------------------------------------------------
+    def _pop_block(self):
+        blk = self.free.pop()
+        if blk in self.bkey:                  # an idle cached block is reused: evicted
+            del self.table[self.bkey.pop(blk)]
+            self.evictions += 1
+        return blk
+
+    def _step_cached(self, tail):
+        bs = self.bs
+        plan = Plan()
+        plan.tail = tail
+        # (1) retire
+        for b in range(self.max_batch):
+            r = self.running[b]
+            if r is not None and r.finished:
+                idle = []
+                for blk in r.blocks:
+                    if blk in self.bkey:
+                        self.ref[blk] -= 1
+                        if self.ref[blk] == 0:
+                            self.pinned -= 1
+                            idle.append(blk)
+                    else:
+                        self.free.append(blk)
+                for blk in reversed(idle):
+                    self.free.insert(0, blk)
+                self.committed -= r.reserved
+                self.running[b] = None
+        # (2)+(3) admit in ticket order against the table and the reference counts of the start of the iteration
+        ref0 = list(self.ref)
+        load = self.committed + self.pinned
+        admitted_tokens = 0
+        new_slots = []
+        while self.next_ticket < tail:
+            t = self.next_ticket
+            prompt, max_new = self.requests[t]
+            P = prompt.size
+            h, matched = PREFIX_H0, []
+            for j in range((P - 1) // bs):
+                hj = prefix_chain(h, prompt[j * bs:(j + 1) * bs])
+                if hj not in self.table:
+                    break
+                matched.append(self.table[hj])
+                h = hj
+            m = len(matched)
+            need = blocks_needed(P, max_new, bs) - m
+            charge = need + sum(1 for blk in matched if ref0[blk] == 0)
+            free_slots = [b for b in range(self.max_batch) if self.running[b] is None]
+            if not free_slots:
+                break
+            if load + charge > self.n_blocks:
+                break
+            if new_slots and admitted_tokens + (P - m * bs) > self.max_prefill_tokens:
+                break
+            for blk in matched:
+                if self.ref[blk] == 0:           # idle: out of the queue, the top element fills its place
+                    i = self.free.index(blk)
+                    top = self.free.pop()
+                    if i < len(self.free):
+                        self.free[i] = top
+                    self.pinned += 1
+                self.ref[blk] += 1
+            self.cache_hits += m
+            r = Running()
+            r.ticket, r.P, r.max_new, r.gen, r.ctx_len = t, P, max_new, 0, 0
+            r.reserved, r.blocks, r.finished, r.last_token, r.prefilled = need, list(matched), False, -1, P
+            r.h_end, r.n_matched = h, m
+            b = free_slots[0]
+            self.running[b] = r
+            self.committed += need
+            load += charge
+            admitted_tokens += P - m * bs
+            new_slots.append(b)
+            plan.admitted.append(t)
+            self._set(t, PREFILL_PROCESSING)
+            self.next_ticket = t + 1
+        # (4) kind
+        if new_slots:
+            plan.kind = PREFILL
+            slots = sorted(new_slots)
+            for b in range(self.max_batch):
+                r = self.running[b]
+                if r is not None and b not in new_slots and self.state[r.ticket] == DECODE_PROCESSING:
+                    self._set(r.ticket, DECODE_PAUSED)
+        else:
+            slots = [b for b in range(self.max_batch) if self.running[b] is not None]
+            if not slots:
+                plan.kind = IDLE
+                return plan
+            plan.kind = DECODE
+            for b in slots:
+                r = self.running[b]
+                if self.state[r.ticket] == DECODE_PAUSED:
+                    self._set(r.ticket, DECODE_PROCESSING)
+        plan.iteration = self.iteration
+        self.iteration += 1
+        # (5) allocate, (6) metadata
+        for si, b in enumerate(slots):
+            r = self.running[b]
+            if plan.kind == PREFILL:
+                p0 = len(r.blocks) * bs                      # the matched prefix is not recomputed
+                for _ in range(-(-r.P // bs) - len(r.blocks)):
+                    r.blocks.append(self._pop_block())
+                toks = list(self.requests[r.ticket][0][p0:])
+                pos = list(range(p0, r.P))
+                r.ctx_len = r.P
+            else:
+                if r.ctx_len == len(r.blocks) * bs:
+                    r.blocks.append(self._pop_block())
+                toks = [r.last_token]
+                pos = [r.ctx_len]
+                r.ctx_len += 1
+            plan.batch_slots.append(b)
+            plan.tickets.append(r.ticket)
+            plan.seq_lens.append(r.ctx_len)
+            plan.input_ids += [int(x) for x in toks]
+            plan.positions += pos
+            plan.slot_mapping += [r.blocks[p // bs] * bs + p % bs for p in pos]
+            plan.tok_seq += [si] * len(pos)
+            plan.cu_seqlens.append(len(plan.input_ids))
+            plan.last_idx.append(len(plan.input_ids) - 1)
+            plan.block_tables.append(list(r.blocks))
+            plan.gen_index.append(r.gen)
+            plan.sample_seq.append(si)
+            plan.pos0.append(pos[0])
+        # the admitted requests' own full prompt blocks enter the table, batch slot ascending
+        if plan.kind == PREFILL:
+            for b in slots:
+                r = self.running[b]
+                prompt = self.requests[r.ticket][0]
+                h = r.h_end
+                for j in range(r.prefilled_blocks(bs), r.P // bs):
+                    h = prefix_chain(h, prompt[j * bs:(j + 1) * bs])
+                    if h not in self.table:
+                        blk = r.blocks[j]
+                        self.table[h] = blk
+                        self.bkey[blk] = h
+                        self.ref[blk] = 1
+                        r.reserved -= 1
+                        self.committed -= 1
+                        self.pinned += 1
         plan.free_blocks_after = len(self.free)
         return plan
 
@@ -459,6 +664,29 @@ class Scheduler:
     # ---- invariants ---------------------------------------------------------------------
     def check_invariants(self):
         held = [blk for r in self.running if r is not None for blk in r.blocks]
+        if self.prefix_cache:
+            # a cached block in use is held by `ref` requests and counts once; an idle one sits in the queue and in the table
+            refs = {}
+            for blk in held:
+                if blk in self.bkey:
+                    refs[blk] = refs.get(blk, 0) + 1
+            assert all(self.ref[blk] == n for blk, n in refs.items())
+            assert all((self.ref[blk] > 0) == (blk in refs) for blk in self.bkey)
+            assert self.pinned == len(refs)
+            assert all(self.table[k] == blk for blk, k in self.bkey.items()) and len(self.table) == len(self.bkey)
+            assert all(blk in self.bkey for blk in range(self.n_blocks) if self.ref[blk] > 0)
+            private = [blk for blk in held if blk not in self.bkey]
+            allb = private + list(refs) + self.free
+            assert len(allb) == self.n_blocks and len(set(allb)) == self.n_blocks, "block leaked or duplicated"
+            assert sum(r.reserved for r in self.running if r is not None) == self.committed
+            assert len(private) <= self.committed and self.committed + self.pinned <= self.n_blocks
+            for r in self.running:
+                if r is not None:
+                    assert len([blk for blk in r.blocks if blk not in self.bkey]) <= r.reserved
+                    assert len(r.blocks) * self.bs >= r.ctx_len
+            for (_, a, b) in self.transitions:
+                assert (a, b) in LEGAL_EDGES, (a, b)
+            return
         allb = held + self.free
         assert len(allb) == self.n_blocks, "block leaked or duplicated"
         assert len(set(allb)) == self.n_blocks, "block id appears twice"

@@ -64,3 +64,21 @@ def make_workload(name, vocab, seed, n_requests=None, rate=None):
                          prompt=rng.integers(0, vocab, int(plen[i])).astype(np.int32),
                          max_new_tokens=int(olen[i]), seed=splitmix64(seed, i), **samp))
     return reqs
+
+
+def with_shared_prefixes(reqs, vocab, seed, n_prefixes=4, prefix_len=(16, 200), share=0.75):
+    """A copy of the request list in which a fraction `share` of the requests start with one of `n_prefixes` common
+    token sequences (system prompts or few-shot headers of a serving workload: the input of prefix caching), drawn
+    with lengths in prefix_len; the request's own prompt follows the prefix, cut so that the total keeps the drawn length
+    when that is longer than the prefix, and at least one own token remains."""
+    rng = np.random.default_rng(seed)
+    heads = [rng.integers(0, vocab, int(rng.integers(prefix_len[0], prefix_len[1] + 1))).astype(np.int32) for _ in range(n_prefixes)]
+    out = []
+    for r in reqs:
+        r = dict(r)
+        if rng.random() < share:
+            h = heads[int(rng.integers(0, n_prefixes))]
+            own = r["prompt"][: max(1, len(r["prompt"]) - len(h))]
+            r["prompt"] = np.concatenate([h, own]).astype(np.int32)
+        out.append(r)
+    return out

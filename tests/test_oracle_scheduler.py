@@ -375,3 +375,113 @@ def test_preempted_service_equals_per_request_generation():
     assert seen                                                   # somebody was preempted
     for t, r in enumerate(reqs):
         assert sched.outputs[t] == SV.generate_reference(cfg, W, r), t
+
+
+# ---- prefix caching --------------------------------------------------------------------------------------------------
+
+def test_prefix_hash_is_splitmix64_finalizer_and_chain():
+    """mix64 is the output function of splitmix64: with the generator's increment as input it gives the generator's
+    published first outputs for seed 0. The block hash is a polynomial in (token + 1) with the same increment as
+    multiplier, mixed once; the chain mixes the previous key xor the block hash."""
+    from oracle.scheduler import mix64, prefix_block_hash, prefix_chain, PREFIX_H0
+    g = 0x9E3779B97F4A7C15
+    assert mix64(g) == 0xE220A8397B1DCDAF and mix64(2 * g) == 0x6E789E6AA1B965F4 and mix64(3 * g) == 0x06C45D188009454F
+    assert prefix_block_hash([]) == mix64(0) == 0
+    assert prefix_block_hash([5]) == mix64(6)
+    assert prefix_block_hash([5, 9]) == mix64((6 * g + 10) % 2 ** 64)
+    assert prefix_chain(PREFIX_H0, [5, 9]) == mix64(PREFIX_H0 ^ prefix_block_hash([5, 9]))
+    assert prefix_block_hash([0, 1]) != prefix_block_hash([1, 0]) != prefix_block_hash([0, 1, 0])
+
+
+def _drive(s, n_visible, token=7):
+    plan = s.step(n_visible)
+    s.check_invariants()
+    if plan.kind != IDLE:
+        s.commit(plan, [token] * len(plan.sample_seq))
+    return plan
+
+
+def test_prefix_cache_hand_worked_sharing_idle_reuse_and_eviction():
+    """bs 4, 8 blocks, 2 batch slots. Worked by hand from the rules in the scheduler's header."""
+    s = Scheduler(8, 4, 2, 8192, 8, prefix_cache=True)
+    A = list(range(1, 11))                                  # 10 tokens, two full blocks
+    B = list(range(1, 9)) + [20, 21, 22]                    # shares A's two full blocks, but arrives in the same iteration
+    C = [1, 2, 3, 4, 30, 31, 32, 33, 34]                    # shares A's first block
+    for p, n in ((A, 2), (B, 1), (C, 2)):
+        s.submit(p, n)
+    p0 = _drive(s, 3)
+    assert (p0.kind, p0.tickets, p0.block_tables, p0.free_blocks_after) == (PREFILL, [0, 1], [[0, 1, 2], [3, 4, 5]], 2)
+    assert sorted(s.table.values()) == [0, 1] and s.pinned == 2 and s.committed == 1 + 3      # B's copies stay private
+    p1 = _drive(s, 3)                                       # B retired (3, 4, 5 back on top); C matches block 0
+    assert (p1.kind, p1.tickets, p1.batch_slots, p1.block_tables) == (PREFILL, [2], [1], [[0, 5, 4]])
+    assert p1.positions == [4, 5, 6, 7, 8] and p1.slot_mapping == [20, 21, 22, 23, 16] and p1.pos0 == [4] and p1.input_ids == C[4:]
+    assert p1.last_idx == [4] and p1.seq_lens == [9] and s.ref[0] == 2 and s.free == [7, 6, 3]
+    assert sorted(s.table.values()) == [0, 1, 5] and s.pinned == 3 and s.committed == 1 + 1 and s.cache_hits == 1
+    p2 = _drive(s, 3)
+    assert (p2.kind, p2.tickets, p2.slot_mapping) == (DECODE, [0, 2], [10, 17])
+    p3 = _drive(s, 3)                                       # both retire: private blocks on top, idle cached ones to the bottom
+    assert p3.kind == IDLE and s.free == [0, 5, 1, 7, 6, 3, 2, 4] and s.pinned == 0 and s.committed == 0 and len(s.table) == 3
+    D = list(range(1, 14))                                  # 13 tokens: matches A's two blocks, both idle
+    s.submit(D, 1)
+    p4 = _drive(s, 4)
+    assert (p4.kind, p4.tickets, p4.block_tables, p4.positions) == (PREFILL, [3], [[0, 1, 3, 6]], [8, 9, 10, 11, 12])
+    assert p4.slot_mapping == [12, 13, 14, 15, 24] and s.free == [4, 5, 2, 7] and s.pinned == 3 and s.committed == 1
+    p5 = _drive(s, 4)
+    assert p5.kind == IDLE and s.free == [0, 1, 3, 4, 5, 2, 7, 6] and len(s.table) == 4
+    s.submit(list(range(40, 60)), 1)                        # 20 fresh tokens: five blocks, the fourth pop evicts C's block 5
+    p6 = _drive(s, 5)
+    assert p6.block_tables == [[6, 7, 2, 5, 4]] and s.evictions == 1 and sorted(s.table.values()) == [0, 1, 2, 3, 4, 5, 6, 7]
+    assert s.free == [0, 1, 3]
+    # (all five blocks of the new prompt are full and were entered: every block is cached now, three of them idle)
+    s.submit(list(range(1, 6)), 1)                          # 5 tokens: matches block 0 (idle)
+    p7 = _drive(s, 6)
+    # the five blocks of the retired request went to the bottom in reverse table order: [6, 7, 2, 5, 4, 0, 1, 3]; the match
+    # takes block 0 out (the top, 3, fills its place) and the one new block is the top, 1: A's second block is evicted
+    assert p7.tickets == [5] and p7.block_tables == [[0, 1]] and s.evictions == 2 and s.free == [6, 7, 2, 5, 4, 3]
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3, 4])
+def test_prefix_cache_invariants_and_no_shared_prefix_reduces_to_plain(seed):
+    """Random load with shared prefixes behind a small pool: the invariants hold after every step, blocks are matched and
+    evicted, every request gets all its tokens. The same load with distinct prompts (no repeated block anywhere) makes
+    the same admissions, kinds and token counts as the plain scheduler: capacity accounting is unchanged when nothing is
+    shared (block ids differ: idle cached blocks go to the bottom of the queue)."""
+    rng = np.random.default_rng(seed)
+    base = synth.make_workload("mini", 50000, seed, n_requests=40)
+    shared = synth.with_shared_prefixes(base, 50000, seed + 10, n_prefixes=3, prefix_len=(16, 70), share=0.8)
+    eng = dict(kv_block_size=16, kv_num_blocks=40, max_batch=5, max_prefill_tokens=300, ring_slots=64, eos_token_id=-1)
+    tails = list(np.minimum(40, np.cumsum(rng.integers(0, 4, 400))))
+    s = Scheduler.from_engine(dict(eng, prefix_cache=True))
+    SV.run_schedule(s, shared, lambda pl: [1] * len(pl.sample_seq), tails=tails)
+    assert [len(s.outputs[t]) for t in range(40)] == [r["max_new_tokens"] for r in shared]
+    assert s.cache_hits > 10 and s.evictions > 0
+    s.step(40)
+    assert s.committed == 0 and s.pinned == 0 and sorted(s.free) == list(range(40))
+    pa, pb = [], []
+    a = Scheduler.from_engine(eng)
+    SV.run_schedule(a, base, lambda pl: [1] * len(pl.sample_seq), tails=tails, on_plan=pa.append)
+    b = Scheduler.from_engine(dict(eng, prefix_cache=True))
+    SV.run_schedule(b, base, lambda pl: [1] * len(pl.sample_seq), tails=tails, on_plan=pb.append)
+    assert b.cache_hits == 0 and len(pa) == len(pb)
+    for x, y in zip(pa, pb):
+        for f in ("kind", "tickets", "batch_slots", "input_ids", "positions", "tok_seq", "cu_seqlens", "last_idx", "gen_index", "admitted"):
+            assert getattr(x, f) == getattr(y, f), (x.iteration, f)
+
+
+def test_prefix_cached_service_equals_per_request_generation():
+    """The model side: a request whose prompt starts with cached blocks computes only the rest and attends to the shared
+    blocks; its stream is exactly what it generates alone. Blocks are matched while their first user is still running,
+    after it has retired (idle), and after evictions."""
+    cfg = dict(synth.model_config("tiny"), n_layers=2, vocab=97, d_model=64, n_q_heads=4, n_kv_heads=2, head_dim=16, d_ffn=96)
+    W = M.Weights(cfg, synth.make_weights(cfg, 7, gain_jitter=0.1))
+    base = [dict(r, max_new_tokens=min(r["max_new_tokens"], 6)) for r in synth.make_workload("mini", 97, 5, n_requests=14)]
+    reqs = synth.with_shared_prefixes(base, 97, 15, n_prefixes=2, prefix_len=(9, 40), share=0.8)
+    for i, r in enumerate(reqs):
+        if i % 3 == 0:
+            r.update(temperature=0.8, top_k=5, top_p=0.9, seed=synth.splitmix64(3, i))
+    eng = dict(kv_block_size=4, kv_num_blocks=60, max_batch=3, max_prefill_tokens=120, ring_slots=16, eos_token_id=-1, prefix_cache=True)
+    tails = [2, 2, 3, 5, 5, 5, 8, 8, 9, 14]
+    ev, sched = SV.serve(cfg, W, eng, reqs, tails=tails)
+    assert sched.cache_hits > 8 and sched.evictions > 0
+    for t, r in enumerate(reqs):
+        assert sched.outputs[t] == SV.generate_reference(cfg, W, r), t
