@@ -325,6 +325,50 @@ def chunked_leg(B, cfg, eng, blob, reqs, K, W, args):
                 **({"open_loop": ol} if ol else {}), **({"kernel_times_us": kernel_times} if kernel_times else {}))
 
 
+def prefix_leg(B, cfg, eng, blob, reqs, args):
+    """Prefix caching on a request set whose prompts start with common heads (system prompts): the whole set resident at
+    t = 0 and run to completion, once without and once with the cache. Reports the time to serve the set, the prompt
+    tokens computed, the blocks matched and evicted, and the scheduler's time per iteration (its table work is part of it)."""
+    vocab = cfg["vocab"]
+    lo, hi = [int(x) for x in args.prefix_len.split(",")]
+    shared = synth.with_shared_prefixes(reqs, vocab, 77, n_prefixes=args.prefix_heads, prefix_len=(lo, hi), share=args.prefix_share)
+    shared = [dict(r, prompt=r["prompt"][: eng["max_seq_len"] - r["max_new_tokens"]]) for r in shared]
+    out = dict(workload="the workload's requests, %d %% of them behind one of %d common heads of %d..%d tokens"
+                        % (round(100 * args.prefix_share), args.prefix_heads, lo, hi),
+               requests=len(shared), prompt_tokens=int(sum(len(r["prompt"]) for r in shared)))
+    for label, on in (("without_cache", False), ("with_cache", True)):
+        e = B.Engine(cfg, dict(eng, prefix_cache=on), blob, flags=B.FLAG_TRACE | B.FLAG_EXIT_WHEN_IDLE, trace_capacity=1 << 16, tune=args.tune)
+        try:
+            for r in shared:
+                e.submit_request(r)
+            t0 = time.perf_counter()
+            n_out = 0
+            while True:
+                e.run(64)
+                e.wait()
+                n_out += len(e.drain(1 << 16))
+                st = e.stats()
+                if st["n_running"] == 0 and st["next_ticket"] == len(shared):
+                    break
+            dt = time.perf_counter() - t0
+            tr = e.trace(1 << 16)
+        finally:
+            e.shutdown()
+        sched_us = (tr["t_sched_end_ns"].astype(np.int64) - tr["t_sched_begin_ns"].astype(np.int64)) / 1e3
+        pre = tr["kind"] == 1
+        out[label] = dict(seconds=round(dt, 2), output_tokens=n_out, output_tokens_per_s=round(n_out / dt, 1),
+                          iterations=int(st["iterations"]), prefill_iterations=int(st["prefill_iterations"]),
+                          prompt_tokens_computed=int(st["tokens_prefilled"]), blocks_matched=int(st["prefix_hit_blocks"]),
+                          blocks_evicted=int(st["prefix_evictions"]),
+                          sched_us=dict(median=round(float(np.median(sched_us)), 1), p99=round(float(np.percentile(sched_us, 99)), 1),
+                                        max=round(float(sched_us.max()), 1),
+                                        prefill_median=round(float(np.median(sched_us[pre])), 1) if pre.any() else None))
+    a, b = out["without_cache"], out["with_cache"]
+    out["speedup"] = round(a["seconds"] / b["seconds"], 3)
+    out["prompt_tokens_saved_frac"] = round(1.0 - b["prompt_tokens_computed"] / max(1, a["prompt_tokens_computed"]), 3)
+    return out
+
+
 def claim_latency(B, e, vocab, n=24):
     """An idle engine (its scheduler kernel polling the ring on the device) receives one short request at a time:
     time from the entry of blink_submit, and from its return, to the end of the scheduler step that admitted the request
@@ -400,6 +444,11 @@ def main():
     ap.add_argument("--no-chunked-leg", action="store_true", help="skip the second saturation run with chunked prefill")
     ap.add_argument("--chunk-budget", type=int, default=2048, help="tokens per iteration of the run with chunked prefill")
     ap.add_argument("--only-chunked-leg", action="store_true", help="tuning: skip everything else")
+    ap.add_argument("--prefix-leg", action="store_true", help="only this: the request set behind common prompt heads, served to "
+                    "completion without and with prefix caching (BLINK_FLAG_PREFIX_CACHE)")
+    ap.add_argument("--prefix-heads", type=int, default=8)
+    ap.add_argument("--prefix-len", default="256,1024", help="range of the common heads' lengths in tokens")
+    ap.add_argument("--prefix-share", type=float, default=0.8, help="fraction of the requests that start with a common head")
     ap.add_argument("--dump-iterations", default="",
                     help="write one line per iteration of the warm-up and the timed window (kind, sequences, tokens, context "
                          "tokens, timed flag): lets a rocprofv3 trace of the same run be split by iteration kind")
@@ -444,6 +493,9 @@ def main():
     blob = synth.pack_blob(cfg, raw)
     t_gen = time.perf_counter() - t_gen
 
+    if args.prefix_leg:
+        print(json.dumps(dict(prefix_cache=prefix_leg(B, cfg, eng, blob, reqs, args), config={"workload": args.workload, "requests": len(reqs)})))
+        return
     if args.only_chunked_leg:
         print(json.dumps(chunked_leg(B, cfg, eng, blob, reqs, K, W, args)))
         return

@@ -59,6 +59,13 @@ extern "C" {
                                         admission and lowest ticket first, by recomputing prompt + tokens generated so far.
                                         Not together with BLINK_FLAG_CHUNKED_PREFILL */
 
+#define BLINK_FLAG_PREFIX_CACHE 128u /* prefix caching (section 7: a hash table inside the scheduler maps token prefixes to KV blocks):
+                                        a new request whose prompt starts with full blocks of tokens that an earlier prompt
+                                        started with shares those blocks and computes only the rest. Keys are chained 64-bit
+                                        hashes of the prefix; cached blocks are reference-counted; unreferenced ones stay
+                                        in the table at the bottom of the free queue until their block is reused. Plain mode
+                                        only (not with CHUNKED_PREFILL or PREEMPTION) */
+
 /* slot life cycle of the ring (section 4.2, "Ring buffer") */
 enum {
   BLINK_SLOT_EMPTY = 0,
@@ -161,6 +168,10 @@ typedef struct {
   uint32_t running;            /* 1 while the loop is active */
   uint32_t windows;            /* blink_run calls so far */
   uint64_t kv_bytes, weight_bytes, ring_bytes;
+  uint64_t prefix_hit_blocks;  /* prefix caching: prompt blocks found in the table so far */
+  uint64_t prefix_evictions;   /* idle cached blocks whose memory was reused so far */
+  uint32_t pinned_blocks;      /* cached blocks held by running requests */
+  uint32_t pad1;
 } blink_stats;
 
 /* blink_debug_read selectors (tests only; call while the loop is stopped) */

@@ -6,7 +6,7 @@ import numpy as np
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 
-FLAG_TRACE, FLAG_EXIT_WHEN_IDLE, FLAG_KEEP_LOGITS, FLAG_NO_GRAPH, FLAG_CHUNKED_PREFILL, FLAG_PREEMPTION = 1, 2, 8, 16, 32, 64
+FLAG_TRACE, FLAG_EXIT_WHEN_IDLE, FLAG_KEEP_LOGITS, FLAG_NO_GRAPH, FLAG_CHUNKED_PREFILL, FLAG_PREEMPTION, FLAG_PREFIX_CACHE = 1, 2, 8, 16, 32, 64, 128
 ERR_INVAL, ERR_TOO_LARGE, ERR_FULL, ERR_DEVICE, ERR_STATE = -1, -2, -3, -4, -5
 EVENT_FIRST, EVENT_LAST = 1, 2
 
@@ -38,7 +38,8 @@ class Stats(C.Structure):
                 ("tokens_prefilled", C.c_uint64), ("next_ticket", C.c_uint64), ("n_running", C.c_uint32),
                 ("free_blocks", C.c_uint32), ("committed_blocks", C.c_uint32), ("device_error", C.c_uint32),
                 ("running", C.c_uint32), ("windows", C.c_uint32), ("kv_bytes", C.c_uint64), ("weight_bytes", C.c_uint64),
-                ("ring_bytes", C.c_uint64)]
+                ("ring_bytes", C.c_uint64), ("prefix_hit_blocks", C.c_uint64), ("prefix_evictions", C.c_uint64),
+                ("pinned_blocks", C.c_uint32), ("pad1", C.c_uint32)]
 
 
 EVENT_DTYPE = np.dtype([("request_id", "<u8"), ("index", "<u4"), ("token", "<i4"), ("flags", "<u4"), ("iteration", "<u4"),
@@ -144,6 +145,8 @@ class Engine:
             flags |= FLAG_CHUNKED_PREFILL
         if engine.get("preemption"):
             flags |= FLAG_PREEMPTION
+        if engine.get("prefix_cache"):
+            flags |= FLAG_PREFIX_CACHE
         cfg.device, cfg.flags, cfg.trace_capacity, cfg.idle_poll_us = device, flags, trace_capacity, idle_poll_us
         cfg.pump_depth, cfg.tune = pump_depth, tune
         cfg.n_experts, cfg.n_active = model.get("n_experts", 0), model.get("n_active", 0)

@@ -289,7 +289,22 @@ static int init_impl(const blink_config* cfg, blink_engine* e) {
   if (int rc = dalloc(e, &c.run, c.max_batch)) return rc;
   if (int rc = dalloc(e, &c.preq, c.max_batch)) return rc;
   if (int rc = dalloc(e, &c.block_tables, (u64)c.max_batch * c.max_blocks_per_seq)) return rc;
-  if (int rc = dalloc(e, &c.free_stack, c.n_blocks)) return rc;
+  {
+    u32 cap = 1;
+    while (cap < c.n_blocks) cap <<= 1;
+    c.fs_mask = cap - 1;
+    if (int rc = dalloc(e, &c.free_stack, cap)) return rc;
+    if (cfg->flags & BLINK_FLAG_PREFIX_CACHE) {
+      c.pc_bmask = 2 * cap - 1;
+      if (int rc = dalloc(e, &c.pc_ref, c.n_blocks)) return rc;
+      if (int rc = dalloc(e, &c.pc_key, c.n_blocks)) return rc;
+      if (int rc = dalloc(e, &c.pc_flags, c.n_blocks)) return rc;
+      if (int rc = dalloc(e, &c.pc_next, c.n_blocks)) return rc;
+      if (int rc = dalloc(e, &c.pc_pos, c.n_blocks)) return rc;
+      if (int rc = dalloc(e, &c.pc_bucket, 2ull * cap, false)) return rc;
+      HIPCHK(hipMemset(c.pc_bucket, 0xFF, 2ull * cap * 4));     // ~0u: empty chain
+    }
+  }
   if (int rc = dalloc(e, &c.meta, 1)) return rc;
   if (int rc = dalloc(e, &c.seq_bslot, c.max_batch)) return rc;
   if (int rc = dalloc(e, &c.seq_len, c.max_batch)) return rc;
@@ -546,6 +561,8 @@ extern "C" int blink_init(const blink_config* cfg, blink_engine** out) {
   if (!cfg->max_seq_len || !cfg->max_prefill_tokens) return fail(BLINK_ERR_INVAL, "max_seq_len and max_prefill_tokens must be positive");
   if ((cfg->flags & BLINK_FLAG_CHUNKED_PREFILL) && (cfg->flags & BLINK_FLAG_PREEMPTION))
     return fail(BLINK_ERR_INVAL, "preemption is built for the plain (pause-and-resume) mode, not together with chunked prefill");
+  if ((cfg->flags & BLINK_FLAG_PREFIX_CACHE) && (cfg->flags & (BLINK_FLAG_CHUNKED_PREFILL | BLINK_FLAG_PREEMPTION)))
+    return fail(BLINK_ERR_INVAL, "prefix caching is built for the plain mode, not together with chunked prefill or preemption");
   if ((cfg->flags & BLINK_FLAG_CHUNKED_PREFILL) && cfg->max_prefill_tokens <= cfg->max_batch)
     return fail(BLINK_ERR_INVAL, "chunked prefill: max_prefill_tokens (the token budget of an iteration) must exceed max_batch");
   if (!cfg->ring_slots || (cfg->ring_slots & (cfg->ring_slots - 1))) return fail(BLINK_ERR_INVAL, "ring_slots must be a power of two");
@@ -887,7 +904,8 @@ extern "C" int blink_get_stats(blink_engine* e, blink_stats* out) {
   HIPCHK(hipMemcpy(&s, e->ctx.ss, sizeof s, hipMemcpyDeviceToHost));
   out->iterations = s.iteration; out->prefill_iterations = s.prefill_iterations; out->tokens_out = s.tokens_out;
   out->tokens_prefilled = s.tokens_prefilled; out->next_ticket = s.next_ticket; out->n_running = s.n_running;
-  out->free_blocks = s.free_top; out->committed_blocks = s.committed; out->device_error = s.error;
+  out->free_blocks = s.free_top - s.free_lo; out->committed_blocks = s.committed; out->device_error = s.error;
+  out->prefix_hit_blocks = s.cache_hits; out->prefix_evictions = s.evictions; out->pinned_blocks = s.pinned; out->pad1 = 0;
   return BLINK_OK;
 }
 
@@ -906,10 +924,13 @@ extern "C" int blink_debug_read(blink_engine* e, uint32_t what, void* buf, uint6
   switch (what) {
     case BLINK_DBG_LOGITS: src = c.logits; n = (u64)m.n_samples * c.V * 4; break;
     case BLINK_DBG_FREE_STACK: {
-      n = 4 + (u64)s.free_top * 4;
+      const u32 count = s.free_top - s.free_lo;
+      n = 4 + (u64)count * 4;
       if (n > cap_bytes) return fail(BLINK_ERR_INVAL, "buffer too small: need %llu bytes", (unsigned long long)n);
-      memcpy(buf, &s.free_top, 4);
-      HIPCHK(hipMemcpy((char*)buf + 4, c.free_stack, (u64)s.free_top * 4, hipMemcpyDeviceToHost));
+      memcpy(buf, &count, 4);
+      std::vector<u32> ring((u64)c.fs_mask + 1);
+      HIPCHK(hipMemcpy(ring.data(), c.free_stack, ring.size() * 4, hipMemcpyDeviceToHost));
+      for (u32 i = 0; i < count; ++i) ((u32*)buf)[1 + i] = ring[(s.free_lo + i) & c.fs_mask];
       *n_bytes = n;
       return BLINK_OK;
     }

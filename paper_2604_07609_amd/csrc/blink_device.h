@@ -59,9 +59,11 @@ struct RunEntry {     // one batch slot
   u32 in_iter;        // 1 when admitted in the current iteration
   u32 paused;         // 1 while its slot state is DECODE_PAUSED
   u32 prefilled;      // prompt tokens whose K/V are in the cache (== P once the request decodes)
-  u32 chunk;          // chunked prefill: prompt tokens the admitting iteration processes
-  u32 pad;
+  u32 chunk;          // tokens the admitting (or resuming) iteration processes: the prompt, its first chunk (chunked prefill), the
+                      // part of it behind the cached prefix (prefix caching), or prompt + outputs so far (a resumed request)
+  u32 n_matched;      // prefix caching: leading blocks of the block table that were found in the table
   u64 seed;
+  u64 h_end;          // prefix caching: key of the last matched block (the chain continues from it)
 };
 
 struct SchedState {
@@ -79,8 +81,13 @@ struct SchedState {
   u32 pad;
   u64 iter_limit;       // the window ends once `iteration` reaches this (0: no limit); set at blink_run
   u32 n_preempted;      // preempted requests waiting to be resumed (entries of DevCtx::preq)
-  u32 pad2;
+  u32 free_lo;          // prefix caching: the free list is a double-ended queue, free_lo .. free_top (free-running counters,
+                        // reduced modulo the queue's capacity); otherwise 0 and free_top is the number of free blocks
   u64 chains;           // scheduler kernels run so far (iterations, idle polls and launches past the end of a window)
+  u32 pinned;           // prefix caching: cached blocks that running requests hold
+  u32 pad3;
+  u64 cache_hits;       // blocks matched so far
+  u64 evictions;        // idle cached blocks reused so far
 };
 
 // batch metadata of the current iteration (what the scheduler populates before the forward pass)
@@ -164,7 +171,17 @@ struct DevCtx {
   RunEntry* run;
   RunEntry* preq;       // [max_batch] preemption mode: the preempted requests (no blocks, no batch slot), unordered
   u32* block_tables;    // [max_batch][max_blocks_per_seq]
-  u32* free_stack;      // [n_blocks]
+  u32* free_stack;      // [fs_mask + 1 >= n_blocks] (a ring when prefix caching pushes at its bottom)
+  u32 fs_mask;
+  // prefix caching: per block, reference count, key, flags (PC_CACHED: in the table; PC_LINKED: a node of a bucket's chain,
+  // possibly stale), next node of the chain, position in the free queue while idle; the heads of the buckets' chains
+  u32* pc_ref;
+  u64* pc_key;
+  u32* pc_flags;
+  u32* pc_next;
+  u32* pc_pos;
+  u32* pc_bucket;
+  u32 pc_bmask;
   IterMeta* meta;
   u32* seq_bslot;       // [max_batch]
   u32* seq_len;         // [max_batch]

@@ -7,6 +7,14 @@
 // the free stack by prefix-sum offsets (deterministic block ids), and build the batch metadata.
 // With nothing running and nothing pending it keeps polling the ring on the device for a bounded time.
 // Integer work only; all decisions are functions of device state, never of the host.
+//
+// Prefix caching (flag 128; the paper's section 7 names a hash table inside the scheduler that maps token prefixes to
+// blocks): full blocks of prompt tokens are entered into a table under a chained 64-bit hash of the whole prefix. A new
+// request walks its prompt's keys until the first miss; the blocks found head its block table and its prefill starts
+// behind them. Cached blocks carry reference counts; a block whose count drops to zero stays in the table and goes to
+// the BOTTOM of the free list (a double-ended queue then), so private blocks are reused first and idle cached blocks
+// oldest first; a pop of an idle cached block evicts it. The table is a set of chains through the blocks
+// (pc_bucket / pc_next); an evicted block's node stays in its chain, marked stale, until the block is entered again.
 #pragma once
 #include "blink_device.h"
 
@@ -23,6 +31,11 @@
 
 #define SCHED_MAX_BATCH 1024
 
+#define PC_CACHED 1u
+#define PC_LINKED 2u
+#define PC_H0 0x243F6A8885A308D3ull
+#define FS(i) c.free_stack[(i) & c.fs_mask]
+
 struct SchedShared {
   u32 wave_part[8];
   u32 wave_part2[8];
@@ -36,7 +49,56 @@ struct SchedShared {
   u32 exit_idle;
   u64 chain;
   u64 part64[8];
+  u64 pc_g[BLK_THREADS];             // prefix caching: hashes of a strip of blocks
 };
+
+// The output function of splitmix64, and the hash of one block of 16 token ids: a polynomial in (id + 1) modulo 2^64 with
+// that generator's increment as multiplier, mixed once.
+__device__ __forceinline__ u64 pc_mix64(u64 z) {
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+__device__ __forceinline__ u64 pc_block_hash(const i32* toks) {
+  u64 a = 0;
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+    a = a * 0x9E3779B97F4A7C15ull + (u64)(u32)__hip_atomic_load(toks + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) + 1ull;
+  return pc_mix64(a);
+}
+// the cached block with key h, or ~0u (stale nodes of evicted blocks are passed over; the walk is bounded)
+__device__ __forceinline__ u32 pc_lookup(const DevCtx& c, u64 h) {
+  u32 n = c.pc_bucket[(u32)h & c.pc_bmask];
+  for (u32 steps = 0; n != ~0u && steps < c.n_blocks; ++steps) {
+    if ((c.pc_flags[n] & PC_CACHED) && c.pc_key[n] == h) return n;
+    n = c.pc_next[n];
+  }
+  return ~0u;
+}
+// Enters block blk under key h (one thread). A stale node of the block is taken out of its old chain first. Returns
+// false, and leaves the block private, when the key is in the table already.
+__device__ __forceinline__ bool pc_insert(const DevCtx& c, u32 blk, u64 h) {
+  if (c.pc_flags[blk] & PC_LINKED) {
+    const u32 ob = (u32)c.pc_key[blk] & c.pc_bmask;
+    u32 n = c.pc_bucket[ob];
+    if (n == blk) c.pc_bucket[ob] = c.pc_next[blk];
+    else {
+      u32 steps = 0;
+      while (n != ~0u && c.pc_next[n] != blk && steps < c.n_blocks) { n = c.pc_next[n]; ++steps; }
+      if (n != ~0u && c.pc_next[n] == blk) c.pc_next[n] = c.pc_next[blk];
+      else c.ss->error = 4;            // cannot happen: a linked block is in the chain of its key
+    }
+    c.pc_flags[blk] = 0;
+  }
+  if (pc_lookup(c, h) != ~0u) return false;
+  const u32 bi = (u32)h & c.pc_bmask;
+  c.pc_next[blk] = c.pc_bucket[bi];
+  c.pc_bucket[bi] = blk;
+  c.pc_key[blk] = h;
+  c.pc_flags[blk] = PC_CACHED | PC_LINKED;
+  c.pc_ref[blk] = 1;
+  return true;
+}
 
 // Exclusive prefix sum over the 256 threads of the workgroup; total returned in `total`.
 __device__ __forceinline__ u32 block_excl_scan(u32 v, u32& total, u32* part) {
@@ -161,9 +223,67 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
   u32 top = ss->free_top, committed = ss->committed, nrun = ss->n_running;
   const u64 next0 = ss->next_ticket;
   const u32 mbs = c.max_blocks_per_seq;
+  const bool pcache = (c.flags & 128u) != 0;
+  u32 lo = ss->free_lo, pinned = ss->pinned, hits = 0;
   __syncthreads();
 
   // ---- (1) retire, batch slot ascending; blocks go back in block-table order ------------------------------
+  if (pcache) {
+    // prefix caching: the finished requests one at a time (their shared blocks' counts and the order at the bottom of the
+    // queue depend on it), the threads over a request's blocks. A private block goes on top; a cached block loses a
+    // reference, and one whose count reaches zero goes to the bottom, the request's idle blocks in table order upwards.
+    u32 n_fin = 0;
+    for (u32 base = 0; base < c.max_batch; base += BLK_THREADS) {
+      const u32 b = base + tid;
+      const bool fin = b < c.max_batch && c.run[b].valid && c.run[b].finished;
+      u32 tot;
+      const u32 off = block_excl_scan(fin ? 1u : 0u, tot, sh.wave_part);
+      if (fin) sh.seq_bslot[n_fin + off] = b;
+      n_fin += tot;
+    }
+    __syncthreads();
+    for (u32 i = 0; i < n_fin; ++i) {
+      const u32 b = sh.seq_bslot[i], nb = c.run[b].n_blocks, resv = c.run[b].reserved;
+      const u32* bt = c.block_tables + (u64)b * mbs;
+      u32 n_idle = 0;
+      for (u32 jb = 0; jb < nb; jb += BLK_THREADS) {
+        const u32 j = jb + tid;
+        const bool v = j < nb;
+        const u32 blk = v ? bt[j] : 0u;
+        const bool cached = v && (c.pc_flags[blk] & PC_CACHED);
+        bool idle = false;
+        if (cached) {
+          const u32 left = c.pc_ref[blk] - 1;
+          c.pc_ref[blk] = left;
+          idle = left == 0;
+        }
+        u32 totp, toti;
+        const u32 offp = block_excl_scan((v && !cached) ? 1u : 0u, totp, sh.wave_part);
+        const u32 offi = block_excl_scan(idle ? 1u : 0u, toti, sh.wave_part2);
+        if (v && !cached) FS(top + offp) = blk;
+        if (idle) c.pc_pos[blk] = n_idle + offi;         // its rank among the request's idle blocks, for the second pass
+        top += totp;
+        n_idle += toti;
+      }
+      __syncthreads();
+      // a cached block of this request's table with no reference left is one this request has just brought to zero (it
+      // held a reference until now): its pc_pos holds its rank among them
+      for (u32 j = tid; j < nb; j += BLK_THREADS) {
+        const u32 blk = bt[j];
+        if ((c.pc_flags[blk] & PC_CACHED) && c.pc_ref[blk] == 0) {
+          const u32 p = lo - n_idle + c.pc_pos[blk];
+          FS(p) = blk;
+          c.pc_pos[blk] = p;
+        }
+      }
+      if (tid == 0) c.run[b].valid = 0;
+      lo -= n_idle;
+      pinned -= n_idle;
+      committed -= resv;
+      nrun -= 1;
+      __syncthreads();
+    }
+  } else
   for (u32 base = 0; base < c.max_batch; base += BLK_THREADS) {
     const u32 b = base + tid;
     const bool fin = b < c.max_batch && c.run[b].valid && c.run[b].finished;
@@ -172,7 +292,7 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
     const u32 off = block_excl_scan(nb, tot, sh.wave_part);
     block_excl_scan(fin ? c.run[b].reserved : 0u, tot_resv, sh.wave_part2);
     block_excl_scan(fin ? 1u : 0u, tot_fin, sh.wave_part);
-    for (u32 j = 0; j < nb; ++j) c.free_stack[top + off + j] = c.block_tables[(u64)b * mbs + j];
+    for (u32 j = 0; j < nb; ++j) FS(top + off + j) = c.block_tables[(u64)b * mbs + j];
     if (fin) c.run[b].valid = 0;
     top += tot;
     committed -= tot_resv;
@@ -255,7 +375,7 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
   }
 
   // ---- (2) poll the ring + (3) admit FCFS, 256 candidate tickets at a time ----------------------------------
-  u32 admitted = 0;
+  u32 admitted = 0, charged_idle = 0;
   u64 tail = next0;
   u64 first_admitted = 0;
   for (;;) {
@@ -278,18 +398,41 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
       P = __hip_atomic_load(&c.desc[slot].n_prompt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
       max_new = __hip_atomic_load(&c.desc[slot].max_new, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
+    const u32 ord = resumed + admitted + tid;                              // admission order within the iteration
     u32 need = 0;
     if (cand) {
       need = preempt ? (P + c.bs - 1) / c.bs : (P + max_new - 1 + c.bs - 1) / c.bs;   // blocks of the prompt now, or the worst-case reservation
       if (need == 0) need = 1;
     }
-    u32 totn, totp;
-    const u32 sn = block_excl_scan(need, totn, sh.wave_part) + need;     // inclusive
-    const u32 sp = block_excl_scan(cand ? P : 0u, totp, sh.wave_part2) + (cand ? P : 0u);
-    const u32 ord = resumed + admitted + tid;                              // admission order within the iteration
+    // prefix caching: the candidate walks the keys of its prompt's leading blocks (never the block of the last prompt token)
+    // until the first miss; the blocks found go straight into the block table of the batch slot it would take. The table
+    // and the reference counts do not change before every admission of the iteration is decided.
+    u32 n_match = 0, n_idle_match = 0;
+    u64 h_end = PC_H0;
+    if (pcache && cand && ord < n_free) {
+      u32* bt = c.block_tables + (u64)sh.free_list[ord] * mbs;
+      const i32* toks = c.in_arena + (u64)slot * c.max_seq_len;
+      for (u32 j = 0; j < (P - 1) / c.bs; ++j) {
+        const u64 hj = pc_mix64(h_end ^ pc_block_hash(toks + (u64)j * 16));
+        const u32 blk = pc_lookup(c, hj);
+        if (blk == ~0u) break;
+        bt[j] = blk;
+        n_idle_match += c.pc_ref[blk] == 0 ? 1u : 0u;
+        h_end = hj;
+        ++n_match;
+      }
+      need -= n_match;                  // its private reservation: the matched blocks are the table's
+    }
+    const u32 charge = need + n_idle_match;          // a matched block that is idle now becomes a block in use
+    const u32 P_new = cand ? P - n_match * c.bs : 0u;  // tokens it computes
+    u32 totn, totp, totr;
+    const u32 sn = block_excl_scan(charge, totn, sh.wave_part) + charge;     // inclusive
+    const u32 sp = block_excl_scan(P_new, totp, sh.wave_part2) + P_new;
+    const u32 sr = pcache ? block_excl_scan(need, totr, sh.wave_part) + need : sn;
     // tokens of the budget already spoken for when this candidate's turn comes (chunked mode)
-    const u64 before = (u64)used + tokens_admitted + (sp - (cand ? P : 0u));
-    const bool ok = cand && ord < n_free && (preempt ? (u64)promised + sn <= (u64)top : (u64)committed + sn <= (u64)c.n_blocks) &&
+    const u64 before = (u64)used + tokens_admitted + (sp - P_new);
+    const bool ok = cand && ord < n_free &&
+                    (preempt ? (u64)promised + sn <= (u64)top : (u64)committed + pinned + charged_idle + sn <= (u64)c.n_blocks) &&
                     (chunked ? before < (u64)budget : (ord == 0 || (u64)tokens_admitted + sp <= (u64)c.max_prefill_tokens));
     const u32 adm = block_prefix_count(ok, sh.wave_part);
     if (tid < adm) {
@@ -303,7 +446,9 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
       r.gen = 0;
       r.ctx_len = 0;
       r.reserved = preempt ? 0u : need;
-      r.n_blocks = 0;
+      r.n_blocks = n_match;
+      r.n_matched = n_match;
+      r.h_end = h_end;
       r.finished = 0;
       r.last_token = -1;
       r.temperature = c.desc[slot].temperature;
@@ -313,7 +458,7 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
       r.in_iter = 1;
       r.paused = 0;
       r.prefilled = chunked ? 0u : P;       // without chunking the whole prompt is processed in this iteration
-      r.chunk = chunked ? (u32)min((u64)P, (u64)budget - before) : P;
+      r.chunk = chunked ? (u32)min((u64)P, (u64)budget - before) : P_new;
       // claim by compare-and-swap (section 4.2 "Ring buffer")
       u32 expect = SLOT_PREFILL_PENDING;
       if (!__hip_atomic_compare_exchange_strong(&c.status[slot].state, &expect, SLOT_PREFILL_PROCESSING, __ATOMIC_ACQ_REL,
@@ -325,10 +470,15 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
     if (adm > 0 && tid == adm - 1) {
       sh.wave_part2[0] = sn;
       sh.wave_part2[1] = sp;
+      sh.wave_part2[2] = sr;
     }
     __syncthreads();
     if (adm > 0) {
-      if (preempt) promised += sh.wave_part2[0]; else committed += sh.wave_part2[0];
+      if (preempt) promised += sh.wave_part2[0];
+      else {
+        committed += sh.wave_part2[2];                            // the private reservations
+        charged_idle += sh.wave_part2[0] - sh.wave_part2[2];      // idle blocks the admitted take into use (counted per candidate)
+      }
       tokens_admitted += sh.wave_part2[1];
       if (admitted == 0) first_admitted = next0;
     }
@@ -337,6 +487,45 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
     if (adm < BLK_THREADS) break;   // stopped inside this chunk (nothing pending, or a limit was hit)
   }
   nrun += admitted + resumed;
+
+  // ---- prefix caching: the admitted requests take their matched blocks, in admission order. The threads raise the counts
+  // of one request's blocks; a block that was idle leaves the free queue, the queue's top element taking its place (one
+  // thread, in block-table order: the arrangement of the queue depends on the order) -------------------------------
+  if (pcache) {
+    for (u32 i = 0; i < admitted; ++i) {
+      const u32 b = sh.free_list[i], m = c.run[b].n_matched;
+      const u32* bt = c.block_tables + (u64)b * mbs;
+      for (u32 jb = 0; jb < m; jb += BLK_THREADS) {
+        const u32 j = jb + tid;
+        const bool v = j < m;
+        const u32 blk = v ? bt[j] : 0u;
+        bool was_idle = false;
+        if (v) {
+          const u32 r0 = c.pc_ref[blk];
+          c.pc_ref[blk] = r0 + 1;
+          was_idle = r0 == 0;
+        }
+        u32 tot;
+        const u32 off = block_excl_scan(was_idle ? 1u : 0u, tot, sh.wave_part);
+        if (was_idle) sh.seq_tok0[off] = blk;
+        __syncthreads();
+        if (tid == 0) {
+          u32 t = top;
+          for (u32 q = 0; q < tot; ++q) {
+            const u32 p = c.pc_pos[sh.seq_tok0[q]];
+            --t;
+            const u32 moved = FS(t);
+            FS(p) = moved;
+            if (c.pc_flags[moved] & PC_CACHED) c.pc_pos[moved] = p;
+          }
+        }
+        top -= tot;
+        pinned += tot;
+        __syncthreads();
+      }
+      hits += m;
+    }
+  }
 
   // ---- (4) kind: an iteration with prompt tokens in it counts as a prefill iteration ---------------------------
   const u32 kind = (admitted + resumed > 0 || chunk_part > 0) ? KIND_PREFILL : (nrun > 0 ? KIND_DECODE : KIND_IDLE);
@@ -365,7 +554,7 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
       const u32 b = (u32)(key & 0xFFFu);
       const RunEntry v = c.run[b];
       __syncthreads();
-      for (u32 j = tid; j < v.n_blocks; j += BLK_THREADS) c.free_stack[top + j] = c.block_tables[(u64)b * mbs + j];
+      for (u32 j = tid; j < v.n_blocks; j += BLK_THREADS) FS(top + j) = c.block_tables[(u64)b * mbs + j];
       if (tid == 0) {
         RunEntry& q = c.preq[n_pre];
         q = v;
@@ -408,7 +597,8 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
           smp = !pref || r.prefilled + ntok == r.P;
         } else if (kind == KIND_PREFILL) {
           in = pref = smp = r.in_iter != 0;
-          ntok = r.P + r.gen;                 // (gen > 0: a preempted request recomputes its prompt and its own outputs)
+          ntok = r.chunk;                     // the prompt; behind a cached prefix, its rest; a resumed request's prompt and outputs
+          pos0 = r.P + r.gen - r.chunk;
           if (!in && !r.paused) {
             set_slot_state(&c.status[r.ring_slot], SLOT_DECODE_PAUSED);   // running decodes wait for the prefill
             r.paused = 1;
@@ -436,7 +626,14 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
       if (in) {
         RunEntry& r = c.run[b];
         u32* bt = c.block_tables + (u64)b * mbs;
-        for (u32 j = 0; j < nalloc; ++j) bt[nb + j] = c.free_stack[top - 1 - (aoff + j)];
+        for (u32 j = 0; j < nalloc; ++j) {
+          const u32 blk = FS(top - 1 - (aoff + j));
+          bt[nb + j] = blk;
+          if (pcache && (c.pc_flags[blk] & PC_CACHED)) {      // an idle cached block is reused: out of the table (its node goes stale)
+            c.pc_flags[blk] = PC_LINKED;
+            atomicAdd((unsigned long long*)&ss->evictions, 1ull);
+          }
+        }
         r.n_blocks = nb + nalloc;
         c.seq_bslot[si] = b;
         c.cu_seqlens[si] = toff;
@@ -532,10 +729,46 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
   }
   __syncthreads();
 
+  // ---- prefix caching: the admitted requests enter their own full prompt blocks behind the matched ones into the table,
+  // batch slot ascending (a key that is there already, from an earlier request of this very iteration too, leaves the
+  // block private). The threads hash a strip of blocks; one thread chains the keys and links the blocks ------------
+  if (pcache && kind == KIND_PREFILL) {
+    for (u32 s = 0; s < n_seqs; ++s) {
+      const u32 b = c.seq_bslot[s];
+      const u32 m = c.run[b].n_matched, nfull = c.run[b].P / c.bs;
+      const i32* toks = c.in_arena + (u64)c.run[b].ring_slot * c.max_seq_len;
+      const u32* bt = c.block_tables + (u64)b * mbs;
+      u64 h = c.run[b].h_end;
+      for (u32 jb = m; jb < nfull; jb += BLK_THREADS) {
+        const u32 cnt = min((u32)BLK_THREADS, nfull - jb);
+        if (tid < cnt) sh.pc_g[tid] = pc_block_hash(toks + (u64)(jb + tid) * 16);
+        __syncthreads();
+        if (tid == 0) {
+          u32 n_ins = 0;
+          for (u32 q = 0; q < cnt; ++q) {
+            h = pc_mix64(h ^ sh.pc_g[q]);
+            if (pc_insert(c, bt[jb + q], h)) ++n_ins;
+          }
+          c.run[b].reserved -= n_ins;
+          sh.wave_part[0] = n_ins;
+          sh.part64[0] = h;
+        }
+        __syncthreads();
+        committed -= sh.wave_part[0];
+        pinned += sh.wave_part[0];
+        h = sh.part64[0];
+        __syncthreads();
+      }
+    }
+  }
+
   // ---- write back ------------------------------------------------------------------------------------------
   if (tid == 0) {
     const u64 now = dev_now_ns();
     ss->free_top = top;
+    ss->free_lo = lo;
+    ss->pinned = pinned;
+    ss->cache_hits += hits;
     ss->committed = committed;
     ss->n_running = nrun;
     ss->next_ticket = next0 + admitted;
@@ -570,7 +803,7 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
         tr.n_admitted = admitted;
         tr.n_seqs = n_seqs;
         tr.n_tokens = n_tok;
-        tr.free_blocks = top;
+        tr.free_blocks = top - lo;
         tr.first_admitted = first_admitted;
         tr.t_sched_begin = t_begin;
         tr.t_sched_end = now;

@@ -234,6 +234,10 @@ def stepwise_check(B, cfg, eng, raw, blob, reqs, rtol, max_iters=10000, tune=0, 
             e.wait()
             plan = sched.step(len(reqs))
             sched.check_invariants()
+            if eng.get("prefix_cache"):
+                st = e.stats()
+                assert (st["prefix_hit_blocks"], st["prefix_evictions"], st["pinned_blocks"], st["committed_blocks"]) == \
+                    (sched.cache_hits, sched.evictions, sched.pinned, sched.committed), (it, st)
             if plan.kind == 0:
                 assert e.stats()["iterations"] == it
                 assert moe_stats["unclear"] <= 0.08 * moe_stats["pairs"], moe_stats
