@@ -240,7 +240,8 @@ int blink_debug_read(blink_engine* e, uint32_t what, void* buf, uint64_t cap_byt
  * 8 down GEMM; 9 final norm, 10 LM head, 11 sample + publish; bf16 models also 12 merge of the decode attention's
  * chunks, 13 / 14 / 15 second kernel of the QKV / output / down GEMM when K is split across workgroups; a
  * mixture-of-experts model runs, in place of 7 and 8: 16 router GEMM, 17 expert selection, 18 grouped gate/up GEMMs,
- * 19 grouped down GEMMs, 20 weighted sum + residual; -1 none). A
+ * 19 grouped down GEMMs, 20 weighted sum + residual, and 21 (between 17 and 18) the experts' operand gathered by
+ * expert; -1 none). A
  * bf16 model has no kernels for phases 1, 3, 6 and 9 (fused into the GEMMs). While a phase is selected, the loop
  * brackets every launch of that phase's kernel with HIP events on the compute stream. After the loop has
  * stopped, blink_get_phase_times returns, per iteration enqueued in the last window and in enqueue order, the

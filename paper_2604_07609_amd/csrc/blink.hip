@@ -58,6 +58,7 @@ PHASE_KERNEL(k_moe_route, PH_ROUTE)
 PHASE_KERNEL(k_moe_gateup, PH_MOE_GATEUP)
 PHASE_KERNEL(k_moe_down, PH_MOE_DOWN)
 PHASE_KERNEL(k_moe_combine, PH_MOE_COMBINE)
+PHASE_KERNEL(k_moe_permute, PH_MOE_PERMUTE)
 
 typedef void (*phase_kernel_t)(DevCtx, u32);
 static phase_kernel_t phase_kernel(int ph) {
@@ -82,6 +83,7 @@ static phase_kernel_t phase_kernel(int ph) {
     case PH_MOE_GATEUP: return k_moe_gateup;
     case PH_MOE_DOWN: return k_moe_down;
     case PH_MOE_COMBINE: return k_moe_combine;
+    case PH_MOE_PERMUTE: return k_moe_permute;
     default: return k_sample_publish;
   }
 }
@@ -471,6 +473,7 @@ static int init_impl(const blink_config* cfg, blink_engine* e) {
       const u64 cols = (u64)c.maxT * c.n_active + 16ull * c.n_experts + 256 + 16;
       c.moe_TBS = (u32)((cols + 15) / 16);
       if (int rc = dalloc(e, &c.hq_moe, (u64)c.moe_TBS * 16 * c.F)) return rc;
+      if (int rc = dalloc(e, &c.xq_moe, (u64)c.moe_TBS * 16 * c.d)) return rc;
       if (int rc = dalloc(e, &c.y_moe, (u64)c.moe_TBS * 16 * c.d, false)) return rc;
       if (int rc = dalloc(e, &c.moe_logits, (u64)c.maxT * c.n_experts, false)) return rc;
       if (int rc = dalloc(e, &c.moe_count, c.n_experts)) return rc;
@@ -645,7 +648,8 @@ static int launch_phase(blink_engine* e, const DevCtx& ctx, hipStream_t st, int 
     b = e->phase_ev[2 * slot + 1];
     HIPCHK(hipEventRecord(a, st));
   }
-  const bool wide = ph == PH_ATTN || ph == PH_QKV || ph == PH_OPROJ || ph == PH_DOWN;
+  // (bit 31 of the tuning word: the narrow projections run four waves per workgroup like the other GEMMs)
+  const bool wide = ph == PH_ATTN || ((ph == PH_QKV || ph == PH_OPROJ || ph == PH_DOWN) && !(e->cfg.tune & 0x80000000u));
   const u32 threads = (wide && e->ctx.dtype == 1) ? 512u : (u32)BLK_THREADS;
   hipLaunchKernelGGL(phase_kernel(ph), dim3(e->grid), dim3(threads), 0, st, ctx, layer);
   if (timed) HIPCHK(hipEventRecord(b, st));
@@ -664,9 +668,10 @@ static int enqueue_iteration_kernels(blink_engine* e, hipStream_t st, u64 enq_in
   if (int rc = launch_phase(e, c, st, PH_EMBED, 0, enq_index)) return rc;
   for (u32 l = 0; l < c.n_layers; ++l)
     for (int ph = PH_LAYER_FIRST; ph <= PH_LAYER_LAST; ++ph) {
-      if (c.n_experts && (ph == PH_GATEUP || ph == PH_DOWN)) {    // mixture of experts: five kernels in place of the two
+      if (c.n_experts && (ph == PH_GATEUP || ph == PH_DOWN)) {    // mixture of experts: six kernels in place of the two
         if (ph == PH_DOWN) continue;
-        for (int mp = PH_ROUTER; mp <= PH_MOE_COMBINE; ++mp)
+        static const int moe_chain[] = {PH_ROUTER, PH_ROUTE, PH_MOE_PERMUTE, PH_MOE_GATEUP, PH_MOE_DOWN, PH_MOE_COMBINE};
+        for (int mp : moe_chain)
           if (int rc = launch_phase(e, c, st, mp, l, enq_index)) return rc;
         continue;
       }
@@ -973,7 +978,7 @@ extern "C" int blink_time_phase(blink_engine* e, int32_t phase) {
   g_err.clear();
   if (!e) return fail(BLINK_ERR_INVAL, "null engine");
   if (e->loop_active.load()) return fail(BLINK_ERR_STATE, "stop the loop first");
-  if (phase < -1 || phase > PH_MOE_COMBINE) return fail(BLINK_ERR_INVAL, "phase out of range");
+  if (phase < -1 || phase > PH_MOE_PERMUTE) return fail(BLINK_ERR_INVAL, "phase out of range");
   e->timed_phase = phase;
   return BLINK_OK;
 }

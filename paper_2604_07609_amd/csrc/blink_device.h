@@ -232,7 +232,8 @@ struct DevCtx {
   u32* moe_sel;         // [n_layers][maxT * n_active] selected expert of every (token, slot), kept per layer for tests
   u32* moe_pos;         // [maxT * n_active] place of the pair in its expert's list
   float* moe_w;         // [maxT * n_active] softmax weight of the pair
-  float* moe_rstd;      // [maxT] norm scale of the token's FFN input (times the inverse of the weight scale)
+  float* moe_rstd;      // [maxT] norm scale of the token's FFN input
+  f16_t* xq_moe;        // packed normalised FFN input of all pairs, columns grouped by expert, inner dimension d
   f16_t* hq_moe;        // packed silu(gate)*up of all pairs, columns grouped by expert (groups padded to 16), inner dimension F
   float* y_moe;         // [columns][d] expert outputs of all pairs
   u32 moe_TBS;          // token-block stride of hq_moe

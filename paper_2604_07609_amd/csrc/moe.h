@@ -1,7 +1,8 @@
 // Mixture-of-experts FFN of a bf16 model (the second workload of the paper's evaluation, section 6, is such a model):
 // router GEMM -> per-token selection of the n_active largest router logits (ties to the lower expert id) and softmax over
-// them -> one list of tokens per expert -> grouped gate/up and down GEMMs, every expert's tokens as one GEMM of the
-// existing schedules -> weighted sum of a token's expert outputs in selection order + residual + next norm's operand.
+// them -> one list of tokens per expert -> the normalised inputs of all (token, expert) pairs gathered into columns grouped
+// by expert -> grouped gate/up and down GEMMs (an expert's columns as independent wave items or as one GEMM of the tile
+// schedules) -> weighted sum of a token's expert outputs in selection order + residual + next norm's operand.
 // The expert lists are filled with atomic counters: the order of the tokens inside a list depends on timing, but a
 // token's result does not depend on its place in the list (every GEMM column is accumulated on its own, in an order fixed
 // by the schedule), and the per-token sum over its experts runs in selection order, so results are reproducible.
@@ -22,6 +23,7 @@ struct MoeShared {
   u32 small_e[MOE_MAX_EXPERTS];   // experts with 1..MOE_WAVE_MAX_TOKENS tokens, and the first wave item of each
   u32 small_base[MOE_MAX_EXPERTS + 1];
   u32 big_e[MOE_MAX_EXPERTS];     // experts with more tokens: one GEMM of the workgroup schedules each
+  u32 big_start[MOE_MAX_EXPERTS]; // workgroup that takes the first tile of that GEMM: the tiles of all such GEMMs go round the grid
   u32 n_small, n_big;
   float wrstd[4][64];             // per wave: norm scales of the tokens of its current item
 };
@@ -31,11 +33,11 @@ struct MoeShared {
 // wave items (moe_wave_rows row tiles each), and the rest.
 __device__ __forceinline__ u32 moe_wave_rows(u32 n_tokens) { return n_tokens <= 32 ? 4u : 2u; }
 
-__device__ __forceinline__ void moe_offsets(const DevCtx& c, MoeShared& sh, u32 NT = 0) {
+__device__ __forceinline__ void moe_offsets(const DevCtx& c, MoeShared& sh, u32 NT = 0, u32 nwg = 1) {
   for (u32 e = threadIdx.x; e < c.n_experts; e += blockDim.x) sh.cnt[e] = c.moe_count[e];
   __syncthreads();
   if (threadIdx.x == 0) {
-    u32 o = 0, ns = 0, nb = 0, base = 0;
+    u32 o = 0, ns = 0, nb = 0, base = 0, tiles = 0;
     for (u32 e = 0; e < c.n_experts; ++e) {
       const u32 n = sh.cnt[e];
       sh.off[e] = o;
@@ -45,7 +47,12 @@ __device__ __forceinline__ void moe_offsets(const DevCtx& c, MoeShared& sh, u32 
           const u32 nw = moe_wave_rows(n);
           sh.small_e[ns] = e; sh.small_base[ns] = base; base += (NT + nw - 1) / nw; ++ns;
         }
-        else sh.big_e[nb++] = e;
+        else {
+          // workgroup tiles of the expert's GEMM at the tile width moe_grouped forces: 128 rows x (all tokens up to 192, else 256)
+          sh.big_e[nb] = e;
+          sh.big_start[nb++] = tiles % nwg;
+          tiles += ((NT + 7) / 8) * (n <= 192 ? 1u : (n + 255) / 256);
+        }
       }
     }
     sh.off[c.n_experts] = o;
@@ -60,13 +67,13 @@ __device__ __forceinline__ void moe_route(const DevCtx& c, u32 layer, u32 wg, u3
   const u32 T = c.meta->n_tokens, E = c.n_experts, k = c.n_active;
   const u32 lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = blockDim.x >> 6;
   for (u32 t = wg * nw + w; t < T; t += nwg * nw) {
-    {   // the norm scale of the token (times the inverse of the weight scale), for the waves of the grouped gate/up GEMM
+    {   // the norm scale of the token, applied when the experts' operand is gathered
       const u32 np = c.d / 16;
       float v = 0.f;
       for (u32 q = lane; q < np; q += 64) v += c.ssq[(u64)t * np + q];
 #pragma unroll
       for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-      if (lane == 0) c.moe_rstd[t] = W_SCALE_INV / sqrtf(v / (float)c.d + c.eps);
+      if (lane == 0) c.moe_rstd[t] = 1.0f / sqrtf(v / (float)c.d + c.eps);
     }
     const float* r = c.moe_logits + (u64)t * E;
     unsigned long long key[MOE_MAX_EXPERTS / 64];
@@ -106,6 +113,49 @@ __device__ __forceinline__ void moe_route(const DevCtx& c, u32 layer, u32 wg, u3
   }
 }
 
+// ---- the experts' operand: the normalised FFN input of every (token, expert) pair, columns grouped by expert ----------
+// A wave writes one packed 16-column x 32-k tile (1 KB, contiguous) at a time: lane (c, kg) reads eight consecutive
+// fp32 values of the residual stream of column c's token, applies the norm's gain and scale and rounds once to half
+// precision. Gathering the tokens here, once, lets the grouped GEMMs read whole operand tiles instead of sixteen-byte
+// pieces of sixteen different tokens per load. Columns past an expert's count (its group is padded to 16) get zeros.
+__device__ __forceinline__ void moe_permute(const DevCtx& c, u32 layer, MoeShared& sh, u32 wg, u32 nwg) {
+  moe_offsets(c, sh);
+  const u32 lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = blockDim.x >> 6, E = c.n_experts;
+  const u32 nblk = sh.off[E] / 16, KT = c.d / 32, lc = lane & 15, kg = lane >> 4;
+  const float* g = c.layers[layer].g2;
+  const u32 KQ = (KT + 3) / 4;                   // a wave item: one column block x a quarter of the k-tiles
+  for (u32 item = wg * nw + w; item < nblk * 4; item += nwg * nw) {
+    const u32 cb = item >> 2, k_lo = (item & 3u) * KQ, k_hi = min(KT, k_lo + KQ);
+    u32 lo = 0, hi = E;                        // the expert of column block cb: last e with off[e] / 16 <= cb
+    while (hi - lo > 1) {
+      const u32 mid = (lo + hi) >> 1;
+      if (sh.off[mid] / 16 <= cb) lo = mid; else hi = mid;
+    }
+    const u32 e = lo, pos = (cb - sh.off[e] / 16) * 16 + lc;
+    const bool live = pos < sh.cnt[e];
+    const u32 tok = live ? c.moe_list[(u64)e * c.maxT + pos] : 0u;
+    const float r = live ? c.moe_rstd[tok] : 0.f;
+    const float* xr = c.x + (u64)tok * c.d + kg * 8;
+    f16_t* dst = c.xq_moe + ((u64)cb * 64 + lane) * 8;
+    const u64 kstride = (u64)c.moe_TBS * 512;
+    for (u32 k0 = k_lo; k0 < k_hi; k0 += 4) {
+      float4 a[4], b[4], ga[4], gb[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {              // four k-tiles of loads in flight (the last ones of a ragged quarter repeat its last tile)
+        const u32 kt = min(k0 + u, k_hi - 1);
+        a[u] = *(const float4*)(xr + kt * 32); b[u] = *(const float4*)(xr + kt * 32 + 4);
+        ga[u] = *(const float4*)(g + kt * 32 + kg * 8); gb[u] = *(const float4*)(g + kt * 32 + kg * 8 + 4);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (k0 + u < k_hi)
+          *(uint4*)(dst + (k0 + u) * kstride) =
+              make_uint4(pack_f16x2(a[u].x * ga[u].x * r, a[u].y * ga[u].y * r), pack_f16x2(a[u].z * ga[u].z * r, a[u].w * ga[u].w * r),
+                         pack_f16x2(b[u].x * gb[u].x * r, b[u].y * gb[u].y * r), pack_f16x2(b[u].z * gb[u].z * r, b[u].w * gb[u].w * r));
+    }
+  }
+}
+
 // ---- grouped GEMMs -----------------------------------------------------------------------------------------------------
 // An expert with at most MOE_WAVE_MAX_TOKENS tokens (every expert of a decode iteration, as a rule) is bound by the
 // bytes of its matrices. Its GEMM is cut into wave items of four (two, beyond 32 tokens) 16-row weight tiles x all its
@@ -126,17 +176,9 @@ __device__ __forceinline__ void moe_wave_item(const DevCtx& c, const LayerWP* P,
 #pragma unroll
   for (int i = 0; i < NW; ++i) wp[i] = Wp + (u64)min(g * NW + i, NT - 1) * KT * 512 + lane * 8;
   const f16_t* xp[TW];
-  const u64 xk_stride = (u64)(GATEUP ? c.TBS : c.moe_TBS) * 512;
+  const u64 xk_stride = (u64)c.moe_TBS * 512;
 #pragma unroll
-  for (int tw = 0; tw < TW; ++tw) {
-    if (GATEUP) {
-      const u32 tok = c.moe_list[(u64)e * c.maxT + min(tw * 16 + (lane & 15), cnt - 1)];
-      xp[tw] = c.xq + (u64)((tok >> 4) * 64 + (tok & 15) + 16 * (lane >> 4)) * 8;
-      if (lane < 16) sh.wrstd[w][tw * 16 + lane] = c.moe_rstd[tok];
-    } else {
-      xp[tw] = c.hq_moe + (u64)(col0 / 16 + tw) * 512 + lane * 8;
-    }
-  }
+  for (int tw = 0; tw < TW; ++tw) xp[tw] = (GATEUP ? c.xq_moe : c.hq_moe) + (u64)(col0 / 16 + tw) * 512 + lane * 8;
   struct Buf { f16x8_t w[U][NW], x[U][TW]; };
   const f16x8_t zero = {0, 0, 0, 0, 0, 0, 0, 0};
   auto issue = [&](Buf& b, u32 kt0) {
@@ -183,15 +225,15 @@ __device__ __forceinline__ void moe_wave_item(const DevCtx& c, const LayerWP* P,
     }
 }
 
-// Experts with more tokens run as one GEMM of the workgroup schedules each (shared operand tiles in LDS); the workgroups
-// start each expert's items at a different place so that the experts' items interleave over the grid.
+// Experts with more tokens run as one GEMM of the workgroup schedules each (shared operand tiles in LDS); every GEMM
+// starts at the workgroup behind the previous one's last tile, so the tiles of all of them go round the grid evenly.
 template <bool GATEUP>
 __device__ __forceinline__ void moe_grouped(const DevCtx& c, u32 layer, MoeShared& sh, u32 wg, u32 nwg) {
   const LayerWP* P = c.players + layer;
   const u32 Fe = c.F, N = GATEUP ? 2 * Fe : c.d;
-  moe_offsets(c, sh, N / 16);
+  moe_offsets(c, sh, N / 16, nwg);
   const u32 lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = blockDim.x >> 6;
-  if (!GATEUP) sh.wrstd[w][lane] = W_SCALE_INV;      // each wave reads only its own row
+  sh.wrstd[w][lane] = W_SCALE_INV;                   // the operands are normalised already; each wave reads only its own row
   const u32 total = sh.small_base[sh.n_small];
   for (u32 i = wg * nw + w; i < total; i += nwg * nw) {
     u32 lo = 0, hi = sh.n_small;                     // the expert of item i: last s with small_base[s] <= i
@@ -216,14 +258,13 @@ __device__ __forceinline__ void moe_grouped(const DevCtx& c, u32 layer, MoeShare
     if (((a.tune_nw >> 12) & 7u) == 0)
       a.tune_nw |= (a.T <= 64 ? 2u : a.T <= 96 ? 3u : a.T <= 128 ? 4u : a.T <= 192 ? 6u : 7u) << 12;
     if (GATEUP) {
-      a.TBS = c.TBS; a.Wp = P->wgu + (u64)e * (2 * Fe) * c.d; a.Xp = c.xq; a.N = 2 * Fe; a.K = c.d; a.ssq_in = c.ssq;
-      a.tok_index = c.moe_list + (u64)e * c.maxT;
-      a.Hp = c.hq_moe; a.TBS_out = c.moe_TBS;
-      gemm_mfma<EPI_SILU_GATE, false>(a, sh.mfma, (wg + nwg - (b * 97u) % nwg) % nwg, nwg);
+      a.TBS = c.moe_TBS; a.Wp = P->wgu + (u64)e * (2 * Fe) * c.d; a.Xp = c.xq_moe + (u64)(sh.off[e] / 16) * 512; a.N = 2 * Fe; a.K = c.d;
+      a.Hp = c.hq_moe;
+      gemm_mfma<EPI_SILU_GATE, false>(a, sh.mfma, (wg + nwg - sh.big_start[b]) % nwg, nwg);
     } else {
       a.TBS = c.moe_TBS; a.Wp = P->wd + (u64)e * c.d * Fe; a.Xp = c.hq_moe + (u64)(sh.off[e] / 16) * 512; a.N = c.d; a.K = Fe;
       a.out = c.y_moe; a.ldo = c.d;
-      gemm_mfma<EPI_SCALED_STORE, false>(a, sh.mfma, (wg + nwg - (b * 61u) % nwg) % nwg, nwg);
+      gemm_mfma<EPI_SCALED_STORE, false>(a, sh.mfma, (wg + nwg - sh.big_start[b]) % nwg, nwg);
     }
   }
 }

@@ -16,7 +16,8 @@ enum {
   PH_FINAL_NORM, PH_LM_HEAD, PH_SAMPLE,
   PH_ATTN_COMBINE,  // bf16 path only, directly after PH_ATTN of the same layer
   PH_QKV_RED, PH_OPROJ_RED, PH_DOWN_RED,  // bf16 path, chains with K split across workgroups: second kernel of that GEMM
-  PH_ROUTER, PH_ROUTE, PH_MOE_GATEUP, PH_MOE_DOWN, PH_MOE_COMBINE   // mixture of experts: in place of PH_GATEUP and PH_DOWN
+  PH_ROUTER, PH_ROUTE, PH_MOE_GATEUP, PH_MOE_DOWN, PH_MOE_COMBINE,  // mixture of experts: in place of PH_GATEUP and PH_DOWN
+  PH_MOE_PERMUTE                                                    // (runs between PH_ROUTE and PH_MOE_GATEUP)
 };
 #define PH_LAYER_FIRST PH_NORM1
 #define PH_LAYER_LAST PH_DOWN
@@ -47,6 +48,7 @@ template <> struct PhaseSharedOf<PH_ROUTE> { typedef SmallPhaseShared type; };
 template <> struct PhaseSharedOf<PH_MOE_GATEUP> { typedef MoeShared type; };
 template <> struct PhaseSharedOf<PH_MOE_DOWN> { typedef MoeShared type; };
 template <> struct PhaseSharedOf<PH_MOE_COMBINE> { typedef MoeShared type; };
+template <> struct PhaseSharedOf<PH_MOE_PERMUTE> { typedef MoeShared type; };
 
 template <typename WT>
 __device__ __forceinline__ void run_phase_t(const DevCtx& c, int ph, u32 layer, void* shp, u32 wg, u32 nwg) {
@@ -119,6 +121,7 @@ __device__ __forceinline__ void run_phase_bf16(const DevCtx& c, int ph, u32 laye
       else gemm_mfma<EPI_SCALED_STORE, false>(a, sh.mfma, wg, nwg);
       break;
     case PH_ROUTE: moe_route(c, layer, wg, nwg); break;
+    case PH_MOE_PERMUTE: moe_permute(c, layer, *(MoeShared*)shp, wg, nwg); break;
     case PH_MOE_GATEUP: moe_gateup(c, layer, *(MoeShared*)shp, wg, nwg); break;
     case PH_MOE_DOWN: moe_down(c, layer, *(MoeShared*)shp, wg, nwg); break;
     case PH_MOE_COMBINE: moe_combine(c, layer, *(MoeShared*)shp, wg, nwg); break;
