@@ -63,8 +63,24 @@ table inside the scheduler can map token prefixes to blocks. It says no more). T
     blocks are reused first, idle cached blocks oldest first, and a prefix loses its tail before its head. Popping
     an idle cached block evicts it from the table. A match on an idle block takes it out of the queue by moving
     the top element into its place.
+
+Speculative decoding (`speculative=k > 0`; section 7: the scheduler runs draft generation followed by target verification
+and publishes only accepted tokens. It names no draft source). The reading taken here needs no second model:
+  * Drafts by lookup in the request's own tokens (prompt, then outputs), for greedy requests only: with n tokens so far,
+    the last of them not yet in the cache, find the most recent earlier place i <= n - 3, not further back than
+    SPEC_LOOKBACK positions, where tokens i, i + 1 equal tokens n - 2, n - 1; the up to k tokens that followed there
+    (i + 2 ...) are the drafts, never more than the request may still emit minus one.
+  * A decode iteration processes, per request, its last token and its m drafts at consecutive positions (blocks for all of
+    them are taken from the request's reservation) and computes a logits row at every one of the m + 1 positions.
+  * Verification, per request in row order: row j gives token t_j (the request's own sampler at output index gen + j);
+    t_j is emitted; the walk goes on to row j + 1 only if t_j equals draft j and the request has not finished. What is
+    emitted is exactly what one-token-per-iteration decoding emits; cached entries of rejected drafts lie beyond the
+    context length and are overwritten later.
+Plain mode only.
 """
 import numpy as np
+
+SPEC_LOOKBACK = 1024
 
 MASK64 = (1 << 64) - 1
 PREFIX_H0 = 0x243F6A8885A308D3
@@ -136,6 +152,9 @@ class Plan:
                                 # last_idx and gen_index have one entry per sampling sequence. Without chunked prefill every
                                 # sequence of an iteration samples
         self.pos0 = []          # position of the first token each sequence processes in this iteration
+        self.row0 = []          # speculative decoding: first logits row (index into last_idx) of each sequence; the rows of a
+                                # sequence are consecutive, one per token it processes in a decode iteration (last_idx then has
+                                # one entry per row, not per sequence)
         self.free_blocks_after = 0
 
     @property
@@ -149,9 +168,13 @@ def blocks_needed(P, max_new, bs):
 
 class Scheduler:
     def __init__(self, n_blocks, block_size, max_batch, max_prefill_tokens, ring_slots, eos_token_id=-1,
-                 free_list=None, chunked=False, preempt=False, prefix_cache=False):
+                 free_list=None, chunked=False, preempt=False, prefix_cache=False, speculative=0):
         self.chunked, self.preempt, self.prefix_cache = chunked, preempt, prefix_cache
         assert not (prefix_cache and (chunked or preempt)), "prefix caching is defined for the plain mode only"
+        self.speculative = int(speculative)
+        assert not (self.speculative and (chunked or preempt or prefix_cache)), "speculative decoding is defined for the plain mode only"
+        self.greedy = {}            # ticket -> whether the request decodes greedily (only those speculate)
+        self.drafted = self.accepted = 0
         self.table = {}             # prefix caching: key -> block
         self.bkey = {}              # block -> key, for the cached blocks
         self.ref = [0] * n_blocks   # running requests that hold the cached block
@@ -180,11 +203,12 @@ class Scheduler:
         """From an engine configuration dict (synth.configs)."""
         return cls(eng["kv_num_blocks"], eng["kv_block_size"], eng["max_batch"], eng["max_prefill_tokens"], eng["ring_slots"],
                    eng.get("eos_token_id", -1), chunked=bool(eng.get("chunked_prefill", False)), preempt=bool(eng.get("preemption", False)),
-                   prefix_cache=bool(eng.get("prefix_cache", False)))
+                   prefix_cache=bool(eng.get("prefix_cache", False)), speculative=int(eng.get("speculative", 0)))
 
     # ---- ring side -------------------------------------------------------------------
-    def submit(self, prompt, max_new):
+    def submit(self, prompt, max_new, greedy=True):
         t = len(self.requests)
+        self.greedy[t] = bool(greedy)
         self.requests[t] = (np.asarray(prompt, dtype=np.int64), int(max_new))
         self.outputs[t] = []
         self.state[t] = EMPTY
@@ -270,26 +294,48 @@ class Scheduler:
                 pos = list(range(r.P))
                 r.ctx_len = r.P
             else:
-                if r.ctx_len == len(r.blocks) * bs:
+                drafts = self._drafts(r) if self.speculative else []
+                toks = [r.last_token] + drafts
+                pos = list(range(r.ctx_len, r.ctx_len + len(toks)))
+                while len(r.blocks) * bs < r.ctx_len + len(toks):
                     r.blocks.append(self.free.pop())
-                toks = [r.last_token]
-                pos = [r.ctx_len]
-                r.ctx_len += 1
+                r.ctx_len += len(toks)               # provisional: commit() takes back the rejected drafts
             plan.batch_slots.append(b)
             plan.tickets.append(r.ticket)
             plan.seq_lens.append(r.ctx_len)
+            first_row = len(plan.input_ids) if (plan.kind == DECODE and self.speculative) else len(plan.input_ids) + len(toks) - 1
             plan.input_ids += [int(x) for x in toks]
             plan.positions += pos
             plan.slot_mapping += [r.blocks[p // bs] * bs + p % bs for p in pos]
             plan.tok_seq += [si] * len(pos)
             plan.cu_seqlens.append(len(plan.input_ids))
-            plan.last_idx.append(len(plan.input_ids) - 1)
+            if self.speculative:                      # a logits row at every position of a decoding sequence
+                plan.row0.append(len(plan.last_idx))
+                plan.last_idx += list(range(first_row, len(plan.input_ids)))
+            else:
+                plan.last_idx.append(len(plan.input_ids) - 1)
             plan.block_tables.append(list(r.blocks))
             plan.gen_index.append(r.gen)
             plan.sample_seq.append(si)
             plan.pos0.append(pos[0])
         plan.free_blocks_after = len(self.free)
         return plan
+
+    def _tokens_so_far(self, r):
+        return [int(x) for x in self.requests[r.ticket][0]] + self.outputs[r.ticket]
+
+    def _drafts(self, r):
+        if not self.greedy[r.ticket]:
+            return []
+        s = self._tokens_so_far(r)
+        n = len(s)
+        room = min(self.speculative, r.max_new - r.gen - 1)
+        if n < 3 or room <= 0:
+            return []
+        for i in range(n - 3, max(-1, n - 3 - SPEC_LOOKBACK), -1):
+            if s[i] == s[n - 2] and s[i + 1] == s[n - 1]:
+                return s[i + 2:i + 2 + room]
+        return []
 
     # ---- one iteration with prefix caching ---------------------------------------------------------------------------
     def _pop_block(self):
@@ -643,6 +689,8 @@ class Scheduler:
     def commit(self, plan, tokens):
         """tokens[i]: sampled token of the i-th sampling sequence of the plan. Returns events
         (ticket, index, token, is_first, is_last) in batch-slot order."""
+        if self.speculative:
+            return self._commit_speculative(plan, tokens)
         events = []
         assert len(tokens) == len(plan.sample_seq)
         for b, tok in zip([plan.batch_slots[i] for i in plan.sample_seq], tokens):
@@ -659,6 +707,45 @@ class Scheduler:
                 r.finished = True
                 self._set(r.ticket, DECODE_COMPLETED)
             events.append((r.ticket, idx, tok, idx == 0, done))
+        return events
+
+    def rows_of(self, plan, i):
+        """Speculative mode: the logits rows (indices into last_idx) of the i-th sequence of the plan."""
+        end = plan.row0[i + 1] if i + 1 < len(plan.row0) else len(plan.last_idx)
+        return list(range(plan.row0[i], end))
+
+    def _commit_speculative(self, plan, row_tokens):
+        """row_tokens[j]: the token the sampler gives for logits row j (every row, whether the walk reaches it or not).
+        Emits per sequence row by row while the row's token equals the draft that was fed at the next position."""
+        events = []
+        assert len(row_tokens) == len(plan.last_idx)
+        for i, b in enumerate(plan.batch_slots):
+            r = self.running[b]
+            rows = self.rows_of(plan, i)
+            n_fed = len(rows)                                   # 1 + drafts in a decode iteration; 1 in a prefill iteration
+            base = plan.cu_seqlens[i + 1] - n_fed               # index of the first token that has a row
+            emitted = 0
+            done = False
+            for j, row in enumerate(rows):
+                tok = int(row_tokens[row])
+                self.outputs[r.ticket].append(tok)
+                idx = r.gen
+                r.gen += 1
+                r.last_token = tok
+                emitted += 1
+                done = r.gen == r.max_new or tok == self.eos
+                events.append((r.ticket, idx, tok, idx == 0, done))
+                if done or j + 1 == n_fed or tok != plan.input_ids[base + j + 1]:
+                    break
+            if plan.kind == DECODE:
+                self.drafted += n_fed - 1
+                self.accepted += emitted - 1
+                r.ctx_len -= n_fed - emitted                    # the rejected drafts' cache entries are dead
+            if self.state[r.ticket] in (PREFILL_PROCESSING, DECODE_PAUSED) and not done:
+                self._set(r.ticket, DECODE_PROCESSING)
+            if done:
+                r.finished = True
+                self._set(r.ticket, DECODE_COMPLETED)
         return events
 
     # ---- invariants ---------------------------------------------------------------------

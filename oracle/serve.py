@@ -18,7 +18,7 @@ def run_schedule(sched, requests, token_fn, tails=None, max_iterations=None, on_
     tails: per non-idle iteration, the ring tail the poll saw (None: all requests visible).
     Returns the list of events (iteration, ticket, index, token, first, last)."""
     for r in requests:
-        sched.submit(r["prompt"], r["max_new_tokens"])
+        sched.submit(r["prompt"], r["max_new_tokens"], greedy=r.get("temperature", 0.0) == 0.0)
     events = []
     n = len(requests)
     it = 0
@@ -54,6 +54,12 @@ def serve(cfg, W, eng, requests, tails=None, max_iterations=None, on_plan=None, 
         if keep_logits is not None:
             keep_logits.append((plan.iteration, logits))
         out = []
+        if sched.speculative:           # one token per logits row: row j of a sequence samples output index gen + j
+            for i, t in enumerate(plan.tickets):
+                r = requests[t]
+                for j, row in enumerate(sched.rows_of(plan, i)):
+                    out.append(S.sample(logits[row], r["temperature"], r["top_k"], r["top_p"], r["seed"], plan.gen_index[i] + j))
+            return out
         for i, t in enumerate(plan.sample_tickets):
             r = requests[t]
             out.append(S.sample(logits[i], r["temperature"], r["top_k"], r["top_p"], r["seed"], plan.gen_index[i]))

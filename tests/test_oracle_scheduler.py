@@ -485,3 +485,94 @@ def test_prefix_cached_service_equals_per_request_generation():
     assert sched.cache_hits > 8 and sched.evictions > 0
     for t, r in enumerate(reqs):
         assert sched.outputs[t] == SV.generate_reference(cfg, W, r), t
+
+
+# ---- speculative decoding ----------------------------------------------------------------------------------------------
+
+def _spec_token_fn(sched, f):
+    """token_fn for run_schedule: f(ticket, output index) is what the 'model' emits, whatever is fed (rows past a rejected
+    draft are computed like the others and ignored by the walk)."""
+    def fn(plan):
+        if not sched.speculative:
+            return [f(t, plan.gen_index[i]) for i, t in enumerate(plan.sample_tickets)]
+        return [f(t, plan.gen_index[i] + j) for i, t in enumerate(plan.tickets) for j, _ in enumerate(sched.rows_of(plan, i))]
+    return fn
+
+
+def test_speculative_hand_worked_drafts_acceptance_and_rejection():
+    """Prompt 5 6 7 5 6, four tokens wanted, up to three drafts. The model says 7 after the prompt: the last two tokens
+    (6, 7) occurred at places 1, 2, so the tokens that followed there (5, 6: two, because only three more tokens may be
+    emitted) are fed as drafts behind the 7 at positions 5, 6, 7. Accepting run: the rows say 5, 6, 9: all three emitted.
+    Rejecting run: the rows say 5, 8, 9: 5 is emitted and confirms the first draft, 8 is emitted and refutes the second,
+    the third row is ignored and the context shrinks by the rejected draft."""
+    for rows, outs, ctx in (([5, 6, 9], [7, 5, 6, 9], 8), ([5, 8, 9], [7, 5, 8], 7)):
+        s = Scheduler(8, 4, 2, 8192, 8, speculative=3)
+        s.submit([5, 6, 7, 5, 6], 4)
+        p0 = s.step(1)
+        assert (p0.kind, p0.last_idx, p0.row0) == (PREFILL, [4], [0])
+        s.commit(p0, [7])
+        p1 = s.step(1)
+        assert (p1.kind, p1.input_ids, p1.positions, p1.last_idx, p1.row0) == (DECODE, [7, 5, 6], [5, 6, 7], [0, 1, 2], [0])
+        assert p1.slot_mapping == [5, 6, 7] and p1.block_tables == [[0, 1]] and p1.seq_lens == [8]
+        ev = s.commit(p1, rows)
+        s.check_invariants()
+        assert s.outputs[0] == outs and s.running[0].ctx_len == ctx and s.running[0].last_token == outs[-1]
+        assert [e[1] for e in ev] == list(range(1, len(outs))) and ev[-1][4] == (len(outs) == 4)
+        assert (s.drafted, s.accepted) == (2, len(outs) - 2)
+    # no earlier occurrence of the last two tokens, a sampled request, or one token left: no drafts
+    s = Scheduler(8, 4, 2, 8192, 8, speculative=3)
+    s.submit([1, 2, 3, 4, 5], 4)
+    s.submit([5, 6, 7, 5, 6], 4, greedy=False)
+    s.submit([5, 6, 7, 5, 6], 2)
+    p0 = s.step(2)
+    s.commit(p0, [9, 7])
+    p1 = s.step(2)
+    assert p1.input_ids == [9, 7] and p1.last_idx == [0, 1]
+    s = Scheduler(8, 4, 2, 8192, 8, speculative=3)
+    s.submit([5, 6, 7, 5, 6], 2)
+    s.commit(s.step(1), [7])
+    assert s.step(1).input_ids == [7]
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_speculative_schedule_emits_what_the_plain_schedule_emits(seed):
+    """A 'model' whose token depends on (request, output index) only, with few distinct values so that lookups hit: the
+    speculative scheduler emits exactly the plain scheduler's streams in fewer iterations; invariants after every step."""
+    f = lambda t, idx: (t * 7 + (idx // 3) * (idx // 3)) % 4
+    rng = np.random.default_rng(seed)
+    reqs = [dict(prompt=rng.integers(0, 4, int(rng.integers(1, 40))), max_new_tokens=int(rng.integers(1, 30)), temperature=0.0)
+            for _ in range(30)]
+    for i in (3, 11):
+        reqs[i]["temperature"] = 0.7            # sampled requests never speculate
+    eng = dict(kv_block_size=4, kv_num_blocks=60, max_batch=4, max_prefill_tokens=64, ring_slots=32, eos_token_id=-1)
+    tails = list(np.minimum(30, 1 + np.cumsum(rng.integers(0, 3, 300))))      # (the first poll sees a request: no idle spin)
+    a = Scheduler.from_engine(eng)
+    SV.run_schedule(a, reqs, _spec_token_fn(a, f), tails=tails)
+    b = Scheduler.from_engine(dict(eng, speculative=4))
+    seen = []
+    SV.run_schedule(b, reqs, _spec_token_fn(b, f), tails=tails, on_plan=seen.append)
+    assert [b.outputs[t] for t in range(30)] == [a.outputs[t] for t in range(30)]
+    assert b.accepted > 20 and b.drafted > b.accepted and b.iteration < a.iteration
+    sampled = {3, 11}
+    for pl in seen:
+        if pl.kind == DECODE:
+            for i, t in enumerate(pl.tickets):
+                if t in sampled:
+                    assert len(b.rows_of(pl, i)) == 1
+    b.step(30)
+    assert b.committed == 0 and sorted(b.free) == list(range(60))
+
+
+def test_speculative_service_equals_per_request_generation():
+    """The model side: drafts are fed at consecutive positions of one iteration and every position gets a logits row; what
+    is emitted is exactly what the request generates alone, greedy or sampled, and drafts are accepted on the way (a
+    random tiny model decoding greedily soon repeats itself)."""
+    cfg = dict(synth.model_config("tiny"), n_layers=2, vocab=97, d_model=64, n_q_heads=4, n_kv_heads=2, head_dim=16, d_ffn=96)
+    W = M.Weights(cfg, synth.make_weights(cfg, 9, gain_jitter=0.1))
+    reqs = [dict(r, max_new_tokens=24) for r in synth.make_workload("mini", 97, 5, n_requests=8)]
+    reqs[2].update(temperature=0.8, top_k=5, top_p=0.9, seed=synth.splitmix64(3, 2))
+    eng = dict(kv_block_size=4, kv_num_blocks=120, max_batch=3, max_prefill_tokens=150, ring_slots=16, eos_token_id=-1, speculative=4)
+    ev, sched = SV.serve(cfg, W, eng, reqs)
+    assert sched.accepted > 10, (sched.drafted, sched.accepted)
+    for t, r in enumerate(reqs):
+        assert sched.outputs[t] == SV.generate_reference(cfg, W, r), t
