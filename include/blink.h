@@ -66,6 +66,14 @@ extern "C" {
                                         in the table at the bottom of the free queue until their block is reused. Plain mode
                                         only (not with CHUNKED_PREFILL or PREEMPTION) */
 
+#define BLINK_FLAG_SPECULATIVE 256u  /* speculative decoding (section 7: draft generation, target verification, only accepted tokens
+                                        are published) without a second model: a greedy request's drafts are the up to
+                                        blink_config.spec_tokens tokens that followed the most recent earlier occurrence of its
+                                        last two tokens in its own prompt and outputs (within the last 1024 positions); a decode
+                                        iteration feeds them behind the last token, computes logits at every fed position, and
+                                        emits row by row while the row's token confirms the next draft: exactly the tokens
+                                        one-token-per-iteration decoding emits. Sampled requests never speculate. Plain mode only */
+
 /* slot life cycle of the ring (section 4.2, "Ring buffer") */
 enum {
   BLINK_SLOT_EMPTY = 0,
@@ -115,6 +123,7 @@ typedef struct {
                                   wd[E][d][F] */
   uint32_t n_active;           /* experts per token (1 .. min(8, n_experts)): the n_active largest router logits, ties to
                                   the lower expert id; their outputs are weighted by the softmax over those logits */
+  uint32_t spec_tokens;        /* BLINK_FLAG_SPECULATIVE: most drafts per request and iteration, 1 .. 7 */
 } blink_config;
 
 typedef struct {
@@ -172,6 +181,8 @@ typedef struct {
   uint64_t prefix_evictions;   /* idle cached blocks whose memory was reused so far */
   uint32_t pinned_blocks;      /* cached blocks held by running requests */
   uint32_t pad1;
+  uint64_t spec_drafted;       /* speculative decoding: draft tokens fed so far */
+  uint64_t spec_accepted;      /* draft tokens confirmed so far */
 } blink_stats;
 
 /* blink_debug_read selectors (tests only; call while the loop is stopped) */

@@ -6,7 +6,7 @@ import numpy as np
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 
-FLAG_TRACE, FLAG_EXIT_WHEN_IDLE, FLAG_KEEP_LOGITS, FLAG_NO_GRAPH, FLAG_CHUNKED_PREFILL, FLAG_PREEMPTION, FLAG_PREFIX_CACHE = 1, 2, 8, 16, 32, 64, 128
+FLAG_TRACE, FLAG_EXIT_WHEN_IDLE, FLAG_KEEP_LOGITS, FLAG_NO_GRAPH, FLAG_CHUNKED_PREFILL, FLAG_PREEMPTION, FLAG_PREFIX_CACHE, FLAG_SPECULATIVE = 1, 2, 8, 16, 32, 64, 128, 256
 ERR_INVAL, ERR_TOO_LARGE, ERR_FULL, ERR_DEVICE, ERR_STATE = -1, -2, -3, -4, -5
 EVENT_FIRST, EVENT_LAST = 1, 2
 
@@ -26,7 +26,7 @@ class Config(C.Structure):
         ("kv_block_size", C.c_uint32), ("kv_num_blocks", C.c_uint32), ("max_batch", C.c_uint32), ("max_seq_len", C.c_uint32),
         ("max_prefill_tokens", C.c_uint32), ("ring_slots", C.c_uint32), ("eos_token_id", C.c_int32), ("device", C.c_int32),
         ("flags", C.c_uint32), ("trace_capacity", C.c_uint32), ("idle_poll_us", C.c_uint32), ("pump_depth", C.c_uint32),
-        ("tune", C.c_uint32), ("n_experts", C.c_uint32), ("n_active", C.c_uint32)]
+        ("tune", C.c_uint32), ("n_experts", C.c_uint32), ("n_active", C.c_uint32), ("spec_tokens", C.c_uint32)]
 
 
 class Sampling(C.Structure):
@@ -39,7 +39,7 @@ class Stats(C.Structure):
                 ("free_blocks", C.c_uint32), ("committed_blocks", C.c_uint32), ("device_error", C.c_uint32),
                 ("running", C.c_uint32), ("windows", C.c_uint32), ("kv_bytes", C.c_uint64), ("weight_bytes", C.c_uint64),
                 ("ring_bytes", C.c_uint64), ("prefix_hit_blocks", C.c_uint64), ("prefix_evictions", C.c_uint64),
-                ("pinned_blocks", C.c_uint32), ("pad1", C.c_uint32)]
+                ("pinned_blocks", C.c_uint32), ("pad1", C.c_uint32), ("spec_drafted", C.c_uint64), ("spec_accepted", C.c_uint64)]
 
 
 EVENT_DTYPE = np.dtype([("request_id", "<u8"), ("index", "<u4"), ("token", "<i4"), ("flags", "<u4"), ("iteration", "<u4"),
@@ -147,6 +147,9 @@ class Engine:
             flags |= FLAG_PREEMPTION
         if engine.get("prefix_cache"):
             flags |= FLAG_PREFIX_CACHE
+        if engine.get("speculative"):
+            flags |= FLAG_SPECULATIVE
+            cfg.spec_tokens = int(engine["speculative"])
         cfg.device, cfg.flags, cfg.trace_capacity, cfg.idle_poll_us = device, flags, trace_capacity, idle_poll_us
         cfg.pump_depth, cfg.tune = pump_depth, tune
         cfg.n_experts, cfg.n_active = model.get("n_experts", 0), model.get("n_active", 0)
@@ -206,7 +209,7 @@ class Engine:
         if max_bytes is None:
             m, e = self.model, self.engine
             max_t = max(e["max_prefill_tokens"], e["max_seq_len"], e["max_batch"])
-            max_bytes = 8 + 4 * max(e["max_batch"] * m["vocab"], e["kv_num_blocks"] + 1, max_t * m["d_model"],
+            max_bytes = 8 + 4 * max(e["max_batch"] * (1 + int(e.get("speculative", 0))) * m["vocab"], e["kv_num_blocks"] + 1, max_t * m["d_model"],
                                     m["n_layers"] * max_t * m.get("n_active", 0),
                                     e["max_batch"] * ((e["max_seq_len"] + 15) // 16), e["ring_slots"])
         buf = np.zeros(max_bytes, dtype=np.uint8)

@@ -23,6 +23,9 @@ __global__ void __launch_bounds__(BLK_THREADS) k_sched(DevCtx c) {
   sched_step(c, sh);
 }
 
+// speculative decoding: the drafts of the running greedy requests, ahead of the scheduler step that feeds them
+__global__ void __launch_bounds__(BLK_THREADS) k_spec_draft(DevCtx c) { spec_draft(c, blockIdx.x, gridDim.x); }
+
 // one named kernel per phase so that profiles attribute time to the step of the forward pass. Two workgroups per
 // compute unit (at most 256 registers per lane): the start and the end of one workgroup overlap the other's streaming.
 #define PHASE_KERNEL(name, PH)                                                   \
@@ -264,6 +267,10 @@ static int init_impl(const blink_config* cfg, blink_engine* e) {
   c.eos = cfg->eos_token_id; c.flags = cfg->flags; c.trace_cap = cfg->trace_capacity ? cfg->trace_capacity : 65536u;
   c.qkv_n = (c.nq + 2 * c.nkv) * c.hd;
   c.n_experts = cfg->n_experts; c.n_active = cfg->n_experts ? cfg->n_active : 0;
+  // speculative decoding: a decoding sequence feeds up to 1 + spec_k tokens and has a logits row for each of them
+  c.spec_k = (cfg->flags & BLINK_FLAG_SPECULATIVE) ? cfg->spec_tokens : 0u;
+  const u64 rows_cap = (u64)c.max_batch * (c.spec_k + 1);
+  c.maxT = std::max<u32>(c.maxT, (u32)rows_cap);
   const u64 es = c.dtype == 1 ? 2 : 4;
 
   // ---- ring ----
@@ -311,7 +318,14 @@ static int init_impl(const blink_config* cfg, blink_engine* e) {
   if (int rc = dalloc(e, &c.seq_bslot, c.max_batch)) return rc;
   if (int rc = dalloc(e, &c.seq_len, c.max_batch)) return rc;
   if (int rc = dalloc(e, &c.cu_seqlens, c.max_batch + 1)) return rc;
-  if (int rc = dalloc(e, &c.last_idx, c.max_batch)) return rc;
+  if (int rc = dalloc(e, &c.last_idx, rows_cap)) return rc;
+  if (c.spec_k) {
+    if (int rc = dalloc(e, &c.spec_len, c.max_batch)) return rc;
+    if (int rc = dalloc(e, &c.spec_tok, (u64)c.max_batch * SPEC_MAX_DRAFTS)) return rc;
+    if (int rc = dalloc(e, &c.sample_row0, c.max_batch)) return rc;
+    if (int rc = dalloc(e, &c.sample_nrow, c.max_batch)) return rc;
+    if (int rc = dalloc(e, &c.sample_tok0, c.max_batch)) return rc;
+  }
   if (int rc = dalloc(e, &c.sample_bslot, c.max_batch)) return rc;
   if (int rc = dalloc(e, &c.seq_pos0, c.max_batch)) return rc;
   if (int rc = dalloc(e, &c.seq_ring, c.max_batch)) return rc;
@@ -513,9 +527,9 @@ static int init_impl(const blink_config* cfg, blink_engine* e) {
     if (int rc = dalloc(e, &c.qkv, (u64)c.maxT * c.qkv_n)) return rc;
     if (int rc = dalloc(e, &c.attn, (u64)c.maxT * c.nq * c.hd)) return rc;
     if (int rc = dalloc(e, &c.gu, (u64)c.maxT * 2 * c.F)) return rc;
-    if (int rc = dalloc(e, &c.hlast, (u64)c.max_batch * c.d)) return rc;
+    if (int rc = dalloc(e, &c.hlast, rows_cap * c.d)) return rc;
   }
-  if (int rc = dalloc(e, &c.logits, (u64)c.max_batch * c.V)) return rc;
+  if (int rc = dalloc(e, &c.logits, rows_cap * c.V)) return rc;
   HIPCHK(hipStreamSynchronize(e->compute));
   HIPCHK(hipDeviceSynchronize());
   c.idle_poll_ns = 1000ull * (cfg->idle_poll_us ? cfg->idle_poll_us : 2000u);
@@ -568,6 +582,12 @@ extern "C" int blink_init(const blink_config* cfg, blink_engine** out) {
     return fail(BLINK_ERR_INVAL, "prefix caching is built for the plain mode, not together with chunked prefill or preemption");
   if ((cfg->flags & BLINK_FLAG_CHUNKED_PREFILL) && cfg->max_prefill_tokens <= cfg->max_batch)
     return fail(BLINK_ERR_INVAL, "chunked prefill: max_prefill_tokens (the token budget of an iteration) must exceed max_batch");
+  if (cfg->flags & BLINK_FLAG_SPECULATIVE) {
+    if (cfg->flags & (BLINK_FLAG_CHUNKED_PREFILL | BLINK_FLAG_PREEMPTION | BLINK_FLAG_PREFIX_CACHE))
+      return fail(BLINK_ERR_INVAL, "speculative decoding is built for the plain mode, not together with chunked prefill, preemption or prefix caching");
+    if (cfg->spec_tokens < 1 || cfg->spec_tokens >= SPEC_MAX_DRAFTS)
+      return fail(BLINK_ERR_INVAL, "speculative decoding: spec_tokens must be in [1, %u]", SPEC_MAX_DRAFTS - 1);
+  }
   if (!cfg->ring_slots || (cfg->ring_slots & (cfg->ring_slots - 1))) return fail(BLINK_ERR_INVAL, "ring_slots must be a power of two");
   if (cfg->weights_bytes != expected_weight_bytes(cfg))
     return fail(BLINK_ERR_INVAL, "weights_bytes is %llu, the model needs %llu", (unsigned long long)cfg->weights_bytes,
@@ -664,6 +684,7 @@ static int launch_phase(blink_engine* e, const DevCtx& ctx, hipStream_t st, int 
 static int enqueue_iteration_kernels(blink_engine* e, hipStream_t st, u64 enq_index) {
   const bool split = has_split_chain(e);
   const DevCtx& c = e->ctx;
+  if (c.spec_k) hipLaunchKernelGGL(k_spec_draft, dim3((c.max_batch + 3) / 4), dim3(BLK_THREADS), 0, st, c);
   hipLaunchKernelGGL(k_sched, dim3(1), dim3(BLK_THREADS), 0, st, c);
   if (int rc = launch_phase(e, c, st, PH_EMBED, 0, enq_index)) return rc;
   for (u32 l = 0; l < c.n_layers; ++l)
@@ -911,6 +932,7 @@ extern "C" int blink_get_stats(blink_engine* e, blink_stats* out) {
   out->tokens_prefilled = s.tokens_prefilled; out->next_ticket = s.next_ticket; out->n_running = s.n_running;
   out->free_blocks = s.free_top - s.free_lo; out->committed_blocks = s.committed; out->device_error = s.error;
   out->prefix_hit_blocks = s.cache_hits; out->prefix_evictions = s.evictions; out->pinned_blocks = s.pinned; out->pad1 = 0;
+  out->spec_drafted = s.drafted; out->spec_accepted = s.accepted;
   return BLINK_OK;
 }
 

@@ -88,6 +88,8 @@ struct SchedState {
   u32 pad3;
   u64 cache_hits;       // blocks matched so far
   u64 evictions;        // idle cached blocks reused so far
+  u64 drafted;          // speculative decoding: draft tokens fed / confirmed so far
+  u64 accepted;
 };
 
 // batch metadata of the current iteration (what the scheduler populates before the forward pass)
@@ -102,6 +104,8 @@ struct IterMeta {
   u32 skip;             // 1: the window has ended, phases do nothing (the rest describes the last real iteration)
   u32 n_samples;        // sequences that sample a token in this iteration (all of them unless a prompt chunk leaves its prompt incomplete)
   u32 max_pref_ctx;     // longest context after this iteration among the sequences that process prompt tokens
+  u32 n_sample_seqs;    // sequences that sample (n_samples counts logits rows: more than one per sequence with speculative decoding)
+  u32 pad;
 };
 
 struct TraceRec {       // mirrors blink_trace_record
@@ -171,6 +175,14 @@ struct DevCtx {
   RunEntry* run;
   RunEntry* preq;       // [max_batch] preemption mode: the preempted requests (no blocks, no batch slot), unordered
   u32* block_tables;    // [max_batch][max_blocks_per_seq]
+  // speculative decoding: drafts per batch slot (written by the draft kernel ahead of the scheduler), and per sampling
+  // sequence its first logits row, number of rows and the token index of its first row
+  u32 spec_k;
+  u32* spec_len;        // [max_batch]
+  i32* spec_tok;        // [max_batch][8]
+  u32* sample_row0;     // [max_batch]
+  u32* sample_nrow;     // [max_batch]
+  u32* sample_tok0;     // [max_batch]
   u32* free_stack;      // [fs_mask + 1 >= n_blocks] (a ring when prefix caching pushes at its bottom)
   u32 fs_mask;
   // prefix caching: per block, reference count, key, flags (PC_CACHED: in the table; PC_LINKED: a node of a bucket's chain,
@@ -186,7 +198,8 @@ struct DevCtx {
   u32* seq_bslot;       // [max_batch]
   u32* seq_len;         // [max_batch]
   u32* cu_seqlens;      // [max_batch+1]
-  u32* last_idx;        // [max_batch] token index of the last token of every sampling sequence
+  u32* last_idx;        // [max_batch * (spec_k + 1)] token index of every logits row (one per sampling sequence: its last token; with
+                        // speculative decoding one per token a decoding sequence processes)
   u32* sample_bslot;    // [max_batch] batch slot of every sampling sequence
   u32* seq_pos0;        // [max_batch] position of the first token every sequence processes in this iteration
   u32* seq_ring;        // [max_batch] ring slot of a sequence that processes prompt tokens, ~0 for a decoding one

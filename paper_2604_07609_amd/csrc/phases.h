@@ -78,7 +78,10 @@ __device__ __forceinline__ void run_phase_t(const DevCtx& c, int ph, u32 layer, 
     case PH_LM_HEAD:
       phase_gemm<WT, GA_PLAIN, GE_STORE>(c.hlast, c.d, (const WT*)c.lm, c.logits, c.V, B, c.V, c.d, sh.gemm, wg, nwg);
       break;
-    case PH_SAMPLE: phase_sample_publish(c, *(SamplerShared*)shp, wg, nwg); break;
+    case PH_SAMPLE:
+      if (c.spec_k) phase_sample_publish_spec(c, *(SamplerShared*)shp, wg, nwg);
+      else phase_sample_publish(c, *(SamplerShared*)shp, wg, nwg);
+      break;
   }
 }
 
@@ -149,7 +152,10 @@ __device__ __forceinline__ void run_phase_bf16(const DevCtx& c, int ph, u32 laye
       a.out = c.logits; a.ldo = c.V;
       gemm_mfma<EPI_SCALED_STORE, false>(a, sh.mfma, wg, nwg);
       break;
-    case PH_SAMPLE: phase_sample_publish(c, *(SamplerShared*)shp, wg, nwg); break;
+    case PH_SAMPLE:
+      if (c.spec_k) phase_sample_publish_spec(c, *(SamplerShared*)shp, wg, nwg);
+      else phase_sample_publish(c, *(SamplerShared*)shp, wg, nwg);
+      break;
     default: break;   // the norms and the rotary / KV-write step are fused into the GEMMs
   }
 }

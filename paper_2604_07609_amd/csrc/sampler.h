@@ -316,6 +316,61 @@ __device__ __forceinline__ void phase_sample_publish(const DevCtx& c, SamplerSha
   if (wg == 0 && tid == 0 && (c.flags & 1u)) c.trace[meta->trace_idx].t_publish_end = dev_now_ns();
 }
 
+// Speculative decoding: a sequence has one logits row per token it was fed (its last token, then its drafts). One workgroup
+// walks the rows of a sequence in order: row j gives the token of output index gen + j, which is emitted; the walk goes on
+// only while the token equals the draft fed at the next position and the request has not finished. What is emitted is what
+// one-token-per-iteration decoding emits; the cache entries of rejected drafts lie beyond the context length afterwards.
+__device__ __forceinline__ void phase_sample_publish_spec(const DevCtx& c, SamplerShared& sh, u32 wg, u32 nwg) {
+  const IterMeta* meta = c.meta;
+  const u32 V = c.V, tid = threadIdx.x;
+  if (wg == 0 && tid == 0 && (c.flags & 1u)) c.trace[meta->trace_idx].t_forward_end = dev_now_ns();
+  for (u32 s = wg; s < meta->n_sample_seqs; s += nwg) {
+    const u32 b = c.sample_bslot[s], row0 = c.sample_row0[s], nrow = c.sample_nrow[s], tok0 = c.sample_tok0[s];
+    RunEntry& r = c.run[b];
+    const u32 idx0 = r.gen, slot = r.ring_slot, max_new = r.max_new;
+    const float temperature = r.temperature, top_p = r.top_p;
+    const u32 top_k = r.top_k;
+    const u64 seed = r.seed;
+    u32 emitted = 0;
+    i32 last = -1;
+    bool done = false;
+    for (u32 j = 0; j < nrow; ++j) {
+      const i32 token = sample_row(c.logits + (u64)(row0 + j) * V, V, temperature, top_k, top_p, seed, idx0 + j, sh);
+      if (tid == 0) {
+        OutRec* o = c.out_arena + (u64)slot * c.max_seq_len + idx0 + j;
+        o->token = token;
+        o->iteration = meta->iteration;
+        o->device_ns = dev_now_ns();
+      }
+      ++emitted;
+      last = token;
+      done = (idx0 + emitted == max_new) || (token == c.eos);
+      if (done || j + 1 == nrow || token != c.input_ids[tok0 + j + 1]) break;
+    }
+    if (tid == 0) {
+      r.gen = idx0 + emitted;
+      r.last_token = last;
+      r.paused = 0;
+      r.ctx_len -= nrow - emitted;            // the scheduler counted every fed token; the rejected drafts' entries are dead
+      u32 state = SLOT_DECODE_PROCESSING;
+      if (done) {
+        r.finished = 1;
+        state = SLOT_DECODE_COMPLETED;
+      }
+      atomicAdd((unsigned long long*)&c.ss->tokens_out, (unsigned long long)emitted);
+      if (nrow > 1) {
+        atomicAdd((unsigned long long*)&c.ss->drafted, (unsigned long long)(nrow - 1));
+        atomicAdd((unsigned long long*)&c.ss->accepted, (unsigned long long)(emitted - 1));
+      }
+      __threadfence_system();
+      const u64 word = (u64)state | ((u64)(idx0 + emitted) << 32);
+      __hip_atomic_store((u64*)&c.status[slot], word, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+    __syncthreads();
+  }
+  if (wg == 0 && tid == 0 && (c.flags & 1u)) c.trace[meta->trace_idx].t_publish_end = dev_now_ns();
+}
+
 // Stand-alone sampling of a batch of logits rows (no engine): one workgroup per row, grid-stride.
 struct SampleRowParams {   // the layout of blink_sampling (24 bytes)
   float temperature;

@@ -100,6 +100,43 @@ __device__ __forceinline__ bool pc_insert(const DevCtx& c, u32 blk, u64 h) {
   return true;
 }
 
+// ---- speculative decoding: the drafts of every running greedy request, one wave per batch slot ------------------------
+// Token i of a request: its prompt, then its outputs.
+#define SPEC_LOOKBACK 1024u
+#define SPEC_MAX_DRAFTS 8u
+__device__ __forceinline__ i32 spec_token_at(const DevCtx& c, const RunEntry& r, u32 i) {
+  const u64 base = (u64)r.ring_slot * c.max_seq_len;
+  if (i < r.P) return __hip_atomic_load(c.in_arena + base + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+  return c.out_arena[base + (i - r.P)].token;
+}
+// With n tokens so far: the most recent i <= n - 3 (not below n - 2 - SPEC_LOOKBACK) with tokens i, i + 1 equal to tokens
+// n - 2, n - 1; the tokens from i + 2 on, at most spec_k, are the drafts. The lanes test 64 places at a time, from the
+// most recent backwards. Runs ahead of the scheduler kernel, which cuts the count to what the request may still emit.
+__device__ __forceinline__ void spec_draft(const DevCtx& c, u32 wg, u32 nwg) {
+  const u32 lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  for (u32 b = wg * nw + w; b < c.max_batch; b += nwg * nw) {
+    const RunEntry r = c.run[b];
+    u32 len = 0;
+    if (r.valid && !r.finished && r.temperature == 0.f && r.gen >= 1 && r.P + r.gen >= 3) {
+      const i32 n = (i32)(r.P + r.gen);
+      const i32 t1 = spec_token_at(c, r, (u32)n - 2), t2 = spec_token_at(c, r, (u32)n - 1);
+      const i32 lowest = max(0, n - 2 - (i32)SPEC_LOOKBACK);
+      i32 found = -1;
+      for (i32 hi = n - 3; hi >= lowest && found < 0; hi -= 64) {
+        const i32 i = hi - (i32)lane;
+        const bool hit = i >= lowest && spec_token_at(c, r, (u32)i) == t1 && spec_token_at(c, r, (u32)i + 1) == t2;
+        const unsigned long long bal = __ballot(hit);
+        if (bal) found = hi - (i32)(__ffsll((long long)bal) - 1);      // the lowest lane that hit tested the most recent place
+      }
+      if (found >= 0) {
+        len = min(c.spec_k, (u32)(n - (found + 2)));
+        if (lane < len) c.spec_tok[(u64)b * SPEC_MAX_DRAFTS + lane] = spec_token_at(c, r, (u32)found + 2 + lane);
+      }
+    }
+    if (lane == 0) c.spec_len[b] = len;
+  }
+}
+
 // Exclusive prefix sum over the 256 threads of the workgroup; total returned in `total`.
 __device__ __forceinline__ u32 block_excl_scan(u32 v, u32& total, u32* part) {
   const u32 lane = threadIdx.x & 63u, w = threadIdx.x >> 6;
@@ -579,13 +616,14 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
   // Sequences of the iteration: without chunking the newly admitted (prefill iteration) or all running (decode
   // iteration); with chunking all running, each with its share of the token budget. A sequence samples a token
   // unless its prompt is still incomplete after this iteration.
-  u32 n_seqs = 0, n_tok = 0, n_alloc = 0, n_qt = 0, n_ch = 0, n_smp = 0, n_dec_seq = 0, max_q = 0, max_ctx = 0, max_pref = 0;
+  u32 n_seqs = 0, n_tok = 0, n_alloc = 0, n_qt = 0, n_ch = 0, n_smp = 0, n_rows = 0, n_dec_seq = 0, max_q = 0, max_ctx = 0, max_pref = 0;
+  const u32 spec_k = (c.flags & 256u) ? c.spec_k : 0u;
   u64 n_ctx = 0;
   if (kind != KIND_IDLE) {
     for (u32 base = 0; base < c.max_batch; base += BLK_THREADS) {
       const u32 b = base + tid;
-      bool in = false, pref = false, smp = false;
-      u32 nalloc = 0, ntok = 0, pos0 = 0, nb = 0;
+      bool in = false, pref = false, smp = false, multi = false;   // multi: several tokens of one sequence attend like a prompt chunk
+      u32 nalloc = 0, ntok = 0, pos0 = 0, nb = 0, nrow = 0;
       if (b < c.max_batch && c.run[b].valid) {
         RunEntry& r = c.run[b];
         nb = r.n_blocks;
@@ -607,18 +645,25 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
           in = smp = true;
           ntok = 1;
           pos0 = r.ctx_len;
+          // speculative decoding: a greedy request also processes its drafts, as many as it may still emit minus one
+          if (spec_k && r.temperature == 0.f) ntok += min(c.spec_len[b], r.max_new - r.gen - 1);
         }
-        if (in) nalloc = (pos0 + ntok + c.bs - 1) / c.bs - nb;
+        multi = pref || ntok > 1;
+        // (a request whose drafts were rejected may already hold the block its next tokens go to)
+        if (in) nalloc = max((pos0 + ntok + c.bs - 1) / c.bs, nb) - nb;
         else ntok = 0;
+        nrow = smp ? ((spec_k && !pref) ? ntok : 1u) : 0u;    // logits rows: the last token; every token of a decoding sequence when drafts are verified
       }
       u32 tots, tota, tott, totq, totc, totm, totx;
       const u32 ctx_after = in ? pos0 + ntok : 0u;
-      const u32 coff = n_ch + block_excl_scan((in && !pref) ? (ctx_after + ATTN_CHUNK_TOKENS - 1) / ATTN_CHUNK_TOKENS : 0u, totc, sh.wave_part);
-      const u32 qoff = n_qt + block_excl_scan(pref ? (ntok + 15) / 16 : 0u, totq, sh.wave_part2);
+      const u32 coff = n_ch + block_excl_scan((in && !multi) ? (ctx_after + ATTN_CHUNK_TOKENS - 1) / ATTN_CHUNK_TOKENS : 0u, totc, sh.wave_part);
+      const u32 qoff = n_qt + block_excl_scan(multi ? (ntok + 15) / 16 : 0u, totq, sh.wave_part2);
       const u32 si = n_seqs + block_excl_scan(in ? 1u : 0u, tots, sh.wave_part);
       const u32 aoff = n_alloc + block_excl_scan(nalloc, tota, sh.wave_part2);
       const u32 toff = n_tok + block_excl_scan(ntok, tott, sh.wave_part);
       const u32 mi = n_smp + block_excl_scan(smp ? 1u : 0u, totm, sh.wave_part2);
+      u32 totr;
+      const u32 ri = n_rows + block_excl_scan(nrow, totr, sh.wave_part);
       block_excl_scan(ctx_after, totx, sh.wave_part);     // context tokens the attention of this iteration reads
       u32 totd;
       block_excl_scan((in && !pref) ? 1u : 0u, totd, sh.wave_part2);
@@ -643,14 +688,22 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
         c.seq_ring[si] = pref ? r.ring_slot : ~0u;
         c.seq_len[si] = ctx_after;
         if (smp) {
-          c.last_idx[mi] = toff + ntok - 1;
+          for (u32 j = 0; j < nrow; ++j) c.last_idx[ri + j] = toff + ntok - nrow + j;
           c.sample_bslot[mi] = b;
+          if (spec_k) { c.sample_row0[mi] = ri; c.sample_nrow[mi] = nrow; c.sample_tok0[mi] = toff + ntok - nrow; }
         }
         if (!pref) {
           c.input_ids[toff] = r.last_token;
           c.positions[toff] = (i32)pos0;
           c.slot_mapping[toff] = (i32)(bt[pos0 / c.bs] * c.bs + pos0 % c.bs);
           c.tok_seq[toff] = si;
+          for (u32 j = 1; j < ntok; ++j) {          // the drafts behind the last token, at the next positions
+            const u32 p = pos0 + j;
+            c.input_ids[toff + j] = c.spec_tok[(u64)b * SPEC_MAX_DRAFTS + j - 1];
+            c.positions[toff + j] = (i32)p;
+            c.slot_mapping[toff + j] = (i32)(bt[p / c.bs] * c.bs + p % c.bs);
+            c.tok_seq[toff + j] = si;
+          }
           if (r.paused) {
             set_slot_state(&c.status[r.ring_slot], SLOT_DECODE_PROCESSING);
             r.paused = 0;
@@ -663,7 +716,7 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
       }
       max_q = max(max_q, block_max(ntok, sh.wave_part2));
       max_ctx = max(max_ctx, block_max(ctx_after, sh.wave_part));
-      max_pref = max(max_pref, block_max(pref ? ctx_after : 0u, sh.wave_part2));
+      max_pref = max(max_pref, block_max(multi ? ctx_after : 0u, sh.wave_part2));
       n_ctx += totx;
       n_seqs += tots;
       n_alloc += tota;
@@ -671,6 +724,7 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
       n_qt += totq;
       n_ch += totc;
       n_smp += totm;
+      n_rows += totr;
     }
     top -= n_alloc;
     __syncthreads();
@@ -777,7 +831,8 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
     m->kind = kind;
     m->skip = 0;
     m->n_seqs = n_seqs;
-    m->n_samples = n_smp;
+    m->n_samples = n_rows;
+    m->n_sample_seqs = n_smp;
     m->n_tokens = n_tok;
     m->max_q_len = max_q;
     m->max_ctx = max_ctx;
@@ -787,7 +842,7 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
       const u64 it = ss->iteration;
       m->iteration = (u32)it;
       ss->iteration = it + 1;
-      ss->tokens_out += n_smp;
+      if (!spec_k) ss->tokens_out += n_smp;      // (with speculative decoding the sampler counts what it emits)
       ss->idle_since_ns = 0;
       if (kind == KIND_PREFILL) {
         ss->prefill_iterations += 1;

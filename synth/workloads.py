@@ -82,3 +82,21 @@ def with_shared_prefixes(reqs, vocab, seed, n_prefixes=4, prefix_len=(16, 200), 
             r["prompt"] = np.concatenate([h, own]).astype(np.int32)
         out.append(r)
     return out
+
+
+def with_repetition(reqs, vocab, seed, phrase_len=(2, 6), noise=0.0):
+    """A copy of the request list whose prompts repeat a short random phrase (2..6 tokens by default), each token replaced
+    by a random one with probability `noise`: text that copies from its own context (code edits, summaries, retrieved
+    passages), the input on which drafting by lookup in the request's own tokens finds matches. Lengths are kept."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for r in reqs:
+        r = dict(r)
+        n = len(r["prompt"])
+        phrase = rng.integers(0, vocab, int(rng.integers(phrase_len[0], phrase_len[1] + 1)))
+        p = np.resize(phrase, n)
+        flip = rng.random(n) < noise
+        p = np.where(flip, rng.integers(0, vocab, n), p)
+        r["prompt"] = p.astype(np.int32)
+        out.append(r)
+    return out

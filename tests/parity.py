@@ -278,3 +278,77 @@ def stepwise_check(B, cfg, eng, raw, blob, reqs, rtol, max_iters=10000, tune=0, 
         raise AssertionError("did not finish")
     finally:
         e.shutdown()
+
+
+def stepwise_check_speculative(B, cfg, eng, raw, blob, reqs, rtol, max_iters=10000):
+    """Speculative decoding, one iteration per blink_run call: the drafts (input ids behind each last token), positions,
+    slot mapping, block tables, free stack and the logits rows' token indices bit-exact against the oracle's scheduler;
+    every logits row (one per fed position) within rtol of the oracle's paged forward on the engine's token history; the
+    verification walk exact: the oracle commits, row by row, its own sampler's tokens on the engine's logits rows, and
+    the events it emits (request, index, token, first/last) must be the engine's events of the iteration, the counters of
+    drafted and accepted tokens the engine's counters. Returns (worst relative logit error, tokens per ticket)."""
+    W = M.Weights(cfg, raw)
+    sched = Scheduler.from_engine(eng)
+    assert sched.speculative
+    kv = M.PagedKV(cfg, eng["kv_num_blocks"], eng["kv_block_size"])
+    for r in reqs:
+        sched.submit(r["prompt"], r["max_new_tokens"], greedy=r["temperature"] == 0.0)
+    e = B.Engine(cfg, eng, blob, flags=B.FLAG_TRACE | B.FLAG_EXIT_WHEN_IDLE | B.FLAG_KEEP_LOGITS)
+    D = B.DBG
+    worst = 0.0
+    toks = {}
+    try:
+        for r in reqs:
+            e.submit_request(r)
+        for it in range(max_iters):
+            e.run(1)
+            e.wait()
+            plan = sched.step(len(reqs))
+            sched.check_invariants()
+            if plan.kind == 0:
+                st = e.stats()
+                assert st["iterations"] == it
+                assert (st["spec_drafted"], st["spec_accepted"]) == (sched.drafted, sched.accepted)
+                assert st["tokens_out"] == sum(len(v) for v in toks.values())
+                assert st["free_blocks"] == eng["kv_num_blocks"] and st["committed_blocks"] == 0
+                return worst, toks
+            assert list(e.debug_read(D.INPUT_IDS, np.int32)) == plan.input_ids
+            assert list(e.debug_read(D.POSITIONS, np.int32)) == plan.positions
+            assert list(e.debug_read(D.SLOT_MAPPING, np.int32)) == plan.slot_mapping
+            assert list(e.debug_read(D.SEQ_BATCH_SLOT, np.uint32)) == plan.batch_slots
+            assert list(e.debug_read(D.SEQ_LENS, np.uint32)) == plan.seq_lens
+            assert list(e.debug_read(D.CU_SEQLENS, np.uint32)) == plan.cu_seqlens
+            fs = e.debug_read(D.FREE_STACK, np.uint32)
+            assert fs[0] == len(sched.free) and list(fs[1:]) == sched.free
+            bt = e.debug_read(D.BLOCK_TABLES, np.uint32).reshape(eng["max_batch"], -1)
+            for b, blocks in zip(plan.batch_slots, plan.block_tables):
+                assert list(bt[b][: len(blocks)]) == blocks
+            ref = M.paged_forward(cfg, W, kv, plan.input_ids, plan.positions, plan.slot_mapping, plan.tok_seq,
+                                  plan.block_tables, plan.last_idx)
+            got = e.debug_read(D.LOGITS, np.float32).reshape(len(plan.last_idx), cfg["vocab"])
+            err = np.abs(got - ref).max(axis=1) / np.abs(ref).max(axis=1)
+            worst = max(worst, float(err.max()))
+            assert err.max() < rtol, (it, err)
+            evs = e.drain()
+            mine = {}
+            for x in evs:
+                mine.setdefault(int(x["request_id"]), []).append((int(x["index"]), int(x["token"]), bool(x["flags"] & 1), bool(x["flags"] & 2)))
+            row_tokens = []
+            for i, t in enumerate(plan.tickets):
+                r = reqs[t]
+                rows = sched.rows_of(plan, i)
+                if r["temperature"] == 0.0:
+                    row_tokens += [S.greedy(np.asarray(got[row], dtype=np.float64)) for row in rows]
+                else:           # a sampled request has one row; its token is checked against the oracle's sampler on that row
+                    assert len(rows) == 1 and len(mine[t]) == 1
+                    token_matches_own_logits(got[rows[0]], r, plan.gen_index[i], mine[t][0][1])
+                    row_tokens.append(mine[t][0][1])
+            exp = {}
+            for (t, idx, tok, first, last) in sched.commit(plan, row_tokens):
+                exp.setdefault(t, []).append((idx, tok, first, last))
+                toks.setdefault(t, []).append(tok)
+            assert {t: sorted(v) for t, v in mine.items()} == exp, (it, mine, exp)
+            assert all(int(x["iteration"]) == plan.iteration for x in evs)
+        raise AssertionError("did not finish")
+    finally:
+        e.shutdown()

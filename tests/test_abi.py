@@ -38,7 +38,7 @@ def test_struct_sizes_match_header(tmp_path):
     got = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
     assert got == [ctypes.sizeof(binding.Config), ctypes.sizeof(binding.Sampling), ctypes.sizeof(binding.Stats), binding.EVENT_DTYPE.itemsize,
                    binding.TRACE_DTYPE.itemsize, binding.Config.weights.offset, binding.Config.tune.offset, binding.Sampling.seed.offset]
-    assert got[:5] == [120, 24, 112, 32, 96]
+    assert got[:5] == [120, 24, 128, 32, 96]
 
 
 def test_argument_errors_without_gpu():
