@@ -369,6 +369,70 @@ def prefix_leg(B, cfg, eng, blob, reqs, args):
     return out
 
 
+def cycle_weights(cfg, raw, period=16):
+    """Weights of the same shapes whose greedy stream is known: attention output and FFN down projections zero (the
+    residual stream stays the token's embedding) and row v of the LM head equal to the embedding of the token before v in
+    its group of `period` consecutive ids, so that the largest logit after token t is that of t's successor in the group.
+    Every stream then cycles with that period, and a lookup of its last two tokens finds the continuation: the input on
+    which every draft is right."""
+    V = cfg["vocab"]
+    assert V % period == 0
+    w = dict(raw)
+    for l in range(cfg["n_layers"]):
+        w[f"l{l}.wo"] = np.zeros_like(raw[f"l{l}.wo"])
+        w[f"l{l}.wd"] = np.zeros_like(raw[f"l{l}.wd"])
+    v = np.arange(V)
+    w["lm"] = raw["embed"][(v // period) * period + (v % period - 1) % period]
+    return w
+
+
+def speculative_leg(B, cfg, eng, raw, reqs, args):
+    """Speculative decoding on the workload's requests made greedy, the whole set resident at t = 0 and run to
+    completion, without and with drafts, on two sets of weights. Random weights: a 32-layer random model neither copies
+    from its context nor falls into a loop within a request's length, lookups find next to nothing, and the run shows
+    what the draft kernel and the wider bookkeeping cost. Cycle weights (cycle_weights): every draft is right, the
+    run shows what an iteration that verifies spec_tokens drafts per request costs against the tokens it saves: the
+    upper bound of the gain at that draft count. Trained weights on text lie in between; there are none here."""
+    greedy = [dict(r, temperature=0.0, top_k=0, top_p=1.0) for r in reqs]
+    out = dict(workload="the workload's requests, greedy", requests=len(greedy), spec_tokens=args.spec_tokens)
+    for wname in ("random_weights", "cycle_weights"):
+        blob = synth.pack_blob(cfg, raw if wname == "random_weights" else cycle_weights(cfg, raw))
+        res = {}
+        for label, k in (("plain", 0), ("speculative", args.spec_tokens)):
+            e = B.Engine(cfg, dict(eng, speculative=k), blob, flags=B.FLAG_TRACE | B.FLAG_EXIT_WHEN_IDLE, trace_capacity=1 << 16, tune=args.tune)
+            try:
+                for r in greedy:
+                    e.submit_request(r)
+                t0 = time.perf_counter()
+                n_out = 0
+                while True:
+                    e.run(64)
+                    e.wait()
+                    n_out += len(e.drain(1 << 16))
+                    st = e.stats()
+                    if st["n_running"] == 0 and st["next_ticket"] == len(greedy):
+                        break
+                dt = time.perf_counter() - t0
+                tr = e.trace(1 << 16)
+            finally:
+                e.shutdown()
+            dec = tr[tr["kind"] == 2]
+            dec_ms = (dec["t_publish_end_ns"].astype(np.int64) - dec["t_sched_begin_ns"].astype(np.int64)) / 1e6
+            res[label] = dict(seconds=round(dt, 2), output_tokens=n_out, output_tokens_per_s=round(n_out / dt, 1),
+                              iterations=int(st["iterations"]), prefill_iterations=int(st["prefill_iterations"]),
+                              decode_iteration_ms_median=round(float(np.median(dec_ms)), 3) if len(dec) else None,
+                              tokens_fed_per_decode_iteration=round(float(dec["n_tokens"].mean()), 1) if len(dec) else None,
+                              decode_seconds=round(float(dec_ms.sum()) / 1e3, 2),
+                              drafted=int(st["spec_drafted"]), accepted=int(st["spec_accepted"]))
+        a, b = res["plain"], res["speculative"]
+        res["speedup"] = round(a["seconds"] / b["seconds"], 3)
+        res["decode_speedup"] = round(a["decode_seconds"] / max(1e-9, b["decode_seconds"]), 3)
+        res["acceptance"] = round(b["accepted"] / max(1, b["drafted"]), 3)
+        out[wname] = res
+        del blob
+    return out
+
+
 def claim_latency(B, e, vocab, n=24):
     """An idle engine (its scheduler kernel polling the ring on the device) receives one short request at a time:
     time from the entry of blink_submit, and from its return, to the end of the scheduler step that admitted the request
@@ -446,6 +510,9 @@ def main():
     ap.add_argument("--only-chunked-leg", action="store_true", help="tuning: skip everything else")
     ap.add_argument("--prefix-leg", action="store_true", help="only this: the request set behind common prompt heads, served to "
                     "completion without and with prefix caching (BLINK_FLAG_PREFIX_CACHE)")
+    ap.add_argument("--spec-leg", action="store_true", help="only this: the request set made greedy with repetitive prompts, served to "
+                    "completion without and with speculative decoding")
+    ap.add_argument("--spec-tokens", type=int, default=4, help="most drafts per request and iteration in --spec-leg")
     ap.add_argument("--prefix-heads", type=int, default=8)
     ap.add_argument("--prefix-len", default="256,1024", help="range of the common heads' lengths in tokens")
     ap.add_argument("--prefix-share", type=float, default=0.8, help="fraction of the requests that start with a common head")
@@ -495,6 +562,9 @@ def main():
 
     if args.prefix_leg:
         print(json.dumps(dict(prefix_cache=prefix_leg(B, cfg, eng, blob, reqs, args), config={"workload": args.workload, "requests": len(reqs)})))
+        return
+    if args.spec_leg:
+        print(json.dumps(dict(speculative=speculative_leg(B, cfg, eng, raw, reqs, args), config={"workload": args.workload, "requests": len(reqs)})))
         return
     if args.only_chunked_leg:
         print(json.dumps(chunked_leg(B, cfg, eng, blob, reqs, K, W, args)))
