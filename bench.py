@@ -648,7 +648,7 @@ def main():
             kernel_times[str(ph)] = row
         trace = e.trace(1 << 18)
         e.calibration_copy(64 << 20)    # one plain copy kernel of known size: scales the HBM counters of a --pmc run
-        copy_gbs, mfma_tflops = e.calibration_rates()
+        copy_gbs, mfma_tflops, read_gbs = e.calibration_rates()
     finally:
         e.shutdown()
         if stressor:
@@ -765,8 +765,8 @@ def main():
         "decode_step": dec_step,
         "prefill_step": pre_step,
         "roofline": roofline,
-        "measured_ceilings": {"copy_kernel_GBs": round(copy_gbs, 1), "mfma_bf16_loop_TFLOPs": round(mfma_tflops, 1),
-                              "note": "plain kernels on this device: a 1 GiB copy (read + written) and a register-only MFMA loop"},
+        "measured_ceilings": {"copy_kernel_GBs": round(copy_gbs, 1), "read_kernel_GBs": round(read_gbs, 1), "mfma_bf16_loop_TFLOPs": round(mfma_tflops, 1),
+                              "note": "plain kernels on this device: a 1 GiB copy (read + written), a 1 GiB read and a register-only MFMA loop"},
         "setup_s": {"weights_and_workload": round(t_gen, 1)},
     }
     if kernel_times:

@@ -263,11 +263,13 @@ int blink_get_phase_times(blink_engine* e, float* ms_per_iteration, uint64_t cap
  * 64 MiB, between two buffers set aside at init) on the compute stream and waits for it: a kernel of known traffic
  * against which hardware HBM counters are scaled. The loop must be stopped. */
 int blink_calibration_copy(blink_engine* e, uint64_t bytes);
-/* Measures, with HIP events on the compute stream, what two plain kernels sustain on this device: a device-to-device
- * copy of 1 GiB between two buffers this call allocates and frees (bytes read plus bytes written per second, in GB/s) and a register-only loop of 16x16x32 bf16 MFMA
- * products on every compute unit (TFLOP/s). Both are written to host memory; the best of three timed runs counts.
- * Context for the roofline report: what the GEMM and attention kernels could reach at most. The loop must be stopped. */
-int blink_calibration_rates(blink_engine* e, double* copy_gbs, double* mfma_bf16_tflops);
+/* Measures, with HIP events on the compute stream, what three plain kernels sustain on this device: a device-to-device
+ * copy of 1 GiB between two buffers this call allocates and frees (bytes read plus bytes written per second, in GB/s), a
+ * register-only loop of 16x16x32 bf16 MFMA products on every compute unit (TFLOP/s), and a read of the same 1 GiB with
+ * eight 16-byte loads in flight per lane (bytes read per second, in GB/s). All are written to host memory; the best of
+ * three timed runs counts. Context for the roofline report: what the GEMM and attention kernels could reach at most.
+ * The loop must be stopped. */
+int blink_calibration_rates(blink_engine* e, double* copy_gbs, double* mfma_bf16_tflops, double* read_gbs);
 /* Relates the device clock of blink_event.device_ns and of the trace to the host's monotonic clock (CLOCK_MONOTONIC,
  * nanoseconds): a one-thread kernel on a side stream writes the device clock to pinned host memory while the host
  * reads its own clock before the launch and after the value arrives. Of eight such probes the one with the shortest

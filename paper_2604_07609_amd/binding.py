@@ -87,7 +87,7 @@ def load_library():
     lib.blink_debug_read.argtypes = [vp, u32, vp, u64, C.POINTER(u64)]
     lib.blink_time_phase.argtypes = [vp, C.c_int32]
     lib.blink_calibration_copy.argtypes = [vp, u64]
-    lib.blink_calibration_rates.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    lib.blink_calibration_rates.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.blink_get_phase_times.argtypes = [vp, vp, u64, C.POINTER(u64)]
     lib.blink_clock_sync.argtypes = [vp, C.POINTER(u64), C.POINTER(u64), C.POINTER(u64)]
     lib.blink_sample_rows.argtypes = [C.c_int32, vp, u32, u32, vp, vp, vp]
@@ -224,10 +224,11 @@ class Engine:
         _check(self.lib, self.lib.blink_calibration_copy(self.h, int(nbytes)))
 
     def calibration_rates(self):
-        """(GB/s of a plain 1 GiB copy kernel, read + written; TFLOP/s of a register-only bf16 MFMA loop) on this device."""
-        c, m = C.c_double(), C.c_double()
-        _check(self.lib, self.lib.blink_calibration_rates(self.h, C.byref(c), C.byref(m)))
-        return c.value, m.value
+        """(GB/s of a plain 1 GiB copy kernel, read + written; TFLOP/s of a register-only bf16 MFMA loop; GB/s of a plain
+        read of 1 GiB) on this device."""
+        c, m, r = C.c_double(), C.c_double(), C.c_double()
+        _check(self.lib, self.lib.blink_calibration_rates(self.h, C.byref(c), C.byref(m), C.byref(r)))
+        return c.value, m.value, r.value
 
     def clock_sync(self):
         """(device_ns, host_ns on CLOCK_MONOTONIC, uncertainty_ns): the device clock read no later than host_ns."""

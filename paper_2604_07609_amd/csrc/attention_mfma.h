@@ -133,6 +133,7 @@ struct AttnMfmaShared {
   float m[ATTN_WAVES][16], l[ATTN_WAVES][16];
   float o[ATTN_WAVES][16][128];  // [wave][q head of the group (decode) or query of the tile (prefill)][dim]
   u32 cu_chunks[ATTN_META_MAX + 1], tok[ATTN_META_MAX], ctx[ATTN_META_MAX], bslot[ATTN_META_MAX], pos0[ATTN_META_MAX];
+  u32 next_item;   // decode items taken through the work counter: the item after the next one
 };
 
 // ---- decode: one workgroup per (sequence, kv head); its waves take the KV blocks round-robin ----------------------
@@ -246,6 +247,136 @@ __device__ __forceinline__ void attn_decode(const DevCtx& c, u32 layer, AttnMfma
     if (!more) break;
     cur = nxt;
     item = nitem;
+  }
+}
+
+// The decode items taken from the scheduler's chunk list through a work counter. What a launch loses against a plain
+// stream of the same tiles is fixed cost, not bandwidth (measured: a launch takes 26 us + 11.1 us per full item and
+// compute unit, and 11.1 us per 256 KB item is what a load-only kernel reaches): a second generation of workgroups
+// that starts, stages the batch metadata and waits for its first tiles when the first generation ends (only one
+// eight-wave workgroup with 256 registers per lane fits a compute unit), and the uneven ends of workgroups whose items
+// are dealt round-robin whatever their size. Here one workgroup per compute unit runs; its first two items are fixed
+// (workgroup id, then id + workgroups), every further one is the next of the list (one relaxed atomic add on the
+// launch's counter, issued a whole item ahead; the counters are zeroed by the scheduler step); the list has the full
+// chunks first, so the small items fill the ends; and an item's description is one 32-byte scalar load instead of a
+// search in metadata staged through LDS. A wave refills each of its four tile slots with the next item's tile as soon
+// as it has consumed the slot (the next item's description and queries are fetched first: loads complete in order, so
+// the queries must not queue behind the refills); the last item of a workgroup runs without the fetching ahead.
+// Results do not depend on which workgroup takes an item.
+template <int HD>
+__device__ __forceinline__ void attn_decode_dyn(const DevCtx& c, u32 layer, AttnMfmaShared& sh, u32 wg, u32 nwg) {
+  const u32 nwg_eff = max(1u, nwg / 2);          // the launch has two workgroups per compute unit, of which one is resident
+  if (wg >= nwg_eff) return;
+  const u32 G = c.nq / c.nkv;
+  const u32 lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lg = lane >> 4, lc = lane & 15;
+  const f16_t* Kc = (const f16_t*)c.kv + (u64)layer * c.kv_layer_stride;
+  const f16_t* Vc = Kc + c.kv_kv_stride;
+  const u64 tile = (u64)16 * HD;
+  static_assert(ATTN_CHUNK_BLOCKS == 4 * ATTN_WAVES, "four KV tiles per wave");
+  constexpr u32 nw = ATTN_WAVES;
+  const u32 n_full = c.meta->n_full_chunks, total_items = c.meta->n_chunks * c.nkv;
+  typedef const __attribute__((address_space(4))) u32 const_u32;
+  // a wave-uniform pointer for scalar loads (the builtin returns int: each half goes through u32 before it is widened)
+  auto scalar_ptr = [&](const void* p) {
+    const u64 a = (u64)p;
+    const u32 hi = (u32)__builtin_amdgcn_readfirstlane((u32)(a >> 32)), lo = (u32)__builtin_amdgcn_readfirstlane((u32)a);
+    return (const_u32*)(((u64)hi << 32) | (u64)lo);
+  };
+  struct Item { u32 ci, g, nch, t, ctx, b_lo, nb, id[4]; };
+  auto describe = [&](u32 item) {
+    Item it;
+    const u32 ord = item / c.nkv;
+    it.g = item % c.nkv;
+    const_u32* rec = scalar_ptr(c.chunk_rec + (ord < n_full ? ord : c.chunk_cap + (ord - n_full)));
+    it.t = rec[0]; it.ctx = rec[1];
+    const u32 bslot = rec[2], ch = rec[3];
+    it.ci = rec[4]; it.nch = rec[5];
+    const_u32* bt = scalar_ptr(c.block_tables + (u64)bslot * c.max_blocks_per_seq);
+    it.b_lo = ch * ATTN_CHUNK_BLOCKS;
+    it.nb = min((it.ctx + 15) / 16, it.b_lo + ATTN_CHUNK_BLOCKS) - it.b_lo;   // 1..32 blocks: up to four per wave
+    const u32 wfirst = w < it.nb ? w : 0u;
+#pragma unroll
+    for (u32 j = 0; j < 4; ++j) it.id[j] = bt[__builtin_amdgcn_readfirstlane(it.b_lo + ((w + j * nw < it.nb) ? w + j * nw : wfirst))];
+    return it;
+  };
+  auto load_q = [&](const Item& it, f16x8_t (&qq)[1][HD / 32]) {
+    // (columns past the group's heads repeat its last head: an unconditional load; their results are never stored)
+#pragma unroll
+    for (int st = 0; st < HD / 32; ++st)
+      qq[0][st] = ld_tile(c.qbuf + ((u64)it.t * c.nq + it.g * G + min(lc, G - 1)) * HD + st * 32 + lg * 8);
+  };
+  auto load_tile = [&](u32 id, u32 g, KVTile<HD>& tl) {
+    const u64 b0 = ((u64)id * c.nkv + g) * tile;
+    kv_load<HD>(Kc + b0, Vc + b0, tl);
+  };
+  u32 item = wg, nitem = wg + nwg_eff;
+  if (item >= total_items) return;
+  f16x8_t q[1][HD / 32];
+  KVTile<HD> t0, t1, t2, t3;
+  Item cur = describe(item);
+  load_q(cur, q);
+  load_tile(cur.id[0], cur.g, t0); load_tile(cur.id[1], cur.g, t1); load_tile(cur.id[2], cur.g, t2); load_tile(cur.id[3], cur.g, t3);
+  // merges the eight waves' partial results of item `it` through LDS (fixed order) and stores the item's result
+  auto finish = [&](const Item& it, const AttnAcc<HD, 1>& acc, u32 fetched) {
+    __syncthreads();   // the previous item's merge has finished reading LDS (and every wave has read the previous next_item)
+    if (threadIdx.x == 0) sh.next_item = fetched;
+    if (lg == 0) { sh.m[w][lc] = acc.m[0]; sh.l[w][lc] = acc.l[0]; }
+#pragma unroll
+    for (int d = 0; d < HD / 16; ++d)
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (lg * 4 + i < G) sh.o[w][lg * 4 + i][d * 16 + lc] = acc.o[0][d][i];
+    __syncthreads();
+    float* po = c.attn_part_o + ((u64)it.ci * c.nkv + it.g) * G * HD;
+    float* pml = c.attn_part_ml + ((u64)it.ci * c.nkv + it.g) * G * 2;
+    for (u32 idx = threadIdx.x; idx < G * HD; idx += blockDim.x) {
+      const u32 h = idx / HD, dim = idx % HD;
+      float M = -INFINITY;
+      for (u32 ww = 0; ww < nw; ++ww) M = fmaxf(M, sh.m[ww][h]);
+      float L = 0.f, O = 0.f;
+      for (u32 ww = 0; ww < nw; ++ww) {      // a wave without blocks has m = -inf and contributes 0
+        const float f = __expf(sh.m[ww][h] - M);
+        L += sh.l[ww][h] * f;
+        O += sh.o[ww][h][dim] * f;
+      }
+      if (it.nch == 1) {
+        c.aq[packed_off(it.t, (it.g * G + h) * HD + dim, c.TBS)] = f32_to_f16(O / L);
+      } else {
+        po[(u64)h * HD + dim] = O;
+        if (dim == 0) { pml[h * 2] = M; pml[h * 2 + 1] = L; }
+      }
+    }
+  };
+  while (nitem < total_items) {
+    // the item after the next one: asked for now, handed to the other waves through LDS at the merge
+    u32 fetched = ~0u;
+    if (threadIdx.x == 0) fetched = 2 * nwg_eff + atomicAdd(c.attn_ctr + layer, 1u);
+    const Item nxt = describe(nitem);
+    f16x8_t qn[1][HD / 32];
+    load_q(nxt, qn);
+    AttnAcc<HD, 1> acc;
+    attn_init(acc);
+    const u32 lim[1] = {cur.ctx};
+    auto us = [&](const KVTile<HD>& tl, u32 j) { const u32 i = w + j * nw; if (i < cur.nb) attn_block<HD, 1>(tl, q, (cur.b_lo + i) * 16, lim, acc); };
+    us(t0, 0); load_tile(nxt.id[0], nxt.g, t0);
+    us(t1, 1); load_tile(nxt.id[1], nxt.g, t1);
+    us(t2, 2); load_tile(nxt.id[2], nxt.g, t2);
+    us(t3, 3); load_tile(nxt.id[3], nxt.g, t3);
+    finish(cur, acc, fetched);
+    const u32 after = __builtin_amdgcn_readfirstlane(sh.next_item);     // written between the merge's barriers, rewritten only behind the next merge's first one
+#pragma unroll
+    for (int st = 0; st < HD / 32; ++st) q[0][st] = qn[0][st];
+    cur = nxt;
+    item = nitem;
+    nitem = after;
+  }
+  {   // the workgroup's last item: nothing to fetch ahead
+    AttnAcc<HD, 1> acc;
+    attn_init(acc);
+    const u32 lim[1] = {cur.ctx};
+    auto us = [&](const KVTile<HD>& tl, u32 j) { const u32 i = w + j * nw; if (i < cur.nb) attn_block<HD, 1>(tl, q, (cur.b_lo + i) * 16, lim, acc); };
+    us(t0, 0); us(t1, 1); us(t2, 2); us(t3, 3);
+    finish(cur, acc, ~0u);
   }
 }
 
@@ -491,7 +622,12 @@ __device__ __forceinline__ void phase_attention_mfma(const DevCtx& c, u32 layer,
     __syncthreads();
   }
   if (dec) {
-    if (c.hd == 64) attn_decode<64>(c, layer, sh, wg, nwg); else attn_decode<128>(c, layer, sh, wg, nwg);
+    // bit 23 of the tuning word (A/B): static items, one batch of loads per item, instead of the items taken through the work counter
+    if (c.tune_nw & 0x800000u) {
+      if (c.hd == 64) attn_decode<64>(c, layer, sh, wg, nwg); else attn_decode<128>(c, layer, sh, wg, nwg);
+    } else {
+      if (c.hd == 64) attn_decode_dyn<64>(c, layer, sh, wg, nwg); else attn_decode_dyn<128>(c, layer, sh, wg, nwg);
+    }
   }
   if (dec && pre && !pre_first) __syncthreads();   // the batch metadata in LDS is staged again for the other part
   if (pre && !pre_first) {

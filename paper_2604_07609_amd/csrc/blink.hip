@@ -109,6 +109,23 @@ __global__ void __launch_bounds__(BLK_THREADS) k_copy_calibration(const uint4* s
   for (u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (u64)gridDim.x * blockDim.x) dst[i] = src[i];
 }
 
+// plain read of `n16` 16-byte words, eight loads in flight per lane: what a kernel that only reads (the decode attention's KV
+// stream, a decode GEMM's weight stream) can reach. The sum is written only if it equals a value it never takes.
+__global__ void __launch_bounds__(BLK_THREADS) k_read_calibration(const uint4* src, u32* dst, u64 n16) {
+  const u64 stride = (u64)gridDim.x * blockDim.x;
+  u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
+  u32 acc = 0;
+  for (; i + 7 * stride < n16; i += 8 * stride) {
+    uint4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = src[i + u * stride];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+  }
+  for (; i < n16; i += stride) { const uint4 v = src[i]; acc ^= v.x ^ v.y ^ v.z ^ v.w; }
+  if (acc == 0x9E3779B9u) dst[(u64)blockIdx.x * blockDim.x + threadIdx.x] = acc;     // (the buffer holds zeros)
+}
+
 // register-only MFMA loop (sixteen independent 16x16x32 bf16 products per round and wave): the rate the matrix cores
 // sustain on this chip at its clocks, beside which the GEMM kernels' rates are read
 __global__ void __launch_bounds__(BLK_THREADS) k_mfma_calibration(float* dst, u32 rounds) {
@@ -504,6 +521,11 @@ static int init_impl(const blink_config* cfg, blink_engine* e) {
       const u64 rows = ((std::max<u64>(c.qkv_n, c.d) + 127) / 128) * 128;
       c.gemm_part_cap = 8ull * rows * 256;
       if (int rc = dalloc(e, &c.gemm_part, c.gemm_part_cap, false)) return rc;
+    }
+    {
+      c.chunk_cap = c.max_batch * ((c.max_seq_len + ATTN_CHUNK_TOKENS - 1) / ATTN_CHUNK_TOKENS);
+      if (int rc = dalloc(e, &c.chunk_rec, 2ull * c.chunk_cap)) return rc;
+      if (int rc = dalloc(e, &c.attn_ctr, c.n_layers)) return rc;
     }
     {
       const u64 chunks = (u64)c.max_batch * ((c.max_seq_len + ATTN_CHUNK_TOKENS - 1) / ATTN_CHUNK_TOKENS), G = c.nq / c.nkv;
@@ -1030,9 +1052,9 @@ extern "C" int blink_calibration_copy(blink_engine* e, uint64_t bytes) {
   return BLINK_OK;
 }
 
-extern "C" int blink_calibration_rates(blink_engine* e, double* copy_gbs, double* mfma_bf16_tflops) {
+extern "C" int blink_calibration_rates(blink_engine* e, double* copy_gbs, double* mfma_bf16_tflops, double* read_gbs) {
   g_err.clear();
-  if (!e || !copy_gbs || !mfma_bf16_tflops) return fail(BLINK_ERR_INVAL, "null argument");
+  if (!e || !copy_gbs || !mfma_bf16_tflops || !read_gbs) return fail(BLINK_ERR_INVAL, "null argument");
   if (e->loop_active.load()) return fail(BLINK_ERR_STATE, "stop the loop first");
   HIPCHK(hipSetDevice(e->cfg.device));
   hipEvent_t t0, t1;
@@ -1049,7 +1071,7 @@ extern "C" int blink_calibration_rates(blink_engine* e, double* copy_gbs, double
     return fail(BLINK_ERR_DEVICE, "no room for the two 1 GiB copy buffers");
   }
   const u32 rounds = 4096, wgs = e->grid * 2;        // the MFMA loop writes one float per lane: 1 MiB of the 64 MiB buffer
-  float best_copy = 0.f, best_mfma = 0.f;
+  float best_copy = 0.f, best_mfma = 0.f, best_read = 0.f;
   int rc = hipMemsetAsync(src, 0, copy_bytes, e->compute) == hipSuccess ? BLINK_OK : BLINK_ERR_DEVICE;
   for (int rep = 0; rep < 4 && rc == BLINK_OK; ++rep) {   // the first repetition warms up; the best of the rest counts
     float ms = 0.f;
@@ -1061,6 +1083,10 @@ extern "C" int blink_calibration_rates(blink_engine* e, double* copy_gbs, double
     hipLaunchKernelGGL(k_mfma_calibration, dim3(wgs), dim3(BLK_THREADS), 0, e->compute, (float*)e->calib_dst, rounds);
     if (hipEventRecord(t1, e->compute) != hipSuccess || hipEventSynchronize(t1) != hipSuccess || hipEventElapsedTime(&ms, t0, t1) != hipSuccess) { rc = BLINK_ERR_DEVICE; break; }
     if (rep && (best_mfma == 0.f || ms < best_mfma)) best_mfma = ms;
+    if (hipEventRecord(t0, e->compute) != hipSuccess) { rc = BLINK_ERR_DEVICE; break; }
+    hipLaunchKernelGGL(k_read_calibration, dim3(e->grid * 2), dim3(BLK_THREADS), 0, e->compute, (const uint4*)src, (u32*)e->calib_dst, n16);
+    if (hipEventRecord(t1, e->compute) != hipSuccess || hipEventSynchronize(t1) != hipSuccess || hipEventElapsedTime(&ms, t0, t1) != hipSuccess) { rc = BLINK_ERR_DEVICE; break; }
+    if (rep && (best_read == 0.f || ms < best_read)) best_read = ms;
   }
   (void)hipStreamSynchronize(e->compute);
   (void)hipFree(src);
@@ -1069,6 +1095,7 @@ extern "C" int blink_calibration_rates(blink_engine* e, double* copy_gbs, double
   (void)hipEventDestroy(t1);
   if (rc != BLINK_OK || hipGetLastError() != hipSuccess) return fail(BLINK_ERR_DEVICE, "calibration kernels failed");
   *copy_gbs = 2.0 * (double)(n16 * 16) / ((double)best_copy * 1e-3) / 1e9;   // bytes read + bytes written
+  *read_gbs = (double)(n16 * 16) / ((double)best_read * 1e-3) / 1e9;
   *mfma_bf16_tflops = (double)wgs * (BLK_THREADS / 64) * rounds * 16.0 * (2.0 * 16 * 16 * 32) / ((double)best_mfma * 1e-3) / 1e12;
   return BLINK_OK;
 }

@@ -105,7 +105,22 @@ struct IterMeta {
   u32 n_samples;        // sequences that sample a token in this iteration (all of them unless a prompt chunk leaves its prompt incomplete)
   u32 max_pref_ctx;     // longest context after this iteration among the sequences that process prompt tokens
   u32 n_sample_seqs;    // sequences that sample (n_samples counts logits rows: more than one per sequence with speculative decoding)
+  u32 n_full_chunks;    // decode attention work: chunks of ATTN_CHUNK_TOKENS context tokens that are full, listed first ...
+  u32 n_chunks;         // ... and all chunks (the others are the last, partly filled chunk of a context)
   u32 pad;
+};
+
+// One chunk of one decoding sequence's context, as the decode attention takes it from the scheduler (32 bytes: one scalar
+// load of a wave). Full chunks are listed first (DevCtx::chunk_rec[0 .. n_full_chunks)), the partly filled ones behind
+// them from DevCtx::chunk_rec[chunk_cap]: the workgroups take the list in order, largest items first.
+struct ChunkRec {
+  u32 tok;              // index of the sequence's token of this iteration
+  u32 ctx;              // context length after this iteration
+  u32 bslot;            // batch slot (row of the block table)
+  u32 ch;               // chunk index inside the context
+  u32 ci;               // chunk id: cu_chunks[sequence] + ch (where its partial result goes)
+  u32 nch;              // chunks of this context
+  u32 pad0, pad1;
 };
 
 struct TraceRec {       // mirrors blink_trace_record
@@ -204,6 +219,9 @@ struct DevCtx {
   u32* seq_pos0;        // [max_batch] position of the first token every sequence processes in this iteration
   u32* seq_ring;        // [max_batch] ring slot of a sequence that processes prompt tokens, ~0 for a decoding one
   u32* cu_qtiles;       // [max_batch+1] prefix sum of ceil(tokens/16) per sequence of the iteration
+  ChunkRec* chunk_rec;  // [2 * chunk_cap] (bf16 models; null otherwise)
+  u32 chunk_cap;        // max_batch * chunks of the longest context
+  u32* attn_ctr;        // [n_layers] work counters of the decode attention launches, zeroed by the scheduler step
   u32* cu_chunks;       // [max_batch+1] prefix sum of ceil(context/ATTN_CHUNK_TOKENS) per sequence (decode attention work items)
   i32* input_ids;       // [maxT]
   i32* positions;       // [maxT]

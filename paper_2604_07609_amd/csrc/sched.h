@@ -617,6 +617,7 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
   // iteration); with chunking all running, each with its share of the token budget. A sequence samples a token
   // unless its prompt is still incomplete after this iteration.
   u32 n_seqs = 0, n_tok = 0, n_alloc = 0, n_qt = 0, n_ch = 0, n_smp = 0, n_rows = 0, n_dec_seq = 0, max_q = 0, max_ctx = 0, max_pref = 0;
+  u32 n_full = 0, n_part = 0;     // full and partly filled chunks of the decoding sequences so far
   const u32 spec_k = (c.flags & 256u) ? c.spec_k : 0u;
   u64 n_ctx = 0;
   if (kind != KIND_IDLE) {
@@ -656,7 +657,12 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
       }
       u32 tots, tota, tott, totq, totc, totm, totx;
       const u32 ctx_after = in ? pos0 + ntok : 0u;
-      const u32 coff = n_ch + block_excl_scan((in && !multi) ? (ctx_after + ATTN_CHUNK_TOKENS - 1) / ATTN_CHUNK_TOKENS : 0u, totc, sh.wave_part);
+      const u32 nch = (in && !multi) ? (ctx_after + ATTN_CHUNK_TOKENS - 1) / ATTN_CHUNK_TOKENS : 0u;
+      const u32 nfull = (in && !multi) ? ctx_after / ATTN_CHUNK_TOKENS : 0u;
+      u32 totf, totp;
+      const u32 foff = n_full + block_excl_scan(nfull, totf, sh.wave_part);
+      const u32 poff = n_part + block_excl_scan(nch - nfull, totp, sh.wave_part2);
+      const u32 coff = n_ch + block_excl_scan(nch, totc, sh.wave_part);
       const u32 qoff = n_qt + block_excl_scan(multi ? (ntok + 15) / 16 : 0u, totq, sh.wave_part2);
       const u32 si = n_seqs + block_excl_scan(in ? 1u : 0u, tots, sh.wave_part);
       const u32 aoff = n_alloc + block_excl_scan(nalloc, tota, sh.wave_part2);
@@ -687,6 +693,13 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
         c.seq_pos0[si] = pos0;
         c.seq_ring[si] = pref ? r.ring_slot : ~0u;
         c.seq_len[si] = ctx_after;
+        if (c.chunk_rec) {      // the decode attention's work list: full chunks first, the partly filled ones behind them
+          for (u32 j = 0; j < nch; ++j) {
+            ChunkRec rec;
+            rec.tok = toff; rec.ctx = ctx_after; rec.bslot = b; rec.ch = j; rec.ci = coff + j; rec.nch = nch; rec.pad0 = rec.pad1 = 0;
+            c.chunk_rec[j < nfull ? foff + j : c.chunk_cap + poff] = rec;
+          }
+        }
         if (smp) {
           for (u32 j = 0; j < nrow; ++j) c.last_idx[ri + j] = toff + ntok - nrow + j;
           c.sample_bslot[mi] = b;
@@ -723,6 +736,8 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
       n_tok += tott;
       n_qt += totq;
       n_ch += totc;
+      n_full += totf;
+      n_part += totp;
       n_smp += totm;
       n_rows += totr;
     }
@@ -817,6 +832,8 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
   }
 
   // ---- write back ------------------------------------------------------------------------------------------
+  if (c.attn_ctr)
+    for (u32 l = tid; l < c.n_layers; l += BLK_THREADS) c.attn_ctr[l] = 0;     // work counters of this iteration's decode attention launches
   if (tid == 0) {
     const u64 now = dev_now_ns();
     ss->free_top = top;
@@ -833,6 +850,8 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
     m->n_seqs = n_seqs;
     m->n_samples = n_rows;
     m->n_sample_seqs = n_smp;
+    m->n_full_chunks = n_full;
+    m->n_chunks = n_full + n_part;
     m->n_tokens = n_tok;
     m->max_q_len = max_q;
     m->max_ctx = max_ctx;

@@ -256,14 +256,15 @@ def test_init_rejects_more_bf16_batch_slots_than_attention_stages(lib):
 
 
 def test_calibration_rates_are_within_the_published_peaks(lib):
-    """The plain copy kernel and the register-only MFMA loop: positive, and not above the chip's HBM and bf16 MFMA peaks."""
+    """The plain copy and read kernels and the register-only MFMA loop: positive, and not above the chip's HBM and bf16 MFMA peaks."""
     cfg, eng, raw, blob = setup("mini_gqa", 91)
     e = lib.Engine(cfg, eng, blob)
     try:
-        copy_gbs, mfma_tflops = e.calibration_rates()
+        copy_gbs, mfma_tflops, read_gbs = e.calibration_rates()
     finally:
         e.shutdown()
     assert 500.0 < copy_gbs < 8000.0 * 1.05
+    assert 500.0 < read_gbs < 8000.0 * 1.05
     assert 100.0 < mfma_tflops < 2500.0 * 1.05
 
 
