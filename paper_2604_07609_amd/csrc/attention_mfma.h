@@ -250,19 +250,23 @@ __device__ __forceinline__ void attn_decode(const DevCtx& c, u32 layer, AttnMfma
   }
 }
 
-// The decode items taken from the scheduler's chunk list through a work counter. What a launch loses against a plain
-// stream of the same tiles is fixed cost, not bandwidth (measured: a launch takes 26 us + 11.1 us per full item and
+// The decode items taken from the scheduler's work list through a counter. What a launch loses against a plain
+// stream of the same tiles is fixed cost, not bandwidth (measured: a launch took 26 us + 11.1 us per full item and
 // compute unit, and 11.1 us per 256 KB item is what a load-only kernel reaches): a second generation of workgroups
 // that starts, stages the batch metadata and waits for its first tiles when the first generation ends (only one
 // eight-wave workgroup with 256 registers per lane fits a compute unit), and the uneven ends of workgroups whose items
 // are dealt round-robin whatever their size. Here one workgroup per compute unit runs; its first two items are fixed
 // (workgroup id, then id + workgroups), every further one is the next of the list (one relaxed atomic add on the
-// launch's counter, issued a whole item ahead; the counters are zeroed by the scheduler step); the list has the full
-// chunks first, so the small items fill the ends; and an item's description is one 32-byte scalar load instead of a
-// search in metadata staged through LDS. A wave refills each of its four tile slots with the next item's tile as soon
-// as it has consumed the slot (the next item's description and queries are fetched first: loads complete in order, so
-// the queries must not queue behind the refills); the last item of a workgroup runs without the fetching ahead.
-// Results do not depend on which workgroup takes an item.
+// launch's counter, issued while the item before it is still running; the counters are zeroed by the scheduler step);
+// the list has the large items first, so the small ones fill the ends; and an item's description is one 32-byte scalar
+// load instead of a search in metadata staged through LDS. An item is a run of KV blocks of one sequence and one kv head,
+// walked in rounds of 32 blocks (four tile slots per wave) with the running maxima, sums and outputs kept in registers
+// from round to round, and merged across the waves once, at its end: one chunk of a context (its partial result is
+// merged with the other chunks' by the combine kernel) or, when the scheduler has many sequences to hand out, a whole
+// context (no partial results). A wave refills each tile slot with the tile of the next round (of the same item or of
+// the next one) as soon as it has consumed the slot; the next round's description and queries are fetched first (loads
+// complete in order, so the queries must not queue behind the refills); the workgroup's last round runs without the
+// fetching ahead. Results do not depend on which workgroup takes an item.
 template <int HD>
 __device__ __forceinline__ void attn_decode_dyn(const DevCtx& c, u32 layer, AttnMfmaShared& sh, u32 wg, u32 nwg) {
   const u32 nwg_eff = max(1u, nwg / 2);          // the launch has two workgroups per compute unit, of which one is resident
@@ -282,42 +286,45 @@ __device__ __forceinline__ void attn_decode_dyn(const DevCtx& c, u32 layer, Attn
     const u32 hi = (u32)__builtin_amdgcn_readfirstlane((u32)(a >> 32)), lo = (u32)__builtin_amdgcn_readfirstlane((u32)a);
     return (const_u32*)(((u64)hi << 32) | (u64)lo);
   };
-  struct Item { u32 ci, g, nch, t, ctx, b_lo, nb, id[4]; };
-  auto describe = [&](u32 item) {
-    Item it;
-    const u32 ord = item / c.nkv;
-    it.g = item % c.nkv;
-    const_u32* rec = scalar_ptr(c.chunk_rec + (ord < n_full ? ord : c.chunk_cap + (ord - n_full)));
-    it.t = rec[0]; it.ctx = rec[1];
-    const u32 bslot = rec[2], ch = rec[3];
-    it.ci = rec[4]; it.nch = rec[5];
-    const_u32* bt = scalar_ptr(c.block_tables + (u64)bslot * c.max_blocks_per_seq);
-    it.b_lo = ch * ATTN_CHUNK_BLOCKS;
-    it.nb = min((it.ctx + 15) / 16, it.b_lo + ATTN_CHUNK_BLOCKS) - it.b_lo;   // 1..32 blocks: up to four per wave
-    const u32 wfirst = w < it.nb ? w : 0u;
+  // one round of an item: blocks b_lo .. b_lo + nb of the item's run (which ends at b_end), this wave's four block ids
+  struct Round { u32 ci, g, nch, t, ctx, bslot, b_lo, b_end, nb, id[4]; };
+  auto block_ids = [&](Round& r) {       // (slots past the round's end repeat its first block)
+    const_u32* bt = scalar_ptr(c.block_tables + (u64)r.bslot * c.max_blocks_per_seq);
+    r.nb = min(r.b_end, r.b_lo + ATTN_CHUNK_BLOCKS) - r.b_lo;   // 1..32 blocks: up to four per wave
+    const u32 wfirst = w < r.nb ? w : 0u;
 #pragma unroll
-    for (u32 j = 0; j < 4; ++j) it.id[j] = bt[__builtin_amdgcn_readfirstlane(it.b_lo + ((w + j * nw < it.nb) ? w + j * nw : wfirst))];
-    return it;
+    for (u32 j = 0; j < 4; ++j) r.id[j] = bt[__builtin_amdgcn_readfirstlane(r.b_lo + ((w + j * nw < r.nb) ? w + j * nw : wfirst))];
   };
-  auto load_q = [&](const Item& it, f16x8_t (&qq)[1][HD / 32]) {
+  auto first_round = [&](u32 item) {
+    Round r;
+    const u32 ord = item / c.nkv;
+    r.g = item % c.nkv;
+    const_u32* rec = scalar_ptr(c.chunk_rec + (ord < n_full ? ord : c.chunk_cap + (ord - n_full)));
+    r.t = rec[0]; r.ctx = rec[1]; r.bslot = rec[2];
+    r.b_lo = rec[3] * ATTN_CHUNK_BLOCKS;
+    r.ci = rec[4]; r.nch = rec[5]; r.b_end = rec[6];
+    block_ids(r);
+    return r;
+  };
+  auto load_q = [&](const Round& r, f16x8_t (&qq)[1][HD / 32]) {
     // (columns past the group's heads repeat its last head: an unconditional load; their results are never stored)
 #pragma unroll
     for (int st = 0; st < HD / 32; ++st)
-      qq[0][st] = ld_tile(c.qbuf + ((u64)it.t * c.nq + it.g * G + min(lc, G - 1)) * HD + st * 32 + lg * 8);
+      qq[0][st] = ld_tile(c.qbuf + ((u64)r.t * c.nq + r.g * G + min(lc, G - 1)) * HD + st * 32 + lg * 8);
   };
   auto load_tile = [&](u32 id, u32 g, KVTile<HD>& tl) {
     const u64 b0 = ((u64)id * c.nkv + g) * tile;
     kv_load<HD>(Kc + b0, Vc + b0, tl);
   };
-  u32 item = wg, nitem = wg + nwg_eff;
-  if (item >= total_items) return;
+  u32 nitem = wg + nwg_eff;
+  if (wg >= total_items) return;
   f16x8_t q[1][HD / 32];
   KVTile<HD> t0, t1, t2, t3;
-  Item cur = describe(item);
+  Round cur = first_round(wg);
   load_q(cur, q);
   load_tile(cur.id[0], cur.g, t0); load_tile(cur.id[1], cur.g, t1); load_tile(cur.id[2], cur.g, t2); load_tile(cur.id[3], cur.g, t3);
-  // merges the eight waves' partial results of item `it` through LDS (fixed order) and stores the item's result
-  auto finish = [&](const Item& it, const AttnAcc<HD, 1>& acc, u32 fetched) {
+  // merges the eight waves' partial results of the item of round `it` through LDS (fixed order) and stores the item's result
+  auto finish = [&](const Round& it, const AttnAcc<HD, 1>& acc, u32 fetched) {
     __syncthreads();   // the previous item's merge has finished reading LDS (and every wave has read the previous next_item)
     if (threadIdx.x == 0) sh.next_item = fetched;
     if (lg == 0) { sh.m[w][lc] = acc.m[0]; sh.l[w][lc] = acc.l[0]; }
@@ -347,32 +354,41 @@ __device__ __forceinline__ void attn_decode_dyn(const DevCtx& c, u32 layer, Attn
       }
     }
   };
-  while (nitem < total_items) {
-    // the item after the next one: asked for now, handed to the other waves through LDS at the merge
+  AttnAcc<HD, 1> acc;
+  attn_init(acc);
+  for (;;) {
+    const bool last_round = cur.b_lo + ATTN_CHUNK_BLOCKS >= cur.b_end;     // of the item
+    if (last_round && nitem >= total_items) break;                          // and of the workgroup
+    // the next round: of the same item, or the first of the next item (then the item after that one is asked for now
+    // and handed to the other waves through LDS at the merge)
     u32 fetched = ~0u;
-    if (threadIdx.x == 0) fetched = 2 * nwg_eff + atomicAdd(c.attn_ctr + layer, 1u);
-    const Item nxt = describe(nitem);
+    Round nxt;
+    if (last_round) {
+      if (threadIdx.x == 0) fetched = 2 * nwg_eff + atomicAdd(c.attn_ctr + layer, 1u);
+      nxt = first_round(nitem);
+    } else {
+      nxt = cur;
+      nxt.b_lo = cur.b_lo + ATTN_CHUNK_BLOCKS;
+      block_ids(nxt);
+    }
     f16x8_t qn[1][HD / 32];
     load_q(nxt, qn);
-    AttnAcc<HD, 1> acc;
-    attn_init(acc);
     const u32 lim[1] = {cur.ctx};
     auto us = [&](const KVTile<HD>& tl, u32 j) { const u32 i = w + j * nw; if (i < cur.nb) attn_block<HD, 1>(tl, q, (cur.b_lo + i) * 16, lim, acc); };
     us(t0, 0); load_tile(nxt.id[0], nxt.g, t0);
     us(t1, 1); load_tile(nxt.id[1], nxt.g, t1);
     us(t2, 2); load_tile(nxt.id[2], nxt.g, t2);
     us(t3, 3); load_tile(nxt.id[3], nxt.g, t3);
-    finish(cur, acc, fetched);
-    const u32 after = __builtin_amdgcn_readfirstlane(sh.next_item);     // written between the merge's barriers, rewritten only behind the next merge's first one
+    if (last_round) {
+      finish(cur, acc, fetched);
+      nitem = __builtin_amdgcn_readfirstlane(sh.next_item);     // written between the merge's barriers, rewritten only behind the next merge's first one
+      attn_init(acc);
+    }
 #pragma unroll
     for (int st = 0; st < HD / 32; ++st) q[0][st] = qn[0][st];
     cur = nxt;
-    item = nitem;
-    nitem = after;
   }
-  {   // the workgroup's last item: nothing to fetch ahead
-    AttnAcc<HD, 1> acc;
-    attn_init(acc);
+  {   // the workgroup's last round: nothing to fetch ahead
     const u32 lim[1] = {cur.ctx};
     auto us = [&](const KVTile<HD>& tl, u32 j) { const u32 i = w + j * nw; if (i < cur.nb) attn_block<HD, 1>(tl, q, (cur.b_lo + i) * 16, lim, acc); };
     us(t0, 0); us(t1, 1); us(t2, 2); us(t3, 3);

@@ -269,6 +269,7 @@ static int init_impl(const blink_config* cfg, blink_engine* e) {
   hipDeviceProp_t prop;
   HIPCHK(hipGetDeviceProperties(&prop, cfg->device));
   e->n_cu = prop.multiProcessorCount;
+  e->ctx.n_cu = (u32)e->n_cu;
   e->grid = (u32)e->n_cu * 2;
   HIPCHK(hipStreamCreateWithFlags(&e->compute, hipStreamNonBlocking));
   HIPCHK(hipStreamCreateWithFlags(&e->s_in, hipStreamNonBlocking));

@@ -110,17 +110,21 @@ struct IterMeta {
   u32 pad;
 };
 
-// One chunk of one decoding sequence's context, as the decode attention takes it from the scheduler (32 bytes: one scalar
-// load of a wave). Full chunks are listed first (DevCtx::chunk_rec[0 .. n_full_chunks)), the partly filled ones behind
-// them from DevCtx::chunk_rec[chunk_cap]: the workgroups take the list in order, largest items first.
+// One work item of the decode attention (times the kv heads), as the kernel takes it from the scheduler (32 bytes: one
+// scalar load of a wave): a run of KV blocks of one decoding sequence that one workgroup walks, ATTN_CHUNK_TOKENS at a
+// time, into one result. With few sequences an item is one chunk of a context (so that the chip has enough items; the
+// chunks' partial results are merged by the combine kernel): full chunks are listed first (DevCtx::chunk_rec[0 ..
+// n_full_chunks)), the partly filled ones behind them from DevCtx::chunk_rec[chunk_cap]. With many sequences an item is
+// a whole context (no partial results, fewer merges), listed longest first. The workgroups take the list in order.
 struct ChunkRec {
   u32 tok;              // index of the sequence's token of this iteration
   u32 ctx;              // context length after this iteration
   u32 bslot;            // batch slot (row of the block table)
-  u32 ch;               // chunk index inside the context
-  u32 ci;               // chunk id: cu_chunks[sequence] + ch (where its partial result goes)
-  u32 nch;              // chunks of this context
-  u32 pad0, pad1;
+  u32 ch;               // first chunk of the run inside the context
+  u32 ci;               // chunk id of the result: cu_chunks[sequence] + ch (where a partial result goes)
+  u32 nch;              // results of this context (1: the item's result is final)
+  u32 b_end;            // KV block behind the run's last one
+  u32 pad1;
 };
 
 struct TraceRec {       // mirrors blink_trace_record
@@ -177,6 +181,7 @@ struct DevCtx {
   u32 bs, n_blocks, max_batch, max_seq_len, max_prefill_tokens, ring_slots, max_blocks_per_seq, maxT;
   i32 eos;
   u32 flags, trace_cap, qkv_n;
+  u32 n_cu;             // compute units of the device
   u64 idle_poll_ns;     // how long the scheduler step of an empty engine polls the ring before it reports an idle iteration
   // ring
   SlotStatus* status;

@@ -45,6 +45,8 @@ struct SchedShared {
   u32 seq_ring[SCHED_MAX_BATCH];
   u32 seq_pos0[SCHED_MAX_BATCH];
   u32 seq_P[SCHED_MAX_BATCH];        // prompt length: positions beyond it take the request's own output tokens (a resumed request)
+  u32 dec_key[SCHED_MAX_BATCH];      // per batch slot: context length of a decoding sequence (0: none), and its sequence index
+  u32 dec_si[SCHED_MAX_BATCH];
   u32 flag;
   u32 exit_idle;
   u64 chain;
@@ -618,6 +620,9 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
   // unless its prompt is still incomplete after this iteration.
   u32 n_seqs = 0, n_tok = 0, n_alloc = 0, n_qt = 0, n_ch = 0, n_smp = 0, n_rows = 0, n_dec_seq = 0, max_q = 0, max_ctx = 0, max_pref = 0;
   u32 n_full = 0, n_part = 0;     // full and partly filled chunks of the decoding sequences so far
+  // Work items of the decode attention: chunks of the contexts, or, with at least three sequence x kv-head pairs per
+  // compute unit, whole contexts (bit 22 of the tuning word: always; bit 23, the kernel with static items: never)
+  const bool group = c.chunk_rec && !(c.tune_nw & 0x800000u) && ((c.tune_nw & 0x400000u) || (u64)nrun * c.nkv >= 3ull * c.n_cu);
   const u32 spec_k = (c.flags & 256u) ? c.spec_k : 0u;
   u64 n_ctx = 0;
   if (kind != KIND_IDLE) {
@@ -657,8 +662,9 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
       }
       u32 tots, tota, tott, totq, totc, totm, totx;
       const u32 ctx_after = in ? pos0 + ntok : 0u;
-      const u32 nch = (in && !multi) ? (ctx_after + ATTN_CHUNK_TOKENS - 1) / ATTN_CHUNK_TOKENS : 0u;
-      const u32 nfull = (in && !multi) ? ctx_after / ATTN_CHUNK_TOKENS : 0u;
+      const bool dec_seq = in && !multi;
+      const u32 nch = !dec_seq ? 0u : group ? 1u : (ctx_after + ATTN_CHUNK_TOKENS - 1) / ATTN_CHUNK_TOKENS;
+      const u32 nfull = (!dec_seq || group) ? 0u : ctx_after / ATTN_CHUNK_TOKENS;
       u32 totf, totp;
       const u32 foff = n_full + block_excl_scan(nfull, totf, sh.wave_part);
       const u32 poff = n_part + block_excl_scan(nch - nfull, totp, sh.wave_part2);
@@ -693,10 +699,11 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
         c.seq_pos0[si] = pos0;
         c.seq_ring[si] = pref ? r.ring_slot : ~0u;
         c.seq_len[si] = ctx_after;
-        if (c.chunk_rec) {      // the decode attention's work list: full chunks first, the partly filled ones behind them
+        if (c.chunk_rec && !group) {      // the decode attention's work list: full chunks first, the partly filled ones behind them
           for (u32 j = 0; j < nch; ++j) {
             ChunkRec rec;
-            rec.tok = toff; rec.ctx = ctx_after; rec.bslot = b; rec.ch = j; rec.ci = coff + j; rec.nch = nch; rec.pad0 = rec.pad1 = 0;
+            rec.tok = toff; rec.ctx = ctx_after; rec.bslot = b; rec.ch = j; rec.ci = coff + j; rec.nch = nch;
+            rec.b_end = min((ctx_after + 15) / 16, (j + 1) * (u32)(ATTN_CHUNK_TOKENS / 16)); rec.pad1 = 0;
             c.chunk_rec[j < nfull ? foff + j : c.chunk_cap + poff] = rec;
           }
         }
@@ -727,6 +734,7 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
         }
         r.ctx_len = ctx_after;
       }
+      if (group && b < c.max_batch) { sh.dec_key[b] = dec_seq ? ctx_after : 0u; sh.dec_si[b] = si; }
       max_q = max(max_q, block_max(ntok, sh.wave_part2));
       max_ctx = max(max_ctx, block_max(ctx_after, sh.wave_part));
       max_pref = max(max_pref, block_max(multi ? ctx_after : 0u, sh.wave_part2));
@@ -743,6 +751,28 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
     }
     top -= n_alloc;
     __syncthreads();
+    if (group) {
+      // whole contexts, longest first: a sequence's place in the list is the number of decoding sequences with a longer
+      // context (or an equal one in a lower batch slot)
+      for (u32 base = 0; base < c.max_batch; base += BLK_THREADS) {
+        const u32 b = base + tid;
+        const u32 key = b < c.max_batch ? sh.dec_key[b] : 0u;
+        if (key) {
+          u32 rank = 0;
+          for (u32 b2 = 0; b2 < c.max_batch; ++b2) {
+            const u32 k2 = sh.dec_key[b2];
+            rank += (k2 > key || (k2 == key && b2 < b)) ? 1u : 0u;
+          }
+          const u32 si = sh.dec_si[b];
+          ChunkRec rec;
+          rec.tok = c.cu_seqlens[si]; rec.ctx = key; rec.bslot = b; rec.ch = 0; rec.ci = c.cu_chunks[si]; rec.nch = 1;
+          rec.b_end = (key + 15) / 16; rec.pad1 = 0;
+          c.chunk_rec[rank] = rec;
+        }
+      }
+      n_full = n_ch;      // one item per decoding sequence, all in the first list
+      n_part = 0;
+    }
     if (tid == 0) {
       c.cu_seqlens[n_seqs] = n_tok;
       c.cu_qtiles[n_seqs] = n_qt;

@@ -31,6 +31,10 @@ MODEL_CONFIGS = {
                     vocab=1900, dtype=1, rms_eps=1e-5, rope_theta=10000.0),
     "mini_g8": dict(n_layers=2, d_model=512, n_q_heads=16, n_kv_heads=2, head_dim=64, d_ffn=768,
                     vocab=2100, dtype=1, rms_eps=1e-5, rope_theta=500000.0),
+    # eight kv heads in one small layer: enough (sequence, chunk, kv head) items of decode attention at 40 sequences that
+    # workgroups take items beyond their first two
+    "mini_kv8": dict(n_layers=1, d_model=256, n_q_heads=16, n_kv_heads=8, head_dim=64, d_ffn=512,
+                     vocab=1500, dtype=1, rms_eps=1e-5, rope_theta=10000.0),
     # mixture of experts: d_ffn is the width of one expert
     "mini_moe": dict(n_layers=2, d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=64, d_ffn=96, n_experts=8, n_active=2,
                      vocab=1500, dtype=1, rms_eps=1e-5, rope_theta=10000.0),
@@ -67,6 +71,8 @@ ENGINE_CONFIGS = {
                     max_prefill_tokens=700, ring_slots=32, eos_token_id=-1),
     "mini_g8": dict(kv_block_size=16, kv_num_blocks=96, max_batch=6, max_seq_len=700,
                     max_prefill_tokens=700, ring_slots=32, eos_token_id=-1),
+    "mini_kv8": dict(kv_block_size=16, kv_num_blocks=3200, max_batch=40, max_seq_len=1300,
+                     max_prefill_tokens=4096, ring_slots=64, eos_token_id=-1),
     "mini_moe": dict(kv_block_size=16, kv_num_blocks=96, max_batch=6, max_seq_len=160,
                      max_prefill_tokens=256, ring_slots=32, eos_token_id=-1),
     "mini_moe16": dict(kv_block_size=16, kv_num_blocks=400, max_batch=48, max_seq_len=700,

@@ -141,12 +141,20 @@ def test_bf16_large_prefill_iterations(lib, tune):
     print("large prefill: worst relative logit error", worst)
 
 
-@pytest.mark.parametrize("name,prompts", [("mini_gqa128", [1030, 2070, 7, 1023]), ("mini_gqa", [1030, 2070, 7, 1023]),
-                                          ("mini_gqa128", [6300, 40])])
-def test_bf16_long_contexts(lib, name, prompts):
+# decode attention: bit 22 of the tuning word hands out whole contexts as work items (the scheduler does so by itself
+# only with many sequences), bit 23 selects the kernel with static items
+WHOLE_CONTEXTS, STATIC_ITEMS = 0x400000, 0x800000
+
+
+@pytest.mark.parametrize("name,prompts,tune", [("mini_gqa128", [1030, 2070, 7, 1023], 0), ("mini_gqa", [1030, 2070, 7, 1023], 0),
+                                               ("mini_gqa128", [6300, 40], 0),
+                                               ("mini_gqa128", [1030, 2070, 7, 1023], WHOLE_CONTEXTS), ("mini_gqa", [1030, 2070, 7, 1023], WHOLE_CONTEXTS),
+                                               ("mini_gqa128", [6300, 40], WHOLE_CONTEXTS), ("mini_gqa", [1030, 2070, 7, 1023], STATIC_ITEMS)])
+def test_bf16_long_contexts(lib, name, prompts, tune):
     """Contexts of 500..2100 tokens: decode attention works in 512-token chunks whose partial results a second
     kernel merges (up to 12 chunks fetched together; the 6300-token context has 13 and takes the kernel's general
-    loop); prefill attention walks up to 394 KV blocks; one short context shares the batch."""
+    loop), or walks a whole context in rounds of 512 tokens; prefill attention walks up to 394 KV blocks; one short
+    context shares the batch."""
     cfg, eng, raw, blob = setup(name, 37)
     top = max(prompts)
     eng = dict(eng, max_seq_len=top + 130, kv_num_blocks=(sum(prompts) + 16 * len(prompts)) // 16 + 40,
@@ -156,8 +164,23 @@ def test_bf16_long_contexts(lib, name, prompts):
     for i, P in enumerate(prompts):
         reqs.append(dict(arrival_s=0.0, prompt=rng.integers(0, cfg["vocab"], P).astype(np.int32), max_new_tokens=5,
                          temperature=0.0, top_k=0, top_p=1.0, seed=i))
-    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2)
+    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2, tune=tune)
     print(name, "long contexts: worst relative logit error", worst)
+
+
+@pytest.mark.parametrize("tune", [0, WHOLE_CONTEXTS])
+def test_decode_attention_work_list(lib, tune):
+    """40 sequences x 8 kv heads with contexts of 20..1200 tokens: as chunks about 700 items, as whole contexts 320, for
+    256 workgroups that each take two fixed items and every further one through the launch's counter; the list has the
+    large items first. Results must not depend on who takes what: logits against the oracle every iteration."""
+    cfg, eng, raw, blob = setup("mini_kv8", 49)
+    rng = np.random.default_rng(49)
+    plens = [int(x) for x in rng.integers(20, 1200, 40)]
+    plens[:4] = [1200, 511, 512, 513]
+    reqs = [dict(arrival_s=0.0, prompt=rng.integers(0, cfg["vocab"], P).astype(np.int32), max_new_tokens=4 if i % 3 else 2,
+                 temperature=0.0, top_k=0, top_p=1.0, seed=i) for i, P in enumerate(plens)]
+    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2, tune=tune)
+    print("work list, tune", hex(tune), "worst relative logit error", worst)
 
 
 @pytest.mark.parametrize("name,wpi", [("mini_gqa128", 1), ("mini_gqa128", 2), ("mini_gqa", 4), ("mini_gqa128", 8), ("mini_gqa", 8)])
