@@ -599,6 +599,7 @@ extern "C" int blink_init(const blink_config* cfg, blink_engine** out) {
   if (cfg->dtype == 1 && cfg->max_batch > ATTN_META_MAX)
     return fail(BLINK_ERR_INVAL, "bf16 models take at most %d batch slots (attention keeps the batch metadata in LDS)", ATTN_META_MAX);
   if (!cfg->max_seq_len || !cfg->max_prefill_tokens) return fail(BLINK_ERR_INVAL, "max_seq_len and max_prefill_tokens must be positive");
+  if (cfg->max_seq_len >= (1u << 22)) return fail(BLINK_ERR_INVAL, "max_seq_len must be below 2^22 (the scheduler sorts contexts by a 32-bit key)");
   if ((cfg->flags & BLINK_FLAG_CHUNKED_PREFILL) && (cfg->flags & BLINK_FLAG_PREEMPTION))
     return fail(BLINK_ERR_INVAL, "preemption is built for the plain (pause-and-resume) mode, not together with chunked prefill");
   if ((cfg->flags & BLINK_FLAG_PREFIX_CACHE) && (cfg->flags & (BLINK_FLAG_CHUNKED_PREFILL | BLINK_FLAG_PREEMPTION)))

@@ -45,8 +45,9 @@ struct SchedShared {
   u32 seq_ring[SCHED_MAX_BATCH];
   u32 seq_pos0[SCHED_MAX_BATCH];
   u32 seq_P[SCHED_MAX_BATCH];        // prompt length: positions beyond it take the request's own output tokens (a resumed request)
-  u32 dec_key[SCHED_MAX_BATCH];      // per batch slot: context length of a decoding sequence (0: none), and its sequence index
+  alignas(16) u32 dec_key[SCHED_MAX_BATCH];   // per batch slot: sort key of a decoding sequence (0: none), its chunk id ...
   u32 dec_si[SCHED_MAX_BATCH];
+  u32 dec_tok[SCHED_MAX_BATCH];      // ... and the index of its token
   u32 flag;
   u32 exit_idle;
   u64 chain;
@@ -160,6 +161,31 @@ __device__ __forceinline__ u32 block_excl_scan(u32 v, u32& total, u32* part) {
   }
   total = tot;
   return base + inc - v;
+}
+
+// Two exclusive prefix sums at once (one pair of barriers): the values travel as the halves of a 64-bit word.
+__device__ __forceinline__ void block_excl_scan2(u32 a, u32 b, u32& off_a, u32& off_b, u32& tot_a, u32& tot_b, u64* part) {
+  const u32 lane = threadIdx.x & 63u, w = threadIdx.x >> 6;
+  const u64 v = (u64)a | ((u64)b << 32);
+  u64 inc = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const u32 lo = __shfl_up((u32)inc, o), hi = __shfl_up((u32)(inc >> 32), o);
+    if (lane >= (u32)o) inc += (u64)lo | ((u64)hi << 32);
+  }
+  __syncthreads();
+  if (lane == 63u) part[w] = inc;
+  __syncthreads();
+  u64 base = 0, tot = 0;
+#pragma unroll
+  for (u32 i = 0; i < BLK_THREADS / WAVE; ++i) {
+    const u64 s = part[i];
+    if (i < w) base += s;
+    tot += s;
+  }
+  const u64 ex = base + inc - v;
+  off_a = (u32)ex; off_b = (u32)(ex >> 32);
+  tot_a = (u32)tot; tot_b = (u32)(tot >> 32);
 }
 
 __device__ __forceinline__ u32 block_max(u32 v, u32* part) {
@@ -660,25 +686,19 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
         else ntok = 0;
         nrow = smp ? ((spec_k && !pref) ? ntok : 1u) : 0u;    // logits rows: the last token; every token of a decoding sequence when drafts are verified
       }
-      u32 tots, tota, tott, totq, totc, totm, totx;
+      u32 tots, tota, tott, totq, totc, totm, totx, totf, totp, totr, totd;
       const u32 ctx_after = in ? pos0 + ntok : 0u;
       const bool dec_seq = in && !multi;
       const u32 nch = !dec_seq ? 0u : group ? 1u : (ctx_after + ATTN_CHUNK_TOKENS - 1) / ATTN_CHUNK_TOKENS;
       const u32 nfull = (!dec_seq || group) ? 0u : ctx_after / ATTN_CHUNK_TOKENS;
-      u32 totf, totp;
-      const u32 foff = n_full + block_excl_scan(nfull, totf, sh.wave_part);
-      const u32 poff = n_part + block_excl_scan(nch - nfull, totp, sh.wave_part2);
-      const u32 coff = n_ch + block_excl_scan(nch, totc, sh.wave_part);
-      const u32 qoff = n_qt + block_excl_scan(multi ? (ntok + 15) / 16 : 0u, totq, sh.wave_part2);
-      const u32 si = n_seqs + block_excl_scan(in ? 1u : 0u, tots, sh.wave_part);
-      const u32 aoff = n_alloc + block_excl_scan(nalloc, tota, sh.wave_part2);
-      const u32 toff = n_tok + block_excl_scan(ntok, tott, sh.wave_part);
-      const u32 mi = n_smp + block_excl_scan(smp ? 1u : 0u, totm, sh.wave_part2);
-      u32 totr;
-      const u32 ri = n_rows + block_excl_scan(nrow, totr, sh.wave_part);
+      u32 foff, poff, coff, qoff, si, mi, aoff, toff, ri, doff;
+      block_excl_scan2(nfull, nch - nfull, foff, poff, totf, totp, sh.part64);
+      block_excl_scan2(nch, multi ? (ntok + 15) / 16 : 0u, coff, qoff, totc, totq, sh.part64);
+      block_excl_scan2(in ? 1u : 0u, smp ? 1u : 0u, si, mi, tots, totm, sh.part64);
+      block_excl_scan2(nalloc, ntok, aoff, toff, tota, tott, sh.part64);
+      block_excl_scan2(nrow, (in && !pref) ? 1u : 0u, ri, doff, totr, totd, sh.part64);
       block_excl_scan(ctx_after, totx, sh.wave_part);     // context tokens the attention of this iteration reads
-      u32 totd;
-      block_excl_scan((in && !pref) ? 1u : 0u, totd, sh.wave_part2);
+      foff += n_full; poff += n_part; coff += n_ch; qoff += n_qt; si += n_seqs; mi += n_smp; aoff += n_alloc; toff += n_tok; ri += n_rows;
       n_dec_seq += totd;
       if (in) {
         RunEntry& r = c.run[b];
@@ -734,7 +754,8 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
         }
         r.ctx_len = ctx_after;
       }
-      if (group && b < c.max_batch) { sh.dec_key[b] = dec_seq ? ctx_after : 0u; sh.dec_si[b] = si; }
+      // (sort key of a decoding sequence: context length, then the lower batch slot first; unique, 0 for no sequence)
+      if (group && b < SCHED_MAX_BATCH) { sh.dec_key[b] = (b < c.max_batch && dec_seq) ? (ctx_after << 10) | (1023u - b) : 0u; sh.dec_si[b] = coff; sh.dec_tok[b] = toff; }
       max_q = max(max_q, block_max(ntok, sh.wave_part2));
       max_ctx = max(max_ctx, block_max(ctx_after, sh.wave_part));
       max_pref = max(max_pref, block_max(multi ? ctx_after : 0u, sh.wave_part2));
@@ -752,21 +773,23 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
     top -= n_alloc;
     __syncthreads();
     if (group) {
-      // whole contexts, longest first: a sequence's place in the list is the number of decoding sequences with a longer
-      // context (or an equal one in a lower batch slot)
+      // whole contexts, longest first: a sequence's place in the list is the number of decoding sequences with a larger
+      // key (a longer context, or an equal one in a lower batch slot); sixteen keys per step, read as four 16-byte words
+      const u32 strips = (c.max_batch + BLK_THREADS - 1) / BLK_THREADS * BLK_THREADS;      // (keys behind max_batch up to here are 0)
       for (u32 base = 0; base < c.max_batch; base += BLK_THREADS) {
         const u32 b = base + tid;
         const u32 key = b < c.max_batch ? sh.dec_key[b] : 0u;
         if (key) {
           u32 rank = 0;
-          for (u32 b2 = 0; b2 < c.max_batch; ++b2) {
-            const u32 k2 = sh.dec_key[b2];
-            rank += (k2 > key || (k2 == key && b2 < b)) ? 1u : 0u;
+          for (u32 b2 = 0; b2 < strips; b2 += 16) {
+            const uint4 k0 = *(const uint4*)&sh.dec_key[b2], k1 = *(const uint4*)&sh.dec_key[b2 + 4];
+            const uint4 k2 = *(const uint4*)&sh.dec_key[b2 + 8], k3 = *(const uint4*)&sh.dec_key[b2 + 12];
+            rank += (k0.x > key) + (k0.y > key) + (k0.z > key) + (k0.w > key) + (k1.x > key) + (k1.y > key) + (k1.z > key) + (k1.w > key) +
+                    (k2.x > key) + (k2.y > key) + (k2.z > key) + (k2.w > key) + (k3.x > key) + (k3.y > key) + (k3.z > key) + (k3.w > key);
           }
-          const u32 si = sh.dec_si[b];
           ChunkRec rec;
-          rec.tok = c.cu_seqlens[si]; rec.ctx = key; rec.bslot = b; rec.ch = 0; rec.ci = c.cu_chunks[si]; rec.nch = 1;
-          rec.b_end = (key + 15) / 16; rec.pad1 = 0;
+          rec.tok = sh.dec_tok[b]; rec.ctx = key >> 10; rec.bslot = b; rec.ch = 0; rec.ci = sh.dec_si[b]; rec.nch = 1;
+          rec.b_end = ((key >> 10) + 15) / 16; rec.pad1 = 0;
           c.chunk_rec[rank] = rec;
         }
       }
