@@ -199,8 +199,12 @@ enum {
   BLINK_DBG_CU_SEQLENS = 9,    /* uint32[n_seqs + 1] */
   BLINK_DBG_SLOT_STATES = 10,  /* uint32[ring_slots] */
   BLINK_DBG_HIDDEN = 11,       /* float[n_tokens][d_model]: residual stream after the last layer */
-  BLINK_DBG_ROUTING = 12       /* mixture of experts: uint32[n_layers][n_tokens][n_active], the experts every token of the
+  BLINK_DBG_ROUTING = 12,      /* mixture of experts: uint32[n_layers][n_tokens][n_active], the experts every token of the
                                   last iteration was routed to, in selection order */
+  BLINK_DBG_ATTN_ITEMS = 13    /* bf16 models: the work list the scheduler step handed to the decode attention of the last
+                                  iteration, in the order the workgroups take it: uint32[items][8] = token index, context
+                                  length, batch slot, first 512-token chunk of the item, chunk id of its result, results
+                                  of its context, KV block behind its last one, 0 */
 };
 
 /* Provisioning (section 4.1): allocates all device memory, uploads and re-tiles the weights, builds the

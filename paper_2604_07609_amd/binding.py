@@ -17,7 +17,7 @@ EXPORTS = ["blink_init", "blink_submit", "blink_run", "blink_set_exit_when_idle"
 
 class DBG:
     LOGITS, FREE_STACK, INPUT_IDS, POSITIONS, SLOT_MAPPING, SEQ_BATCH_SLOT, BLOCK_TABLES, SEQ_LENS, CU_SEQLENS, \
-        SLOT_STATES, HIDDEN, ROUTING = range(1, 13)
+        SLOT_STATES, HIDDEN, ROUTING, ATTN_ITEMS = range(1, 14)
 
 
 class Config(C.Structure):

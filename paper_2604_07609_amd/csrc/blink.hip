@@ -1012,6 +1012,17 @@ extern "C" int blink_debug_read(blink_engine* e, uint32_t what, void* buf, uint6
       *n_bytes = n;
       return BLINK_OK;
     }
+    case BLINK_DBG_ATTN_ITEMS: {
+      if (!c.chunk_rec) return fail(BLINK_ERR_INVAL, "not a bf16 model");
+      static_assert(sizeof(ChunkRec) == 32, "work list record layout");
+      n = (u64)m.n_chunks * sizeof(ChunkRec);
+      if (n > cap_bytes) return fail(BLINK_ERR_INVAL, "buffer too small: need %llu bytes", (unsigned long long)n);
+      const u64 n_first = (u64)m.n_full_chunks * sizeof(ChunkRec);
+      if (n_first) HIPCHK(hipMemcpy(buf, c.chunk_rec, n_first, hipMemcpyDeviceToHost));
+      if (n > n_first) HIPCHK(hipMemcpy((char*)buf + n_first, c.chunk_rec + c.chunk_cap, n - n_first, hipMemcpyDeviceToHost));
+      *n_bytes = n;
+      return BLINK_OK;
+    }
     default: return fail(BLINK_ERR_INVAL, "unknown selector %u", what);
   }
   if (n > cap_bytes) return fail(BLINK_ERR_INVAL, "buffer too small: need %llu bytes", (unsigned long long)n);

@@ -212,6 +212,38 @@ def check_routing(cfg, routing, route_log, stats):
             assert (sel == rl["own"])[ordered].all(), rl["layer"]
 
 
+def check_attention_items(items, plan, whole_contexts):
+    """The decode attention's work list against the plan: every 512-token chunk of every decoding sequence's context
+    exactly once (as chunks: full ones first; as whole contexts: longest first, the lower batch slot first among equals),
+    the fields of an item those of its sequence."""
+    items = items.reshape(-1, 8)
+    assert plan.kind == 2       # (decode iteration: every sequence that processes one token decodes)
+    decoding = [i for i in range(len(plan.batch_slots)) if plan.cu_seqlens[i + 1] - plan.cu_seqlens[i] == 1]
+    by_slot = {plan.batch_slots[i]: i for i in decoding}
+    seen = set()
+    for tok, ctx, bslot, ch, ci, nres, b_end, _ in items.tolist():
+        i = by_slot[bslot]
+        assert (tok, ctx) == (plan.cu_seqlens[i], plan.seq_lens[i])
+        nblocks = -(-ctx // 16)
+        if whole_contexts:
+            assert (ch, nres, b_end) == (0, 1, nblocks)
+            covered = range(0, -(-ctx // 512))
+        else:
+            assert nres == -(-ctx // 512) and b_end == min(nblocks, 32 * (ch + 1)) and ch < nres
+            covered = [ch]
+        for k in covered:
+            assert (bslot, k) not in seen
+            seen.add((bslot, k))
+    assert seen == {(plan.batch_slots[i], k) for i in decoding for k in range(-(-plan.seq_lens[i] // 512))}
+    if whole_contexts:
+        keys = [(-int(r[1]), int(r[2])) for r in items]
+        assert keys == sorted(keys)
+        assert sorted(int(r[4]) for r in items) == list(range(len(items)))     # one result per sequence
+    else:
+        full = [int(r[6]) - 32 * int(r[3]) == 32 and int(r[1]) >= 512 * (int(r[3]) + 1) for r in items]
+        assert full == sorted(full, reverse=True)                               # the full chunks come first
+
+
 def stepwise_check(B, cfg, eng, raw, blob, reqs, rtol, max_iters=10000, tune=0, tokens_out=None):
     """One iteration per blink_run call: batch metadata, block tables and free stack bit-exact against the
     oracle's scheduler; logits within rtol of the row maximum against the oracle's paged forward fed with
@@ -253,6 +285,8 @@ def stepwise_check(B, cfg, eng, raw, blob, reqs, rtol, max_iters=10000, tune=0, 
             bt = e.debug_read(D.BLOCK_TABLES, np.uint32).reshape(eng["max_batch"], -1)
             for b, blocks in zip(plan.batch_slots, plan.block_tables):
                 assert list(bt[b][: len(blocks)]) == blocks
+            if cfg["dtype"] == 1 and plan.kind == 2:
+                check_attention_items(e.debug_read(D.ATTN_ITEMS, np.uint32), plan, bool(tune & 0x400000))
             routing, route_log = None, None
             if cfg.get("n_experts", 0):   # mixture of experts: the oracle follows the engine's routing and reports its own
                 routing = e.debug_read(D.ROUTING, np.uint32).reshape(cfg["n_layers"], len(plan.input_ids), cfg["n_active"])
