@@ -109,20 +109,22 @@ __global__ void __launch_bounds__(BLK_THREADS) k_copy_calibration(const uint4* s
   for (u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (u64)gridDim.x * blockDim.x) dst[i] = src[i];
 }
 
-// plain read of `n16` 16-byte words, eight loads in flight per lane: what a kernel that only reads (the decode attention's KV
-// stream, a decode GEMM's weight stream) can reach. The sum is written only if it equals a value it never takes.
+// plain read of `n16` 16-byte words, eight non-temporal loads in flight per lane: what a kernel that only reads (the decode
+// attention's KV stream, a decode GEMM's weight stream) can reach. The sum is written only if it equals a value it never takes.
 __global__ void __launch_bounds__(BLK_THREADS) k_read_calibration(const uint4* src, u32* dst, u64 n16) {
+  typedef u32 u32x4_t __attribute__((ext_vector_type(4)));
+  const u32x4_t* p = (const u32x4_t*)src;
   const u64 stride = (u64)gridDim.x * blockDim.x;
   u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
   u32 acc = 0;
   for (; i + 7 * stride < n16; i += 8 * stride) {
-    uint4 v[8];
+    u32x4_t v[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = src[i + u * stride];
+    for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(p + i + u * stride);
 #pragma unroll
-    for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    for (int u = 0; u < 8; ++u) acc ^= v[u][0] ^ v[u][1] ^ v[u][2] ^ v[u][3];
   }
-  for (; i < n16; i += stride) { const uint4 v = src[i]; acc ^= v.x ^ v.y ^ v.z ^ v.w; }
+  for (; i < n16; i += stride) { const u32x4_t v = p[i]; acc ^= v[0] ^ v[1] ^ v[2] ^ v[3]; }
   if (acc == 0x9E3779B9u) dst[(u64)blockIdx.x * blockDim.x + threadIdx.x] = acc;     // (the buffer holds zeros)
 }
 
@@ -1097,7 +1099,7 @@ extern "C" int blink_calibration_rates(blink_engine* e, double* copy_gbs, double
     if (hipEventRecord(t1, e->compute) != hipSuccess || hipEventSynchronize(t1) != hipSuccess || hipEventElapsedTime(&ms, t0, t1) != hipSuccess) { rc = BLINK_ERR_DEVICE; break; }
     if (rep && (best_mfma == 0.f || ms < best_mfma)) best_mfma = ms;
     if (hipEventRecord(t0, e->compute) != hipSuccess) { rc = BLINK_ERR_DEVICE; break; }
-    hipLaunchKernelGGL(k_read_calibration, dim3(e->grid * 2), dim3(BLK_THREADS), 0, e->compute, (const uint4*)src, (u32*)e->calib_dst, n16);
+    hipLaunchKernelGGL(k_read_calibration, dim3(e->grid), dim3(BLK_THREADS), 0, e->compute, (const uint4*)src, (u32*)e->calib_dst, n16);
     if (hipEventRecord(t1, e->compute) != hipSuccess || hipEventSynchronize(t1) != hipSuccess || hipEventElapsedTime(&ms, t0, t1) != hipSuccess) { rc = BLINK_ERR_DEVICE; break; }
     if (rep && (best_read == 0.f || ms < best_read)) best_read = ms;
   }
