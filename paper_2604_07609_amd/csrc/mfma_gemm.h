@@ -78,6 +78,9 @@ struct MfmaGemmArgs {
                            // Bit 11: no 64 x 64 streaming items for 64 < T <= 256. Bits 12-14: 2, 3, 4 or 6 force the
                            // token tiles per wave of the LDS-staged tile schedule, 7 its 256-token tile. Bit 20: eight-wave kernels never
                            // take the pair of tiles with shared weight tiles. Bit 21: no tiles wider than 128 tokens.
+                           // Bit 15 (scheduler): the decode attention's work items are always chunks, bit 22: always whole
+                           // contexts; bit 23: the decode attention kernel with static items. Bits 16-19: waves per item of the
+                           // prefill attention. Bit 30: mixed launches run their decode part first in every workgroup.
                            // Bits 24-27: K slices of the split across workgroups (1: never split; 0: automatic).
                            // (Bits 28-29 are read at init: 2 builds the kernel chain with the reduce kernels; only it splits K.)
 };
