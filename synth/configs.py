@@ -35,6 +35,10 @@ MODEL_CONFIGS = {
     # workgroups take items beyond their first two
     "mini_kv8": dict(n_layers=1, d_model=256, n_q_heads=16, n_kv_heads=8, head_dim=64, d_ffn=512,
                      vocab=1500, dtype=1, rms_eps=1e-5, rope_theta=10000.0),
+    # the head configuration of the llama3_8b shape (32 q / 8 kv heads of 128) in one narrow layer: decode attention at
+    # the full head count with enough sequences that the scheduler hands out whole contexts by itself
+    "mini_heads32": dict(n_layers=1, d_model=512, n_q_heads=32, n_kv_heads=8, head_dim=128, d_ffn=512,
+                         vocab=1024, dtype=1, rms_eps=1e-5, rope_theta=500000.0),
     # mixture of experts: d_ffn is the width of one expert
     "mini_moe": dict(n_layers=2, d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=64, d_ffn=96, n_experts=8, n_active=2,
                      vocab=1500, dtype=1, rms_eps=1e-5, rope_theta=10000.0),
@@ -73,6 +77,8 @@ ENGINE_CONFIGS = {
                     max_prefill_tokens=700, ring_slots=32, eos_token_id=-1),
     "mini_kv8": dict(kv_block_size=16, kv_num_blocks=3200, max_batch=40, max_seq_len=1300,
                      max_prefill_tokens=4096, ring_slots=64, eos_token_id=-1),
+    "mini_heads32": dict(kv_block_size=16, kv_num_blocks=1400, max_batch=176, max_seq_len=2200,
+                         max_prefill_tokens=8192, ring_slots=256, eos_token_id=-1),
     "mini_moe": dict(kv_block_size=16, kv_num_blocks=96, max_batch=6, max_seq_len=160,
                      max_prefill_tokens=256, ring_slots=32, eos_token_id=-1),
     "mini_moe16": dict(kv_block_size=16, kv_num_blocks=400, max_batch=48, max_seq_len=700,

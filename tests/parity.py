@@ -218,6 +218,16 @@ def check_attention_items(items, plan, whole_contexts):
     the fields of an item those of its sequence."""
     items = items.reshape(-1, 8)
     assert plan.kind == 2       # (decode iteration: every sequence that processes one token decodes)
+    if whole_contexts is None:  # the scheduler's own choice: told apart by the items unless every context fits one chunk
+        if any(r[3] > 0 or r[5] > 1 for r in items.tolist()):
+            whole_contexts = False
+        elif any(r[1] > 512 for r in items.tolist()):
+            whole_contexts = True
+        else:
+            assert sorted((int(r[2]), 0) for r in items) == sorted((plan.batch_slots[i], 0) for i in range(len(plan.batch_slots))
+                                                                   if plan.cu_seqlens[i + 1] - plan.cu_seqlens[i] == 1)
+            return None
+    
     decoding = [i for i in range(len(plan.batch_slots)) if plan.cu_seqlens[i + 1] - plan.cu_seqlens[i] == 1]
     by_slot = {plan.batch_slots[i]: i for i in decoding}
     seen = set()
@@ -242,9 +252,10 @@ def check_attention_items(items, plan, whole_contexts):
     else:
         full = [int(r[6]) - 32 * int(r[3]) == 32 and int(r[1]) >= 512 * (int(r[3]) + 1) for r in items]
         assert full == sorted(full, reverse=True)                               # the full chunks come first
+    return whole_contexts
 
 
-def stepwise_check(B, cfg, eng, raw, blob, reqs, rtol, max_iters=10000, tune=0, tokens_out=None):
+def stepwise_check(B, cfg, eng, raw, blob, reqs, rtol, max_iters=10000, tune=0, tokens_out=None, item_modes=None):
     """One iteration per blink_run call: batch metadata, block tables and free stack bit-exact against the
     oracle's scheduler; logits within rtol of the row maximum against the oracle's paged forward fed with
     the engine's own token history; every token against the oracle's sampler run on the engine's own logits
@@ -286,7 +297,10 @@ def stepwise_check(B, cfg, eng, raw, blob, reqs, rtol, max_iters=10000, tune=0, 
             for b, blocks in zip(plan.batch_slots, plan.block_tables):
                 assert list(bt[b][: len(blocks)]) == blocks
             if cfg["dtype"] == 1 and plan.kind == 2:
-                check_attention_items(e.debug_read(D.ATTN_ITEMS, np.uint32), plan, bool(tune & 0x400000))
+                forced = True if tune & 0x400000 else False if tune & 0x808000 else None
+                mode = check_attention_items(e.debug_read(D.ATTN_ITEMS, np.uint32), plan, forced)
+                if item_modes is not None:
+                    item_modes.append(mode)
             routing, route_log = None, None
             if cfg.get("n_experts", 0):   # mixture of experts: the oracle follows the engine's routing and reports its own
                 routing = e.debug_read(D.ROUTING, np.uint32).reshape(cfg["n_layers"], len(plan.input_ids), cfg["n_active"])

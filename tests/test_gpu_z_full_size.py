@@ -128,3 +128,22 @@ def test_llama3_8b_shape_schedule_exact_and_probe_logits(lib):
           "sampled probe tokens: equal to the oracle's sampler on the engine's logits", sampled_exact, "of", N_PROBES * NEW_TOKENS,
           "; on the oracle's logits: equal", sampled_checked, "undecided", sampled_undecided)
     assert sampled_exact >= N_PROBES * NEW_TOKENS - 2
+
+
+def test_full_head_configuration_whole_context_items(lib):
+    """The llama3_8b head configuration (32 q / 8 kv heads of 128) in one narrow layer, 172 sequences with contexts of 8 to
+    2100 tokens: enough (sequence, kv head) pairs that the scheduler hands whole contexts to the decode attention by
+    itself, longest first, about 1400 items on 256 workgroups, the long ones walked in up to five rounds. Every logits row
+    of every iteration against the oracle, the work list against the plan."""
+    cfg, eng = synth.model_config("mini_heads32"), synth.engine_config("mini_heads32")
+    raw = synth.make_weights(cfg, 51, gain_jitter=0.1)
+    blob = synth.pack_blob(cfg, raw)
+    rng = np.random.default_rng(51)
+    plens = [int(x) for x in rng.integers(8, 120, 172)]
+    plens[:6] = [2100, 1100, 1030, 700, 511, 513]
+    reqs = [dict(arrival_s=0.0, prompt=rng.integers(0, cfg["vocab"], P).astype(np.int32), max_new_tokens=3, temperature=0.0, top_k=0,
+                 top_p=1.0, seed=i) for i, P in enumerate(plens)]
+    modes = []
+    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2, item_modes=modes)
+    print("full head configuration, whole contexts: worst relative logit error", worst, "item modes", modes)
+    assert True in modes        # the decode iterations of the full batch took whole contexts
