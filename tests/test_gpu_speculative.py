@@ -144,3 +144,17 @@ def test_speculative_lookup_window_boundary(lib):
     assert seen[0][:2] == [x0, x1] and len(seen[0]) >= 2        # drafted from the edge of the window
     assert seen[1] == [x0]                                      # one position further back: not found
     parity.stepwise_check_speculative(lib, cfg, eng, raw, blob, reqs, rtol=2e-2)
+
+
+def test_speculative_windows_give_the_same_streams(lib):
+    """The same speculative run in windows of 2 iterations (blink_run(2) again and again: the drafts of an iteration are
+    looked up from what the previous window published) and in one go: identical events."""
+    cfg, eng, raw, blob = setup("mini_gqa", 169)
+    eng = dict(eng, speculative=4)
+    reqs = repetitive_requests(cfg, eng, 169, 10)
+    ev1, tr1, st1 = parity.run_engine(lib, cfg, eng, blob, reqs)
+    ev2, tr2, st2 = parity.run_engine(lib, cfg, eng, blob, reqs, window=2)
+    key = lambda ev: sorted((int(x["request_id"]), int(x["index"]), int(x["token"]), int(x["iteration"]), int(x["flags"])) for x in ev)
+    assert key(ev1) == key(ev2)
+    assert (st1["spec_drafted"], st1["spec_accepted"], st1["iterations"]) == (st2["spec_drafted"], st2["spec_accepted"], st2["iterations"])
+    assert st1["spec_accepted"] > 10
