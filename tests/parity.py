@@ -345,6 +345,7 @@ def stepwise_check_speculative(B, cfg, eng, raw, blob, reqs, rtol, max_iters=100
     D = B.DBG
     worst = 0.0
     toks = {}
+    moe_stats = dict(pairs=0, unclear=0)
     try:
         for r in reqs:
             e.submit_request(r)
@@ -356,6 +357,7 @@ def stepwise_check_speculative(B, cfg, eng, raw, blob, reqs, rtol, max_iters=100
             if plan.kind == 0:
                 st = e.stats()
                 assert st["iterations"] == it
+                assert moe_stats["unclear"] <= 0.08 * moe_stats["pairs"], moe_stats
                 assert (st["spec_drafted"], st["spec_accepted"]) == (sched.drafted, sched.accepted)
                 assert st["tokens_out"] == sum(len(v) for v in toks.values())
                 assert st["free_blocks"] == eng["kv_num_blocks"] and st["committed_blocks"] == 0
@@ -371,8 +373,14 @@ def stepwise_check_speculative(B, cfg, eng, raw, blob, reqs, rtol, max_iters=100
             bt = e.debug_read(D.BLOCK_TABLES, np.uint32).reshape(eng["max_batch"], -1)
             for b, blocks in zip(plan.batch_slots, plan.block_tables):
                 assert list(bt[b][: len(blocks)]) == blocks
+            routing, route_log = None, None
+            if cfg.get("n_experts", 0):   # mixture of experts: the oracle follows the engine's routing and reports its own
+                routing = e.debug_read(D.ROUTING, np.uint32).reshape(cfg["n_layers"], len(plan.input_ids), cfg["n_active"])
+                route_log = []
             ref = M.paged_forward(cfg, W, kv, plan.input_ids, plan.positions, plan.slot_mapping, plan.tok_seq,
-                                  plan.block_tables, plan.last_idx)
+                                  plan.block_tables, plan.last_idx, routing=routing, route_log=route_log)
+            if routing is not None:
+                check_routing(cfg, routing, route_log, moe_stats)
             got = e.debug_read(D.LOGITS, np.float32).reshape(len(plan.last_idx), cfg["vocab"])
             err = np.abs(got - ref).max(axis=1) / np.abs(ref).max(axis=1)
             worst = max(worst, float(err.max()))

@@ -36,7 +36,8 @@ def free_run(lib, cfg, eng, blob, reqs):
     return got, st
 
 
-@pytest.mark.parametrize("name,dtype,seed,k", [("mini_gqa", 1, 161, 4), ("mini_gqa128", 1, 162, 7), ("mini_gqa", 0, 163, 3), ("mini_g8", 1, 164, 2)])
+@pytest.mark.parametrize("name,dtype,seed,k", [("mini_gqa", 1, 161, 4), ("mini_gqa128", 1, 162, 7), ("mini_gqa", 0, 163, 3), ("mini_g8", 1, 164, 2),
+                                               ("mini_moe", 1, 170, 3)])
 def test_speculative_stepwise(lib, name, dtype, seed, k):
     """Prompts that repeat a short phrase, so that lookups hit from the first decode iteration on, and a random model that
     decodes greedily and soon repeats itself, so that drafts are accepted as well as rejected; every third request samples
