@@ -46,6 +46,27 @@ def test_moe16_stepwise(lib, prompts, max_new):
     assert free_run_tokens(lib, cfg, eng, blob, reqs) == toks
 
 
+@pytest.mark.parametrize("mode", ["chunked_prefill", "preemption", "prefix_cache"])
+def test_moe_with_the_scheduler_extensions(lib, mode):
+    """The routed FFN under the scheduler's optional modes (mixed prefill + decode iterations with a budget of 48 tokens; on-demand
+    KV growth with preemptions in a pool of 14 blocks; prefix caching on prompts with common heads): the modes change
+    which tokens an iteration carries, not what the model computes for them."""
+    cfg, eng, raw, blob = setup("mini_moe", 145)
+    reqs = synth.make_workload("mini", cfg["vocab"], 245, n_requests=10)
+    if mode == "chunked_prefill":
+        eng = dict(eng, chunked_prefill=True, max_prefill_tokens=48)
+    elif mode == "preemption":
+        eng = dict(eng, preemption=True, kv_num_blocks=14, max_batch=4)
+        for r in reqs:
+            r["prompt"] = r["prompt"][:40]
+    else:
+        eng = dict(eng, prefix_cache=True, kv_num_blocks=40)
+        reqs = synth.with_shared_prefixes(reqs, cfg["vocab"], 345, n_prefixes=2, prefix_len=(16, 50), share=0.8)
+        reqs = [dict(r, prompt=r["prompt"][: eng["max_seq_len"] - r["max_new_tokens"] - 1]) for r in reqs]
+    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2)
+    print("mini_moe with", mode, ": worst relative logit error", worst)
+
+
 def test_moe_one_expert_equals_dense(lib):
     """One expert, one active: the routed path must reproduce the dense FFN of the same matrices (its weight is 1)."""
     cfg, eng, raw, blob = setup("mini_moe", 143)
