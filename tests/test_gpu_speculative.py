@@ -159,3 +159,21 @@ def test_speculative_windows_give_the_same_streams(lib):
     assert key(ev1) == key(ev2)
     assert (st1["spec_drafted"], st1["spec_accepted"], st1["iterations"]) == (st2["spec_drafted"], st2["spec_accepted"], st2["iterations"])
     assert st1["spec_accepted"] > 10
+
+
+def test_speculative_end_of_sequence_inside_a_run_of_drafts(lib):
+    """The end-of-sequence token set to a token the streams emit often: a request finishes at the row that emits it, whether
+    the drafts behind it would have been confirmed or not, and the rows behind it are ignored."""
+    from collections import Counter
+    cfg, eng, raw, blob = setup("mini_gqa", 171)
+    eng = dict(eng, speculative=4)
+    reqs = repetitive_requests(cfg, eng, 171, 10)
+    _, toks = parity.stepwise_check_speculative(lib, cfg, eng, raw, blob, reqs, rtol=2e-2)
+    late = Counter(t for v in toks.values() for t in v[3:])
+    eos = late.most_common(1)[0][0]
+    eng2 = dict(eng, eos_token_id=int(eos))
+    _, toks2 = parity.stepwise_check_speculative(lib, cfg, eng2, raw, blob, reqs, rtol=2e-2)
+    cut = sum(1 for t, v in toks2.items() if v[-1] == eos and len(v) < len(toks[t]))
+    assert cut >= 1, (eos, cut)
+    for t, v in toks2.items():
+        assert eos not in v[:-1]
