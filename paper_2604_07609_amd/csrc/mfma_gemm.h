@@ -224,6 +224,84 @@ __device__ __forceinline__ void epilogue_tile(const MfmaGemmArgs& a, floatx4_t a
   }
 }
 
+// Epilogue of the TJ accumulator tiles a wave holds for one row tile (tokens t_base + 16 j + lane % 16). The epilogues that
+// read memory (the residual stream, the positions and the rotary table) request the operands of all TJ tiles first and
+// then compute and store tile by tile: written one tile after the other, every tile's loads would wait behind the
+// previous tile's stores (the compiler has to assume that they may alias), a chain of TJ memory latencies per row tile.
+// Tokens behind the last one read the last token's operands (an unconditional load) and store nothing.
+// (Bit 6 of the tuning word: tile by tile, for comparison.)
+template <int EPI, int TJ>
+__device__ __forceinline__ void epilogue_row(const MfmaGemmArgs& a, const floatx4_t (&acc)[TJ], u32 nt, u32 t_base, const float* rstd) {
+  if ((EPI != EPI_RESIDUAL && EPI != EPI_QKV_ROPE) || (a.tune_nw & 0x40u)) {
+#pragma unroll
+    for (int j = 0; j < TJ; ++j) epilogue_tile<EPI>(a, acc[j], nt, t_base + j * 16, rstd + j * 16);
+    return;
+  }
+  const u32 lane = threadIdx.x & 63;
+  const u32 n0 = nt * 16 + (lane >> 4) * 4;
+  u32 t[TJ], tc[TJ];
+#pragma unroll
+  for (int j = 0; j < TJ; ++j) { t[j] = t_base + j * 16 + (lane & 15); tc[j] = min(t[j], a.T - 1); }
+  if (EPI == EPI_RESIDUAL) {
+    float4 old[TJ];
+#pragma unroll
+    for (int j = 0; j < TJ; ++j) old[j] = *(const float4*)(a.x + (u64)tc[j] * a.ldx + n0);
+    const float4 g = *(const float4*)(a.g_next + n0);
+#pragma unroll
+    for (int j = 0; j < TJ; ++j) {
+      const bool tv = t[j] < a.T;
+      float v[4] = {0.f, 0.f, 0.f, 0.f};
+      if (tv) {
+        v[0] = old[j].x + acc[j][0] * W_SCALE_INV; v[1] = old[j].y + acc[j][1] * W_SCALE_INV;
+        v[2] = old[j].z + acc[j][2] * W_SCALE_INV; v[3] = old[j].w + acc[j][3] * W_SCALE_INV;
+        *(float4*)(a.x + (u64)t[j] * a.ldx + n0) = make_float4(v[0], v[1], v[2], v[3]);
+        *(uint2*)(a.Xp_next + packed_off(t[j], n0, a.TBS)) = make_uint2(pack_f16x2(v[0] * g.x, v[1] * g.y), pack_f16x2(v[2] * g.z, v[3] * g.w));
+      }
+      float s = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+      s += __shfl_xor(s, 16);
+      s += __shfl_xor(s, 32);
+      if (lane < 16 && tv) a.ssq_out[(u64)t[j] * (a.N / 16) + nt] = s;
+    }
+  } else {   // EPI_QKV_ROPE
+    const u32 hd = a.hd, half = hd / 2, head = n0 / hd, p = (n0 % hd) >> 1;   // rows: (p, p+half, p+1, p+1+half)
+    const bool rot = head < a.nq + a.nkv;
+    i32 pos[TJ];
+    u32 slot[TJ];
+#pragma unroll
+    for (int j = 0; j < TJ; ++j) { pos[j] = a.positions[tc[j]]; slot[j] = (u32)a.slot_mapping[tc[j]]; }
+    float4 cs[TJ];
+#pragma unroll
+    for (int j = 0; j < TJ; ++j) cs[j] = *(const float4*)(a.rope_tab + (u64)(rot ? pos[j] : 0) * half + (rot ? p : 0u));   // (cos,sin) of pairs p, p+1
+#pragma unroll
+    for (int j = 0; j < TJ; ++j) {
+      if (t[j] >= a.T) continue;
+      const float r = rstd[j * 16 + (lane & 15)];
+      float lo0 = acc[j][0] * r, hi0 = acc[j][1] * r, lo1 = acc[j][2] * r, hi1 = acc[j][3] * r;
+      if (rot) {
+        const float a0 = lo0 * cs[j].x - hi0 * cs[j].y, b0 = hi0 * cs[j].x + lo0 * cs[j].y;
+        const float a1 = lo1 * cs[j].z - hi1 * cs[j].w, b1 = hi1 * cs[j].z + lo1 * cs[j].w;
+        lo0 = a0; hi0 = b0; lo1 = a1; hi1 = b1;
+      }
+      if (head < a.nq) {
+        const float sc = 1.0f / sqrtf((float)hd);
+        f16_t* q = a.qbuf + ((u64)t[j] * a.nq + head) * hd;
+        *(u32*)(q + p) = pack_f16x2(lo0 * sc, lo1 * sc);
+        *(u32*)(q + half + p) = pack_f16x2(hi0 * sc, hi1 * sc);
+      } else if (rot) {
+        f16_t* k = a.Kc + (((u64)(slot[j] / a.bs) * a.nkv + (head - a.nq)) * a.bs + slot[j] % a.bs) * hd;
+        *(u32*)(k + p) = pack_f16x2(lo0, lo1);
+        *(u32*)(k + half + p) = pack_f16x2(hi0, hi1);
+      } else {   // V is kept dimension-major inside a block: [hd][16 tokens]
+        f16_t* v = a.Vc + ((u64)(slot[j] / a.bs) * a.nkv + (head - a.nq - a.nkv)) * a.bs * hd + slot[j] % a.bs;
+        v[(u64)p * a.bs] = f32_to_f16(lo0);
+        v[(u64)(p + 1) * a.bs] = f32_to_f16(lo1);
+        v[(u64)(half + p) * a.bs] = f32_to_f16(hi0);
+        v[(u64)(half + p + 1) * a.bs] = f32_to_f16(hi1);
+      }
+    }
+  }
+}
+
 // ---- stream schedule: T <= 64 ------------------------------------------------------------------------------------
 // Weight loads bypass temporal caching: every weight byte is used once per launch, while the activation operand
 // is re-read by every workgroup and should stay in L2.
@@ -621,9 +699,7 @@ __device__ __forceinline__ void gemm_tile_lds(const MfmaGemmArgs& a, MfmaShared&
 #pragma unroll
       for (int i = 0; i < 4; ++i)
         if (nt0 + i < NT) {
-#pragma unroll
-          for (int j = 0; j < TJ; ++j)
-            epilogue_tile<EPI>(a, acc[i][j], nt0 + i, tb * BT + (wt * TJ + j) * 16, &sh.rstd[rstd_off + (wt * TJ + j) * 16]);
+          epilogue_row<EPI, TJ>(a, acc[i], nt0 + i, tb * BT + wt * TJ * 16, &sh.rstd[rstd_off + wt * TJ * 16]);
         }
     }
   }
@@ -752,9 +828,7 @@ __device__ __forceinline__ void gemm_tile_lds_pair(const MfmaGemmArgs& a, MfmaSh
 #pragma unroll
       for (int i = 0; i < 4; ++i)
         if (nt0 + i < NT) {
-#pragma unroll
-          for (int j = 0; j < TJ; ++j)
-            epilogue_tile<EPI>(a, acc[i][j], nt0 + i, tb * BT + (wt * TJ + j) * 16, &sh.rstd[half * BT + (wt * TJ + j) * 16]);
+          epilogue_row<EPI, TJ>(a, acc[i], nt0 + i, tb * BT + wt * TJ * 16, &sh.rstd[half * BT + wt * TJ * 16]);
         }
     }
   }
@@ -846,9 +920,7 @@ __device__ __forceinline__ void gemm_tile_lds_wide(const MfmaGemmArgs& a, MfmaSh
 #pragma unroll
     for (int i = 0; i < 4; ++i)
       if (nt0 + i < NT) {
-#pragma unroll
-        for (int j = 0; j < TJ; ++j)
-          epilogue_tile<EPI>(a, acc[i][j], nt0 + i, tb * BT + (wt * TJ + j) * 16, &sh.rstd[(wt * TJ + j) * 16]);
+        epilogue_row<EPI, TJ>(a, acc[i], nt0 + i, tb * BT + wt * TJ * 16, &sh.rstd[wt * TJ * 16]);
       }
   }
 }
