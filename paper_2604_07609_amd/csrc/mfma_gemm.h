@@ -224,6 +224,24 @@ __device__ __forceinline__ void epilogue_tile(const MfmaGemmArgs& a, floatx4_t a
   }
 }
 
+// EPI_RESIDUAL of one tile with its operands already loaded: `old` = this lane's four residual values of token
+// min(t, T - 1) (the caller's unconditional load), `g` = the next norm's gains of its four rows.
+__device__ __forceinline__ void residual_finish(const MfmaGemmArgs& a, floatx4_t acc, u32 nt, u32 t, float4 old, float4 g) {
+  const u32 lane = threadIdx.x & 63, n0 = nt * 16 + (lane >> 4) * 4;
+  const bool tv = t < a.T;
+  float v[4] = {0.f, 0.f, 0.f, 0.f};
+  if (tv) {
+    v[0] = old.x + acc[0] * W_SCALE_INV; v[1] = old.y + acc[1] * W_SCALE_INV;
+    v[2] = old.z + acc[2] * W_SCALE_INV; v[3] = old.w + acc[3] * W_SCALE_INV;
+    *(float4*)(a.x + (u64)t * a.ldx + n0) = make_float4(v[0], v[1], v[2], v[3]);
+    *(uint2*)(a.Xp_next + packed_off(t, n0, a.TBS)) = make_uint2(pack_f16x2(v[0] * g.x, v[1] * g.y), pack_f16x2(v[2] * g.z, v[3] * g.w));
+  }
+  float s = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+  s += __shfl_xor(s, 16);
+  s += __shfl_xor(s, 32);
+  if (lane < 16 && tv) a.ssq_out[(u64)t * (a.N / 16) + nt] = s;
+}
+
 // Epilogue of the TJ accumulator tiles a wave holds for one row tile (tokens t_base + 16 j + lane % 16). The epilogues that
 // read memory (the residual stream, the positions and the rotary table) request the operands of all TJ tiles first and
 // then compute and store tile by tile: written one tile after the other, every tile's loads would wait behind the
@@ -248,20 +266,7 @@ __device__ __forceinline__ void epilogue_row(const MfmaGemmArgs& a, const floatx
     for (int j = 0; j < TJ; ++j) old[j] = *(const float4*)(a.x + (u64)tc[j] * a.ldx + n0);
     const float4 g = *(const float4*)(a.g_next + n0);
 #pragma unroll
-    for (int j = 0; j < TJ; ++j) {
-      const bool tv = t[j] < a.T;
-      float v[4] = {0.f, 0.f, 0.f, 0.f};
-      if (tv) {
-        v[0] = old[j].x + acc[j][0] * W_SCALE_INV; v[1] = old[j].y + acc[j][1] * W_SCALE_INV;
-        v[2] = old[j].z + acc[j][2] * W_SCALE_INV; v[3] = old[j].w + acc[j][3] * W_SCALE_INV;
-        *(float4*)(a.x + (u64)t[j] * a.ldx + n0) = make_float4(v[0], v[1], v[2], v[3]);
-        *(uint2*)(a.Xp_next + packed_off(t[j], n0, a.TBS)) = make_uint2(pack_f16x2(v[0] * g.x, v[1] * g.y), pack_f16x2(v[2] * g.z, v[3] * g.w));
-      }
-      float s = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
-      s += __shfl_xor(s, 16);
-      s += __shfl_xor(s, 32);
-      if (lane < 16 && tv) a.ssq_out[(u64)t[j] * (a.N / 16) + nt] = s;
-    }
+    for (int j = 0; j < TJ; ++j) residual_finish(a, acc[j], nt, t[j], old[j], g);
   } else {   // EPI_QKV_ROPE
     const u32 hd = a.hd, half = hd / 2, head = n0 / hd, p = (n0 % hd) >> 1;   // rows: (p, p+half, p+1, p+1+half)
     const bool rot = head < a.nq + a.nkv;
@@ -410,6 +415,17 @@ __device__ __forceinline__ void gemm_stream(const MfmaGemmArgs& a, MfmaShared& s
             acc[i][tw] = __builtin_amdgcn_mfma_f32_16x16x32_f16(use.w[u][i], use.x[u][tw], acc[i][tw], 0, 0, 0);
     }
     if (!last) { ++b; return true; }
+    // the residual values and gains the epilogue of this wave's tiles will need: requested before the reduction, not behind it
+    float4 pre_old[NW], pre_g[NW];
+    if (EPI == EPI_RESIDUAL && w < TW && !(a.tune_nw & 0x40u)) {
+      const u32 tq = min((ng % TG) * 64 + w * 16 + (lane & 15), a.T - 1);
+#pragma unroll
+      for (int i = 0; i < NW; ++i) {
+        const u32 n0 = min((ng / TG) * NW + i, NT - 1) * 16 + (lane >> 4) * 4;
+        pre_old[i] = *(const float4*)(a.x + (u64)tq * a.ldx + n0);
+        pre_g[i] = *(const float4*)(a.g_next + n0);
+      }
+    }
     // reduce the four K-quarters through LDS, one weight tile of the group at a time
 #pragma unroll
     for (int i = 0; i < NW; ++i) {
@@ -424,7 +440,8 @@ __device__ __forceinline__ void gemm_stream(const MfmaGemmArgs& a, MfmaShared& s
         if (KS == 8)
           s += (*(floatx4_t*)&sh.red[4][w][lane][0] + *(floatx4_t*)&sh.red[5][w][lane][0]) +
                (*(floatx4_t*)&sh.red[6][w][lane][0] + *(floatx4_t*)&sh.red[7][w][lane][0]);
-        epilogue_tile<EPI>(a, s, nt, tg * 64 + w * 16, &sh.rstd[tg * 64 + w * 16]);
+        if (EPI == EPI_RESIDUAL && !(a.tune_nw & 0x40u)) residual_finish(a, s, nt, tg * 64 + w * 16 + (lane & 15), pre_old[i], pre_g[i]);
+        else epilogue_tile<EPI>(a, s, nt, tg * 64 + w * 16, &sh.rstd[tg * 64 + w * 16]);
       }
 #pragma unroll
       for (int tw = 0; tw < TW; ++tw) acc[i][tw] = floatx4_t{0.f, 0.f, 0.f, 0.f};
