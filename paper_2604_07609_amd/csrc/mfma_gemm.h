@@ -224,6 +224,36 @@ __device__ __forceinline__ void epilogue_tile(const MfmaGemmArgs& a, floatx4_t a
   }
 }
 
+// EPI_QKV_ROPE of one tile with its operands already loaded: `r` = the token's norm scale, `slot` = its place in the paged
+// cache, `cs` = (cos, sin) of the two rotary pairs of this lane's rows at the token's position (unused for V rows).
+__device__ __forceinline__ void rope_finish(const MfmaGemmArgs& a, floatx4_t acc, u32 nt, u32 t, float r, u32 slot, float4 cs) {
+  if (t >= a.T) return;
+  const u32 lane = threadIdx.x & 63, n0 = nt * 16 + (lane >> 4) * 4;
+  const u32 hd = a.hd, half = hd / 2, head = n0 / hd, p = (n0 % hd) >> 1;   // rows: (p, p+half, p+1, p+1+half)
+  float lo0 = acc[0] * r, hi0 = acc[1] * r, lo1 = acc[2] * r, hi1 = acc[3] * r;
+  if (head < a.nq + a.nkv) {
+    const float a0 = lo0 * cs.x - hi0 * cs.y, b0 = hi0 * cs.x + lo0 * cs.y;
+    const float a1 = lo1 * cs.z - hi1 * cs.w, b1 = hi1 * cs.z + lo1 * cs.w;
+    lo0 = a0; hi0 = b0; lo1 = a1; hi1 = b1;
+  }
+  if (head < a.nq) {
+    const float sc = 1.0f / sqrtf((float)hd);
+    f16_t* q = a.qbuf + ((u64)t * a.nq + head) * hd;
+    *(u32*)(q + p) = pack_f16x2(lo0 * sc, lo1 * sc);
+    *(u32*)(q + half + p) = pack_f16x2(hi0 * sc, hi1 * sc);
+  } else if (head < a.nq + a.nkv) {
+    f16_t* k = a.Kc + (((u64)(slot / a.bs) * a.nkv + (head - a.nq)) * a.bs + slot % a.bs) * hd;
+    *(u32*)(k + p) = pack_f16x2(lo0, lo1);
+    *(u32*)(k + half + p) = pack_f16x2(hi0, hi1);
+  } else {   // V is kept dimension-major inside a block: [hd][16 tokens]
+    f16_t* v = a.Vc + ((u64)(slot / a.bs) * a.nkv + (head - a.nq - a.nkv)) * a.bs * hd + slot % a.bs;
+    v[(u64)p * a.bs] = f32_to_f16(lo0);
+    v[(u64)(p + 1) * a.bs] = f32_to_f16(lo1);
+    v[(u64)(half + p) * a.bs] = f32_to_f16(hi0);
+    v[(u64)(half + p + 1) * a.bs] = f32_to_f16(hi1);
+  }
+}
+
 // EPI_RESIDUAL of one tile with its operands already loaded: `old` = this lane's four residual values of token
 // min(t, T - 1) (the caller's unconditional load), `g` = the next norm's gains of its four rows.
 __device__ __forceinline__ void residual_finish(const MfmaGemmArgs& a, floatx4_t acc, u32 nt, u32 t, float4 old, float4 g) {
@@ -278,32 +308,7 @@ __device__ __forceinline__ void epilogue_row(const MfmaGemmArgs& a, const floatx
 #pragma unroll
     for (int j = 0; j < TJ; ++j) cs[j] = *(const float4*)(a.rope_tab + (u64)(rot ? pos[j] : 0) * half + (rot ? p : 0u));   // (cos,sin) of pairs p, p+1
 #pragma unroll
-    for (int j = 0; j < TJ; ++j) {
-      if (t[j] >= a.T) continue;
-      const float r = rstd[j * 16 + (lane & 15)];
-      float lo0 = acc[j][0] * r, hi0 = acc[j][1] * r, lo1 = acc[j][2] * r, hi1 = acc[j][3] * r;
-      if (rot) {
-        const float a0 = lo0 * cs[j].x - hi0 * cs[j].y, b0 = hi0 * cs[j].x + lo0 * cs[j].y;
-        const float a1 = lo1 * cs[j].z - hi1 * cs[j].w, b1 = hi1 * cs[j].z + lo1 * cs[j].w;
-        lo0 = a0; hi0 = b0; lo1 = a1; hi1 = b1;
-      }
-      if (head < a.nq) {
-        const float sc = 1.0f / sqrtf((float)hd);
-        f16_t* q = a.qbuf + ((u64)t[j] * a.nq + head) * hd;
-        *(u32*)(q + p) = pack_f16x2(lo0 * sc, lo1 * sc);
-        *(u32*)(q + half + p) = pack_f16x2(hi0 * sc, hi1 * sc);
-      } else if (rot) {
-        f16_t* k = a.Kc + (((u64)(slot[j] / a.bs) * a.nkv + (head - a.nq)) * a.bs + slot[j] % a.bs) * hd;
-        *(u32*)(k + p) = pack_f16x2(lo0, lo1);
-        *(u32*)(k + half + p) = pack_f16x2(hi0, hi1);
-      } else {   // V is kept dimension-major inside a block: [hd][16 tokens]
-        f16_t* v = a.Vc + ((u64)(slot[j] / a.bs) * a.nkv + (head - a.nq - a.nkv)) * a.bs * hd + slot[j] % a.bs;
-        v[(u64)p * a.bs] = f32_to_f16(lo0);
-        v[(u64)(p + 1) * a.bs] = f32_to_f16(lo1);
-        v[(u64)(half + p) * a.bs] = f32_to_f16(hi0);
-        v[(u64)(half + p + 1) * a.bs] = f32_to_f16(hi1);
-      }
-    }
+    for (int j = 0; j < TJ; ++j) rope_finish(a, acc[j], nt, t[j], rstd[j * 16 + (lane & 15)], slot[j], cs[j]);
   }
 }
 
@@ -426,6 +431,19 @@ __device__ __forceinline__ void gemm_stream(const MfmaGemmArgs& a, MfmaShared& s
         pre_g[i] = *(const float4*)(a.g_next + n0);
       }
     }
+    float4 pre_cs[NW];
+    u32 pre_slot = 0;
+    if (EPI == EPI_QKV_ROPE && w < TW && !(a.tune_nw & 0x40u)) {     // likewise the position, the cache slot and the rotary table entries
+      const u32 tq = min((ng % TG) * 64 + w * 16 + (lane & 15), a.T - 1), half = a.hd / 2;
+      const u32 pos = (u32)a.positions[tq];
+      pre_slot = (u32)a.slot_mapping[tq];
+#pragma unroll
+      for (int i = 0; i < NW; ++i) {
+        const u32 n0 = min((ng / TG) * NW + i, NT - 1) * 16 + (lane >> 4) * 4;
+        const bool rot = n0 / a.hd < a.nq + a.nkv;
+        pre_cs[i] = *(const float4*)(a.rope_tab + (u64)(rot ? pos : 0u) * half + (rot ? (n0 % a.hd) >> 1 : 0u));
+      }
+    }
     // reduce the four K-quarters through LDS, one weight tile of the group at a time
 #pragma unroll
     for (int i = 0; i < NW; ++i) {
@@ -441,6 +459,8 @@ __device__ __forceinline__ void gemm_stream(const MfmaGemmArgs& a, MfmaShared& s
           s += (*(floatx4_t*)&sh.red[4][w][lane][0] + *(floatx4_t*)&sh.red[5][w][lane][0]) +
                (*(floatx4_t*)&sh.red[6][w][lane][0] + *(floatx4_t*)&sh.red[7][w][lane][0]);
         if (EPI == EPI_RESIDUAL && !(a.tune_nw & 0x40u)) residual_finish(a, s, nt, tg * 64 + w * 16 + (lane & 15), pre_old[i], pre_g[i]);
+        else if (EPI == EPI_QKV_ROPE && !(a.tune_nw & 0x40u))
+          rope_finish(a, s, nt, tg * 64 + w * 16 + (lane & 15), sh.rstd[tg * 64 + w * 16 + (lane & 15)], pre_slot, pre_cs[i]);
         else epilogue_tile<EPI>(a, s, nt, tg * 64 + w * 16, &sh.rstd[tg * 64 + w * 16]);
       }
 #pragma unroll
