@@ -222,7 +222,10 @@ int blink_submit(blink_engine* e, const int32_t* prompt, uint32_t n_prompt, uint
  * max_iterations forward passes (0: unbounded), on blink_shutdown, or when idle if BLINK_FLAG_EXIT_WHEN_IDLE.
  * All state lives in device memory and survives the end of the loop: calling blink_run again continues
  * from the same logical point. BLINK_ERR_STATE if the loop is still active. Host work per iteration: one graph
- * launch and one event record by the launcher thread, nothing else. */
+ * launch and one event record by the launcher thread, nothing else. (bf16 engines in the plain mode hold two
+ * captured chains, with and without the kernels that merge partial results of the decode attention; the launcher
+ * picks one from the number of running sequences the device last mirrored to host memory, a hint that no result
+ * depends on.) */
 int blink_run(blink_engine* e, uint64_t max_iterations);
 
 /* Whether the loop ends by itself when it finds nothing running and nothing pending (on), or keeps polling the ring

@@ -207,6 +207,8 @@ struct blink_engine {
   // loop
   std::thread launcher;
   hipGraphExec_t iter_graph = nullptr;        // the kernel chain of one iteration
+  hipGraphExec_t iter_graph_whole = nullptr;  // the chain without the merge kernels of the decode attention (whole_chain_ok)
+  bool whole_chain_ok = false;                // the shorter chain exists for this engine
   int timed_phase = -1;                 // phase whose launches are bracketed by HIP events (-1: none)
   std::vector<hipEvent_t> phase_ev;     // [depth][n_layers][2]
   std::vector<float> phase_ms;          // per enqueued iteration of the current window: summed duration
@@ -254,6 +256,7 @@ static u64 expected_weight_bytes(const blink_config* c) {
 
 static void free_all(blink_engine* e) {
   if (e->iter_graph) (void)hipGraphExecDestroy(e->iter_graph);
+  if (e->iter_graph_whole) (void)hipGraphExecDestroy(e->iter_graph_whole);
   for (hipEvent_t ev : e->events) (void)hipEventDestroy(ev);
   for (hipEvent_t ev : e->phase_ev) (void)hipEventDestroy(ev);
   for (void* p : e->dev_allocs) (void)hipFree(p);
@@ -707,9 +710,14 @@ static int launch_phase(blink_engine* e, const DevCtx& ctx, hipStream_t st, int 
 // each of them (three more launches per layer, which do nothing in other iterations). Measured on the llama3_8b shape at
 // 256 tokens, the second kernel costs what the split saves (QKV 60 -> 32 + 21 us, attention output 32 -> 26 + 14 us,
 // down 69 -> 54 + 14 us), so the default chain does not split.
-static int enqueue_iteration_kernels(blink_engine* e, hipStream_t st, u64 enq_index) {
+// whole_chain: the chain for iterations whose decode attention takes whole contexts as its items. The scheduler step
+// of this chain is told to make them so whatever the batch (bit 22 of its tuning word), no item leaves a partial
+// result, and the merge kernel behind every attention launch is left out: 32 launches less per iteration on a
+// 32-layer model (an empty kernel costs 4-5 us here, the gap before the next one 2-3 us).
+static int enqueue_iteration_kernels(blink_engine* e, hipStream_t st, u64 enq_index, bool whole_chain) {
   const bool split = has_split_chain(e);
-  const DevCtx& c = e->ctx;
+  DevCtx c = e->ctx;
+  if (whole_chain) c.tune_nw |= 0x400000u;
   if (c.spec_k) hipLaunchKernelGGL(k_spec_draft, dim3((c.max_batch + 3) / 4), dim3(BLK_THREADS), 0, st, c);
   hipLaunchKernelGGL(k_sched, dim3(1), dim3(BLK_THREADS), 0, st, c);
   if (int rc = launch_phase(e, c, st, PH_EMBED, 0, enq_index)) return rc;
@@ -724,7 +732,7 @@ static int enqueue_iteration_kernels(blink_engine* e, hipStream_t st, u64 enq_in
       }
       if (int rc = launch_phase(e, c, st, ph, l, enq_index)) return rc;
       const int after = ph == PH_ATTN ? PH_ATTN_COMBINE : ph == PH_QKV ? PH_QKV_RED : ph == PH_OPROJ ? PH_OPROJ_RED : ph == PH_DOWN ? PH_DOWN_RED : -1;
-      if (c.dtype == 1 && after >= 0 && (after == PH_ATTN_COMBINE || split))
+      if (c.dtype == 1 && after >= 0 && (after == PH_ATTN_COMBINE ? !whole_chain : split))
         if (int rc = launch_phase(e, c, st, after, l, enq_index)) return rc;
     }
   if (int rc = launch_phase(e, c, st, PH_FINAL_NORM, 0, enq_index)) return rc;
@@ -734,25 +742,49 @@ static int enqueue_iteration_kernels(blink_engine* e, hipStream_t st, u64 enq_in
   return 0;
 }
 
-static int build_graph(blink_engine* e) {
-  if (e->cfg.flags & BLINK_FLAG_NO_GRAPH) return 0;
+static int capture_chain(blink_engine* e, bool whole_chain, hipGraphExec_t* out) {
   hipGraph_t g = nullptr;
   HIPCHK(hipStreamBeginCapture(e->compute, hipStreamCaptureModeThreadLocal));
-  const int rc = enqueue_iteration_kernels(e, e->compute, ~0ull);
+  const int rc = enqueue_iteration_kernels(e, e->compute, ~0ull, whole_chain);
   hipError_t er = hipStreamEndCapture(e->compute, &g);
   if (rc) return rc;
   HIPCHK(er);
-  HIPCHK(hipGraphInstantiate(&e->iter_graph, g, nullptr, nullptr, 0));
+  HIPCHK(hipGraphInstantiate(out, g, nullptr, nullptr, 0));
   HIPCHK(hipGraphDestroy(g));
   return 0;
 }
 
+static int build_graph(blink_engine* e) {
+  // The shorter chain exists where the scheduler can make whole contexts the items of every decode iteration: bf16
+  // models in the plain mode, unless the tuning word forces chunk items or the static kernel (bits 15, 23) or rules
+  // the chain out (bit 5).
+  const u32 ext = BLINK_FLAG_CHUNKED_PREFILL | BLINK_FLAG_PREEMPTION | BLINK_FLAG_PREFIX_CACHE | BLINK_FLAG_SPECULATIVE;
+  e->whole_chain_ok = e->ctx.dtype == 1 && e->ctx.chunk_rec && !(e->cfg.flags & ext) && !(e->cfg.tune & 0x808020u);
+  if (e->cfg.flags & BLINK_FLAG_NO_GRAPH) return 0;
+  if (int rc = capture_chain(e, false, &e->iter_graph)) return rc;
+  if (e->whole_chain_ok)
+    if (int rc = capture_chain(e, true, &e->iter_graph_whole)) return rc;
+  return 0;
+}
+
+// Which chain the next iteration runs is the launcher's choice, and the only one it makes: from the number of running
+// sequences the scheduler step last mirrored to the host (a plain read of pinned memory, several iterations old, a hint
+// and nothing more) it takes the shorter chain when the device would make whole contexts the items anyway (the same
+// threshold). Either chain is correct for any iteration; a stale hint costs a few iterations with the other item shape.
+static bool pick_whole_chain(const blink_engine* e) {
+  if (!e->whole_chain_ok) return false;
+  if (e->cfg.tune & 0x80u) return true;          // bit 7 of the tuning word: always (tests)
+  const u32 nrun = *(volatile const u32*)&e->hmirror->n_running;
+  return (u64)nrun * e->ctx.nkv >= 5ull * e->ctx.n_cu;
+}
+
 static int enqueue_iteration(blink_engine* e, u64 enq_index) {
+  const bool whole = pick_whole_chain(e);
   if (e->iter_graph && e->timed_phase < 0) {
-    HIPCHK(hipGraphLaunch(e->iter_graph, e->compute));
+    HIPCHK(hipGraphLaunch(whole ? e->iter_graph_whole : e->iter_graph, e->compute));
     return 0;
   }
-  return enqueue_iteration_kernels(e, e->compute, enq_index);
+  return enqueue_iteration_kernels(e, e->compute, enq_index, whole);
 }
 
 // durations of the timed phase for the iteration enqueued at enq_index (its events have completed)

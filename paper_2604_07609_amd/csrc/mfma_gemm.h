@@ -72,7 +72,8 @@ struct MfmaGemmArgs {
   // leaves fp32 partial sums per K slice here, gemm_splitk_reduce adds them in slice order and runs the epilogue
   float* part;             // [slice][row tile][token block of 16][lane][4]; null: never split
   u64 part_cap;            // floats
-  u32 tune_nw;             // tests and tuning. Low byte: 0 automatic choice of weight tiles per workgroup, 1/2/4 forced.
+  u32 tune_nw;             // tests and tuning. Low three bits: 0 automatic choice of weight tiles per workgroup, 1/2/4 forced.
+                           // Bit 5 (launcher): never the kernel chain without the decode attention's merge kernels, bit 7: always.
                            // Bit 9: tile schedule with direct loads instead of LDS staging (bit 8: its 256-token
                            // workgroup tile in eight-wave kernels). Bit 10: no split of K between workgroup halves.
                            // Bit 11: no 64 x 64 streaming items for 64 < T <= 256. Bits 12-14: 2, 3, 4 or 6 force the
@@ -1026,7 +1027,7 @@ template <int EPI, int TW, bool WIDE>
 __device__ __forceinline__ void gemm_stream_nw(const MfmaGemmArgs& a, MfmaShared& sh, u32 wg, u32 nwg) {
   // enough tile groups to occupy the chip (one workgroup per group, >= 1.5 per CU) decides the group size
   const u32 NT = (a.N + 15) / 16;
-  const u32 forced = a.tune_nw & 0xFFu;
+  const u32 forced = a.tune_nw & 0x07u;
   if (forced == 1) gemm_stream<EPI, 1, TW>(a, sh, wg, nwg);
   else if (forced == 2) gemm_stream<EPI, 2, TW>(a, sh, wg, nwg);
   else if (forced == 4 && !WIDE) gemm_stream<EPI, 4, TW>(a, sh, wg, nwg);

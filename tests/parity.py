@@ -297,7 +297,7 @@ def stepwise_check(B, cfg, eng, raw, blob, reqs, rtol, max_iters=10000, tune=0, 
             for b, blocks in zip(plan.batch_slots, plan.block_tables):
                 assert list(bt[b][: len(blocks)]) == blocks
             if cfg["dtype"] == 1 and plan.kind == 2:
-                forced = True if tune & 0x400000 else False if tune & 0x808000 else None
+                forced = False if tune & 0x808000 else True if tune & 0x400080 else None   # bit 7: the chain without merge kernels
                 mode = check_attention_items(e.debug_read(D.ATTN_ITEMS, np.uint32), plan, forced)
                 if item_modes is not None:
                     item_modes.append(mode)

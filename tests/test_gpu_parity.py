@@ -142,14 +142,17 @@ def test_bf16_large_prefill_iterations(lib, tune):
 
 
 # decode attention: bit 22 of the tuning word hands out whole contexts as work items (the scheduler does so by itself
-# only with many sequences), bit 23 selects the kernel with static items
-WHOLE_CONTEXTS, STATIC_ITEMS = 0x400000, 0x800000
+# only with many sequences), bit 23 selects the kernel with static items; bit 7 makes the launcher always run the kernel
+# chain without the merge kernels (it does so by itself only once many sequences run), whose scheduler step hands out
+# whole contexts
+WHOLE_CONTEXTS, STATIC_ITEMS, SHORT_CHAIN = 0x400000, 0x800000, 0x80
 
 
 @pytest.mark.parametrize("name,prompts,tune", [("mini_gqa128", [1030, 2070, 7, 1023], 0), ("mini_gqa", [1030, 2070, 7, 1023], 0),
                                                ("mini_gqa128", [6300, 40], 0),
                                                ("mini_gqa128", [1030, 2070, 7, 1023], WHOLE_CONTEXTS), ("mini_gqa", [1030, 2070, 7, 1023], WHOLE_CONTEXTS),
-                                               ("mini_gqa128", [6300, 40], WHOLE_CONTEXTS), ("mini_gqa", [1030, 2070, 7, 1023], STATIC_ITEMS)])
+                                               ("mini_gqa128", [6300, 40], WHOLE_CONTEXTS), ("mini_gqa", [1030, 2070, 7, 1023], STATIC_ITEMS),
+                                               ("mini_gqa128", [1030, 2070, 7, 1023], SHORT_CHAIN), ("mini_gqa", [6300, 40], SHORT_CHAIN)])
 def test_bf16_long_contexts(lib, name, prompts, tune):
     """Contexts of 500..2100 tokens: decode attention works in 512-token chunks whose partial results a second
     kernel merges (up to 12 chunks fetched together; the 6300-token context has 13 and takes the kernel's general
@@ -168,7 +171,7 @@ def test_bf16_long_contexts(lib, name, prompts, tune):
     print(name, "long contexts: worst relative logit error", worst)
 
 
-@pytest.mark.parametrize("tune", [0, WHOLE_CONTEXTS])
+@pytest.mark.parametrize("tune", [0, WHOLE_CONTEXTS, SHORT_CHAIN])
 def test_decode_attention_work_list(lib, tune):
     """40 sequences x 8 kv heads with contexts of 20..1200 tokens: as chunks about 700 items, as whole contexts 320, for
     256 workgroups that each take two fixed items and every further one through the launch's counter; the list has the
