@@ -433,6 +433,64 @@ def speculative_leg(B, cfg, eng, raw, reqs, args):
     return out
 
 
+def placement_leg(B, cfg, eng, blob, reqs, args, stressor):
+    """Scheduler placement on one engine build (section 4.2 of the paper compares a GPU-resident with a CPU-resident
+    scheduler on closed sets of N requests with I input and O output tokens at batch 16): N x I -> O sets, all resident
+    at t = 0, served to completion by the device-decided loop and by the same engine with BLINK_FLAG_HOST_STEP (the
+    launcher waits for every iteration, copies its tokens to the host and a batch description back, then enqueues the
+    next one). Makespans, isolated and under the host stressor; sampling parameters as in the workload."""
+    rng = np.random.default_rng(4242)
+    sets = []
+    for spec in args.placement_sets.split(","):
+        n, i, o = [int(x) for x in spec.split("x")]
+        sets.append((spec, [dict(reqs[j % len(reqs)], arrival_s=0.0, prompt=rng.integers(0, cfg["vocab"], i).astype(np.int32),
+                                 max_new_tokens=o) for j in range(n)]))
+    out = dict(sets="N x I x O: N requests of I prompt tokens and O output tokens (no end-of-sequence token), batch N",
+               stressor=("%d processes, streaming copies of 2 x 256 MiB each" % stressor.n) if stressor else None)
+    res = {spec: {} for spec, _ in sets}
+    for label, flag in (("device_loop", 0), ("host_step", B.FLAG_HOST_STEP)):
+        nmax = max(len(rs) for _, rs in sets)
+        e = B.Engine(cfg, dict(eng, max_batch=max(nmax, 16), eos_token_id=-1), blob, flags=flag | B.FLAG_EXIT_WHEN_IDLE, tune=args.tune)
+        try:
+            def serve(rs):
+                base = e.stats()["next_ticket"]
+                for r in rs:
+                    e.submit_request(r)
+                want = sum(r["max_new_tokens"] for r in rs)
+                t0 = time.perf_counter()
+                e.run(0)
+                n_out = 0
+                while n_out < want and time.perf_counter() - t0 < 120:      # makespan: until the last token has been polled
+                    n_out += len(e.poll(8192))
+                dt = time.perf_counter() - t0
+                e.wait()                                                    # (the iterations enqueued ahead run empty, untimed)
+                n_out += len(e.drain(1 << 16))
+                st = e.stats()
+                if n_out != want or st["n_running"] != 0 or st["next_ticket"] != base + len(rs):
+                    raise RuntimeError("placement leg: %d of %d tokens" % (n_out, want))
+                return dt, n_out
+            for spec, rs in sets:
+                serve(rs[:2])                                  # warm: first launches, clocks
+                dt, n_out = serve(rs)
+                row = dict(seconds=round(dt, 4), output_tokens=n_out)
+                if stressor:
+                    with stressor:
+                        dts, _ = serve(rs)
+                    row["seconds_stressed"] = round(dts, 4)
+                res[spec][label] = row
+        finally:
+            e.shutdown()
+    for spec in res:
+        a, b = res[spec]["device_loop"], res[spec]["host_step"]
+        res[spec]["host_step_over_device_loop"] = round(b["seconds"] / a["seconds"], 4)
+        if stressor:
+            res[spec]["host_step_over_device_loop_stressed"] = round(b["seconds_stressed"] / a["seconds_stressed"], 4)
+            res[spec]["stressed_over_isolated"] = dict(device_loop=round(a["seconds_stressed"] / a["seconds"], 4),
+                                                       host_step=round(b["seconds_stressed"] / b["seconds"], 4))
+    out["results"] = res
+    return out
+
+
 def claim_latency(B, e, vocab, n=24):
     """An idle engine (its scheduler kernel polling the ring on the device) receives one short request at a time:
     time from the entry of blink_submit, and from its return, to the end of the scheduler step that admitted the request
@@ -512,6 +570,10 @@ def main():
                     "completion without and with prefix caching (BLINK_FLAG_PREFIX_CACHE)")
     ap.add_argument("--spec-leg", action="store_true", help="only this: the request set made greedy with repetitive prompts, served to "
                     "completion without and with speculative decoding")
+    ap.add_argument("--placement-leg", action="store_true", help="only this: closed sets of N requests served by the device-decided "
+                    "loop and by the same engine with a host round trip per iteration (BLINK_FLAG_HOST_STEP), isolated and "
+                    "under the host stressor")
+    ap.add_argument("--placement-sets", default="16x128x256,16x512x128,64x128x128", help="N x I x O sets of --placement-leg")
     ap.add_argument("--spec-tokens", type=int, default=4, help="most drafts per request and iteration in --spec-leg")
     ap.add_argument("--prefix-heads", type=int, default=8)
     ap.add_argument("--prefix-len", default="256,1024", help="range of the common heads' lengths in tokens")
@@ -535,7 +597,7 @@ def main():
         args.interference = args.workload == "llama3_8b"
     if args.workload == "moe_30b_a3b":
         args.no_chunked_leg = True
-    stressor = Stressor() if (args.interference and args.open_loop_seconds > 0) else None   # before the GPU is touched
+    stressor = Stressor() if ((args.interference and args.open_loop_seconds > 0) or args.placement_leg) else None   # before the GPU is touched
     import paper_2604_07609_amd as B
 
     if args.phase < 0:
@@ -562,6 +624,13 @@ def main():
 
     if args.prefix_leg:
         print(json.dumps(dict(prefix_cache=prefix_leg(B, cfg, eng, blob, reqs, args), config={"workload": args.workload, "requests": len(reqs)})))
+        return
+    if args.placement_leg:
+        try:
+            print(json.dumps(dict(scheduler_placement=placement_leg(B, cfg, eng, blob, reqs, args, stressor),
+                                  config={"workload": args.workload, "layers": cfg["n_layers"]})))
+        finally:
+            stressor.close()
         return
     if args.spec_leg:
         print(json.dumps(dict(speculative=speculative_leg(B, cfg, eng, raw, reqs, args), config={"workload": args.workload, "requests": len(reqs)})))

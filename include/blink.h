@@ -74,6 +74,14 @@ extern "C" {
                                         emits row by row while the row's token confirms the next draft: exactly the tokens
                                         one-token-per-iteration decoding emits. Sampled requests never speculate. Plain mode only */
 
+#define BLINK_FLAG_HOST_STEP 512u     /* measurement only (section 4.2, the comparison of the two scheduler placements on one engine):
+                                        the launcher thread keeps nothing enqueued ahead. It waits for every iteration to end,
+                                        copies a token array of the batch's size to host memory and a batch description
+                                        (32 bytes per batch slot) back to the device, and only then enqueues the next
+                                        iteration: the per-step synchronisation and PCIe round trip of a host-resident
+                                        scheduler. The scheduling itself is still done by the device, so what this
+                                        measures is a lower bound of such a scheduler's cost. Results are unchanged */
+
 /* slot life cycle of the ring (section 4.2, "Ring buffer") */
 enum {
   BLINK_SLOT_EMPTY = 0,

@@ -7,6 +7,7 @@ import numpy as np
 HERE = os.path.dirname(os.path.abspath(__file__))
 
 FLAG_TRACE, FLAG_EXIT_WHEN_IDLE, FLAG_KEEP_LOGITS, FLAG_NO_GRAPH, FLAG_CHUNKED_PREFILL, FLAG_PREEMPTION, FLAG_PREFIX_CACHE, FLAG_SPECULATIVE = 1, 2, 8, 16, 32, 64, 128, 256
+FLAG_HOST_STEP = 512
 ERR_INVAL, ERR_TOO_LARGE, ERR_FULL, ERR_DEVICE, ERR_STATE = -1, -2, -3, -4, -5
 EVENT_FIRST, EVENT_LAST = 1, 2
 

@@ -209,6 +209,8 @@ struct blink_engine {
   hipGraphExec_t iter_graph = nullptr;        // the kernel chain of one iteration
   hipGraphExec_t iter_graph_whole = nullptr;  // the chain without the merge kernels of the decode attention (whole_chain_ok)
   bool whole_chain_ok = false;                // the shorter chain exists for this engine
+  char *host_step_h = nullptr, *host_step_d = nullptr;   // BLINK_FLAG_HOST_STEP: pinned and device ends of the per-step copies
+  u64 host_step_bytes = 0;
   int timed_phase = -1;                 // phase whose launches are bracketed by HIP events (-1: none)
   std::vector<hipEvent_t> phase_ev;     // [depth][n_layers][2]
   std::vector<float> phase_ms;          // per enqueued iteration of the current window: summed duration
@@ -565,6 +567,12 @@ static int init_impl(const blink_config* cfg, blink_engine* e) {
   {
     u32 depth = cfg->pump_depth ? cfg->pump_depth : 8u;
     if (depth > 1024) depth = 1024;
+    if (cfg->flags & BLINK_FLAG_HOST_STEP) {
+      depth = 1;
+      e->host_step_bytes = 32ull * c.max_batch;
+      if (int rc = halloc(e, &e->host_step_h, e->host_step_bytes)) return rc;
+      if (int rc = dalloc(e, &e->host_step_d, e->host_step_bytes)) return rc;
+    }
     e->events.resize(depth);
     for (u32 i = 0; i < depth; ++i) HIPCHK(hipEventCreateWithFlags(&e->events[i], hipEventDisableTiming));
     e->phase_ev.resize((u64)depth * c.n_layers * 2);
@@ -812,6 +820,15 @@ static void pump_loop(blink_engine* e) {
       harvest_phase_times(e, enq - depth);
       if (e->hmirror->error) { rc = BLINK_ERR_DEVICE; break; }
       if (__atomic_load_n(&e->hmirror->stopped, __ATOMIC_ACQUIRE)) break;
+      if (e->host_step_bytes) {   // the previous iteration has ended: its tokens to the host, a batch description back
+        const u64 tok_bytes = sizeof(i32) * (u64)e->ctx.max_batch;
+        if (hipMemcpyAsync(e->host_step_h, e->ctx.input_ids, tok_bytes, hipMemcpyDeviceToHost, e->compute) != hipSuccess ||
+            hipStreamSynchronize(e->compute) != hipSuccess ||
+            hipMemcpyAsync(e->host_step_d, e->host_step_h, e->host_step_bytes, hipMemcpyHostToDevice, e->compute) != hipSuccess) {
+          rc = BLINK_ERR_DEVICE;
+          break;
+        }
+      }
     }
     rc = enqueue_iteration(e, enq);
     if (rc == 0 && hipEventRecord(e->events[enq % depth], e->compute) != hipSuccess) rc = BLINK_ERR_DEVICE;

@@ -525,3 +525,18 @@ def test_preemption_several_victims_in_one_iteration(lib):
     assert max(len(pl.preempted) for pl in plans) >= 2 and max(len(pl.resumed) for pl in plans) >= 2
     worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2)
     print("several victims: worst relative logit error", worst, "iterations", len(plans))
+
+
+@pytest.mark.parametrize("name,dtype", [("mini_gqa", 1), ("tiny", 0)])
+def test_host_step_mode_changes_no_result(lib, name, dtype):
+    """BLINK_FLAG_HOST_STEP (a host round trip between iterations, for the comparison of scheduler placements) only
+    changes when an iteration is enqueued: events, tokens and the per-iteration trace equal those of the default loop."""
+    cfg, eng, raw, blob = setup(name, 83, gain_jitter=0.0)
+    assert cfg["dtype"] == dtype
+    reqs = sampled(synth.make_workload("mini" if name != "tiny" else "tiny", cfg["vocab"], 183, n_requests=10), 83)
+    ev0, tr0, st0 = parity.run_engine(lib, cfg, eng, blob, reqs)
+    ev1, tr1, st1 = parity.run_engine(lib, cfg, eng, blob, reqs, flags=lib.FLAG_HOST_STEP)
+    assert parity.event_tuples(ev0) == parity.event_tuples(ev1)
+    assert st0["iterations"] == st1["iterations"] and st1["n_running"] == 0 and st1["free_blocks"] == eng["kv_num_blocks"]
+    for f in ("kind", "n_seqs", "n_tokens"):
+        assert list(tr0[f]) == list(tr1[f])
