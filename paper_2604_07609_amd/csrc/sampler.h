@@ -27,28 +27,38 @@ __device__ __forceinline__ float key_to_float(u32 k) {
   return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
 }
 
-// Visits every element of a logits row once: f(value, index). 16-byte loads, eight in flight per thread.
+// Visits every element of a logits row once, each thread in ascending index order: f(value, index). 16-byte loads in
+// batches of eight per thread; the loads of the next batch are in flight while the current one is consumed (two
+// register sets that swap roles by code position).
+#define SCAN_LOAD(v, c)                                                                                  \
+  _Pragma("unroll") for (int u = 0; u < 8; ++u) {                                                        \
+    const u32 idx = (c) + u * (BLK_THREADS * 4) + tid * 4;                                               \
+    v[u] = idx < V ? *(const float4*)(row + idx) : make_float4(0.f, 0.f, 0.f, 0.f);                       \
+  }
+#define SCAN_USE(v, c)                                                                                   \
+  _Pragma("unroll") for (int u = 0; u < 8; ++u) {                                                        \
+    const u32 idx = (c) + u * (BLK_THREADS * 4) + tid * 4;                                               \
+    if (idx < V) { f(v[u].x, idx); f(v[u].y, idx + 1); f(v[u].z, idx + 2); f(v[u].w, idx + 3); }          \
+  }
 template <typename F>
 __device__ __forceinline__ void scan_row(const float* row, u32 V, F f) {
   const u32 tid = threadIdx.x;
   if ((V & 3u) == 0 && ((size_t)row & 15u) == 0) {
-    for (u32 c0 = 0; c0 < V; c0 += BLK_THREADS * 32) {
-      float4 v[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const u32 idx = c0 + u * (BLK_THREADS * 4) + tid * 4;
-        v[u] = idx < V ? *(const float4*)(row + idx) : make_float4(0.f, 0.f, 0.f, 0.f);
-      }
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const u32 idx = c0 + u * (BLK_THREADS * 4) + tid * 4;
-        if (idx < V) { f(v[u].x, idx); f(v[u].y, idx + 1); f(v[u].z, idx + 2); f(v[u].w, idx + 3); }
-      }
+    constexpr u32 STEP = BLK_THREADS * 32;
+    float4 va[8], vb[8];
+    SCAN_LOAD(va, 0u)
+    for (u32 c0 = 0; c0 < V; c0 += 2 * STEP) {
+      SCAN_LOAD(vb, c0 + STEP)          // past the end of the row every load is switched off
+      SCAN_USE(va, c0)
+      SCAN_LOAD(va, c0 + 2 * STEP)
+      SCAN_USE(vb, c0 + STEP)
     }
   } else {
     for (u32 i = tid; i < V; i += BLK_THREADS) f(row[i], i);
   }
 }
+#undef SCAN_LOAD
+#undef SCAN_USE
 
 // Philox4x32-10 (Salmon et al., SC'11): returns the first output word.
 __device__ __forceinline__ u32 philox4x32_10_first(u32 c0, u32 c1, u32 c2, u32 c3, u32 k0, u32 k1) {
@@ -127,30 +137,31 @@ __device__ __forceinline__ void bitonic_sort_desc(unsigned long long* v, u32 n) 
 // rest of sh.cand[0..npow) holding smaller keys or zero padding. Returns npow (a power of two >= k).
 __device__ __forceinline__ u32 select_top_k(const float* row, u32 V, u32 k, SamplerShared& sh) {
   const u32 tid = threadIdx.x;
-  // (1) One pass: every thread keeps the four largest keys among the elements it visits and the largest key it
+  // (1) One pass: every thread keeps the four largest keys among the elements it visits and the largest logit it
   // dropped. The 1024 kept keys are sorted; their k-th largest is the exact threshold unless some thread dropped
-  // a key at or above it.
+  // a logit at or above its logit (a tie with the threshold's logit goes to the exact stages below).
   if (k <= 256) {
-    unsigned long long k0 = 0, k1 = 0, k2 = 0, k3 = 0, dropped = 0;
+    // Sorted by (logit descending, id ascending): a thread meets its ids in ascending order, so among equal logits the
+    // one it holds already comes first, and a strict comparison of the 32-bit logit keys decides every insertion. No
+    // branches: key and id move down the four places through selects.
+    u32 q0 = 0, q1 = 0, q2 = 0, q3 = 0, i0 = 0, i1 = 0, i2 = 0, i3 = 0, dropped = 0;
     scan_row(row, V, [&](float val, u32 i) {
-      const unsigned long long key = ((unsigned long long)order_key(val) << 32) | (u32)~i;
-      if (key > k3) {
-        dropped = k3 > dropped ? k3 : dropped;
-        if (key > k0) { k3 = k2; k2 = k1; k1 = k0; k0 = key; }
-        else if (key > k1) { k3 = k2; k2 = k1; k1 = key; }
-        else if (key > k2) { k3 = k2; k2 = key; }
-        else k3 = key;
-      } else {
-        dropped = key > dropped ? key : dropped;
-      }
+      u32 xk = order_key(val), xi = i;
+#define TOPK_PLACE(q, id) { const bool c = xk > q; const u32 hk = c ? xk : q, hi = c ? xi : id; xk = c ? q : xk; xi = c ? id : xi; q = hk; id = hi; }
+      TOPK_PLACE(q0, i0) TOPK_PLACE(q1, i1) TOPK_PLACE(q2, i2) TOPK_PLACE(q3, i3)
+#undef TOPK_PLACE
+      dropped = max(dropped, xk);      // the logit key of whatever fell out at the bottom
     });
     __syncthreads();
-    sh.cand[tid * 4] = k0; sh.cand[tid * 4 + 1] = k1; sh.cand[tid * 4 + 2] = k2; sh.cand[tid * 4 + 3] = k3;
+    sh.cand[tid * 4] = q0 ? ((unsigned long long)q0 << 32) | (u32)~i0 : 0ull;
+    sh.cand[tid * 4 + 1] = q1 ? ((unsigned long long)q1 << 32) | (u32)~i1 : 0ull;
+    sh.cand[tid * 4 + 2] = q2 ? ((unsigned long long)q2 << 32) | (u32)~i2 : 0ull;
+    sh.cand[tid * 4 + 3] = q3 ? ((unsigned long long)q3 << 32) | (u32)~i3 : 0ull;
     __syncthreads();
     bitonic_sort_desc(sh.cand, SAMPLER_MAX_K);
-    const unsigned long long thr = sh.cand[k - 1];
-    const unsigned long long worst = block_max_u64(dropped, sh.red64);
-    if (worst < thr) return SAMPLER_MAX_K;
+    const u32 thr = (u32)(sh.cand[k - 1] >> 32);
+    const u32 worst = block_max(dropped, sh.misc);
+    if (worst < thr) return SAMPLER_MAX_K;      // every dropped logit lies strictly below the k-th kept one
   }
   // (2) Counting search for a key `lo` with k <= f(lo) <= SAMPLER_MAX_K, f(p) = #{key >= p} (non-increasing in p):
   // start at the row maximum, double the distance below it until k keys are covered, bisect if too many are.
