@@ -783,7 +783,7 @@ static bool pick_whole_chain(const blink_engine* e) {
   if (!e->whole_chain_ok) return false;
   if (e->cfg.tune & 0x80u) return true;          // bit 7 of the tuning word: always (tests)
   const u32 nrun = *(volatile const u32*)&e->hmirror->n_running;
-  return (u64)nrun * e->ctx.nkv >= 5ull * e->ctx.n_cu;
+  return (u64)nrun * e->ctx.nkv >= WHOLE_CONTEXT_PAIRS_PER_CU * (u64)e->ctx.n_cu;
 }
 
 static int enqueue_iteration(blink_engine* e, u64 enq_index) {

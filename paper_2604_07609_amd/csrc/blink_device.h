@@ -110,6 +110,10 @@ struct IterMeta {
   u32 pad;
 };
 
+// (sequence, kv head) pairs per compute unit from which the decode attention's work items are whole contexts; the
+// launcher takes the kernel chain without the merge kernels from the same count (read from the host mirror)
+#define WHOLE_CONTEXT_PAIRS_PER_CU 4ull
+
 // One work item of the decode attention (times the kv heads), as the kernel takes it from the scheduler (32 bytes: one
 // scalar load of a wave): a run of KV blocks of one decoding sequence that one workgroup walks, ATTN_CHUNK_TOKENS at a
 // time, into one result. With few sequences an item is one chunk of a context (so that the chip has enough items; the

@@ -646,12 +646,14 @@ __device__ void sched_step(const DevCtx& c, SchedShared& sh) {
   // unless its prompt is still incomplete after this iteration.
   u32 n_seqs = 0, n_tok = 0, n_alloc = 0, n_qt = 0, n_ch = 0, n_smp = 0, n_rows = 0, n_dec_seq = 0, max_q = 0, max_ctx = 0, max_pref = 0;
   u32 n_full = 0, n_part = 0;     // full and partly filled chunks of the decoding sequences so far
-  // Work items of the decode attention: chunks of the contexts, or, with at least five sequence x kv-head pairs per
+  // Work items of the decode attention: chunks of the contexts, or, with at least four sequence x kv-head pairs per
   // compute unit, whole contexts (bit 22 of the tuning word: always; bit 15, or bit 23, the kernel with static items: never).
   // Measured on the llama3_8b shape (8 kv heads, 256 compute units), decode iteration with chunks / whole contexts: 96
   // sequences 10.04 / 10.23 ms, 128: 11.12 / 11.11, 192: 13.62 / 13.22, 256: 14.94 / 14.44 (with few items per compute unit
-  // whole contexts of 1 to 10 rounds do not balance; with many, the saved merges and partial results win).
-  const bool group = c.chunk_rec && !(c.tune_nw & 0x808000u) && ((c.tune_nw & 0x400000u) || (u64)nrun * c.nkv >= 5ull * c.n_cu);
+  // whole contexts of 1 to 10 rounds do not balance; with many, the saved merges and partial results win). From the same
+  // count on the launcher runs the kernel chain without the merge kernels, which takes a further 0.1 ms off the whole
+  // contexts' side (96 sequences 10.10 / 10.22, 128: 11.22 / 11.12, 144: 12.56 / 12.23).
+  const bool group = c.chunk_rec && !(c.tune_nw & 0x808000u) && ((c.tune_nw & 0x400000u) || (u64)nrun * c.nkv >= WHOLE_CONTEXT_PAIRS_PER_CU * (u64)c.n_cu);
   const u32 spec_k = (c.flags & 256u) ? c.spec_k : 0u;
   u64 n_ctx = 0;
   if (kind != KIND_IDLE) {
