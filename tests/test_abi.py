@@ -19,6 +19,18 @@ def test_header_and_binding_agree():
     assert names and sorted(B.EXPORTS) == names
 
 
+def test_flag_values_match_header():
+    """Every BLINK_FLAG_* of the header has a constant of the same value in the binding."""
+    from paper_2604_07609_amd import binding
+    src = open(os.path.join(ROOT, "include", "blink.h")).read()
+    flags = re.findall(r"#define\s+BLINK_(FLAG_[A-Z_]+)\s+(\d+)u", src)
+    assert len(flags) >= 9
+    for name, value in flags:
+        assert getattr(binding, name) == int(value), name
+    assert len({int(v) for _, v in flags}) == len(flags)        # one bit each, no value twice
+    assert all(int(v) & (int(v) - 1) == 0 for _, v in flags)
+
+
 def test_library_exports_every_declared_symbol():
     lib = ctypes.CDLL(B.lib_path())
     for n in declared_functions():
