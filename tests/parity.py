@@ -328,7 +328,7 @@ def stepwise_check(B, cfg, eng, raw, blob, reqs, rtol, max_iters=10000, tune=0, 
         e.shutdown()
 
 
-def stepwise_check_speculative(B, cfg, eng, raw, blob, reqs, rtol, max_iters=10000):
+def stepwise_check_speculative(B, cfg, eng, raw, blob, reqs, rtol, max_iters=10000, tune=0):
     """Speculative decoding, one iteration per blink_run call: the drafts (input ids behind each last token), positions,
     slot mapping, block tables, free stack and the logits rows' token indices bit-exact against the oracle's scheduler;
     every logits row (one per fed position) within rtol of the oracle's paged forward on the engine's token history; the
@@ -341,7 +341,7 @@ def stepwise_check_speculative(B, cfg, eng, raw, blob, reqs, rtol, max_iters=100
     kv = M.PagedKV(cfg, eng["kv_num_blocks"], eng["kv_block_size"])
     for r in reqs:
         sched.submit(r["prompt"], r["max_new_tokens"], greedy=r["temperature"] == 0.0)
-    e = B.Engine(cfg, eng, blob, flags=B.FLAG_TRACE | B.FLAG_EXIT_WHEN_IDLE | B.FLAG_KEEP_LOGITS)
+    e = B.Engine(cfg, eng, blob, flags=B.FLAG_TRACE | B.FLAG_EXIT_WHEN_IDLE | B.FLAG_KEEP_LOGITS, tune=tune)
     D = B.DBG
     worst = 0.0
     toks = {}

@@ -425,14 +425,17 @@ def test_chunked_prefill_stepwise(lib, name, budget, dtype):
     print("chunked prefill", name, "budget", budget, "worst relative logit error", worst)
 
 
-def test_chunked_prefill_long_prompts_and_contexts(lib):
+@pytest.mark.parametrize("tune", [0, 0x400000])
+def test_chunked_prefill_long_prompts_and_contexts(lib, tune):
     """Prompts of 1030 and 600 tokens in chunks of at most 256 tokens while other requests decode: prompt chunks attend
-    to the chunks cached before them (up to 65 KV blocks back), decode contexts cross the 512-token chunk boundary."""
+    to the chunks cached before them (up to 65 KV blocks back), decode contexts cross the 512-token chunk boundary. With
+    bit 22 of the tuning word the decode part of a mixed launch takes whole contexts as its items, as it does by itself
+    once many sequences decode."""
     cfg, eng, raw, blob = setup("mini_gqa128", 55)
     eng = dict(eng, chunked_prefill=True, max_prefill_tokens=256, max_batch=4, kv_num_blocks=140, max_seq_len=1100, ring_slots=16)
     reqs = _fixed_prompts(cfg, [505, 1030, 40, 600, 7], 6, 25)
-    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2)
-    print("chunked prefill, long prompts: worst relative logit error", worst)
+    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2, tune=tune)
+    print("chunked prefill, long prompts, tune", hex(tune), ": worst relative logit error", worst)
 
 
 def test_chunked_prefill_end_to_end_and_windows(lib):
@@ -463,8 +466,8 @@ def test_chunked_prefill_needs_a_budget_beyond_the_batch(lib):
 
 # ---- on-demand KV growth with preemption ---------------------------------------------------------------------------------
 
-@pytest.mark.parametrize("name,dtype", [("mini_gqa", 1), ("mini_gqa128", 1), ("mini_gqa", 0)])
-def test_preemption_stepwise(lib, name, dtype):
+@pytest.mark.parametrize("name,dtype,tune", [("mini_gqa", 1, 0), ("mini_gqa128", 1, 0), ("mini_gqa", 0, 0), ("mini_gqa128", 1, WHOLE_CONTEXTS)])
+def test_preemption_stepwise(lib, name, dtype, tune):
     """A pool well below the worst-case demand of the batch: decode iterations run out of blocks, the highest tickets are
     preempted (blocks back on the free stack in table order, batch slot freed), wait until blocks are free again and come
     back by recomputing prompt + outputs so far. Every iteration against the oracle: batch metadata, block tables and
@@ -485,8 +488,8 @@ def test_preemption_stepwise(lib, name, dtype):
     plans = []
     run_schedule(probe, reqs, lambda pl: [1] * len(pl.sample_seq), on_plan=plans.append)
     assert sum(len(pl.preempted) for pl in plans) >= 2            # the case does preempt (token values do not matter for that)
-    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2 if dtype else 1e-4)
-    print("preemption", name, "worst relative logit error", worst, "preemptions", sum(len(pl.preempted) for pl in plans))
+    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2 if dtype else 1e-4, tune=tune)
+    print("preemption", name, "tune", hex(tune), "worst relative logit error", worst, "preemptions", sum(len(pl.preempted) for pl in plans))
 
 
 def test_preemption_end_to_end(lib):

@@ -46,7 +46,8 @@ def test_prefix_cache_stepwise(lib, name, dtype, seed):
     assert st["prefix_hit_blocks"] > 10 and st["prefix_evictions"] > 0
 
 
-def test_prefix_cache_long_prefix_over_256_blocks(lib):
+@pytest.mark.parametrize("tune", [0, 0x400000])    # bit 22: the decode attention takes whole contexts (here one of 4200 tokens, nine rounds)
+def test_prefix_cache_long_prefix_over_256_blocks(lib, tune):
     """A prompt head of 4200 tokens (262 blocks: more than the scheduler's 256 threads take in one strip) shared by three
     requests: the second matches it while the first is running, both retire (262 blocks go idle), the third matches
     the idle blocks; a fourth, unrelated prompt then evicts part of the head."""
@@ -59,8 +60,8 @@ def test_prefix_cache_long_prefix_over_256_blocks(lib):
         return dict(arrival_s=0.0, prompt=np.concatenate([head, own]).astype(np.int32), max_new_tokens=n, temperature=0.0, top_k=0, top_p=1.0, seed=0)
     fresh = dict(arrival_s=0.0, prompt=rng.integers(0, cfg["vocab"], 1500).astype(np.int32), max_new_tokens=2, temperature=0.0, top_k=0, top_p=1.0, seed=0)
     reqs = [rq(5, 1, 3), rq(40, 2, 2), fresh, rq(17, 3, 2)]
-    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2)
-    print("long shared head: worst relative logit error", worst)
+    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2, tune=tune)
+    print("long shared head, tune", hex(tune), ": worst relative logit error", worst)
 
 
 def test_prefix_cache_batch_shares_head_in_use(lib):

@@ -75,7 +75,8 @@ def test_speculative_streams_equal_plain_streams_fp32(lib):
     print("iterations", st0["iterations"], "->", st1["iterations"], "drafted", st1["spec_drafted"], "accepted", st1["spec_accepted"])
 
 
-def test_speculative_wide_batch_and_long_lookback(lib):
+@pytest.mark.parametrize("tune", [0, 0x400000])    # bit 22: the decode attention takes whole contexts, as it does by itself with many sequences
+def test_speculative_wide_batch_and_long_lookback(lib, tune):
     """40 batch slots with up to 8 fed tokens each (a decode iteration of several hundred tokens: the tiled GEMM schedules
     and query tiles of many sequences in one launch), prompts of up to 1500 tokens (lookups past the 1024-position window
     must not be found; contexts of several attention chunks)."""
@@ -90,8 +91,8 @@ def test_speculative_wide_batch_and_long_lookback(lib):
         else:
             p = np.resize(rng.integers(0, cfg["vocab"], int(rng.integers(2, 6))), n)
         reqs.append(dict(arrival_s=0.0, prompt=p.astype(np.int32), max_new_tokens=int(rng.integers(1, 14)), temperature=0.0, top_k=0, top_p=1.0, seed=i))
-    worst, toks = parity.stepwise_check_speculative(lib, cfg, eng, raw, blob, reqs, rtol=2e-2)
-    print("wide speculative batch: worst relative logit error", worst)
+    worst, toks = parity.stepwise_check_speculative(lib, cfg, eng, raw, blob, reqs, rtol=2e-2, tune=tune)
+    print("wide speculative batch, tune", hex(tune), ": worst relative logit error", worst)
 
 
 def test_speculative_rejected_with_other_modes_and_bad_counts(lib):
