@@ -46,6 +46,17 @@ def test_moe16_stepwise(lib, prompts, max_new):
     assert free_run_tokens(lib, cfg, eng, blob, reqs) == toks
 
 
+def test_moe_on_the_chain_without_merge_kernels(lib):
+    """Bit 7 of the tuning word: the launcher always runs the kernel chain without the decode attention's merge kernels,
+    whose scheduler step hands out whole contexts (it does so by itself only once many sequences run). Contexts of up to
+    540 tokens, two rounds of KV blocks per item."""
+    cfg, eng, raw, blob = setup("mini_moe16", 143)
+    reqs = _fixed_prompts(cfg, [530, 260, 7, 90], 4, 243)
+    toks = {}
+    worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2, tokens_out=toks, tune=0x80)
+    print("mini_moe16 on the short chain: worst relative logit error", worst)
+
+
 @pytest.mark.parametrize("mode", ["chunked_prefill", "preemption", "prefix_cache"])
 def test_moe_with_the_scheduler_extensions(lib, mode):
     """The routed FFN under the scheduler's optional modes (mixed prefill + decode iterations with a budget of 48 tokens; on-demand
