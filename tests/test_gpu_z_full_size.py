@@ -147,3 +147,27 @@ def test_full_head_configuration_whole_context_items(lib):
     worst = parity.stepwise_check(lib, cfg, eng, raw, blob, reqs, rtol=2e-2, item_modes=modes)
     print("full head configuration, whole contexts: worst relative logit error", worst, "item modes", modes)
     assert True in modes        # the decode iterations of the full batch took whole contexts
+
+
+def test_free_running_loop_switches_between_the_two_chains(lib):
+    """The llama3_8b head configuration in one narrow layer, 172 sequences served by the free-running loop (one window,
+    HIP graphs, eight iterations enqueued ahead): while 128 or more sequences run the launcher takes the kernel chain
+    without the merge kernels, before and after it the full chain, from a host view that is iterations old. The
+    schedule is bit-exact and every token is the oracle's, teacher-forced, whichever chain an iteration ran on."""
+    cfg, eng = synth.model_config("mini_heads32"), synth.engine_config("mini_heads32")
+    raw = synth.make_weights(cfg, 52, gain_jitter=0.1)
+    blob = synth.pack_blob(cfg, raw)
+    rng = np.random.default_rng(52)
+    plens = [int(x) for x in rng.integers(8, 120, 172)]
+    plens[:4] = [1100, 700, 511, 513]
+    reqs = [dict(arrival_s=0.0, prompt=rng.integers(0, cfg["vocab"], P).astype(np.int32), max_new_tokens=int(rng.integers(14, 40)),
+                 temperature=0.0, top_k=0, top_p=1.0, seed=i) for i, P in enumerate(plens)]
+    ev, trace, st = parity.run_engine(lib, cfg, eng, blob, reqs, poll_cap=1 << 16)
+    assert st["n_running"] == 0 and st["free_blocks"] == eng["kv_num_blocks"]
+    assert len(ev) == sum(r["max_new_tokens"] for r in reqs)
+    res = parity.check_against_oracle(cfg, M.Weights(cfg, raw), eng, reqs, ev, trace, rtol=2e-2, tok_rtol=2e-3)
+    dec = trace[trace["kind"] == 2]
+    print("free run over both chains: tokens", res["tokens"], "near ties", res["near_ties"], "decode iterations with >= 128 sequences",
+          int((dec["n_seqs"] >= 128).sum()), "with fewer", int((dec["n_seqs"] < 128).sum()))
+    assert (dec["n_seqs"] >= 128).sum() >= 12 and (dec["n_seqs"] < 128).sum() >= 12    # longer than the launcher's lead of eight iterations
+    assert res["near_ties"] <= res["tokens"] // 8      # token tolerance 2e-3 of the largest logit, as in the other end-to-end tests
